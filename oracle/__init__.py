@@ -1,0 +1,12 @@
+"""CPU oracle for the fused parallel-pattern attention forward path.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product package may import this
+package; only tests/, __graft_entry__.smoke() and the cpu_baseline leg of
+bench.py do.  It shares no code with the HIP kernels or their Python binding.
+"""
+from .attention_oracle import (  # noqa: F401
+    attention,
+    attention_head,
+    brute,
+    weights_head,
+)

@@ -1,0 +1,97 @@
+"""Seeded synthetic workloads shared by the tests, the benchmark and smoke().
+
+This module holds NO arithmetic of the attention method: it only names the
+workload shapes and draws the inputs.  Both the CPU oracle's callers and the
+HIP path's callers read the same bf16 tensors produced here.
+
+Recipe: Q, K, V are i.i.d. N(0, 1) drawn in fp32 with
+torch.Generator('cpu').manual_seed(1000 * config_id + {0: Q, 1: K, 2: V}) and
+rounded to bf16 (round to nearest even).  They stand in for the random tensors
+of the paper's operator microbenchmark (Table 2 and the batch/sequence grid of
+Section 6.1), whose shapes the configurations below take.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, replace
+from typing import Optional, Tuple
+
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    config_id: int
+    B: int
+    H_q: int
+    H_kv: int
+    L_q: int
+    L_k: int
+    D_qk: int
+    D_v: int
+    score_mod: str = "none"      # none | bias | head_decay | relu
+    norm: str = "softmax"        # softmax | sigmoid | abssum | abs_of_sum | none
+    mask: str = "none"           # none | causal
+    scale: Optional[float] = None  # default 1/sqrt(D_qk)
+    bias: float = 0.0
+    decay: bool = False          # per-head gamma_h = 1 - 2^(-5-h)
+
+    @property
+    def scale_value(self) -> float:
+        return self.scale if self.scale is not None else 1.0 / math.sqrt(self.D_qk)
+
+    def gamma(self) -> Optional[Tuple[float, ...]]:
+        """Per-query-head decay rates of the retention configuration
+        (gamma_h = 1 - 2^(-5-h), h = 0..H_q-1); an input, not derived data."""
+        if not self.decay:
+            return None
+        return tuple(1.0 - 2.0 ** (-5 - h) for h in range(self.H_q))
+
+    def visible_pairs_per_head(self) -> int:
+        if self.mask == "none":
+            return self.L_q * self.L_k
+        off = self.L_k - self.L_q
+        return sum(max(0, min(self.L_k, i + off + 1)) for i in range(self.L_q))
+
+    def mfma_flop(self) -> int:
+        """2*(D_qk + D_v) flop per visible (query, key) pair."""
+        return 2 * (self.D_qk + self.D_v) * self.visible_pairs_per_head() * self.B * self.H_q
+
+    def compulsory_bytes(self) -> int:
+        q = self.B * self.H_q * self.L_q * self.D_qk * 2
+        k = self.B * self.H_kv * self.L_k * self.D_qk * 2
+        v = self.B * self.H_kv * self.L_k * self.D_v * 2
+        o = self.B * self.H_q * self.L_q * self.D_v * 4
+        return q + k + v + o
+
+    def scaled(self, **kw) -> "Workload":
+        return replace(self, **kw)
+
+
+# The five benchmark configurations, in the order the benchmark spec lists them.
+C1 = Workload("c1_softmax_noncausal", 1, 1, 2, 2, 256, 256, 64, 64)
+C2 = Workload("c2_gqa_causal_softmax", 2, 4, 32, 8, 2048, 2048, 128, 128, mask="causal")
+C3 = Workload("c3_sigmoid_causal", 3, 8, 16, 16, 4096, 4096, 64, 64,
+              score_mod="bias", norm="sigmoid", mask="causal", bias=-math.log(4096.0))
+C4 = Workload("c4_retnet", 4, 4, 8, 8, 4096, 4096, 128, 256,
+              score_mod="head_decay", norm="abssum", mask="causal", decay=True)
+C5 = Workload("c5_mla_causal_softmax", 5, 1, 128, 128, 8192, 8192, 192, 128, mask="causal")
+
+CONFIGS = {w.name: w for w in (C1, C2, C3, C4, C5)}
+BY_ID = {w.config_id: w for w in (C1, C2, C3, C4, C5)}
+
+
+def make_inputs(w: Workload, seed_base: Optional[int] = None):
+    """Return (Q, K, V) as contiguous CPU bf16 tensors [B, H, L, D]."""
+    base = 1000 * w.config_id if seed_base is None else seed_base
+    out = []
+    for idx, shape in enumerate((
+            (w.B, w.H_q, w.L_q, w.D_qk),
+            (w.B, w.H_kv, w.L_k, w.D_qk),
+            (w.B, w.H_kv, w.L_k, w.D_v))):
+        g = torch.Generator(device="cpu")
+        g.manual_seed(base + idx)
+        x = torch.randn(shape, generator=g, dtype=torch.float32)
+        out.append(x.to(torch.bfloat16).contiguous())
+    return tuple(out)
