@@ -1,0 +1,134 @@
+/*
+ * ae_attn.h -- C ABI of the fused parallel-pattern attention forward operator
+ * for AMD MI355X (gfx950).
+ *
+ * The operator is the parallel pattern of the paper's unified attention
+ * template (Section 4.1, "Attention Patterns and Templates"): relevance
+ * scoring S = Q K^T, a customizable function on the scores made of an
+ * elementwise `modification` (which may be annotated as a mask) and a
+ * `row-wise normalization` (Section 4.1, "Customizable functions and
+ * flexibility"), then aggregation O = P V.  The score matrix never reaches
+ * device memory: the normalization runs in its online form (prologue / per
+ * key-block update / epilogue, Section 4.1 "online row-norm interface").
+ * The customization points are closed enums here instead of a DSL.
+ *
+ * All entry points are host functions.  They return a status code, never
+ * throw and never abort.  Q, K, V, O are DEVICE pointers owned by the caller;
+ * everything else is host memory.
+ */
+#ifndef AE_ATTN_H
+#define AE_ATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ae_attn ae_attn_t; /* opaque; host memory only */
+
+typedef enum {
+  AE_OK = 0,
+  AE_ERR_INVALID_ARG = 1, /* null/misaligned pointer, bad size, bad parameter  */
+  AE_ERR_UNSUPPORTED = 2, /* well-formed, but no kernel for this combination    */
+  AE_ERR_HIP = 3,         /* the HIP runtime reported an error on launch        */
+  AE_ERR_NOMEM = 4        /* host allocation of the handle failed               */
+} ae_status_t;
+
+/* Elementwise modification of the scaled scores s' = scale * s
+ * (Section 4.1, "Examples of Attention variants").                           */
+typedef enum {
+  AE_MOD_NONE = 0,       /* s'                                                 */
+  AE_MOD_BIAS = 1,       /* s' + bias            (constant additive bias)      */
+  AE_MOD_HEAD_DECAY = 2, /* s' * gamma[h_q]^(i + L_k - L_q - j): the retention
+                            mask of RetNet parallel attention; needs CAUSAL    */
+  AE_MOD_RELU = 3        /* max(s', 0)           (ReLU attention)              */
+} ae_score_mod_t;
+
+/* Row-wise normalization of the modified scores over the visible keys.      */
+typedef enum {
+  AE_NORM_SOFTMAX = 0,    /* exp(x - rowmax) / rowsum, computed online         */
+  AE_NORM_SIGMOID = 1,    /* 1 / (1 + exp(-x)), no row reduction               */
+  AE_NORM_ABSSUM = 2,     /* x / max(sum_j |x|, 1)   (reduceAbssum, clamp 1)   */
+  AE_NORM_ABS_OF_SUM = 3, /* x / max(|sum_j x|, 1)   (alternative reading)     */
+  AE_NORM_NONE = 4        /* x                                                 */
+} ae_norm_t;
+
+/* Mask annotation of the modification.  A masked (query, key) pair
+ * contributes nothing: its weight is 0 and it takes no part in any row
+ * reduction.  A query row with no visible key produces a zero output row.    */
+typedef enum {
+  AE_MASK_NONE = 0,
+  AE_MASK_CAUSAL = 1 /* key j visible to query i iff j <= i + (L_k - L_q)      */
+} ae_mask_t;
+
+typedef enum { AE_OUT_F32 = 0 } ae_out_dtype_t;
+
+#define AE_MAX_DECAY_HEADS 256
+
+/*
+ * Problem descriptor (host memory, copied by ae_attn_create).
+ *
+ * Layouts (bf16 inputs, fp32 output, innermost dimension contiguous):
+ *   Q [B, H_q,  L_q, D_qk]   K [B, H_kv, L_k, D_qk]
+ *   V [B, H_kv, L_k, D_v ]   O [B, H_q,  L_q, D_v ]
+ * Query head h_q reads key/value head h_q / (H_q / H_kv) (contiguous groups).
+ * Strides are in ELEMENTS, ordered {batch, head, row}; an all-zero triple
+ * means "contiguous [B, H, L, D]".  Row strides of Q, K, V must be multiples
+ * of 8 elements and that of O a multiple of 4, so that every row starts on a
+ * 16-byte boundary.
+ */
+typedef struct {
+  int32_t B, H_q, H_kv, L_q, L_k, D_qk, D_v;
+  ae_score_mod_t score_mod;
+  float bias;          /* used by AE_MOD_BIAS                                   */
+  const float *gamma;  /* host array [H_q], each finite and > 0; read only by
+                          AE_MOD_HEAD_DECAY (H_q <= AE_MAX_DECAY_HEADS)         */
+  ae_norm_t norm;
+  ae_mask_t mask;
+  float scale;         /* finite and non-zero; multiplies the scores            */
+  ae_out_dtype_t out_dtype;
+  int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3];
+} ae_attn_desc_t;
+
+/* Validates the descriptor, picks the kernel and its tile shape for
+ * (D_qk, D_v, mask, norm, score_mod) and returns a handle in *out.  Touches no
+ * device.  Supported head dims (D_qk/D_v): 64/64, 128/128, 128/256, 192/128.
+ * Supported (score_mod, norm) pairs: NONE or BIAS with every norm;
+ * HEAD_DECAY with ABSSUM, ABS_OF_SUM or NONE (CAUSAL mask only); RELU with NONE.
+ * Errors: AE_ERR_INVALID_ARG, AE_ERR_UNSUPPORTED, AE_ERR_NOMEM; *out is set
+ * to NULL on error.                                                           */
+ae_status_t ae_attn_create(const ae_attn_desc_t *desc, ae_attn_t **out);
+
+/* Enqueues O = rownorm(mod(scale * Q K^T)) V on `stream` (a hipStream_t, may
+ * be NULL for the default stream) of the current device and returns without
+ * synchronising.  Q, K, V, O: device pointers, 16-byte aligned, sized as the
+ * descriptor says; O must not alias the inputs.  The handle is not modified:
+ * concurrent calls on one handle from several threads or streams are allowed.
+ * Allocates no device memory.  Errors: AE_ERR_INVALID_ARG (nothing is
+ * launched), AE_ERR_HIP.                                                       */
+ae_status_t ae_attn_forward(const ae_attn_t *h, const void *Q, const void *K,
+                            const void *V, void *O, void *stream);
+
+/* Frees the handle.  NULL is a no-op.                                         */
+ae_status_t ae_attn_destroy(ae_attn_t *h);
+
+/* Tile shape and launch geometry chosen at create time (for harnesses).
+ * Any output pointer may be NULL.                                             */
+ae_status_t ae_attn_query(const ae_attn_t *h, int32_t *block_m, int32_t *block_n,
+                          int32_t *lds_bytes, int32_t *grid_size, int32_t *block_threads);
+
+/* Name of the device kernel a handle launches (for matching profiler rows);
+ * owned by the library, valid for the life of the process.                    */
+const char *ae_attn_kernel_name(const ae_attn_t *h);
+
+/* Message of the calling thread's most recent failing call ("" if none).     */
+const char *ae_attn_last_error(void);
+
+/* Library version as major * 100 + minor.                                     */
+int32_t ae_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AE_ATTN_H */

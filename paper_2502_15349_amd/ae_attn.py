@@ -1,0 +1,148 @@
+"""ctypes binding of libae_attn.so: argument marshalling only.
+
+Names mirror the C ABI (include/ae_attn.h): ae_attn_create, ae_attn_forward,
+ae_attn_destroy, ae_attn_query.  Every step of the attention path runs in the
+HIP kernels; PyTorch supplies device memory and the stream, nothing else.
+Importing this module fails if the library has not been built
+(`python -m paper_2502_15349_amd.build`): there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libae_attn.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        f"{_LIB_PATH} is missing: build it with `python -m paper_2502_15349_amd.build` "
+        "(the HIP library is the only implementation; there is no fallback)")
+_lib = C.CDLL(_LIB_PATH)
+
+AE_OK, AE_ERR_INVALID_ARG, AE_ERR_UNSUPPORTED, AE_ERR_HIP, AE_ERR_NOMEM = range(5)
+SCORE_MODS = {"none": 0, "bias": 1, "head_decay": 2, "relu": 3}
+NORMS = {"softmax": 0, "sigmoid": 1, "abssum": 2, "abs_of_sum": 3, "none": 4}
+MASKS = {"none": 0, "causal": 1}
+
+
+class ae_attn_desc_t(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("H_q", C.c_int32), ("H_kv", C.c_int32), ("L_q", C.c_int32),
+        ("L_k", C.c_int32), ("D_qk", C.c_int32), ("D_v", C.c_int32),
+        ("score_mod", C.c_int), ("bias", C.c_float), ("gamma", C.POINTER(C.c_float)),
+        ("norm", C.c_int), ("mask", C.c_int), ("scale", C.c_float), ("out_dtype", C.c_int),
+        ("q_stride", C.c_int64 * 3), ("k_stride", C.c_int64 * 3),
+        ("v_stride", C.c_int64 * 3), ("o_stride", C.c_int64 * 3),
+    ]
+
+
+_lib.ae_attn_create.argtypes = [C.POINTER(ae_attn_desc_t), C.POINTER(C.c_void_p)]
+_lib.ae_attn_create.restype = C.c_int
+_lib.ae_attn_forward.argtypes = [C.c_void_p] * 6
+_lib.ae_attn_forward.restype = C.c_int
+_lib.ae_attn_destroy.argtypes = [C.c_void_p]
+_lib.ae_attn_destroy.restype = C.c_int
+_lib.ae_attn_query.argtypes = [C.c_void_p] + [C.POINTER(C.c_int32)] * 5
+_lib.ae_attn_query.restype = C.c_int
+_lib.ae_attn_kernel_name.argtypes = [C.c_void_p]
+_lib.ae_attn_kernel_name.restype = C.c_char_p
+_lib.ae_attn_last_error.argtypes = []
+_lib.ae_attn_last_error.restype = C.c_char_p
+_lib.ae_attn_version.argtypes = []
+_lib.ae_attn_version.restype = C.c_int32
+
+
+class AeAttnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"ae_attn status {status}: {message}")
+        self.status = status
+
+
+def ae_attn_last_error() -> str:
+    return _lib.ae_attn_last_error().decode()
+
+
+def ae_attn_version() -> int:
+    return int(_lib.ae_attn_version())
+
+
+def _check(status: int) -> None:
+    if status != AE_OK:
+        raise AeAttnError(status, ae_attn_last_error())
+
+
+def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int, D_v: int,
+                   scale: float, score_mod="none", bias: float = 0.0,
+                   gamma: Optional[Sequence[float]] = None, norm="softmax", mask="none",
+                   q_stride=(0, 0, 0), k_stride=(0, 0, 0), v_stride=(0, 0, 0), o_stride=(0, 0, 0)) -> int:
+    """Returns an opaque handle (int).  Enum arguments accept names or raw ints."""
+    d = ae_attn_desc_t()
+    d.B, d.H_q, d.H_kv, d.L_q, d.L_k, d.D_qk, d.D_v = B, H_q, H_kv, L_q, L_k, D_qk, D_v
+    d.score_mod = SCORE_MODS[score_mod] if isinstance(score_mod, str) else int(score_mod)
+    d.norm = NORMS[norm] if isinstance(norm, str) else int(norm)
+    d.mask = MASKS[mask] if isinstance(mask, str) else int(mask)
+    d.bias, d.scale, d.out_dtype = float(bias), float(scale), 0
+    keep = None
+    if gamma is not None:
+        keep = (C.c_float * len(gamma))(*[float(x) for x in gamma])
+        d.gamma = C.cast(keep, C.POINTER(C.c_float))
+    for name, val in (("q_stride", q_stride), ("k_stride", k_stride), ("v_stride", v_stride), ("o_stride", o_stride)):
+        setattr(d, name, (C.c_int64 * 3)(*[int(x) for x in val]))
+    h = C.c_void_p()
+    _check(_lib.ae_attn_create(C.byref(d), C.byref(h)))
+    return h.value
+
+
+def ae_attn_forward(handle: int, Q: int, K: int, V: int, O: int, stream: int = 0) -> None:
+    """Q, K, V, O are device addresses (tensor.data_ptr()); stream is a raw hipStream_t."""
+    _check(_lib.ae_attn_forward(handle, Q, K, V, O, stream))
+
+
+def ae_attn_destroy(handle: Optional[int]) -> None:
+    _check(_lib.ae_attn_destroy(handle))
+
+
+def ae_attn_query(handle: int) -> dict:
+    v = [C.c_int32() for _ in range(5)]
+    _check(_lib.ae_attn_query(handle, *[C.byref(x) for x in v]))
+    keys = ("block_m", "block_n", "lds_bytes", "grid_size", "block_threads")
+    out = {k: int(x.value) for k, x in zip(keys, v)}
+    out["kernel"] = _lib.ae_attn_kernel_name(handle).decode()
+    return out
+
+
+# ---- convenience for torch callers (still marshalling only) -------------------
+def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
+                      mask="none", out=None, stream=None):
+    """Runs the HIP operator on CUDA/HIP bf16 tensors laid out [B, H, L, D]
+    (last dim contiguous) and returns O as fp32 [B, H_q, L_q, D_v]."""
+    import torch
+
+    if not (Q.is_cuda and K.is_cuda and V.is_cuda):
+        raise ValueError("attention_forward needs device tensors; there is no CPU path")
+    for t in (Q, K, V):
+        if t.dtype != torch.bfloat16 or t.dim() != 4 or t.stride(3) != 1:
+            raise ValueError("Q, K, V must be 4-D bf16 with a contiguous last dimension")
+    B, H_q, L_q, D_qk = Q.shape
+    _, H_kv, L_k, D_v = V.shape
+    if K.shape != (B, H_kv, L_k, D_qk):
+        raise ValueError("K shape does not match Q / V")
+    if out is None:
+        out = torch.empty((B, H_q, L_q, D_v), dtype=torch.float32, device=Q.device)
+    h = ae_attn_create(B=B, H_q=H_q, H_kv=H_kv, L_q=L_q, L_k=L_k, D_qk=D_qk, D_v=D_v, scale=scale,
+                       score_mod=score_mod, bias=bias, gamma=gamma, norm=norm, mask=mask,
+                       q_stride=Q.stride()[:3], k_stride=K.stride()[:3], v_stride=V.stride()[:3],
+                       o_stride=out.stride()[:3])
+    try:
+        s = torch.cuda.current_stream(Q.device) if stream is None else stream
+        with torch.cuda.device(Q.device):
+            ae_attn_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), s.cuda_stream)
+    finally:
+        ae_attn_destroy(h)
+    return out
+
+
+def run_workload(w, Q, K, V, out=None):
+    """attention_forward with the parameters of a workloads.Workload."""
+    return attention_forward(Q, K, V, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
+                             gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out)

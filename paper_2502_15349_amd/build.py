@@ -1,0 +1,83 @@
+"""Builds libae_attn.so (HIP, gfx950) in-tree.
+
+    python -m paper_2502_15349_amd.build [--report]
+
+hipcc cross-compiles without a GPU.  Objects go to csrc/_build/ (git-ignored);
+the shared library lands next to this file, where the ctypes binding loads it.
+"""
+from __future__ import annotations
+
+import concurrent.futures as cf
+import os
+import re
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+BUILD = os.path.join(CSRC, "_build")
+LIB = os.path.join(HERE, "libae_attn.so")
+
+SOURCES = ["ae_attn.hip", "inst_64_64.hip", "inst_128_128.hip", "inst_128_256.hip", "inst_192_128.hip"]
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+    # packed fp32 VALU forms stay off on the test machines
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wno-unused-result", "-Wno-unused-command-line-argument",
+]
+
+
+def _hipcc() -> str:
+    for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
+        if cand and (os.path.isabs(cand) and os.path.exists(cand) or not os.path.isabs(cand)):
+            return cand
+    raise RuntimeError("hipcc not found")
+
+
+def _compile(src: str) -> str:
+    obj = os.path.join(BUILD, src.replace(".hip", ".o"))
+    cmd = [_hipcc(), *HIPCC_FLAGS, "-save-temps=obj", "-c", os.path.join(CSRC, src), "-o", obj]
+    r = subprocess.run(cmd, capture_output=True, text=True, cwd=BUILD)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for {src}:\n{r.stderr[-4000:]}")
+    return obj
+
+
+def resource_report() -> str:
+    """VGPR / spill / LDS usage per kernel, read from the saved device assembly."""
+    rows = []
+    for f in sorted(os.listdir(BUILD)):
+        if not (f.endswith(".s") and "amdgcn" in f):
+            continue
+        txt = open(os.path.join(BUILD, f)).read()
+        for blk in txt.split("- .agpr_count:")[1:]:
+            def g(key):
+                m = re.search(rf"\.{key}:\s+(\S+)", blk)
+                return m.group(1) if m else "?"
+            name = g("name")
+            m = re.search(r"CfgILi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELb(\d)ELi(\d+)ELi(\d+)E", name)
+            short = "attn_fwd<%s>" % ",".join(m.groups()) if m else name
+            rows.append(f"{short:34s} vgpr {g('vgpr_count'):>4s} agpr {blk.split()[0]:>3s} sgpr {g('sgpr_count'):>3s} "
+                        f"spill {g('vgpr_spill_count'):>3s} scratch {g('private_segment_fixed_size'):>4s} "
+                        f"lds {g('group_segment_fixed_size'):>6s}")
+    return "\n".join(rows)
+
+
+def build(verbose: bool = True) -> str:
+    os.makedirs(BUILD, exist_ok=True)
+    with cf.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+        objs = list(ex.map(_compile, SOURCES))
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link failed:\n{r.stderr[-4000:]}")
+    if verbose:
+        print(f"built {LIB}")
+    return LIB
+
+
+if __name__ == "__main__":
+    build()
+    if "--report" in sys.argv:
+        print(resource_report())

@@ -1,0 +1,214 @@
+// C ABI of the fused parallel-pattern attention forward operator: descriptor
+// validation, kernel/tile selection, launch.  See include/ae_attn.h.
+#include "../../include/ae_attn.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "dispatch.hpp"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+ae_status_t fail(ae_status_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+const ae::KernelEntry* find_kernel(int dqk, int dv, int norm, int mod, int causal) {
+  typedef const ae::KernelEntry* (*table_fn)(int*);
+  static const table_fn tables[] = {ae::table_64_64, ae::table_128_128, ae::table_128_256, ae::table_192_128};
+  for (table_fn tf : tables) {
+    int n = 0;
+    const ae::KernelEntry* t = tf(&n);
+    for (int i = 0; i < n; ++i)
+      if (t[i].dqk == dqk && t[i].dv == dv && t[i].norm == norm && t[i].mod == mod && t[i].causal == causal)
+        return &t[i];
+  }
+  return nullptr;
+}
+
+bool dims_supported(int dqk, int dv) {
+  return (dqk == 64 && dv == 64) || (dqk == 128 && dv == 128) || (dqk == 128 && dv == 256) ||
+         (dqk == 192 && dv == 128);
+}
+
+void fill_strides(int64_t dst[3], const int64_t src[3], int H, int L, int D) {
+  if (src[0] == 0 && src[1] == 0 && src[2] == 0) {
+    dst[2] = D;
+    dst[1] = (int64_t)L * D;
+    dst[0] = (int64_t)H * L * D;
+  } else {
+    dst[0] = src[0];
+    dst[1] = src[1];
+    dst[2] = src[2];
+  }
+}
+
+}  // namespace
+
+struct ae_attn {
+  ae_attn_desc_t desc;
+  const ae::KernelEntry* kernel;
+  ae::Params params;  // pointers filled in per call
+  ae::DecayTable decay;
+  int grid;
+};
+
+extern "C" {
+
+ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
+  if (out) *out = nullptr;
+  if (!d || !out) return fail(AE_ERR_INVALID_ARG, "ae_attn_create: null argument");
+  if (d->B <= 0 || d->H_q <= 0 || d->H_kv <= 0 || d->L_q <= 0 || d->L_k <= 0 || d->D_qk <= 0 || d->D_v <= 0)
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: every size must be positive");
+  if (d->H_q % d->H_kv != 0)
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: H_q (%d) is not a multiple of H_kv (%d)", d->H_q, d->H_kv);
+  if (!std::isfinite(d->scale) || d->scale == 0.f)
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: scale must be finite and non-zero");
+  if ((int)d->score_mod < 0 || (int)d->score_mod > AE_MOD_RELU)
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown score_mod %d", (int)d->score_mod);
+  if ((int)d->norm < 0 || (int)d->norm > AE_NORM_NONE)
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown norm %d", (int)d->norm);
+  if ((int)d->mask < 0 || (int)d->mask > AE_MASK_CAUSAL)
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown mask %d", (int)d->mask);
+  if (d->out_dtype != AE_OUT_F32)
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: only fp32 output is implemented");
+  if (d->score_mod == AE_MOD_BIAS && !std::isfinite(d->bias))
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: bias must be finite");
+  if ((int64_t)d->B * d->H_kv > (1 << 24) || (int64_t)d->L_q > (1 << 28) || (int64_t)d->L_k > (1 << 28))
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: problem too large for 32-bit tile indices");
+
+  if (!dims_supported(d->D_qk, d->D_v))
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: head dims %d/%d not in the tile table (64/64, 128/128, 128/256, 192/128)",
+                d->D_qk, d->D_v);
+
+  int mod = ae::MOD_PLAIN;
+  if (d->score_mod == AE_MOD_HEAD_DECAY) mod = ae::MOD_DECAY;
+  if (d->score_mod == AE_MOD_RELU) mod = ae::MOD_RELU;
+  if (d->score_mod == AE_MOD_HEAD_DECAY) {
+    if (d->mask != AE_MASK_CAUSAL)
+      return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: HEAD_DECAY needs the causal mask");
+    if (!d->gamma) return fail(AE_ERR_INVALID_ARG, "ae_attn_create: HEAD_DECAY needs gamma[H_q]");
+    if (d->H_q > AE_MAX_DECAY_HEADS)
+      return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: HEAD_DECAY supports at most %d query heads", AE_MAX_DECAY_HEADS);
+    for (int h = 0; h < d->H_q; ++h)
+      if (!std::isfinite(d->gamma[h]) || !(d->gamma[h] > 0.f))
+        return fail(AE_ERR_INVALID_ARG, "ae_attn_create: gamma[%d] must be finite and > 0", h);
+  }
+  const ae::KernelEntry* k = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, d->mask == AE_MASK_CAUSAL);
+  if (!k)
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: no kernel for score_mod %d with norm %d", (int)d->score_mod,
+                (int)d->norm);
+
+  ae_attn* h = new (std::nothrow) ae_attn;
+  if (!h) return fail(AE_ERR_NOMEM, "ae_attn_create: out of host memory");
+  std::memset(h, 0, sizeof(*h));
+  h->desc = *d;
+  h->desc.gamma = nullptr;  // the caller's array is not kept
+  h->kernel = k;
+
+  ae::Params& p = h->params;
+  p.B = d->B; p.H_q = d->H_q; p.H_kv = d->H_kv; p.L_q = d->L_q; p.L_k = d->L_k;
+  p.g = d->H_q / d->H_kv;
+  p.n_qtiles = (d->L_q + k->block_m - 1) / k->block_m;
+  p.n_groups = d->B * d->H_kv;
+  fill_strides(p.qs, d->q_stride, d->H_q, d->L_q, d->D_qk);
+  fill_strides(p.ks, d->k_stride, d->H_kv, d->L_k, d->D_qk);
+  fill_strides(p.vs, d->v_stride, d->H_kv, d->L_k, d->D_v);
+  fill_strides(p.os, d->o_stride, d->H_q, d->L_q, d->D_v);
+  const int64_t* in_strides[3] = {p.qs, p.ks, p.vs};
+  const int in_d[3] = {d->D_qk, d->D_qk, d->D_v};
+  for (int t = 0; t < 3; ++t) {
+    for (int a = 0; a < 3; ++a)
+      if (in_strides[t][a] < 0 || in_strides[t][a] % 8 != 0) {
+        delete h;
+        return fail(AE_ERR_INVALID_ARG, "ae_attn_create: Q/K/V strides must be non-negative multiples of 8 elements");
+      }
+    if (in_strides[t][2] < in_d[t]) {
+      delete h;
+      return fail(AE_ERR_INVALID_ARG, "ae_attn_create: a Q/K/V row stride is smaller than the head dim");
+    }
+  }
+  for (int a = 0; a < 3; ++a)
+    if (p.os[a] < 0 || p.os[a] % 4 != 0) {
+      delete h;
+      return fail(AE_ERR_INVALID_ARG, "ae_attn_create: O strides must be non-negative multiples of 4 elements");
+    }
+  if (p.os[2] < d->D_v) {
+    delete h;
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: the O row stride is smaller than D_v");
+  }
+
+  const float log2e = 1.4426950408889634f;
+  const float a = std::fabs(d->scale);
+  const float bias = d->score_mod == AE_MOD_BIAS ? d->bias : 0.f;
+  if (d->norm == AE_NORM_SOFTMAX || d->norm == AE_NORM_SIGMOID) {
+    p.c = a * log2e;
+    p.b2 = bias * log2e;
+  } else {
+    p.c = a;
+    p.b2 = bias;
+  }
+  p.neg_q = d->scale < 0.f ? 1 : 0;
+  if (mod == ae::MOD_DECAY)
+    for (int hh = 0; hh < d->H_q; ++hh) h->decay.log2_gamma[hh] = std::log2(d->gamma[hh]);
+
+  const int64_t per_group = (int64_t)p.n_qtiles * p.g;
+  const int64_t rounds = (p.n_groups + 7) / 8;
+  const int64_t grid = rounds * 8 * per_group;
+  if (grid > 0x7fffffffLL) {
+    delete h;
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: grid of %lld workgroups exceeds the launch limit", (long long)grid);
+  }
+  h->grid = (int)grid;
+  *out = h;
+  return AE_OK;
+}
+
+ae_status_t ae_attn_forward(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, void* stream) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null handle");
+  if (!Q || !K || !V || !O) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null device pointer");
+  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: device pointers must be 16-byte aligned");
+  if (O == Q || O == K || O == V) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: O aliases an input");
+  ae::Params p = h->params;
+  p.Q = static_cast<const __bf16*>(Q);
+  p.K = static_cast<const __bf16*>(K);
+  p.V = static_cast<const __bf16*>(V);
+  p.O = static_cast<float*>(O);
+  hipError_t e = h->kernel->launch(p, h->decay, h->grid, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_forward: launch failed: %s", hipGetErrorString(e));
+  return AE_OK;
+}
+
+ae_status_t ae_attn_destroy(ae_attn_t* h) {
+  delete h;
+  return AE_OK;
+}
+
+ae_status_t ae_attn_query(const ae_attn_t* h, int32_t* block_m, int32_t* block_n, int32_t* lds_bytes,
+                          int32_t* grid_size, int32_t* block_threads) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_query: null handle");
+  if (block_m) *block_m = h->kernel->block_m;
+  if (block_n) *block_n = h->kernel->block_n;
+  if (lds_bytes) *lds_bytes = h->kernel->lds_bytes;
+  if (grid_size) *grid_size = h->grid;
+  if (block_threads) *block_threads = h->kernel->threads;
+  return AE_OK;
+}
+
+const char* ae_attn_kernel_name(const ae_attn_t* h) { return h ? h->kernel->name : ""; }
+
+const char* ae_attn_last_error(void) { return g_err; }
+
+int32_t ae_attn_version(void) { return 1; }
+
+}  // extern "C"

@@ -1,0 +1,58 @@
+// Kernel table shared by the per-head-dim instantiation units and the C ABI.
+#pragma once
+#include "attn_kernel.hpp"
+
+namespace ae {
+
+typedef hipError_t (*launch_fn)(const Params&, const DecayTable&, int grid, hipStream_t);
+
+struct KernelEntry {
+  int dqk, dv, norm, mod, causal;
+  int block_m, block_n, threads, lds_bytes;
+  launch_fn launch;
+  const char* name;
+};
+
+template <class C>
+hipError_t launch_cfg(const Params& p, const DecayTable& dt, int grid, hipStream_t s) {
+  hipLaunchKernelGGL(attn_fwd_kernel<C>, dim3(grid), dim3(C::THREADS), 0, s, p, dt);
+  return hipGetLastError();
+}
+
+template <class C>
+constexpr KernelEntry make_entry(const char* name) {
+  return KernelEntry{C::DQK, C::DV, C::NORM, C::MOD, C::CAUSAL ? 1 : 0,
+                     C::BLOCK_M, C::BLOCK_N, C::THREADS, C::LDS_BYTES, &launch_cfg<C>, name};
+}
+
+// One row of the tile-shape table: for head dims (DQK, DV) and mask CAUSAL the
+// workgroup has WAVES wavefronts, each owning QB blocks of 32 query rows.
+#define AE_ENTRY(DQK, DV, NORM, MOD, CAUSAL, WAVES, QB) \
+  make_entry<Cfg<DQK, DV, NORM, MOD, CAUSAL, WAVES, QB>>( \
+      "attn_fwd<" #DQK "," #DV "," #NORM "," #MOD "," #CAUSAL "," #WAVES "," #QB ">")
+
+// Every (norm, mod) pair the library supports, for one (DQK, DV) and one tile
+// shape per mask value.
+#define AE_ENTRIES_FOR_DIMS(DQK, DV, W_NC, QB_NC, W_C, QB_C)            \
+  AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_PLAIN, false, W_NC, QB_NC),       \
+  AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_PLAIN, false, W_NC, QB_NC),       \
+  AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_PLAIN, false, W_NC, QB_NC),        \
+  AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_PLAIN, false, W_NC, QB_NC),    \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_PLAIN, false, W_NC, QB_NC),          \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_RELU, false, W_NC, QB_NC),           \
+  AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_PLAIN, true, W_C, QB_C),          \
+  AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_PLAIN, true, W_C, QB_C),          \
+  AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_PLAIN, true, W_C, QB_C),           \
+  AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_PLAIN, true, W_C, QB_C),       \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_PLAIN, true, W_C, QB_C),             \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_RELU, true, W_C, QB_C),              \
+  AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_DECAY, true, W_C, QB_C),           \
+  AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_DECAY, true, W_C, QB_C),       \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_DECAY, true, W_C, QB_C)
+
+const KernelEntry* table_64_64(int* n);
+const KernelEntry* table_128_128(int* n);
+const KernelEntry* table_128_256(int* n);
+const KernelEntry* table_192_128(int* n);
+
+}  // namespace ae

@@ -1,0 +1,86 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad descriptors without touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2502_15349_amd", "libae_attn.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libae_attn.so not built (run __graft_entry__.build())")
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "ae_attn.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(ae_attn_[a-z_]+)\s*\(", hdr))
+    assert {"ae_attn_create", "ae_attn_forward", "ae_attn_destroy", "ae_attn_query"} <= names
+    lib = ctypes.CDLL(LIB)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+
+
+def _ok_desc():
+    return dict(B=1, H_q=4, H_kv=2, L_q=100, L_k=100, D_qk=128, D_v=128, scale=0.1)
+
+
+def test_create_query_destroy_roundtrip():
+    from paper_2502_15349_amd import ae_attn as A
+    h = A.ae_attn_create(**_ok_desc(), mask="causal")
+    q = A.ae_attn_query(h)
+    assert q["block_n"] == 64 and q["block_m"] % 32 == 0 and q["block_threads"] % 64 == 0
+    assert q["lds_bytes"] <= 160 * 1024
+    # grid covers every (group, q head in group, q tile) at least once
+    n_qt = -(-100 // q["block_m"])
+    assert q["grid_size"] >= 1 * 2 * 2 * n_qt
+    assert "attn_fwd" in q["kernel"]
+    A.ae_attn_destroy(h)
+    A.ae_attn_destroy(None)
+    assert A.ae_attn_version() >= 1
+
+
+@pytest.mark.parametrize("patch,status", [
+    (dict(B=0), 1), (dict(L_q=-3), 1), (dict(H_q=3), 1), (dict(scale=float("nan")), 1),
+    (dict(scale=0.0), 1), (dict(scale=float("inf")), 1),
+    (dict(D_qk=96), 2), (dict(D_qk=64), 2), (dict(D_v=64), 2),
+    (dict(norm=9), 2), (dict(score_mod=7), 2), (dict(mask=5), 2),
+    (dict(score_mod="head_decay", norm="abssum", mask="causal"), 1),            # gamma missing
+    (dict(score_mod="head_decay", norm="abssum", mask="none", gamma=[.9] * 4), 2),
+    (dict(score_mod="head_decay", norm="softmax", mask="causal", gamma=[.9] * 4), 2),
+    (dict(score_mod="head_decay", norm="abssum", mask="causal", gamma=[.9, 0.0, .9, .9]), 1),
+    (dict(score_mod="relu", norm="softmax"), 2),
+    (dict(score_mod="bias", bias=float("inf")), 1),
+    (dict(q_stride=(100 * 4 * 128, 100 * 128, 132)), 1),                          # not a multiple of 8
+    (dict(k_stride=(100 * 2 * 128, 100 * 128, 64)), 1),                           # row stride < D
+    (dict(o_stride=(100 * 4 * 130, 100 * 130, 130)), 1),                          # not a multiple of 4
+])
+def test_create_rejects_bad_descriptors(patch, status):
+    from paper_2502_15349_amd import ae_attn as A
+    d = _ok_desc()
+    d.update(patch)
+    with pytest.raises(A.AeAttnError) as ei:
+        A.ae_attn_create(**d)
+    assert ei.value.status == status
+    assert A.ae_attn_last_error() != ""
+
+
+def test_forward_rejects_bad_pointers_without_launching():
+    from paper_2502_15349_amd import ae_attn as A
+    h = A.ae_attn_create(**_ok_desc())
+    try:
+        for args in ((0, 256, 512, 768), (256, 512, 768, 0), (256 + 4, 512, 768, 1024), (256, 512, 768, 256)):
+            with pytest.raises(A.AeAttnError) as ei:
+                A.ae_attn_forward(h, *args)
+            assert ei.value.status == A.AE_ERR_INVALID_ARG
+        with pytest.raises(A.AeAttnError):
+            A.ae_attn_forward(None, 256, 512, 768, 1024)
+    finally:
+        A.ae_attn_destroy(h)
+
+
+def test_padded_strides_accepted():
+    from paper_2502_15349_amd import ae_attn as A
+    h = A.ae_attn_create(**_ok_desc(), q_stride=(100 * 4 * 136, 100 * 136, 136))
+    A.ae_attn_destroy(h)
