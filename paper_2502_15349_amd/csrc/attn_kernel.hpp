@@ -24,6 +24,7 @@ namespace ae {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -81,8 +82,29 @@ struct Cfg {
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 
-// Exchange with the lane that holds the other 16 keys of the same query row.
-__device__ __forceinline__ float xchg32(float x) { return __shfl_xor(x, 32, 64); }
+// The other 16 keys of a query row live in lane l^32.  v_permlane32_swap
+// exchanges the upper half of its first operand with the lower half of its
+// second: fed the same value twice it returns (x[l%32], x[l%32 + 32]) in every
+// lane.  (The results are copied to scalars before the bit cast: a bit cast
+// applied directly to a vector element reads element 0 with this compiler.)
+__device__ __forceinline__ void swap_halves(float x, float& lo, float& hi) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const uint32_t r0 = r[0], r1 = r[1];
+  lo = __builtin_bit_cast(float, r0);
+  hi = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ float max_halves(float x) {
+  float lo, hi;
+  swap_halves(x, lo, hi);
+  return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float sum_halves(float x) {
+  float lo, hi;
+  swap_halves(x, lo, hi);
+  return lo + hi;
+}
+constexpr float kLazyLog2 = 8.0f;
 
 template <class C>
 __device__ __forceinline__ void stage_load(const Params& p, const __bf16* kbase, const __bf16* vbase,
@@ -188,26 +210,28 @@ __device__ __forceinline__ void tile_compute(const Params& p, const char* ksm, c
           x[kb][r] = v;
           mx = fmaxf(mx, v);
         }
-      mx = fmaxf(mx, xchg32(mx));
-      const float m_new = fmaxf(st.m[qb], __builtin_fmaf(mx, p.c, p.b2));  // c > 0
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = fast_exp2(st.m[qb] - m_use);
-      st.m[qb] = m_new;
-      const float k0 = p.b2 - m_use;
-      float sum = 0.f;
+      mx = max_halves(mx);
+      // Lazy reference maximum: the running reference m only moves when the
+      // tile's row max exceeds it by more than kLazyLog2 (weights then stay
+      // below 2^kLazyLog2, harmless in bf16/fp32), so the rescale of l and O
+      // is skipped for almost every tile after the first.
+      const float xm = __builtin_fmaf(mx, p.c, p.b2);  // c > 0
+      const bool moved = xm > st.m[qb] + kLazyLog2;
+      if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+        const float m_new = moved ? xm : st.m[qb];
+        const float alpha = moved ? fast_exp2(st.m[qb] - m_new) : 1.f;
+        st.m[qb] = m_new;
+        st.l[qb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < C::DV / 32; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) st.o[qb][db][r] *= alpha;
+      }
+      const float k0 = p.b2 - ((st.m[qb] == -INFINITY) ? 0.f : st.m[qb]);
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float e = fast_exp2(__builtin_fmaf(x[kb][r], p.c, k0));
-          x[kb][r] = e;
-          sum += e;
-        }
-      st.l[qb] = st.l[qb] * alpha + sum;
-#pragma unroll
-      for (int db = 0; db < C::DV / 32; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st.o[qb][db][r] *= alpha;
+        for (int r = 0; r < 16; ++r) x[kb][r] = fast_exp2(__builtin_fmaf(x[kb][r], p.c, k0));
     } else {
       // decay exponent base for this lane: log2(gamma) * (i + off - j) with
       // j = j0 + 4*half + const(kb, r); log2|scale| is folded in as well.
@@ -240,10 +264,26 @@ __device__ __forceinline__ void tile_compute(const Params& p, const char* ksm, c
       if constexpr (C::NORM == NORM_ABSSUM || C::NORM == NORM_ABS_OF_SUM) st.l[qb] += sum;
     }
 
+    // P -> bf16 pairs (hardware RNE pack); for softmax the row sum is taken
+    // over the rounded weights, two per v_dot2c_f32_bf16.
+    float psum = 0.f;
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t) {
+      u32x4 pk;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pf[qb][t][e] = (__bf16)x[t >> 1][8 * (t & 1) + e];
+      for (int e2 = 0; e2 < 4; ++e2) {
+        bf16x2 pr;
+        pr[0] = (__bf16)x[t >> 1][8 * (t & 1) + 2 * e2];
+        pr[1] = (__bf16)x[t >> 1][8 * (t & 1) + 2 * e2 + 1];
+        if constexpr (C::NORM == NORM_SOFTMAX) {
+          const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+          psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+        }
+        pk[e2] = __builtin_bit_cast(uint32_t, pr);
+      }
+      pf[qb][t] = __builtin_bit_cast(bf16x8, pk);
+    }
+    if constexpr (C::NORM == NORM_SOFTMAX) st.l[qb] += psum;
   }
 
   // ---- aggregation: O^T[d, query] += V^T P^T --------------------------------
@@ -372,13 +412,13 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   for (int qb = 0; qb < C::QB; ++qb) {
     float inv = 1.f;
     if constexpr (C::NORM == NORM_SOFTMAX) {
-      const float l = st.l[qb] + xchg32(st.l[qb]);
+      const float l = sum_halves(st.l[qb]);
       inv = l > 0.f ? 1.f / l : 0.f;
     } else if constexpr (C::NORM == NORM_ABSSUM) {
-      const float l = st.l[qb] + xchg32(st.l[qb]);
+      const float l = sum_halves(st.l[qb]);
       inv = 1.f / fmaxf(l, 1.f);
     } else if constexpr (C::NORM == NORM_ABS_OF_SUM) {
-      const float l = st.l[qb] + xchg32(st.l[qb]);
+      const float l = sum_halves(st.l[qb]);
       inv = 1.f / fmaxf(fabsf(l), 1.f);
     }
     const int i = iw0 + qb * 32 + ql;
