@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <new>
 
 #include "dispatch.hpp"
@@ -158,6 +159,8 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     p.b2 = bias;
   }
   p.neg_q = d->scale < 0.f ? 1 : 0;
+  { const char* e = getenv("AE_ATTN_MAP"); p.map_mode = e ? atoi(e) : 0; }
+  { const char* e = getenv("AE_ATTN_PROF"); p.prof = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr; }
   if (mod == ae::MOD_DECAY)
     for (int hh = 0; hh < d->H_q; ++hh) h->decay.log2_gamma[hh] = std::log2(d->gamma[hh]);
 

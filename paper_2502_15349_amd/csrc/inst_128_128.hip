@@ -1,10 +1,16 @@
 // Kernel instantiations and tile shapes for D_qk = 128, D_v = 128.
 #include "dispatch.hpp"
 
+// tile shape: wavefronts, 32-key blocks per tile, 32-row q blocks per wave, LDS stages, pipelined loop
+#ifndef AE_SHAPE_128_128_NC
+#define AE_SHAPE_128_128_NC 8, 1, 1, 2, true
+#endif
+#ifndef AE_SHAPE_128_128_C
+#define AE_SHAPE_128_128_C 8, 1, 1, 2, true
+#endif
+
 namespace ae {
-static const KernelEntry kTable[] = {
-    //                  D_qk D_v  non-causal: waves, q-blocks/wave   causal: waves, q-blocks/wave
-    AE_ENTRIES_FOR_DIMS(128, 128, 8, 1, 8, 1)};
+static const KernelEntry kTable[] = {AE_ENTRIES_FOR_DIMS(128, 128, AE_SHAPE_128_128_NC, AE_SHAPE_128_128_C)};
 
 const KernelEntry* table_128_128(int* n) {
   *n = (int)(sizeof(kTable) / sizeof(kTable[0]));

@@ -1,10 +1,16 @@
 // Kernel instantiations and tile shapes for D_qk = 64, D_v = 64.
 #include "dispatch.hpp"
 
+// tile shape: wavefronts, 32-key blocks per tile, 32-row q blocks per wave, LDS stages, pipelined loop
+#ifndef AE_SHAPE_64_64_NC
+#define AE_SHAPE_64_64_NC 8, 2, 1, 2, true
+#endif
+#ifndef AE_SHAPE_64_64_C
+#define AE_SHAPE_64_64_C 8, 2, 1, 2, true
+#endif
+
 namespace ae {
-static const KernelEntry kTable[] = {
-    //                  D_qk D_v  non-causal: waves, q-blocks/wave   causal: waves, q-blocks/wave
-    AE_ENTRIES_FOR_DIMS(64, 64, 8, 1, 8, 1)};
+static const KernelEntry kTable[] = {AE_ENTRIES_FOR_DIMS(64, 64, AE_SHAPE_64_64_NC, AE_SHAPE_64_64_C)};
 
 const KernelEntry* table_64_64(int* n) {
   *n = (int)(sizeof(kTable) / sizeof(kTable[0]));
