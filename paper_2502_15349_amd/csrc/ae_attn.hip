@@ -159,14 +159,21 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     p.b2 = bias;
   }
   p.neg_q = d->scale < 0.f ? 1 : 0;
-  { const char* e = getenv("AE_ATTN_MAP"); p.map_mode = e ? atoi(e) : 0; }
   { const char* e = getenv("AE_ATTN_PROF"); p.prof = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr; }
   if (mod == ae::MOD_DECAY)
     for (int hh = 0; hh < d->H_q; ++hh) h->decay.log2_gamma[hh] = std::log2(d->gamma[hh]);
 
+  // Workgroup -> tile mapping (see attn_fwd_kernel): groups are dealt to the 8
+  // XCDs round-robin and walked `interleave` at a time per XCD.
   const int64_t per_group = (int64_t)p.n_qtiles * p.g;
-  const int64_t rounds = (p.n_groups + 7) / 8;
-  const int64_t grid = rounds * 8 * per_group;
+  const int64_t rounds = (p.n_groups + 7) / 8;  // groups per XCD
+  int interleave = 4;
+  if (const char* e = getenv("AE_ATTN_INTERLEAVE")) interleave = atoi(e);  // tuning aid
+  if (interleave < 1) interleave = 1;
+  if (interleave > rounds) interleave = (int)rounds;
+  p.interleave = interleave;
+  const int64_t blocks = (rounds + interleave - 1) / interleave;
+  const int64_t grid = blocks * interleave * 8 * per_group;
   if (grid > 0x7fffffffLL) {
     delete h;
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: grid of %lld workgroups exceeds the launch limit", (long long)grid);

@@ -26,31 +26,30 @@ constexpr KernelEntry make_entry(const char* name) {
 }
 
 // One row of the tile-shape table: for head dims (DQK, DV) and mask CAUSAL the
-// workgroup has WAVES wavefronts, each owning QB blocks of 32 query rows; the key tile has 32*NKB keys, fetched through
-// STAGES LDS buffers; PIPE selects the software-pipelined key loop.
+// workgroup has WAVES wavefronts of 32 query rows each; PIPE selects the
+// software-pipelined key loop (needs registers for a second score buffer).
 #define AE_ENTRY(...) AE_ENTRY_(__VA_ARGS__)
-#define AE_ENTRY_(DQK, DV, NORM, MOD, CAUSAL, WAVES, NKB, QB, STAGES, PIPE) \
-  make_entry<Cfg<DQK, DV, NORM, MOD, CAUSAL, WAVES, NKB, QB, STAGES, PIPE>>( \
-      "attn_fwd<" #DQK "," #DV "," #NORM "," #MOD "," #CAUSAL "," #WAVES "," #NKB "," #QB "," #STAGES "," #PIPE ">")
+#define AE_ENTRY_(DQK, DV, NORM, MOD, CAUSAL, WAVES, PIPE)  \
+  make_entry<Cfg<DQK, DV, NORM, MOD, CAUSAL, WAVES, PIPE>>( \
+      "attn_fwd<" #DQK "," #DV "," #NORM "," #MOD "," #CAUSAL "," #WAVES "," #PIPE ">")
 
 // Every (norm, mod) pair the library supports, for one (DQK, DV) and one tile
-// shape per mask value.
-// SHAPE_NC / SHAPE_C: "WAVES, NKB, QB, STAGES, PIPE" for the unmasked / causal kernels
+// shape "WAVES, PIPE" per mask value (SHAPE_NC unmasked, SHAPE_C causal).
 #define AE_ENTRIES_FOR_DIMS(DQK, DV, SHAPE_NC, SHAPE_C)            \
-  AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_PLAIN, false, SHAPE_NC),       \
-  AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_PLAIN, false, SHAPE_NC),       \
-  AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_PLAIN, false, SHAPE_NC),        \
-  AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_PLAIN, false, SHAPE_NC),    \
-  AE_ENTRY(DQK, DV, NORM_NONE, MOD_PLAIN, false, SHAPE_NC),          \
-  AE_ENTRY(DQK, DV, NORM_NONE, MOD_RELU, false, SHAPE_NC),           \
-  AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_PLAIN, true, SHAPE_C),          \
-  AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_PLAIN, true, SHAPE_C),          \
-  AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_PLAIN, true, SHAPE_C),           \
-  AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_PLAIN, true, SHAPE_C),       \
-  AE_ENTRY(DQK, DV, NORM_NONE, MOD_PLAIN, true, SHAPE_C),             \
-  AE_ENTRY(DQK, DV, NORM_NONE, MOD_RELU, true, SHAPE_C),              \
-  AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_DECAY, true, SHAPE_C),           \
-  AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_DECAY, true, SHAPE_C),       \
+  AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_PLAIN, false, SHAPE_NC),    \
+  AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_PLAIN, false, SHAPE_NC),    \
+  AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_PLAIN, false, SHAPE_NC),     \
+  AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_PLAIN, false, SHAPE_NC), \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_PLAIN, false, SHAPE_NC),       \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_RELU, false, SHAPE_NC),        \
+  AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_PLAIN, true, SHAPE_C),      \
+  AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_PLAIN, true, SHAPE_C),      \
+  AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_PLAIN, true, SHAPE_C),       \
+  AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_PLAIN, true, SHAPE_C),   \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_PLAIN, true, SHAPE_C),         \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_RELU, true, SHAPE_C),          \
+  AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_DECAY, true, SHAPE_C),       \
+  AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_DECAY, true, SHAPE_C),   \
   AE_ENTRY(DQK, DV, NORM_NONE, MOD_DECAY, true, SHAPE_C)
 
 const KernelEntry* table_64_64(int* n);

@@ -1,12 +1,12 @@
 // Kernel instantiations and tile shapes for D_qk = 64, D_v = 64.
 #include "dispatch.hpp"
 
-// tile shape: wavefronts, 32-key blocks per tile, 32-row q blocks per wave, LDS stages, pipelined loop
+// tile shape: wavefronts per workgroup, software-pipelined key loop
 #ifndef AE_SHAPE_64_64_NC
-#define AE_SHAPE_64_64_NC 8, 2, 1, 2, true
+#define AE_SHAPE_64_64_NC 8, false
 #endif
 #ifndef AE_SHAPE_64_64_C
-#define AE_SHAPE_64_64_C 8, 2, 1, 2, true
+#define AE_SHAPE_64_64_C 8, false
 #endif
 
 namespace ae {
