@@ -105,6 +105,9 @@ def main():
     ap.add_argument("--workload", default="c2_gqa_causal_softmax")
     ap.add_argument("--no-variants", action="store_true", help="skip the per-variant table (other configs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
+                    help="instead of the benchmark, run a plain device-to-device copy of this many MiB "
+                         "(reference reading for the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -119,6 +122,16 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if a.calib_copy:
+        n = a.calib_copy << 20
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calib_copy_bytes": n, "reads": n, "writes": n}))
+        return
     w = CONFIGS[a.workload]
     Qc, Kc, Vc = make_inputs(w)
     Q, K, V = Qc.to(dev), Kc.to(dev), Vc.to(dev)
