@@ -77,13 +77,14 @@ constexpr int kMaxDecayHeads = 256;
 struct Params {
   const __bf16* Q;
   const __bf16* K;
-  const __bf16* V;
+  const __bf16* V;   // [B, H_kv, L_k, D_v], or with VT kernels the transposed copy [B, H_kv, D_v, ldvt]
   float* O;
   int B, H_q, H_kv, L_q, L_k;
   int g;           // H_q / H_kv
   int n_qtiles;    // ceil(L_q / BLOCK_M)
   int n_groups;    // B * H_kv
   int interleave;  // (batch, kv head) groups walked together on one XCD
+  int ldvt;        // VT kernels: keys per row of the transposed V copy (L_k rounded up to 64, zero filled)
   int64_t qs[3], ks[3], vs[3], os[3];  // element strides {batch, head, row}
   float c;         // |scale| * log2(e)  (softmax, sigmoid)  or |scale| (others)
   float b2;        // bias * log2(e)     (softmax, sigmoid)  or bias (others)
@@ -95,19 +96,25 @@ struct DecayTable {
   float log2_gamma[kMaxDecayHeads];
 };
 
-template <int DQK_, int DV_, int NORM_, int MOD_, bool CAUSAL_, int WAVES_, bool PIPE_>
+template <int DQK_, int DV_, int NORM_, int MOD_, bool CAUSAL_, int WAVES_, bool PIPE_, bool VT_>
 struct Cfg {
   static constexpr int DQK = DQK_, DV = DV_, NORM = NORM_, MOD = MOD_, WAVES = WAVES_;
   static constexpr bool CAUSAL = CAUSAL_, PIPE = PIPE_;
+  // VT: V arrives pre-transposed ([D_v][keys], written by transpose_v_kernel), so the
+  // aggregation reads its A fragments with one 128-bit LDS load instead of two
+  // 64-bit transposing loads (LDS instruction issue is the first limit of this
+  // kernel).  The key order inside a 16-key step then has to be the natural one,
+  // which is arranged by permuting which K row each lane scores (k_frag_offsets).
+  static constexpr bool VT = VT_;
   static constexpr int SUB_N = 32;    // keys per compute sub-tile
   static constexpr int BLOCK_N = 64;  // keys per LDS tile (two sub-tiles)
   static constexpr int BLOCK_M = 32 * WAVES;
   static constexpr int THREADS = 64 * WAVES;
   // LDS tiles are row-major and unpadded; CPR = 16-byte chunks per row.
   static constexpr int RB_K = DQK * 2, RB_V = DV * 2;
-  static constexpr int CPR_K = DQK / 8, CPR_V = DV / 8;
+  static constexpr int CPR_K = DQK / 8, CPR_V = VT ? 8 : DV / 8;  // VT: rows are 64 keys = 128 bytes
   static constexpr int K_BYTES = BLOCK_N * RB_K;
-  static constexpr int V_BYTES = BLOCK_N * RB_V;
+  static constexpr int V_BYTES = BLOCK_N * RB_V;  // same size either way round
   // Scoring runs one sub-tile ahead of aggregation, so while tile j is being
   // aggregated K(j) and K(j+1) are both read and K(j+2) is arriving; V(j) is
   // read while V(j+1) arrives.
@@ -117,6 +124,7 @@ struct Cfg {
   static constexpr int KI = (NB_K + WAVES - 1) / WAVES, VI = (NB_V + WAVES - 1) / WAVES;
   static constexpr int T = DQK / 16;  // contraction steps of the scoring MFMA
   static constexpr int DB = DV / 32;  // 32-wide blocks of output columns
+  static constexpr int VA = VT ? 4 : DB;  // per-lane V fragment base addresses
   static_assert(DQK % 16 == 0 && DV % 32 == 0, "head dims must fit the MFMA tile");
   static_assert(K_BYTES % 1024 == 0 && V_BYTES % 1024 == 0, "tiles must be whole 1 KB blocks");
   static_assert(CPR_K == 8 || CPR_K == 16 || CPR_K == 24, "K swizzle is defined for these row sizes");
@@ -256,20 +264,25 @@ struct RowState {
 // j0 + 8*(r/4) + 4*half + (r%4).  Work on them is cut into 8 pairs (registers
 // 2q, 2q+1 -> one packed bf16x2 word); pairs 0..3 form the B operand of the
 // first aggregation step (keys 0..15 of the sub-tile), pairs 4..7 of the second.
-__device__ __forceinline__ constexpr int key_offset(int r) { return 8 * (r / 4) + (r % 4); }
+// (VT kernels: register r is key j0 + 16*(r/8) + 8*half + (r%8), see k_frag_offsets.)
+template <bool VT>
+__device__ __forceinline__ constexpr int key_offset(int r) {
+  return VT ? 16 * (r / 8) + (r % 8) : 8 * (r / 4) + (r % 4);
+}
 
 // Per-sub-tile, per-lane constants of the modification.
 struct TileCtx {
   int jlim;     // register r is visible  <=>  key_offset(r) <= jlim   (masked sub-tiles only)
-  float dbase;  // decay: log2(gamma) * (i + off - j0 - 4*half)
+  float dbase;  // decay: log2(gamma) * (i + off - j0 - (4 or 8)*half)
 };
 
 template <class C, bool MASKED>
 __device__ __forceinline__ TileCtx tile_ctx(const Params& p, int i, int j0, int off, float g2) {
   const int half = (threadIdx.x & 63) >> 5;
   TileCtx c;
-  c.jlim = MASKED ? min(C::CAUSAL ? i + off : p.L_k - 1, p.L_k - 1) - j0 - 4 * half : 0;
-  c.dbase = C::MOD == MOD_DECAY ? g2 * (float)(i + off - j0 - 4 * half) : 0.f;
+  constexpr int HS = C::VT ? 8 : 4;  // key offset of the upper half wave
+  c.jlim = MASKED ? min(C::CAUSAL ? i + off : p.L_k - 1, p.L_k - 1) - j0 - HS * half : 0;
+  c.dbase = C::MOD == MOD_DECAY ? g2 * (float)(i + off - j0 - HS * half) : 0.f;
   return c;
 }
 
@@ -284,7 +297,7 @@ __device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, con
   for (int u = 0; u < 2; ++u) {
     const int r = 2 * q + u;
     float x = s[r];
-    const bool hidden = MASKED && (key_offset(r) > tc.jlim);
+    const bool hidden = MASKED && (key_offset<C::VT>(r) > tc.jlim);
     if constexpr (C::NORM == NORM_SOFTMAX) {
       if (hidden) x = -INFINITY;
     } else if constexpr (C::NORM == NORM_SIGMOID) {
@@ -293,7 +306,7 @@ __device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, con
     } else {
       if constexpr (C::MOD == MOD_DECAY) {
         // gamma^(i + off - j) = 2^(log2(gamma) * (i + off - j))
-        x = x * p.c * fast_exp2(__builtin_fmaf(-g2, (float)key_offset(r), tc.dbase));
+        x = x * p.c * fast_exp2(__builtin_fmaf(-g2, (float)key_offset<C::VT>(r), tc.dbase));
       } else {
         x = __builtin_fmaf(x, p.c, p.b2);
         if constexpr (C::MOD == MOD_RELU) x = fmaxf(x, 0.f);
@@ -377,7 +390,12 @@ __device__ __forceinline__ void finish_done(RowState<C>& st, float acc) {
 template <class C>
 __device__ __forceinline__ void k_frag_offsets(uint32_t base, uint32_t (&kaddr)[C::T]) {
   const int lane = threadIdx.x & 63;
-  const int ql = lane & 31, half = lane >> 5;
+  const int half = lane >> 5;
+  int ql = lane & 31;
+  // VT: MFMA row m scores key (m with bits 2 and 3 swapped), so that a lane's
+  // accumulator registers 8t..8t+7 are keys 16t + 8*half + 0..7 in order -- the
+  // order of a 16-byte piece of a transposed V row.
+  if (C::VT) ql = (ql & ~12) | ((ql & 4) << 1) | ((ql & 8) >> 1);
 #pragma unroll
   for (int t = 0; t < C::T; ++t) kaddr[t] = base + ql * C::RB_K + (((2 * t + half) ^ kswz<C::CPR_K>(ql)) * 16);
 }
@@ -390,14 +408,23 @@ __device__ __forceinline__ void k_frag_offsets(uint32_t base, uint32_t (&kaddr)[
 // 4*half + (i/4) -- swizzle included (it only depends on the row modulo 4, a
 // per-lane constant).
 template <class C>
-__device__ __forceinline__ void v_frag_offsets(uint32_t base, uint32_t (&vaddr)[C::DB]) {
+__device__ __forceinline__ void v_frag_offsets(uint32_t base, uint32_t (&vaddr)[C::VA]) {
   const int lane = threadIdx.x & 63;
   const int half = lane >> 5, li = lane & 15;
-  const int row = 4 * half + (li >> 2);
-  const int cl = 2 * ((lane >> 4) & 1) + ((li & 3) >> 1);  // chunk within the 64-byte group
+  if constexpr (C::VT) {
+    // Transposed tile: row d (128 bytes = 64 keys), chunk 2*ts + half holds keys
+    // 16*ts + 8*half .. +7 (ts = 16-key step inside the tile, 0..3).  Chunks are
+    // swizzled like K rows of 128 bytes; output-column block db is at +32 rows.
+    const int d = lane & 31;
 #pragma unroll
-  for (int db = 0; db < C::DB; ++db)
-    vaddr[db] = base + row * C::RB_V + ((4 * (db ^ vswz<C::CPR_V>(row)) + cl) * 16) + (li & 1) * 8;
+    for (int ts = 0; ts < 4; ++ts) vaddr[ts] = base + d * 128 + (((2 * ts + half) ^ kswz<8>(d)) * 16);
+  } else {
+    const int row = 4 * half + (li >> 2);
+    const int cl = 2 * ((lane >> 4) & 1) + ((li & 3) >> 1);  // chunk within the 64-byte group
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db)
+      vaddr[db] = base + row * C::RB_V + ((4 * (db ^ vswz<C::CPR_V>(row)) + cl) * 16) + (li & 1) * 8;
+  }
 }
 
 typedef __attribute__((address_space(3))) char lds_char;
@@ -410,6 +437,16 @@ __device__ __forceinline__ bf16x8 read_v_frag(uint32_t addr, int row8_bytes) {
       __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)(addr + row8_bytes));
   const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, both);
+}
+
+// A operand of the aggregation MFMA for sub-tile `sub` (0/1) of the V tile,
+// 16-key step t (0/1) and output-column block db.
+template <class C>
+__device__ __forceinline__ bf16x8 load_v_frag(const uint32_t (&vaddr)[C::VA], int sub, int t, int db) {
+  if constexpr (C::VT)
+    return read_k_frag(vaddr[2 * sub + t] + db * 32 * 128);
+  else
+    return read_v_frag(vaddr[db] + (32 * sub + 16 * t) * C::RB_V, 8 * C::RB_V);
 }
 
 constexpr int kFragAhead = 4;  // LDS fragment reads kept in flight ahead of their MFMA
@@ -451,12 +488,12 @@ __device__ __forceinline__ void phase_a(const Params& p, const uint32_t (&kaddr)
 
 // ---- phase B: O^T += V_sub^T P^T  ||  weight pairs [FIN_LO, 8) of s_cur, then the
 //      modification / row max of s_nxt ---------------------------------------------
-//   DO_PV    aggregate the sub-tile whose first row is at LDS offset `vrow_off`
+//   DO_PV    aggregate sub-tile `vsub` (0/1) of the V tile vaddr points into
 //   DO_POST  mask / modify / reduce the freshly scored s_nxt (sub-tile starting at j0)
 // The aggregation MFMAs run key-step major: the first DB of them need weight
 // pairs 0..3 only, so pairs 4..7 may still be computed next to those.
 template <class C, bool DO_PV, int FIN_LO, bool DO_POST, bool MASKED>
-__device__ __forceinline__ void phase_b(const Params& p, const uint32_t (&vaddr)[C::DB], int vrow_off, u32x4 (&pk)[2],
+__device__ __forceinline__ void phase_b(const Params& p, const uint32_t (&vaddr)[C::VA], int vsub, u32x4 (&pk)[2],
                                         RowState<C>& st, const f32x16& s_cur, float k0, float& acc, f32x16& s_nxt,
                                         int i, int j0, int off, float g2, bool& moved, float& xm) {
   constexpr int DB = C::DB, NM = DO_PV ? 2 * DB : 0;
@@ -469,7 +506,7 @@ __device__ __forceinline__ void phase_b(const Params& p, const uint32_t (&vaddr)
 
   bf16x8 ring[PF > 0 ? PF : 1];
 #pragma unroll
-  for (int g = 0; g < PF; ++g) ring[g] = read_v_frag(vaddr[g % DB] + vrow_off + 16 * (g / DB) * C::RB_V, 8 * C::RB_V);
+  for (int g = 0; g < PF; ++g) ring[g] = load_v_frag<C>(vaddr, vsub, g / DB, g % DB);
 
   TileCtx tc;
   if constexpr (DO_POST) tc = tile_ctx<C, MASKED>(p, i, j0, off, g2);
@@ -483,8 +520,7 @@ __device__ __forceinline__ void phase_b(const Params& p, const uint32_t (&vaddr)
     const int t = g / DB, db = g % DB;
     st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[g % PF], __builtin_bit_cast(bf16x8, pk[t]), st.o[db], 0, 0, 0);
     if (g + PF < NM)  // refill the slot just consumed
-      ring[g % PF] =
-          read_v_frag(vaddr[(g + PF) % DB] + vrow_off + 16 * ((g + PF) / DB) * C::RB_V, 8 * C::RB_V);
+      ring[g % PF] = load_v_frag<C>(vaddr, vsub, (g + PF) / DB, (g + PF) % DB);
     if (g < DB) {
 #pragma unroll
       for (int q = FIN_LO; q < 8; ++q)
@@ -534,7 +570,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
 
   const __bf16* qbase = p.Q + b * p.qs[0] + hq * p.qs[1];
   const __bf16* kbase = p.K + b * p.ks[0] + hkv * p.ks[1];
-  const __bf16* vbase = p.V + b * p.vs[0] + hkv * p.vs[1];
+  const __bf16* vbase = C::VT ? p.V + ((int64_t)b * p.H_kv + hkv) * C::DV * p.ldvt : p.V + b * p.vs[0] + hkv * p.vs[1];
   float* obase = p.O + b * p.os[0] + hq * p.os[1];
 
   // ---- Q fragments (B operand of S^T = K Q^T), resident for the whole kernel -
@@ -574,13 +610,16 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // LDS: K_STAGES K buffers, then V_STAGES V buffers; tile j lives in buffer j % stages.
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const uint32_t vlds0 = lds0 + C::K_STAGES * C::K_BYTES;
-  uint32_t kaddr[C::T], vaddr[C::DB];  // fragment addresses inside the K / V buffer in use
+  uint32_t kaddr[C::T], vaddr[C::VA];  // fragment addresses inside the K / V buffer in use
   k_frag_offsets<C>(lds0, kaddr);
   v_frag_offsets<C>(vlds0, vaddr);
   uint32_t kgoff[C::KI], vgoff[C::VI];
   int kgrow[C::KI], vgrow[C::VI];
   dma_offsets<C::WAVES, C::BLOCK_N, C::CPR_K, false>(wave, p.ks[2], kgoff, kgrow);
-  dma_offsets<C::WAVES, C::BLOCK_N, C::CPR_V, true>(wave, p.vs[2], vgoff, vgrow);
+  if constexpr (C::VT)  // tile = D_v rows of 64 keys out of rows of ldvt keys; swizzled like K
+    dma_offsets<C::WAVES, C::DV, 8, false>(wave, p.ldvt, vgoff, vgrow);
+  else
+    dma_offsets<C::WAVES, C::BLOCK_N, C::CPR_V, true>(wave, p.vs[2], vgoff, vgrow);
   // Tile indices past the last tile are clamped: the copy is redundant but keeps
   // every wave's stream of loads identical.
   const int last_tile = max(n_tiles - 1, 0);
@@ -589,8 +628,16 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
                                              lds0 + (jt % C::K_STAGES) * C::K_BYTES, wave, kgoff, kgrow);
   };
   auto load_v = [&](int jt) {
-    dma_tile<C::WAVES, C::BLOCK_N, C::CPR_V>(vbase, p.vs[2], min(jt, last_tile) * C::BLOCK_N, p.L_k,
-                                             vlds0 + (jt % C::V_STAGES) * C::V_BYTES, wave, vgoff, vgrow);
+    const uint32_t dst = vlds0 + (jt % C::V_STAGES) * C::V_BYTES;
+    if constexpr (C::VT) {
+      // key columns [64*jt, +64) of every row of the transposed copy (zero filled past L_k)
+      const __bf16* tile = vbase + (int64_t)min(jt, last_tile) * C::BLOCK_N;
+#pragma unroll
+      for (int n = 0; n < C::VI; ++n) dma16(tile, vgoff[n], dst + ((wave + n * C::WAVES) % C::NB_V) * 1024);
+    } else {
+      dma_tile<C::WAVES, C::BLOCK_N, C::CPR_V>(vbase, p.vs[2], min(jt, last_tile) * C::BLOCK_N, p.L_k, dst, wave, vgoff,
+                                               vgrow);
+    }
   };
 
   f32x16 s_a, s_b;  // scores of the even / odd sub-tile in flight (without PIPE only s_a)
@@ -623,9 +670,9 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
 
   // One sub-step: sub-tile u (scores in s_cur, already modified / reduced) is
   // turned into weights and aggregated from V rows [vrow_off, +32) of the
-  // current V buffer while sub-tile u+1 is scored from K rows [krow_off, +32)
+  // current V buffer (sub-tile vsub of it) while sub-tile u+1 is scored from K rows [krow_off, +32)
   // of the buffer kaddr points into, into s_nxt.
-  auto sub_step = [&](int u, f32x16& s_cur, f32x16& s_nxt, int krow_off, int vrow_off) {
+  auto sub_step = [&](int u, f32x16& s_cur, f32x16& s_nxt, int krow_off, int vsub) {
     if (u >= n_vis) return;
     const bool more = u + 1 < n_vis;
     const float k0 = finish_k0<C>(p, st);
@@ -636,10 +683,10 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
         phase_a<C, true, 0, 4>(p, kaddr, krow_off, qf, s_nxt, s_cur, k0, acc, pk);
         AE_TICK(1);
         if (needs_mask(u + 1))
-          phase_b<C, true, 4, true, true>(p, vaddr, vrow_off, pk, st, s_cur, k0, acc, s_nxt, i, (u + 1) * C::SUB_N, off,
+          phase_b<C, true, 4, true, true>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_nxt, i, (u + 1) * C::SUB_N, off,
                                           g2, moved, xm);
         else
-          phase_b<C, true, 4, true, false>(p, vaddr, vrow_off, pk, st, s_cur, k0, acc, s_nxt, i, (u + 1) * C::SUB_N, off,
+          phase_b<C, true, 4, true, false>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_nxt, i, (u + 1) * C::SUB_N, off,
                                            g2, moved, xm);
         AE_TICK(2);
         finish_done<C>(st, acc);
@@ -648,7 +695,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       } else {
         // this wave's last visible sub-tile: nothing further to score
         phase_a<C, false, 0, 4>(p, kaddr, krow_off, qf, s_nxt, s_cur, k0, acc, pk);
-        phase_b<C, true, 4, false, false>(p, vaddr, vrow_off, pk, st, s_cur, k0, acc, s_nxt, i, 0, off, g2, moved, xm);
+        phase_b<C, true, 4, false, false>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_nxt, i, 0, off, g2, moved, xm);
         finish_done<C>(st, acc);
       }
     } else {
@@ -658,16 +705,16 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       phase_a<C, false, 0, 8>(p, kaddr, krow_off, qf, s_cur, s_cur, k0, acc, pk);
       finish_done<C>(st, acc);
       AE_TICK(1);
-      phase_b<C, true, 8, false, false>(p, vaddr, vrow_off, pk, st, s_cur, k0, acc, s_cur, i, 0, off, g2, moved, xm);
+      phase_b<C, true, 8, false, false>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_cur, i, 0, off, g2, moved, xm);
       AE_TICK(2);
       if (more) {
         phase_a<C, true, 0, 0>(p, kaddr, krow_off, qf, s_cur, s_cur, k0, acc, pk);
         AE_TICK(3);
         if (needs_mask(u + 1))
-          phase_b<C, false, 8, true, true>(p, vaddr, vrow_off, pk, st, s_cur, k0, acc, s_cur, i, (u + 1) * C::SUB_N, off,
+          phase_b<C, false, 8, true, true>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_cur, i, (u + 1) * C::SUB_N, off,
                                            g2, moved, xm);
         else
-          phase_b<C, false, 8, true, false>(p, vaddr, vrow_off, pk, st, s_cur, k0, acc, s_cur, i, (u + 1) * C::SUB_N, off,
+          phase_b<C, false, 8, true, false>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_cur, i, (u + 1) * C::SUB_N, off,
                                             g2, moved, xm);
         lazy_rescale<C>(st, moved, xm);
         AE_TICK(4);
@@ -694,12 +741,12 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       for (int t = 0; t < C::T; ++t) kaddr[t] += dk;
       kbuf = nk;
     }
-    sub_step(2 * jt + 1, s_odd, s_a, 0, 32 * C::RB_V);  // scores rows 0..31 of K(jt+1)
+    sub_step(2 * jt + 1, s_odd, s_a, 0, 1);  // scores rows 0..31 of K(jt+1)
     {
       const int nv = (vbuf + 1 == C::V_STAGES) ? 0 : vbuf + 1;
       const uint32_t dv = (uint32_t)((nv - vbuf) * C::V_BYTES);
 #pragma unroll
-      for (int db = 0; db < C::DB; ++db) vaddr[db] += dv;
+      for (int a = 0; a < C::VA; ++a) vaddr[a] += dv;
       vbuf = nv;
     }
     AE_TICK(6);
