@@ -28,7 +28,7 @@ PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flo
 MEASURED_TRAFFIC_BYTES = {}
 
 
-def time_gpu(A, torch, w, Q, K, V, steps, warmup, entry="forward_ws", settle_s=0.4):
+def time_gpu(A, torch, w, Q, K, V, steps, warmup, entry="forward", settle_s=0.4):
     """Returns (wall ms per step, mean step ms by HIP events, output, launch info).
     entry: "forward" (one kernel) or "forward_ws" (layout pass + attention kernel,
     caller-provided workspace allocated here, outside the timed region)."""
@@ -122,7 +122,7 @@ def main():
     ap.add_argument("--workload", default="c2_gqa_causal_softmax")
     ap.add_argument("--no-variants", action="store_true", help="skip the per-variant table (other configs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--entry", choices=["forward", "forward_ws"], default="forward_ws",
+    ap.add_argument("--entry", choices=["forward", "forward_ws"], default="forward",
                     help="C-ABI entry point to time (forward_ws: V layout pass + attention kernel, both timed)")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device-to-device copy of this many MiB "
