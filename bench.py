@@ -28,24 +28,16 @@ PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flo
 MEASURED_TRAFFIC_BYTES = {}
 
 
-def time_gpu(A, torch, w, Q, K, V, steps, warmup, entry="forward", settle_s=0.4):
-    """Returns (wall ms per step, mean step ms by HIP events, output, launch info).
-    entry: "forward" (one kernel) or "forward_ws" (layout pass + attention kernel,
-    caller-provided workspace allocated here, outside the timed region)."""
+def time_gpu(A, torch, w, Q, K, V, steps, warmup, settle_s=0.4):
+    """Returns (wall ms per step, mean step ms by HIP events, output, launch info)."""
     O = torch.empty((w.B, w.H_q, w.L_q, w.D_v), dtype=torch.float32, device=Q.device)
     h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
                          scale=w.scale_value, score_mod=w.score_mod, bias=w.bias, gamma=w.gamma(),
                          norm=w.norm, mask=w.mask)
     info = A.ae_attn_query(h)
     stream = torch.cuda.current_stream()
-    info["entry"] = entry
-    if entry == "forward_ws":
-        ws = torch.empty(A.ae_attn_workspace_size(h), dtype=torch.uint8, device=Q.device)
-        args = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), ws.data_ptr(), ws.numel(), stream.cuda_stream)
-        fwd = A.ae_attn_forward_ws
-    else:
-        args = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), stream.cuda_stream)
-        fwd = A.ae_attn_forward
+    args = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), stream.cuda_stream)
+    fwd = A.ae_attn_forward
     try:
         # The GPU reaches its working clock only after ~0.1-0.3 s of sustained load and a
         # step lasts a fraction of a millisecond: spin the same call until the clock has
@@ -122,8 +114,6 @@ def main():
     ap.add_argument("--workload", default="c2_gqa_causal_softmax")
     ap.add_argument("--no-variants", action="store_true", help="skip the per-variant table (other configs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--entry", choices=["forward", "forward_ws"], default="forward",
-                    help="C-ABI entry point to time (forward_ws: V layout pass + attention kernel, both timed)")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device-to-device copy of this many MiB "
                          "(reference reading for the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
@@ -155,7 +145,7 @@ def main():
     Qc, Kc, Vc = make_inputs(w)
     Q, K, V = Qc.to(dev), Kc.to(dev), Vc.to(dev)
     torch.cuda.synchronize()
-    wall_ms, ker_ms, O, info = time_gpu(A, torch, w, Q, K, V, a.steps, a.warmup, a.entry)
+    wall_ms, ker_ms, O, info = time_gpu(A, torch, w, Q, K, V, a.steps, a.warmup)
     par = parity_sample(w, Q, K, V, O)
     flop = w.mfma_flop()
     value = flop / (wall_ms * 1e-3) / 1e12
@@ -168,8 +158,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H_q": w.H_q, "H_kv": w.H_kv, "L_q": w.L_q, "L_k": w.L_k,
                    "D_qk": w.D_qk, "D_v": w.D_v, "score_mod": w.score_mod, "norm": w.norm, "mask": w.mask,
-                   "out": "fp32", "entry": "ae_attn_" + info["entry"],
-                   "kernel": info["kernel_ws"] if info["entry"] == "forward_ws" else info["kernel"], "block_m": info["block_m"], "block_n": info["block_n"],
+                   "out": "fp32", "entry": "ae_attn_forward",
+                   "kernel": info["kernel"], "block_m": info["block_m"], "block_n": info["block_n"],
                    "grid": info["grid_size"], "threads": info["block_threads"], "lds_bytes": info["lds_bytes"]},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
@@ -190,7 +180,7 @@ def main():
             q, k, v = make_inputs(wv)
             Q, K, V = q.to(dev), k.to(dev), v.to(dev)
             steps = max(5, min(a.steps, 20))
-            _, kms, O, _ = time_gpu(A, torch, wv, Q, K, V, steps, min(a.warmup, 5), a.entry)
+            _, kms, O, _ = time_gpu(A, torch, wv, Q, K, V, steps, min(a.warmup, 5))
             pv = parity_sample(wv, Q, K, V, O)
             tf = wv.mfma_flop() / (kms * 1e-3) / 1e12
             variants[name] = {"tflops": round(tf, 2), "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4),

@@ -111,25 +111,6 @@ ae_status_t ae_attn_create(const ae_attn_desc_t *desc, ae_attn_t **out);
 ae_status_t ae_attn_forward(const ae_attn_t *h, const void *Q, const void *K,
                             const void *V, void *O, void *stream);
 
-/* Bytes of caller-provided device workspace ae_attn_forward_ws needs for this
- * handle (B * H_kv * D_v * roundup(L_k, 64) bf16 values); 0 for a NULL handle.  */
-size_t ae_attn_workspace_size(const ae_attn_t *h);
-
-/* Same operator and arguments as ae_attn_forward, plus a device workspace of at
- * least ae_attn_workspace_size(h) bytes (16-byte aligned, not aliasing the other
- * buffers).  Enqueues two kernels on `stream`: a layout pass that writes V
- * transposed ([D_v, keys] per kv head) into the workspace, then the attention
- * kernel reading V from there with 128-bit LDS fragment loads -- the faster
- * path on MI355X, where LDS instruction issue limits the kernel.  The whole
- * operator (scoring, modification, row normalization, aggregation) still runs in
- * the one fused kernel; the score matrix never reaches device memory.  The
- * workspace is scratch: its contents are undefined afterwards, and calls that
- * overlap in time must not share it.  Allocates nothing.
- * Errors: as ae_attn_forward, plus AE_ERR_INVALID_ARG for a short workspace.    */
-ae_status_t ae_attn_forward_ws(const ae_attn_t *h, const void *Q, const void *K,
-                               const void *V, void *O, void *workspace,
-                               size_t workspace_bytes, void *stream);
-
 /* Frees the handle.  NULL is a no-op.                                         */
 ae_status_t ae_attn_destroy(ae_attn_t *h);
 
@@ -141,8 +122,6 @@ ae_status_t ae_attn_query(const ae_attn_t *h, int32_t *block_m, int32_t *block_n
 /* Name of the device kernel a handle launches (for matching profiler rows);
  * owned by the library, valid for the life of the process.                    */
 const char *ae_attn_kernel_name(const ae_attn_t *h);
-/* Same for the attention kernel of ae_attn_forward_ws.                        */
-const char *ae_attn_kernel_name_ws(const ae_attn_t *h);
 
 /* Message of the calling thread's most recent failing call ("" if none).     */
 const char *ae_attn_last_error(void);

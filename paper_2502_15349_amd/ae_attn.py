@@ -1,7 +1,7 @@
 """ctypes binding of libae_attn.so: argument marshalling only.
 
 Names mirror the C ABI (include/ae_attn.h): ae_attn_create, ae_attn_forward,
-ae_attn_forward_ws, ae_attn_workspace_size, ae_attn_destroy, ae_attn_query.  Every step of the attention path runs in the
+ae_attn_destroy, ae_attn_query.  Every step of the attention path runs in the
 HIP kernels; PyTorch supplies device memory and the stream, nothing else.
 Importing this module fails if the library has not been built
 (`python -m paper_2502_15349_amd.build`): there is no fallback path.
@@ -40,12 +40,6 @@ _lib.ae_attn_create.argtypes = [C.POINTER(ae_attn_desc_t), C.POINTER(C.c_void_p)
 _lib.ae_attn_create.restype = C.c_int
 _lib.ae_attn_forward.argtypes = [C.c_void_p] * 6
 _lib.ae_attn_forward.restype = C.c_int
-_lib.ae_attn_workspace_size.argtypes = [C.c_void_p]
-_lib.ae_attn_workspace_size.restype = C.c_size_t
-_lib.ae_attn_forward_ws.argtypes = [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
-_lib.ae_attn_forward_ws.restype = C.c_int
-_lib.ae_attn_kernel_name_ws.argtypes = [C.c_void_p]
-_lib.ae_attn_kernel_name_ws.restype = C.c_char_p
 _lib.ae_attn_destroy.argtypes = [C.c_void_p]
 _lib.ae_attn_destroy.restype = C.c_int
 _lib.ae_attn_query.argtypes = [C.c_void_p] + [C.POINTER(C.c_int32)] * 5
@@ -104,16 +98,6 @@ def ae_attn_forward(handle: int, Q: int, K: int, V: int, O: int, stream: int = 0
     _check(_lib.ae_attn_forward(handle, Q, K, V, O, stream))
 
 
-def ae_attn_workspace_size(handle: int) -> int:
-    return int(_lib.ae_attn_workspace_size(handle))
-
-
-def ae_attn_forward_ws(handle: int, Q: int, K: int, V: int, O: int, workspace: int, workspace_bytes: int,
-                       stream: int = 0) -> None:
-    """As ae_attn_forward, with a caller-provided device workspace (address, size in bytes)."""
-    _check(_lib.ae_attn_forward_ws(handle, Q, K, V, O, workspace, workspace_bytes, stream))
-
-
 def ae_attn_destroy(handle: Optional[int]) -> None:
     _check(_lib.ae_attn_destroy(handle))
 
@@ -124,18 +108,14 @@ def ae_attn_query(handle: int) -> dict:
     keys = ("block_m", "block_n", "lds_bytes", "grid_size", "block_threads")
     out = {k: int(x.value) for k, x in zip(keys, v)}
     out["kernel"] = _lib.ae_attn_kernel_name(handle).decode()
-    out["kernel_ws"] = _lib.ae_attn_kernel_name_ws(handle).decode()
-    out["workspace_bytes"] = ae_attn_workspace_size(handle)
     return out
 
 
 # ---- convenience for torch callers (still marshalling only) -------------------
 def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
-                      mask="none", out=None, stream=None, workspace=None):
+                      mask="none", out=None, stream=None):
     """Runs the HIP operator on CUDA/HIP bf16 tensors laid out [B, H, L, D]
-    (last dim contiguous) and returns O as fp32 [B, H_q, L_q, D_v].
-    workspace: None -> ae_attn_forward; True -> a scratch tensor is allocated here and
-    ae_attn_forward_ws is used; a uint8 device tensor -> used as the workspace."""
+    (last dim contiguous) and returns O as fp32 [B, H_q, L_q, D_v]."""
     import torch
 
     if not (Q.is_cuda and K.is_cuda and V.is_cuda):
@@ -156,19 +136,13 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
     try:
         s = torch.cuda.current_stream(Q.device) if stream is None else stream
         with torch.cuda.device(Q.device):
-            if workspace is None or workspace is False:
-                ae_attn_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), s.cuda_stream)
-            else:
-                if workspace is True:
-                    workspace = torch.empty(ae_attn_workspace_size(h), dtype=torch.uint8, device=Q.device)
-                ae_attn_forward_ws(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
-                                   workspace.data_ptr(), workspace.numel(), s.cuda_stream)
+            ae_attn_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), s.cuda_stream)
     finally:
         ae_attn_destroy(h)
     return out
 
 
-def run_workload(w, Q, K, V, out=None, workspace=None):
+def run_workload(w, Q, K, V, out=None):
     """attention_forward with the parameters of a workloads.Workload."""
     return attention_forward(Q, K, V, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
-                             gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out, workspace=workspace)
+                             gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out)

@@ -23,14 +23,14 @@ ae_status_t fail(ae_status_t code, const char* fmt, ...) {
   return code;
 }
 
-const ae::KernelEntry* find_kernel(int dqk, int dv, int norm, int mod, int causal, int vt) {
+const ae::KernelEntry* find_kernel(int dqk, int dv, int norm, int mod, int causal) {
   typedef const ae::KernelEntry* (*table_fn)(int*);
   static const table_fn tables[] = {ae::table_64_64, ae::table_128_128, ae::table_128_256, ae::table_192_128};
   for (table_fn tf : tables) {
     int n = 0;
     const ae::KernelEntry* t = tf(&n);
     for (int i = 0; i < n; ++i)
-      if (t[i].dqk == dqk && t[i].dv == dv && t[i].norm == norm && t[i].mod == mod && t[i].causal == causal && t[i].vt == vt)
+      if (t[i].dqk == dqk && t[i].dv == dv && t[i].norm == norm && t[i].mod == mod && t[i].causal == causal)
         return &t[i];
   }
   return nullptr;
@@ -57,8 +57,7 @@ void fill_strides(int64_t dst[3], const int64_t src[3], int H, int L, int D) {
 
 struct ae_attn {
   ae_attn_desc_t desc;
-  const ae::KernelEntry* kernel;     // V read as given
-  const ae::KernelEntry* kernel_vt;  // V read from the transposed copy in the caller's workspace
+  const ae::KernelEntry* kernel;
   ae::Params params;  // pointers filled in per call
   ae::DecayTable decay;
   int grid;
@@ -105,8 +104,7 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
       if (!std::isfinite(d->gamma[h]) || !(d->gamma[h] > 0.f))
         return fail(AE_ERR_INVALID_ARG, "ae_attn_create: gamma[%d] must be finite and > 0", h);
   }
-  const ae::KernelEntry* k = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, d->mask == AE_MASK_CAUSAL, 0);
-  const ae::KernelEntry* kvt = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, d->mask == AE_MASK_CAUSAL, 1);
+  const ae::KernelEntry* k = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, d->mask == AE_MASK_CAUSAL);
   if (!k)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: no kernel for score_mod %d with norm %d", (int)d->score_mod,
                 (int)d->norm);
@@ -117,7 +115,6 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   h->desc = *d;
   h->desc.gamma = nullptr;  // the caller's array is not kept
   h->kernel = k;
-  h->kernel_vt = kvt;
 
   ae::Params& p = h->params;
   p.B = d->B; p.H_q = d->H_q; p.H_kv = d->H_kv; p.L_q = d->L_q; p.L_k = d->L_k;
@@ -162,8 +159,6 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     p.b2 = bias;
   }
   p.neg_q = d->scale < 0.f ? 1 : 0;
-  p.ldvt = (d->L_k + 63) / 64 * 64;
-  { const char* e = getenv("AE_ATTN_PROF"); p.prof = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr; }
   if (mod == ae::MOD_DECAY)
     for (int hh = 0; hh < d->H_q; ++hh) h->decay.log2_gamma[hh] = std::log2(d->gamma[hh]);
 
@@ -203,37 +198,6 @@ ae_status_t ae_attn_forward(const ae_attn_t* h, const void* Q, const void* K, co
   return AE_OK;
 }
 
-size_t ae_attn_workspace_size(const ae_attn_t* h) {
-  if (!h || !h->kernel_vt) return 0;
-  return (size_t)h->params.B * h->params.H_kv * h->desc.D_v * h->params.ldvt * sizeof(__bf16);
-}
-
-ae_status_t ae_attn_forward_ws(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O,
-                               void* workspace, size_t workspace_bytes, void* stream) {
-  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_ws: null handle");
-  if (!Q || !K || !V || !O || !workspace) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_ws: null device pointer");
-  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O | (uintptr_t)workspace) & 15)
-    return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_ws: device pointers must be 16-byte aligned");
-  if (O == Q || O == K || O == V || workspace == O || workspace == Q || workspace == K || workspace == V)
-    return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_ws: O / workspace alias another buffer");
-  if (!h->kernel_vt) return fail(AE_ERR_UNSUPPORTED, "ae_attn_forward_ws: no workspace kernel for this descriptor");
-  if (workspace_bytes < ae_attn_workspace_size(h))
-    return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_ws: workspace of %zu bytes is smaller than the %zu required",
-                workspace_bytes, ae_attn_workspace_size(h));
-  ae::Params p = h->params;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = ae::launch_transpose_v(static_cast<const __bf16*>(V), static_cast<__bf16*>(workspace), p.B, p.H_kv, p.L_k,
-                                        h->desc.D_v, p.ldvt, p.vs, s);
-  if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_forward_ws: transpose launch failed: %s", hipGetErrorString(e));
-  p.Q = static_cast<const __bf16*>(Q);
-  p.K = static_cast<const __bf16*>(K);
-  p.V = static_cast<const __bf16*>(workspace);
-  p.O = static_cast<float*>(O);
-  e = h->kernel_vt->launch(p, h->decay, h->grid, s);
-  if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_forward_ws: launch failed: %s", hipGetErrorString(e));
-  return AE_OK;
-}
-
 ae_status_t ae_attn_destroy(ae_attn_t* h) {
   delete h;
   return AE_OK;
@@ -251,8 +215,6 @@ ae_status_t ae_attn_query(const ae_attn_t* h, int32_t* block_m, int32_t* block_n
 }
 
 const char* ae_attn_kernel_name(const ae_attn_t* h) { return h ? h->kernel->name : ""; }
-
-const char* ae_attn_kernel_name_ws(const ae_attn_t* h) { return h && h->kernel_vt ? h->kernel_vt->name : ""; }
 
 const char* ae_attn_last_error(void) { return g_err; }
 

@@ -18,20 +18,12 @@
 // in which keys are contracted is free, so V is read from LDS in the key order
 // that the accumulator layout dictates (ds_read_b64_tr_b16 does the transpose).
 //
-// Instruction stream.  On this hardware a wave that issues MFMAs back to back
-// keeps the SIMD's issue stage to itself: the vector work of the other wave on
-// the SIMD does not slip in between, and matrix and vector phases of the two
-// waves simply add up.  What does overlap is vector work placed BETWEEN the
-// MFMAs of the same wave.  The key loop is therefore software-pipelined over
-// sub-tiles (PIPE) so that every MFMA has vector work of a different sub-tile
-// next to it:
-//   phase A(u):  S(u+1) = K(u+1) Q^T  (MFMA)  ||  first half of the weights P(u)
-//   phase B(u):  O += V(u)^T P(u)     (MFMA)  ||  second half of P(u), then
-//                                                  mask / row max of S(u+1)
-// written as explicit groups "one MFMA + the LDS read for a later MFMA + a slice
-// of vector work" fenced from each other.  Without PIPE (head dims whose
-// accumulators leave no room for a second score buffer) the four pieces run one
-// after the other per sub-tile.
+// Key loop.  The tiles every wave of the workgroup sees in full (no causal
+// diagonal, no ragged end) are walked by a branch-free loop in which the two
+// waves of a SIMD alternate between a vector phase and a matrix phase, one
+// always a phase behind the other (see Steady below).  The remaining tiles
+// (diagonal, ragged tail) go through a general loop with wave-uniform branches
+// for "nothing visible" and "needs the mask".
 //
 // K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4:
 // no staging registers, no ds_write): a wave instruction fills 1 KB of LDS
@@ -43,21 +35,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-// Optional phase timing (build with -DAE_PROFILE): per-wave cycle totals between
-// the marked points are written to the buffer passed in Params::prof.
-#ifdef AE_PROFILE
-#define AE_TICK(k)                                      \
-  do {                                                  \
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  \
-    const uint64_t now_ = __builtin_readcyclecounter(); \
-    prof_acc[k] += now_ - prof_last;                    \
-    prof_last = now_;                                   \
-  } while (0)
-#else
-#define AE_TICK(k) \
-  do {             \
-  } while (0)
-#endif
+#include <type_traits>
 
 namespace ae {
 
@@ -77,54 +55,46 @@ constexpr int kMaxDecayHeads = 256;
 struct Params {
   const __bf16* Q;
   const __bf16* K;
-  const __bf16* V;   // [B, H_kv, L_k, D_v], or with VT kernels the transposed copy [B, H_kv, D_v, ldvt]
+  const __bf16* V;
   float* O;
   int B, H_q, H_kv, L_q, L_k;
   int g;           // H_q / H_kv
   int n_qtiles;    // ceil(L_q / BLOCK_M)
   int n_groups;    // B * H_kv
   int interleave;  // (batch, kv head) groups walked together on one XCD
-  int ldvt;        // VT kernels: keys per row of the transposed V copy (L_k rounded up to 64, zero filled)
   int64_t qs[3], ks[3], vs[3], os[3];  // element strides {batch, head, row}
   float c;         // |scale| * log2(e)  (softmax, sigmoid)  or |scale| (others)
   float b2;        // bias * log2(e)     (softmax, sigmoid)  or bias (others)
   int neg_q;       // scale < 0: the sign is moved onto Q (exact for bf16)
-  unsigned long long* prof;  // AE_PROFILE builds: [grid][waves][8] cycle totals, else unused
 };
 
 struct DecayTable {
   float log2_gamma[kMaxDecayHeads];
 };
 
-template <int DQK_, int DV_, int NORM_, int MOD_, bool CAUSAL_, int WAVES_, bool PIPE_, bool VT_>
+template <int DQK_, int DV_, int NORM_, int MOD_, bool CAUSAL_, int WAVES_>
 struct Cfg {
   static constexpr int DQK = DQK_, DV = DV_, NORM = NORM_, MOD = MOD_, WAVES = WAVES_;
-  static constexpr bool CAUSAL = CAUSAL_, PIPE = PIPE_;
-  // VT: V arrives pre-transposed ([D_v][keys], written by transpose_v_kernel), so the
-  // aggregation reads its A fragments with one 128-bit LDS load instead of two
-  // 64-bit transposing loads (LDS instruction issue is the first limit of this
-  // kernel).  The key order inside a 16-key step then has to be the natural one,
-  // which is arranged by permuting which K row each lane scores (k_frag_offsets).
-  static constexpr bool VT = VT_;
+  static constexpr bool CAUSAL = CAUSAL_;
   static constexpr int SUB_N = 32;    // keys per compute sub-tile
   static constexpr int BLOCK_N = 64;  // keys per LDS tile (two sub-tiles)
   static constexpr int BLOCK_M = 32 * WAVES;
   static constexpr int THREADS = 64 * WAVES;
   // LDS tiles are row-major and unpadded; CPR = 16-byte chunks per row.
   static constexpr int RB_K = DQK * 2, RB_V = DV * 2;
-  static constexpr int CPR_K = DQK / 8, CPR_V = VT ? 8 : DV / 8;  // VT: rows are 64 keys = 128 bytes
+  static constexpr int CPR_K = DQK / 8, CPR_V = DV / 8;
   static constexpr int K_BYTES = BLOCK_N * RB_K;
-  static constexpr int V_BYTES = BLOCK_N * RB_V;  // same size either way round
-  // Scoring runs one sub-tile ahead of aggregation, so while tile j is being
-  // aggregated K(j) and K(j+1) are both read and K(j+2) is arriving; V(j) is
-  // read while V(j+1) arrives.
-  static constexpr int K_STAGES = 3, V_STAGES = 2;
-  static constexpr int LDS_BYTES = K_STAGES * K_BYTES + V_STAGES * V_BYTES;
+  static constexpr int V_BYTES = BLOCK_N * RB_V;
+  // While tile j is being worked on, tiles j and j+1 are readable (scoring and
+  // the fragment ring run ahead of aggregation) and tile j+2 is arriving.
+  static constexpr int STAGES = 3;
+  static constexpr int LDS_BYTES = STAGES * (K_BYTES + V_BYTES);
   static constexpr int NB_K = K_BYTES / 1024, NB_V = V_BYTES / 1024;  // 1 KB blocks per tile
   static constexpr int KI = (NB_K + WAVES - 1) / WAVES, VI = (NB_V + WAVES - 1) / WAVES;
   static constexpr int T = DQK / 16;  // contraction steps of the scoring MFMA
   static constexpr int DB = DV / 32;  // 32-wide blocks of output columns
-  static constexpr int VA = VT ? 4 : DB;  // per-lane V fragment base addresses
+  static constexpr int PF = 4;  // LDS fragment reads kept in flight ahead of their MFMA
+  static_assert(WAVES % 2 == 0, "waves pair up per SIMD");
   static_assert(DQK % 16 == 0 && DV % 32 == 0, "head dims must fit the MFMA tile");
   static_assert(K_BYTES % 1024 == 0 && V_BYTES % 1024 == 0, "tiles must be whole 1 KB blocks");
   static_assert(CPR_K == 8 || CPR_K == 16 || CPR_K == 24, "K swizzle is defined for these row sizes");
@@ -132,15 +102,24 @@ struct Cfg {
   static_assert(LDS_BYTES <= 160 * 1024, "tiles do not fit LDS");
 };
 
+// Calls f(std::integral_constant<int, B>) ... f(std::integral_constant<int, E-1>):
+// a loop whose index is a compile-time constant inside the body.
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
-// max(a, b, c) in one instruction.  Written as asm because fmaxf() on values the
-// compiler cannot prove canonical costs an extra v_max per operand in IEEE mode.
-__device__ __forceinline__ float max3(float a, float b, float c) {
-  float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
-}
+// max(a, b, c): one v_max3_f32.  The device code is built with NaNs assumed
+// absent, otherwise every operand the compiler cannot prove canonical costs an
+// extra v_max in IEEE mode.  (Not written as inline asm: the scores come straight
+// out of an MFMA, and the wait states between an MFMA and the first read of its
+// result are only inserted in front of instructions the compiler knows.)
+__device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
 // The other 16 keys of a query row live in lane l^32.  v_permlane32_swap
 // exchanges the upper half of its first operand with the lower half of its
@@ -223,14 +202,15 @@ __device__ __forceinline__ void dma16(const void* base_uniform, uint32_t byte_of
 }
 
 // Starts the copy of tile rows [j0, j0 + ROWS) into the LDS tile at `lds`.
-// Rows past the end of the sequence re-read the last valid row: their scores
-// are masked, and finite values keep 0 * V finite.
-template <int WAVES, int ROWS, int CPR, int N>
+// FULL: the caller knows all rows exist.  Otherwise rows past the end of the
+// sequence re-read the last valid row: their scores are masked, and finite
+// values keep 0 * V finite.
+template <int WAVES, int ROWS, int CPR, bool FULL, int N>
 __device__ __forceinline__ void dma_tile(const __bf16* base, int64_t row_stride, int j0, int L_k, uint32_t lds, int wave,
                                          const uint32_t (&goff)[N], const int (&grow)[N]) {
   constexpr int NB = ROWS * CPR / 64;
   const __bf16* tile = base + (int64_t)j0 * row_stride;  // wave-uniform
-  if (j0 + ROWS <= L_k) {
+  if (FULL || j0 + ROWS <= L_k) {
 #pragma unroll
     for (int i = 0; i < N; ++i) dma16(tile, goff[i], lds + ((wave + i * WAVES) % NB) * 1024);
   } else {
@@ -243,11 +223,23 @@ __device__ __forceinline__ void dma_tile(const __bf16* base, int64_t row_stride,
 }
 
 // Waits until none of this wave's DMA loads is in flight, then meets the other
-// waves: what they waited for is visible too.  A bare s_barrier is enough: LDS
-// reads of the step have returned by then (each was awaited by the MFMA that
-// consumed it), so a buffer is only overwritten after every wave is done
-// reading it.
+// waves: what they waited for is visible too.  A bare s_barrier is enough: the
+// LDS reads of a tile have returned before the barrier that precedes the copy
+// into its buffer (each was awaited by the MFMA that consumed it, and reads
+// still in flight at a barrier belong to tiles that stay resident), so a buffer
+// is only overwritten after every wave is done reading it.
 __device__ __forceinline__ void wait_dma_and_sync() { asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Workgroup barrier between phases of the steady-state loop.
+__device__ __forceinline__ void phase_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// The value is computed before this point and not recomputed after it: an
+// empty volatile asm keeps the optimiser from sinking the arithmetic of a vector
+// phase past the barrier, next to its first use in the following matrix phase.
+template <class V>
+__device__ __forceinline__ void pin(V& v) {
+  asm volatile("" : "+v"(v));
+}
 
 // Nothing may be moved across this point by the instruction scheduler.
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
@@ -264,25 +256,20 @@ struct RowState {
 // j0 + 8*(r/4) + 4*half + (r%4).  Work on them is cut into 8 pairs (registers
 // 2q, 2q+1 -> one packed bf16x2 word); pairs 0..3 form the B operand of the
 // first aggregation step (keys 0..15 of the sub-tile), pairs 4..7 of the second.
-// (VT kernels: register r is key j0 + 16*(r/8) + 8*half + (r%8), see k_frag_offsets.)
-template <bool VT>
-__device__ __forceinline__ constexpr int key_offset(int r) {
-  return VT ? 16 * (r / 8) + (r % 8) : 8 * (r / 4) + (r % 4);
-}
+__device__ __forceinline__ constexpr int key_offset(int r) { return 8 * (r / 4) + (r % 4); }
 
 // Per-sub-tile, per-lane constants of the modification.
 struct TileCtx {
   int jlim;     // register r is visible  <=>  key_offset(r) <= jlim   (masked sub-tiles only)
-  float dbase;  // decay: log2(gamma) * (i + off - j0 - (4 or 8)*half)
+  float dbase;  // decay: log2(gamma) * (i + off - j0 - 4*half)
 };
 
 template <class C, bool MASKED>
 __device__ __forceinline__ TileCtx tile_ctx(const Params& p, int i, int j0, int off, float g2) {
   const int half = (threadIdx.x & 63) >> 5;
   TileCtx c;
-  constexpr int HS = C::VT ? 8 : 4;  // key offset of the upper half wave
-  c.jlim = MASKED ? min(C::CAUSAL ? i + off : p.L_k - 1, p.L_k - 1) - j0 - HS * half : 0;
-  c.dbase = C::MOD == MOD_DECAY ? g2 * (float)(i + off - j0 - HS * half) : 0.f;
+  c.jlim = MASKED ? min(C::CAUSAL ? i + off : p.L_k - 1, p.L_k - 1) - j0 - 4 * half : 0;
+  c.dbase = C::MOD == MOD_DECAY ? g2 * (float)(i + off - j0 - 4 * half) : 0.f;
   return c;
 }
 
@@ -297,7 +284,7 @@ __device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, con
   for (int u = 0; u < 2; ++u) {
     const int r = 2 * q + u;
     float x = s[r];
-    const bool hidden = MASKED && (key_offset<C::VT>(r) > tc.jlim);
+    const bool hidden = MASKED && (key_offset(r) > tc.jlim);
     if constexpr (C::NORM == NORM_SOFTMAX) {
       if (hidden) x = -INFINITY;
     } else if constexpr (C::NORM == NORM_SIGMOID) {
@@ -306,7 +293,7 @@ __device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, con
     } else {
       if constexpr (C::MOD == MOD_DECAY) {
         // gamma^(i + off - j) = 2^(log2(gamma) * (i + off - j))
-        x = x * p.c * fast_exp2(__builtin_fmaf(-g2, (float)key_offset<C::VT>(r), tc.dbase));
+        x = x * p.c * fast_exp2(__builtin_fmaf(-g2, (float)key_offset(r), tc.dbase));
       } else {
         x = __builtin_fmaf(x, p.c, p.b2);
         if constexpr (C::MOD == MOD_RELU) x = fmaxf(x, 0.f);
@@ -390,12 +377,7 @@ __device__ __forceinline__ void finish_done(RowState<C>& st, float acc) {
 template <class C>
 __device__ __forceinline__ void k_frag_offsets(uint32_t base, uint32_t (&kaddr)[C::T]) {
   const int lane = threadIdx.x & 63;
-  const int half = lane >> 5;
-  int ql = lane & 31;
-  // VT: MFMA row m scores key (m with bits 2 and 3 swapped), so that a lane's
-  // accumulator registers 8t..8t+7 are keys 16t + 8*half + 0..7 in order -- the
-  // order of a 16-byte piece of a transposed V row.
-  if (C::VT) ql = (ql & ~12) | ((ql & 4) << 1) | ((ql & 8) >> 1);
+  const int half = lane >> 5, ql = lane & 31;
 #pragma unroll
   for (int t = 0; t < C::T; ++t) kaddr[t] = base + ql * C::RB_K + (((2 * t + half) ^ kswz<C::CPR_K>(ql)) * 16);
 }
@@ -408,23 +390,14 @@ __device__ __forceinline__ void k_frag_offsets(uint32_t base, uint32_t (&kaddr)[
 // 4*half + (i/4) -- swizzle included (it only depends on the row modulo 4, a
 // per-lane constant).
 template <class C>
-__device__ __forceinline__ void v_frag_offsets(uint32_t base, uint32_t (&vaddr)[C::VA]) {
+__device__ __forceinline__ void v_frag_offsets(uint32_t base, uint32_t (&vaddr)[C::DB]) {
   const int lane = threadIdx.x & 63;
   const int half = lane >> 5, li = lane & 15;
-  if constexpr (C::VT) {
-    // Transposed tile: row d (128 bytes = 64 keys), chunk 2*ts + half holds keys
-    // 16*ts + 8*half .. +7 (ts = 16-key step inside the tile, 0..3).  Chunks are
-    // swizzled like K rows of 128 bytes; output-column block db is at +32 rows.
-    const int d = lane & 31;
+  const int row = 4 * half + (li >> 2);
+  const int cl = 2 * ((lane >> 4) & 1) + ((li & 3) >> 1);  // chunk within the 64-byte group
 #pragma unroll
-    for (int ts = 0; ts < 4; ++ts) vaddr[ts] = base + d * 128 + (((2 * ts + half) ^ kswz<8>(d)) * 16);
-  } else {
-    const int row = 4 * half + (li >> 2);
-    const int cl = 2 * ((lane >> 4) & 1) + ((li & 3) >> 1);  // chunk within the 64-byte group
-#pragma unroll
-    for (int db = 0; db < C::DB; ++db)
-      vaddr[db] = base + row * C::RB_V + ((4 * (db ^ vswz<C::CPR_V>(row)) + cl) * 16) + (li & 1) * 8;
-  }
+  for (int db = 0; db < C::DB; ++db)
+    vaddr[db] = base + row * C::RB_V + ((4 * (db ^ vswz<C::CPR_V>(row)) + cl) * 16) + (li & 1) * 8;
 }
 
 typedef __attribute__((address_space(3))) char lds_char;
@@ -442,98 +415,187 @@ __device__ __forceinline__ bf16x8 read_v_frag(uint32_t addr, int row8_bytes) {
 // A operand of the aggregation MFMA for sub-tile `sub` (0/1) of the V tile,
 // 16-key step t (0/1) and output-column block db.
 template <class C>
-__device__ __forceinline__ bf16x8 load_v_frag(const uint32_t (&vaddr)[C::VA], int sub, int t, int db) {
-  if constexpr (C::VT)
-    return read_k_frag(vaddr[2 * sub + t] + db * 32 * 128);
-  else
-    return read_v_frag(vaddr[db] + (32 * sub + 16 * t) * C::RB_V, 8 * C::RB_V);
+__device__ __forceinline__ bf16x8 load_v_frag(const uint32_t (&vaddr)[C::DB], int sub, int t, int db) {
+  return read_v_frag(vaddr[db] + (32 * sub + 16 * t) * C::RB_V, 8 * C::RB_V);
 }
 
-constexpr int kFragAhead = 4;  // LDS fragment reads kept in flight ahead of their MFMA
 
-// ---- phase A: S_nxt = K_sub Q^T  ||  weight pairs [FIN_LO, FIN_HI) of s_cur ------
-//   DO_QK   score the sub-tile whose first row is at LDS offset `krow_off` of the
-//           buffer kaddr points into
-template <class C, bool DO_QK, int FIN_LO, int FIN_HI>
-__device__ __forceinline__ void phase_a(const Params& p, const uint32_t (&kaddr)[C::T], int krow_off,
-                                        const bf16x8 (&qf)[C::T], f32x16& s_nxt, const f32x16& s_cur, float k0,
-                                        float& acc, u32x4 (&pk)[2]) {
-  constexpr int NM = DO_QK ? C::T : 0, NPAIR = FIN_HI - FIN_LO;
-  // Pairs done before the first MFMA: they cover the latency of the first
-  // fragment reads, which cannot be issued before the tile is published.
-  constexpr int FRONT = !DO_QK ? NPAIR : (NPAIR >= 4 ? 1 : 0);
-  constexpr int PF = kFragAhead < NM ? kFragAhead : NM;
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.f;
+  return z;
+}
 
-  bf16x8 ring[PF > 0 ? PF : 1];
+// ================================================================================
+// General sub-step pieces (prologue, diagonal and ragged tiles): each block of
+// MFMAs primes its own fragment ring.
+// ================================================================================
+
+// s = K_sub Q^T for the sub-tile whose first row is at LDS offset krow_off of the
+// buffer kaddr points into.
+template <class C>
+__device__ __forceinline__ void score_block(const uint32_t (&kaddr)[C::T], int krow_off, const bf16x8 (&qf)[C::T],
+                                            f32x16& s) {
+  constexpr int PF = C::PF;
+  bf16x8 ring[PF];
 #pragma unroll
   for (int g = 0; g < PF; ++g) ring[g] = read_k_frag(kaddr[g] + krow_off);
-#pragma unroll
-  for (int q = FIN_LO; q < FIN_LO + FRONT; ++q) pk[q / 4][q % 4] = finish_pair<C>(p, q, s_cur, k0, acc);
   sched_fence();
-
+  s = zero16();
 #pragma unroll
-  for (int g = 0; g < NM; ++g) {
-    if (g == 0) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
-    }
-    s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[g % PF], qf[g], s_nxt, 0, 0, 0);
-    if (g + PF < NM) ring[g % PF] = read_k_frag(kaddr[g + PF] + krow_off);  // refill the slot just consumed
-#pragma unroll
-    for (int q = FIN_LO + FRONT; q < FIN_HI; ++q)
-      if ((q - FIN_LO - FRONT) * NM / (NPAIR - FRONT) == g) pk[q / 4][q % 4] = finish_pair<C>(p, q, s_cur, k0, acc);
+  for (int g = 0; g < C::T; ++g) {
+    s = mfma(ring[g % PF], qf[g], s);
+    if (g + PF < C::T) ring[g % PF] = read_k_frag(kaddr[g + PF] + krow_off);
     sched_fence();
   }
 }
 
-// ---- phase B: O^T += V_sub^T P^T  ||  weight pairs [FIN_LO, 8) of s_cur, then the
-//      modification / row max of s_nxt ---------------------------------------------
-//   DO_PV    aggregate sub-tile `vsub` (0/1) of the V tile vaddr points into
-//   DO_POST  mask / modify / reduce the freshly scored s_nxt (sub-tile starting at j0)
-// The aggregation MFMAs run key-step major: the first DB of them need weight
-// pairs 0..3 only, so pairs 4..7 may still be computed next to those.
-template <class C, bool DO_PV, int FIN_LO, bool DO_POST, bool MASKED>
-__device__ __forceinline__ void phase_b(const Params& p, const uint32_t (&vaddr)[C::VA], int vsub, u32x4 (&pk)[2],
-                                        RowState<C>& st, const f32x16& s_cur, float k0, float& acc, f32x16& s_nxt,
-                                        int i, int j0, int off, float g2, bool& moved, float& xm) {
-  constexpr int DB = C::DB, NM = DO_PV ? 2 * DB : 0;
-  constexpr int NFIN = DO_PV ? 8 - FIN_LO : 0, NPOST = DO_POST ? 8 : 0;
-  static_assert(FIN_LO >= 4 || !DO_PV, "pairs 0..3 must be complete before aggregation starts");
-  constexpr int PF = kFragAhead < NM ? kFragAhead : NM;
-  // MFMAs [0, DB) carry the remaining weight pairs, MFMAs [DB, 2*DB) the post work;
-  // with nothing to aggregate the post work simply runs.
-  constexpr int POST_FRONT = !DO_PV ? NPOST : 0;
-
-  bf16x8 ring[PF > 0 ? PF : 1];
+// O^T += V_sub^T P^T for sub-tile vsub of the V buffer vaddr points into.
+template <class C>
+__device__ __forceinline__ void aggregate_block(const uint32_t (&vaddr)[C::DB], int vsub, const u32x4 (&pk)[2],
+                                                RowState<C>& st) {
+  constexpr int PF = C::PF, DB = C::DB, NM = 2 * DB;
+  bf16x8 ring[PF];
 #pragma unroll
   for (int g = 0; g < PF; ++g) ring[g] = load_v_frag<C>(vaddr, vsub, g / DB, g % DB);
-
-  TileCtx tc;
-  if constexpr (DO_POST) tc = tile_ctx<C, MASKED>(p, i, j0, off, g2);
-  float mx = -INFINITY;
-#pragma unroll
-  for (int q = 0; q < POST_FRONT; ++q) post_pair<C, MASKED>(p, q, s_nxt, tc, g2, mx);
   sched_fence();
-
 #pragma unroll
   for (int g = 0; g < NM; ++g) {
     const int t = g / DB, db = g % DB;
-    st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[g % PF], __builtin_bit_cast(bf16x8, pk[t]), st.o[db], 0, 0, 0);
-    if (g + PF < NM)  // refill the slot just consumed
-      ring[g % PF] = load_v_frag<C>(vaddr, vsub, (g + PF) / DB, (g + PF) % DB);
-    if (g < DB) {
-#pragma unroll
-      for (int q = FIN_LO; q < 8; ++q)
-        if ((q - FIN_LO) * DB / (NFIN > 0 ? NFIN : 1) == g) pk[q / 4][q % 4] = finish_pair<C>(p, q, s_cur, k0, acc);
-    } else {
-#pragma unroll
-      for (int q = 0; q < NPOST; ++q)
-        if (q * DB / 8 == g - DB) post_pair<C, MASKED>(p, q, s_nxt, tc, g2, mx);
-    }
+    st.o[db] = mfma(ring[g % PF], __builtin_bit_cast(bf16x8, pk[t]), st.o[db]);
+    if (g + PF < NM) ring[g % PF] = load_v_frag<C>(vaddr, vsub, (g + PF) / DB, (g + PF) % DB);
     sched_fence();
   }
-  if constexpr (DO_POST) post_done<C>(p, st, mx, moved, xm);
 }
+
+// Modified scores of a sub-tile -> packed weights, row sum folded into the state.
+template <class C>
+__device__ __forceinline__ void weights_all(const Params& p, const f32x16& s, RowState<C>& st, u32x4 (&pk)[2]) {
+  const float k0 = finish_k0<C>(p, st);
+  float acc = 0.f;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) pk[q / 4][q % 4] = finish_pair<C>(p, q, s, k0, acc);
+  finish_done<C>(st, acc);
+}
+
+// Modification (+ mask) and row max of the freshly scored sub-tile starting at key j0.
+template <class C, bool MASKED>
+__device__ __forceinline__ void modify_all(const Params& p, f32x16& s, RowState<C>& st, int i, int j0, int off, float g2) {
+  const TileCtx tc = tile_ctx<C, MASKED>(p, i, j0, off, g2);
+  float mx = -INFINITY, xm = 0.f;
+  bool moved = false;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) post_pair<C, MASKED>(p, q, s, tc, g2, mx);
+  post_done<C>(p, st, mx, moved, xm);
+  lazy_rescale<C>(st, moved, xm);
+}
+
+// ================================================================================
+// Steady-state iteration: one 64-key tile = two sub-steps, branch free.
+// ================================================================================
+//
+// A sub-step is a vector phase (modification and row max of the scores at hand,
+// weights, row sum) followed by a matrix phase (aggregation of that sub-tile,
+// scoring of the next one), each closed by a workgroup barrier.  The upper half
+// of the waves -- the second wave of every SIMD -- runs exactly one phase behind
+// the lower half (it passes one extra barrier on entry, the lower half one on
+// exit).  So at any time each SIMD has one wave in its vector phase and one in
+// its matrix phase: vector instructions and MFMAs of two waves that run the same
+// phase at the same time would simply queue behind each other.
+//
+// The MFMAs of an iteration are numbered 0 .. N-1 in issue order; numbers >= N
+// wrap into the next iteration.  Their A operands pass through one small ring of
+// registers that is kept full across phases and iterations: the LDS read for
+// MFMA n + PF is issued right behind MFMA n, so no matrix phase starts by
+// waiting for LDS.
+template <class C>
+struct Sched {
+  static constexpr int T = C::T, DB = C::DB, NPV = 2 * C::DB, NS = NPV + T, N = 2 * NS, PF = C::PF;
+  static_assert(T >= PF && NPV >= PF, "the ring must not span more than two blocks of MFMAs");
+  static constexpr bool is_score(int r) { return r >= NPV; }  // position r inside a sub-step: aggregate, then score
+  // first MFMA that reads the NEXT K buffer (sub-step 1 scores rows 0..31 of it)
+  static constexpr int kFirstNextK = NS + NPV;
+};
+
+template <class C>
+struct Steady {
+  using S = Sched<C>;
+  const Params& p;
+  const bf16x8 (&qf)[C::T];
+  RowState<C>& st;
+  u32x4 (&pk)[2];
+  bf16x8 (&ring)[S::PF];
+  uint32_t (&kaddr)[C::T];
+  uint32_t (&vaddr)[C::DB];
+  uint32_t dk, dv;  // byte distance to the next K / V buffer of the ring of LDS stages
+  int i, off;
+  float g2;
+
+  // Issues the LDS read that feeds MFMA n.  Reads are issued in MFMA order, so
+  // the fragment addresses are advanced to the next buffer exactly where the
+  // first read of that buffer is due.
+  template <int n>
+  __device__ __forceinline__ void fetch() {
+    constexpr int m = n % S::N, sub = m / S::NS, r = m % S::NS;
+    if constexpr (n == S::kFirstNextK) {
+#pragma unroll
+      for (int t = 0; t < C::T; ++t) kaddr[t] += dk;
+    }
+    if constexpr (n == S::N) {  // the wrapped reads are V fragments of the next tile
+#pragma unroll
+      for (int db = 0; db < C::DB; ++db) vaddr[db] += dv;
+    }
+    if constexpr (S::is_score(r))
+      ring[n % S::PF] = read_k_frag(kaddr[r - S::NPV] + (sub == 0 ? 32 * C::RB_K : 0));
+    else
+      ring[n % S::PF] = load_v_frag<C>(vaddr, sub, r / C::DB, r % C::DB);
+  }
+
+  // Vector phase of sub-step SUB: the scores in s (sub-tile starting at key j0,
+  // every key visible) become packed weights in pk; the row state follows.
+  template <int SUB>
+  __device__ __forceinline__ void vector_phase(f32x16& s, int j0) {
+    const TileCtx tc = tile_ctx<C, false>(p, i, j0, off, g2);
+    float mx = -INFINITY, xm = 0.f, acc = 0.f;
+    bool moved = false;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) post_pair<C, false>(p, q, s, tc, g2, mx);
+    post_done<C>(p, st, mx, moved, xm);
+    lazy_rescale<C>(st, moved, xm);
+    const float k0 = finish_k0<C>(p, st);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) pk[q / 4][q % 4] = finish_pair<C>(p, q, s, k0, acc);
+    finish_done<C>(st, acc);
+    pin(pk[0]);
+    pin(pk[1]);
+    sched_fence();
+  }
+
+  // Matrix phase of sub-step SUB (0/1): O += V_sub^T P^T with the weights in pk,
+  // then s = scores of the next sub-tile.
+  // `aside` is called once, behind the second MFMA (a slot for a few independent instructions).
+  template <int SUB, class F>
+  __device__ __forceinline__ void matrix_phase(f32x16& s, F&& aside) {
+    static_for<0, S::NS>([&](auto rc) {
+      constexpr int r = decltype(rc)::value, n = SUB * S::NS + r;
+      if constexpr (S::is_score(r)) {
+        constexpr int g = r - S::NPV;
+        if constexpr (g == 0) s = zero16();
+        s = mfma(ring[n % S::PF], qf[g], s);
+      } else {
+        constexpr int t = r / C::DB, db = r % C::DB;
+        st.o[db] = mfma(ring[n % S::PF], __builtin_bit_cast(bf16x8, pk[t]), st.o[db]);
+      }
+      fetch<n + S::PF>();
+      if constexpr (r == 1) aside();
+      sched_fence();
+    });
+  }
+};
 
 template <class C>
 __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, const DecayTable dt) {
@@ -570,7 +632,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
 
   const __bf16* qbase = p.Q + b * p.qs[0] + hq * p.qs[1];
   const __bf16* kbase = p.K + b * p.ks[0] + hkv * p.ks[1];
-  const __bf16* vbase = C::VT ? p.V + ((int64_t)b * p.H_kv + hkv) * C::DV * p.ldvt : p.V + b * p.vs[0] + hkv * p.vs[1];
+  const __bf16* vbase = p.V + b * p.vs[0] + hkv * p.vs[1];
   float* obase = p.O + b * p.os[0] + hq * p.os[1];
 
   // ---- Q fragments (B operand of S^T = K Q^T), resident for the whole kernel -
@@ -586,9 +648,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   st.m = -INFINITY;
   st.l = 0.f;
 #pragma unroll
-  for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
+  for (int db = 0; db < C::DB; ++db) st.o[db] = zero16();
 
   float g2 = 0.f;
   if constexpr (C::MOD == MOD_DECAY) g2 = dt.log2_gamma[hq];
@@ -601,164 +661,158 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   }
   const int n_tiles = (kmax + C::BLOCK_N - 1) / C::BLOCK_N;  // LDS tiles (workgroup)
   const int n_vis = (kmax_w + C::SUB_N - 1) / C::SUB_N;      // visible sub-tiles (wave)
+  // Tiles [0, n_steady) take the branch-free loop.  Iteration jt scores sub-tiles
+  // up to 2*jt + 2, which the workgroup's first query row must see in full, and
+  // starts the copy of tile jt + 2, which must be a whole tile.
+  int n_steady;
+  {
+    const int lim = C::CAUSAL ? min(p.L_k - 1, i_wg + off) : p.L_k - 1;  // last key visible to every row
+    n_steady = lim >= 95 ? (lim - 31) / 64 : 0;
+    n_steady = max(0, min(n_steady, p.L_k / 64 - 2));
+  }
   // wave-uniform: does sub-tile u cross the causal diagonal or the end of the keys?
   auto needs_mask = [&](int u) {
     const int j0 = u * C::SUB_N;
     return (j0 + C::SUB_N > p.L_k) || (C::CAUSAL && (j0 + C::SUB_N - 1 > iw0 + off));
   };
 
-  // LDS: K_STAGES K buffers, then V_STAGES V buffers; tile j lives in buffer j % stages.
+  // LDS: STAGES K buffers, then STAGES V buffers; tile j lives in buffer j % STAGES.
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
-  const uint32_t vlds0 = lds0 + C::K_STAGES * C::K_BYTES;
-  uint32_t kaddr[C::T], vaddr[C::VA];  // fragment addresses inside the K / V buffer in use
+  const uint32_t vlds0 = lds0 + C::STAGES * C::K_BYTES;
+  uint32_t kaddr[C::T], vaddr[C::DB];  // fragment addresses inside the K / V buffer in use
   k_frag_offsets<C>(lds0, kaddr);
   v_frag_offsets<C>(vlds0, vaddr);
   uint32_t kgoff[C::KI], vgoff[C::VI];
   int kgrow[C::KI], vgrow[C::VI];
   dma_offsets<C::WAVES, C::BLOCK_N, C::CPR_K, false>(wave, p.ks[2], kgoff, kgrow);
-  if constexpr (C::VT)  // tile = D_v rows of 64 keys out of rows of ldvt keys; swizzled like K
-    dma_offsets<C::WAVES, C::DV, 8, false>(wave, p.ldvt, vgoff, vgrow);
-  else
-    dma_offsets<C::WAVES, C::BLOCK_N, C::CPR_V, true>(wave, p.vs[2], vgoff, vgrow);
+  dma_offsets<C::WAVES, C::BLOCK_N, C::CPR_V, true>(wave, p.vs[2], vgoff, vgrow);
   // Tile indices past the last tile are clamped: the copy is redundant but keeps
   // every wave's stream of loads identical.
   const int last_tile = max(n_tiles - 1, 0);
-  auto load_k = [&](int jt) {
-    dma_tile<C::WAVES, C::BLOCK_N, C::CPR_K>(kbase, p.ks[2], min(jt, last_tile) * C::BLOCK_N, p.L_k,
-                                             lds0 + (jt % C::K_STAGES) * C::K_BYTES, wave, kgoff, kgrow);
+  auto load_kv = [&](int jt, int buf, auto full) {
+    constexpr bool FULL = decltype(full)::value;
+    const int j0 = (FULL ? jt : min(jt, last_tile)) * C::BLOCK_N;
+    dma_tile<C::WAVES, C::BLOCK_N, C::CPR_K, FULL>(kbase, p.ks[2], j0, p.L_k, lds0 + buf * C::K_BYTES, wave, kgoff, kgrow);
+    dma_tile<C::WAVES, C::BLOCK_N, C::CPR_V, FULL>(vbase, p.vs[2], j0, p.L_k, vlds0 + buf * C::V_BYTES, wave, vgoff, vgrow);
   };
-  auto load_v = [&](int jt) {
-    const uint32_t dst = vlds0 + (jt % C::V_STAGES) * C::V_BYTES;
-    if constexpr (C::VT) {
-      // key columns [64*jt, +64) of every row of the transposed copy (zero filled past L_k)
-      const __bf16* tile = vbase + (int64_t)min(jt, last_tile) * C::BLOCK_N;
-#pragma unroll
-      for (int n = 0; n < C::VI; ++n) dma16(tile, vgoff[n], dst + ((wave + n * C::WAVES) % C::NB_V) * 1024);
-    } else {
-      dma_tile<C::WAVES, C::BLOCK_N, C::CPR_V>(vbase, p.vs[2], min(jt, last_tile) * C::BLOCK_N, p.L_k, dst, wave, vgoff,
-                                               vgrow);
-    }
-  };
+  auto next_buf = [](int bidx) { return bidx + 1 == C::STAGES ? 0 : bidx + 1; };
 
-  f32x16 s_a, s_b;  // scores of the even / odd sub-tile in flight (without PIPE only s_a)
+  f32x16 s_a;       // scores of the sub-tile to aggregate next
   u32x4 pk[2];      // packed weights of the sub-tile being aggregated
-  bool moved = false;
-  float xm = 0.f;
 
-#ifdef AE_PROFILE
-  uint64_t prof_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  uint64_t prof_last = __builtin_readcyclecounter();
-#endif
-
-  // ---- prologue: K(0), K(1), V(0) -> LDS; score and reduce sub-tile 0 ------------
+  // ---- prologue: tiles 0 and 1 -> LDS; score and modify sub-tile 0 ---------------
   if (n_tiles > 0) {
-    load_k(0);
+    load_kv(0, 0, std::false_type{});
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    load_k(1);
-    load_v(0);
+    load_kv(1, 1, std::false_type{});
     if (n_vis > 0) {
-      float acc0 = 0.f;
-      phase_a<C, true, 0, 0>(p, kaddr, 0, qf, s_a, s_a, 0.f, acc0, pk);
-      if (needs_mask(0))
-        phase_b<C, false, 8, true, true>(p, vaddr, 0, pk, st, s_a, 0.f, acc0, s_a, i, 0, off, g2, moved, xm);
-      else
-        phase_b<C, false, 8, true, false>(p, vaddr, 0, pk, st, s_a, 0.f, acc0, s_a, i, 0, off, g2, moved, xm);
-      lazy_rescale<C>(st, moved, xm);
+      score_block<C>(kaddr, 0, qf, s_a);
+      if (n_steady == 0) {  // the steady-state loop modifies the scores it is handed itself
+        if (needs_mask(0))
+          modify_all<C, true>(p, s_a, st, i, 0, off, g2);
+        else
+          modify_all<C, false>(p, s_a, st, i, 0, off, g2);
+      }
     }
     wait_dma_and_sync();
   }
 
-  // One sub-step: sub-tile u (scores in s_cur, already modified / reduced) is
-  // turned into weights and aggregated from V rows [vrow_off, +32) of the
-  // current V buffer (sub-tile vsub of it) while sub-tile u+1 is scored from K rows [krow_off, +32)
-  // of the buffer kaddr points into, into s_nxt.
-  auto sub_step = [&](int u, f32x16& s_cur, f32x16& s_nxt, int krow_off, int vsub) {
+  // On entry to iteration jt LDS holds tiles jt and jt+1; kaddr / vaddr point into
+  // the buffers of tile jt (index buf); s_a holds sub-tile 2*jt, modified.
+  int buf = 0;
+  int jt = 0;
+
+  // ---- steady state ----------------------------------------------------------------
+  // Per iteration and wave: vector(2jt) | matrix<0> | vector(2jt+1) | matrix<1>, a
+  // barrier after each.  The copy of tile jt+2 goes into the buffer of tile jt-1,
+  // which the trailing half of the waves reads until the barrier that ends the
+  // leading half's vector(2jt); it is issued in three slices -- in matrix<0>,
+  // vector(2jt+1) and matrix<1> -- because the CU's vector memory path takes
+  // 64 bytes per clock and an instruction that finds its queue full blocks the
+  // wave that issues it.  Each wave awaits its slices at the end of matrix<0> of
+  // the next iteration, one barrier before the first wave reads the tile.
+  if (n_steady > 0) {
+    bf16x8 ring[C::PF];
+    Steady<C> sd{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, g2};
+    static_for<0, C::PF>([&](auto nc) { sd.template fetch<decltype(nc)::value>(); });
+    const bool trailing = wave >= C::WAVES / 2;  // second wave of its SIMD
+    // slice PART (0..2) of the copy of the whole tile at (ktile, vtile) into LDS stage `stage`
+    constexpr int kSlices = 3;
+    auto copy_slice = [&](auto part, const __bf16* ktile, const __bf16* vtile, int stage) {
+      constexpr int PART = decltype(part)::value;
+      static_for<0, C::KI + C::VI>([&](auto ic) {
+        constexpr int n = decltype(ic)::value;
+        if constexpr (n % kSlices == PART) {
+          if constexpr (n < C::KI)
+            dma16(ktile, kgoff[n], lds0 + stage * C::K_BYTES + ((wave + n * C::WAVES) % C::NB_K) * 1024);
+          else
+            dma16(vtile, vgoff[n - C::KI], vlds0 + stage * C::V_BYTES + ((wave + (n - C::KI) * C::WAVES) % C::NB_V) * 1024);
+        }
+      });
+    };
+    constexpr int kSlice0 = (C::KI + C::VI + kSlices - 1) / kSlices;  // instructions in slice 0
+    if (trailing) phase_barrier();
+    for (; jt < n_steady; ++jt) {
+      const int nb = next_buf(buf), stage = next_buf(nb);
+      sd.dk = (uint32_t)((nb - buf) * C::K_BYTES);
+      sd.dv = (uint32_t)((nb - buf) * C::V_BYTES);
+      const __bf16* ktile = kbase + (int64_t)(jt + 2) * C::BLOCK_N * p.ks[2];  // a whole tile (see n_steady)
+      const __bf16* vtile = vbase + (int64_t)(jt + 2) * C::BLOCK_N * p.vs[2];
+      sd.template vector_phase<0>(s_a, 2 * jt * C::SUB_N);
+      phase_barrier();
+      sd.template matrix_phase<0>(s_a, [&] { copy_slice(std::integral_constant<int, 0>{}, ktile, vtile, stage); });
+      // all but the slice just issued: this wave's share of tile jt+1 has landed
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kSlice0) : "memory");
+      phase_barrier();
+      copy_slice(std::integral_constant<int, 1>{}, ktile, vtile, stage);
+      sd.template vector_phase<1>(s_a, (2 * jt + 1) * C::SUB_N);
+      phase_barrier();
+      sd.template matrix_phase<1>(s_a, [&] { copy_slice(std::integral_constant<int, 2>{}, ktile, vtile, stage); });
+      phase_barrier();
+      buf = nb;
+    }
+    if (!trailing) phase_barrier();  // both halves are at the same point again
+    wait_dma_and_sync();             // every wave's share of tile jt+1 has landed
+    // s_a: scores of sub-tile 2*jt, which every row of the workgroup sees in full
+    modify_all<C, false>(p, s_a, st, i, 2 * jt * C::SUB_N, off, g2);
+  }
+
+  // ---- general loop: diagonal and ragged tiles -----------------------------------------
+  // Sub-step u: sub-tile u is turned into weights and aggregated (sub-tile vsub of
+  // the current V buffer); then sub-tile u+1 is scored from K rows [krow_off, +32)
+  // of the buffer kaddr points into, and modified.
+  auto sub_step = [&](int u, int krow_off, int vsub) {
     if (u >= n_vis) return;
-    const bool more = u + 1 < n_vis;
-    const float k0 = finish_k0<C>(p, st);
-    float acc = 0.f;
-    if constexpr (C::PIPE) {
-      if (more) {
-        AE_TICK(0);
-        phase_a<C, true, 0, 4>(p, kaddr, krow_off, qf, s_nxt, s_cur, k0, acc, pk);
-        AE_TICK(1);
-        if (needs_mask(u + 1))
-          phase_b<C, true, 4, true, true>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_nxt, i, (u + 1) * C::SUB_N, off,
-                                          g2, moved, xm);
-        else
-          phase_b<C, true, 4, true, false>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_nxt, i, (u + 1) * C::SUB_N, off,
-                                           g2, moved, xm);
-        AE_TICK(2);
-        finish_done<C>(st, acc);
-        lazy_rescale<C>(st, moved, xm);
-        AE_TICK(3);
-      } else {
-        // this wave's last visible sub-tile: nothing further to score
-        phase_a<C, false, 0, 4>(p, kaddr, krow_off, qf, s_nxt, s_cur, k0, acc, pk);
-        phase_b<C, true, 4, false, false>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_nxt, i, 0, off, g2, moved, xm);
-        finish_done<C>(st, acc);
-      }
-    } else {
-      // one score buffer: weights and aggregation of sub-tile u, then the scores
-      // of sub-tile u+1 into the same registers
-      AE_TICK(0);
-      phase_a<C, false, 0, 8>(p, kaddr, krow_off, qf, s_cur, s_cur, k0, acc, pk);
-      finish_done<C>(st, acc);
-      AE_TICK(1);
-      phase_b<C, true, 8, false, false>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_cur, i, 0, off, g2, moved, xm);
-      AE_TICK(2);
-      if (more) {
-        phase_a<C, true, 0, 0>(p, kaddr, krow_off, qf, s_cur, s_cur, k0, acc, pk);
-        AE_TICK(3);
-        if (needs_mask(u + 1))
-          phase_b<C, false, 8, true, true>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_cur, i, (u + 1) * C::SUB_N, off,
-                                           g2, moved, xm);
-        else
-          phase_b<C, false, 8, true, false>(p, vaddr, vsub, pk, st, s_cur, k0, acc, s_cur, i, (u + 1) * C::SUB_N, off,
-                                            g2, moved, xm);
-        lazy_rescale<C>(st, moved, xm);
-        AE_TICK(4);
-      }
+    weights_all<C>(p, s_a, st, pk);
+    sched_fence();
+    aggregate_block<C>(vaddr, vsub, pk, st);
+    if (u + 1 < n_vis) {
+      score_block<C>(kaddr, krow_off, qf, s_a);
+      if (needs_mask(u + 1))
+        modify_all<C, true>(p, s_a, st, i, (u + 1) * C::SUB_N, off, g2);
+      else
+        modify_all<C, false>(p, s_a, st, i, (u + 1) * C::SUB_N, off, g2);
     }
   };
-
-  // ---- main loop over LDS tiles -------------------------------------------------
-  // On entry to iteration jt LDS holds K(jt), K(jt+1) and V(jt); kaddr points
-  // into K(jt)'s buffer and vaddr into V(jt)'s; s_a holds sub-tile 2*jt.
-  int kbuf = 0, vbuf = 0;  // buffer index of tile jt
-  for (int jt = 0; jt < n_tiles; ++jt) {
-    // K(jt+2) replaces K(jt-1), V(jt+1) replaces V(jt-1): nobody reads those any more
-    load_k(jt + 2);
-    load_v(jt + 1);
-    AE_TICK(5);
-
-    f32x16& s_odd = C::PIPE ? s_b : s_a;
-    sub_step(2 * jt, s_a, s_odd, 32 * C::RB_K, 0);  // scores rows 32..63 of K(jt)
+  for (; jt < n_tiles; ++jt) {
+    const int nb = next_buf(buf);
+    load_kv(jt + 2, next_buf(nb), std::false_type{});
+    sub_step(2 * jt, 32 * C::RB_K, 0);  // scores rows 32..63 of K(jt)
     {
-      const int nk = (kbuf + 1 == C::K_STAGES) ? 0 : kbuf + 1;
-      const uint32_t dk = (uint32_t)((nk - kbuf) * C::K_BYTES);
+      const uint32_t dk = (uint32_t)((nb - buf) * C::K_BYTES);
 #pragma unroll
       for (int t = 0; t < C::T; ++t) kaddr[t] += dk;
-      kbuf = nk;
     }
-    sub_step(2 * jt + 1, s_odd, s_a, 0, 1);  // scores rows 0..31 of K(jt+1)
+    sub_step(2 * jt + 1, 0, 1);  // scores rows 0..31 of K(jt+1)
     {
-      const int nv = (vbuf + 1 == C::V_STAGES) ? 0 : vbuf + 1;
-      const uint32_t dv = (uint32_t)((nv - vbuf) * C::V_BYTES);
+      const uint32_t dv = (uint32_t)((nb - buf) * C::V_BYTES);
 #pragma unroll
-      for (int a = 0; a < C::VA; ++a) vaddr[a] += dv;
-      vbuf = nv;
+      for (int db = 0; db < C::DB; ++db) vaddr[db] += dv;
     }
-    AE_TICK(6);
-    wait_dma_and_sync();  // K(jt+2) and V(jt+1) have landed everywhere
-    AE_TICK(7);
+    buf = nb;
+    wait_dma_and_sync();
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // redundant tail copies must land before LDS is released
-
-#ifdef AE_PROFILE
-  if (p.prof && lane == 0)
-    for (int k = 0; k < 8; ++k) p.prof[((size_t)blockIdx.x * C::WAVES + wave) * 8 + k] = prof_acc[k];
-#endif
 
   // ---- online_epilogue + store ------------------------------------------------
   float inv = 1.f;

@@ -7,7 +7,7 @@ namespace ae {
 typedef hipError_t (*launch_fn)(const Params&, const DecayTable&, int grid, hipStream_t);
 
 struct KernelEntry {
-  int dqk, dv, norm, mod, causal, vt;
+  int dqk, dv, norm, mod, causal;
   int block_m, block_n, threads, lds_bytes;
   launch_fn launch;
   const char* name;
@@ -21,23 +21,18 @@ hipError_t launch_cfg(const Params& p, const DecayTable& dt, int grid, hipStream
 
 template <class C>
 constexpr KernelEntry make_entry(const char* name) {
-  return KernelEntry{C::DQK, C::DV, C::NORM, C::MOD, C::CAUSAL ? 1 : 0, C::VT ? 1 : 0,
+  return KernelEntry{C::DQK, C::DV, C::NORM, C::MOD, C::CAUSAL ? 1 : 0,
                      C::BLOCK_M, C::BLOCK_N, C::THREADS, C::LDS_BYTES, &launch_cfg<C>, name};
 }
 
 // One row of the tile-shape table: for head dims (DQK, DV) and mask CAUSAL the
-// workgroup has WAVES wavefronts of 32 query rows each; PIPE selects the
-// software-pipelined key loop (needs registers for a second score buffer).  Each
-// row yields two kernels: V read as given, and V read from a transposed copy.
-#define AE_ENTRY(...) AE_ENTRY_(__VA_ARGS__)
-#define AE_ENTRY_(DQK, DV, NORM, MOD, CAUSAL, WAVES, PIPE)                                      \
-  make_entry<Cfg<DQK, DV, NORM, MOD, CAUSAL, WAVES, PIPE, false>>(                              \
-      "attn_fwd<" #DQK "," #DV "," #NORM "," #MOD "," #CAUSAL "," #WAVES "," #PIPE ",false>"),  \
-  make_entry<Cfg<DQK, DV, NORM, MOD, CAUSAL, WAVES, PIPE, true>>(                               \
-      "attn_fwd<" #DQK "," #DV "," #NORM "," #MOD "," #CAUSAL "," #WAVES "," #PIPE ",true>")
+// workgroup has WAVES wavefronts of 32 query rows each.
+#define AE_ENTRY(DQK, DV, NORM, MOD, CAUSAL, WAVES)     \
+  make_entry<Cfg<DQK, DV, NORM, MOD, CAUSAL, WAVES>>(   \
+      "attn_fwd<" #DQK "," #DV "," #NORM "," #MOD "," #CAUSAL "," #WAVES ">")
 
 // Every (norm, mod) pair the library supports, for one (DQK, DV) and one tile
-// shape "WAVES, PIPE" per mask value (SHAPE_NC unmasked, SHAPE_C causal).
+// shape (WAVES) per mask value (SHAPE_NC unmasked, SHAPE_C causal).
 #define AE_ENTRIES_FOR_DIMS(DQK, DV, SHAPE_NC, SHAPE_C)            \
   AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_PLAIN, false, SHAPE_NC),    \
   AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_PLAIN, false, SHAPE_NC),    \
@@ -54,10 +49,6 @@ constexpr KernelEntry make_entry(const char* name) {
   AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_DECAY, true, SHAPE_C),       \
   AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_DECAY, true, SHAPE_C),   \
   AE_ENTRY(DQK, DV, NORM_NONE, MOD_DECAY, true, SHAPE_C)
-
-// [B*H_kv] x [L_k, D_v] (strided) -> [B*H_kv] x [D_v, ldvt] contiguous, zero filled past L_k
-hipError_t launch_transpose_v(const __bf16* V, __bf16* Vt, int B, int H_kv, int L_k, int D_v, int ldvt,
-                              const int64_t (&vs)[3], hipStream_t s);
 
 const KernelEntry* table_64_64(int* n);
 const KernelEntry* table_128_128(int* n);

@@ -1,12 +1,12 @@
 // Kernel instantiations and tile shapes for D_qk = 128, D_v = 128.
 #include "dispatch.hpp"
 
-// tile shape: wavefronts per workgroup, software-pipelined key loop
+// tile shape: wavefronts per workgroup
 #ifndef AE_SHAPE_128_128_NC
-#define AE_SHAPE_128_128_NC 8, false
+#define AE_SHAPE_128_128_NC 8
 #endif
 #ifndef AE_SHAPE_128_128_C
-#define AE_SHAPE_128_128_C 8, false
+#define AE_SHAPE_128_128_C 8
 #endif
 
 namespace ae {

@@ -23,15 +23,9 @@ def A():
     return ae_attn
 
 
-# Both entry points are exercised: ae_attn_forward and ae_attn_forward_ws (V read from a
-# transposed copy in a caller workspace).
-ENTRY = [False, True]
-ENTRY_IDS = ["forward", "forward_ws"]
-
-
-def gpu_run(A, w, Q, K, V, ws=False):
+def gpu_run(A, w, Q, K, V):
     dev = torch.device("cuda:0")
-    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), workspace=ws)
+    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev))
     torch.cuda.synchronize()
     return O.cpu().double().numpy()
 
@@ -66,16 +60,15 @@ VARIANTS = {
 }
 
 
-@pytest.mark.parametrize("ws", ENTRY, ids=ENTRY_IDS)
 @pytest.mark.parametrize("dims", DIMS, ids=lambda d: f"d{d[0]}_{d[1]}")
 @pytest.mark.parametrize("variant", sorted(VARIANTS))
-def test_small_ragged_all_variants(A, dims, variant, ws):
+def test_small_ragged_all_variants(A, dims, variant):
     # 2 query tiles with a ragged tail, 6 key tiles with a ragged tail, GQA 2:1
     kw = dict(VARIANTS[variant])
     w = Workload(f"{variant}", 11, 2, 4, 2, 300, 333, dims[0], dims[1], **kw)
     Q, K, V = make_inputs(w)
     print(f"case {variant} dims {dims}", flush=True)
-    got, ref = gpu_run(A, w, Q, K, V, ws), oracle_run(w, Q, K, V)
+    got, ref = gpu_run(A, w, Q, K, V), oracle_run(w, Q, K, V)
     # Variants whose outputs are not O(1) (no normalisation, |sum| normaliser
     # with cancelling denominators, sigmoid without the -ln L bias) are judged
     # relative to the row scale; for normalised variants the factor is 1.
@@ -86,12 +79,11 @@ def test_small_ragged_all_variants(A, dims, variant, ws):
 
 @pytest.mark.parametrize("Lq,Lk", [(1, 1), (1, 77), (77, 1), (64, 64), (257, 255), (40, 700), (700, 40), (513, 513)])
 @pytest.mark.parametrize("mask", ["none", "causal"])
-@pytest.mark.parametrize("ws", ENTRY, ids=ENTRY_IDS)
-def test_shapes_softmax(A, Lq, Lk, mask, ws):
+def test_shapes_softmax(A, Lq, Lk, mask):
     w = Workload("shape", 12, 1, 2, 1, Lq, Lk, 128, 128, mask=mask)
     Q, K, V = make_inputs(w)
-    print(f"case Lq {Lq} Lk {Lk} mask {mask} ws {ws}", flush=True)
-    got, ref = gpu_run(A, w, Q, K, V, ws), oracle_run(w, Q, K, V)
+    print(f"case Lq {Lq} Lk {Lk} mask {mask}", flush=True)
+    got, ref = gpu_run(A, w, Q, K, V), oracle_run(w, Q, K, V)
     check(got, ref, f"softmax Lq={Lq} Lk={Lk} {mask}")
     if mask == "causal" and Lq > Lk:
         assert (got[:, :, : Lq - Lk] == 0).all()   # rows with no visible key
@@ -99,27 +91,25 @@ def test_shapes_softmax(A, Lq, Lk, mask, ws):
 
 @pytest.mark.parametrize("cid", [3, 4])
 @pytest.mark.parametrize("Lq,Lk", [(1, 1), (130, 130), (100, 400), (400, 100)])
-@pytest.mark.parametrize("ws", ENTRY, ids=ENTRY_IDS)
-def test_shapes_sigmoid_retnet(A, cid, Lq, Lk, ws):
+def test_shapes_sigmoid_retnet(A, cid, Lq, Lk):
     w = BY_ID[cid].scaled(B=1, H_q=3, H_kv=3, L_q=Lq, L_k=Lk)
     Q, K, V = make_inputs(w)
     print(f"case config {cid} Lq {Lq} Lk {Lk}", flush=True)
-    check(gpu_run(A, w, Q, K, V, ws), oracle_run(w, Q, K, V), f"c{cid} Lq={Lq} Lk={Lk} ws={ws}")
+    check(gpu_run(A, w, Q, K, V), oracle_run(w, Q, K, V), f"c{cid} Lq={Lq} Lk={Lk}")
 
 
-@pytest.mark.parametrize("ws", ENTRY, ids=ENTRY_IDS)
-def test_c1_full_elementwise(A, ws):
+def test_c1_full_elementwise(A):
     Q, K, V = make_inputs(C1)
-    check(gpu_run(A, C1, Q, K, V, ws), oracle_run(C1, Q, K, V), f"C1 ws={ws}")
+    check(gpu_run(A, C1, Q, K, V), oracle_run(C1, Q, K, V), f"C1")
 
 
-def _sampled_full_config(A, w, ws, n_heads=3, n_rows=96, seed=0):
+def _sampled_full_config(A, w, n_heads=3, n_rows=96, seed=0):
     """Full-size launch (the configuration the benchmark times); the oracle
     recomputes sampled query rows of sampled heads over the whole key range."""
     Q, K, V = make_inputs(w)
     dev = torch.device("cuda:0")
-    print(f"case full {w.name} ws {ws}", flush=True)
-    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), workspace=ws)
+    print(f"case full {w.name}", flush=True)
+    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev))
     torch.cuda.synchronize()
     assert torch.isfinite(O).all()
     rng = np.random.default_rng(seed)
@@ -145,10 +135,9 @@ def _sampled_full_config(A, w, ws, n_heads=3, n_rows=96, seed=0):
     return O
 
 
-@pytest.mark.parametrize("ws", ENTRY, ids=ENTRY_IDS)
 @pytest.mark.parametrize("w", [C2, C3, C4, C5], ids=lambda w: w.name)
-def test_full_config_sampled(A, w, ws):
-    _sampled_full_config(A, w, ws)
+def test_full_config_sampled(A, w):
+    _sampled_full_config(A, w)
 
 
 def test_full_size_properties_c2(A):
@@ -170,24 +159,13 @@ def test_full_size_properties_c2(A):
     assert err.max().item() <= MAX_ABS and err.mean().item() <= MEAN_ABS
 
 
-@pytest.mark.parametrize("ws", ENTRY, ids=ENTRY_IDS)
-def test_determinism_bit_exact(A, ws):
+def test_determinism_bit_exact(A):
     w = C2.scaled(B=1, H_q=8, H_kv=2, L_q=1024, L_k=1024)
     dev = torch.device("cuda:0")
     Q, K, V = (t.to(dev) for t in make_inputs(w))
-    a = A.run_workload(w, Q, K, V, workspace=ws)
-    b = A.run_workload(w, Q, K, V, workspace=ws)
+    a = A.run_workload(w, Q, K, V)
+    b = A.run_workload(w, Q, K, V)
     assert torch.equal(a, b)
-
-
-def test_workspace_entry_rejects_short_workspace(A):
-    w = C1
-    dev = torch.device("cuda:0")
-    Q, K, V = (t.to(dev) for t in make_inputs(w))
-    small = torch.empty(64, dtype=torch.uint8, device=dev)
-    with pytest.raises(A.AeAttnError) as ei:
-        A.run_workload(w, Q, K, V, workspace=small)
-    assert ei.value.status == A.AE_ERR_INVALID_ARG
 
 
 def test_strided_inputs_and_output(A):
@@ -201,11 +179,9 @@ def test_strided_inputs_and_output(A):
 
     out = torch.full((w.B, w.L_q, w.H_q, w.D_v + 4), 7.0, dtype=torch.float32, device=dev)
     ov = out[..., : w.D_v].permute(0, 2, 1, 3)
-    for ws in ENTRY:
-        ov.zero_()
-        A.run_workload(w, blhd(Q), blhd(K), blhd(V), out=ov, workspace=ws)
-        torch.cuda.synchronize()
-        check(ov.cpu().double().numpy(), oracle_run(w, Q, K, V), f"strided ws={ws}")
+    A.run_workload(w, blhd(Q), blhd(K), blhd(V), out=ov)
+    torch.cuda.synchronize()
+    check(ov.cpu().double().numpy(), oracle_run(w, Q, K, V), "strided")
     assert (out[..., w.D_v:] == 7.0).all()   # padding untouched
 
 
