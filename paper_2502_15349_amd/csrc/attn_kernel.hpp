@@ -18,12 +18,13 @@
 // in which keys are contracted is free, so V is read from LDS in the key order
 // that the accumulator layout dictates (ds_read_b64_tr_b16 does the transpose).
 //
-// Key loop.  The tiles every wave of the workgroup sees in full (no causal
-// diagonal, no ragged end) are walked by a branch-free loop in which the two
-// waves of a SIMD alternate between a vector phase and a matrix phase, one
-// always a phase behind the other (see Steady below).  The remaining tiles
-// (diagonal, ragged tail) go through a general loop with wave-uniform branches
-// for "nothing visible" and "needs the mask".
+// Key loop.  Per sub-tile a wave runs a vector phase (modification, row max,
+// weights, row sum) and a matrix phase (aggregation of that sub-tile, scoring of
+// the next one); the two waves of a SIMD alternate, one always a phase behind
+// the other (see KeyLoop below).  A wave whose rows see no further keys (causal
+// diagonal) keeps passing the barriers and skips the work; masking is a small
+// wave-uniform branch around the sub-tiles that cross the diagonal or the end
+// of the keys.
 //
 // K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4:
 // no staging registers, no ds_write): a wave instruction fills 1 KB of LDS
@@ -201,36 +202,15 @@ __device__ __forceinline__ void dma16(const void* base_uniform, uint32_t byte_of
       : "memory", "m0");
 }
 
-// Starts the copy of tile rows [j0, j0 + ROWS) into the LDS tile at `lds`.
-// FULL: the caller knows all rows exist.  Otherwise rows past the end of the
-// sequence re-read the last valid row: their scores are masked, and finite
-// values keep 0 * V finite.
-template <int WAVES, int ROWS, int CPR, bool FULL, int N>
-__device__ __forceinline__ void dma_tile(const __bf16* base, int64_t row_stride, int j0, int L_k, uint32_t lds, int wave,
-                                         const uint32_t (&goff)[N], const int (&grow)[N]) {
-  constexpr int NB = ROWS * CPR / 64;
-  const __bf16* tile = base + (int64_t)j0 * row_stride;  // wave-uniform
-  if (FULL || j0 + ROWS <= L_k) {
-#pragma unroll
-    for (int i = 0; i < N; ++i) dma16(tile, goff[i], lds + ((wave + i * WAVES) % NB) * 1024);
-  } else {
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const uint32_t back = (uint32_t)max(0, j0 + grow[i] - (L_k - 1)) * (uint32_t)row_stride * 2u;
-      dma16(tile, goff[i] - back, lds + ((wave + i * WAVES) % NB) * 1024);
-    }
-  }
-}
-
 // Waits until none of this wave's DMA loads is in flight, then meets the other
-// waves: what they waited for is visible too.  A bare s_barrier is enough: the
-// LDS reads of a tile have returned before the barrier that precedes the copy
-// into its buffer (each was awaited by the MFMA that consumed it, and reads
-// still in flight at a barrier belong to tiles that stay resident), so a buffer
-// is only overwritten after every wave is done reading it.
+// waves: what they waited for is visible too.
 __device__ __forceinline__ void wait_dma_and_sync() { asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// Workgroup barrier between phases of the steady-state loop.
+// Workgroup barrier between phases of the key loop.  A bare s_barrier is enough:
+// the LDS reads of a tile have returned before the barrier that precedes the copy
+// into its buffer (each was awaited by the MFMA that consumed it, and reads still
+// in flight at a barrier belong to tiles that stay resident), so a buffer is only
+// overwritten after every wave is done reading it.
 __device__ __forceinline__ void phase_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // The value is computed before this point and not recomputed after it: an
@@ -258,47 +238,48 @@ struct RowState {
 // first aggregation step (keys 0..15 of the sub-tile), pairs 4..7 of the second.
 __device__ __forceinline__ constexpr int key_offset(int r) { return 8 * (r / 4) + (r % 4); }
 
-// Per-sub-tile, per-lane constants of the modification.
-struct TileCtx {
-  int jlim;     // register r is visible  <=>  key_offset(r) <= jlim   (masked sub-tiles only)
-  float dbase;  // decay: log2(gamma) * (i + off - j0 - 4*half)
-};
-
-template <class C, bool MASKED>
-__device__ __forceinline__ TileCtx tile_ctx(const Params& p, int i, int j0, int off, float g2) {
-  const int half = (threadIdx.x & 63) >> 5;
-  TileCtx c;
-  c.jlim = MASKED ? min(C::CAUSAL ? i + off : p.L_k - 1, p.L_k - 1) - j0 - 4 * half : 0;
-  c.dbase = C::MOD == MOD_DECAY ? g2 * (float)(i + off - j0 - 4 * half) : 0.f;
-  return c;
+// ---- masking ------------------------------------------------------------------------
+// Hidden scores (beyond the causal diagonal or the end of the keys) are replaced
+// before the modification by the value that makes their weight exactly 0 where
+// such a value exists (softmax: -inf; sigmoid: -inf, which the modification turns
+// into 2^+inf), otherwise the modified score is zeroed afterwards.
+template <class C>
+__device__ __forceinline__ void mask_raw(f32x16& s, int jlim) {
+  if constexpr (C::NORM == NORM_SOFTMAX || C::NORM == NORM_SIGMOID) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (key_offset(r) > jlim) s[r] = -INFINITY;
+  }
+}
+template <class C>
+__device__ __forceinline__ void mask_modified(f32x16& s, int jlim) {
+  if constexpr (C::NORM != NORM_SOFTMAX && C::NORM != NORM_SIGMOID) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (key_offset(r) > jlim) s[r] = 0.f;
+  }
 }
 
 // ---- modification + first half of the row norm, one pair of a scored sub-tile --
 // Afterwards the two registers hold, per norm:
-//   softmax  the raw score, -inf where masked (mx accumulates the lane's max)
-//   sigmoid  2^-(scale*s + bias) in log2 units, +inf where masked
-//   others   the fully modified score x, 0 where masked
-template <class C, bool MASKED>
-__device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, const TileCtx& tc, float g2, float& mx) {
+//   softmax  the raw score (mx accumulates the lane's max)
+//   sigmoid  2^-(scale*s + bias) in log2 units
+//   others   the fully modified score x
+template <class C>
+__device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, float dbase, float g2, float& mx) {
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int r = 2 * q + u;
     float x = s[r];
-    const bool hidden = MASKED && (key_offset(r) > tc.jlim);
     if constexpr (C::NORM == NORM_SOFTMAX) {
-      if (hidden) x = -INFINITY;
     } else if constexpr (C::NORM == NORM_SIGMOID) {
       x = fast_exp2(__builtin_fmaf(x, -p.c, -p.b2));
-      if (hidden) x = INFINITY;
+    } else if constexpr (C::MOD == MOD_DECAY) {
+      // gamma^(i + off - j) = 2^(log2(gamma) * (i + off - j))
+      x = x * p.c * fast_exp2(__builtin_fmaf(-g2, (float)key_offset(r), dbase));
     } else {
-      if constexpr (C::MOD == MOD_DECAY) {
-        // gamma^(i + off - j) = 2^(log2(gamma) * (i + off - j))
-        x = x * p.c * fast_exp2(__builtin_fmaf(-g2, (float)key_offset(r), tc.dbase));
-      } else {
-        x = __builtin_fmaf(x, p.c, p.b2);
-        if constexpr (C::MOD == MOD_RELU) x = fmaxf(x, 0.f);
-      }
-      if (hidden) x = 0.f;
+      x = __builtin_fmaf(x, p.c, p.b2);
+      if constexpr (C::MOD == MOD_RELU) x = fmaxf(x, 0.f);
     }
     s[r] = x;
   }
@@ -430,13 +411,8 @@ __device__ __forceinline__ f32x16 zero16() {
   return z;
 }
 
-// ================================================================================
-// General sub-step pieces (prologue, diagonal and ragged tiles): each block of
-// MFMAs primes its own fragment ring.
-// ================================================================================
-
 // s = K_sub Q^T for the sub-tile whose first row is at LDS offset krow_off of the
-// buffer kaddr points into.
+// buffer kaddr points into (prologue: scores of the very first sub-tile).
 template <class C>
 __device__ __forceinline__ void score_block(const uint32_t (&kaddr)[C::T], int krow_off, const bf16x8 (&qf)[C::T],
                                             f32x16& s) {
@@ -454,48 +430,8 @@ __device__ __forceinline__ void score_block(const uint32_t (&kaddr)[C::T], int k
   }
 }
 
-// O^T += V_sub^T P^T for sub-tile vsub of the V buffer vaddr points into.
-template <class C>
-__device__ __forceinline__ void aggregate_block(const uint32_t (&vaddr)[C::DB], int vsub, const u32x4 (&pk)[2],
-                                                RowState<C>& st) {
-  constexpr int PF = C::PF, DB = C::DB, NM = 2 * DB;
-  bf16x8 ring[PF];
-#pragma unroll
-  for (int g = 0; g < PF; ++g) ring[g] = load_v_frag<C>(vaddr, vsub, g / DB, g % DB);
-  sched_fence();
-#pragma unroll
-  for (int g = 0; g < NM; ++g) {
-    const int t = g / DB, db = g % DB;
-    st.o[db] = mfma(ring[g % PF], __builtin_bit_cast(bf16x8, pk[t]), st.o[db]);
-    if (g + PF < NM) ring[g % PF] = load_v_frag<C>(vaddr, vsub, (g + PF) / DB, (g + PF) % DB);
-    sched_fence();
-  }
-}
-
-// Modified scores of a sub-tile -> packed weights, row sum folded into the state.
-template <class C>
-__device__ __forceinline__ void weights_all(const Params& p, const f32x16& s, RowState<C>& st, u32x4 (&pk)[2]) {
-  const float k0 = finish_k0<C>(p, st);
-  float acc = 0.f;
-#pragma unroll
-  for (int q = 0; q < 8; ++q) pk[q / 4][q % 4] = finish_pair<C>(p, q, s, k0, acc);
-  finish_done<C>(st, acc);
-}
-
-// Modification (+ mask) and row max of the freshly scored sub-tile starting at key j0.
-template <class C, bool MASKED>
-__device__ __forceinline__ void modify_all(const Params& p, f32x16& s, RowState<C>& st, int i, int j0, int off, float g2) {
-  const TileCtx tc = tile_ctx<C, MASKED>(p, i, j0, off, g2);
-  float mx = -INFINITY, xm = 0.f;
-  bool moved = false;
-#pragma unroll
-  for (int q = 0; q < 8; ++q) post_pair<C, MASKED>(p, q, s, tc, g2, mx);
-  post_done<C>(p, st, mx, moved, xm);
-  lazy_rescale<C>(st, moved, xm);
-}
-
 // ================================================================================
-// Steady-state iteration: one 64-key tile = two sub-steps, branch free.
+// Key loop body: one 64-key tile = two sub-steps.
 // ================================================================================
 //
 // A sub-step is a vector phase (modification and row max of the scores at hand,
@@ -511,7 +447,8 @@ __device__ __forceinline__ void modify_all(const Params& p, f32x16& s, RowState<
 // wrap into the next iteration.  Their A operands pass through one small ring of
 // registers that is kept full across phases and iterations: the LDS read for
 // MFMA n + PF is issued right behind MFMA n, so no matrix phase starts by
-// waiting for LDS.
+// waiting for LDS.  (A wave only ever skips phases at the end of its key range,
+// so the ring never has to be resynchronised.)
 template <class C>
 struct Sched {
   static constexpr int T = C::T, DB = C::DB, NPV = 2 * C::DB, NS = NPV + T, N = 2 * NS, PF = C::PF;
@@ -522,7 +459,7 @@ struct Sched {
 };
 
 template <class C>
-struct Steady {
+struct KeyLoop {
   using S = Sched<C>;
   const Params& p;
   const bf16x8 (&qf)[C::T];
@@ -532,7 +469,8 @@ struct Steady {
   uint32_t (&kaddr)[C::T];
   uint32_t (&vaddr)[C::DB];
   uint32_t dk, dv;  // byte distance to the next K / V buffer of the ring of LDS stages
-  int i, off;
+  int i, off;       // this lane's query row; L_k - L_q
+  int iw0;          // first query row of the wave
   float g2;
 
   // Issues the LDS read that feeds MFMA n.  Reads are issued in MFMA order, so
@@ -555,15 +493,21 @@ struct Steady {
       ring[n % S::PF] = load_v_frag<C>(vaddr, sub, r / C::DB, r % C::DB);
   }
 
-  // Vector phase of sub-step SUB: the scores in s (sub-tile starting at key j0,
-  // every key visible) become packed weights in pk; the row state follows.
-  template <int SUB>
+  // Vector phase: the raw scores in s (sub-tile u, starting at key j0 = 32u) become
+  // packed weights in pk; the row state follows.
   __device__ __forceinline__ void vector_phase(f32x16& s, int j0) {
-    const TileCtx tc = tile_ctx<C, false>(p, i, j0, off, g2);
+    const int half = (threadIdx.x & 63) >> 5;
+    // wave-uniform: does the sub-tile cross the causal diagonal or the end of the keys?
+    const bool masked = (j0 + C::SUB_N > p.L_k) || (C::CAUSAL && (j0 + C::SUB_N - 1 > iw0 + off));
+    // register r is visible  <=>  key_offset(r) <= jlim
+    const int jlim = min(C::CAUSAL ? i + off : p.L_k - 1, p.L_k - 1) - j0 - 4 * half;
+    const float dbase = C::MOD == MOD_DECAY ? g2 * (float)(i + off - j0 - 4 * half) : 0.f;
     float mx = -INFINITY, xm = 0.f, acc = 0.f;
     bool moved = false;
+    if (masked) mask_raw<C>(s, jlim);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) post_pair<C, false>(p, q, s, tc, g2, mx);
+    for (int q = 0; q < 8; ++q) post_pair<C>(p, q, s, dbase, g2, mx);
+    if (masked) mask_modified<C>(s, jlim);
     post_done<C>(p, st, mx, moved, xm);
     lazy_rescale<C>(st, moved, xm);
     const float k0 = finish_k0<C>(p, st);
@@ -576,24 +520,28 @@ struct Steady {
   }
 
   // Matrix phase of sub-step SUB (0/1): O += V_sub^T P^T with the weights in pk,
-  // then s = scores of the next sub-tile.
-  // `aside` is called once, behind the second MFMA (a slot for a few independent instructions).
+  // then (if `score`) s = raw scores of the next sub-tile.  `aside` is called once,
+  // behind the second MFMA (a slot for a few independent instructions).
   template <int SUB, class F>
-  __device__ __forceinline__ void matrix_phase(f32x16& s, F&& aside) {
-    static_for<0, S::NS>([&](auto rc) {
+  __device__ __forceinline__ void matrix_phase(f32x16& s, bool score, F&& aside) {
+    static_for<0, S::NPV>([&](auto rc) {
       constexpr int r = decltype(rc)::value, n = SUB * S::NS + r;
-      if constexpr (S::is_score(r)) {
-        constexpr int g = r - S::NPV;
-        if constexpr (g == 0) s = zero16();
-        s = mfma(ring[n % S::PF], qf[g], s);
-      } else {
-        constexpr int t = r / C::DB, db = r % C::DB;
-        st.o[db] = mfma(ring[n % S::PF], __builtin_bit_cast(bf16x8, pk[t]), st.o[db]);
-      }
+      constexpr int t = r / C::DB, db = r % C::DB;
+      st.o[db] = mfma(ring[n % S::PF], __builtin_bit_cast(bf16x8, pk[t]), st.o[db]);
       fetch<n + S::PF>();
       if constexpr (r == 1) aside();
       sched_fence();
     });
+    if (score) {
+      static_for<S::NPV, S::NS>([&](auto rc) {
+        constexpr int r = decltype(rc)::value, n = SUB * S::NS + r, g = r - S::NPV;
+        if constexpr (g == 0) s = zero16();
+        s = mfma(ring[n % S::PF], qf[g], s);
+        fetch<n + S::PF>();
+        sched_fence();
+      });
+      pin(s);
+    }
   }
 };
 
@@ -661,21 +609,6 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   }
   const int n_tiles = (kmax + C::BLOCK_N - 1) / C::BLOCK_N;  // LDS tiles (workgroup)
   const int n_vis = (kmax_w + C::SUB_N - 1) / C::SUB_N;      // visible sub-tiles (wave)
-  // Tiles [0, n_steady) take the branch-free loop.  Iteration jt scores sub-tiles
-  // up to 2*jt + 2, which the workgroup's first query row must see in full, and
-  // starts the copy of tile jt + 2, which must be a whole tile.
-  int n_steady;
-  {
-    const int lim = C::CAUSAL ? min(p.L_k - 1, i_wg + off) : p.L_k - 1;  // last key visible to every row
-    n_steady = lim >= 95 ? (lim - 31) / 64 : 0;
-    n_steady = max(0, min(n_steady, p.L_k / 64 - 2));
-  }
-  // wave-uniform: does sub-tile u cross the causal diagonal or the end of the keys?
-  auto needs_mask = [&](int u) {
-    const int j0 = u * C::SUB_N;
-    return (j0 + C::SUB_N > p.L_k) || (C::CAUSAL && (j0 + C::SUB_N - 1 > iw0 + off));
-  };
-
   // LDS: STAGES K buffers, then STAGES V buffers; tile j lives in buffer j % STAGES.
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const uint32_t vlds0 = lds0 + C::STAGES * C::K_BYTES;
@@ -689,40 +622,61 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // Tile indices past the last tile are clamped: the copy is redundant but keeps
   // every wave's stream of loads identical.
   const int last_tile = max(n_tiles - 1, 0);
-  auto load_kv = [&](int jt, int buf, auto full) {
-    constexpr bool FULL = decltype(full)::value;
-    const int j0 = (FULL ? jt : min(jt, last_tile)) * C::BLOCK_N;
-    dma_tile<C::WAVES, C::BLOCK_N, C::CPR_K, FULL>(kbase, p.ks[2], j0, p.L_k, lds0 + buf * C::K_BYTES, wave, kgoff, kgrow);
-    dma_tile<C::WAVES, C::BLOCK_N, C::CPR_V, FULL>(vbase, p.vs[2], j0, p.L_k, vlds0 + buf * C::V_BYTES, wave, vgoff, vgrow);
+  constexpr int kCopies = C::KI + C::VI;  // copy instructions per wave and tile
+  // Copy instructions n of tile jt with n % NSL == PART into LDS stage `stage`
+  // (NSL = 1: the whole tile).
+  auto copy_slice = [&](auto nsl, auto part, int jt, int stage) {
+    constexpr int NSL = decltype(nsl)::value, PART = decltype(part)::value;
+    const int j0 = min(jt, last_tile) * C::BLOCK_N;
+    const __bf16* ktile = kbase + (int64_t)j0 * p.ks[2];  // wave-uniform
+    const __bf16* vtile = vbase + (int64_t)j0 * p.vs[2];
+    const bool whole = j0 + C::BLOCK_N <= p.L_k;
+    static_for<0, kCopies>([&](auto ic) {
+      constexpr int n = decltype(ic)::value;
+      if constexpr (n % NSL == PART) {
+        constexpr bool isk = n < C::KI;
+        constexpr int m = isk ? n : n - C::KI, NB = isk ? C::NB_K : C::NB_V;
+        const uint32_t dst = (isk ? lds0 + stage * C::K_BYTES : vlds0 + stage * C::V_BYTES) + ((wave + m * C::WAVES) % NB) * 1024;
+        const __bf16* tile = isk ? ktile : vtile;
+        uint32_t goff;
+        int row;
+        if constexpr (isk) {
+          goff = kgoff[m];
+          row = kgrow[m];
+        } else {
+          goff = vgoff[m];
+          row = vgrow[m];
+        }
+        if (!whole) {
+          // rows past the end of the sequence re-read the last valid row: their
+          // scores are masked, and finite values keep 0 * V finite
+          const uint32_t pitch = (uint32_t)(isk ? p.ks[2] : p.vs[2]) * 2u;
+          goff -= (uint32_t)max(0, j0 + row - (p.L_k - 1)) * pitch;
+        }
+        dma16(tile, goff, dst);
+      }
+    });
   };
+  using One = std::integral_constant<int, 1>;
+  using Zero = std::integral_constant<int, 0>;
   auto next_buf = [](int bidx) { return bidx + 1 == C::STAGES ? 0 : bidx + 1; };
 
-  f32x16 s_a;       // scores of the sub-tile to aggregate next
-  u32x4 pk[2];      // packed weights of the sub-tile being aggregated
+  f32x16 s_a;   // scores of the sub-tile to aggregate next
+  u32x4 pk[2];  // packed weights of the sub-tile being aggregated
 
-  // ---- prologue: tiles 0 and 1 -> LDS; score and modify sub-tile 0 ---------------
+  // ---- prologue: tiles 0 and 1 -> LDS; raw scores of sub-tile 0 -------------------
   if (n_tiles > 0) {
-    load_kv(0, 0, std::false_type{});
+    copy_slice(One{}, Zero{}, 0, 0);
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    load_kv(1, 1, std::false_type{});
-    if (n_vis > 0) {
-      score_block<C>(kaddr, 0, qf, s_a);
-      if (n_steady == 0) {  // the steady-state loop modifies the scores it is handed itself
-        if (needs_mask(0))
-          modify_all<C, true>(p, s_a, st, i, 0, off, g2);
-        else
-          modify_all<C, false>(p, s_a, st, i, 0, off, g2);
-      }
-    }
+    copy_slice(One{}, Zero{}, 1, 1);
+    if (n_vis > 0) score_block<C>(kaddr, 0, qf, s_a);
     wait_dma_and_sync();
   }
 
-  // On entry to iteration jt LDS holds tiles jt and jt+1; kaddr / vaddr point into
-  // the buffers of tile jt (index buf); s_a holds sub-tile 2*jt, modified.
-  int buf = 0;
-  int jt = 0;
-
-  // ---- steady state ----------------------------------------------------------------
+  // ---- key loop ------------------------------------------------------------------------
+  // On entry to iteration jt LDS holds tile jt, and tile jt+1 is complete or about
+  // to be (see below); kaddr / vaddr point into the buffers of tile jt (stage index
+  // buf); s_a holds the raw scores of sub-tile 2*jt.
   // Per iteration and wave: vector(2jt) | matrix<0> | vector(2jt+1) | matrix<1>, a
   // barrier after each.  The copy of tile jt+2 goes into the buffer of tile jt-1,
   // which the trailing half of the waves reads until the barrier that ends the
@@ -731,86 +685,41 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // 64 bytes per clock and an instruction that finds its queue full blocks the
   // wave that issues it.  Each wave awaits its slices at the end of matrix<0> of
   // the next iteration, one barrier before the first wave reads the tile.
-  if (n_steady > 0) {
+  if (n_tiles > 0) {
     bf16x8 ring[C::PF];
-    Steady<C> sd{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, g2};
-    static_for<0, C::PF>([&](auto nc) { sd.template fetch<decltype(nc)::value>(); });
+    KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2};
+    if (n_vis > 0) static_for<0, C::PF>([&](auto nc) { kl.template fetch<decltype(nc)::value>(); });
     const bool trailing = wave >= C::WAVES / 2;  // second wave of its SIMD
-    // slice PART (0..2) of the copy of the whole tile at (ktile, vtile) into LDS stage `stage`
-    constexpr int kSlices = 3;
-    auto copy_slice = [&](auto part, const __bf16* ktile, const __bf16* vtile, int stage) {
-      constexpr int PART = decltype(part)::value;
-      static_for<0, C::KI + C::VI>([&](auto ic) {
-        constexpr int n = decltype(ic)::value;
-        if constexpr (n % kSlices == PART) {
-          if constexpr (n < C::KI)
-            dma16(ktile, kgoff[n], lds0 + stage * C::K_BYTES + ((wave + n * C::WAVES) % C::NB_K) * 1024);
-          else
-            dma16(vtile, vgoff[n - C::KI], vlds0 + stage * C::V_BYTES + ((wave + (n - C::KI) * C::WAVES) % C::NB_V) * 1024);
-        }
-      });
-    };
-    constexpr int kSlice0 = (C::KI + C::VI + kSlices - 1) / kSlices;  // instructions in slice 0
+    using Two = std::integral_constant<int, 2>;
+    using Three = std::integral_constant<int, 3>;
+    constexpr int kSlice0 = (kCopies + 2) / 3;  // instructions in slice 0
+    int buf = 0;
     if (trailing) phase_barrier();
-    for (; jt < n_steady; ++jt) {
+    for (int jt = 0; jt < n_tiles; ++jt) {
       const int nb = next_buf(buf), stage = next_buf(nb);
-      sd.dk = (uint32_t)((nb - buf) * C::K_BYTES);
-      sd.dv = (uint32_t)((nb - buf) * C::V_BYTES);
-      const __bf16* ktile = kbase + (int64_t)(jt + 2) * C::BLOCK_N * p.ks[2];  // a whole tile (see n_steady)
-      const __bf16* vtile = vbase + (int64_t)(jt + 2) * C::BLOCK_N * p.vs[2];
-      sd.template vector_phase<0>(s_a, 2 * jt * C::SUB_N);
+      kl.dk = (uint32_t)((nb - buf) * C::K_BYTES);
+      kl.dv = (uint32_t)((nb - buf) * C::V_BYTES);
+      const int u = 2 * jt;
+      if (u < n_vis) kl.vector_phase(s_a, u * C::SUB_N);
       phase_barrier();
-      sd.template matrix_phase<0>(s_a, [&] { copy_slice(std::integral_constant<int, 0>{}, ktile, vtile, stage); });
+      if (u < n_vis)
+        kl.template matrix_phase<0>(s_a, u + 1 < n_vis, [&] { copy_slice(Three{}, Zero{}, jt + 2, stage); });
+      else
+        copy_slice(Three{}, Zero{}, jt + 2, stage);
       // all but the slice just issued: this wave's share of tile jt+1 has landed
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kSlice0) : "memory");
       phase_barrier();
-      copy_slice(std::integral_constant<int, 1>{}, ktile, vtile, stage);
-      sd.template vector_phase<1>(s_a, (2 * jt + 1) * C::SUB_N);
+      copy_slice(Three{}, One{}, jt + 2, stage);
+      if (u + 1 < n_vis) kl.vector_phase(s_a, (u + 1) * C::SUB_N);
       phase_barrier();
-      sd.template matrix_phase<1>(s_a, [&] { copy_slice(std::integral_constant<int, 2>{}, ktile, vtile, stage); });
+      if (u + 1 < n_vis)
+        kl.template matrix_phase<1>(s_a, u + 2 < n_vis, [&] { copy_slice(Three{}, Two{}, jt + 2, stage); });
+      else
+        copy_slice(Three{}, Two{}, jt + 2, stage);
       phase_barrier();
       buf = nb;
     }
     if (!trailing) phase_barrier();  // both halves are at the same point again
-    wait_dma_and_sync();             // every wave's share of tile jt+1 has landed
-    // s_a: scores of sub-tile 2*jt, which every row of the workgroup sees in full
-    modify_all<C, false>(p, s_a, st, i, 2 * jt * C::SUB_N, off, g2);
-  }
-
-  // ---- general loop: diagonal and ragged tiles -----------------------------------------
-  // Sub-step u: sub-tile u is turned into weights and aggregated (sub-tile vsub of
-  // the current V buffer); then sub-tile u+1 is scored from K rows [krow_off, +32)
-  // of the buffer kaddr points into, and modified.
-  auto sub_step = [&](int u, int krow_off, int vsub) {
-    if (u >= n_vis) return;
-    weights_all<C>(p, s_a, st, pk);
-    sched_fence();
-    aggregate_block<C>(vaddr, vsub, pk, st);
-    if (u + 1 < n_vis) {
-      score_block<C>(kaddr, krow_off, qf, s_a);
-      if (needs_mask(u + 1))
-        modify_all<C, true>(p, s_a, st, i, (u + 1) * C::SUB_N, off, g2);
-      else
-        modify_all<C, false>(p, s_a, st, i, (u + 1) * C::SUB_N, off, g2);
-    }
-  };
-  for (; jt < n_tiles; ++jt) {
-    const int nb = next_buf(buf);
-    load_kv(jt + 2, next_buf(nb), std::false_type{});
-    sub_step(2 * jt, 32 * C::RB_K, 0);  // scores rows 32..63 of K(jt)
-    {
-      const uint32_t dk = (uint32_t)((nb - buf) * C::K_BYTES);
-#pragma unroll
-      for (int t = 0; t < C::T; ++t) kaddr[t] += dk;
-    }
-    sub_step(2 * jt + 1, 0, 1);  // scores rows 0..31 of K(jt+1)
-    {
-      const uint32_t dv = (uint32_t)((nb - buf) * C::V_BYTES);
-#pragma unroll
-      for (int db = 0; db < C::DB; ++db) vaddr[db] += dv;
-    }
-    buf = nb;
-    wait_dma_and_sync();
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // redundant tail copies must land before LDS is released
 
