@@ -23,9 +23,15 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (see profiles/); filled in per workload once measured, else null.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# each scaled by the same counter's reading for a 1 GiB device copy; the runs and their
+# commands are in profiles/attn_fwd_<workload>.txt.  null where not measured.
+MEASURED_TRAFFIC_BYTES = {
+    "c2_gqa_causal_softmax": int((152.7 + 134.4) * 1e6),
+    "c3_sigmoid_causal": int((303.7 + 134.2) * 1e6),
+    "c4_retnet": int((356.0 + 204.7) * 1e6),
+    "c5_mla_causal_softmax": int((4818.2 + 543.7) * 1e6),
+}
 
 
 def time_gpu(A, torch, w, Q, K, V, steps, warmup, settle_s=0.4):
