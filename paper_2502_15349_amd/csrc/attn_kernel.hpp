@@ -94,6 +94,7 @@ struct Cfg {
   static constexpr int KI = (NB_K + WAVES - 1) / WAVES, VI = (NB_V + WAVES - 1) / WAVES;
   static constexpr int T = DQK / 16;  // contraction steps of the scoring MFMA
   static constexpr int DB = DV / 32;  // 32-wide blocks of output columns
+  static constexpr int VA = DB < 4 ? DB : 4;  // V fragment base addresses kept per lane
   static constexpr int PF = 4;  // LDS fragment reads kept in flight ahead of their MFMA
   static_assert(WAVES % 2 == 0, "waves pair up per SIMD");
   static_assert(DQK % 16 == 0 && DV % 32 == 0, "head dims must fit the MFMA tile");
@@ -166,23 +167,35 @@ __device__ __forceinline__ int vswz(int row) {
 }
 
 // ---- global -> LDS, no registers in between --------------------------------------
-// Byte offsets (from the tile's first row) of the 16-byte chunks this lane
-// fetches for each of the wave's 1 KB blocks, and the tile row they sit in;
-// loop invariant.  A wave with no block left repeats one (same bytes to the
-// same place), so every wave issues the same number of loads per tile.
-template <int WAVES, int ROWS, int CPR, bool IS_V, int N>
-__device__ __forceinline__ void dma_offsets(int wave, int64_t row_stride, uint32_t (&goff)[N], int (&grow)[N]) {
-  constexpr int NB = ROWS * CPR / 64;
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int i = 0; i < N; ++i) {
-    const int p = ((wave + i * WAVES) % NB) * 64 + lane;  // chunk position in the LDS tile
-    const int row = p / CPR, pc = p % CPR;
-    const int c = IS_V ? (pc ^ (4 * vswz<CPR>(row))) : (pc ^ kswz<CPR>(row));
-    grow[i] = row;
-    goff[i] = (uint32_t)(row * (int)row_stride + c * 8) * 2u;
+// A tile of ROWS rows x CPR chunks is copied as NB blocks of 1 KB (64 chunks), one
+// wave instruction each; wave w copies blocks w, w + WAVES, ...  (a wave with no
+// block left repeats one -- same bytes to the same place -- so every wave issues
+// the same number of loads per tile).  Per block a lane needs the byte offset of
+// its chunk from the tile's first row.  Where the blocks of a wave are a whole
+// number of swizzle periods apart, one offset serves them all and the distance
+// is added to the wave-uniform base pointer instead.
+template <int WAVES, int ROWS, int CPR, bool IS_V>
+struct DmaMap {
+  static constexpr int NB = ROWS * CPR / 64, N = (NB + WAVES - 1) / WAVES;
+  static constexpr int kPeriod = IS_V ? 4 : 16;        // rows after which the swizzle repeats
+  static constexpr int kRowStep = WAVES * 64 / CPR;    // rows between two blocks of a wave
+  static constexpr bool kShared = NB % WAVES == 0 && (WAVES * 64) % CPR == 0 && kRowStep % kPeriod == 0;
+  static constexpr int NOFF = kShared ? 1 : N;
+
+  // tile row of this lane's chunk in block i of the wave
+  static __device__ __forceinline__ int row(int wave, int i) {
+    return ((((wave + i * WAVES) % NB) * 64) + (int)(threadIdx.x & 63)) / CPR;
   }
-}
+  static __device__ __forceinline__ void offsets(int wave, int64_t row_stride, uint32_t (&goff)[NOFF]) {
+#pragma unroll
+    for (int i = 0; i < NOFF; ++i) {
+      const int p = ((wave + i * WAVES) % NB) * 64 + (int)(threadIdx.x & 63);  // chunk position in the LDS tile
+      const int r = p / CPR, pc = p % CPR;
+      const int c = IS_V ? (pc ^ (4 * vswz<CPR>(r))) : (pc ^ kswz<CPR>(r));
+      goff[i] = (uint32_t)(r * (int)row_stride + c * 8) * 2u;
+    }
+  }
+};
 
 // One LDS-DMA instruction: 64 lanes x 16 bytes from base + byte_off (per lane)
 // to LDS bytes [lds_addr, lds_addr + 1024).
@@ -369,15 +382,16 @@ __device__ __forceinline__ void k_frag_offsets(uint32_t base, uint32_t (&kaddr)[
 // same for key half 1.  vaddr[db]: this lane's LDS byte address inside the
 // current V buffer for the 32-wide block db of output columns, key rows
 // 4*half + (i/4) -- swizzle included (it only depends on the row modulo 4, a
-// per-lane constant).
+// per-lane constant).  The swizzle permutes blocks within groups of 4, so block
+// db >= 4 is block db - 4 plus 256 bytes and only VA = min(DB, 4) addresses are kept.
 template <class C>
-__device__ __forceinline__ void v_frag_offsets(uint32_t base, uint32_t (&vaddr)[C::DB]) {
+__device__ __forceinline__ void v_frag_offsets(uint32_t base, uint32_t (&vaddr)[C::VA]) {
   const int lane = threadIdx.x & 63;
   const int half = lane >> 5, li = lane & 15;
   const int row = 4 * half + (li >> 2);
   const int cl = 2 * ((lane >> 4) & 1) + ((li & 3) >> 1);  // chunk within the 64-byte group
 #pragma unroll
-  for (int db = 0; db < C::DB; ++db)
+  for (int db = 0; db < C::VA; ++db)
     vaddr[db] = base + row * C::RB_V + ((4 * (db ^ vswz<C::CPR_V>(row)) + cl) * 16) + (li & 1) * 8;
 }
 
@@ -396,8 +410,8 @@ __device__ __forceinline__ bf16x8 read_v_frag(uint32_t addr, int row8_bytes) {
 // A operand of the aggregation MFMA for sub-tile `sub` (0/1) of the V tile,
 // 16-key step t (0/1) and output-column block db.
 template <class C>
-__device__ __forceinline__ bf16x8 load_v_frag(const uint32_t (&vaddr)[C::DB], int sub, int t, int db) {
-  return read_v_frag(vaddr[db] + (32 * sub + 16 * t) * C::RB_V, 8 * C::RB_V);
+__device__ __forceinline__ bf16x8 load_v_frag(const uint32_t (&vaddr)[C::VA], int sub, int t, int db) {
+  return read_v_frag(vaddr[db % C::VA] + (db / C::VA) * 256 + (32 * sub + 16 * t) * C::RB_V, 8 * C::RB_V);
 }
 
 
@@ -467,7 +481,7 @@ struct KeyLoop {
   u32x4 (&pk)[2];
   bf16x8 (&ring)[S::PF];
   uint32_t (&kaddr)[C::T];
-  uint32_t (&vaddr)[C::DB];
+  uint32_t (&vaddr)[C::VA];
   uint32_t dk, dv;  // byte distance to the next K / V buffer of the ring of LDS stages
   int i, off;       // this lane's query row; L_k - L_q
   int iw0;          // first query row of the wave
@@ -485,7 +499,7 @@ struct KeyLoop {
     }
     if constexpr (n == S::N) {  // the wrapped reads are V fragments of the next tile
 #pragma unroll
-      for (int db = 0; db < C::DB; ++db) vaddr[db] += dv;
+      for (int db = 0; db < C::VA; ++db) vaddr[db] += dv;
     }
     if constexpr (S::is_score(r))
       ring[n % S::PF] = read_k_frag(kaddr[r - S::NPV] + (sub == 0 ? 32 * C::RB_K : 0));
@@ -612,13 +626,15 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // LDS: STAGES K buffers, then STAGES V buffers; tile j lives in buffer j % STAGES.
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const uint32_t vlds0 = lds0 + C::STAGES * C::K_BYTES;
-  uint32_t kaddr[C::T], vaddr[C::DB];  // fragment addresses inside the K / V buffer in use
+  uint32_t kaddr[C::T], vaddr[C::VA];  // fragment addresses inside the K / V buffer in use
   k_frag_offsets<C>(lds0, kaddr);
   v_frag_offsets<C>(vlds0, vaddr);
-  uint32_t kgoff[C::KI], vgoff[C::VI];
-  int kgrow[C::KI], vgrow[C::VI];
-  dma_offsets<C::WAVES, C::BLOCK_N, C::CPR_K, false>(wave, p.ks[2], kgoff, kgrow);
-  dma_offsets<C::WAVES, C::BLOCK_N, C::CPR_V, true>(wave, p.vs[2], vgoff, vgrow);
+  using KMap = DmaMap<C::WAVES, C::BLOCK_N, C::CPR_K, false>;
+  using VMap = DmaMap<C::WAVES, C::BLOCK_N, C::CPR_V, true>;
+  static_assert(KMap::N == C::KI && VMap::N == C::VI, "copy instruction counts");
+  uint32_t kgoff[KMap::NOFF], vgoff[VMap::NOFF];
+  KMap::offsets(wave, p.ks[2], kgoff);
+  VMap::offsets(wave, p.vs[2], vgoff);
   // Tile indices past the last tile are clamped: the copy is redundant but keeps
   // every wave's stream of loads identical.
   const int last_tile = max(n_tiles - 1, 0);
@@ -637,21 +653,21 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
         constexpr bool isk = n < C::KI;
         constexpr int m = isk ? n : n - C::KI, NB = isk ? C::NB_K : C::NB_V;
         const uint32_t dst = (isk ? lds0 + stage * C::K_BYTES : vlds0 + stage * C::V_BYTES) + ((wave + m * C::WAVES) % NB) * 1024;
+        using Map = std::conditional_t<isk, KMap, VMap>;
+        const int64_t pitch = isk ? p.ks[2] : p.vs[2];  // elements per row
         const __bf16* tile = isk ? ktile : vtile;
         uint32_t goff;
-        int row;
-        if constexpr (isk) {
-          goff = kgoff[m];
-          row = kgrow[m];
+        if constexpr (isk) goff = kgoff[Map::kShared ? 0 : m];
+        else goff = vgoff[Map::kShared ? 0 : m];
+        if (whole) {
+          if constexpr (Map::kShared) tile += (int64_t)(m * Map::kRowStep) * pitch;  // wave-uniform
         } else {
-          goff = vgoff[m];
-          row = vgrow[m];
-        }
-        if (!whole) {
-          // rows past the end of the sequence re-read the last valid row: their
-          // scores are masked, and finite values keep 0 * V finite
-          const uint32_t pitch = (uint32_t)(isk ? p.ks[2] : p.vs[2]) * 2u;
-          goff -= (uint32_t)max(0, j0 + row - (p.L_k - 1)) * pitch;
+          // Rows past the end of the sequence re-read the last valid row: their
+          // scores are masked, and finite values keep 0 * V finite.  The lane
+          // offset is an unsigned 32-bit quantity added to the base pointer: the
+          // base stays at the tile's first row so that stepping back never wraps.
+          if constexpr (Map::kShared) goff += (uint32_t)(m * Map::kRowStep) * (uint32_t)pitch * 2u;
+          goff -= (uint32_t)max(0, j0 + Map::row(wave, m) - (p.L_k - 1)) * (uint32_t)pitch * 2u;
         }
         dma16(tile, goff, dst);
       }
