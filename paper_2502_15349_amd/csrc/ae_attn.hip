@@ -159,6 +159,8 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     p.b2 = bias;
   }
   p.neg_q = d->scale < 0.f ? 1 : 0;
+  p.fold = (d->norm == AE_NORM_SIGMOID && std::fabs(p.b2) <= 64.f) ? 1 : 0;
+  p.kfac = p.fold ? std::exp2(-p.b2) : 1.f;
   if (mod == ae::MOD_DECAY)
     for (int hh = 0; hh < d->H_q; ++hh) h->decay.log2_gamma[hh] = std::log2(d->gamma[hh]);
 

@@ -67,6 +67,11 @@ struct Params {
   float c;         // |scale| * log2(e)  (softmax, sigmoid)  or |scale| (others)
   float b2;        // bias * log2(e)     (softmax, sigmoid)  or bias (others)
   int neg_q;       // scale < 0: the sign is moved onto Q (exact for bf16)
+  // sigmoid with a bias small enough for 2^(-b2) to be a normal number: Q is
+  // multiplied by -scale*log2(e) when loaded (rounded to bf16 again), so that the
+  // MFMA delivers the exponent itself and 1 + 2^(-b2) * 2^x is a single FMA
+  int fold;
+  float kfac;      // 2^(-b2) when fold
 };
 
 struct DecayTable {
@@ -254,14 +259,14 @@ __device__ __forceinline__ constexpr int key_offset(int r) { return 8 * (r / 4) 
 // ---- masking ------------------------------------------------------------------------
 // Hidden scores (beyond the causal diagonal or the end of the keys) are replaced
 // before the modification by the value that makes their weight exactly 0 where
-// such a value exists (softmax: -inf; sigmoid: -inf, which the modification turns
-// into 2^+inf), otherwise the modified score is zeroed afterwards.
+// such a value exists (softmax: -inf; sigmoid: the infinity that the modification
+// turns into 2^+inf), otherwise the modified score is zeroed afterwards.
 template <class C>
-__device__ __forceinline__ void mask_raw(f32x16& s, int jlim) {
+__device__ __forceinline__ void mask_raw(f32x16& s, int jlim, float hidden) {
   if constexpr (C::NORM == NORM_SOFTMAX || C::NORM == NORM_SIGMOID) {
 #pragma unroll
     for (int r = 0; r < 16; ++r)
-      if (key_offset(r) > jlim) s[r] = -INFINITY;
+      if (key_offset(r) > jlim) s[r] = hidden;
   }
 }
 template <class C>
@@ -278,7 +283,7 @@ __device__ __forceinline__ void mask_modified(f32x16& s, int jlim) {
 //   softmax  the raw score (mx accumulates the lane's max)
 //   sigmoid  2^-(scale*s + bias) in log2 units
 //   others   the fully modified score x
-template <class C>
+template <class C, bool FOLD = false>
 __device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, float dbase, float g2, float& mx) {
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
@@ -286,7 +291,7 @@ __device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, flo
     float x = s[r];
     if constexpr (C::NORM == NORM_SOFTMAX) {
     } else if constexpr (C::NORM == NORM_SIGMOID) {
-      x = fast_exp2(__builtin_fmaf(x, -p.c, -p.b2));
+      x = FOLD ? fast_exp2(x) : fast_exp2(__builtin_fmaf(x, -p.c, -p.b2));
     } else if constexpr (C::MOD == MOD_DECAY) {
       // gamma^(i + off - j) = 2^(log2(gamma) * (i + off - j))
       x = x * p.c * fast_exp2(__builtin_fmaf(-g2, (float)key_offset(r), dbase));
@@ -329,15 +334,18 @@ __device__ __forceinline__ void lazy_rescale(RowState<C>& st, bool moved, float 
 }
 
 // ---- second half of the row norm, one pair: weight -> packed bf16x2 ------------
-template <class C>
+template <class C, bool FOLD = false>
 __device__ __forceinline__ uint32_t finish_pair(const Params& p, int q, const f32x16& s, float k0, float& acc) {
   float x0 = s[2 * q], x1 = s[2 * q + 1];
   if constexpr (C::NORM == NORM_SOFTMAX) {
     x0 = fast_exp2(__builtin_fmaf(x0, p.c, k0));
     x1 = fast_exp2(__builtin_fmaf(x1, p.c, k0));
+    // Row sum in fp32 with plain adds: v_dot2c_f32_bf16 on the packed weights would
+    // halve the instruction count but runs on the matrix pipe, in the MFMAs' way.
+    acc += x0 + x1;
   } else if constexpr (C::NORM == NORM_SIGMOID) {
-    x0 = fast_rcp(1.f + x0);
-    x1 = fast_rcp(1.f + x1);
+    x0 = fast_rcp(FOLD ? __builtin_fmaf(p.kfac, x0, 1.f) : 1.f + x0);
+    x1 = fast_rcp(FOLD ? __builtin_fmaf(p.kfac, x1, 1.f) : 1.f + x1);
   } else if constexpr (C::NORM == NORM_ABSSUM) {
     acc += fabsf(x0) + fabsf(x1);
   } else if constexpr (C::NORM == NORM_ABS_OF_SUM) {
@@ -346,11 +354,6 @@ __device__ __forceinline__ uint32_t finish_pair(const Params& p, int q, const f3
   bf16x2 pr;
   pr[0] = (__bf16)x0;
   pr[1] = (__bf16)x1;
-  if constexpr (C::NORM == NORM_SOFTMAX) {
-    // row sum over the rounded weights, two per v_dot2c_f32_bf16
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
-  }
   return __builtin_bit_cast(uint32_t, pr);
 }
 
@@ -518,15 +521,26 @@ struct KeyLoop {
     const float dbase = C::MOD == MOD_DECAY ? g2 * (float)(i + off - j0 - 4 * half) : 0.f;
     float mx = -INFINITY, xm = 0.f, acc = 0.f;
     bool moved = false;
-    if (masked) mask_raw<C>(s, jlim);
+    const bool fold = C::NORM == NORM_SIGMOID && p.fold;  // wave-uniform
+    if (masked) mask_raw<C>(s, jlim, fold ? INFINITY : -INFINITY);
+    if (fold) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) post_pair<C>(p, q, s, dbase, g2, mx);
+      for (int q = 0; q < 8; ++q) post_pair<C, true>(p, q, s, dbase, g2, mx);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) post_pair<C, false>(p, q, s, dbase, g2, mx);
+    }
     if (masked) mask_modified<C>(s, jlim);
     post_done<C>(p, st, mx, moved, xm);
     lazy_rescale<C>(st, moved, xm);
     const float k0 = finish_k0<C>(p, st);
+    if (fold) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) pk[q / 4][q % 4] = finish_pair<C>(p, q, s, k0, acc);
+      for (int q = 0; q < 8; ++q) pk[q / 4][q % 4] = finish_pair<C, true>(p, q, s, k0, acc);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) pk[q / 4][q % 4] = finish_pair<C, false>(p, q, s, k0, acc);
+    }
     finish_done<C>(st, acc);
     pin(pk[0]);
     pin(pk[1]);
@@ -604,7 +618,12 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     u32x4 v = {0u, 0u, 0u, 0u};
     if (i < p.L_q) v = *reinterpret_cast<const u32x4*>(qbase + (int64_t)i * p.qs[2] + tt * 16 + half * 8);
     if (p.neg_q) v ^= (u32x4){0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
-    qf[tt] = __builtin_bit_cast(bf16x8, v);
+    bf16x8 qv = __builtin_bit_cast(bf16x8, v);
+    if (C::NORM == NORM_SIGMOID && p.fold) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qv[e] = (__bf16)((float)qv[e] * -p.c);
+    }
+    qf[tt] = qv;
   }
   RowState<C> st;
   st.m = -INFINITY;

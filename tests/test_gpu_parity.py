@@ -49,6 +49,9 @@ VARIANTS = {
     "softmax_bias_causal": dict(score_mod="bias", bias=0.75, mask="causal"),
     "sigmoid_causal": dict(score_mod="bias", norm="sigmoid", mask="causal", bias=-math.log(300.0)),
     "sigmoid": dict(norm="sigmoid"),
+    # |bias| * log2(e) > 64: the kernel keeps scale and bias in the exponent FMA
+    # instead of folding the scale into Q
+    "sigmoid_big_bias_causal": dict(score_mod="bias", norm="sigmoid", mask="causal", bias=-48.0, scale=6.0),
     "retnet_abssum": dict(score_mod="head_decay", norm="abssum", mask="causal", decay=True),
     "retnet_abs_of_sum": dict(score_mod="head_decay", norm="abs_of_sum", mask="causal", decay=True),
     "decay_nonorm": dict(score_mod="head_decay", norm="none", mask="causal", decay=True, scale=0.01),
