@@ -112,6 +112,26 @@ def cpu_baseline(w, Q, K, V, budget_s=15.0):
                       f"visible-pair flop as the GPU figure"}
 
 
+def calib_mfma(A, torch, seconds):
+    """Sustained rate of the pure-MFMA calibration kernel (two waves per SIMD on every CU),
+    reported per half second so that the settling of the clock is visible."""
+    wgs, iters = 256, 20000
+    sink = torch.empty(wgs * 512, dtype=torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+    rates, t0 = [], time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        flop = A.ae_calib_mfma_bf16(sink.data_ptr(), sink.numel() * 4, wgs, iters, stream.cuda_stream)
+        b.record(stream)
+        torch.cuda.synchronize()
+        rates.append((time.perf_counter() - t0, flop / (a.elapsed_time(b) * 1e-3) / 1e12))
+    tail = [r for t, r in rates if t > seconds / 2] or [r for _, r in rates]
+    return {"calib": "pure bf16 MFMA, operands in registers, 2 waves per SIMD", "seconds": seconds,
+            "tflops_first": round(rates[0][1], 1), "tflops_sustained": round(float(np.mean(tail)), 1),
+            "nominal_peak": PEAK_BF16_TFLOPS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,6 +143,9 @@ def main():
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device-to-device copy of this many MiB "
                          "(reference reading for the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
+    ap.add_argument("--calib-mfma", type=float, default=0.0, metavar="SECONDS",
+                    help="instead of the benchmark, run the library's pure-MFMA kernel for this long and print "
+                         "the bf16 TFLOP/s the matrix pipes sustain under the board's power limit")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -147,6 +170,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calib_copy_bytes": n, "reads": n, "writes": n}))
         return
+    if a.calib_mfma > 0:
+        print(json.dumps(calib_mfma(A, torch, a.calib_mfma)))
+        return
     w = CONFIGS[a.workload]
     Qc, Kc, Vc = make_inputs(w)
     Q, K, V = Qc.to(dev), Kc.to(dev), Vc.to(dev)
@@ -170,7 +196,8 @@ def main():
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
                      "kernel_ms": round(ker_ms, 5), "flop_per_launch": flop,
-                     "compulsory_bytes": w.compulsory_bytes()},
+                     "compulsory_bytes": w.compulsory_bytes(),
+                     },
         "parity": par,
     }
 
@@ -192,6 +219,13 @@ def main():
             variants[name] = {"tflops": round(tf, 2), "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4),
                               "kernel_ms": round(kms, 5), "parity_max_abs": pv["max_abs"]}
         out["variants"] = variants
+
+    # What the matrix pipes sustain on this board with nothing else in the way: the library's
+    # pure-MFMA kernel, run after the timed work so that it does not disturb it.  Context for frac:
+    # the ceiling the board's power limit leaves of the nominal peak.
+    cal = calib_mfma(A, torch, 2.0)
+    out["roofline"]["mfma_sustained_tflops"] = cal["tflops_sustained"]
+    out["roofline"]["frac_of_sustained"] = round(achieved / cal["tflops_sustained"], 4)
 
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, Qc, Kc, Vc)

@@ -123,6 +123,17 @@ ae_status_t ae_attn_query(const ae_attn_t *h, int32_t *block_m, int32_t *block_n
  * owned by the library, valid for the life of the process.                    */
 const char *ae_attn_kernel_name(const ae_attn_t *h);
 
+/* Measurement aid, not part of the operator: enqueues a kernel that does nothing
+ * but bf16 MFMAs (v_mfma_f32_32x32x16_bf16, operands in registers, values that
+ * toggle like data), `iters` x 16 per wavefront, 8 wavefronts per workgroup, and
+ * stores *flop = the floating-point operations it performs.  Timed by the
+ * caller, it gives the rate the matrix pipes sustain under the board's power
+ * limit -- the practical ceiling next to the nominal peak.  sink: device buffer of
+ * at least workgroups * 512 floats (written, contents meaningless).
+ * Errors: AE_ERR_INVALID_ARG, AE_ERR_HIP.                                      */
+ae_status_t ae_calib_mfma_bf16(void *sink, size_t sink_bytes, int32_t workgroups,
+                               int32_t iters, double *flop, void *stream);
+
 /* Message of the calling thread's most recent failing call ("" if none).     */
 const char *ae_attn_last_error(void);
 

@@ -46,6 +46,8 @@ _lib.ae_attn_query.argtypes = [C.c_void_p] + [C.POINTER(C.c_int32)] * 5
 _lib.ae_attn_query.restype = C.c_int
 _lib.ae_attn_kernel_name.argtypes = [C.c_void_p]
 _lib.ae_attn_kernel_name.restype = C.c_char_p
+_lib.ae_calib_mfma_bf16.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
+_lib.ae_calib_mfma_bf16.restype = C.c_int
 _lib.ae_attn_last_error.argtypes = []
 _lib.ae_attn_last_error.restype = C.c_char_p
 _lib.ae_attn_version.argtypes = []
@@ -96,6 +98,13 @@ def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int
 def ae_attn_forward(handle: int, Q: int, K: int, V: int, O: int, stream: int = 0) -> None:
     """Q, K, V, O are device addresses (tensor.data_ptr()); stream is a raw hipStream_t."""
     _check(_lib.ae_attn_forward(handle, Q, K, V, O, stream))
+
+
+def ae_calib_mfma_bf16(sink: int, sink_bytes: int, workgroups: int, iters: int, stream: int = 0) -> float:
+    """Enqueues the pure-MFMA calibration kernel; returns the flop it performs."""
+    flop = C.c_double(0.0)
+    _check(_lib.ae_calib_mfma_bf16(sink, sink_bytes, workgroups, iters, C.byref(flop), stream))
+    return float(flop.value)
 
 
 def ae_attn_destroy(handle: Optional[int]) -> None:

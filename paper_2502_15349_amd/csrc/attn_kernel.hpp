@@ -470,6 +470,7 @@ template <class C>
 struct Sched {
   static constexpr int T = C::T, DB = C::DB, NPV = 2 * C::DB, NS = NPV + T, N = 2 * NS, PF = C::PF;
   static_assert(T >= PF && NPV >= PF, "the ring must not span more than two blocks of MFMAs");
+  static_assert(N % PF == 0, "ring slots are assigned by MFMA number modulo PF, across iterations too");
   static constexpr bool is_score(int r) { return r >= NPV; }  // position r inside a sub-step: aggregate, then score
   // first MFMA that reads the NEXT K buffer (sub-step 1 scores rows 0..31 of it)
   static constexpr int kFirstNextK = NS + NPV;
