@@ -165,10 +165,13 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     for (int hh = 0; hh < d->H_q; ++hh) h->decay.log2_gamma[hh] = std::log2(d->gamma[hh]);
 
   // Workgroup -> tile mapping (see attn_fwd_kernel): groups are dealt to the 8
-  // XCDs round-robin and walked `interleave` at a time per XCD.
+  // XCDs round-robin and walked `interleave` at a time per XCD.  Measured: a group
+  // whose workgroups fill the XCD's 32 CUs on their own runs best with 1-2 groups
+  // walked together, smaller groups with 8 (more K/V streams spread the reads
+  // over more L2 channels).
   const int64_t per_group = (int64_t)p.n_qtiles * p.g;
   const int64_t rounds = (p.n_groups + 7) / 8;  // groups per XCD
-  int interleave = 4;
+  int interleave = per_group >= 32 ? 2 : 8;
   if (const char* e = getenv("AE_ATTN_INTERLEAVE")) interleave = atoi(e);  // tuning aid
   if (interleave < 1) interleave = 1;
   if (interleave > rounds) interleave = (int)rounds;
