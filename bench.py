@@ -56,16 +56,18 @@ def time_gpu(A, torch, w, Q, K, V, steps, warmup, settle_s=0.4):
         for _ in range(warmup):
             fwd(*args)
         torch.cuda.synchronize()
-        # events are recorded on the stream the kernel is launched on
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        # One pair of events around the K launches, recorded on the stream the kernel is
+        # launched on: launches queue back to back, so elapsed / K is the kernel's mean
+        # duration (launch gaps included) without an event between every two kernels.
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
-        for a, b in evs:
-            a.record(stream)
+        ev0.record(stream)
+        for _ in range(steps):
             fwd(*args)
-            b.record(stream)
+        ev1.record(stream)
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-        ker_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        ker_ms = ev0.elapsed_time(ev1) / steps
     finally:
         A.ae_attn_destroy(h)
     return wall_ms, ker_ms, O, info

@@ -15,8 +15,8 @@ pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libae_attn.so n
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "ae_attn.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(ae_attn_[a-z_]+)\s*\(", hdr))
-    assert {"ae_attn_create", "ae_attn_forward", "ae_attn_destroy", "ae_attn_query"} <= names
+    names = set(re.findall(r"\b(ae_(?:attn|calib)_[a-z0-9_]+)\s*\(", hdr))
+    assert {"ae_attn_create", "ae_attn_forward", "ae_attn_destroy", "ae_attn_query", "ae_calib_mfma_bf16"} <= names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
@@ -84,3 +84,11 @@ def test_padded_strides_accepted():
     from paper_2502_15349_amd import ae_attn as A
     h = A.ae_attn_create(**_ok_desc(), q_stride=(100 * 4 * 136, 100 * 136, 136))
     A.ae_attn_destroy(h)
+
+
+def test_calibration_kernel_rejects_bad_arguments_without_launching():
+    from paper_2502_15349_amd import ae_attn as A
+    for args in [(0, 1 << 20, 4, 10), (4096, 100, 4, 10), (4096, 1 << 20, 0, 10), (4096, 1 << 20, 4, 0)]:
+        with pytest.raises(A.AeAttnError) as ei:
+            A.ae_calib_mfma_bf16(*args)
+        assert ei.value.status == A.AE_ERR_INVALID_ARG

@@ -205,3 +205,13 @@ def test_online_equals_two_pass_across_key_tilings(A):
     perm = torch.randperm(1000, generator=torch.Generator().manual_seed(5))
     shuf = gpu_run(A, w, Q, K[:, :, perm].contiguous(), V[:, :, perm].contiguous())
     assert np.abs(full - shuf).max() <= 2e-3   # same math, different blocking of the online update
+
+
+def test_calibration_kernel_runs(A):
+    # measurement aid: launches, reports its flop count, writes its sink
+    dev = torch.device("cuda:0")
+    sink = torch.full((4 * 512,), float("nan"), dtype=torch.float32, device=dev)
+    flop = A.ae_calib_mfma_bf16(sink.data_ptr(), sink.numel() * 4, 4, 10, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert flop == 4 * 8 * 10 * 16 * 32768.0
+    assert torch.isfinite(sink).all()
