@@ -489,7 +489,12 @@ struct KeyLoop {
   uint32_t dk, dv;  // byte distance to the next K / V buffer of the ring of LDS stages
   int i, off;       // this lane's query row; L_k - L_q
   int iw0;          // first query row of the wave
-  float g2;
+  float g2;         // decay: log2(gamma) of this head
+  // Decay, factorised per sub-tile where that cannot overflow (gamma in [1/16, 1]):
+  // gamma^(i + off - j) = 2^(g2 * (i + off - j0 - 4*half)) * a8^(r/4) * b[r%4] for
+  // register r, with the wave-uniform constants a8 = gamma^-8, b[k] = gamma^-k.
+  bool fact;
+  float a8, b1, b2, b3;
 
   // Issues the LDS read that feeds MFMA n.  Reads are issued in MFMA order, so
   // the fragment addresses are advanced to the next buffer exactly where the
@@ -524,7 +529,18 @@ struct KeyLoop {
     bool moved = false;
     const bool fold = C::NORM == NORM_SIGMOID && p.fold;  // wave-uniform
     if (masked) mask_raw<C>(s, jlim, fold ? INFINITY : -INFINITY);
-    if (fold) {
+    if (C::MOD == MOD_DECAY && fact) {
+      // one exponential per lane and sub-tile instead of one per score
+      float ra = p.c * fast_exp2(dbase);
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        s[4 * a + 0] *= ra;
+        s[4 * a + 1] *= ra * b1;
+        s[4 * a + 2] *= ra * b2;
+        s[4 * a + 3] *= ra * b3;
+        ra *= a8;
+      }
+    } else if (fold) {
 #pragma unroll
       for (int q = 0; q < 8; ++q) post_pair<C, true>(p, q, s, dbase, g2, mx);
     } else {
@@ -723,7 +739,14 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // the next iteration, one barrier before the first wave reads the tile.
   if (n_tiles > 0) {
     bf16x8 ring[C::PF];
-    KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2};
+    KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2, false, 1.f, 1.f, 1.f, 1.f};
+    if constexpr (C::MOD == MOD_DECAY) {
+      kl.fact = g2 <= 0.f && g2 >= -4.f;  // per head, hence uniform over the workgroup
+      kl.a8 = fast_exp2(-8.f * g2);
+      kl.b1 = fast_exp2(-g2);
+      kl.b2 = fast_exp2(-2.f * g2);
+      kl.b3 = fast_exp2(-3.f * g2);
+    }
     if (n_vis > 0) static_for<0, C::PF>([&](auto nc) { kl.template fetch<decltype(nc)::value>(); });
     const bool trailing = wave >= C::WAVES / 2;  // second wave of its SIMD
     using Two = std::integral_constant<int, 2>;

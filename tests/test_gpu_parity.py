@@ -215,3 +215,22 @@ def test_calibration_kernel_runs(A):
     torch.cuda.synchronize()
     assert flop == 4 * 8 * 10 * 16 * 32768.0
     assert torch.isfinite(sink).all()
+
+
+def test_decay_rates_outside_the_factorised_range(A):
+    # gamma < 1/16 and gamma > 1 take the per-score exponential, the others the
+    # per-sub-tile factorisation; both against the oracle
+    from oracle.attention_oracle import attention as oracle_attention
+    B, H, L, D = 1, 4, 90, 128
+    gam = [0.01, 0.5, 1.25, 1.0]
+    g = torch.Generator("cpu").manual_seed(4242)
+    Q, K, V = (torch.randn(B, H, L, d, generator=g).to(torch.bfloat16) for d in (D, D, 256))
+    dev = torch.device("cuda:0")
+    for norm in ("abssum", "none"):
+        scale = 0.09 if norm == "abssum" else 1e-4
+        O = A.attention_forward(Q.to(dev), K.to(dev), V.to(dev), scale=scale, score_mod="head_decay", gamma=gam,
+                                norm=norm, mask="causal")
+        torch.cuda.synchronize()
+        ref = oracle_attention(Q, K, V, scale=scale, score_mod="head_decay", gamma=gam, norm=norm, mask="causal")
+        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+        check(O.cpu().double().numpy() / rs, ref / rs, f"decay gammas {gam} norm {norm}")
