@@ -92,6 +92,16 @@ def test_shapes_softmax(A, Lq, Lk, mask):
         assert (got[:, :, : Lq - Lk] == 0).all()   # rows with no visible key
 
 
+@pytest.mark.parametrize("Lq,Lk", [(777, 1111), (1111, 777), (1024, 1024)])
+@pytest.mark.parametrize("mask", ["none", "causal"])
+def test_shapes_many_tiles_mla_dims(A, Lq, Lk, mask):
+    # several query tiles and a long key loop with ragged ends, D_qk != D_v
+    w = Workload("shape192", 16, 1, 2, 2, Lq, Lk, 192, 128, mask=mask)
+    Q, K, V = make_inputs(w)
+    print(f"case 192/128 Lq {Lq} Lk {Lk} mask {mask}", flush=True)
+    check(gpu_run(A, w, Q, K, V), oracle_run(w, Q, K, V), f"192/128 Lq={Lq} Lk={Lk} {mask}")
+
+
 @pytest.mark.parametrize("cid", [3, 4])
 @pytest.mark.parametrize("Lq,Lk", [(1, 1), (130, 130), (100, 400), (400, 100)])
 def test_shapes_sigmoid_retnet(A, cid, Lq, Lk):
