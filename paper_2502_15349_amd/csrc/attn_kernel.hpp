@@ -101,6 +101,13 @@ struct Cfg {
   static constexpr int DB = DV / 32;  // 32-wide blocks of output columns
   static constexpr int VA = DB < 4 ? DB : 4;  // V fragment base addresses kept per lane
   static constexpr int PF = 4;  // LDS fragment reads kept in flight ahead of their MFMA
+  // A copy instruction that finds the CU's vector memory queue full blocks the wave
+  // that issues it, and with it everything behind it in program order.  Where the
+  // matrix phase is the longer one the copies are issued in the vector phases (the
+  // K tile in the first, the V tile in the second of an iteration), so that the
+  // wave issuing MFMAs is never held up; where the vector phase is the longer one
+  // (few MFMAs per sub-tile), in three slices spread over matrix and vector phases.
+  static constexpr bool kCopyInVector = T + 2 * DB >= 12;
   static_assert(WAVES % 2 == 0, "waves pair up per SIMD");
   static_assert(DQK % 16 == 0 && DV % 32 == 0, "head dims must fit the MFMA tile");
   static_assert(K_BYTES % 1024 == 0 && V_BYTES % 1024 == 0, "tiles must be whole 1 KB blocks");
@@ -685,7 +692,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     const bool whole = j0 + C::BLOCK_N <= p.L_k;
     static_for<0, kCopies>([&](auto ic) {
       constexpr int n = decltype(ic)::value;
-      if constexpr (n % NSL == PART) {
+      if constexpr (NSL > 0 ? n % (NSL > 0 ? NSL : 1) == PART : ((n < C::KI) == (PART == 0))) {
         constexpr bool isk = n < C::KI;
         constexpr int m = isk ? n : n - C::KI, NB = isk ? C::NB_K : C::NB_V;
         const uint32_t dst = (isk ? lds0 + stage * C::K_BYTES : vlds0 + stage * C::V_BYTES) + ((wave + m * C::WAVES) % NB) * 1024;
@@ -730,13 +737,14 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // to be (see below); kaddr / vaddr point into the buffers of tile jt (stage index
   // buf); s_a holds the raw scores of sub-tile 2*jt.
   // Per iteration and wave: vector(2jt) | matrix<0> | vector(2jt+1) | matrix<1>, a
-  // barrier after each.  The copy of tile jt+2 goes into the buffer of tile jt-1,
-  // which the trailing half of the waves reads until the barrier that ends the
-  // leading half's vector(2jt); it is issued in three slices -- in matrix<0>,
-  // vector(2jt+1) and matrix<1> -- because the CU's vector memory path takes
-  // 64 bytes per clock and an instruction that finds its queue full blocks the
-  // wave that issues it.  Each wave awaits its slices at the end of matrix<0> of
-  // the next iteration, one barrier before the first wave reads the tile.
+  // barrier after each.  The copy of tile jt+2 goes into the stage of tile jt-1.
+  // The trailing half of the waves reads V(jt-1) until the barrier that ends the
+  // leading half's vector(2jt), and K(jt-1) only until a phase earlier; so the K
+  // tile may be copied from vector(2jt) on and the V tile from matrix<0> on.  The
+  // copy is cut into slices issued in different phases (the CU's vector memory
+  // path takes 64 bytes per clock; see Cfg::kCopyInVector for where).  Each wave
+  // awaits its slices at the end of matrix<0> of the next iteration, one barrier
+  // before the first wave reads the tile.
   if (n_tiles > 0) {
     bf16x8 ring[C::PF];
     KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2, false, 1.f, 1.f, 1.f, 1.f};
@@ -749,9 +757,6 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     }
     if (n_vis > 0) static_for<0, C::PF>([&](auto nc) { kl.template fetch<decltype(nc)::value>(); });
     const bool trailing = wave >= C::WAVES / 2;  // second wave of its SIMD
-    using Two = std::integral_constant<int, 2>;
-    using Three = std::integral_constant<int, 3>;
-    constexpr int kSlice0 = (kCopies + 2) / 3;  // instructions in slice 0
     int buf = 0;
     if (trailing) phase_barrier();
     for (int jt = 0; jt < n_tiles; ++jt) {
@@ -759,23 +764,43 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       kl.dk = (uint32_t)((nb - buf) * C::K_BYTES);
       kl.dv = (uint32_t)((nb - buf) * C::V_BYTES);
       const int u = 2 * jt;
-      if (u < n_vis) kl.vector_phase(s_a, u * C::SUB_N);
-      phase_barrier();
-      if (u < n_vis)
-        kl.template matrix_phase<0>(s_a, u + 1 < n_vis, [&] { copy_slice(Three{}, Zero{}, jt + 2, stage); });
-      else
-        copy_slice(Three{}, Zero{}, jt + 2, stage);
-      // all but the slice just issued: this wave's share of tile jt+1 has landed
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kSlice0) : "memory");
-      phase_barrier();
-      copy_slice(Three{}, One{}, jt + 2, stage);
-      if (u + 1 < n_vis) kl.vector_phase(s_a, (u + 1) * C::SUB_N);
-      phase_barrier();
-      if (u + 1 < n_vis)
-        kl.template matrix_phase<1>(s_a, u + 2 < n_vis, [&] { copy_slice(Three{}, Two{}, jt + 2, stage); });
-      else
-        copy_slice(Three{}, Two{}, jt + 2, stage);
-      phase_barrier();
+      // Where the copy of tile jt+2 is issued (see Cfg::kCopyInVector).
+      if constexpr (C::kCopyInVector) {
+        using Part = std::integral_constant<int, -1>;  // 0: the K tile, 1: the V tile
+        copy_slice(Part{}, Zero{}, jt + 2, stage);
+        if (u < n_vis) kl.vector_phase(s_a, u * C::SUB_N);
+        phase_barrier();
+        if (u < n_vis) kl.template matrix_phase<0>(s_a, u + 1 < n_vis, [] {});
+        // all but the K copy just issued: this wave's share of tile jt+1 has landed
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::KI) : "memory");
+        phase_barrier();
+        copy_slice(Part{}, One{}, jt + 2, stage);
+        if (u + 1 < n_vis) kl.vector_phase(s_a, (u + 1) * C::SUB_N);
+        phase_barrier();
+        if (u + 1 < n_vis) kl.template matrix_phase<1>(s_a, u + 2 < n_vis, [] {});
+        phase_barrier();
+      } else {
+        using Two = std::integral_constant<int, 2>;
+        using Three = std::integral_constant<int, 3>;
+        constexpr int kSlice0 = (kCopies + 2) / 3;  // instructions in slice 0
+        if (u < n_vis) kl.vector_phase(s_a, u * C::SUB_N);
+        phase_barrier();
+        if (u < n_vis)
+          kl.template matrix_phase<0>(s_a, u + 1 < n_vis, [&] { copy_slice(Three{}, Zero{}, jt + 2, stage); });
+        else
+          copy_slice(Three{}, Zero{}, jt + 2, stage);
+        // all but the slice just issued: this wave's share of tile jt+1 has landed
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kSlice0) : "memory");
+        phase_barrier();
+        copy_slice(Three{}, One{}, jt + 2, stage);
+        if (u + 1 < n_vis) kl.vector_phase(s_a, (u + 1) * C::SUB_N);
+        phase_barrier();
+        if (u + 1 < n_vis)
+          kl.template matrix_phase<1>(s_a, u + 2 < n_vis, [&] { copy_slice(Three{}, Two{}, jt + 2, stage); });
+        else
+          copy_slice(Three{}, Two{}, jt + 2, stage);
+        phase_barrier();
+      }
       buf = nb;
     }
     if (!trailing) phase_barrier();  // both halves are at the same point again
