@@ -726,10 +726,9 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // ---- prologue: tiles 0 and 1 -> LDS; raw scores of sub-tile 0 -------------------
   if (n_tiles > 0) {
     copy_slice(One{}, Zero{}, 0, 0);
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     copy_slice(One{}, Zero{}, 1, 1);
+    wait_dma_and_sync();  // one memory latency for both tiles (and the Q fragments)
     if (n_vis > 0) score_block<C>(kaddr, 0, qf, s_a);
-    wait_dma_and_sync();
   }
 
   // ---- key loop ------------------------------------------------------------------------
