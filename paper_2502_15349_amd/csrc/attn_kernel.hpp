@@ -227,6 +227,19 @@ __device__ __forceinline__ void dma16(const void* base_uniform, uint32_t byte_of
       : "memory", "m0");
 }
 
+// The same with the LDS address given as a wave-uniform base plus a compile-time
+// constant, added on the way into M0.
+template <int LDS_IMM>
+__device__ __forceinline__ void dma16_at(const void* base_uniform, uint32_t byte_off, uint32_t lds_base_uniform) {
+  asm volatile(
+      "s_add_i32 m0, %0, %3\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2"
+      :
+      : "s"(lds_base_uniform), "v"(byte_off), "s"(base_uniform), "n"(LDS_IMM)
+      : "memory", "m0", "scc");
+}
+
 // Waits until none of this wave's DMA loads is in flight, then meets the other
 // waves: what they waited for is visible too.
 __device__ __forceinline__ void wait_dma_and_sync() { asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); }
@@ -525,10 +538,12 @@ struct KeyLoop {
 
   // Vector phase: the raw scores in s (sub-tile u, starting at key j0 = 32u) become
   // packed weights in pk; the row state follows.
+  // FAST: the caller knows that no key of the sub-tile is hidden from any row of the wave.
+  template <bool FAST>
   __device__ __forceinline__ void vector_phase(f32x16& s, int j0) {
     const int half = (threadIdx.x & 63) >> 5;
     // wave-uniform: does the sub-tile cross the causal diagonal or the end of the keys?
-    const bool masked = (j0 + C::SUB_N > p.L_k) || (C::CAUSAL && (j0 + C::SUB_N - 1 > iw0 + off));
+    const bool masked = !FAST && ((j0 + C::SUB_N > p.L_k) || (C::CAUSAL && (j0 + C::SUB_N - 1 > iw0 + off)));
     // register r is visible  <=>  key_offset(r) <= jlim
     const int jlim = min(C::CAUSAL ? i + off : p.L_k - 1, p.L_k - 1) - j0 - 4 * half;
     const float dbase = C::MOD == MOD_DECAY ? g2 * (float)(i + off - j0 - 4 * half) : 0.f;
@@ -720,6 +735,35 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   using Zero = std::integral_constant<int, 0>;
   auto next_buf = [](int bidx) { return bidx + 1 == C::STAGES ? 0 : bidx + 1; };
 
+  // The same copy for a tile known to lie wholly inside the sequence, with the
+  // tile's first rows and the LDS stage's bases (this wave's first block) kept in
+  // running wave-uniform variables: per instruction a pointer step (shared
+  // offsets only), the LDS address and the copy itself.
+  static_assert(KMap::NB % C::WAVES == 0 && VMap::NB % C::WAVES == 0, "every wave copies the same number of distinct blocks");
+  const int64_t ktile_step = (int64_t)C::BLOCK_N * p.ks[2], vtile_step = (int64_t)C::BLOCK_N * p.vs[2];
+  const int64_t kblk_step = (int64_t)KMap::kRowStep * p.ks[2], vblk_step = (int64_t)VMap::kRowStep * p.vs[2];
+  const __bf16* kcp = kbase + 2 * ktile_step;  // tile 2 is the first one copied inside the loop
+  const __bf16* vcp = vbase + 2 * vtile_step;
+  const uint32_t kdst0 = lds0 + wave * 1024, vdst0 = vlds0 + wave * 1024;
+  auto copy_whole = [&](auto nsl, auto part, int stage) {
+    constexpr int NSL = decltype(nsl)::value, PART = decltype(part)::value;
+    const uint32_t kdst = kdst0 + stage * C::K_BYTES, vdst = vdst0 + stage * C::V_BYTES;
+    static_for<0, kCopies>([&](auto ic) {
+      constexpr int n = decltype(ic)::value;
+      if constexpr (NSL > 0 ? n % (NSL > 0 ? NSL : 1) == PART : ((n < C::KI) == (PART == 0))) {
+        constexpr bool isk = n < C::KI;
+        constexpr int m = isk ? n : n - C::KI;
+        using Map = std::conditional_t<isk, KMap, VMap>;
+        const __bf16* tile = isk ? kcp : vcp;
+        if constexpr (Map::kShared) tile += m * (isk ? kblk_step : vblk_step);
+        uint32_t goff;
+        if constexpr (isk) goff = kgoff[Map::kShared ? 0 : m];
+        else goff = vgoff[Map::kShared ? 0 : m];
+        dma16_at<m * C::WAVES * 1024>(tile, goff, isk ? kdst : vdst);
+      }
+    });
+  };
+
   f32x16 s_a;   // scores of the sub-tile to aggregate next
   u32x4 pk[2];  // packed weights of the sub-tile being aggregated
 
@@ -744,6 +788,14 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // path takes 64 bytes per clock; see Cfg::kCopyInVector for where).  Each wave
   // awaits its slices at the end of matrix<0> of the next iteration, one barrier
   // before the first wave reads the tile.
+  //
+  // A wave issues at most one instruction every four to five clocks, whatever its
+  // kind, so the length of a vector phase is its instruction count: the first
+  // n_main iterations of a wave -- every key visible to every row, the following
+  // sub-tile needed, the tile to copy whole -- run a form of the iteration with no
+  // visibility tests, no masking and the short copy; the rest (the diagonal and
+  // the end of the keys) run the general form.  Both pass the same barriers and
+  // issue the same number of copies.
   if (n_tiles > 0) {
     bf16x8 ring[C::PF];
     KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2, false, 1.f, 1.f, 1.f, 1.f};
@@ -757,51 +809,73 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     if (n_vis > 0) static_for<0, C::PF>([&](auto nc) { kl.template fetch<decltype(nc)::value>(); });
     const bool trailing = wave >= C::WAVES / 2;  // second wave of its SIMD
     int buf = 0;
-    if (trailing) phase_barrier();
-    for (int jt = 0; jt < n_tiles; ++jt) {
+
+    auto iteration = [&](auto fastc, int jt) {
+      constexpr bool FAST = decltype(fastc)::value;
       const int nb = next_buf(buf), stage = next_buf(nb);
       kl.dk = (uint32_t)((nb - buf) * C::K_BYTES);
       kl.dv = (uint32_t)((nb - buf) * C::V_BYTES);
       const int u = 2 * jt;
+      const bool vis0 = FAST || u < n_vis, vis1 = FAST || u + 1 < n_vis;    // sub-tiles to aggregate
+      const bool sc0 = FAST || u + 1 < n_vis, sc1 = FAST || u + 2 < n_vis;  // sub-tiles to score
+      auto copy = [&](auto nsl, auto part) {
+        if constexpr (FAST) copy_whole(nsl, part, stage);
+        else copy_slice(nsl, part, jt + 2, stage);
+      };
       // Where the copy of tile jt+2 is issued (see Cfg::kCopyInVector).
       if constexpr (C::kCopyInVector) {
         using Part = std::integral_constant<int, -1>;  // 0: the K tile, 1: the V tile
-        copy_slice(Part{}, Zero{}, jt + 2, stage);
-        if (u < n_vis) kl.vector_phase(s_a, u * C::SUB_N);
+        copy(Part{}, Zero{});
+        if (vis0) kl.template vector_phase<FAST>(s_a, u * C::SUB_N);
         phase_barrier();
-        if (u < n_vis) kl.template matrix_phase<0>(s_a, u + 1 < n_vis, [] {});
+        if (vis0) kl.template matrix_phase<0>(s_a, sc0, [] {});
         // all but the K copy just issued: this wave's share of tile jt+1 has landed
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::KI) : "memory");
         phase_barrier();
-        copy_slice(Part{}, One{}, jt + 2, stage);
-        if (u + 1 < n_vis) kl.vector_phase(s_a, (u + 1) * C::SUB_N);
+        copy(Part{}, One{});
+        if (vis1) kl.template vector_phase<FAST>(s_a, (u + 1) * C::SUB_N);
         phase_barrier();
-        if (u + 1 < n_vis) kl.template matrix_phase<1>(s_a, u + 2 < n_vis, [] {});
+        if (vis1) kl.template matrix_phase<1>(s_a, sc1, [] {});
         phase_barrier();
       } else {
         using Two = std::integral_constant<int, 2>;
         using Three = std::integral_constant<int, 3>;
         constexpr int kSlice0 = (kCopies + 2) / 3;  // instructions in slice 0
-        if (u < n_vis) kl.vector_phase(s_a, u * C::SUB_N);
+        if (vis0) kl.template vector_phase<FAST>(s_a, u * C::SUB_N);
         phase_barrier();
-        if (u < n_vis)
-          kl.template matrix_phase<0>(s_a, u + 1 < n_vis, [&] { copy_slice(Three{}, Zero{}, jt + 2, stage); });
+        if (vis0)
+          kl.template matrix_phase<0>(s_a, sc0, [&] { copy(Three{}, Zero{}); });
         else
-          copy_slice(Three{}, Zero{}, jt + 2, stage);
+          copy(Three{}, Zero{});
         // all but the slice just issued: this wave's share of tile jt+1 has landed
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kSlice0) : "memory");
         phase_barrier();
-        copy_slice(Three{}, One{}, jt + 2, stage);
-        if (u + 1 < n_vis) kl.vector_phase(s_a, (u + 1) * C::SUB_N);
+        copy(Three{}, One{});
+        if (vis1) kl.template vector_phase<FAST>(s_a, (u + 1) * C::SUB_N);
         phase_barrier();
-        if (u + 1 < n_vis)
-          kl.template matrix_phase<1>(s_a, u + 2 < n_vis, [&] { copy_slice(Three{}, Two{}, jt + 2, stage); });
+        if (vis1)
+          kl.template matrix_phase<1>(s_a, sc1, [&] { copy(Three{}, Two{}); });
         else
-          copy_slice(Three{}, Two{}, jt + 2, stage);
+          copy(Three{}, Two{});
         phase_barrier();
       }
+      if constexpr (FAST) {
+        kcp += ktile_step;
+        vcp += vtile_step;
+      }
       buf = nb;
-    }
+    };
+
+    // Iterations jt < n_main of this wave: sub-tiles 2jt, 2jt+1 and 2jt+2 are visible,
+    // no key of tile jt is hidden from any of its rows, tile jt+2 is a whole tile.
+    int n_main = min((n_vis - 1) / 2, min(p.L_k / C::BLOCK_N, n_tiles) - 2);
+    if (C::CAUSAL) n_main = min(n_main, (iw0 + off + 1) / C::BLOCK_N);
+    n_main = max(n_main, 0);
+
+    if (trailing) phase_barrier();
+    int jt = 0;
+    for (; jt < n_main; ++jt) iteration(std::true_type{}, jt);
+    for (; jt < n_tiles; ++jt) iteration(std::false_type{}, jt);
     if (!trailing) phase_barrier();  // both halves are at the same point again
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // redundant tail copies must land before LDS is released
