@@ -94,7 +94,10 @@ struct Cfg {
   // While tile j is being worked on, tiles j and j+1 are readable (scoring and
   // the fragment ring run ahead of aggregation) and tile j+2 is arriving.
   static constexpr int STAGES = 3;
-  static constexpr int LDS_BYTES = STAGES * (K_BYTES + V_BYTES);
+  // At the end the same LDS stages the output: per wave 32 rows x OC columns of fp32.
+  static constexpr int OC = DV < 128 ? DV : 128;
+  static constexpr int TILE_BYTES = STAGES * (K_BYTES + V_BYTES), OUT_BYTES = WAVES * 32 * OC * 4;
+  static constexpr int LDS_BYTES = TILE_BYTES > OUT_BYTES ? TILE_BYTES : OUT_BYTES;
   static constexpr int NB_K = K_BYTES / 1024, NB_V = V_BYTES / 1024;  // 1 KB blocks per tile
   static constexpr int KI = (NB_K + WAVES - 1) / WAVES, VI = (NB_V + WAVES - 1) / WAVES;
   static constexpr int T = DQK / 16;  // contraction steps of the scoring MFMA
@@ -428,6 +431,13 @@ __device__ __forceinline__ bf16x8 read_v_frag(uint32_t addr, int row8_bytes) {
       __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)(addr + row8_bytes));
   const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, both);
+}
+
+__device__ __forceinline__ void lds_write16(uint32_t addr, f32x4 v) {
+  *reinterpret_cast<__attribute__((address_space(3))) f32x4*>((lds_char*)(uintptr_t)addr) = v;
+}
+__device__ __forceinline__ f32x4 lds_read16(uint32_t addr) {
+  return *reinterpret_cast<__attribute__((address_space(3))) const f32x4*>((lds_char*)(uintptr_t)addr);
 }
 
 // A operand of the aggregation MFMA for sub-tile `sub` (0/1) of the V tile,
@@ -878,7 +888,9 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     for (; jt < n_tiles; ++jt) iteration(std::false_type{}, jt);
     if (!trailing) phase_barrier();  // both halves are at the same point again
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // redundant tail copies must land before LDS is released
+  // The tail's redundant copies have landed and every wave is past its last fragment
+  // read: the LDS of the tiles is free.
+  wait_dma_and_sync();
 
   // ---- online_epilogue + store ------------------------------------------------
   float inv = 1.f;
@@ -890,17 +902,33 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   } else if constexpr (C::NORM == NORM_ABS_OF_SUM) {
     inv = 1.f / fmaxf(fabsf(sum_halves(st.l)), 1.f);
   }
-  if (i < p.L_q) {
-    float* orow = obase + (int64_t)i * p.os[2];
+  // A lane holds 4-column pieces of one output row, 32 bytes apart from its
+  // partner's: stored directly, every instruction would touch 32 rows with 32
+  // bytes each.  Instead each wave turns its 32 x OC block around in a private
+  // piece of LDS (16-byte chunk c of row r at position c ^ (r % 16): both the
+  // column-wise writes and the row-wise reads are free of bank conflicts) and
+  // stores whole rows, 1 KB of full cache lines per instruction.
+  constexpr int OC = C::OC, CPRO = OC / 4, DBP = OC / 32;
+  const uint32_t obuf = lds0 + wave * (32 * OC * 4);
 #pragma unroll
-    for (int db = 0; db < C::DB; ++db)
+  for (int pass = 0; pass < C::DV / OC; ++pass) {
+#pragma unroll
+    for (int dbl = 0; dbl < DBP; ++dbl)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         f32x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = st.o[db][4 * r4 + e] * inv;
-        *reinterpret_cast<f32x4*>(orow + db * 32 + r4 * 8 + half * 4) = v;
+        for (int e = 0; e < 4; ++e) v[e] = st.o[pass * DBP + dbl][4 * r4 + e] * inv;
+        const int c = dbl * 8 + r4 * 2 + half;
+        lds_write16(obuf + ql * (OC * 4) + ((c ^ (ql & 15)) * 16), v);
       }
+#pragma unroll
+    for (int k = 0; k < 32 * CPRO / 64; ++k) {
+      const int row = k * (64 / CPRO) + lane / CPRO, pc = lane % CPRO;
+      const f32x4 v = lds_read16(obuf + row * (OC * 4) + ((pc ^ (row & 15)) * 16));
+      if (iw0 + row < p.L_q)
+        *reinterpret_cast<f32x4*>(obase + (int64_t)(iw0 + row) * p.os[2] + pass * OC + pc * 4) = v;
+    }
   }
 }
 
