@@ -96,8 +96,12 @@ struct Cfg {
   static constexpr int STAGES = 3;
   // At the end the same LDS stages the output: per wave 32 rows x OC columns of fp32.
   static constexpr int OC = DV < 128 ? DV : 128;
-  static constexpr int TILE_BYTES = STAGES * (K_BYTES + V_BYTES), OUT_BYTES = WAVES * 32 * OC * 4;
-  static constexpr int LDS_BYTES = TILE_BYTES > OUT_BYTES ? TILE_BYTES : OUT_BYTES;
+  // A stage holds a K tile followed by a V tile.  At the start the query rows pass
+  // through the LDS behind stage 0 (32 rows per wave, laid out like a K sub-tile).
+  static constexpr int STAGE_BYTES = K_BYTES + V_BYTES, Q_BYTES = WAVES * 32 * RB_K;
+  static constexpr int TILE_BYTES = STAGES * STAGE_BYTES, OUT_BYTES = WAVES * 32 * OC * 4;
+  static constexpr int cmax(int a, int b) { return a > b ? a : b; }
+  static constexpr int LDS_BYTES = cmax(TILE_BYTES, cmax(OUT_BYTES, STAGE_BYTES + Q_BYTES));
   static constexpr int NB_K = K_BYTES / 1024, NB_V = V_BYTES / 1024;  // 1 KB blocks per tile
   static constexpr int KI = (NB_K + WAVES - 1) / WAVES, VI = (NB_V + WAVES - 1) / WAVES;
   static constexpr int T = DQK / 16;  // contraction steps of the scoring MFMA
@@ -660,20 +664,6 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   const __bf16* vbase = p.V + b * p.vs[0] + hkv * p.vs[1];
   float* obase = p.O + b * p.os[0] + hq * p.os[1];
 
-  // ---- Q fragments (B operand of S^T = K Q^T), resident for the whole kernel -
-  bf16x8 qf[C::T];
-#pragma unroll
-  for (int tt = 0; tt < C::T; ++tt) {
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (i < p.L_q) v = *reinterpret_cast<const u32x4*>(qbase + (int64_t)i * p.qs[2] + tt * 16 + half * 8);
-    if (p.neg_q) v ^= (u32x4){0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
-    bf16x8 qv = __builtin_bit_cast(bf16x8, v);
-    if (C::NORM == NORM_SIGMOID && p.fold) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qv[e] = (__bf16)((float)qv[e] * -p.c);
-    }
-    qf[tt] = qv;
-  }
   RowState<C> st;
   st.m = -INFINITY;
   st.l = 0.f;
@@ -691,9 +681,9 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   }
   const int n_tiles = (kmax + C::BLOCK_N - 1) / C::BLOCK_N;  // LDS tiles (workgroup)
   const int n_vis = (kmax_w + C::SUB_N - 1) / C::SUB_N;      // visible sub-tiles (wave)
-  // LDS: STAGES K buffers, then STAGES V buffers; tile j lives in buffer j % STAGES.
+  // LDS: STAGES stages of a K buffer and a V buffer; tile j lives in stage j % STAGES.
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
-  const uint32_t vlds0 = lds0 + C::STAGES * C::K_BYTES;
+  const uint32_t vlds0 = lds0 + C::K_BYTES;
   uint32_t kaddr[C::T], vaddr[C::VA];  // fragment addresses inside the K / V buffer in use
   k_frag_offsets<C>(lds0, kaddr);
   v_frag_offsets<C>(vlds0, vaddr);
@@ -720,7 +710,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       if constexpr (NSL > 0 ? n % (NSL > 0 ? NSL : 1) == PART : ((n < C::KI) == (PART == 0))) {
         constexpr bool isk = n < C::KI;
         constexpr int m = isk ? n : n - C::KI, NB = isk ? C::NB_K : C::NB_V;
-        const uint32_t dst = (isk ? lds0 + stage * C::K_BYTES : vlds0 + stage * C::V_BYTES) + ((wave + m * C::WAVES) % NB) * 1024;
+        const uint32_t dst = (isk ? lds0 : vlds0) + stage * C::STAGE_BYTES + ((wave + m * C::WAVES) % NB) * 1024;
         using Map = std::conditional_t<isk, KMap, VMap>;
         const int64_t pitch = isk ? p.ks[2] : p.vs[2];  // elements per row
         const __bf16* tile = isk ? ktile : vtile;
@@ -757,7 +747,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   const uint32_t kdst0 = lds0 + wave * 1024, vdst0 = vlds0 + wave * 1024;
   auto copy_whole = [&](auto nsl, auto part, int stage) {
     constexpr int NSL = decltype(nsl)::value, PART = decltype(part)::value;
-    const uint32_t kdst = kdst0 + stage * C::K_BYTES, vdst = vdst0 + stage * C::V_BYTES;
+    const uint32_t kdst = kdst0 + stage * C::STAGE_BYTES, vdst = vdst0 + stage * C::STAGE_BYTES;
     static_for<0, kCopies>([&](auto ic) {
       constexpr int n = decltype(ic)::value;
       if constexpr (NSL > 0 ? n % (NSL > 0 ? NSL : 1) == PART : ((n < C::KI) == (PART == 0))) {
@@ -777,11 +767,45 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   f32x16 s_a;   // scores of the sub-tile to aggregate next
   u32x4 pk[2];  // packed weights of the sub-tile being aggregated
 
-  // ---- prologue: tiles 0 and 1 -> LDS; raw scores of sub-tile 0 -------------------
+  // ---- prologue: Q fragments; tiles 0 and 1 -> LDS; raw scores of sub-tile 0 -------
+  // The Q fragments (B operand of S^T = K Q^T, resident for the whole kernel) hold,
+  // per lane, 16-byte pieces of one query row: loaded straight from memory, every
+  // instruction would touch 32 rows.  The wave's 32 rows are copied to LDS like a K
+  // sub-tile instead (1 KB of consecutive bytes per instruction, same swizzle)
+  // and read back as fragments.  They land behind stage 0, next to tile 0, which is
+  // copied at the same time; tile 1 follows once every wave has its fragments.
+  bf16x8 qf[C::T];
   if (n_tiles > 0) {
+    using QMap = DmaMap<1, 32, C::CPR_K, false>;
+    const uint32_t qlds = lds0 + C::STAGE_BYTES + wave * (32 * C::RB_K);
+    // rows past the end of the queries repeat the last one (their output is not stored)
+    const int qrow0 = min(iw0, max(p.L_q - 32, 0));
+    const __bf16* qtile = qbase + (int64_t)qrow0 * p.qs[2];
+    static_for<0, QMap::N>([&](auto mc) {
+      constexpr int m = decltype(mc)::value;
+      const int pos = m * 64 + lane, r = pos / C::CPR_K, pc = pos % C::CPR_K;
+      const int row = min(iw0 + r, p.L_q - 1) - qrow0;
+      const uint32_t goff = (uint32_t)(row * (int)p.qs[2] + (pc ^ kswz<C::CPR_K>(r)) * 8) * 2u;
+      dma16_at<m * 1024>(qtile, goff, qlds);
+    });
     copy_slice(One{}, Zero{}, 0, 0);
+    wait_dma_and_sync();  // one memory latency for the queries and tile 0
+    uint32_t qaddr[C::T];
+    k_frag_offsets<C>(qlds, qaddr);
+#pragma unroll
+    for (int tt = 0; tt < C::T; ++tt) {
+      u32x4 v = __builtin_bit_cast(u32x4, read_k_frag(qaddr[tt]));
+      if (p.neg_q) v ^= (u32x4){0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
+      bf16x8 qv = __builtin_bit_cast(bf16x8, v);
+      if (C::NORM == NORM_SIGMOID && p.fold) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qv[e] = (__bf16)((float)qv[e] * -p.c);
+      }
+      qf[tt] = qv;
+    }
+    // every wave has read its rows before tile 1 overwrites them
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     copy_slice(One{}, Zero{}, 1, 1);
-    wait_dma_and_sync();  // one memory latency for both tiles (and the Q fragments)
     if (n_vis > 0) score_block<C>(kaddr, 0, qf, s_a);
   }
 
@@ -823,8 +847,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     auto iteration = [&](auto fastc, int jt) {
       constexpr bool FAST = decltype(fastc)::value;
       const int nb = next_buf(buf), stage = next_buf(nb);
-      kl.dk = (uint32_t)((nb - buf) * C::K_BYTES);
-      kl.dv = (uint32_t)((nb - buf) * C::V_BYTES);
+      kl.dk = kl.dv = (uint32_t)((nb - buf) * C::STAGE_BYTES);
       const int u = 2 * jt;
       const bool vis0 = FAST || u < n_vis, vis1 = FAST || u + 1 < n_vis;    // sub-tiles to aggregate
       const bool sc0 = FAST || u + 1 < n_vis, sc1 = FAST || u + 2 < n_vis;  // sub-tiles to score
