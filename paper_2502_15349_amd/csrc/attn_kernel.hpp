@@ -693,8 +693,8 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   uint32_t kgoff[KMap::NOFF], vgoff[VMap::NOFF];
   KMap::offsets(wave, p.ks[2], kgoff);
   VMap::offsets(wave, p.vs[2], vgoff);
-  // Tile indices past the last tile are clamped: the copy is redundant but keeps
-  // every wave's stream of loads identical.
+  // A tile index past the last tile is clamped (only the prologue's copy of tile 1
+  // of a one-tile walk asks for one).
   const int last_tile = max(n_tiles - 1, 0);
   constexpr int kCopies = C::KI + C::VI;  // copy instructions per wave and tile
   // Copy instructions n of tile jt with n % NSL == PART into LDS stage `stage`
@@ -828,8 +828,8 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // n_main iterations of a wave -- every key visible to every row, the following
   // sub-tile needed, the tile to copy whole -- run a form of the iteration with no
   // visibility tests, no masking and the short copy; the rest (the diagonal and
-  // the end of the keys) run the general form.  Both pass the same barriers and
-  // issue the same number of copies.
+  // the end of the keys) run the general form.  Both pass the same barriers; the
+  // last two iterations have no tile left to copy and wait for all copies instead.
   if (n_tiles > 0) {
     bf16x8 ring[C::PF];
     KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2, false, 1.f, 1.f, 1.f, 1.f};
@@ -851,9 +851,16 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       const int u = 2 * jt;
       const bool vis0 = FAST || u < n_vis, vis1 = FAST || u + 1 < n_vis;    // sub-tiles to aggregate
       const bool sc0 = FAST || u + 1 < n_vis, sc1 = FAST || u + 2 < n_vis;  // sub-tiles to score
+      const bool more = FAST || jt + 2 < n_tiles;  // there is a tile jt+2 to copy
       auto copy = [&](auto nsl, auto part) {
         if constexpr (FAST) copy_whole(nsl, part, stage);
-        else copy_slice(nsl, part, jt + 2, stage);
+        else if (more) copy_slice(nsl, part, jt + 2, stage);
+      };
+      // This wave's share of tile jt+1 has landed: all of its copies but the `newest`
+      // of tile jt+2 just issued (if there is a tile jt+2).
+      auto await_next_tile = [&](auto newest) {
+        if (more) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(decltype(newest)::value) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       };
       // Where the copy of tile jt+2 is issued (see Cfg::kCopyInVector).
       if constexpr (C::kCopyInVector) {
@@ -862,8 +869,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
         if (vis0) kl.template vector_phase<FAST>(s_a, u * C::SUB_N);
         phase_barrier();
         if (vis0) kl.template matrix_phase<0>(s_a, sc0, [] {});
-        // all but the K copy just issued: this wave's share of tile jt+1 has landed
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::KI) : "memory");
+        await_next_tile(std::integral_constant<int, C::KI>{});
         phase_barrier();
         copy(Part{}, One{});
         if (vis1) kl.template vector_phase<FAST>(s_a, (u + 1) * C::SUB_N);
@@ -880,8 +886,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
           kl.template matrix_phase<0>(s_a, sc0, [&] { copy(Three{}, Zero{}); });
         else
           copy(Three{}, Zero{});
-        // all but the slice just issued: this wave's share of tile jt+1 has landed
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kSlice0) : "memory");
+        await_next_tile(std::integral_constant<int, kSlice0>{});
         phase_barrier();
         copy(Three{}, One{});
         if (vis1) kl.template vector_phase<FAST>(s_a, (u + 1) * C::SUB_N);
@@ -911,8 +916,8 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     for (; jt < n_tiles; ++jt) iteration(std::false_type{}, jt);
     if (!trailing) phase_barrier();  // both halves are at the same point again
   }
-  // The tail's redundant copies have landed and every wave is past its last fragment
-  // read: the LDS of the tiles is free.
+  // No copy is in flight (the last iterations issue none) and every wave is past its
+  // last fragment read: the LDS of the tiles is free.
   wait_dma_and_sync();
 
   // ---- online_epilogue + store ------------------------------------------------
