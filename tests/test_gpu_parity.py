@@ -181,9 +181,11 @@ def test_determinism_bit_exact(A):
     assert torch.equal(a, b)
 
 
-def test_strided_inputs_and_output(A):
-    # rows padded to a wider pitch, heads interleaved: [B, L, H, D] storage viewed as [B, H, L, D]
-    w = Workload("strided", 13, 2, 4, 2, 200, 200, 128, 128, mask="causal")
+@pytest.mark.parametrize("dims", DIMS, ids=lambda d: f"d{d[0]}_{d[1]}")
+def test_strided_inputs_and_output(A, dims):
+    # rows padded to a wider pitch, heads interleaved: [B, L, H, D] storage viewed as [B, H, L, D];
+    # 300 rows: a full 256-row query tile plus a ragged one, five key tiles
+    w = Workload("strided", 13, 2, 4, 2, 300, 300, dims[0], dims[1], mask="causal")
     Q, K, V = make_inputs(w)
     dev = torch.device("cuda:0")
 
