@@ -82,6 +82,33 @@ CONFIGS = {w.name: w for w in (C1, C2, C3, C4, C5)}
 BY_ID = {w.config_id: w for w in (C1, C2, C3, C4, C5)}
 
 
+def table2_workloads():
+    """The parallel-pattern rows of the paper's operator microbenchmark (Table 2) that the
+    tile table covers, over its grid of batch 1 / 8 and sequence 2k / 4k / 8k (Section 6.1).
+    The paper does not say which rows are causal: the language-model rows are taken as
+    causal, the vision row (ReLU attention, ViT) as unmasked; the sigmoid row gets the
+    bias -ln(L) of sigmoid attention.  Retention parallel at 256/512 is outside the table
+    of head dims."""
+    rows = (
+        ("softmax_llama31_8b", 32, 128, 128, dict(mask="causal")),
+        ("softmax_dsv2_lite", 16, 192, 128, dict(mask="causal")),
+        ("softmax_difftr_3b", 12, 128, 256, dict(mask="causal")),
+        ("sigmoid_llama3_8b", 32, 128, 128, dict(mask="causal", norm="sigmoid", score_mod="bias")),
+        ("relu_vit_s16", 6, 64, 64, dict(norm="none", score_mod="relu")),
+    )
+    out = []
+    cid = 100
+    for name, heads, dqk, dv, kw in rows:
+        for batch in (1, 8):
+            for seq in (2048, 4096, 8192):
+                cid += 1
+                extra = dict(kw)
+                if extra.get("score_mod") == "bias":
+                    extra["bias"] = -math.log(float(seq))
+                out.append(Workload(f"t2_{name}_b{batch}_s{seq}", cid, batch, heads, heads, seq, seq, dqk, dv, **extra))
+    return out
+
+
 def make_inputs(w: Workload, seed_base: Optional[int] = None):
     """Return (Q, K, V) as contiguous CPU bf16 tensors [B, H, L, D]."""
     base = 1000 * w.config_id if seed_base is None else seed_base

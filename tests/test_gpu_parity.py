@@ -153,6 +153,28 @@ def test_full_config_sampled(A, w):
     _sampled_full_config(A, w)
 
 
+def test_table2_shapes_sampled(A):
+    """The paper's microbenchmark shapes (Table 2) at batch 1, sequence 2k: one sampled head each,
+    rows compared after scaling by max(1, max |oracle row|) (ReLU attention is not normalised)."""
+    from paper_2502_15349_amd.workloads import table2_workloads
+    dev = torch.device("cuda:0")
+    for w in table2_workloads():
+        if w.B != 1 or w.L_q != 2048:
+            continue
+        Q, K, V = make_inputs(w)
+        print(f"case {w.name}", flush=True)
+        O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev))
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(w.config_id)
+        h = int(rng.integers(w.H_q))
+        rows = np.unique(np.concatenate([[0, 255, 256, w.L_q - 1], rng.integers(0, w.L_q, 40)])).astype(np.int64)
+        ref = attention_head(Q[0, h], K[0, h], V[0, h], scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
+                             gamma_h=None, norm=w.norm, mask=w.mask, rows=rows)
+        got = O[0, h].cpu().double().numpy()[rows]
+        e = np.abs(got - ref) / np.maximum(1.0, np.abs(ref).max(axis=1, keepdims=True))
+        assert e.max() <= MAX_ABS and e.mean() <= MEAN_ABS, (w.name, e.max(), e.mean())
+
+
 def test_full_size_properties_c2(A):
     """Properties that hold at any size, at C2's full shape and launch geometry."""
     w = C2
