@@ -34,12 +34,12 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def time_gpu(A, torch, w, Q, K, V, steps, warmup, settle_s=0.4):
+def time_gpu(A, torch, w, Q, K, V, steps, warmup, settle_s=0.4, out_bf16=False):
     """Returns (wall ms per step, mean step ms by HIP events, output, launch info)."""
-    O = torch.empty((w.B, w.H_q, w.L_q, w.D_v), dtype=torch.float32, device=Q.device)
+    O = torch.empty((w.B, w.H_q, w.L_q, w.D_v), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=Q.device)
     h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
                          scale=w.scale_value, score_mod=w.score_mod, bias=w.bias, gamma=w.gamma(),
-                         norm=w.norm, mask=w.mask)
+                         norm=w.norm, mask=w.mask, out_dtype="bf16" if out_bf16 else "f32")
     info = A.ae_attn_query(h)
     stream = torch.cuda.current_stream()
     args = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), stream.cuda_stream)
@@ -244,6 +244,15 @@ def main():
             tf = wv.mfma_flop() / (kms * 1e-3) / 1e12
             variants[name] = {"tflops": round(tf, 2), "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4),
                               "kernel_ms": round(kms, 5), "parity_max_abs": pv["max_abs"]}
+        # the same workload storing bf16 instead of fp32 (half the output bytes)
+        del Q, K, V, O
+        torch.cuda.empty_cache()
+        Q, K, V = Qc.to(dev), Kc.to(dev), Vc.to(dev)
+        _, kms, Ob, _ = time_gpu(A, torch, w, Q, K, V, max(5, min(a.steps, 20)), min(a.warmup, 5), out_bf16=True)
+        pv = parity_sample(w, Q, K, V, Ob.float())
+        tf = flop / (kms * 1e-3) / 1e12
+        variants[w.name + "_bf16_out"] = {"tflops": round(tf, 2), "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4),
+                                          "kernel_ms": round(kms, 5), "parity_max_abs": pv["max_abs"]}
         out["variants"] = variants
 
     # What the matrix pipes sustain on this board with nothing else in the way: the library's

@@ -63,14 +63,16 @@ typedef enum {
   AE_MASK_CAUSAL = 1 /* key j visible to query i iff j <= i + (L_k - L_q)      */
 } ae_mask_t;
 
-typedef enum { AE_OUT_F32 = 0 } ae_out_dtype_t;
+/* Element type of O.  The kernel computes the normalised rows in fp32 either
+ * way; AE_OUT_BF16 rounds them to bf16 (nearest even) when they are stored.   */
+typedef enum { AE_OUT_F32 = 0, AE_OUT_BF16 = 1 } ae_out_dtype_t;
 
 #define AE_MAX_DECAY_HEADS 256
 
 /*
  * Problem descriptor (host memory, copied by ae_attn_create).
  *
- * Layouts (bf16 inputs, fp32 output, innermost dimension contiguous):
+ * Layouts (bf16 inputs, fp32 or bf16 output, innermost dimension contiguous):
  *   Q [B, H_q,  L_q, D_qk]   K [B, H_kv, L_k, D_qk]
  *   V [B, H_kv, L_k, D_v ]   O [B, H_q,  L_q, D_v ]
  * Query head h_q reads key/value head h_q / (H_q / H_kv) (contiguous groups).

@@ -23,6 +23,7 @@ AE_OK, AE_ERR_INVALID_ARG, AE_ERR_UNSUPPORTED, AE_ERR_HIP, AE_ERR_NOMEM = range(
 SCORE_MODS = {"none": 0, "bias": 1, "head_decay": 2, "relu": 3}
 NORMS = {"softmax": 0, "sigmoid": 1, "abssum": 2, "abs_of_sum": 3, "none": 4}
 MASKS = {"none": 0, "causal": 1}
+OUT_DTYPES = {"f32": 0, "bf16": 1}
 
 
 class ae_attn_desc_t(C.Structure):
@@ -76,14 +77,16 @@ def _check(status: int) -> None:
 def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int, D_v: int,
                    scale: float, score_mod="none", bias: float = 0.0,
                    gamma: Optional[Sequence[float]] = None, norm="softmax", mask="none",
-                   q_stride=(0, 0, 0), k_stride=(0, 0, 0), v_stride=(0, 0, 0), o_stride=(0, 0, 0)) -> int:
+                   q_stride=(0, 0, 0), k_stride=(0, 0, 0), v_stride=(0, 0, 0), o_stride=(0, 0, 0),
+                   out_dtype="f32") -> int:
     """Returns an opaque handle (int).  Enum arguments accept names or raw ints."""
     d = ae_attn_desc_t()
     d.B, d.H_q, d.H_kv, d.L_q, d.L_k, d.D_qk, d.D_v = B, H_q, H_kv, L_q, L_k, D_qk, D_v
     d.score_mod = SCORE_MODS[score_mod] if isinstance(score_mod, str) else int(score_mod)
     d.norm = NORMS[norm] if isinstance(norm, str) else int(norm)
     d.mask = MASKS[mask] if isinstance(mask, str) else int(mask)
-    d.bias, d.scale, d.out_dtype = float(bias), float(scale), 0
+    d.bias, d.scale = float(bias), float(scale)
+    d.out_dtype = OUT_DTYPES[out_dtype] if isinstance(out_dtype, str) else int(out_dtype)
     keep = None
     if gamma is not None:
         keep = (C.c_float * len(gamma))(*[float(x) for x in gamma])
@@ -122,9 +125,10 @@ def ae_attn_query(handle: int) -> dict:
 
 # ---- convenience for torch callers (still marshalling only) -------------------
 def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
-                      mask="none", out=None, stream=None):
+                      mask="none", out=None, stream=None, out_dtype=None):
     """Runs the HIP operator on CUDA/HIP bf16 tensors laid out [B, H, L, D]
-    (last dim contiguous) and returns O as fp32 [B, H_q, L_q, D_v]."""
+    (last dim contiguous) and returns O [B, H_q, L_q, D_v]: fp32, or bf16 if `out` is a
+    bf16 tensor or out_dtype is torch.bfloat16."""
     import torch
 
     if not (Q.is_cuda and K.is_cuda and V.is_cuda):
@@ -137,11 +141,13 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
     if K.shape != (B, H_kv, L_k, D_qk):
         raise ValueError("K shape does not match Q / V")
     if out is None:
-        out = torch.empty((B, H_q, L_q, D_v), dtype=torch.float32, device=Q.device)
+        out = torch.empty((B, H_q, L_q, D_v), dtype=out_dtype or torch.float32, device=Q.device)
+    if out.dtype not in (torch.float32, torch.bfloat16) or out.stride(3) != 1:
+        raise ValueError("O must be fp32 or bf16 with a contiguous last dimension")
     h = ae_attn_create(B=B, H_q=H_q, H_kv=H_kv, L_q=L_q, L_k=L_k, D_qk=D_qk, D_v=D_v, scale=scale,
                        score_mod=score_mod, bias=bias, gamma=gamma, norm=norm, mask=mask,
                        q_stride=Q.stride()[:3], k_stride=K.stride()[:3], v_stride=V.stride()[:3],
-                       o_stride=out.stride()[:3])
+                       o_stride=out.stride()[:3], out_dtype="bf16" if out.dtype == torch.bfloat16 else "f32")
     try:
         s = torch.cuda.current_stream(Q.device) if stream is None else stream
         with torch.cuda.device(Q.device):
@@ -151,7 +157,7 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
     return out
 
 
-def run_workload(w, Q, K, V, out=None):
+def run_workload(w, Q, K, V, out=None, out_dtype=None):
     """attention_forward with the parameters of a workloads.Workload."""
     return attention_forward(Q, K, V, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
-                             gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out)
+                             gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out, out_dtype=out_dtype)

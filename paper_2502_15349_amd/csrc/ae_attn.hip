@@ -80,8 +80,8 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown norm %d", (int)d->norm);
   if ((int)d->mask < 0 || (int)d->mask > AE_MASK_CAUSAL)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown mask %d", (int)d->mask);
-  if (d->out_dtype != AE_OUT_F32)
-    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: only fp32 output is implemented");
+  if (d->out_dtype != AE_OUT_F32 && d->out_dtype != AE_OUT_BF16)
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown out_dtype %d", (int)d->out_dtype);
   if (d->score_mod == AE_MOD_BIAS && !std::isfinite(d->bias))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_create: bias must be finite");
   if ((int64_t)d->B * d->H_kv > (1 << 24) || (int64_t)d->L_q > (1 << 28) || (int64_t)d->L_k > (1 << 28))
@@ -159,6 +159,7 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     p.b2 = bias;
   }
   p.neg_q = d->scale < 0.f ? 1 : 0;
+  p.out_bf16 = d->out_dtype == AE_OUT_BF16 ? 1 : 0;
   p.fold = (d->norm == AE_NORM_SIGMOID && std::fabs(p.b2) <= 64.f) ? 1 : 0;
   p.kfac = p.fold ? std::exp2(-p.b2) : 1.f;
   if (mod == ae::MOD_DECAY)
@@ -197,7 +198,7 @@ ae_status_t ae_attn_forward(const ae_attn_t* h, const void* Q, const void* K, co
   p.Q = static_cast<const __bf16*>(Q);
   p.K = static_cast<const __bf16*>(K);
   p.V = static_cast<const __bf16*>(V);
-  p.O = static_cast<float*>(O);
+  p.O = O;
   hipError_t e = h->kernel->launch(p, h->decay, h->grid, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_forward: launch failed: %s", hipGetErrorString(e));
   return AE_OK;

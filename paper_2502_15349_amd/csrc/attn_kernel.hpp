@@ -46,6 +46,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 enum : int { NORM_SOFTMAX = 0, NORM_SIGMOID = 1, NORM_ABSSUM = 2, NORM_ABS_OF_SUM = 3, NORM_NONE = 4 };
@@ -57,7 +58,7 @@ struct Params {
   const __bf16* Q;
   const __bf16* K;
   const __bf16* V;
-  float* O;
+  void* O;  // fp32, or bf16 if out_bf16
   int B, H_q, H_kv, L_q, L_k;
   int g;           // H_q / H_kv
   int n_qtiles;    // ceil(L_q / BLOCK_M)
@@ -67,6 +68,7 @@ struct Params {
   float c;         // |scale| * log2(e)  (softmax, sigmoid)  or |scale| (others)
   float b2;        // bias * log2(e)     (softmax, sigmoid)  or bias (others)
   int neg_q;       // scale < 0: the sign is moved onto Q (exact for bf16)
+  int out_bf16;    // O holds bf16 instead of fp32
   // sigmoid with a bias small enough for 2^(-b2) to be a normal number: Q is
   // multiplied by -scale*log2(e) when loaded (rounded to bf16 again), so that the
   // MFMA delivers the exponent itself and 1 + 2^(-b2) * 2^x is a single FMA
@@ -224,7 +226,16 @@ struct DmaMap {
 // s_waitcnt vmcnt(0) in front of the fragment reads -- which serialises every
 // step on the full latency of the copies just started.  Here the waits are
 // explicit instead (wait_dma_and_sync).
+// (The base pointer is passed through readfirstlane: under scalar register pressure the
+// compiler may have moved its arithmetic to the vector unit, and the instruction needs it
+// in scalar registers; for a value that already is scalar this is a plain copy.)
+__device__ __forceinline__ const void* uniform_ptr(const void* ptr) {
+  const uint64_t a = (uint64_t)(uintptr_t)ptr;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  return (const void*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ void dma16(const void* base_uniform, uint32_t byte_off, uint32_t lds_addr_uniform) {
+  base_uniform = uniform_ptr(base_uniform);
   asm volatile(
       "s_mov_b32 m0, %0\n\t"
       "s_nop 0\n\t"
@@ -238,6 +249,7 @@ __device__ __forceinline__ void dma16(const void* base_uniform, uint32_t byte_of
 // constant, added on the way into M0.
 template <int LDS_IMM>
 __device__ __forceinline__ void dma16_at(const void* base_uniform, uint32_t byte_off, uint32_t lds_base_uniform) {
+  base_uniform = uniform_ptr(base_uniform);
   asm volatile(
       "s_add_i32 m0, %0, %3\n\t"
       "s_nop 0\n\t"
@@ -662,7 +674,8 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   const __bf16* qbase = p.Q + b * p.qs[0] + hq * p.qs[1];
   const __bf16* kbase = p.K + b * p.ks[0] + hkv * p.ks[1];
   const __bf16* vbase = p.V + b * p.vs[0] + hkv * p.vs[1];
-  float* obase = p.O + b * p.os[0] + hq * p.os[1];
+  // byte address of the head's first output row (O holds 4- or 2-byte elements)
+  char* obase = static_cast<char*>(p.O) + (b * p.os[0] + hq * p.os[1]) * (p.out_bf16 ? 2 : 4);
 
   RowState<C> st;
   st.m = -INFINITY;
@@ -954,8 +967,17 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     for (int k = 0; k < 32 * CPRO / 64; ++k) {
       const int row = k * (64 / CPRO) + lane / CPRO, pc = lane % CPRO;
       const f32x4 v = lds_read16(obuf + row * (OC * 4) + ((pc ^ (row & 15)) * 16));
-      if (iw0 + row < p.L_q)
-        *reinterpret_cast<f32x4*>(obase + (int64_t)(iw0 + row) * p.os[2] + pass * OC + pc * 4) = v;
+      if (iw0 + row < p.L_q) {
+        const int64_t e = (int64_t)(iw0 + row) * p.os[2] + pass * OC + pc * 4;  // element offset in the head
+        if (p.out_bf16) {
+          bf16x4 h;
+#pragma unroll
+          for (int k4 = 0; k4 < 4; ++k4) h[k4] = (__bf16)v[k4];
+          *reinterpret_cast<bf16x4*>(obase + e * 2) = h;
+        } else {
+          *reinterpret_cast<f32x4*>(obase + e * 4) = v;
+        }
+      }
     }
   }
 }

@@ -222,6 +222,28 @@ def test_strided_inputs_and_output(A, dims):
     assert (out[..., w.D_v:] == 7.0).all()   # padding untouched
 
 
+@pytest.mark.parametrize("dims", DIMS, ids=lambda d: f"d{d[0]}_{d[1]}")
+@pytest.mark.parametrize("norm,mod", [("softmax", "none"), ("abssum", "head_decay")])
+def test_bf16_output(A, dims, norm, mod):
+    """AE_OUT_BF16: the fp32 rows rounded to bf16 when stored.  Bound: the fp32 path's bound plus
+    one bf16 rounding of the result (half an ulp = 2^-9 relative; 2^-8 allowed)."""
+    w = Workload("bf16out", 15, 2, 4, 2, 300, 333, dims[0], dims[1], mask="causal", norm=norm, score_mod=mod,
+                 decay=(mod == "head_decay"))
+    Q, K, V = make_inputs(w)
+    dev = torch.device("cuda:0")
+    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert O.dtype == torch.bfloat16
+    got = O.float().cpu().double().numpy()
+    ref = oracle_run(w, Q, K, V)
+    err = np.abs(got - ref)
+    assert (err <= MAX_ABS + np.abs(ref) * 2.0 ** -8).all(), err.max()
+    assert err.mean() <= MEAN_ABS + np.abs(ref).mean() * 2.0 ** -8
+    # and it is exactly the fp32 result rounded to nearest even
+    O32 = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev))
+    assert torch.equal(O32.to(torch.bfloat16), O)
+
+
 def test_negative_scale_and_large_scores(A):
     w = Workload("neg", 14, 1, 2, 2, 150, 150, 64, 64, mask="causal", scale=-0.125)
     Q, K, V = make_inputs(w)
