@@ -8,5 +8,6 @@ from .attention_oracle import (  # noqa: F401
     attention,
     attention_head,
     brute,
+    row_stats_head,
     weights_head,
 )

@@ -72,13 +72,9 @@ def _visible(rows, L_q, L_k, mask):
     return j <= (rows[:, None] + off)
 
 
-def weights_head(q, k, *, scale, score_mod="none", bias=0.0, gamma_h=None,
-                 norm="softmax", mask="none", rows=None):
-    """P[rows, :] for one head: q [L_q, D_qk], k [L_k, D_qk] -> [len(rows), L_k].
-
-    `rows` selects query rows (default all); each row is independent, so a
-    subset is the same definition evaluated on fewer rows.
-    """
+def _modified_scores(q, k, *, scale, score_mod, bias, gamma_h, mask, rows):
+    """(S'[rows, :], visibility[rows, :]) for one head: relevance scoring and
+    the elementwise modification, before any row-wise normalization."""
     q = _as_f64(q)
     k = _as_f64(k)
     L_q, L_k = q.shape[0], k.shape[0]
@@ -103,7 +99,18 @@ def weights_head(q, k, *, scale, score_mod="none", bias=0.0, gamma_h=None,
         s = np.maximum(s, 0.0)
     else:
         raise ValueError(f"unknown score_mod {score_mod!r}")
+    return s, vis
 
+
+def weights_head(q, k, *, scale, score_mod="none", bias=0.0, gamma_h=None,
+                 norm="softmax", mask="none", rows=None):
+    """P[rows, :] for one head: q [L_q, D_qk], k [L_k, D_qk] -> [len(rows), L_k].
+
+    `rows` selects query rows (default all); each row is independent, so a
+    subset is the same definition evaluated on fewer rows.
+    """
+    s, vis = _modified_scores(q, k, scale=scale, score_mod=score_mod, bias=bias,
+                              gamma_h=gamma_h, mask=mask, rows=rows)
     # row-wise normalization; masked entries take no part
     if norm == "softmax":
         sm = np.where(vis, s, -np.inf)
@@ -127,6 +134,32 @@ def weights_head(q, k, *, scale, score_mod="none", bias=0.0, gamma_h=None,
     else:
         raise ValueError(f"unknown norm {norm!r}")
     return p
+
+
+def row_stats_head(q, k, *, scale, score_mod="none", bias=0.0, gamma_h=None,
+                   norm="softmax", mask="none", rows=None):
+    """The final result of the row reduction that the normalization keeps per
+    query row (Section 4.1, online row-norm interface: the final row scales),
+    over the visible keys of each row:
+      softmax     ln sum_j exp(S'_ij)   (-inf for a row with no visible key);
+      abssum      sum_j |S'_ij|         (before the clamp at 1);
+      abs_of_sum  sum_j S'_ij           (signed, before |.| and the clamp).
+    The running maximum and running sum of the online form are not unique
+    (they depend on the block order); their combination above is."""
+    s, vis = _modified_scores(q, k, scale=scale, score_mod=score_mod, bias=bias,
+                              gamma_h=gamma_h, mask=mask, rows=rows)
+    if norm == "softmax":
+        sm = np.where(vis, s, -np.inf)
+        m = sm.max(axis=1)
+        safe = np.where(np.isfinite(m), m, 0.0)
+        tot = np.where(vis, np.exp(sm - safe[:, None]), 0.0).sum(axis=1)
+        with np.errstate(divide="ignore"):
+            return np.where(tot > 0, safe + np.log(tot), -np.inf)
+    if norm == "abssum":
+        return np.abs(np.where(vis, s, 0.0)).sum(axis=1)
+    if norm == "abs_of_sum":
+        return np.where(vis, s, 0.0).sum(axis=1)
+    raise ValueError(f"normalization {norm!r} keeps no row statistic")
 
 
 def attention_head(q, k, v, *, scale, score_mod="none", bias=0.0, gamma_h=None,

@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import attention, attention_head, brute, weights_head
+from oracle import attention, attention_head, brute, row_stats_head, weights_head
 
 RNG = np.random.default_rng(20250215)
 
@@ -330,3 +330,83 @@ def test_pins_catch_planted_mistakes():
         attention_head(q, k, v, scale=1.0, mask="causal"),
     ):
         assert np.abs(bad - ref).max() > 1e-3
+
+
+# ---- the row statistic of the normalization (final row scales) -----------------------------------
+
+def _scores_by_loops(q, k, scale, bias, gamma, off):
+    """S' element by element (plain Python), None where the causal mask hides the pair."""
+    L_q, L_k = q.shape[0], k.shape[0]
+    out = [[None] * L_k for _ in range(L_q)]
+    for i in range(L_q):
+        for j in range(L_k):
+            if off is not None and j > i + off:
+                continue
+            s = sum(float(q[i, d]) * float(k[j, d]) for d in range(q.shape[1])) * scale + bias
+            if gamma is not None:
+                s *= gamma ** (i + off - j)
+            out[i][j] = s
+    return out
+
+
+def test_row_stats_softmax_closed_forms():
+    k = rnd(9, 8)
+    # Q = 0: every visible score is the bias, so lse = bias + ln(number of visible keys)
+    q0 = np.zeros((5, 8))
+    got = row_stats_head(q0, k, scale=0.3, score_mod="bias", bias=0.7, norm="softmax")
+    assert np.allclose(got, 0.7 + math.log(9), rtol=0, atol=1e-13)
+    got = row_stats_head(q0, k, scale=0.3, norm="softmax", mask="causal")       # off = 4: row i sees i + 5 keys
+    assert np.allclose(got, [math.log(i + 5) for i in range(5)], rtol=0, atol=1e-13)
+    # one key: lse is the modified score itself
+    q = rnd(6, 8)
+    k1 = rnd(1, 8)
+    got = row_stats_head(q, k1, scale=0.25, score_mod="bias", bias=-1.5, norm="softmax")
+    assert np.allclose(got, (q @ k1.T)[:, 0] * 0.25 - 1.5, rtol=0, atol=1e-13)
+    # a constant added to every score moves lse by that constant
+    a = row_stats_head(q, k, scale=0.25, norm="softmax", mask="causal")
+    b = row_stats_head(q, k, scale=0.25, score_mod="bias", bias=3.25, norm="softmax", mask="causal")
+    assert np.allclose(b - a, 3.25, rtol=0, atol=1e-12)
+    # rows with no visible key (L_q > L_k, bottom-right alignment)
+    got = row_stats_head(rnd(6, 8), rnd(2, 8), scale=1.0, norm="softmax", mask="causal")
+    assert np.isneginf(got[:4]).all() and np.isfinite(got[4:]).all()
+
+
+def test_row_stats_softmax_against_library_logsumexp_and_weights():
+    q, k = rnd(7, 16), rnd(11, 16)
+    for mask, off in (("none", None), ("causal", 4)):
+        sc = _scores_by_loops(q, k, 0.2, 0.0, None, off)
+        got = row_stats_head(q, k, scale=0.2, norm="softmax", mask=mask)
+        # torch.logsumexp over the visible scores computed element by element above
+        lib = [float(torch.logsumexp(torch.tensor([x for x in row if x is not None], dtype=torch.float64), 0))
+               for row in sc]
+        assert np.allclose(got, lib, rtol=0, atol=1e-12)
+        # and it is the normaliser of the (separately pinned) weights: P_ij = exp(S'_ij - lse_i)
+        P = weights_head(q, k, scale=0.2, norm="softmax", mask=mask)
+        for i, row in enumerate(sc):
+            for j, x in enumerate(row):
+                assert abs(P[i, j] - (0.0 if x is None else math.exp(x - got[i]))) < 1e-13
+    # huge scores do not overflow
+    big = row_stats_head(q * 300, k * 300, scale=1.0, norm="softmax")
+    assert np.isfinite(big).all()
+
+
+def test_row_stats_abs_sums():
+    q, k = rnd(6, 8), rnd(10, 8)
+    gamma = 0.9
+    sc = _scores_by_loops(q, k, 0.5, 0.0, gamma, 4)
+    a = row_stats_head(q, k, scale=0.5, score_mod="head_decay", gamma_h=gamma, norm="abssum", mask="causal")
+    s = row_stats_head(q, k, scale=0.5, score_mod="head_decay", gamma_h=gamma, norm="abs_of_sum", mask="causal")
+    assert np.allclose(a, [sum(abs(x) for x in row if x is not None) for row in sc], rtol=1e-13, atol=0)
+    assert np.allclose(s, [sum(x for x in row if x is not None) for row in sc], rtol=0, atol=1e-13)
+    # the weights are the scores over max(statistic, 1): sum_j |P_ij| = a / max(a, 1)
+    P = weights_head(q, k, scale=0.5, score_mod="head_decay", gamma_h=gamma, norm="abssum", mask="causal")
+    assert np.allclose(np.abs(P).sum(axis=1), a / np.maximum(a, 1.0), rtol=1e-13, atol=0)
+    # non-negative scores: the two statistics coincide
+    qp, kp = np.abs(q), np.abs(k)
+    a = row_stats_head(qp, kp, scale=0.5, norm="abssum")
+    s = row_stats_head(qp, kp, scale=0.5, norm="abs_of_sum")
+    assert np.allclose(a, s, rtol=1e-14, atol=0)
+    # norms without a row reduction keep nothing
+    for norm in ("sigmoid", "none"):
+        with pytest.raises(ValueError):
+            row_stats_head(q, k, scale=1.0, norm=norm)
