@@ -113,6 +113,20 @@ ae_status_t ae_attn_create(const ae_attn_desc_t *desc, ae_attn_t **out);
 ae_status_t ae_attn_forward(const ae_attn_t *h, const void *Q, const void *K,
                             const void *V, void *O, void *stream);
 
+/* ae_attn_forward that also writes, per query row, the final result of the row
+ * reduction its normalization keeps (the online row-norm interface's final row
+ * scales, Section 4.1) -- what a backward pass recomputes the weights from:
+ *   AE_NORM_SOFTMAX     ln sum_j exp(x_ij)  over the visible keys (-inf if none),
+ *   AE_NORM_ABSSUM      sum_j |x_ij|        (before the clamp at 1),
+ *   AE_NORM_ABS_OF_SUM  sum_j x_ij          (signed, before |.| and the clamp),
+ * with x the modified scores.  stats: device pointer, fp32 [B, H_q, L_q]
+ * contiguous, 4-byte aligned, not aliasing the other buffers.  Same launch, same
+ * ownership and error rules as ae_attn_forward; AE_ERR_UNSUPPORTED for
+ * normalizations without a row reduction (SIGMOID, NONE).                      */
+ae_status_t ae_attn_forward_stats(const ae_attn_t *h, const void *Q,
+                                  const void *K, const void *V, void *O,
+                                  void *stats, void *stream);
+
 /* Frees the handle.  NULL is a no-op.                                         */
 ae_status_t ae_attn_destroy(ae_attn_t *h);
 

@@ -41,6 +41,8 @@ _lib.ae_attn_create.argtypes = [C.POINTER(ae_attn_desc_t), C.POINTER(C.c_void_p)
 _lib.ae_attn_create.restype = C.c_int
 _lib.ae_attn_forward.argtypes = [C.c_void_p] * 6
 _lib.ae_attn_forward.restype = C.c_int
+_lib.ae_attn_forward_stats.argtypes = [C.c_void_p] * 7
+_lib.ae_attn_forward_stats.restype = C.c_int
 _lib.ae_attn_destroy.argtypes = [C.c_void_p]
 _lib.ae_attn_destroy.restype = C.c_int
 _lib.ae_attn_query.argtypes = [C.c_void_p] + [C.POINTER(C.c_int32)] * 5
@@ -98,6 +100,11 @@ def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int
     return h.value
 
 
+def ae_attn_forward_stats(handle: int, Q: int, K: int, V: int, O: int, stats: int, stream: int = 0) -> None:
+    """ae_attn_forward that also writes the row statistic (fp32 [B, H_q, L_q]) to `stats`."""
+    _check(_lib.ae_attn_forward_stats(handle, Q, K, V, O, stats, stream))
+
+
 def ae_attn_forward(handle: int, Q: int, K: int, V: int, O: int, stream: int = 0) -> None:
     """Q, K, V, O are device addresses (tensor.data_ptr()); stream is a raw hipStream_t."""
     _check(_lib.ae_attn_forward(handle, Q, K, V, O, stream))
@@ -125,10 +132,11 @@ def ae_attn_query(handle: int) -> dict:
 
 # ---- convenience for torch callers (still marshalling only) -------------------
 def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
-                      mask="none", out=None, stream=None, out_dtype=None):
+                      mask="none", out=None, stream=None, out_dtype=None, stats=None):
     """Runs the HIP operator on CUDA/HIP bf16 tensors laid out [B, H, L, D]
     (last dim contiguous) and returns O [B, H_q, L_q, D_v]: fp32, or bf16 if `out` is a
-    bf16 tensor or out_dtype is torch.bfloat16."""
+    bf16 tensor or out_dtype is torch.bfloat16.  stats: optional contiguous fp32 device
+    tensor [B, H_q, L_q] that receives the row statistic of the normalization."""
     import torch
 
     if not (Q.is_cuda and K.is_cuda and V.is_cuda):
@@ -151,13 +159,19 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
     try:
         s = torch.cuda.current_stream(Q.device) if stream is None else stream
         with torch.cuda.device(Q.device):
-            ae_attn_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), s.cuda_stream)
+            if stats is None:
+                ae_attn_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), s.cuda_stream)
+            else:
+                if stats.dtype != torch.float32 or tuple(stats.shape) != (B, H_q, L_q) or not stats.is_contiguous():
+                    raise ValueError("stats must be a contiguous fp32 tensor [B, H_q, L_q]")
+                ae_attn_forward_stats(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), stats.data_ptr(),
+                                      s.cuda_stream)
     finally:
         ae_attn_destroy(h)
     return out
 
 
-def run_workload(w, Q, K, V, out=None, out_dtype=None):
+def run_workload(w, Q, K, V, out=None, out_dtype=None, stats=None):
     """attention_forward with the parameters of a workloads.Workload."""
     return attention_forward(Q, K, V, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
-                             gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out, out_dtype=out_dtype)
+                             gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out, out_dtype=out_dtype, stats=stats)

@@ -188,7 +188,8 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   return AE_OK;
 }
 
-ae_status_t ae_attn_forward(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, void* stream) {
+static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, float* stats,
+                                void* stream) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null handle");
   if (!Q || !K || !V || !O) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null device pointer");
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
@@ -199,9 +200,26 @@ ae_status_t ae_attn_forward(const ae_attn_t* h, const void* Q, const void* K, co
   p.K = static_cast<const __bf16*>(K);
   p.V = static_cast<const __bf16*>(V);
   p.O = O;
+  p.stats = stats;
   hipError_t e = h->kernel->launch(p, h->decay, h->grid, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_forward: launch failed: %s", hipGetErrorString(e));
   return AE_OK;
+}
+
+ae_status_t ae_attn_forward(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, void* stream) {
+  return forward_impl(h, Q, K, V, O, nullptr, stream);
+}
+
+ae_status_t ae_attn_forward_stats(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, void* stats,
+                                  void* stream) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_stats: null handle");
+  if (!stats || ((uintptr_t)stats & 3)) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_stats: stats must be a 4-byte aligned device pointer");
+  if (stats == O || stats == Q || stats == K || stats == V)
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_stats: stats aliases another buffer");
+  const int norm = h->kernel->norm;
+  if (norm != ae::NORM_SOFTMAX && norm != ae::NORM_ABSSUM && norm != ae::NORM_ABS_OF_SUM)
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_forward_stats: this normalization keeps no row statistic");
+  return forward_impl(h, Q, K, V, O, static_cast<float*>(stats), stream);
 }
 
 ae_status_t ae_attn_destroy(ae_attn_t* h) {

@@ -59,6 +59,7 @@ struct Params {
   const __bf16* K;
   const __bf16* V;
   void* O;  // fp32, or bf16 if out_bf16
+  float* stats;  // optional [B, H_q, L_q]: final row statistic of the normalization (null: not written)
   int B, H_q, H_kv, L_q, L_k;
   int g;           // H_q / H_kv
   int n_qtiles;    // ceil(L_q / BLOCK_M)
@@ -935,13 +936,19 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
 
   // ---- online_epilogue + store ------------------------------------------------
   float inv = 1.f;
-  if constexpr (C::NORM == NORM_SOFTMAX) {
+  if constexpr (C::NORM == NORM_SOFTMAX || C::NORM == NORM_ABSSUM || C::NORM == NORM_ABS_OF_SUM) {
     const float l = sum_halves(st.l);
-    inv = l > 0.f ? 1.f / l : 0.f;
-  } else if constexpr (C::NORM == NORM_ABSSUM) {
-    inv = 1.f / fmaxf(sum_halves(st.l), 1.f);
-  } else if constexpr (C::NORM == NORM_ABS_OF_SUM) {
-    inv = 1.f / fmaxf(fabsf(sum_halves(st.l)), 1.f);
+    float stat = l;  // abs-sum family: the sum itself
+    if constexpr (C::NORM == NORM_SOFTMAX) {
+      inv = l > 0.f ? 1.f / l : 0.f;
+      // weights are 2^(x*log2e - m): sum_j exp(x_j) = 2^m * l
+      stat = l > 0.f ? (st.m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : -INFINITY;
+    } else if constexpr (C::NORM == NORM_ABSSUM) {
+      inv = 1.f / fmaxf(l, 1.f);
+    } else {
+      inv = 1.f / fmaxf(fabsf(l), 1.f);
+    }
+    if (p.stats != nullptr && half == 0 && i < p.L_q) p.stats[((int64_t)b * p.H_q + hq) * p.L_q + i] = stat;
   }
   // A lane holds 4-column pieces of one output row, 32 bytes apart from its
   // partner's: stored directly, every instruction would touch 32 rows with 32

@@ -80,6 +80,37 @@ def test_forward_rejects_bad_pointers_without_launching():
         A.ae_attn_destroy(h)
 
 
+def test_forward_stats_rejects_bad_arguments_without_launching():
+    from paper_2502_15349_amd import ae_attn as A
+    h = A.ae_attn_create(**_ok_desc())
+    try:
+        for args in ((256, 512, 768, 1024, 0), (256, 512, 768, 1024, 2048 + 2), (256, 512, 768, 1024, 1024),
+                     (0, 512, 768, 1024, 2048)):
+            with pytest.raises(A.AeAttnError) as ei:
+                A.ae_attn_forward_stats(h, *args)
+            assert ei.value.status == A.AE_ERR_INVALID_ARG
+    finally:
+        A.ae_attn_destroy(h)
+    # a normalization without a row reduction keeps no statistic
+    d = _ok_desc()
+    d.update(norm="sigmoid")
+    h = A.ae_attn_create(**d)
+    try:
+        with pytest.raises(A.AeAttnError) as ei:
+            A.ae_attn_forward_stats(h, 256, 512, 768, 1024, 2048)
+        assert ei.value.status == A.AE_ERR_UNSUPPORTED
+    finally:
+        A.ae_attn_destroy(h)
+
+
+def test_bf16_output_accepted_and_unknown_dtype_rejected():
+    from paper_2502_15349_amd import ae_attn as A
+    A.ae_attn_destroy(A.ae_attn_create(**_ok_desc(), out_dtype="bf16"))
+    with pytest.raises(A.AeAttnError) as ei:
+        A.ae_attn_create(**_ok_desc(), out_dtype=7)
+    assert ei.value.status == A.AE_ERR_UNSUPPORTED
+
+
 def test_padded_strides_accepted():
     from paper_2502_15349_amd import ae_attn as A
     h = A.ae_attn_create(**_ok_desc(), q_stride=(100 * 4 * 136, 100 * 136, 136))

@@ -244,6 +244,52 @@ def test_bf16_output(A, dims, norm, mod):
     assert torch.equal(O32.to(torch.bfloat16), O)
 
 
+@pytest.mark.parametrize("dims", DIMS, ids=lambda d: f"d{d[0]}_{d[1]}")
+@pytest.mark.parametrize("norm,mod,mask", [("softmax", "none", "causal"), ("softmax", "bias", "none"),
+                                           ("abssum", "head_decay", "causal"), ("abs_of_sum", "none", "causal")])
+def test_row_statistics(A, dims, norm, mod, mask):
+    """ae_attn_forward_stats: the row statistic against the oracle's (fp32 sums of fp32 terms: 1e-3
+    absolute on ln-sum-exp, 1e-4 relative on the abs sums), and O unchanged by asking for it."""
+    from oracle import row_stats_head
+    w = Workload("stats", 16, 2, 4, 2, 300, 333 if mask == "causal" else 280, dims[0], dims[1], mask=mask, norm=norm,
+                 score_mod=mod, bias=0.75, decay=(mod == "head_decay"))
+    Q, K, V = make_inputs(w)
+    dev = torch.device("cuda:0")
+    st = torch.full((w.B, w.H_q, w.L_q), 123.0, dtype=torch.float32, device=dev)
+    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), stats=st)
+    O0 = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev))
+    torch.cuda.synchronize()
+    assert torch.equal(O, O0)
+    got = st.cpu().double().numpy()
+    g = w.H_q // w.H_kv
+    gam = w.gamma()
+    for b in range(w.B):
+        for h in range(w.H_q):
+            ref = row_stats_head(Q[b, h], K[b, h // g], scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
+                                 gamma_h=None if gam is None else gam[h], norm=w.norm, mask=w.mask)
+            if norm == "softmax":
+                assert np.abs(got[b, h] - ref).max() <= 1e-3, (b, h, np.abs(got[b, h] - ref).max())
+            else:
+                assert np.allclose(got[b, h], ref, rtol=1e-4, atol=1e-4), (b, h)
+
+
+def test_row_statistics_rows_without_keys(A):
+    from oracle import row_stats_head
+    w = Workload("stats0", 17, 1, 2, 2, 100, 37, 64, 64, mask="causal")   # rows 0..62 see no key
+    Q, K, V = make_inputs(w)
+    dev = torch.device("cuda:0")
+    st = torch.zeros((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev)
+    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), stats=st)
+    torch.cuda.synchronize()
+    got = st.cpu().double().numpy()
+    for h in range(w.H_q):
+        ref = row_stats_head(Q[0, h], K[0, h], scale=w.scale_value, norm="softmax", mask="causal")
+        assert (np.isneginf(got[0, h]) == np.isneginf(ref)).all()
+        fin = np.isfinite(ref)
+        assert np.abs(got[0, h][fin] - ref[fin]).max() <= 1e-3
+    assert (O[:, :, :63] == 0).all()
+
+
 def test_negative_scale_and_large_scores(A):
     w = Workload("neg", 14, 1, 2, 2, 150, 150, 64, 64, mask="causal", scale=-0.125)
     Q, K, V = make_inputs(w)
