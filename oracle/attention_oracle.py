@@ -29,7 +29,8 @@ Readings taken where the paper is silent (all listed in the design notes):
     row reduction, for every normalization;
   * a row with no visible key yields a zero output row;
   * causal alignment for L_q != L_k is bottom-right: key j is visible to
-    query i iff j <= i + (L_k - L_q);
+    query i iff j <= i + (L_k - L_q); a sliding window of W keeps, of those,
+    the W keys nearest the diagonal: i + (L_k - L_q) - W < j;
   * grouped-query heads are contiguous groups: h_kv = h_q // (H_q // H_kv);
   * the decay mask entry is gamma[h_q] ** (i + (L_k - L_q) - j) on visible
     entries;
@@ -49,7 +50,7 @@ import numpy as np
 
 SCORE_MODS = ("none", "bias", "head_decay", "relu")
 NORMS = ("softmax", "sigmoid", "abssum", "abs_of_sum", "none")
-MASKS = ("none", "causal")
+MASKS = ("none", "causal", "sliding_window")  # the last one is passed as ("sliding_window", W)
 
 
 def _as_f64(x):
@@ -65,11 +66,16 @@ def _visible(rows, L_q, L_k, mask):
     annotated as a mask; causal = attend to prior tokens only)."""
     if mask == "none":
         return np.ones((len(rows), L_k), dtype=bool)
-    if mask != "causal":
-        raise ValueError(f"unknown mask {mask!r}")
     off = L_k - L_q
     j = np.arange(L_k)[None, :]
-    return j <= (rows[:, None] + off)
+    if mask == "causal":
+        return j <= (rows[:, None] + off)
+    # sliding window (Section 2, "Efficiency Innovations": the interaction is limited
+    # to a local window): the W most recent keys up to and including the causal one
+    if isinstance(mask, tuple) and len(mask) == 2 and mask[0] == "sliding_window" and int(mask[1]) >= 1:
+        d = rows[:, None] + off - j
+        return (d >= 0) & (d < int(mask[1]))
+    raise ValueError(f"unknown mask {mask!r}")
 
 
 def _modified_scores(q, k, *, scale, score_mod, bias, gamma_h, mask, rows):
@@ -211,6 +217,9 @@ def brute(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
                 w = []
                 for j in range(L_k):
                     if mask == "causal" and j > i + off:
+                        w.append(None)
+                        continue
+                    if isinstance(mask, tuple) and not (i + off - mask[1] < j <= i + off):
                         w.append(None)
                         continue
                     s = 0.0

@@ -410,3 +410,36 @@ def test_row_stats_abs_sums():
     for norm in ("sigmoid", "none"):
         with pytest.raises(ValueError):
             row_stats_head(q, k, scale=1.0, norm=norm)
+
+
+# ---- sliding window mask -------------------------------------------------------------------------
+
+def test_sliding_window_limits():
+    q, k, v = rnd(9, 8), rnd(12, 8), rnd(12, 5)
+    kw = dict(scale=0.4, norm="softmax")
+    # a window that reaches past the first key is the causal mask
+    a = attention_head(q, k, v, mask=("sliding_window", 12), **kw)
+    b = attention_head(q, k, v, mask="causal", **kw)
+    assert np.array_equal(a, b)
+    # a window of one key: the output row is the value row on the diagonal (off = 3)
+    a = attention_head(q, k, v, mask=("sliding_window", 1), **kw)
+    assert np.allclose(a, v[3:12], rtol=0, atol=1e-15)
+    # Q = 0: mean of the last W visible value rows
+    W = 4
+    a = attention_head(np.zeros((9, 8)), k, v, mask=("sliding_window", W), **kw)
+    for i in range(9):
+        lo = max(0, i + 3 - W + 1)
+        assert np.allclose(a[i], v[lo:i + 4].mean(axis=0), rtol=0, atol=1e-14)
+    # row i equals unmasked attention over exactly its window of keys
+    for i in range(9):
+        lo = max(0, i + 3 - W + 1)
+        ref = attention_head(q[i:i + 1], k[lo:i + 4], v[lo:i + 4], mask="none", **kw)
+        got = attention_head(q, k, v, mask=("sliding_window", W), rows=[i], **kw)
+        assert np.allclose(got, ref, rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("norm,score_mod", [("softmax", "none"), ("sigmoid", "bias"), ("abssum", "head_decay"), ("none", "relu")])
+def test_sliding_window_equals_brute(norm, score_mod):
+    Q, K, V = rnd(1, 2, 7, 3), rnd(1, 1, 10, 3), rnd(1, 1, 10, 4)
+    kw = dict(scale=0.7, score_mod=score_mod, bias=-0.3, gamma=[0.9, 0.8], norm=norm, mask=("sliding_window", 3))
+    np.testing.assert_allclose(attention(Q, K, V, **kw), brute(Q, K, V, **kw), rtol=1e-12, atol=1e-13)
