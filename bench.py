@@ -39,7 +39,7 @@ def time_gpu(A, torch, w, Q, K, V, steps, warmup, settle_s=0.4, out_bf16=False):
     O = torch.empty((w.B, w.H_q, w.L_q, w.D_v), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=Q.device)
     h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
                          scale=w.scale_value, score_mod=w.score_mod, bias=w.bias, gamma=w.gamma(),
-                         norm=w.norm, mask=w.mask, out_dtype="bf16" if out_bf16 else "f32")
+                         norm=w.norm, mask=w.mask, out_dtype="bf16" if out_bf16 else "f32", window=w.window)
     info = A.ae_attn_query(h)
     stream = torch.cuda.current_stream()
     args = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), stream.cuda_stream)
@@ -84,7 +84,7 @@ def parity_sample(w, Q, K, V, O, n_rows=48, scaled=False):
     gam = w.gamma()
     ref = attention_head(Q[b, h].cpu(), K[b, h // g].cpu(), V[b, h // g].cpu(), scale=w.scale_value,
                          score_mod=w.score_mod, bias=w.bias, gamma_h=None if gam is None else gam[h],
-                         norm=w.norm, mask=w.mask, rows=rows)
+                         norm=w.norm, mask=w.oracle_mask(), rows=rows)
     got = O[b, h].cpu().double().numpy()[rows]
     err = np.abs(got - ref)
     if scaled:
@@ -105,7 +105,7 @@ def cpu_baseline(w, Q, K, V, budget_s=15.0):
     heads = [(b, h) for b in range(w.B) for h in range(w.H_q)]
     for (b, h) in heads:
         attention_head(Q[b, h], K[b, h // g], V[b, h // g], scale=w.scale_value, score_mod=w.score_mod,
-                       bias=w.bias, gamma_h=None if gam is None else gam[h], norm=w.norm, mask=w.mask)
+                       bias=w.bias, gamma_h=None if gam is None else gam[h], norm=w.norm, mask=w.oracle_mask())
         done += 1
         if time.perf_counter() - t0 > budget_s:
             break

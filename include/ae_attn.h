@@ -60,7 +60,9 @@ typedef enum {
  * reduction.  A query row with no visible key produces a zero output row.    */
 typedef enum {
   AE_MASK_NONE = 0,
-  AE_MASK_CAUSAL = 1 /* key j visible to query i iff j <= i + (L_k - L_q)      */
+  AE_MASK_CAUSAL = 1, /* key j visible to query i iff j <= i + (L_k - L_q)     */
+  AE_MASK_SLIDING_WINDOW = 2 /* causal, and only the `window` nearest keys:
+                                i + (L_k - L_q) - window < j <= i + (L_k - L_q)  */
 } ae_mask_t;
 
 /* Element type of O.  The kernel computes the normalised rows in fp32 either
@@ -91,6 +93,8 @@ typedef struct {
   ae_mask_t mask;
   float scale;         /* finite and non-zero; multiplies the scores            */
   ae_out_dtype_t out_dtype;
+  int32_t window;      /* keys per query, >= 1; read only by
+                          AE_MASK_SLIDING_WINDOW                                */
   int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3];
 } ae_attn_desc_t;
 
@@ -99,6 +103,7 @@ typedef struct {
  * device.  Supported head dims (D_qk/D_v): 64/64, 128/128, 128/256, 192/128.
  * Supported (score_mod, norm) pairs: NONE or BIAS with every norm;
  * HEAD_DECAY with ABSSUM, ABS_OF_SUM or NONE (CAUSAL mask only); RELU with NONE.
+ * AE_MASK_SLIDING_WINDOW: score_mod NONE or BIAS with SOFTMAX, SIGMOID or NONE.
  * Errors: AE_ERR_INVALID_ARG, AE_ERR_UNSUPPORTED, AE_ERR_NOMEM; *out is set
  * to NULL on error.                                                           */
 ae_status_t ae_attn_create(const ae_attn_desc_t *desc, ae_attn_t **out);

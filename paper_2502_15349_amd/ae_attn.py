@@ -22,7 +22,7 @@ _lib = C.CDLL(_LIB_PATH)
 AE_OK, AE_ERR_INVALID_ARG, AE_ERR_UNSUPPORTED, AE_ERR_HIP, AE_ERR_NOMEM = range(5)
 SCORE_MODS = {"none": 0, "bias": 1, "head_decay": 2, "relu": 3}
 NORMS = {"softmax": 0, "sigmoid": 1, "abssum": 2, "abs_of_sum": 3, "none": 4}
-MASKS = {"none": 0, "causal": 1}
+MASKS = {"none": 0, "causal": 1, "sliding_window": 2}
 OUT_DTYPES = {"f32": 0, "bf16": 1}
 
 
@@ -32,6 +32,7 @@ class ae_attn_desc_t(C.Structure):
         ("L_k", C.c_int32), ("D_qk", C.c_int32), ("D_v", C.c_int32),
         ("score_mod", C.c_int), ("bias", C.c_float), ("gamma", C.POINTER(C.c_float)),
         ("norm", C.c_int), ("mask", C.c_int), ("scale", C.c_float), ("out_dtype", C.c_int),
+        ("window", C.c_int32),
         ("q_stride", C.c_int64 * 3), ("k_stride", C.c_int64 * 3),
         ("v_stride", C.c_int64 * 3), ("o_stride", C.c_int64 * 3),
     ]
@@ -80,7 +81,7 @@ def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int
                    scale: float, score_mod="none", bias: float = 0.0,
                    gamma: Optional[Sequence[float]] = None, norm="softmax", mask="none",
                    q_stride=(0, 0, 0), k_stride=(0, 0, 0), v_stride=(0, 0, 0), o_stride=(0, 0, 0),
-                   out_dtype="f32") -> int:
+                   out_dtype="f32", window: int = 0) -> int:
     """Returns an opaque handle (int).  Enum arguments accept names or raw ints."""
     d = ae_attn_desc_t()
     d.B, d.H_q, d.H_kv, d.L_q, d.L_k, d.D_qk, d.D_v = B, H_q, H_kv, L_q, L_k, D_qk, D_v
@@ -89,6 +90,7 @@ def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int
     d.mask = MASKS[mask] if isinstance(mask, str) else int(mask)
     d.bias, d.scale = float(bias), float(scale)
     d.out_dtype = OUT_DTYPES[out_dtype] if isinstance(out_dtype, str) else int(out_dtype)
+    d.window = int(window)
     keep = None
     if gamma is not None:
         keep = (C.c_float * len(gamma))(*[float(x) for x in gamma])
@@ -132,11 +134,12 @@ def ae_attn_query(handle: int) -> dict:
 
 # ---- convenience for torch callers (still marshalling only) -------------------
 def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
-                      mask="none", out=None, stream=None, out_dtype=None, stats=None):
+                      mask="none", out=None, stream=None, out_dtype=None, stats=None, window=0):
     """Runs the HIP operator on CUDA/HIP bf16 tensors laid out [B, H, L, D]
     (last dim contiguous) and returns O [B, H_q, L_q, D_v]: fp32, or bf16 if `out` is a
     bf16 tensor or out_dtype is torch.bfloat16.  stats: optional contiguous fp32 device
-    tensor [B, H_q, L_q] that receives the row statistic of the normalization."""
+    tensor [B, H_q, L_q] that receives the row statistic of the normalization.  window: keys
+    per query for mask="sliding_window"."""
     import torch
 
     if not (Q.is_cuda and K.is_cuda and V.is_cuda):
@@ -155,7 +158,8 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
     h = ae_attn_create(B=B, H_q=H_q, H_kv=H_kv, L_q=L_q, L_k=L_k, D_qk=D_qk, D_v=D_v, scale=scale,
                        score_mod=score_mod, bias=bias, gamma=gamma, norm=norm, mask=mask,
                        q_stride=Q.stride()[:3], k_stride=K.stride()[:3], v_stride=V.stride()[:3],
-                       o_stride=out.stride()[:3], out_dtype="bf16" if out.dtype == torch.bfloat16 else "f32")
+                       o_stride=out.stride()[:3], out_dtype="bf16" if out.dtype == torch.bfloat16 else "f32",
+                       window=window)
     try:
         s = torch.cuda.current_stream(Q.device) if stream is None else stream
         with torch.cuda.device(Q.device):
@@ -174,4 +178,5 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
 def run_workload(w, Q, K, V, out=None, out_dtype=None, stats=None):
     """attention_forward with the parameters of a workloads.Workload."""
     return attention_forward(Q, K, V, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
-                             gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out, out_dtype=out_dtype, stats=stats)
+                             gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out, out_dtype=out_dtype, stats=stats,
+                             window=w.window)

@@ -60,7 +60,7 @@ def resource_report() -> str:
                 m = re.search(rf"\.{key}:\s+(\S+)", blk)
                 return m.group(1) if m else "?"
             name = g("name")
-            m = re.search(r"CfgILi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELb(\d)ELi(\d+)E", name)
+            m = re.search(r"CfgILi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)E", name)
             short = "attn_fwd<%s>" % ",".join(m.groups()) if m else name
             rows.append(f"{short:30s} vgpr {g('vgpr_count'):>4s} agpr {blk.split()[0]:>3s} sgpr {g('sgpr_count'):>3s} "
                         f"spill {g('vgpr_spill_count'):>3s} scratch {g('private_segment_fixed_size'):>4s} "

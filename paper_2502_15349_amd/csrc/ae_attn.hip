@@ -23,14 +23,14 @@ ae_status_t fail(ae_status_t code, const char* fmt, ...) {
   return code;
 }
 
-const ae::KernelEntry* find_kernel(int dqk, int dv, int norm, int mod, int causal) {
+const ae::KernelEntry* find_kernel(int dqk, int dv, int norm, int mod, int mask) {
   typedef const ae::KernelEntry* (*table_fn)(int*);
   static const table_fn tables[] = {ae::table_64_64, ae::table_128_128, ae::table_128_256, ae::table_192_128};
   for (table_fn tf : tables) {
     int n = 0;
     const ae::KernelEntry* t = tf(&n);
     for (int i = 0; i < n; ++i)
-      if (t[i].dqk == dqk && t[i].dv == dv && t[i].norm == norm && t[i].mod == mod && t[i].causal == causal)
+      if (t[i].dqk == dqk && t[i].dv == dv && t[i].norm == norm && t[i].mod == mod && t[i].mask == mask)
         return &t[i];
   }
   return nullptr;
@@ -78,8 +78,10 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown score_mod %d", (int)d->score_mod);
   if ((int)d->norm < 0 || (int)d->norm > AE_NORM_NONE)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown norm %d", (int)d->norm);
-  if ((int)d->mask < 0 || (int)d->mask > AE_MASK_CAUSAL)
+  if ((int)d->mask < 0 || (int)d->mask > AE_MASK_SLIDING_WINDOW)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown mask %d", (int)d->mask);
+  if (d->mask == AE_MASK_SLIDING_WINDOW && d->window < 1)
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: the sliding window must hold at least one key");
   if (d->out_dtype != AE_OUT_F32 && d->out_dtype != AE_OUT_BF16)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown out_dtype %d", (int)d->out_dtype);
   if (d->score_mod == AE_MOD_BIAS && !std::isfinite(d->bias))
@@ -104,10 +106,10 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
       if (!std::isfinite(d->gamma[h]) || !(d->gamma[h] > 0.f))
         return fail(AE_ERR_INVALID_ARG, "ae_attn_create: gamma[%d] must be finite and > 0", h);
   }
-  const ae::KernelEntry* k = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, d->mask == AE_MASK_CAUSAL);
+  const ae::KernelEntry* k = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, (int)d->mask);
   if (!k)
-    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: no kernel for score_mod %d with norm %d", (int)d->score_mod,
-                (int)d->norm);
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: no kernel for score_mod %d with norm %d and mask %d",
+                (int)d->score_mod, (int)d->norm, (int)d->mask);
 
   ae_attn* h = new (std::nothrow) ae_attn;
   if (!h) return fail(AE_ERR_NOMEM, "ae_attn_create: out of host memory");
@@ -160,6 +162,7 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   }
   p.neg_q = d->scale < 0.f ? 1 : 0;
   p.out_bf16 = d->out_dtype == AE_OUT_BF16 ? 1 : 0;
+  p.window = d->mask == AE_MASK_SLIDING_WINDOW ? d->window : 0;
   p.fold = (d->norm == AE_NORM_SIGMOID && std::fabs(p.b2) <= 64.f) ? 1 : 0;
   p.kfac = p.fold ? std::exp2(-p.b2) : 1.f;
   if (mod == ae::MOD_DECAY)

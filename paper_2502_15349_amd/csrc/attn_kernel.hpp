@@ -70,6 +70,7 @@ struct Params {
   float b2;        // bias * log2(e)     (softmax, sigmoid)  or bias (others)
   int neg_q;       // scale < 0: the sign is moved onto Q (exact for bf16)
   int out_bf16;    // O holds bf16 instead of fp32
+  int window;      // sliding-window kernels: key j is also hidden if j <= i + (L_k - L_q) - window
   // sigmoid with a bias small enough for 2^(-b2) to be a normal number: Q is
   // multiplied by -scale*log2(e) when loaded (rounded to bf16 again), so that the
   // MFMA delivers the exponent itself and 1 + 2^(-b2) * 2^x is a single FMA
@@ -81,10 +82,12 @@ struct DecayTable {
   float log2_gamma[kMaxDecayHeads];
 };
 
-template <int DQK_, int DV_, int NORM_, int MOD_, bool CAUSAL_, int WAVES_>
+// MASK_: 0 none, 1 causal, 2 causal with a sliding window (Params::window keys per query)
+template <int DQK_, int DV_, int NORM_, int MOD_, int MASK_, int WAVES_>
 struct Cfg {
   static constexpr int DQK = DQK_, DV = DV_, NORM = NORM_, MOD = MOD_, WAVES = WAVES_;
-  static constexpr bool CAUSAL = CAUSAL_;
+  static constexpr int MASK = MASK_;
+  static constexpr bool CAUSAL = MASK_ != 0, WINDOW = MASK_ == 2;
   static constexpr int SUB_N = 32;    // keys per compute sub-tile
   static constexpr int BLOCK_N = 64;  // keys per LDS tile (two sub-tiles)
   static constexpr int BLOCK_M = 32 * WAVES;
@@ -307,6 +310,23 @@ __device__ __forceinline__ void mask_raw(f32x16& s, int jlim, float hidden) {
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       if (key_offset(r) > jlim) s[r] = hidden;
+  }
+}
+// The same for the lower edge of a sliding window: register r is hidden if key_offset(r) < jlo.
+template <class C>
+__device__ __forceinline__ void mask_raw_below(f32x16& s, int jlo, float hidden) {
+  if constexpr (C::NORM == NORM_SOFTMAX || C::NORM == NORM_SIGMOID) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (key_offset(r) < jlo) s[r] = hidden;
+  }
+}
+template <class C>
+__device__ __forceinline__ void mask_modified_below(f32x16& s, int jlo) {
+  if constexpr (C::NORM != NORM_SOFTMAX && C::NORM != NORM_SIGMOID) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (key_offset(r) < jlo) s[r] = 0.f;
   }
 }
 template <class C>
@@ -573,11 +593,15 @@ struct KeyLoop {
     const bool masked = !FAST && ((j0 + C::SUB_N > p.L_k) || (C::CAUSAL && (j0 + C::SUB_N - 1 > iw0 + off)));
     // register r is visible  <=>  key_offset(r) <= jlim
     const int jlim = min(C::CAUSAL ? i + off : p.L_k - 1, p.L_k - 1) - j0 - 4 * half;
+    // sliding window: the sub-tile reaches below the window of the wave's last row; visible <=> key_offset(r) >= jlo
+    const bool masked_lo = !FAST && C::WINDOW && (j0 < iw0 + 31 + off - p.window + 1);
+    const int jlo = i + off - p.window + 1 - j0 - 4 * half;
     const float dbase = C::MOD == MOD_DECAY ? g2 * (float)(i + off - j0 - 4 * half) : 0.f;
     float mx = -INFINITY, xm = 0.f, acc = 0.f;
     bool moved = false;
     const bool fold = C::NORM == NORM_SIGMOID && p.fold;  // wave-uniform
     if (masked) mask_raw<C>(s, jlim, fold ? INFINITY : -INFINITY);
+    if (masked_lo) mask_raw_below<C>(s, jlo, fold ? INFINITY : -INFINITY);
     if (C::MOD == MOD_DECAY && fact) {
       // one exponential per lane and sub-tile instead of one per score
       float ra = p.c * fast_exp2(dbase);
@@ -597,6 +621,7 @@ struct KeyLoop {
       for (int q = 0; q < 8; ++q) post_pair<C, false>(p, q, s, dbase, g2, mx);
     }
     if (masked) mask_modified<C>(s, jlim);
+    if (masked_lo) mask_modified_below<C>(s, jlo);
     post_done<C>(p, st, mx, moved, xm);
     lazy_rescale<C>(st, moved, xm);
     const float k0 = finish_k0<C>(p, st);
@@ -695,6 +720,15 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   }
   const int n_tiles = (kmax + C::BLOCK_N - 1) / C::BLOCK_N;  // LDS tiles (workgroup)
   const int n_vis = (kmax_w + C::SUB_N - 1) / C::SUB_N;      // visible sub-tiles (wave)
+  // Sliding window: the walk starts at the tile of the first key the workgroup's first row sees
+  // (jt0); a wave's own rows start at sub-tile u_first.  Before that the wave runs the matrix
+  // phases with all-zero weights (it would only wait at the barriers otherwise), which keeps
+  // its fragment ring, its LDS addresses and its scores in step with the others.
+  int jt0 = 0, u_first = 0;
+  if (C::WINDOW) {
+    jt0 = max(0, i_wg + off - p.window + 1) / C::BLOCK_N;
+    u_first = max(0, iw0 + off - p.window + 1) / C::SUB_N;
+  }
   // LDS: STAGES stages of a K buffer and a V buffer; tile j lives in stage j % STAGES.
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const uint32_t vlds0 = lds0 + C::K_BYTES;
@@ -756,8 +790,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   static_assert(KMap::NB % C::WAVES == 0 && VMap::NB % C::WAVES == 0, "every wave copies the same number of distinct blocks");
   const int64_t ktile_step = (int64_t)C::BLOCK_N * p.ks[2], vtile_step = (int64_t)C::BLOCK_N * p.vs[2];
   const int64_t kblk_step = (int64_t)KMap::kRowStep * p.ks[2], vblk_step = (int64_t)VMap::kRowStep * p.vs[2];
-  const __bf16* kcp = kbase + 2 * ktile_step;  // tile 2 is the first one copied inside the loop
-  const __bf16* vcp = vbase + 2 * vtile_step;
+  const __bf16 *kcp = kbase, *vcp = vbase;  // first rows of the next tile the short form copies (set before its loop)
   const uint32_t kdst0 = lds0 + wave * 1024, vdst0 = vlds0 + wave * 1024;
   auto copy_whole = [&](auto nsl, auto part, int stage) {
     constexpr int NSL = decltype(nsl)::value, PART = decltype(part)::value;
@@ -789,7 +822,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // and read back as fragments.  They land behind stage 0, next to tile 0, which is
   // copied at the same time; tile 1 follows once every wave has its fragments.
   bf16x8 qf[C::T];
-  if (n_tiles > 0) {
+  if (n_tiles > jt0) {
     using QMap = DmaMap<1, 32, C::CPR_K, false>;
     const uint32_t qlds = lds0 + C::STAGE_BYTES + wave * (32 * C::RB_K);
     // rows past the end of the queries repeat the last one (their output is not stored)
@@ -802,8 +835,8 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       const uint32_t goff = (uint32_t)(row * (int)p.qs[2] + (pc ^ kswz<C::CPR_K>(r)) * 8) * 2u;
       dma16_at<m * 1024>(qtile, goff, qlds);
     });
-    copy_slice(One{}, Zero{}, 0, 0);
-    wait_dma_and_sync();  // one memory latency for the queries and tile 0
+    copy_slice(One{}, Zero{}, jt0, 0);
+    wait_dma_and_sync();  // one memory latency for the queries and the first tile
     uint32_t qaddr[C::T];
     k_frag_offsets<C>(qlds, qaddr);
 #pragma unroll
@@ -819,8 +852,8 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     }
     // every wave has read its rows before tile 1 overwrites them
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    copy_slice(One{}, Zero{}, 1, 1);
-    if (n_vis > 0) score_block<C>(kaddr, 0, qf, s_a);
+    copy_slice(One{}, Zero{}, jt0 + 1, 1);
+    if (2 * jt0 < n_vis) score_block<C>(kaddr, 0, qf, s_a);
   }
 
   // ---- key loop ------------------------------------------------------------------------
@@ -844,7 +877,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // visibility tests, no masking and the short copy; the rest (the diagonal and
   // the end of the keys) run the general form.  Both pass the same barriers; the
   // last two iterations have no tile left to copy and wait for all copies instead.
-  if (n_tiles > 0) {
+  if (n_tiles > jt0) {
     bf16x8 ring[C::PF];
     KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2, false, 1.f, 1.f, 1.f, 1.f};
     if constexpr (C::MOD == MOD_DECAY) {
@@ -854,16 +887,27 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       kl.b2 = fast_exp2(-2.f * g2);
       kl.b3 = fast_exp2(-3.f * g2);
     }
-    if (n_vis > 0) static_for<0, C::PF>([&](auto nc) { kl.template fetch<decltype(nc)::value>(); });
+    if (2 * jt0 < n_vis) static_for<0, C::PF>([&](auto nc) { kl.template fetch<decltype(nc)::value>(); });
     const bool trailing = wave >= C::WAVES / 2;  // second wave of its SIMD
     int buf = 0;
 
+    // The vector phase of a sub-tile, or all-zero weights for one in front of the wave's window.
+    auto vector_or_zero = [&](auto fastc, bool real, int j0) {
+      if (real) {
+        kl.template vector_phase<decltype(fastc)::value>(s_a, j0);
+      } else {
+        pk[0] = pk[1] = (u32x4){0u, 0u, 0u, 0u};
+        pin(pk[0]);
+        pin(pk[1]);
+      }
+    };
     auto iteration = [&](auto fastc, int jt) {
       constexpr bool FAST = decltype(fastc)::value;
       const int nb = next_buf(buf), stage = next_buf(nb);
       kl.dk = kl.dv = (uint32_t)((nb - buf) * C::STAGE_BYTES);
       const int u = 2 * jt;
       const bool vis0 = FAST || u < n_vis, vis1 = FAST || u + 1 < n_vis;    // sub-tiles to aggregate
+      const bool real0 = FAST || u >= u_first, real1 = FAST || u + 1 >= u_first;  // ... with weights of their own
       const bool sc0 = FAST || u + 1 < n_vis, sc1 = FAST || u + 2 < n_vis;  // sub-tiles to score
       const bool more = FAST || jt + 2 < n_tiles;  // there is a tile jt+2 to copy
       auto copy = [&](auto nsl, auto part) {
@@ -880,13 +924,13 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       if constexpr (C::kCopyInVector) {
         using Part = std::integral_constant<int, -1>;  // 0: the K tile, 1: the V tile
         copy(Part{}, Zero{});
-        if (vis0) kl.template vector_phase<FAST>(s_a, u * C::SUB_N);
+        if (vis0) vector_or_zero(fastc, real0, u * C::SUB_N);
         phase_barrier();
         if (vis0) kl.template matrix_phase<0>(s_a, sc0, [] {});
         await_next_tile(std::integral_constant<int, C::KI>{});
         phase_barrier();
         copy(Part{}, One{});
-        if (vis1) kl.template vector_phase<FAST>(s_a, (u + 1) * C::SUB_N);
+        if (vis1) vector_or_zero(fastc, real1, (u + 1) * C::SUB_N);
         phase_barrier();
         if (vis1) kl.template matrix_phase<1>(s_a, sc1, [] {});
         phase_barrier();
@@ -894,7 +938,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
         using Two = std::integral_constant<int, 2>;
         using Three = std::integral_constant<int, 3>;
         constexpr int kSlice0 = (kCopies + 2) / 3;  // instructions in slice 0
-        if (vis0) kl.template vector_phase<FAST>(s_a, u * C::SUB_N);
+        if (vis0) vector_or_zero(fastc, real0, u * C::SUB_N);
         phase_barrier();
         if (vis0)
           kl.template matrix_phase<0>(s_a, sc0, [&] { copy(Three{}, Zero{}); });
@@ -903,7 +947,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
         await_next_tile(std::integral_constant<int, kSlice0>{});
         phase_barrier();
         copy(Three{}, One{});
-        if (vis1) kl.template vector_phase<FAST>(s_a, (u + 1) * C::SUB_N);
+        if (vis1) vector_or_zero(fastc, real1, (u + 1) * C::SUB_N);
         phase_barrier();
         if (vis1)
           kl.template matrix_phase<1>(s_a, sc1, [&] { copy(Three{}, Two{}); });
@@ -918,15 +962,27 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       buf = nb;
     };
 
-    // Iterations jt < n_main of this wave: sub-tiles 2jt, 2jt+1 and 2jt+2 are visible,
-    // no key of tile jt is hidden from any of its rows, tile jt+2 is a whole tile.
-    int n_main = min((n_vis - 1) / 2, min(p.L_k / C::BLOCK_N, n_tiles) - 2);
-    if (C::CAUSAL) n_main = min(n_main, (iw0 + off + 1) / C::BLOCK_N);
-    n_main = max(n_main, 0);
+    // Iterations m0 <= jt < m1 of this wave take the short form: sub-tiles 2jt, 2jt+1 and
+    // 2jt+2 are visible, no key of tile jt is hidden from any of its rows (neither by the
+    // diagonal, nor by the end of the keys, nor by the lower edge of a sliding window), and
+    // tile jt+2 is a whole tile.
+    int m1 = min((n_vis - 1) / 2, min(p.L_k / C::BLOCK_N, n_tiles) - 2);
+    if (C::CAUSAL) m1 = min(m1, (iw0 + off + 1) / C::BLOCK_N);
+    int m0 = jt0;
+    if (C::WINDOW) m0 = max(m0, (max(0, iw0 + off - p.window + 32) + C::BLOCK_N - 1) / C::BLOCK_N);
+    m0 = min(m0, n_tiles);
+    m1 = max(m1, m0);
 
     if (trailing) phase_barrier();
-    int jt = 0;
-    for (; jt < n_main; ++jt) iteration(std::true_type{}, jt);
+    kcp = kbase + (m0 + 2) * ktile_step;  // tile m0 + 2 is the first one the short form copies
+    vcp = vbase + (m0 + 2) * vtile_step;
+    int jt = jt0;
+    if constexpr (!C::WINDOW) {
+      for (; jt < m1; ++jt) iteration(std::true_type{}, jt);
+    }
+    // (With a sliding window every iteration takes the general form: the tiles its lower edge
+    // passes through come first, and a second copy of the general form in front of the short
+    // one costs more registers than the 128/256 and 192/128 kernels have.)
     for (; jt < n_tiles; ++jt) iteration(std::false_type{}, jt);
     if (!trailing) phase_barrier();  // both halves are at the same point again
   }

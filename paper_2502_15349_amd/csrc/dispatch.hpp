@@ -7,7 +7,7 @@ namespace ae {
 typedef hipError_t (*launch_fn)(const Params&, const DecayTable&, int grid, hipStream_t);
 
 struct KernelEntry {
-  int dqk, dv, norm, mod, causal;
+  int dqk, dv, norm, mod, mask;  // mask: 0 none, 1 causal, 2 sliding window
   int block_m, block_n, threads, lds_bytes;
   launch_fn launch;
   const char* name;
@@ -21,18 +21,19 @@ hipError_t launch_cfg(const Params& p, const DecayTable& dt, int grid, hipStream
 
 template <class C>
 constexpr KernelEntry make_entry(const char* name) {
-  return KernelEntry{C::DQK, C::DV, C::NORM, C::MOD, C::CAUSAL ? 1 : 0,
+  return KernelEntry{C::DQK, C::DV, C::NORM, C::MOD, C::MASK,
                      C::BLOCK_M, C::BLOCK_N, C::THREADS, C::LDS_BYTES, &launch_cfg<C>, name};
 }
 
-// One row of the tile-shape table: for head dims (DQK, DV) and mask CAUSAL the
-// workgroup has WAVES wavefronts of 32 query rows each.
-#define AE_ENTRY(DQK, DV, NORM, MOD, CAUSAL, WAVES)     \
-  make_entry<Cfg<DQK, DV, NORM, MOD, CAUSAL, WAVES>>(   \
-      "attn_fwd<" #DQK "," #DV "," #NORM "," #MOD "," #CAUSAL "," #WAVES ">")
+// One row of the tile-shape table: for head dims (DQK, DV) and mask MASK (false / 0: none,
+// true / 1: causal, 2: sliding window) the workgroup has WAVES wavefronts of 32 query rows each.
+#define AE_ENTRY(DQK, DV, NORM, MOD, MASK, WAVES)     \
+  make_entry<Cfg<DQK, DV, NORM, MOD, MASK, WAVES>>(   \
+      "attn_fwd<" #DQK "," #DV "," #NORM "," #MOD "," #MASK "," #WAVES ">")
 
 // Every (norm, mod) pair the library supports, for one (DQK, DV) and one tile
-// shape (WAVES) per mask value (SHAPE_NC unmasked, SHAPE_C causal).
+// shape (WAVES) per mask value (SHAPE_NC unmasked, SHAPE_C causal and sliding window;
+// the sliding window comes with softmax, sigmoid and no normalization).
 #define AE_ENTRIES_FOR_DIMS(DQK, DV, SHAPE_NC, SHAPE_C)            \
   AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_PLAIN, false, SHAPE_NC),    \
   AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_PLAIN, false, SHAPE_NC),    \
@@ -48,7 +49,10 @@ constexpr KernelEntry make_entry(const char* name) {
   AE_ENTRY(DQK, DV, NORM_NONE, MOD_RELU, true, SHAPE_C),          \
   AE_ENTRY(DQK, DV, NORM_ABSSUM, MOD_DECAY, true, SHAPE_C),       \
   AE_ENTRY(DQK, DV, NORM_ABS_OF_SUM, MOD_DECAY, true, SHAPE_C),   \
-  AE_ENTRY(DQK, DV, NORM_NONE, MOD_DECAY, true, SHAPE_C)
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_DECAY, true, SHAPE_C),          \
+  AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_PLAIN, 2, SHAPE_C),         \
+  AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_PLAIN, 2, SHAPE_C),         \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_PLAIN, 2, SHAPE_C)
 
 const KernelEntry* table_64_64(int* n);
 const KernelEntry* table_128_128(int* n);

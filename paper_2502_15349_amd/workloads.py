@@ -32,10 +32,11 @@ class Workload:
     D_v: int
     score_mod: str = "none"      # none | bias | head_decay | relu
     norm: str = "softmax"        # softmax | sigmoid | abssum | abs_of_sum | none
-    mask: str = "none"           # none | causal
+    mask: str = "none"           # none | causal | sliding_window
     scale: Optional[float] = None  # default 1/sqrt(D_qk)
     bias: float = 0.0
     decay: bool = False          # per-head gamma_h = 1 - 2^(-5-h)
+    window: int = 0              # keys per query of the sliding-window mask
 
     @property
     def scale_value(self) -> float:
@@ -52,7 +53,13 @@ class Workload:
         if self.mask == "none":
             return self.L_q * self.L_k
         off = self.L_k - self.L_q
+        if self.mask == "sliding_window":
+            return sum(max(0, min(self.L_k, i + off + 1) - max(0, i + off + 1 - self.window)) for i in range(self.L_q))
         return sum(max(0, min(self.L_k, i + off + 1)) for i in range(self.L_q))
+
+    def oracle_mask(self):
+        """The mask in the form the oracle's functions take."""
+        return ("sliding_window", self.window) if self.mask == "sliding_window" else self.mask
 
     def mfma_flop(self) -> int:
         """2*(D_qk + D_v) flop per visible (query, key) pair."""

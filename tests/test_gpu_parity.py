@@ -32,7 +32,7 @@ def gpu_run(A, w, Q, K, V):
 
 def oracle_run(w, Q, K, V):
     return attention(Q, K, V, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
-                     gamma=w.gamma(), norm=w.norm, mask=w.mask)
+                     gamma=w.gamma(), norm=w.norm, mask=w.oracle_mask())
 
 
 def check(got, ref, what=""):
@@ -137,7 +137,7 @@ def _sampled_full_config(A, w, n_heads=3, n_rows=96, seed=0):
             rng.integers(0, w.L_q, n_rows)])).astype(np.int64)
         rows = rows[(rows >= 0) & (rows < w.L_q)]
         ref = attention_head(Q[b, h], K[b, h // g], V[b, h // g], scale=w.scale_value, score_mod=w.score_mod,
-                             bias=w.bias, gamma_h=None if gam is None else gam[h], norm=w.norm, mask=w.mask,
+                             bias=w.bias, gamma_h=None if gam is None else gam[h], norm=w.norm, mask=w.oracle_mask(),
                              rows=rows)
         got = O[b, h].cpu().double().numpy()[rows]
         errs.append(np.abs(got - ref))
@@ -169,7 +169,7 @@ def test_table2_shapes_sampled(A):
         h = int(rng.integers(w.H_q))
         rows = np.unique(np.concatenate([[0, 255, 256, w.L_q - 1], rng.integers(0, w.L_q, 40)])).astype(np.int64)
         ref = attention_head(Q[0, h], K[0, h], V[0, h], scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
-                             gamma_h=None, norm=w.norm, mask=w.mask, rows=rows)
+                             gamma_h=None, norm=w.norm, mask=w.oracle_mask(), rows=rows)
         got = O[0, h].cpu().double().numpy()[rows]
         e = np.abs(got - ref) / np.maximum(1.0, np.abs(ref).max(axis=1, keepdims=True))
         assert e.max() <= MAX_ABS and e.mean() <= MEAN_ABS, (w.name, e.max(), e.mean())
@@ -266,7 +266,7 @@ def test_row_statistics(A, dims, norm, mod, mask):
     for b in range(w.B):
         for h in range(w.H_q):
             ref = row_stats_head(Q[b, h], K[b, h // g], scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
-                                 gamma_h=None if gam is None else gam[h], norm=w.norm, mask=w.mask)
+                                 gamma_h=None if gam is None else gam[h], norm=w.norm, mask=w.oracle_mask())
             if norm == "softmax":
                 assert np.abs(got[b, h] - ref).max() <= 1e-3, (b, h, np.abs(got[b, h] - ref).max())
             else:
@@ -288,6 +288,26 @@ def test_row_statistics_rows_without_keys(A):
         fin = np.isfinite(ref)
         assert np.abs(got[0, h][fin] - ref[fin]).max() <= 1e-3
     assert (O[:, :, :63] == 0).all()
+
+
+@pytest.mark.parametrize("dims", DIMS, ids=lambda d: f"d{d[0]}_{d[1]}")
+@pytest.mark.parametrize("norm,mod", [("softmax", "none"), ("sigmoid", "bias"), ("none", "none")])
+@pytest.mark.parametrize("Lq,Lk,W", [(300, 333, 100), (700, 700, 64), (513, 600, 1), (40, 300, 129), (300, 300, 5000),
+                                     (200, 90, 33)])
+def test_sliding_window(A, dims, norm, mod, Lq, Lk, W):
+    """AE_MASK_SLIDING_WINDOW: the W keys nearest the causal diagonal; windows shorter than a
+    sub-tile, longer than the sequence, ragged sizes, L_q != L_k (rows without keys included)."""
+    w = Workload("window", 18, 1, 4, 2, Lq, Lk, dims[0], dims[1], mask="sliding_window", window=W, norm=norm,
+                 score_mod=mod, bias=-1.0, scale=0.005 if norm == "none" else None)
+    Q, K, V = make_inputs(w)
+    got, ref = gpu_run(A, w, Q, K, V), oracle_run(w, Q, K, V)
+    rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)   # row scale of the non-normalised variants
+    check(got / rs, ref / rs, f"window {W}")
+
+
+def test_sliding_window_full_size_sampled(A):
+    w = C2.scaled(name="c2_window_512", mask="sliding_window", window=512)
+    _sampled_full_config(A, w)
 
 
 def test_negative_scale_and_large_scores(A):
