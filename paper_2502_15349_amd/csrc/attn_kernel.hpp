@@ -720,15 +720,26 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   }
   const int n_tiles = (kmax + C::BLOCK_N - 1) / C::BLOCK_N;  // LDS tiles (workgroup)
   const int n_vis = (kmax_w + C::SUB_N - 1) / C::SUB_N;      // visible sub-tiles (wave)
-  // Sliding window: the walk starts at the tile of the first key the workgroup's first row sees
-  // (jt0); a wave's own rows start at sub-tile u_first.  Before that the wave runs the matrix
-  // phases with all-zero weights (it would only wait at the barriers otherwise), which keeps
-  // its fragment ring, its LDS addresses and its scores in step with the others.
-  int jt0 = 0, u_first = 0;
+  // The walk over the key tiles.  Without a window: tiles 0 .. n_tiles-1 in order.  With a
+  // sliding window the workgroup needs tiles jt0 .. n_tiles-1 (jt0: tile of the first key its
+  // first row sees) and a wave's own rows start at sub-tile u_first.  The order of the key
+  // tiles is free (every reduction here is commutative), and the walk is rotated: first the
+  // tiles from jtm on -- no row of the workgroup has its window's lower edge in them, so they
+  // are walked exactly like a causal problem that starts at tile jtm -- then tiles jt0 ..
+  // jtm-1, which the lower edges pass through, in the general form of the iteration.  This
+  // keeps the general form behind the short one in the program, as without a window.
+  // A wave with no key of its own in a sub-tile runs the matrix phases with all-zero weights
+  // (it would only wait at the barriers otherwise), which keeps its fragment ring, its LDS
+  // addresses and its scores in step with the others.
+  int jt0 = 0, jtm = 0, u_first = 0;
   if (C::WINDOW) {
     jt0 = max(0, i_wg + off - p.window + 1) / C::BLOCK_N;
+    jtm = (max(0, i_wg + (C::WAVES - 1) * 32 + off - p.window + 32) + C::BLOCK_N - 1) / C::BLOCK_N;
+    jtm = max(jt0, min(jtm, n_tiles));
     u_first = max(0, iw0 + off - p.window + 1) / C::SUB_N;
   }
+  const int n_walk = max(n_tiles - jt0, 0), n_lead = n_tiles - jtm;  // positions in the walk; those before the rotation
+  auto tile_at = [&](int pos) { return C::WINDOW ? (pos < n_lead ? jtm + pos : jt0 + (pos - n_lead)) : pos; };
   // LDS: STAGES stages of a K buffer and a V buffer; tile j lives in stage j % STAGES.
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const uint32_t vlds0 = lds0 + C::K_BYTES;
@@ -822,7 +833,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // and read back as fragments.  They land behind stage 0, next to tile 0, which is
   // copied at the same time; tile 1 follows once every wave has its fragments.
   bf16x8 qf[C::T];
-  if (n_tiles > jt0) {
+  if (n_walk > 0) {
     using QMap = DmaMap<1, 32, C::CPR_K, false>;
     const uint32_t qlds = lds0 + C::STAGE_BYTES + wave * (32 * C::RB_K);
     // rows past the end of the queries repeat the last one (their output is not stored)
@@ -835,7 +846,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       const uint32_t goff = (uint32_t)(row * (int)p.qs[2] + (pc ^ kswz<C::CPR_K>(r)) * 8) * 2u;
       dma16_at<m * 1024>(qtile, goff, qlds);
     });
-    copy_slice(One{}, Zero{}, jt0, 0);
+    copy_slice(One{}, Zero{}, tile_at(0), 0);
     wait_dma_and_sync();  // one memory latency for the queries and the first tile
     uint32_t qaddr[C::T];
     k_frag_offsets<C>(qlds, qaddr);
@@ -852,8 +863,8 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     }
     // every wave has read its rows before tile 1 overwrites them
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    copy_slice(One{}, Zero{}, jt0 + 1, 1);
-    if (2 * jt0 < n_vis) score_block<C>(kaddr, 0, qf, s_a);
+    copy_slice(One{}, Zero{}, n_walk > 1 ? tile_at(1) : tile_at(0), 1);
+    if (C::WINDOW || n_vis > 0) score_block<C>(kaddr, 0, qf, s_a);
   }
 
   // ---- key loop ------------------------------------------------------------------------
@@ -877,7 +888,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // visibility tests, no masking and the short copy; the rest (the diagonal and
   // the end of the keys) run the general form.  Both pass the same barriers; the
   // last two iterations have no tile left to copy and wait for all copies instead.
-  if (n_tiles > jt0) {
+  if (n_walk > 0) {
     bf16x8 ring[C::PF];
     KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2, false, 1.f, 1.f, 1.f, 1.f};
     if constexpr (C::MOD == MOD_DECAY) {
@@ -887,7 +898,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       kl.b2 = fast_exp2(-2.f * g2);
       kl.b3 = fast_exp2(-3.f * g2);
     }
-    if (2 * jt0 < n_vis) static_for<0, C::PF>([&](auto nc) { kl.template fetch<decltype(nc)::value>(); });
+    if (C::WINDOW || n_vis > 0) static_for<0, C::PF>([&](auto nc) { kl.template fetch<decltype(nc)::value>(); });
     const bool trailing = wave >= C::WAVES / 2;  // second wave of its SIMD
     int buf = 0;
 
@@ -901,18 +912,23 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
         pin(pk[1]);
       }
     };
-    auto iteration = [&](auto fastc, int jt) {
+    // One step of the walk: position pos, tile jt = tile_at(pos).
+    auto iteration = [&](auto fastc, int pos) {
       constexpr bool FAST = decltype(fastc)::value;
       const int nb = next_buf(buf), stage = next_buf(nb);
       kl.dk = kl.dv = (uint32_t)((nb - buf) * C::STAGE_BYTES);
+      const int jt = FAST ? pos + jtm : tile_at(pos);
       const int u = 2 * jt;
-      const bool vis0 = FAST || u < n_vis, vis1 = FAST || u + 1 < n_vis;    // sub-tiles to aggregate
-      const bool real0 = FAST || u >= u_first, real1 = FAST || u + 1 >= u_first;  // ... with weights of their own
-      const bool sc0 = FAST || u + 1 < n_vis, sc1 = FAST || u + 2 < n_vis;  // sub-tiles to score
-      const bool more = FAST || jt + 2 < n_tiles;  // there is a tile jt+2 to copy
+      // sub-tiles the wave runs its phases for / has weights of its own in / scores ahead
+      const bool vis0 = FAST || C::WINDOW || u < n_vis, vis1 = FAST || C::WINDOW || u + 1 < n_vis;
+      const bool real0 = FAST || !C::WINDOW || (u >= u_first && u < n_vis);
+      const bool real1 = FAST || !C::WINDOW || (u + 1 >= u_first && u + 1 < n_vis);
+      const bool sc0 = FAST || C::WINDOW || u + 1 < n_vis;
+      const bool sc1 = FAST || (C::WINDOW ? pos + 1 < n_walk : u + 2 < n_vis);
+      const bool more = FAST || pos + 2 < n_walk;  // there is a tile two positions on to copy
       auto copy = [&](auto nsl, auto part) {
         if constexpr (FAST) copy_whole(nsl, part, stage);
-        else if (more) copy_slice(nsl, part, jt + 2, stage);
+        else if (more) copy_slice(nsl, part, tile_at(pos + 2), stage);
       };
       // This wave's share of tile jt+1 has landed: all of its copies but the `newest`
       // of tile jt+2 just issued (if there is a tile jt+2).
@@ -962,28 +978,20 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       buf = nb;
     };
 
-    // Iterations m0 <= jt < m1 of this wave take the short form: sub-tiles 2jt, 2jt+1 and
-    // 2jt+2 are visible, no key of tile jt is hidden from any of its rows (neither by the
-    // diagonal, nor by the end of the keys, nor by the lower edge of a sliding window), and
-    // tile jt+2 is a whole tile.
+    // Positions pos < n_fast of this wave take the short form (tile jt = jtm + pos): sub-tiles
+    // 2jt, 2jt+1 and 2jt+2 are visible, no key of tile jt is hidden from any of its rows
+    // (neither by the diagonal, nor by the end of the keys, nor -- from jtm on -- by the lower
+    // edge of a window), and the tile two positions on is a whole tile before the rotation.
     int m1 = min((n_vis - 1) / 2, min(p.L_k / C::BLOCK_N, n_tiles) - 2);
     if (C::CAUSAL) m1 = min(m1, (iw0 + off + 1) / C::BLOCK_N);
-    int m0 = jt0;
-    if (C::WINDOW) m0 = max(m0, (max(0, iw0 + off - p.window + 32) + C::BLOCK_N - 1) / C::BLOCK_N);
-    m0 = min(m0, n_tiles);
-    m1 = max(m1, m0);
+    const int n_fast = max(m1 - jtm, 0);
 
     if (trailing) phase_barrier();
-    kcp = kbase + (m0 + 2) * ktile_step;  // tile m0 + 2 is the first one the short form copies
-    vcp = vbase + (m0 + 2) * vtile_step;
-    int jt = jt0;
-    if constexpr (!C::WINDOW) {
-      for (; jt < m1; ++jt) iteration(std::true_type{}, jt);
-    }
-    // (With a sliding window every iteration takes the general form: the tiles its lower edge
-    // passes through come first, and a second copy of the general form in front of the short
-    // one costs more registers than the 128/256 and 192/128 kernels have.)
-    for (; jt < n_tiles; ++jt) iteration(std::false_type{}, jt);
+    kcp = kbase + (jtm + 2) * ktile_step;  // the first tile the short form copies
+    vcp = vbase + (jtm + 2) * vtile_step;
+    int pos = 0;
+    for (; pos < n_fast; ++pos) iteration(std::true_type{}, pos);
+    for (; pos < n_walk; ++pos) iteration(std::false_type{}, pos);
     if (!trailing) phase_barrier();  // both halves are at the same point again
   }
   // No copy is in flight (the last iterations issue none) and every wave is past its
