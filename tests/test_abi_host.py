@@ -111,6 +111,21 @@ def test_bf16_output_accepted_and_unknown_dtype_rejected():
     assert ei.value.status == A.AE_ERR_UNSUPPORTED
 
 
+def test_sliding_window_descriptor_checks():
+    from paper_2502_15349_amd import ae_attn as A
+    A.ae_attn_destroy(A.ae_attn_create(**_ok_desc(), mask="sliding_window", window=17))
+    for window in (0, -3):
+        with pytest.raises(A.AeAttnError) as ei:
+            A.ae_attn_create(**_ok_desc(), mask="sliding_window", window=window)
+        assert ei.value.status == A.AE_ERR_INVALID_ARG
+    # the window comes with softmax, sigmoid and no normalization only
+    d = _ok_desc()
+    d.update(norm="abssum")
+    with pytest.raises(A.AeAttnError) as ei:
+        A.ae_attn_create(**d, mask="sliding_window", window=8)
+    assert ei.value.status == A.AE_ERR_UNSUPPORTED
+
+
 def test_padded_strides_accepted():
     from paper_2502_15349_amd import ae_attn as A
     h = A.ae_attn_create(**_ok_desc(), q_stride=(100 * 4 * 136, 100 * 136, 136))
