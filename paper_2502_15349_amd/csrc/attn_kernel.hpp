@@ -23,8 +23,13 @@
 // the next one); the two waves of a SIMD alternate, one always a phase behind
 // the other (see KeyLoop below).  A wave whose rows see no further keys (causal
 // diagonal) keeps passing the barriers and skips the work; masking is a small
-// wave-uniform branch around the sub-tiles that cross the diagonal or the end
-// of the keys.
+// wave-uniform branch around the sub-tiles that cross the diagonal, the end of
+// the keys or the lower edge of a sliding window.  The iterations in which none
+// of that can happen run a short form without those tests (see the kernel).
+//
+// The query rows (on the way in) and the output rows (on the way out) pass
+// through LDS, so that every global memory instruction moves 1 KB of whole
+// cache lines although a lane's MFMA fragments are 16-byte pieces of one row.
 //
 // K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4:
 // no staging registers, no ds_write): a wave instruction fills 1 KB of LDS
