@@ -95,6 +95,13 @@ typedef struct {
   ae_out_dtype_t out_dtype;
   int32_t window;      /* keys per query, >= 1; read only by
                           AE_MASK_SLIDING_WINDOW                                */
+  int32_t kv_splits;   /* 0 or 1: every workgroup walks all keys of its rows.
+                          n > 1 (at most 256): the keys are cut into n ranges
+                          walked by different workgroups, whose partial results
+                          a second kernel combines -- for few query rows and
+                          many keys (decoding).  AE_NORM_SOFTMAX with
+                          AE_MASK_NONE or AE_MASK_CAUSAL only; such a handle
+                          runs through ae_attn_forward_split.                   */
   int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3];
 } ae_attn_desc_t;
 
@@ -131,6 +138,26 @@ ae_status_t ae_attn_forward(const ae_attn_t *h, const void *Q, const void *K,
 ae_status_t ae_attn_forward_stats(const ae_attn_t *h, const void *Q,
                                   const void *K, const void *V, void *O,
                                   void *stats, void *stream);
+
+/* Bytes of device workspace that ae_attn_forward_split needs for this handle:
+ * the partial output rows and their log-sum-exp, fp32,
+ * n * B * H_q * L_q * (D_v + 1) elements for n ranges of keys (0 if the keys
+ * are not split).                                                              */
+ae_status_t ae_attn_workspace_bytes(const ae_attn_t *h, size_t *bytes);
+
+/* Forward for a handle created with kv_splits > 1 (it also serves any other
+ * handle, ignoring the workspace): the attention kernel writes per-range
+ * partial results to `workspace`, a second kernel combines them into O (and
+ * into `stats`, which may be NULL; see ae_attn_forward_stats).  workspace:
+ * device pointer owned by the caller, 16-byte aligned, at least
+ * ae_attn_workspace_bytes() bytes, not aliasing the other buffers; its contents
+ * need not be initialised and are overwritten.  Both kernels are enqueued on
+ * `stream`; nothing is allocated.  Calls that share a workspace must not
+ * overlap in time.  Errors as ae_attn_forward.                                 */
+ae_status_t ae_attn_forward_split(const ae_attn_t *h, const void *Q,
+                                  const void *K, const void *V, void *O,
+                                  void *stats, void *workspace,
+                                  size_t workspace_bytes, void *stream);
 
 /* Frees the handle.  NULL is a no-op.                                         */
 ae_status_t ae_attn_destroy(ae_attn_t *h);

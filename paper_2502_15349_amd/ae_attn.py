@@ -32,7 +32,7 @@ class ae_attn_desc_t(C.Structure):
         ("L_k", C.c_int32), ("D_qk", C.c_int32), ("D_v", C.c_int32),
         ("score_mod", C.c_int), ("bias", C.c_float), ("gamma", C.POINTER(C.c_float)),
         ("norm", C.c_int), ("mask", C.c_int), ("scale", C.c_float), ("out_dtype", C.c_int),
-        ("window", C.c_int32),
+        ("window", C.c_int32), ("kv_splits", C.c_int32),
         ("q_stride", C.c_int64 * 3), ("k_stride", C.c_int64 * 3),
         ("v_stride", C.c_int64 * 3), ("o_stride", C.c_int64 * 3),
     ]
@@ -44,6 +44,10 @@ _lib.ae_attn_forward.argtypes = [C.c_void_p] * 6
 _lib.ae_attn_forward.restype = C.c_int
 _lib.ae_attn_forward_stats.argtypes = [C.c_void_p] * 7
 _lib.ae_attn_forward_stats.restype = C.c_int
+_lib.ae_attn_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+_lib.ae_attn_workspace_bytes.restype = C.c_int
+_lib.ae_attn_forward_split.argtypes = [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
+_lib.ae_attn_forward_split.restype = C.c_int
 _lib.ae_attn_destroy.argtypes = [C.c_void_p]
 _lib.ae_attn_destroy.restype = C.c_int
 _lib.ae_attn_query.argtypes = [C.c_void_p] + [C.POINTER(C.c_int32)] * 5
@@ -81,7 +85,7 @@ def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int
                    scale: float, score_mod="none", bias: float = 0.0,
                    gamma: Optional[Sequence[float]] = None, norm="softmax", mask="none",
                    q_stride=(0, 0, 0), k_stride=(0, 0, 0), v_stride=(0, 0, 0), o_stride=(0, 0, 0),
-                   out_dtype="f32", window: int = 0) -> int:
+                   out_dtype="f32", window: int = 0, kv_splits: int = 0) -> int:
     """Returns an opaque handle (int).  Enum arguments accept names or raw ints."""
     d = ae_attn_desc_t()
     d.B, d.H_q, d.H_kv, d.L_q, d.L_k, d.D_qk, d.D_v = B, H_q, H_kv, L_q, L_k, D_qk, D_v
@@ -91,6 +95,7 @@ def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int
     d.bias, d.scale = float(bias), float(scale)
     d.out_dtype = OUT_DTYPES[out_dtype] if isinstance(out_dtype, str) else int(out_dtype)
     d.window = int(window)
+    d.kv_splits = int(kv_splits)
     keep = None
     if gamma is not None:
         keep = (C.c_float * len(gamma))(*[float(x) for x in gamma])
@@ -100,6 +105,18 @@ def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int
     h = C.c_void_p()
     _check(_lib.ae_attn_create(C.byref(d), C.byref(h)))
     return h.value
+
+
+def ae_attn_workspace_bytes(handle: int) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.ae_attn_workspace_bytes(handle, C.byref(n)))
+    return int(n.value)
+
+
+def ae_attn_forward_split(handle: int, Q: int, K: int, V: int, O: int, stats: int, workspace: int,
+                          workspace_bytes: int, stream: int = 0) -> None:
+    """Forward of a handle created with kv_splits > 1; stats may be 0 (not written)."""
+    _check(_lib.ae_attn_forward_split(handle, Q, K, V, O, stats, workspace, workspace_bytes, stream))
 
 
 def ae_attn_forward_stats(handle: int, Q: int, K: int, V: int, O: int, stats: int, stream: int = 0) -> None:
@@ -134,12 +151,15 @@ def ae_attn_query(handle: int) -> dict:
 
 # ---- convenience for torch callers (still marshalling only) -------------------
 def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
-                      mask="none", out=None, stream=None, out_dtype=None, stats=None, window=0):
+                      mask="none", out=None, stream=None, out_dtype=None, stats=None, window=0, kv_splits=0,
+                      workspace=None):
     """Runs the HIP operator on CUDA/HIP bf16 tensors laid out [B, H, L, D]
     (last dim contiguous) and returns O [B, H_q, L_q, D_v]: fp32, or bf16 if `out` is a
     bf16 tensor or out_dtype is torch.bfloat16.  stats: optional contiguous fp32 device
     tensor [B, H_q, L_q] that receives the row statistic of the normalization.  window: keys
-    per query for mask="sliding_window"."""
+    per query for mask="sliding_window".  kv_splits > 1: the keys are cut into that many ranges
+    (few query rows, many keys); `workspace` is then a device byte tensor of at least
+    ae_attn_workspace_bytes() bytes (allocated here if not given)."""
     import torch
 
     if not (Q.is_cuda and K.is_cuda and V.is_cuda):
@@ -159,11 +179,21 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
                        score_mod=score_mod, bias=bias, gamma=gamma, norm=norm, mask=mask,
                        q_stride=Q.stride()[:3], k_stride=K.stride()[:3], v_stride=V.stride()[:3],
                        o_stride=out.stride()[:3], out_dtype="bf16" if out.dtype == torch.bfloat16 else "f32",
-                       window=window)
+                       window=window, kv_splits=kv_splits)
     try:
         s = torch.cuda.current_stream(Q.device) if stream is None else stream
         with torch.cuda.device(Q.device):
-            if stats is None:
+            if stats is not None and (stats.dtype != torch.float32 or tuple(stats.shape) != (B, H_q, L_q)
+                                      or not stats.is_contiguous()):
+                raise ValueError("stats must be a contiguous fp32 tensor [B, H_q, L_q]")
+            need = ae_attn_workspace_bytes(h)
+            if need:
+                if workspace is None:
+                    workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+                ae_attn_forward_split(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
+                                      0 if stats is None else stats.data_ptr(), workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), s.cuda_stream)
+            elif stats is None:
                 ae_attn_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), s.cuda_stream)
             else:
                 if stats.dtype != torch.float32 or tuple(stats.shape) != (B, H_q, L_q) or not stats.is_contiguous():
@@ -175,8 +205,8 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
     return out
 
 
-def run_workload(w, Q, K, V, out=None, out_dtype=None, stats=None):
+def run_workload(w, Q, K, V, out=None, out_dtype=None, stats=None, kv_splits=0):
     """attention_forward with the parameters of a workloads.Workload."""
     return attention_forward(Q, K, V, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
                              gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out, out_dtype=out_dtype, stats=stats,
-                             window=w.window)
+                             window=w.window, kv_splits=kv_splits)

@@ -53,6 +53,43 @@ void fill_strides(int64_t dst[3], const int64_t src[3], int H, int L, int D) {
   }
 }
 
+// ---- split keys: combining the partial results -----------------------------------------
+// Softmax over a union of key sets: with lse_c = ln sum_{j in set c} exp(x_j) and O_c the
+// normalised partial rows, O = sum_c exp(lse_c - LSE) O_c and LSE = ln sum_c exp(lse_c) (the
+// rule by which the online row-norm state of two key blocks is combined, Section 4.1).  A
+// split without a visible key has lse_c = -inf and weight 0.
+struct MergeParams {
+  const float* ws_o;    // [n_splits, rows, D_v]
+  const float* ws_lse;  // [n_splits, rows]
+  void* O;              // fp32 or bf16, strides os[] in elements
+  float* stats;         // optional [rows]
+  int n_splits, B, H_q, L_q, D_v, out_bf16;
+  int64_t os[3];
+};
+__global__ __launch_bounds__(256) void attn_merge_kernel(const MergeParams p) {
+  const int64_t rows = (int64_t)p.B * p.H_q * p.L_q;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // one wavefront per row
+  if (r >= rows) return;
+  const int lane = threadIdx.x & 63;
+  float mx = -INFINITY;
+  for (int c = 0; c < p.n_splits; ++c) mx = fmaxf(mx, p.ws_lse[c * rows + r]);
+  float tot = 0.f;
+  for (int c = 0; c < p.n_splits; ++c) tot += mx == -INFINITY ? 0.f : __expf(p.ws_lse[c * rows + r] - mx);
+  const float lse = mx == -INFINITY ? -INFINITY : mx + __logf(tot);
+  const int i = (int)(r % p.L_q), hq = (int)((r / p.L_q) % p.H_q), b = (int)(r / ((int64_t)p.L_q * p.H_q));
+  const int64_t obase = b * p.os[0] + hq * p.os[1] + (int64_t)i * p.os[2];
+  for (int d = lane; d < p.D_v; d += 64) {
+    float acc = 0.f;
+    for (int c = 0; c < p.n_splits; ++c) {
+      const float wgt = mx == -INFINITY ? 0.f : __expf(p.ws_lse[c * rows + r] - lse);
+      acc += wgt * p.ws_o[(c * rows + r) * p.D_v + d];
+    }
+    if (p.out_bf16) static_cast<__bf16*>(p.O)[obase + d] = (__bf16)acc;
+    else static_cast<float*>(p.O)[obase + d] = acc;
+  }
+  if (p.stats != nullptr && lane == 0) p.stats[r] = lse;
+}
+
 }  // namespace
 
 struct ae_attn {
@@ -61,6 +98,7 @@ struct ae_attn {
   ae::Params params;  // pointers filled in per call
   ae::DecayTable decay;
   int grid;
+  size_t ws_bytes;  // workspace the split-key forward needs (0: keys are not split)
 };
 
 extern "C" {
@@ -84,6 +122,10 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     return fail(AE_ERR_INVALID_ARG, "ae_attn_create: the sliding window must hold at least one key");
   if (d->out_dtype != AE_OUT_F32 && d->out_dtype != AE_OUT_BF16)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown out_dtype %d", (int)d->out_dtype);
+  if (d->kv_splits < 0 || d->kv_splits > 256)
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: kv_splits must be between 0 and 256");
+  if (d->kv_splits > 1 && (d->norm != AE_NORM_SOFTMAX || d->mask == AE_MASK_SLIDING_WINDOW))
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: split keys come with softmax and the masks NONE and CAUSAL only");
   if (d->score_mod == AE_MOD_BIAS && !std::isfinite(d->bias))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_create: bias must be finite");
   if ((int64_t)d->B * d->H_kv > (1 << 24) || (int64_t)d->L_q > (1 << 28) || (int64_t)d->L_k > (1 << 28))
@@ -187,12 +229,32 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: grid of %lld workgroups exceeds the launch limit", (long long)grid);
   }
   h->grid = (int)grid;
+  // Split keys: n_splits copies of the grid, each over its own range of key tiles.
+  p.n_splits = 1;
+  p.split_tiles = 0;
+  p.base_grid = (int)grid;
+  h->ws_bytes = 0;
+  if (d->kv_splits > 1) {
+    const int key_tiles = (d->L_k + h->kernel->block_n - 1) / h->kernel->block_n;
+    p.split_tiles = (key_tiles + d->kv_splits - 1) / d->kv_splits;
+    p.n_splits = (key_tiles + p.split_tiles - 1) / p.split_tiles;
+    if (p.n_splits > 1) {
+      if (grid * p.n_splits > 0x7fffffffLL) {
+        delete h;
+        return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: grid of %lld workgroups exceeds the launch limit",
+                    (long long)(grid * p.n_splits));
+      }
+      h->grid = (int)(grid * p.n_splits);
+      const size_t rows = (size_t)d->B * d->H_q * d->L_q;
+      h->ws_bytes = (size_t)p.n_splits * rows * ((size_t)d->D_v + 1) * sizeof(float);
+    }
+  }
   *out = h;
   return AE_OK;
 }
 
 static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, float* stats,
-                                void* stream) {
+                                void* stream, void* workspace = nullptr, size_t workspace_bytes = 0) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null handle");
   if (!Q || !K || !V || !O) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null device pointer");
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
@@ -204,8 +266,35 @@ static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K
   p.V = static_cast<const __bf16*>(V);
   p.O = O;
   p.stats = stats;
+  if (p.n_splits > 1) {
+    if (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < h->ws_bytes)
+      return fail(AE_ERR_INVALID_ARG,
+                  "ae_attn_forward: keys are split: call ae_attn_forward_split with a 16-byte aligned workspace of "
+                  "ae_attn_workspace_bytes() bytes");
+    const size_t rows = (size_t)p.B * p.H_q * p.L_q;
+    p.ws_o = static_cast<float*>(workspace);
+    p.ws_lse = p.ws_o + (size_t)p.n_splits * rows * h->desc.D_v;
+  }
   hipError_t e = h->kernel->launch(p, h->decay, h->grid, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_forward: launch failed: %s", hipGetErrorString(e));
+  if (p.n_splits > 1) {
+    MergeParams m;
+    m.ws_o = p.ws_o;
+    m.ws_lse = p.ws_lse;
+    m.O = O;
+    m.stats = stats;
+    m.n_splits = p.n_splits;
+    m.B = p.B;
+    m.H_q = p.H_q;
+    m.L_q = p.L_q;
+    m.D_v = h->desc.D_v;
+    m.out_bf16 = p.out_bf16;
+    for (int a = 0; a < 3; ++a) m.os[a] = p.os[a];
+    const int64_t rows = (int64_t)p.B * p.H_q * p.L_q;
+    hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, static_cast<hipStream_t>(stream), m);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_forward: merge launch failed: %s", hipGetErrorString(e));
+  }
   return AE_OK;
 }
 
@@ -223,6 +312,22 @@ ae_status_t ae_attn_forward_stats(const ae_attn_t* h, const void* Q, const void*
   if (norm != ae::NORM_SOFTMAX && norm != ae::NORM_ABSSUM && norm != ae::NORM_ABS_OF_SUM)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_forward_stats: this normalization keeps no row statistic");
   return forward_impl(h, Q, K, V, O, static_cast<float*>(stats), stream);
+}
+
+ae_status_t ae_attn_workspace_bytes(const ae_attn_t* h, size_t* bytes) {
+  if (!h || !bytes) return fail(AE_ERR_INVALID_ARG, "ae_attn_workspace_bytes: null argument");
+  *bytes = h->ws_bytes;
+  return AE_OK;
+}
+
+ae_status_t ae_attn_forward_split(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, void* stats,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_split: null handle");
+  if (stats && (((uintptr_t)stats & 3) || stats == O || stats == Q || stats == K || stats == V))
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_split: stats must be 4-byte aligned and must not alias another buffer");
+  if (h->params.n_splits > 1 && (workspace == O || workspace == Q || workspace == K || workspace == V || (stats && workspace == stats)))
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_split: the workspace aliases another buffer");
+  return forward_impl(h, Q, K, V, O, static_cast<float*>(stats), stream, workspace, workspace_bytes);
 }
 
 ae_status_t ae_attn_destroy(ae_attn_t* h) {

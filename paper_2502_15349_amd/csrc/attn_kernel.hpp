@@ -76,6 +76,13 @@ struct Params {
   int neg_q;       // scale < 0: the sign is moved onto Q (exact for bf16)
   int out_bf16;    // O holds bf16 instead of fp32
   int window;      // sliding-window kernels: key j is also hidden if j <= i + (L_k - L_q) - window
+  // Split keys (n_splits > 1): the launch holds n_splits copies of the base_grid items; copy c
+  // walks key tiles [c * split_tiles, (c + 1) * split_tiles) only and writes its normalised
+  // partial rows (fp32, [split, B, H_q, L_q, D_v]) and their log-sum-exp ([split, B, H_q, L_q])
+  // to the workspace instead of O / stats; attn_merge_kernel combines them.
+  int n_splits, split_tiles, base_grid;
+  float* ws_o;
+  float* ws_lse;
   // sigmoid with a bias small enough for 2^(-b2) to be a normal number: Q is
   // multiplied by -scale*log2(e) when loaded (rounded to bf16 again), so that the
   // MFMA delivers the exponent itself and 1 + 2^(-b2) * 2^x is a single FMA
@@ -681,7 +688,11 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // tiles at the same time, and with a single group per XCD all 32 CUs would
   // queue on the few L2 channels that hold the current tile.  Within a group the
   // causal tiles with the most key tiles are issued first.
-  const int w = blockIdx.x;
+  int w = blockIdx.x, split = 0;
+  if (p.n_splits > 1) {
+    split = w / p.base_grid;
+    w -= split * p.base_grid;
+  }
   const int per_group = p.n_qtiles * p.g;
   const int I = p.interleave;
   const int slot = w >> 3;
@@ -705,8 +716,19 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   const __bf16* qbase = p.Q + b * p.qs[0] + hq * p.qs[1];
   const __bf16* kbase = p.K + b * p.ks[0] + hkv * p.ks[1];
   const __bf16* vbase = p.V + b * p.vs[0] + hkv * p.vs[1];
-  // byte address of the head's first output row (O holds 4- or 2-byte elements)
-  char* obase = static_cast<char*>(p.O) + (b * p.os[0] + hq * p.os[1]) * (p.out_bf16 ? 2 : 4);
+  // byte address of the head's first output row (O holds 4- or 2-byte elements), its row
+  // stride in elements, and the head's row statistics; with split keys the workspace's
+  bool o_bf16 = p.out_bf16 != 0;
+  int64_t o_row = p.os[2];
+  char* obase = static_cast<char*>(p.O) + (b * p.os[0] + hq * p.os[1]) * (o_bf16 ? 2 : 4);
+  float* stats = p.stats ? p.stats + ((int64_t)b * p.H_q + hq) * p.L_q : nullptr;
+  if (p.n_splits > 1) {
+    const int64_t head = ((int64_t)split * p.B + b) * p.H_q + hq;
+    o_bf16 = false;
+    o_row = C::DV;
+    obase = reinterpret_cast<char*>(p.ws_o + head * p.L_q * C::DV);
+    stats = p.ws_lse + head * p.L_q;
+  }
 
   RowState<C> st;
   st.m = -INFINITY;
@@ -723,8 +745,8 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     kmax = max(0, min(p.L_k, i_wg + C::BLOCK_M + off));
     kmax_w = max(0, min(p.L_k, iw0 + 32 + off));
   }
-  const int n_tiles = (kmax + C::BLOCK_N - 1) / C::BLOCK_N;  // LDS tiles (workgroup)
-  const int n_vis = (kmax_w + C::SUB_N - 1) / C::SUB_N;      // visible sub-tiles (wave)
+  int n_tiles = (kmax + C::BLOCK_N - 1) / C::BLOCK_N;  // LDS tiles (workgroup): tiles [jt0, n_tiles) are walked
+  int n_vis = (kmax_w + C::SUB_N - 1) / C::SUB_N;      // visible sub-tiles (wave): those below n_vis
   // The walk over the key tiles.  Without a window: tiles 0 .. n_tiles-1 in order.  With a
   // sliding window the workgroup needs tiles jt0 .. n_tiles-1 (jt0: tile of the first key its
   // first row sees) and a wave's own rows start at sub-tile u_first.  The order of the key
@@ -737,6 +759,11 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // (it would only wait at the barriers otherwise), which keeps its fragment ring, its LDS
   // addresses and its scores in step with the others.
   int jt0 = 0, jtm = 0, u_first = 0;
+  if (!C::WINDOW && p.n_splits > 1) {  // this workgroup's share of the key tiles
+    jt0 = jtm = split * p.split_tiles;
+    n_tiles = min(n_tiles, jt0 + p.split_tiles);
+    n_vis = min(n_vis, 2 * n_tiles);
+  }
   if (C::WINDOW) {
     jt0 = max(0, i_wg + off - p.window + 1) / C::BLOCK_N;
     jtm = (max(0, i_wg + (C::WAVES - 1) * 32 + off - p.window + 32) + C::BLOCK_N - 1) / C::BLOCK_N;
@@ -744,7 +771,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     u_first = max(0, iw0 + off - p.window + 1) / C::SUB_N;
   }
   const int n_walk = max(n_tiles - jt0, 0), n_lead = n_tiles - jtm;  // positions in the walk; those before the rotation
-  auto tile_at = [&](int pos) { return C::WINDOW ? (pos < n_lead ? jtm + pos : jt0 + (pos - n_lead)) : pos; };
+  auto tile_at = [&](int pos) { return C::WINDOW ? (pos < n_lead ? jtm + pos : jt0 + (pos - n_lead)) : jt0 + pos; };
   // LDS: STAGES stages of a K buffer and a V buffer; tile j lives in stage j % STAGES.
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const uint32_t vlds0 = lds0 + C::K_BYTES;
@@ -869,7 +896,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     // every wave has read its rows before tile 1 overwrites them
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     copy_slice(One{}, Zero{}, n_walk > 1 ? tile_at(1) : tile_at(0), 1);
-    if (C::WINDOW || n_vis > 0) score_block<C>(kaddr, 0, qf, s_a);
+    if (C::WINDOW || n_vis > 2 * jt0) score_block<C>(kaddr, 0, qf, s_a);
   }
 
   // ---- key loop ------------------------------------------------------------------------
@@ -903,7 +930,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       kl.b2 = fast_exp2(-2.f * g2);
       kl.b3 = fast_exp2(-3.f * g2);
     }
-    if (C::WINDOW || n_vis > 0) static_for<0, C::PF>([&](auto nc) { kl.template fetch<decltype(nc)::value>(); });
+    if (C::WINDOW || n_vis > 2 * jt0) static_for<0, C::PF>([&](auto nc) { kl.template fetch<decltype(nc)::value>(); });
     const bool trailing = wave >= C::WAVES / 2;  // second wave of its SIMD
     int buf = 0;
 
@@ -1017,7 +1044,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     } else {
       inv = 1.f / fmaxf(fabsf(l), 1.f);
     }
-    if (p.stats != nullptr && half == 0 && i < p.L_q) p.stats[((int64_t)b * p.H_q + hq) * p.L_q + i] = stat;
+    if (stats != nullptr && half == 0 && i < p.L_q) stats[i] = stat;
   }
   // A lane holds 4-column pieces of one output row, 32 bytes apart from its
   // partner's: stored directly, every instruction would touch 32 rows with 32
@@ -1044,8 +1071,8 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       const int row = k * (64 / CPRO) + lane / CPRO, pc = lane % CPRO;
       const f32x4 v = lds_read16(obuf + row * (OC * 4) + ((pc ^ (row & 15)) * 16));
       if (iw0 + row < p.L_q) {
-        const int64_t e = (int64_t)(iw0 + row) * p.os[2] + pass * OC + pc * 4;  // element offset in the head
-        if (p.out_bf16) {
+        const int64_t e = (int64_t)(iw0 + row) * o_row + pass * OC + pc * 4;  // element offset in the head
+        if (o_bf16) {
           bf16x4 h;
 #pragma unroll
           for (int k4 = 0; k4 < 4; ++k4) h[k4] = (__bf16)v[k4];

@@ -126,6 +126,36 @@ def test_sliding_window_descriptor_checks():
     assert ei.value.status == A.AE_ERR_UNSUPPORTED
 
 
+def test_split_keys_descriptor_and_workspace():
+    from paper_2502_15349_amd import ae_attn as A
+    d = dict(B=2, H_q=4, H_kv=2, L_q=3, L_k=1000, D_qk=128, D_v=128, scale=0.1)
+    h = A.ae_attn_create(**d)
+    assert A.ae_attn_workspace_bytes(h) == 0
+    A.ae_attn_destroy(h)
+    h = A.ae_attn_create(**d, kv_splits=4)          # 16 key tiles -> 4 ranges of 4
+    try:
+        assert A.ae_attn_workspace_bytes(h) == 4 * (2 * 4 * 3) * (128 + 1) * 4
+        with pytest.raises(A.AeAttnError) as ei:     # the plain entry point has no workspace to give
+            A.ae_attn_forward(h, 256, 512, 768, 1024)
+        assert ei.value.status == A.AE_ERR_INVALID_ARG
+        for ws, nbytes in ((0, 1 << 20), (4096 + 8, 1 << 20), (4096, 100), (1024, 1 << 20)):
+            with pytest.raises(A.AeAttnError) as ei:
+                A.ae_attn_forward_split(h, 256, 512, 768, 1024, 0, ws, nbytes)
+            assert ei.value.status == A.AE_ERR_INVALID_ARG
+    finally:
+        A.ae_attn_destroy(h)
+    h = A.ae_attn_create(**d, kv_splits=100)        # more ranges than tiles: one tile each
+    assert A.ae_attn_workspace_bytes(h) == 16 * (2 * 4 * 3) * (128 + 1) * 4
+    A.ae_attn_destroy(h)
+    for bad in (dict(norm="sigmoid"), dict(mask="sliding_window", window=5)):
+        with pytest.raises(A.AeAttnError) as ei:
+            A.ae_attn_create(**d, kv_splits=4, **bad)
+        assert ei.value.status == A.AE_ERR_UNSUPPORTED
+    with pytest.raises(A.AeAttnError) as ei:
+        A.ae_attn_create(**d, kv_splits=-1)
+    assert ei.value.status == A.AE_ERR_INVALID_ARG
+
+
 def test_padded_strides_accepted():
     from paper_2502_15349_amd import ae_attn as A
     h = A.ae_attn_create(**_ok_desc(), q_stride=(100 * 4 * 136, 100 * 136, 136))

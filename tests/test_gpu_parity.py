@@ -310,6 +310,40 @@ def test_sliding_window_full_size_sampled(A):
     _sampled_full_config(A, w)
 
 
+@pytest.mark.parametrize("dims", DIMS, ids=lambda d: f"d{d[0]}_{d[1]}")
+@pytest.mark.parametrize("Lq,Lk,mask,splits", [(1, 2048, "none", 8), (1, 4000, "causal", 32), (5, 1000, "causal", 3),
+                                               (1, 100, "none", 4), (300, 700, "causal", 5), (7, 64, "none", 2)])
+def test_split_keys(A, dims, Lq, Lk, mask, splits):
+    """kv_splits > 1 (decoding shapes and a few others): partial results per key range plus the
+    merge kernel against the oracle; the row statistic too; GQA 4:1."""
+    from oracle import row_stats_head
+    w = Workload("split", 19, 2, 8, 2, Lq, Lk, dims[0], dims[1], mask=mask)
+    Q, K, V = make_inputs(w)
+    dev = torch.device("cuda:0")
+    st = torch.zeros((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev)
+    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), stats=st, kv_splits=splits)
+    torch.cuda.synchronize()
+    check(O.cpu().double().numpy(), oracle_run(w, Q, K, V), f"split {splits}")
+    got = st.cpu().double().numpy()
+    for b in range(w.B):
+        for h in range(w.H_q):
+            ref = row_stats_head(Q[b, h], K[b, h // 4], scale=w.scale_value, norm="softmax", mask=w.oracle_mask())
+            assert np.abs(got[b, h] - ref).max() <= 1e-3
+    # bf16 output through the merge kernel: the fp32 merge result rounded
+    Ob = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), kv_splits=splits, out_dtype=torch.bfloat16)
+    assert torch.equal(Ob, O.to(torch.bfloat16))
+
+
+def test_split_keys_decode_full_size(A):
+    """The paper's decoding row (Table 2: one query row, 16 heads, 192/128) at 8k keys, batch 8."""
+    w = Workload("decode", 20, 8, 16, 16, 1, 8192, 192, 128, mask="causal")
+    Q, K, V = make_inputs(w)
+    dev = torch.device("cuda:0")
+    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), kv_splits=16)
+    torch.cuda.synchronize()
+    check(O.cpu().double().numpy(), oracle_run(w, Q, K, V), "decode")
+
+
 def test_negative_scale_and_large_scores(A):
     w = Workload("neg", 14, 1, 2, 2, 150, 150, 64, 64, mask="causal", scale=-0.125)
     Q, K, V = make_inputs(w)
