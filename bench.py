@@ -147,6 +147,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--table2", action="store_true",
                     help="time the parallel-pattern rows of the paper's Table 2 (batch 1/8, sequence 2k/4k/8k) and print them")
+    ap.add_argument("--decode", action="store_true",
+                    help="time the paper's decoding row (Table 2: one query row, 16 heads, 192/128) with and without "
+                         "split keys and print GB/s against the HBM peak")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device-to-device copy of this many MiB "
                          "(reference reading for the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
@@ -179,6 +182,44 @@ def main():
         return
     if a.calib_mfma > 0:
         print(json.dumps(calib_mfma(A, torch, a.calib_mfma)))
+        return
+    if a.decode:
+        # Decoding is bound by reading K and V once: bytes / time against the 8 TB/s HBM peak.
+        from paper_2502_15349_amd.workloads import Workload
+        rows = []
+        for batch in (1, 8):
+            for seq in (2048, 4096, 8192):
+                w = Workload(f"t2_decode_dsv2_lite_b{batch}_s{seq}", 200 + len(rows), batch, 16, 16, 1, seq, 192, 128, mask="causal")
+                Qc, Kc, Vc = make_inputs(w)
+                Q, K, V = Qc.to(dev), Kc.to(dev), Vc.to(dev)
+                res = {}
+                for splits in (0, max(2, min(seq // 256, 1024 // (batch * 16)))):
+                    O = torch.empty((w.B, w.H_q, w.L_q, w.D_v), dtype=torch.float32, device=dev)
+                    h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
+                                         scale=w.scale_value, mask=w.mask, kv_splits=splits)
+                    need = A.ae_attn_workspace_bytes(h)
+                    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+                    st = torch.cuda.current_stream()
+                    args = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), 0, ws.data_ptr(), ws.numel(), st.cuda_stream)
+                    for _ in range(200):
+                        A.ae_attn_forward_split(*args)
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(st)
+                    for _ in range(200):
+                        A.ae_attn_forward_split(*args)
+                    e1.record(st)
+                    torch.cuda.synchronize()
+                    A.ae_attn_destroy(h)
+                    res[splits] = (e0.elapsed_time(e1) / 200, parity_sample(w, Q, K, V, O, n_rows=1)["max_abs"])
+                byts = w.compulsory_bytes()
+                (s0, (t0, p0)), (s1, (t1, p1)) = sorted(res.items())
+                rows.append({"workload": w.name, "B": batch, "L_k": seq, "bytes": byts, "unsplit_ms": round(t0, 5),
+                             "kv_splits": s1, "split_ms": round(t1, 5), "split_GBps": round(byts / t1 / 1e6, 1),
+                             "frac_of_hbm_peak": round(byts / t1 / 1e6 / 8000.0, 4), "parity_max_abs": max(p0, p1)})
+                print(f"# {w.name:34s} unsplit {t0:8.4f} ms | {s1:3d} splits {t1:8.4f} ms  {byts / t1 / 1e6:8.1f} GB/s "
+                      f"({100 * byts / t1 / 1e6 / 8000.0:4.1f} % of 8 TB/s)  max_abs {max(p0, p1):.2e}", file=sys.stderr, flush=True)
+        print(json.dumps({"decode": rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16", "data": "synthetic"}))
         return
     if a.table2:
         # Not the contract line: the paper's own microbenchmark grid, one row per shape.
