@@ -745,6 +745,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     kmax = max(0, min(p.L_k, i_wg + C::BLOCK_M + off));
     kmax_w = max(0, min(p.L_k, iw0 + 32 + off));
   }
+  if (iw0 >= p.L_q) kmax_w = 0;  // a wave past the last query row only helps with the copies
   int n_tiles = (kmax + C::BLOCK_N - 1) / C::BLOCK_N;  // LDS tiles (workgroup): tiles [jt0, n_tiles) are walked
   int n_vis = (kmax_w + C::SUB_N - 1) / C::SUB_N;      // visible sub-tiles (wave): those below n_vis
   // The walk over the key tiles.  Without a window: tiles 0 .. n_tiles-1 in order.  With a
