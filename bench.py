@@ -27,10 +27,10 @@ PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flo
 # each scaled by the same counter's reading for a 1 GiB device copy; the runs and their
 # commands are in profiles/attn_fwd_<workload>.txt.  null where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "c2_gqa_causal_softmax": int((114.4 + 134.2) * 1e6),
-    "c3_sigmoid_causal": int((414.7 + 134.2) * 1e6),
-    "c4_retnet": int((341.1 + 138.3) * 1e6),
-    "c5_mla_causal_softmax": int((2310.1 + 536.9) * 1e6),
+    "c2_gqa_causal_softmax": int((114.8 + 134.2) * 1e6),
+    "c3_sigmoid_causal": int((407.7 + 134.2) * 1e6),
+    "c4_retnet": int((344.1 + 138.3) * 1e6),
+    "c5_mla_causal_softmax": int((2275.0 + 536.9) * 1e6),
 }
 
 
