@@ -344,6 +344,38 @@ def test_split_keys_decode_full_size(A):
     check(O.cpu().double().numpy(), oracle_run(w, Q, K, V), "decode")
 
 
+def test_seeded_random_shapes(A):
+    """48 seeded draws over shapes (ragged, L_q != L_k in both directions), head grouping, head dims,
+    (norm, mod, mask) combinations, window sizes and split counts, each against the oracle."""
+    rng = np.random.default_rng(20250222)
+    combos = [("softmax", "none"), ("softmax", "bias"), ("sigmoid", "bias"), ("abssum", "none"), ("abssum", "head_decay"),
+              ("abs_of_sum", "head_decay"), ("none", "relu"), ("none", "none")]
+    dev = torch.device("cuda:0")
+    for case in range(48):
+        dims = DIMS[int(rng.integers(len(DIMS)))]
+        norm, mod = combos[int(rng.integers(len(combos)))]
+        g = int(rng.choice([1, 2, 4]))
+        H_kv = int(rng.integers(1, 3))
+        Lq, Lk = int(rng.integers(1, 600)), int(rng.integers(1, 700))
+        mask = "causal" if mod == "head_decay" else str(rng.choice(["none", "causal", "sliding_window"]))
+        if mask == "sliding_window" and norm not in ("softmax", "sigmoid", "none"):
+            mask = "causal"
+        if mask == "sliding_window" and mod == "relu":
+            mask = "none"
+        window = int(rng.integers(1, 400)) if mask == "sliding_window" else 0
+        splits = int(rng.integers(2, 9)) if (norm == "softmax" and mask != "sliding_window" and rng.random() < 0.5) else 0
+        w = Workload(f"rand{case}", 300 + case, int(rng.integers(1, 3)), g * H_kv, H_kv, Lq, Lk, dims[0], dims[1],
+                     score_mod=mod, norm=norm, mask=mask, window=window, bias=float(rng.uniform(-2, 1)),
+                     decay=(mod == "head_decay"), scale=(0.01 if norm == "none" else None))
+        print(f"case {case}: {w} splits {splits}", flush=True)
+        Q, K, V = make_inputs(w)
+        O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), kv_splits=splits)
+        torch.cuda.synchronize()
+        got, ref = O.cpu().double().numpy(), oracle_run(w, Q, K, V)
+        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+        check(got / rs, ref / rs, f"random case {case}")
+
+
 def test_negative_scale_and_large_scores(A):
     w = Workload("neg", 14, 1, 2, 2, 150, 150, 64, 64, mask="causal", scale=-0.125)
     Q, K, V = make_inputs(w)
