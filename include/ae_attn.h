@@ -70,6 +70,7 @@ typedef enum {
 typedef enum { AE_OUT_F32 = 0, AE_OUT_BF16 = 1 } ae_out_dtype_t;
 
 #define AE_MAX_DECAY_HEADS 256
+#define AE_KV_SPLITS_AUTO (-1) /* ae_attn_desc_t.kv_splits: let the library decide */
 
 /*
  * Problem descriptor (host memory, copied by ae_attn_create).
@@ -101,7 +102,11 @@ typedef struct {
                           a second kernel combines -- for few query rows and
                           many keys (decoding).  AE_NORM_SOFTMAX with
                           AE_MASK_NONE or AE_MASK_CAUSAL only; such a handle
-                          runs through ae_attn_forward_split.                   */
+                          runs through ae_attn_forward_split.
+                          AE_KV_SPLITS_AUTO: the library picks (it splits only
+                          where it may and where the query tiles leave most of
+                          the device idle); ask ae_attn_workspace_bytes whether
+                          it did.                                               */
   int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3];
 } ae_attn_desc_t;
 

@@ -2,6 +2,7 @@
 // validation, kernel/tile selection, launch.  See include/ae_attn.h.
 #include "../../include/ae_attn.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -122,8 +123,8 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     return fail(AE_ERR_INVALID_ARG, "ae_attn_create: the sliding window must hold at least one key");
   if (d->out_dtype != AE_OUT_F32 && d->out_dtype != AE_OUT_BF16)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown out_dtype %d", (int)d->out_dtype);
-  if (d->kv_splits < 0 || d->kv_splits > 256)
-    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: kv_splits must be between 0 and 256");
+  if (d->kv_splits < AE_KV_SPLITS_AUTO || d->kv_splits > 256)
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: kv_splits must be AE_KV_SPLITS_AUTO or between 0 and 256");
   if (d->kv_splits > 1 && (d->norm != AE_NORM_SOFTMAX || d->mask == AE_MASK_SLIDING_WINDOW))
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: split keys come with softmax and the masks NONE and CAUSAL only");
   if (d->score_mod == AE_MOD_BIAS && !std::isfinite(d->bias))
@@ -234,9 +235,22 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   p.split_tiles = 0;
   p.base_grid = (int)grid;
   h->ws_bytes = 0;
-  if (d->kv_splits > 1) {
+  int kv_splits = d->kv_splits;
+  if (kv_splits == AE_KV_SPLITS_AUTO) {
+    // Measured on decoding shapes (one query row, 16 heads, 2k-8k keys, batch 1 and 8): the
+    // fastest launches hold some 128-256 workgroups with at least 8 key tiles each; more
+    // ranges cost a start and an end of a workgroup apiece.  Only where the keys may be split
+    // and the query tiles alone leave most of the device idle.
+    kv_splits = 0;
+    if (d->norm == AE_NORM_SOFTMAX && d->mask != AE_MASK_SLIDING_WINDOW && grid < 160) {
+      const int key_tiles = (d->L_k + h->kernel->block_n - 1) / h->kernel->block_n;
+      const int64_t want = (192 + grid / 2) / grid;  // round(192 / workgroups)
+      kv_splits = (int)std::min<int64_t>(std::min<int64_t>(want, key_tiles / 8), 256);
+    }
+  }
+  if (kv_splits > 1) {
     const int key_tiles = (d->L_k + h->kernel->block_n - 1) / h->kernel->block_n;
-    p.split_tiles = (key_tiles + d->kv_splits - 1) / d->kv_splits;
+    p.split_tiles = (key_tiles + kv_splits - 1) / kv_splits;
     p.n_splits = (key_tiles + p.split_tiles - 1) / p.split_tiles;
     if (p.n_splits > 1) {
       if (grid * p.n_splits > 0x7fffffffLL) {

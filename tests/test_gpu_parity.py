@@ -339,9 +339,11 @@ def test_split_keys_decode_full_size(A):
     w = Workload("decode", 20, 8, 16, 16, 1, 8192, 192, 128, mask="causal")
     Q, K, V = make_inputs(w)
     dev = torch.device("cuda:0")
-    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), kv_splits=16)
-    torch.cuda.synchronize()
-    check(O.cpu().double().numpy(), oracle_run(w, Q, K, V), "decode")
+    ref = oracle_run(w, Q, K, V)
+    for splits in (16, -1):   # -1: the library picks the number of key ranges
+        O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), kv_splits=splits)
+        torch.cuda.synchronize()
+        check(O.cpu().double().numpy(), ref, f"decode, kv_splits {splits}")
 
 
 def test_seeded_random_shapes(A):
