@@ -210,19 +210,53 @@ def main():
                         A.ae_attn_forward_split(*args)
                     e1.record(st)
                     torch.cuda.synchronize()
+                    ms = e0.elapsed_time(e1) / 200
+                    par = parity_sample(w, Q, K, V, O, n_rows=1)["max_abs"]
+                    if splits == -1:
+                        # The same launches replayed from a HIP graph (the library allocates nothing and clears
+                        # nothing, so it can be captured): 50 calls per graph, 4 replays timed, every replay's
+                        # output compared with the eager one.
+                        side = torch.cuda.Stream()
+                        gargs = args[:-1] + (side.cuda_stream,)
+                        eager = O.clone()
+                        graph = torch.cuda.CUDAGraph()
+                        side.wait_stream(st)
+                        with torch.cuda.graph(graph, stream=side):
+                            for _ in range(50):
+                                A.ae_attn_forward_split(*gargs)
+                        torch.cuda.synchronize()
+                        graph.replay()
+                        torch.cuda.synchronize()
+                        same = bool(torch.equal(O, eager))
+                        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        for _ in range(4):
+                            O.zero_()
+                            graph.replay()
+                            torch.cuda.synchronize()
+                            same = same and bool(torch.equal(O, eager))
+                        g0.record(st)
+                        for _ in range(4):
+                            graph.replay()
+                        g1.record(st)
+                        torch.cuda.synchronize()
+                        graph_ms = g0.elapsed_time(g1) / 200
+                        del graph
                     A.ae_attn_destroy(h)
-                    res[splits] = (e0.elapsed_time(e1) / 200, parity_sample(w, Q, K, V, O, n_rows=1)["max_abs"])
+                    res[splits] = (ms, par)
                 byts = w.compulsory_bytes()
                 t0, p0 = res[0]
                 s1 = min((k for k in res if k > 0), key=lambda k: res[k][0])   # the fastest split count of the sweep
                 t1, p1 = res[s1]
                 sweep = {("auto" if k < 0 else str(k)): round(v[0], 5) for k, v in sorted(res.items())}
                 rows.append({"workload": w.name, "B": batch, "L_k": seq, "bytes": byts, "unsplit_ms": round(t0, 5),
-                             "kv_splits": s1, "split_ms": round(t1, 5), "auto_ms": round(res[-1][0], 5), "split_GBps": round(byts / t1 / 1e6, 1),
+                             "kv_splits": s1, "split_ms": round(t1, 5), "auto_ms": round(res[-1][0], 5),
+                             "auto_graph_ms": round(graph_ms, 5), "graph_replays_equal_eager": same,
+                             "auto_graph_GBps": round(byts / graph_ms / 1e6, 1), "split_GBps": round(byts / t1 / 1e6, 1),
                              "frac_of_hbm_peak": round(byts / t1 / 1e6 / 8000.0, 4), "parity_max_abs": max(v[1] for v in res.values()),
                              "ms_by_kv_splits": sweep})
                 print(f"# {w.name:34s} unsplit {t0:8.4f} ms | {s1:3d} splits {t1:8.4f} ms  {byts / t1 / 1e6:8.1f} GB/s "
-                      f"({100 * byts / t1 / 1e6 / 8000.0:4.1f} % of 8 TB/s)  max_abs {max(v[1] for v in res.values()):.2e}  sweep {sweep}",
+                      f"({100 * byts / t1 / 1e6 / 8000.0:4.1f} % of 8 TB/s)  max_abs {max(v[1] for v in res.values()):.2e}  "
+                      f"auto from a HIP graph {graph_ms:7.4f} ms {byts / graph_ms / 1e6:7.1f} GB/s (replays equal eager: {same})  sweep {sweep}",
                       file=sys.stderr, flush=True)
         print(json.dumps({"decode": rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16", "data": "synthetic"}))
         return

@@ -346,6 +346,60 @@ def test_split_keys_decode_full_size(A):
         check(O.cpu().double().numpy(), ref, f"decode, kv_splits {splits}")
 
 
+def test_hip_graph_replays(A):
+    """The entry points allocate nothing and clear nothing, so their launches can be captured into a HIP
+    graph.  Each graph (plain, with row statistics, split keys) is replayed four times with new Q values
+    and eager work between the replays; every replay must equal the eager launch on the same inputs bit
+    for bit, and the first one is also held against the oracle."""
+    dev = torch.device("cuda:0")
+    w = Workload("graph", 31, 2, 4, 2, 300, 1333, 128, 128, mask="causal")
+    Qc, Kc, Vc = make_inputs(w)
+    Q, K, V = Qc.to(dev), Kc.to(dev), Vc.to(dev)
+    ref = oracle_run(w, Qc, Kc, Vc)
+    side = torch.cuda.Stream()
+    for name, splits, with_stats in (("plain", 0, False), ("stats", 0, True), ("split", 4, True)):
+        print(f"graph case {name}", flush=True)
+        h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
+                             scale=w.scale_value, mask=w.mask, kv_splits=splits)
+        ws = torch.empty(max(A.ae_attn_workspace_bytes(h), 16), dtype=torch.uint8, device=dev)
+        Qg = Q.clone()
+        Og, Oe = (torch.zeros((w.B, w.H_q, w.L_q, w.D_v), dtype=torch.float32, device=dev) for _ in range(2))
+        Sg, Se = (torch.zeros((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev) for _ in range(2))
+
+        def launch(O, S, stream):
+            sp = S.data_ptr() if with_stats else 0
+            if splits:
+                A.ae_attn_forward_split(h, Qg.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), sp,
+                                        ws.data_ptr(), ws.numel(), stream.cuda_stream)
+            elif with_stats:
+                A.ae_attn_forward_stats(h, Qg.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), sp, stream.cuda_stream)
+            else:
+                A.ae_attn_forward(h, Qg.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), stream.cuda_stream)
+
+        graph = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            launch(Og, Sg, side)
+        torch.cuda.synchronize()
+        for replay in range(4):
+            if replay:
+                Qg.copy_((Q.float() * (1.0 - 0.2 * replay)).to(torch.bfloat16).roll(replay, dims=2))
+            Og.zero_()
+            Sg.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            launch(Oe, Se, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            assert torch.equal(Og, Oe), f"{name}: replay {replay} differs from the eager launch"
+            if with_stats:
+                assert torch.equal(Sg, Se), f"{name}: replay {replay} statistics differ from the eager launch"
+            if replay == 0:
+                check(Og.cpu().double().numpy(), ref, f"graph {name}")
+        del graph
+        A.ae_attn_destroy(h)
+
+
 def test_seeded_random_shapes(A):
     """48 seeded draws over shapes (ragged, L_q != L_k in both directions), head grouping, head dims,
     (norm, mod, mask) combinations, window sizes and split counts, each against the oracle."""
