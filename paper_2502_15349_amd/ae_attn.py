@@ -48,6 +48,10 @@ _lib.ae_attn_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
 _lib.ae_attn_workspace_bytes.restype = C.c_int
 _lib.ae_attn_forward_split.argtypes = [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
 _lib.ae_attn_forward_split.restype = C.c_int
+_lib.ae_attn_backward_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+_lib.ae_attn_backward_workspace_bytes.restype = C.c_int
+_lib.ae_attn_backward.argtypes = [C.c_void_p] * 11 + [C.c_size_t, C.c_void_p]
+_lib.ae_attn_backward.restype = C.c_int
 _lib.ae_attn_destroy.argtypes = [C.c_void_p]
 _lib.ae_attn_destroy.restype = C.c_int
 _lib.ae_attn_query.argtypes = [C.c_void_p] + [C.POINTER(C.c_int32)] * 5
@@ -117,6 +121,20 @@ def ae_attn_forward_split(handle: int, Q: int, K: int, V: int, O: int, stats: in
                           workspace_bytes: int, stream: int = 0) -> None:
     """Forward of a handle created with kv_splits > 1; stats may be 0 (not written)."""
     _check(_lib.ae_attn_forward_split(handle, Q, K, V, O, stats, workspace, workspace_bytes, stream))
+
+
+def ae_attn_backward_workspace_bytes(handle: int) -> int:
+    """Bytes of device workspace ae_attn_backward needs for this handle."""
+    n = C.c_size_t(0)
+    _check(_lib.ae_attn_backward_workspace_bytes(handle, C.byref(n)))
+    return int(n.value)
+
+
+def ae_attn_backward(handle: int, Q: int, K: int, V: int, O: int, dO: int, stats: int, dQ: int, dK: int, dV: int,
+                     workspace: int, workspace_bytes: int, stream: int = 0) -> None:
+    """Device addresses throughout: dQ, dK, dV (fp32, contiguous) receive the gradients for the upstream
+    gradient dO (bf16, contiguous); O and stats are what ae_attn_forward_stats wrote."""
+    _check(_lib.ae_attn_backward(handle, Q, K, V, O, dO, stats, dQ, dK, dV, workspace, workspace_bytes, stream))
 
 
 def ae_attn_forward_stats(handle: int, Q: int, K: int, V: int, O: int, stats: int, stream: int = 0) -> None:
@@ -203,6 +221,42 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
     finally:
         ae_attn_destroy(h)
     return out
+
+
+def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0.0, norm="softmax", mask="none",
+                       stream=None, workspace=None):
+    """Runs the HIP backward pass on device tensors: Q, K, V bf16 [B, H, L, D] (last dim contiguous), O the
+    forward output (fp32 or bf16), dO bf16 contiguous, stats the fp32 row statistic of the forward pass (O and
+    stats may be None for sigmoid).  Returns (dQ, dK, dV) as contiguous fp32 tensors."""
+    import torch
+
+    if not (Q.is_cuda and K.is_cuda and V.is_cuda and dO.is_cuda):
+        raise ValueError("attention_backward needs device tensors; there is no CPU path")
+    B, H_q, L_q, D_qk = Q.shape
+    _, H_kv, L_k, D_v = V.shape
+    if dO.dtype != torch.bfloat16 or tuple(dO.shape) != (B, H_q, L_q, D_v) or not dO.is_contiguous():
+        raise ValueError("dO must be a contiguous bf16 tensor [B, H_q, L_q, D_v]")
+    if stats is not None and (stats.dtype != torch.float32 or tuple(stats.shape) != (B, H_q, L_q) or not stats.is_contiguous()):
+        raise ValueError("stats must be a contiguous fp32 tensor [B, H_q, L_q]")
+    o_dtype, o_stride = ("f32", (0, 0, 0)) if O is None else ("bf16" if O.dtype == torch.bfloat16 else "f32", O.stride()[:3])
+    h = ae_attn_create(B=B, H_q=H_q, H_kv=H_kv, L_q=L_q, L_k=L_k, D_qk=D_qk, D_v=D_v, scale=scale,
+                       score_mod=score_mod, bias=bias, norm=norm, mask=mask, q_stride=Q.stride()[:3],
+                       k_stride=K.stride()[:3], v_stride=V.stride()[:3], o_stride=o_stride, out_dtype=o_dtype)
+    try:
+        s = torch.cuda.current_stream(Q.device) if stream is None else stream
+        with torch.cuda.device(Q.device):
+            dQ = torch.empty((B, H_q, L_q, D_qk), dtype=torch.float32, device=Q.device)
+            dK = torch.empty((B, H_kv, L_k, D_qk), dtype=torch.float32, device=Q.device)
+            dV = torch.empty((B, H_kv, L_k, D_v), dtype=torch.float32, device=Q.device)
+            need = ae_attn_backward_workspace_bytes(h)
+            if workspace is None:
+                workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+            ae_attn_backward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), 0 if O is None else O.data_ptr(), dO.data_ptr(),
+                             0 if stats is None else stats.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                             workspace.data_ptr(), workspace.numel() * workspace.element_size(), s.cuda_stream)
+    finally:
+        ae_attn_destroy(h)
+    return dQ, dK, dV
 
 
 def run_workload(w, Q, K, V, out=None, out_dtype=None, stats=None, kv_splits=0):

@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <new>
 
+#include "bwd.hpp"
 #include "dispatch.hpp"
 
 namespace {
@@ -342,6 +343,74 @@ ae_status_t ae_attn_forward_split(const ae_attn_t* h, const void* Q, const void*
   if (h->params.n_splits > 1 && (workspace == O || workspace == Q || workspace == K || workspace == V || (stats && workspace == stats)))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_split: the workspace aliases another buffer");
   return forward_impl(h, Q, K, V, O, static_cast<float*>(stats), stream, workspace, workspace_bytes);
+}
+
+ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t* h, size_t* bytes) {
+  if (!h || !bytes) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward_workspace_bytes: null argument");
+  *bytes = h->desc.norm == AE_NORM_SOFTMAX ? (size_t)h->desc.B * h->desc.H_q * h->desc.L_q * sizeof(float) : 0;
+  return AE_OK;
+}
+
+ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                             const void* stats, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: null handle");
+  const ae_attn_desc_t& d = h->desc;
+  const int norm = h->kernel->norm;
+  if (!ae::backward_supported(d.D_qk, d.D_v, norm) || (d.score_mod != AE_MOD_NONE && d.score_mod != AE_MOD_BIAS) ||
+      (d.mask != AE_MASK_NONE && d.mask != AE_MASK_CAUSAL))
+    return fail(AE_ERR_UNSUPPORTED,
+                "ae_attn_backward: built for softmax and sigmoid with score_mod NONE or BIAS and masks NONE or CAUSAL");
+  const bool softmax = norm == ae::NORM_SOFTMAX;
+  if (!Q || !K || !V || !dO || !dQ || !dK || !dV || (softmax && (!O || !stats || !workspace)))
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: null device pointer");
+  if ((((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)dO | (uintptr_t)dQ | (uintptr_t)dK | (uintptr_t)dV) & 15) ||
+      (softmax && ((((uintptr_t)O | (uintptr_t)workspace) & 15) || ((uintptr_t)stats & 3))))
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: device pointers must be 16-byte aligned (stats: 4-byte)");
+  const void* ins[] = {Q, K, V, dO, softmax ? O : nullptr, softmax ? stats : nullptr};
+  void* outs[] = {dQ, dK, dV, softmax ? workspace : nullptr};
+  for (int a = 0; a < 4; ++a) {
+    if (!outs[a]) continue;
+    for (const void* in : ins)
+      if (in == outs[a]) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: an output aliases an input");
+    for (int c = a + 1; c < 4; ++c)
+      if (outs[c] == outs[a]) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: two outputs alias");
+  }
+  size_t need = 0;
+  ae_attn_backward_workspace_bytes(h, &need);
+  if (workspace_bytes < need)
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: the workspace holds %zu bytes, %zu are needed", workspace_bytes, need);
+  ae::BwdParams p;
+  p.Q = static_cast<const __bf16*>(Q);
+  p.K = static_cast<const __bf16*>(K);
+  p.V = static_cast<const __bf16*>(V);
+  p.dO = static_cast<const __bf16*>(dO);
+  p.O = O;
+  p.lse = static_cast<const float*>(stats);
+  p.delta = static_cast<float*>(workspace);
+  p.dQ = static_cast<float*>(dQ);
+  p.dK = static_cast<float*>(dK);
+  p.dV = static_cast<float*>(dV);
+  p.B = d.B;
+  p.H_q = d.H_q;
+  p.H_kv = d.H_kv;
+  p.L_q = d.L_q;
+  p.L_k = d.L_k;
+  p.g = d.H_q / d.H_kv;
+  p.o_bf16 = d.out_dtype == AE_OUT_BF16;
+  for (int a = 0; a < 3; ++a) {
+    p.qs[a] = h->params.qs[a];
+    p.ks[a] = h->params.ks[a];
+    p.vs[a] = h->params.vs[a];
+    p.os[a] = h->params.os[a];
+  }
+  const float log2e = 1.4426950408889634f;
+  p.c2 = d.scale * log2e;
+  p.b2 = (d.score_mod == AE_MOD_BIAS ? d.bias : 0.f) * log2e;
+  p.scale = d.scale;
+  hipError_t e = ae::launch_backward(p, d.D_qk, d.D_v, norm, d.mask == AE_MASK_CAUSAL, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_backward: launch failed: %s", hipGetErrorString(e));
+  return AE_OK;
 }
 
 ae_status_t ae_attn_destroy(ae_attn_t* h) {

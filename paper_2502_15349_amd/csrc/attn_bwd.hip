@@ -1,0 +1,65 @@
+// Kernel instantiations and launch of the backward pass (see attn_bwd_kernel.hpp).
+#include "bwd.hpp"
+
+namespace ae {
+namespace {
+
+// delta_i = dO_i . O_i, one wavefront per row.
+__global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const BwdParams p, int D_v) {
+  const int64_t rows = (int64_t)p.B * p.H_q * p.L_q;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const int i = (int)(r % p.L_q), hq = (int)((r / p.L_q) % p.H_q), b = (int)(r / ((int64_t)p.L_q * p.H_q));
+  const int64_t ob = b * p.os[0] + hq * p.os[1] + (int64_t)i * p.os[2];
+  float acc = 0.f;
+  for (int d = lane; d < D_v; d += 64) {
+    const float o = p.o_bf16 ? (float)static_cast<const __bf16*>(p.O)[ob + d] : static_cast<const float*>(p.O)[ob + d];
+    acc += o * (float)p.dO[r * D_v + d];
+  }
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
+  if (lane == 0) p.delta[r] = acc;
+}
+
+template <int DQK, int DV, int NORM, bool CAUSAL>
+hipError_t launch_pair(const BwdParams& p, hipStream_t s) {
+  typedef BwdCfg<DQK, DV, NORM, CAUSAL, true> CK;
+  typedef BwdCfg<DQK, DV, NORM, CAUSAL, false> CQ;
+  const unsigned gk = (unsigned)(p.B * p.H_kv * ((p.L_k + CK::OWN - 1) / CK::OWN));
+  const unsigned gq = (unsigned)(p.B * p.H_q * ((p.L_q + CQ::OWN - 1) / CQ::OWN));
+  hipLaunchKernelGGL(attn_bwd_kernel<CK>, dim3(gk), dim3(CK::THREADS), 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_bwd_kernel<CQ>, dim3(gq), dim3(CQ::THREADS), 0, s, p);
+  return hipGetLastError();
+}
+
+template <int DQK, int DV>
+hipError_t launch_dims(const BwdParams& p, int norm, int causal, hipStream_t s) {
+  if (norm == NORM_SOFTMAX) return causal ? launch_pair<DQK, DV, NORM_SOFTMAX, true>(p, s) : launch_pair<DQK, DV, NORM_SOFTMAX, false>(p, s);
+  return causal ? launch_pair<DQK, DV, NORM_SIGMOID, true>(p, s) : launch_pair<DQK, DV, NORM_SIGMOID, false>(p, s);
+}
+
+}  // namespace
+
+bool backward_supported(int dqk, int dv, int norm) {
+  const bool dims = (dqk == 64 && dv == 64) || (dqk == 128 && dv == 128) || (dqk == 192 && dv == 128) || (dqk == 128 && dv == 256);
+  return dims && (norm == NORM_SOFTMAX || norm == NORM_SIGMOID);
+}
+
+hipError_t launch_backward(const BwdParams& p, int dqk, int dv, int norm, int causal, hipStream_t stream) {
+  if (norm == NORM_SOFTMAX) {
+    const int64_t rows = (int64_t)p.B * p.H_q * p.L_q;
+    hipLaunchKernelGGL(attn_bwd_delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, p, dv);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (dqk == 64 && dv == 64) return launch_dims<64, 64>(p, norm, causal, stream);
+  if (dqk == 128 && dv == 128) return launch_dims<128, 128>(p, norm, causal, stream);
+  if (dqk == 192 && dv == 128) return launch_dims<192, 128>(p, norm, causal, stream);
+  if (dqk == 128 && dv == 256) return launch_dims<128, 256>(p, norm, causal, stream);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace ae

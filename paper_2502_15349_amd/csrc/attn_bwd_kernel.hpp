@@ -1,0 +1,339 @@
+// Backward pass of fused parallel-pattern attention for gfx950 (CDNA4): the gradients
+// of O = normalization(modification(Q K^T)) V with respect to Q, K and V, for a given
+// upstream gradient dO, with the weights recomputed from the row statistic that the
+// forward pass keeps (paper Section 4.1, online row-norm interface: the backward graph
+// is derived from the same definition and reads the final row scales).
+//
+//   P   = exp(S' - lse_i)  (softmax)   |  sigmoid(S')            S' = scale * Q K^T + bias
+//   dV  = P^T dO                          dP = dO V^T
+//   dS' = P * (dP - delta_i), delta_i = dO_i . O_i  (softmax)   |  dP * P * (1 - P)  (sigmoid)
+//   dQ  = scale * dS' K                   dK = scale * dS'^T Q
+//
+// Two kernels of one shape, no atomics, every output written once:
+//   * key side   (KV_SIDE):  a workgroup owns 128 keys of one k/v head and walks the query
+//     tiles of the q heads that share it: dK and dV;
+//   * query side (!KV_SIDE): a workgroup owns 128 query rows of one q head and walks the
+//     key tiles: dQ.
+// In both a wavefront owns 32 rows ("own" side) whose two operand matrices it keeps in
+// registers as MFMA B fragments (K, V | Q, dO), and the tiles of the other side (Q, dO |
+// K, V; 64 rows, double buffered) arrive in LDS by global_load_lds.  Per 32-row sub-tile
+//   S  [other x own] = Y1 X1^T      dP [other x own] = Y2 X2^T        (bf16 MFMA 32x32x16)
+// put a lane's 16 accumulator values in one own column; after the elementwise step they
+// are, packed to bf16 and with no data movement, the B operands of
+//   G1^T [D_qk x own] += Y1^T dS    G2^T [D_v x own] += Y2^T P        (key side only)
+// whose A operands are the same LDS tiles read through the transposing LDS load, in the
+// row order that the accumulator layout dictates.
+#pragma once
+#include "attn_kernel.hpp"
+
+namespace ae {
+
+struct BwdParams {
+  const __bf16* Q;
+  const __bf16* K;
+  const __bf16* V;
+  const __bf16* dO;    // [B, H_q, L_q, D_v] contiguous
+  const void* O;       // as the forward pass wrote it (softmax only): fp32, or bf16 if o_bf16
+  const float* lse;    // [B, H_q, L_q] row statistic of the forward pass (softmax only)
+  float* delta;        // [B, H_q, L_q] workspace (softmax only)
+  float* dQ;           // [B, H_q, L_q, D_qk] contiguous fp32
+  float* dK;           // [B, H_kv, L_k, D_qk]
+  float* dV;           // [B, H_kv, L_k, D_v]
+  int B, H_q, H_kv, L_q, L_k, g;
+  int o_bf16;
+  int64_t qs[3], ks[3], vs[3], os[3];  // element strides {batch, head, row} of Q, K, V, O
+  float c2;     // scale * log2(e)
+  float b2;     // bias * log2(e)
+  float scale;
+};
+
+// Chunk swizzle of the backward tiles.  A tile row is read both ways -- 128-bit row
+// fragments, 16 lanes = 16 consecutive rows at a time, and 64-bit transposing loads, 32
+// lanes = 4 consecutive rows x 4 chunks at a time -- so the XOR pattern takes 16 values
+// over 16 consecutive rows (rows of 128 or 384 bytes alternate between the halves of the
+// 256-byte bank window, which supplies one of the four bits) and its upper bits change
+// within every aligned group of 4 rows.
+template <int CPR>
+__device__ __forceinline__ int bswz(int row) {
+  return CPR % 16 == 0 ? ((4 * (row & 3)) | ((row >> 2) & 3)) : ((4 * ((row >> 1) & 1)) | ((row >> 2) & 3));
+}
+
+template <int DQK_, int DV_, int NORM_, bool CAUSAL_, bool KV_SIDE_>
+struct BwdCfg {
+  static constexpr int DQK = DQK_, DV = DV_, NORM = NORM_;
+  static constexpr bool CAUSAL = CAUSAL_, KV_SIDE = KV_SIDE_;
+  static constexpr int WAVES = 4, THREADS = 256, OWN = 128;  // own rows per workgroup
+  static constexpr int TILE = 64;                            // other-side rows per LDS tile
+  static constexpr int RB1 = DQK * 2, RB2 = DV * 2, CPR1 = DQK / 8, CPR2 = DV / 8;
+  static constexpr int Y1_BYTES = TILE * RB1, Y2_BYTES = TILE * RB2, STAGE_BYTES = Y1_BYTES + Y2_BYTES;
+  static constexpr int ROW_BYTES = 2 * TILE * 4;  // per stage: -lse*log2(e) and delta of the tile's rows
+  static constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * ROW_BYTES;
+  static constexpr int T1 = DQK / 16, T2 = DV / 16, DB1 = DQK / 32, DB2 = DV / 32;
+  static_assert(NORM == NORM_SOFTMAX || NORM == NORM_SIGMOID, "backward: softmax and sigmoid only");
+  static_assert(LDS_BYTES <= 160 * 1024, "tiles do not fit LDS");
+};
+
+__device__ __forceinline__ bf16x8 read_tr_frag(uint32_t addr_lo, uint32_t addr_hi) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)addr_lo);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)addr_hi);
+  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const float (&x)[16], int t) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (__bf16)x[8 * t + e];
+  return r;
+}
+
+template <class C>
+__global__ __launch_bounds__(C::THREADS) void attn_bwd_kernel(const BwdParams p) {
+  __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
+  const uint32_t rows0 = lds0 + 2 * C::STAGE_BYTES;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ln = lane & 31, half = lane >> 5;
+  const int off = p.L_k - p.L_q;
+  const int L_own = C::KV_SIDE ? p.L_k : p.L_q, L_oth = C::KV_SIDE ? p.L_q : p.L_k;
+
+  // ---- which rows this workgroup owns ----------------------------------------------
+  const int n_heads = C::KV_SIDE ? p.H_kv : p.H_q;
+  const int n_own_tiles = (L_own + C::OWN - 1) / C::OWN;
+  const int bh = blockIdx.x % (p.B * n_heads);
+  int ot = blockIdx.x / (p.B * n_heads);        // causal: the workgroups with most work first
+  if (!C::KV_SIDE) ot = n_own_tiles - 1 - ot;
+  const int b = bh / n_heads, ho = bh % n_heads;  // ho: k/v head (key side) or q head (query side)
+  const int hk = C::KV_SIDE ? ho : ho / p.g;
+  const int own0 = ot * C::OWN, ow0 = own0 + wave * 32;  // first own row of the workgroup / of this wave
+  const int own = ow0 + ln;                              // this lane's own row (column of S, dP, G^T)
+  const int own_c = own < L_own ? own : L_own - 1;
+
+  // ---- own operands: B fragments, straight from global memory ------------------------
+  const __bf16* x1 = C::KV_SIDE ? p.K + b * p.ks[0] + hk * p.ks[1] + (int64_t)own_c * p.ks[2]
+                                : p.Q + b * p.qs[0] + ho * p.qs[1] + (int64_t)own_c * p.qs[2];
+  const __bf16* x2 = C::KV_SIDE ? p.V + b * p.vs[0] + hk * p.vs[1] + (int64_t)own_c * p.vs[2]
+                                : p.dO + (((int64_t)b * p.H_q + ho) * p.L_q + own_c) * C::DV;
+  bf16x8 xb1[C::T1], xb2[C::T2];
+#pragma unroll
+  for (int t = 0; t < C::T1; ++t) xb1[t] = *reinterpret_cast<const bf16x8*>(x1 + (2 * t + half) * 8);
+#pragma unroll
+  for (int t = 0; t < C::T2; ++t) xb2[t] = *reinterpret_cast<const bf16x8*>(x2 + (2 * t + half) * 8);
+  // query side: the row quantities belong to the lane's own row
+  float nl_own = -INFINITY, dl_own = 0.f;
+  if constexpr (!C::KV_SIDE && C::NORM == NORM_SOFTMAX) {
+    if (own < p.L_q) {
+      const int64_t r = ((int64_t)b * p.H_q + ho) * p.L_q + own;
+      const float lse = p.lse[r];
+      nl_own = lse == -INFINITY ? -INFINITY : -lse * 1.4426950408889634f;
+      dl_own = p.delta[r];
+    }
+  }
+
+  // ---- the walk over the other side --------------------------------------------------
+  // key side: the query tiles from the first one that sees key own0, for each q head of
+  // the group; query side: the key tiles up to the last one that row own0 + 127 sees.
+  int t_first = 0, t_end = (L_oth + C::TILE - 1) / C::TILE;
+  if constexpr (C::CAUSAL) {
+    if constexpr (C::KV_SIDE) {
+      const int i_first = own0 - off;  // first query that sees key own0
+      t_first = i_first > 0 ? i_first / C::TILE : 0;
+      if (t_first > t_end) t_first = t_end;
+    } else {
+      const int j_last = own0 + C::OWN - 1 + off;  // last key any row here may see
+      const int e = j_last < 0 ? 0 : j_last / C::TILE + 1;
+      if (e < t_end) t_end = e;
+    }
+  }
+  const int nt = t_end - t_first;
+  const int total = C::KV_SIDE ? nt * p.g : nt;
+
+  // LDS-DMA maps: block nb of a tile = 64 chunks of 16 bytes, linear in LDS; position ->
+  // (row, physical chunk), the logical chunk is the physical one XOR the row's swizzle.
+  auto issue_tile = [&](int n, int stage) {
+    const int hq = C::KV_SIDE ? hk * p.g + n / nt : ho;
+    const int r0 = (t_first + (C::KV_SIDE ? n % nt : n)) * C::TILE;
+    const __bf16* y1 = C::KV_SIDE ? p.Q + b * p.qs[0] + hq * p.qs[1] : p.K + b * p.ks[0] + hk * p.ks[1];
+    const __bf16* y2 = C::KV_SIDE ? p.dO + ((int64_t)b * p.H_q + hq) * p.L_q * C::DV : p.V + b * p.vs[0] + hk * p.vs[1];
+    const int64_t s1 = C::KV_SIDE ? p.qs[2] : p.ks[2], s2 = C::KV_SIDE ? (int64_t)C::DV : p.vs[2];
+    const uint32_t base = lds0 + stage * C::STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < C::CPR1 / C::WAVES; ++i) {
+      const int nb = wave + i * C::WAVES, pos = nb * 64 + lane;
+      const int r = pos / C::CPR1, pc = pos % C::CPR1;
+      int row = r0 + r;
+      row = row < L_oth ? row : L_oth - 1;
+      const uint32_t goff = (uint32_t)(((int64_t)row * s1 + ((pc ^ bswz<C::CPR1>(r)) * 8)) * 2);
+      dma16(y1, goff, base + nb * 1024);
+    }
+#pragma unroll
+    for (int i = 0; i < C::CPR2 / C::WAVES; ++i) {
+      const int nb = wave + i * C::WAVES, pos = nb * 64 + lane;
+      const int r = pos / C::CPR2, pc = pos % C::CPR2;
+      int row = r0 + r;
+      row = row < L_oth ? row : L_oth - 1;
+      const uint32_t goff = (uint32_t)(((int64_t)row * s2 + ((pc ^ bswz<C::CPR2>(r)) * 8)) * 2);
+      dma16(y2, goff, base + C::Y1_BYTES + nb * 1024);
+    }
+  };
+  // key side: the tile's row quantities, wave 0 -> -lse*log2(e), wave 1 -> delta
+  auto load_rowq = [&](int n) -> float {
+    float v = 0.f;
+    if constexpr (C::KV_SIDE && C::NORM == NORM_SOFTMAX) {
+      if (wave < 2) {
+        const int hq = hk * p.g + n / nt;
+        const int i = (t_first + n % nt) * C::TILE + lane;
+        const int64_t r = ((int64_t)b * p.H_q + hq) * p.L_q + i;
+        if (wave == 0) {
+          const float lse = i < p.L_q ? p.lse[r] : -INFINITY;
+          v = lse == -INFINITY ? -INFINITY : -lse * 1.4426950408889634f;
+        } else {
+          v = i < p.L_q ? p.delta[r] : 0.f;
+        }
+      }
+    }
+    return v;
+  };
+  auto store_rowq = [&](float v, int stage) {
+    if constexpr (C::KV_SIDE && C::NORM == NORM_SOFTMAX) {
+      if (wave < 2)
+        *reinterpret_cast<__attribute__((address_space(3))) float*>(
+            (lds_char*)(uintptr_t)(rows0 + stage * C::ROW_BYTES + wave * C::TILE * 4 + lane * 4)) = v;
+    }
+  };
+
+  f32x16 g1[C::DB1], g2[C::KV_SIDE ? C::DB2 : 1];
+#pragma unroll
+  for (int d = 0; d < C::DB1; ++d) g1[d] = zero16();
+#pragma unroll
+  for (int d = 0; d < (C::KV_SIDE ? C::DB2 : 1); ++d) g2[d] = zero16();
+
+  // per-lane pieces of the fragment addresses
+  const int f1 = bswz<C::CPR1>(ln), f2 = bswz<C::CPR2>(ln);             // row fragments: row = lane % 32
+  const int li = lane & 15, blk = (lane >> 4) & 1;
+  const int trow = 4 * half + (li >> 2);                               // transposing reads: row within 16
+  const int tcl = 2 * blk + ((li & 3) >> 1);                            // chunk within a 32-column block
+  const int f1lo = bswz<C::CPR1>(trow), f1hi = bswz<C::CPR1>(trow + 8);
+  const int f2lo = bswz<C::CPR2>(trow), f2hi = bswz<C::CPR2>(trow + 8);
+
+  if (total > 0) {
+    issue_tile(0, 0);
+    store_rowq(load_rowq(0), 0);
+  }
+  for (int n = 0; n < total; ++n) {
+    const int stage = n & 1;
+    // tile n has landed, and every wave is done with the stage that tile n + 1 goes to
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    float rowq_next = 0.f;
+    if (n + 1 < total) {
+      issue_tile(n + 1, stage ^ 1);
+      rowq_next = load_rowq(n + 1);
+    }
+    const uint32_t y1b = lds0 + stage * C::STAGE_BYTES, y2b = y1b + C::Y1_BYTES;
+    const uint32_t rqb = rows0 + stage * C::ROW_BYTES;
+    const int r0 = (t_first + (C::KV_SIDE ? n % nt : n)) * C::TILE;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      const int o0 = r0 + 32 * sub;  // first other-side row of the sub-tile
+      // anything visible to this wave's rows?  everything?
+      bool any = o0 < L_oth, full = o0 + 31 < L_oth;
+      if constexpr (C::CAUSAL) {
+        if constexpr (C::KV_SIDE) {  // own = keys j, other = queries i: visible iff j <= i + off
+          any = any && ow0 <= o0 + 31 + off;
+          full = full && ow0 + 31 <= o0 + off;
+        } else {                     // own = queries i, other = keys j
+          any = any && o0 <= ow0 + 31 + off;
+          full = full && o0 + 31 <= ow0 + off;
+        }
+      }
+      if (!any) continue;
+      // S and dP
+      f32x16 s = zero16(), dp = zero16();
+      {
+        const uint32_t a1 = y1b + (32 * sub + ln) * C::RB1, a2 = y2b + (32 * sub + ln) * C::RB2;
+#pragma unroll
+        for (int t = 0; t < C::T1; ++t) s = mfma(read_k_frag(a1 + (((2 * t + half) ^ f1) << 4)), xb1[t], s);
+#pragma unroll
+        for (int t = 0; t < C::T2; ++t) dp = mfma(read_k_frag(a2 + (((2 * t + half) ^ f2) << 4)), xb2[t], dp);
+      }
+      // elementwise: register r is other-side row o0 + 8*(r/4) + 4*half + (r%4)
+      float pw[16], dw[16];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        f32x4 nl4, dl4;
+        if constexpr (C::NORM == NORM_SOFTMAX) {
+          if constexpr (C::KV_SIDE) {
+            nl4 = lds_read16(rqb + (32 * sub + 8 * q + 4 * half) * 4);
+            dl4 = lds_read16(rqb + C::TILE * 4 + (32 * sub + 8 * q + 4 * half) * 4);
+          } else {
+            nl4 = f32x4{nl_own, nl_own, nl_own, nl_own};
+            dl4 = f32x4{dl_own, dl_own, dl_own, dl_own};
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * q + e;
+          float x = __builtin_fmaf(s[r], p.c2, C::NORM == NORM_SOFTMAX ? p.b2 + nl4[e] : p.b2);
+          if (!full) {  // a hidden entry gets the exponent that makes its weight exactly 0
+            const int oth = o0 + 8 * q + 4 * half + e;
+            bool vis = oth < L_oth;
+            if constexpr (C::CAUSAL) vis = vis && (C::KV_SIDE ? own <= oth + off : oth <= own + off);
+            x = vis ? x : -INFINITY;
+          }
+          float pv, dv;
+          if constexpr (C::NORM == NORM_SOFTMAX) {
+            pv = fast_exp2(x);
+            dv = pv * (dp[r] - dl4[e]);
+          } else {
+            pv = fast_rcp(1.f + fast_exp2(-x));
+            dv = dp[r] * pv * (1.f - pv);
+          }
+          pw[r] = pv;
+          dw[r] = dv;
+        }
+      }
+      // G1^T += Y1^T dS,  G2^T += Y2^T P
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 dsb = pack8(dw, t);
+        const uint32_t rb1 = y1b + (32 * sub + 16 * t + trow) * C::RB1 + (li & 1) * 8;
+#pragma unroll
+        for (int db = 0; db < C::DB1; ++db)
+          g1[db] = mfma(read_tr_frag(rb1 + (((4 * db + tcl) ^ f1lo) << 4), rb1 + 8 * C::RB1 + (((4 * db + tcl) ^ f1hi) << 4)),
+                        dsb, g1[db]);
+        if constexpr (C::KV_SIDE) {
+          const bf16x8 pb = pack8(pw, t);
+          const uint32_t rb2 = y2b + (32 * sub + 16 * t + trow) * C::RB2 + (li & 1) * 8;
+#pragma unroll
+          for (int db = 0; db < C::DB2; ++db)
+            g2[db] = mfma(read_tr_frag(rb2 + (((4 * db + tcl) ^ f2lo) << 4), rb2 + 8 * C::RB2 + (((4 * db + tcl) ^ f2hi) << 4)),
+                          pb, g2[db]);
+        }
+      }
+    }
+    if (n + 1 < total) store_rowq(rowq_next, stage ^ 1);
+  }
+
+  // ---- results: register r of block db is column own, row d = 32 db + 8 (r/4) + 4 half + r%4 ----
+  if (own < L_own) {
+    float* o1 = C::KV_SIDE ? p.dK + (((int64_t)b * p.H_kv + hk) * p.L_k + own) * C::DQK
+                           : p.dQ + (((int64_t)b * p.H_q + ho) * p.L_q + own) * C::DQK;
+#pragma unroll
+    for (int db = 0; db < C::DB1; ++db)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<f32x4*>(o1 + 32 * db + 8 * q + 4 * half) =
+            f32x4{g1[db][4 * q] * p.scale, g1[db][4 * q + 1] * p.scale, g1[db][4 * q + 2] * p.scale, g1[db][4 * q + 3] * p.scale};
+    if constexpr (C::KV_SIDE) {
+      float* o2 = p.dV + (((int64_t)b * p.H_kv + hk) * p.L_k + own) * C::DV;
+#pragma unroll
+      for (int db = 0; db < C::DB2; ++db)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *reinterpret_cast<f32x4*>(o2 + 32 * db + 8 * q + 4 * half) =
+              f32x4{g2[db][4 * q], g2[db][4 * q + 1], g2[db][4 * q + 2], g2[db][4 * q + 3]};
+      }
+  }
+}
+
+}  // namespace ae

@@ -129,3 +129,12 @@ def make_inputs(w: Workload, seed_base: Optional[int] = None):
         x = torch.randn(shape, generator=g, dtype=torch.float32)
         out.append(x.to(torch.bfloat16).contiguous())
     return tuple(out)
+
+
+def make_grad(w: Workload, seed_base: Optional[int] = None):
+    """Upstream gradient dO for the backward pass: a contiguous CPU bf16 tensor [B, H_q, L_q, D_v], standard
+    normal like the inputs, from a seed of its own."""
+    base = 1000 * w.config_id if seed_base is None else seed_base
+    g = torch.Generator(device="cpu")
+    g.manual_seed(base + 7)
+    return torch.randn((w.B, w.H_q, w.L_q, w.D_v), generator=g, dtype=torch.float32).to(torch.bfloat16).contiguous()

@@ -1,0 +1,121 @@
+"""GPU parity of the backward pass: ae_attn_backward (through the C ABI, fed by the HIP forward pass's output and
+row statistic) against the fp64 backward oracle on the same seeded bf16 inputs.  Bar as for the forward pass
+(bf16 operands, bf16 weights and score gradients into the second MFMAs, fp32 accumulation): max-abs <= 1e-2 and
+mean-abs <= 1e-3, relative to max(1, the largest |reference| of the row)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention_backward
+from paper_2502_15349_amd.workloads import C2, Workload, make_grad, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 1e-2, 1e-3
+DIMS = [(64, 64), (128, 128), (128, 256), (192, 128)]
+
+
+@pytest.fixture(scope="module")
+def A():
+    from paper_2502_15349_amd import ae_attn
+    return ae_attn
+
+
+def hip_backward(A, w, Q, K, V, dO, out_dtype=None):
+    dev = torch.device("cuda:0")
+    Qd, Kd, Vd, dOd = Q.to(dev), K.to(dev), V.to(dev), dO.to(dev)
+    stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev) if w.norm == "softmax" else None
+    O = A.run_workload(w, Qd, Kd, Vd, stats=stats, out_dtype=out_dtype)
+    dQ, dK, dV = A.attention_backward(Qd, Kd, Vd, O, dOd, stats, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
+                                      norm=w.norm, mask=w.mask)
+    torch.cuda.synchronize()
+    return [x.cpu().double().numpy() for x in (dQ, dK, dV)]
+
+
+def oracle_backward(w, Q, K, V, dO):
+    return attention_backward(Q, K, V, dO, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias, norm=w.norm,
+                              mask=w.oracle_mask())
+
+
+def check(got, ref, what):
+    assert np.isfinite(got).all(), f"{what}: non-finite gradient"
+    rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+    err = np.abs(got - ref) / rs
+    print(f"{what}: max_abs {err.max():.3e} mean_abs {err.mean():.3e} |ref|max {np.abs(ref).max():.3e}", flush=True)
+    assert err.max() <= MAX_ABS, f"{what}: max-abs {err.max():.3e}"
+    assert err.mean() <= MEAN_ABS, f"{what}: mean-abs {err.mean():.3e}"
+
+
+def run_case(A, w, out_dtype=None):
+    print(f"case {w}", flush=True)
+    Q, K, V = make_inputs(w)
+    dO = make_grad(w)
+    got, ref = hip_backward(A, w, Q, K, V, dO, out_dtype), oracle_backward(w, Q, K, V, dO)
+    for name, g, r in zip(("dQ", "dK", "dV"), got, ref):
+        check(g, r, f"{w.name} {name}")
+
+
+VARIANTS = {
+    "softmax": dict(),
+    "softmax_causal": dict(mask="causal"),
+    "softmax_bias_causal": dict(score_mod="bias", bias=0.75, mask="causal"),
+    "softmax_negative_scale": dict(scale=-0.11, mask="causal"),
+    "sigmoid_causal": dict(score_mod="bias", norm="sigmoid", mask="causal", bias=-math.log(300.0)),
+    "sigmoid": dict(norm="sigmoid", score_mod="bias", bias=-3.0),
+}
+
+
+@pytest.mark.parametrize("dims", DIMS, ids=lambda d: f"d{d[0]}_{d[1]}")
+@pytest.mark.parametrize("variant", sorted(VARIANTS))
+def test_backward_small_ragged(A, dims, variant):
+    # 3 own tiles with a ragged tail on either side, 5-6 LDS tiles with a ragged tail, grouped heads 2:1
+    run_case(A, Workload(variant, 40, 2, 4, 2, 300, 333, dims[0], dims[1], **VARIANTS[variant]))
+
+
+@pytest.mark.parametrize("Lq,Lk", [(1, 1), (1, 200), (200, 1), (31, 33), (64, 64), (128, 128), (129, 257), (500, 130),
+                                    (130, 500), (257, 129)])
+@pytest.mark.parametrize("mask", ["none", "causal"])
+def test_backward_lengths(A, Lq, Lk, mask):
+    # L_q != L_k in both directions (causal: bottom-right aligned; with L_q > L_k the first rows see no key and
+    # must get zero gradient), single rows, exact tile multiples
+    run_case(A, Workload(f"len{Lq}x{Lk}{mask}", 41, 1, 3, 1, Lq, Lk, 64, 64, mask=mask))
+    run_case(A, Workload(f"len{Lq}x{Lk}{mask}sig", 42, 1, 2, 2, Lq, Lk, 128, 128, mask=mask, norm="sigmoid", score_mod="bias", bias=-2.0))
+
+
+def test_backward_bf16_forward_output(A):
+    # delta is formed from the forward output as stored: also when that is bf16
+    run_case(A, Workload("bf16_O", 43, 1, 4, 2, 260, 260, 128, 128, mask="causal"), out_dtype=torch.bfloat16)
+
+
+def test_backward_strided_inputs(A):
+    # Q, K, V as [B, L, H, D] memory viewed as [B, H, L, D]
+    w = Workload("strided", 44, 2, 4, 2, 200, 230, 128, 128, mask="causal")
+    Q, K, V = make_inputs(w)
+    dO = make_grad(w)
+    dev = torch.device("cuda:0")
+    Qd, Kd, Vd = (x.to(dev).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for x in (Q, K, V))
+    stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev)
+    O = A.run_workload(w, Qd, Kd, Vd, stats=stats)
+    got = A.attention_backward(Qd, Kd, Vd, O, dO.to(dev), stats, scale=w.scale_value, mask=w.mask)
+    torch.cuda.synchronize()
+    ref = oracle_backward(w, Q, K, V, dO)
+    for name, g, r in zip(("dQ", "dK", "dV"), got, ref):
+        check(g.cpu().double().numpy(), r, f"strided {name}")
+
+
+def test_backward_full_size_c2_one_group(A):
+    """The benchmark shape (4 x 32/8 heads x 2048 x 128, causal softmax) at full size; the oracle checks one
+    (batch, k/v head) group: its four query heads' dQ and the group's dK, dV."""
+    w = C2
+    Q, K, V = make_inputs(w)
+    dO = make_grad(w)
+    got = hip_backward(A, w, Q, K, V, dO)
+    b, hk, g = 2, 5, w.H_q // w.H_kv
+    hs = slice(hk * g, hk * g + g)
+    ref = attention_backward(Q[b:b + 1, hs], K[b:b + 1, hk:hk + 1], V[b:b + 1, hk:hk + 1], dO[b:b + 1, hs],
+                             scale=w.scale_value, norm="softmax", mask="causal")
+    check(got[0][b:b + 1, hs], ref[0], "C2 dQ")
+    check(got[1][b:b + 1, hk:hk + 1], ref[1], "C2 dK")
+    check(got[2][b:b + 1, hk:hk + 1], ref[2], "C2 dV")
