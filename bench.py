@@ -150,6 +150,9 @@ def main():
     ap.add_argument("--decode", action="store_true",
                     help="time the paper's decoding row (Table 2: one query row, 16 heads, 192/128) with and without "
                          "split keys and print GB/s against the HBM peak")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the backward pass (ae_attn_backward: dQ, dK, dV) on the softmax / sigmoid benchmark "
+                         "shapes and print TFLOP/s against the bf16 MFMA peak")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device-to-device copy of this many MiB "
                          "(reference reading for the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
@@ -259,6 +262,67 @@ def main():
                       f"auto from a HIP graph {graph_ms:7.4f} ms {byts / graph_ms / 1e6:7.1f} GB/s (replays equal eager: {same})  sweep {sweep}",
                       file=sys.stderr, flush=True)
         print(json.dumps({"decode": rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16", "data": "synthetic"}))
+        return
+    if a.backward:
+        # Not the contract line.  Algorithmic work of the backward pass: five contractions per visible (query, key)
+        # pair (S, dP, dV, dK, dQ) = 2 * (3 D_qk + 2 D_v) flop; the two kernels recompute S and dP once each, so the
+        # MFMAs they issue amount to 2 * (4 D_qk + 3 D_v) flop per pair.
+        from oracle import attention_backward
+        from paper_2502_15349_amd.workloads import C2, C3, C5, Workload, make_grad
+        rows = []
+        shapes = [C2, C3, C5, Workload("t2_softmax_b8_h32_s8192_noncausal", 150, 8, 32, 32, 8192, 8192, 128, 128),
+                  Workload("t2_softmax_b8_h32_s8192_causal", 151, 8, 32, 32, 8192, 8192, 128, 128, mask="causal")]
+        for w in shapes:
+            Qc, Kc, Vc = make_inputs(w)
+            dOc = make_grad(w)
+            Q, K, V, dO = Qc.to(dev), Kc.to(dev), Vc.to(dev), dOc.to(dev)
+            stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev) if w.norm == "softmax" else None
+            O = A.run_workload(w, Q, K, V, stats=stats)
+            h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
+                                 scale=w.scale_value, score_mod=w.score_mod, bias=w.bias, norm=w.norm, mask=w.mask)
+            dQ = torch.empty(Q.shape, dtype=torch.float32, device=dev)
+            dK = torch.empty(K.shape, dtype=torch.float32, device=dev)
+            dV = torch.empty(V.shape, dtype=torch.float32, device=dev)
+            ws = torch.empty(max(A.ae_attn_backward_workspace_bytes(h), 16), dtype=torch.uint8, device=dev)
+            st = torch.cuda.current_stream()
+            args = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
+                    0 if stats is None else stats.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), ws.data_ptr(),
+                    ws.numel(), st.cuda_stream)
+            t_end = time.perf_counter() + 0.3
+            while time.perf_counter() < t_end:
+                A.ae_attn_backward(*args)
+                torch.cuda.synchronize()
+            n = 10
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            for _ in range(n):
+                A.ae_attn_backward(*args)
+            e1.record(st)
+            torch.cuda.synchronize()
+            A.ae_attn_destroy(h)
+            ms = e0.elapsed_time(e1) / n
+            pairs = w.visible_pairs_per_head() * w.B * w.H_q
+            alg, issued = 2 * (3 * w.D_qk + 2 * w.D_v) * pairs, 2 * (4 * w.D_qk + 3 * w.D_v) * pairs
+            par = None
+            if w.L_q <= 4096:   # one (batch, k/v head) group against the oracle
+                b, hk, g = w.B - 1, w.H_kv // 2, w.H_q // w.H_kv
+                hs = slice(hk * g, hk * g + g)
+                ref = attention_backward(Qc[b:b + 1, hs], Kc[b:b + 1, hk:hk + 1], Vc[b:b + 1, hk:hk + 1], dOc[b:b + 1, hs],
+                                         scale=w.scale_value, score_mod=w.score_mod, bias=w.bias, norm=w.norm, mask=w.mask)
+                got = (dQ[b:b + 1, hs], dK[b:b + 1, hk:hk + 1], dV[b:b + 1, hk:hk + 1])
+                par = {}
+                for name, x, r in zip(("dQ", "dK", "dV"), got, ref):
+                    rs = np.maximum(np.abs(r).max(axis=-1, keepdims=True), 1.0)
+                    err = np.abs(x.cpu().double().numpy() - r) / rs
+                    par[name] = {"max_abs_scaled": float(err.max()), "mean_abs_scaled": float(err.mean())}
+            tf = alg / (ms * 1e-3) / 1e12
+            rows.append({"workload": w.name, "backward_ms": round(ms, 4), "tflops": round(tf, 1),
+                         "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4),
+                         "issued_mfma_tflops": round(issued / (ms * 1e-3) / 1e12, 1), "flop": alg, "parity": par})
+            print(f"# {w.name:40s} backward {ms:9.4f} ms {tf:8.1f} TFLOP/s ({100 * tf / PEAK_BF16_TFLOPS:4.1f} % of peak; "
+                  f"MFMAs issued: {issued / (ms * 1e-3) / 1e12:7.1f} TFLOP/s)  parity {par}", file=sys.stderr, flush=True)
+            del Q, K, V, dO, O, dQ, dK, dV
+        print(json.dumps({"backward": rows, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS, "dtype": "bf16", "data": "synthetic"}))
         return
     if a.table2:
         # Not the contract line: the paper's own microbenchmark grid, one row per shape.

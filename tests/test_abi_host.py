@@ -165,6 +165,53 @@ def test_split_keys_descriptor_and_workspace():
         A.ae_attn_destroy(h)
 
 
+def test_backward_rejects_bad_arguments_without_launching():
+    from paper_2502_15349_amd import ae_attn as A
+    d = _ok_desc()
+    h = A.ae_attn_create(**d)
+    try:
+        rows = d["B"] * d["H_q"] * d["L_q"]
+        assert A.ae_attn_backward_workspace_bytes(h) == 4 * rows
+        ok = [256 * (i + 1) for i in range(10)]   # Q K V O dO stats dQ dK dV workspace
+        bad = []
+        for pos in (0, 4, 6, 9):                  # a null pointer
+            a = list(ok)
+            a[pos] = 0
+            bad.append((a, 4 * rows))
+        a = list(ok)
+        a[7] = ok[7] + 8                          # misaligned output
+        bad.append((a, 4 * rows))
+        a = list(ok)
+        a[6] = ok[0]                              # dQ aliases Q
+        bad.append((a, 4 * rows))
+        a = list(ok)
+        a[8] = ok[7]                              # dV aliases dK
+        bad.append((a, 4 * rows))
+        bad.append((list(ok), 4 * rows - 4))      # workspace too small
+        for args, ws_bytes in bad:
+            with pytest.raises(A.AeAttnError) as ei:
+                A.ae_attn_backward(h, *args, ws_bytes)
+            assert ei.value.status == A.AE_ERR_INVALID_ARG, A.ae_attn_last_error()
+    finally:
+        A.ae_attn_destroy(h)
+    # sigmoid needs no workspace; normalizations and masks outside the built set are refused
+    for patch, want in ((dict(norm="sigmoid"), None), (dict(norm="abssum"), A.AE_ERR_UNSUPPORTED),
+                        (dict(norm="none", score_mod="relu"), A.AE_ERR_UNSUPPORTED),
+                        (dict(mask="sliding_window", window=8), A.AE_ERR_UNSUPPORTED)):
+        dd = _ok_desc()
+        dd.update(patch)
+        h = A.ae_attn_create(**dd)
+        try:
+            if want is None:
+                assert A.ae_attn_backward_workspace_bytes(h) == 0
+            else:
+                with pytest.raises(A.AeAttnError) as ei:
+                    A.ae_attn_backward(h, *[256 * (i + 1) for i in range(10)], 1 << 20)
+                assert ei.value.status == want
+        finally:
+            A.ae_attn_destroy(h)
+
+
 def test_padded_strides_accepted():
     from paper_2502_15349_amd import ae_attn as A
     h = A.ae_attn_create(**_ok_desc(), q_stride=(100 * 4 * 136, 100 * 136, 136))
