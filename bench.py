@@ -153,6 +153,7 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (ae_attn_backward: dQ, dK, dV) on the softmax / sigmoid benchmark "
                          "shapes and print TFLOP/s against the bf16 MFMA peak")
+    ap.add_argument("--only", default="", help="with --backward: only the shapes whose name contains this")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device-to-device copy of this many MiB "
                          "(reference reading for the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
@@ -265,14 +266,16 @@ def main():
         return
     if a.backward:
         # Not the contract line.  Algorithmic work of the backward pass: five contractions per visible (query, key)
-        # pair (S, dP, dV, dK, dQ) = 2 * (3 D_qk + 2 D_v) flop; the two kernels recompute S and dP once each, so the
-        # MFMAs they issue amount to 2 * (4 D_qk + 3 D_v) flop per pair.
+        # pair (S, dP, dV, dK, dQ) = 2 * (3 D_qk + 2 D_v) flop; each of the three kernels (dK, dV, dQ) recomputes the
+        # scores it needs, so the MFMAs they issue amount to 2 * (5 D_qk + 3 D_v) flop per pair.
         from oracle import attention_backward
         from paper_2502_15349_amd.workloads import C2, C3, C5, Workload, make_grad
         rows = []
         shapes = [C2, C3, C5, Workload("t2_softmax_b8_h32_s8192_noncausal", 150, 8, 32, 32, 8192, 8192, 128, 128),
                   Workload("t2_softmax_b8_h32_s8192_causal", 151, 8, 32, 32, 8192, 8192, 128, 128, mask="causal")]
         for w in shapes:
+            if a.only not in w.name:
+                continue
             Qc, Kc, Vc = make_inputs(w)
             dOc = make_grad(w)
             Q, K, V, dO = Qc.to(dev), Kc.to(dev), Vc.to(dev), dOc.to(dev)
@@ -302,7 +305,7 @@ def main():
             A.ae_attn_destroy(h)
             ms = e0.elapsed_time(e1) / n
             pairs = w.visible_pairs_per_head() * w.B * w.H_q
-            alg, issued = 2 * (3 * w.D_qk + 2 * w.D_v) * pairs, 2 * (4 * w.D_qk + 3 * w.D_v) * pairs
+            alg, issued = 2 * (3 * w.D_qk + 2 * w.D_v) * pairs, 2 * (5 * w.D_qk + 3 * w.D_v) * pairs
             par = None
             if w.L_q <= 4096:   # one (batch, k/v head) group against the oracle
                 b, hk, g = w.B - 1, w.H_kv // 2, w.H_q // w.H_kv

@@ -9,18 +9,21 @@
 //   dS' = P * (dP - delta_i), delta_i = dO_i . O_i  (softmax)   |  dP * P * (1 - P)  (sigmoid)
 //   dQ  = scale * dS' K                   dK = scale * dS'^T Q
 //
-// Two kernels of one shape, no atomics, every output written once:
-//   * key side   (KV_SIDE):  a workgroup owns 128 keys of one k/v head and walks the query
-//     tiles of the q heads that share it: dK and dV;
-//   * query side (!KV_SIDE): a workgroup owns 128 query rows of one q head and walks the
-//     key tiles: dQ.
+// Three kernels of one shape, one per gradient, no atomics, every output written once:
+//   * dK, dV (key side, KV_SIDE): a workgroup owns 128 keys of one k/v head and walks the
+//     query tiles of the q heads that share it;
+//   * dQ (query side): a workgroup owns 128 query rows of one q head and walks the key tiles.
+// (dK and dV in one kernel would save recomputing S once, but its two accumulators and two
+// resident operands fill the 256 registers of a two-waves-per-SIMD kernel on their own, and
+// with nothing left to read LDS ahead of the MFMAs it ran at 28 % matrix-pipe occupancy where
+// the kernels below reach twice that.)
 // In both a wavefront owns 32 rows ("own" side) whose two operand matrices it keeps in
 // registers as MFMA B fragments (K, V | Q, dO), and the tiles of the other side (Q, dO |
-// K, V; 64 rows, double buffered) arrive in LDS by global_load_lds.  Per 32-row sub-tile
+// K, V; 64 or 32 rows, double buffered) arrive in LDS by global_load_lds.  Per 32-row sub-tile
 //   S  [other x own] = Y1 X1^T      dP [other x own] = Y2 X2^T        (bf16 MFMA 32x32x16)
 // put a lane's 16 accumulator values in one own column; after the elementwise step they
 // are, packed to bf16 and with no data movement, the B operands of
-//   G1^T [D_qk x own] += Y1^T dS    G2^T [D_v x own] += Y2^T P        (key side only)
+//   dQ^T, dK^T [D_qk x own] += Y1^T dS       dV^T [D_v x own] += Y2^T P
 // whose A operands are the same LDS tiles read through the transposing LDS load, in the
 // row order that the accumulator layout dictates.
 #pragma once
@@ -58,19 +61,31 @@ __device__ __forceinline__ int bswz(int row) {
   return CPR % 16 == 0 ? ((4 * (row & 3)) | ((row >> 2) & 3)) : ((4 * ((row >> 1) & 1)) | ((row >> 2) & 3));
 }
 
-template <int DQK_, int DV_, int NORM_, bool CAUSAL_, bool KV_SIDE_>
+enum : int { BWD_DQ = 0, BWD_DK = 1, BWD_DV = 2 };
+
+template <int DQK_, int DV_, int NORM_, bool CAUSAL_, int OUT_>
 struct BwdCfg {
-  static constexpr int DQK = DQK_, DV = DV_, NORM = NORM_;
-  static constexpr bool CAUSAL = CAUSAL_, KV_SIDE = KV_SIDE_;
+  static constexpr int DQK = DQK_, DV = DV_, NORM = NORM_, OUT = OUT_;
+  static constexpr bool CAUSAL = CAUSAL_, KV_SIDE = OUT_ != BWD_DQ;
+  static constexpr bool NEED_DP = OUT_ != BWD_DV;  // the dV kernel needs the weights only
   static constexpr int WAVES = 4, THREADS = 256, OWN = 128;  // own rows per workgroup
-  static constexpr int TILE = 64;                            // other-side rows per LDS tile
+  static constexpr int T1 = DQK / 16, T2 = NEED_DP ? DV / 16 : 0;
+  static constexpr int DB = (OUT_ == BWD_DV ? DV : DQK) / 32;  // 32-row blocks of the transposed result
+  // Two workgroups per CU (two waves per SIMD, 256 registers each) where the accumulators, the
+  // resident operands and the two score tiles leave room for the rest; one (512 registers) otherwise.
+  static constexpr bool OCC2 = 16 * DB + 4 * T1 + 4 * T2 + (NEED_DP ? 32 : 16) <= 176;
+  // other-side rows per LDS tile: 64, or 32 where two 64-row stages would not leave room for two
+  // workgroups per CU (80 KB each)
+  static constexpr int TILE = !OCC2 || 2 * 64 * (DQK + DV) * 2 + 1024 <= 80 * 1024 ? 64 : 32;
+  // per-lane fragment addresses kept in registers
+  static constexpr bool PRE = !OCC2 || DQK + DV <= 256;
   static constexpr int RB1 = DQK * 2, RB2 = DV * 2, CPR1 = DQK / 8, CPR2 = DV / 8;
   static constexpr int Y1_BYTES = TILE * RB1, Y2_BYTES = TILE * RB2, STAGE_BYTES = Y1_BYTES + Y2_BYTES;
-  static constexpr int ROW_BYTES = 2 * TILE * 4;  // per stage: -lse*log2(e) and delta of the tile's rows
+  static constexpr int ROW_BYTES = 2 * TILE * 4;  // per stage: bias*log2(e) - lse*log2(e) and delta of the tile's rows
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * ROW_BYTES;
-  static constexpr int T1 = DQK / 16, T2 = DV / 16, DB1 = DQK / 32, DB2 = DV / 32;
   static_assert(NORM == NORM_SOFTMAX || NORM == NORM_SIGMOID, "backward: softmax and sigmoid only");
-  static_assert(LDS_BYTES <= 160 * 1024, "tiles do not fit LDS");
+  static_assert(LDS_BYTES <= (OCC2 ? 80 : 160) * 1024, "the workgroups of a CU must fit LDS");
+  static_assert((TILE * CPR1 / 64) % WAVES == 0 && (TILE * CPR2 / 64) % WAVES == 0, "every wave copies the same number of blocks");
 };
 
 __device__ __forceinline__ bf16x8 read_tr_frag(uint32_t addr_lo, uint32_t addr_hi) {
@@ -88,7 +103,7 @@ __device__ __forceinline__ bf16x8 pack8(const float (&x)[16], int t) {
 }
 
 template <class C>
-__global__ __launch_bounds__(C::THREADS) void attn_bwd_kernel(const BwdParams p) {
+__global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(const BwdParams p) {
   __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const uint32_t rows0 = lds0 + 2 * C::STAGE_BYTES;
@@ -114,7 +129,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_bwd_kernel(const BwdParams p)
                                 : p.Q + b * p.qs[0] + ho * p.qs[1] + (int64_t)own_c * p.qs[2];
   const __bf16* x2 = C::KV_SIDE ? p.V + b * p.vs[0] + hk * p.vs[1] + (int64_t)own_c * p.vs[2]
                                 : p.dO + (((int64_t)b * p.H_q + ho) * p.L_q + own_c) * C::DV;
-  bf16x8 xb1[C::T1], xb2[C::T2];
+  bf16x8 xb1[C::T1], xb2[C::NEED_DP ? C::T2 : 1];
 #pragma unroll
   for (int t = 0; t < C::T1; ++t) xb1[t] = *reinterpret_cast<const bf16x8*>(x1 + (2 * t + half) * 8);
 #pragma unroll
@@ -125,7 +140,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_bwd_kernel(const BwdParams p)
     if (own < p.L_q) {
       const int64_t r = ((int64_t)b * p.H_q + ho) * p.L_q + own;
       const float lse = p.lse[r];
-      nl_own = lse == -INFINITY ? -INFINITY : -lse * 1.4426950408889634f;
+      nl_own = lse == -INFINITY ? -INFINITY : p.b2 - lse * 1.4426950408889634f;
       dl_own = p.delta[r];
     }
   }
@@ -158,7 +173,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_bwd_kernel(const BwdParams p)
     const int64_t s1 = C::KV_SIDE ? p.qs[2] : p.ks[2], s2 = C::KV_SIDE ? (int64_t)C::DV : p.vs[2];
     const uint32_t base = lds0 + stage * C::STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < C::CPR1 / C::WAVES; ++i) {
+    for (int i = 0; i < C::TILE * C::CPR1 / 64 / C::WAVES; ++i) {
       const int nb = wave + i * C::WAVES, pos = nb * 64 + lane;
       const int r = pos / C::CPR1, pc = pos % C::CPR1;
       int row = r0 + r;
@@ -167,7 +182,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_bwd_kernel(const BwdParams p)
       dma16(y1, goff, base + nb * 1024);
     }
 #pragma unroll
-    for (int i = 0; i < C::CPR2 / C::WAVES; ++i) {
+    for (int i = 0; i < C::TILE * C::CPR2 / 64 / C::WAVES; ++i) {
       const int nb = wave + i * C::WAVES, pos = nb * 64 + lane;
       const int r = pos / C::CPR2, pc = pos % C::CPR2;
       int row = r0 + r;
@@ -176,17 +191,17 @@ __global__ __launch_bounds__(C::THREADS) void attn_bwd_kernel(const BwdParams p)
       dma16(y2, goff, base + C::Y1_BYTES + nb * 1024);
     }
   };
-  // key side: the tile's row quantities, wave 0 -> -lse*log2(e), wave 1 -> delta
+  // key side: the tile's row quantities, wave 0 -> (bias - lse) * log2(e), wave 1 -> delta
   auto load_rowq = [&](int n) -> float {
     float v = 0.f;
     if constexpr (C::KV_SIDE && C::NORM == NORM_SOFTMAX) {
-      if (wave < 2) {
+      if (wave < 2 && lane < C::TILE) {
         const int hq = hk * p.g + n / nt;
         const int i = (t_first + n % nt) * C::TILE + lane;
         const int64_t r = ((int64_t)b * p.H_q + hq) * p.L_q + i;
         if (wave == 0) {
           const float lse = i < p.L_q ? p.lse[r] : -INFINITY;
-          v = lse == -INFINITY ? -INFINITY : -lse * 1.4426950408889634f;
+          v = lse == -INFINITY ? -INFINITY : p.b2 - lse * 1.4426950408889634f;
         } else {
           v = i < p.L_q ? p.delta[r] : 0.f;
         }
@@ -196,143 +211,163 @@ __global__ __launch_bounds__(C::THREADS) void attn_bwd_kernel(const BwdParams p)
   };
   auto store_rowq = [&](float v, int stage) {
     if constexpr (C::KV_SIDE && C::NORM == NORM_SOFTMAX) {
-      if (wave < 2)
+      if (wave < 2 && lane < C::TILE)
         *reinterpret_cast<__attribute__((address_space(3))) float*>(
             (lds_char*)(uintptr_t)(rows0 + stage * C::ROW_BYTES + wave * C::TILE * 4 + lane * 4)) = v;
     }
   };
 
-  f32x16 g1[C::DB1], g2[C::KV_SIDE ? C::DB2 : 1];
+  f32x16 g[C::DB];
 #pragma unroll
-  for (int d = 0; d < C::DB1; ++d) g1[d] = zero16();
-#pragma unroll
-  for (int d = 0; d < (C::KV_SIDE ? C::DB2 : 1); ++d) g2[d] = zero16();
+  for (int d = 0; d < C::DB; ++d) g[d] = zero16();
 
-  // per-lane pieces of the fragment addresses
-  const int f1 = bswz<C::CPR1>(ln), f2 = bswz<C::CPR2>(ln);             // row fragments: row = lane % 32
+  // Per-lane LDS addresses of the fragments in stage 0, sub-tile 0, step 0; stage, sub-tile and
+  // 16-row step add compile-time constants (the swizzle only depends on the row modulo 16).
+  //   ar1[t], ar2[t]: row fragment of contraction step t, row lane % 32 (A operand of S / dP);
+  //   atl[k], ath[k]: the two transposing reads of 32-column block k, rows 4*half + i/4 (+8).
+  // Where the registers allow (PRE) all of them are kept; otherwise the XOR is redone per read.
+  constexpr int RBT = C::OUT == BWD_DV ? C::RB2 : C::RB1;  // rows of the tile that is read transposed
+  constexpr bool PRE = C::PRE;
+  const int f1 = bswz<C::CPR1>(ln), f2 = bswz<C::CPR2>(ln);
   const int li = lane & 15, blk = (lane >> 4) & 1;
-  const int trow = 4 * half + (li >> 2);                               // transposing reads: row within 16
-  const int tcl = 2 * blk + ((li & 3) >> 1);                            // chunk within a 32-column block
-  const int f1lo = bswz<C::CPR1>(trow), f1hi = bswz<C::CPR1>(trow + 8);
-  const int f2lo = bswz<C::CPR2>(trow), f2hi = bswz<C::CPR2>(trow + 8);
+  const int trow = 4 * half + (li >> 2), tcl = 2 * blk + ((li & 3) >> 1);
+  const int flo = bswz<RBT / 16>(trow), fhi = bswz<RBT / 16>(trow + 8);
+  const uint32_t rb1 = lds0 + ln * C::RB1, rb2 = lds0 + C::Y1_BYTES + ln * C::RB2;
+  const uint32_t tbl = lds0 + (C::OUT == BWD_DV ? C::Y1_BYTES : 0) + (li & 1) * 8 + trow * RBT, tbh = tbl + 8 * RBT;
+  // (!PRE: the swizzle value passes through an empty asm at every use, or the compiler would hoist
+  // the addresses out of the loop all the same and spill them)
+  auto fresh = [](int f) {
+    if constexpr (!PRE) asm volatile("" : "+v"(f));
+    return f;
+  };
+  auto a_r1 = [&](int t) { return rb1 + (((2 * t + half) ^ fresh(f1)) << 4); };
+  auto a_r2 = [&](int t) { return rb2 + (((2 * t + half) ^ fresh(f2)) << 4); };
+  auto a_tl = [&](int k) { return tbl + (((4 * k + tcl) ^ fresh(flo)) << 4); };
+  auto a_th = [&](int k) { return tbh + (((4 * k + tcl) ^ fresh(fhi)) << 4); };
+  uint32_t ar1[PRE ? C::T1 : 1], ar2[PRE && C::NEED_DP ? C::T2 : 1], atl[PRE ? C::DB : 1], ath[PRE ? C::DB : 1];
+  if constexpr (PRE) {
+#pragma unroll
+    for (int t = 0; t < C::T1; ++t) ar1[t] = a_r1(t);
+#pragma unroll
+    for (int t = 0; t < C::T2; ++t) ar2[t] = a_r2(t);
+#pragma unroll
+    for (int k = 0; k < C::DB; ++k) {
+      atl[k] = a_tl(k);
+      ath[k] = a_th(k);
+    }
+  }
+
+  // One 32-row sub-tile of the other side (STAGE, SUB: compile-time LDS position; o0: its first row).
+  auto subtile = [&](auto stagec, auto subc, int o0) {
+    constexpr int STAGE = decltype(stagec)::value, SUB = decltype(subc)::value;
+    // anything visible to this wave's rows?  everything?
+    bool any = o0 < L_oth, full = o0 + 31 < L_oth;
+    if constexpr (C::CAUSAL) {
+      if constexpr (C::KV_SIDE) {  // own = keys j, other = queries i: visible iff j <= i + off
+        any = any && ow0 <= o0 + 31 + off;
+        full = full && ow0 + 31 <= o0 + off;
+      } else {                     // own = queries i, other = keys j
+        any = any && o0 <= ow0 + 31 + off;
+        full = full && o0 + 31 <= ow0 + off;
+      }
+    }
+    if (!any) return;
+    constexpr uint32_t kRow1 = STAGE * C::STAGE_BYTES + SUB * 32 * C::RB1, kRow2 = STAGE * C::STAGE_BYTES + SUB * 32 * C::RB2;
+    f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+    for (int t = 0; t < C::T1; ++t) s = mfma(read_k_frag((PRE ? ar1[PRE ? t : 0] : a_r1(t)) + kRow1), xb1[t], s);
+#pragma unroll
+    for (int t = 0; t < C::T2; ++t) dp = mfma(read_k_frag((PRE ? ar2[PRE ? t : 0] : a_r2(t)) + kRow2), xb2[t], dp);
+    // elementwise: register r is other-side row o0 + 8*(r/4) + 4*half + (r%4)
+    constexpr uint32_t kRq = 2 * C::STAGE_BYTES + STAGE * C::ROW_BYTES + SUB * 32 * 4;
+    float x[16];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      f32x4 nl4 = f32x4{nl_own, nl_own, nl_own, nl_own};
+      if constexpr (C::NORM == NORM_SOFTMAX && C::KV_SIDE) nl4 = lds_read16(lds0 + kRq + (8 * q + 4 * half) * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        x[4 * q + e] = __builtin_fmaf(s[4 * q + e], p.c2, C::NORM == NORM_SOFTMAX ? nl4[e] : p.b2);
+    }
+    if (!full) {  // a hidden entry gets the exponent that makes its weight exactly 0
+      sched_fence();  // (keeps this a branch: most sub-tiles skip it)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int oth = o0 + key_offset(r) + 4 * half;
+        bool vis = oth < L_oth;
+        if constexpr (C::CAUSAL) vis = vis && (C::KV_SIDE ? own <= oth + off : oth <= own + off);
+        x[r] = vis ? x[r] : -INFINITY;
+      }
+      sched_fence();
+    }
+    float w[16];  // the weight (dV) or the score gradient (dQ, dK)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      f32x4 dl4 = f32x4{dl_own, dl_own, dl_own, dl_own};
+      if constexpr (C::NORM == NORM_SOFTMAX && C::KV_SIDE && C::NEED_DP)
+        dl4 = lds_read16(lds0 + kRq + C::TILE * 4 + (8 * q + 4 * half) * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = 4 * q + e;
+        float pv;
+        if constexpr (C::NORM == NORM_SOFTMAX) {
+          pv = fast_exp2(x[r]);
+          if constexpr (C::NEED_DP) pv = pv * (dp[r] - dl4[e]);
+        } else {
+          pv = fast_rcp(1.f + fast_exp2(-x[r]));
+          if constexpr (C::NEED_DP) pv = dp[r] * pv * (1.f - pv);
+        }
+        w[r] = pv;
+      }
+    }
+    // G^T += Y^T W: per 16-row step t, the DB blocks of Y1^T (dQ, dK) or Y2^T (dV)
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const bf16x8 wb = pack8(w, t);
+      constexpr uint32_t kT = STAGE * C::STAGE_BYTES + SUB * 32 * RBT;
+#pragma unroll
+      for (int k = 0; k < C::DB; ++k)
+        g[k] = mfma(read_tr_frag((PRE ? atl[PRE ? k : 0] : a_tl(k)) + kT + t * 16 * RBT, (PRE ? ath[PRE ? k : 0] : a_th(k)) + kT + t * 16 * RBT), wb, g[k]);
+    }
+  };
+  // Tile n: wait for it, start the copy of tile n + 1 into the other stage, work on it.
+  auto tile = [&](auto stagec, int n) {
+    constexpr int STAGE = decltype(stagec)::value;
+    // tile n has landed, and every wave is done with the stage that tile n + 1 goes to
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    float rowq_next = 0.f;
+    if (n + 1 < total) {
+      issue_tile(n + 1, STAGE ^ 1);
+      rowq_next = load_rowq(n + 1);
+    }
+    const int r0 = (t_first + (C::KV_SIDE ? n % nt : n)) * C::TILE;
+    subtile(stagec, std::integral_constant<int, 0>{}, r0);
+    if constexpr (C::TILE == 64) subtile(stagec, std::integral_constant<int, 1>{}, r0 + 32);
+    if (n + 1 < total) store_rowq(rowq_next, STAGE ^ 1);
+  };
 
   if (total > 0) {
     issue_tile(0, 0);
     store_rowq(load_rowq(0), 0);
   }
-  for (int n = 0; n < total; ++n) {
-    const int stage = n & 1;
-    // tile n has landed, and every wave is done with the stage that tile n + 1 goes to
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    float rowq_next = 0.f;
-    if (n + 1 < total) {
-      issue_tile(n + 1, stage ^ 1);
-      rowq_next = load_rowq(n + 1);
-    }
-    const uint32_t y1b = lds0 + stage * C::STAGE_BYTES, y2b = y1b + C::Y1_BYTES;
-    const uint32_t rqb = rows0 + stage * C::ROW_BYTES;
-    const int r0 = (t_first + (C::KV_SIDE ? n % nt : n)) * C::TILE;
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      const int o0 = r0 + 32 * sub;  // first other-side row of the sub-tile
-      // anything visible to this wave's rows?  everything?
-      bool any = o0 < L_oth, full = o0 + 31 < L_oth;
-      if constexpr (C::CAUSAL) {
-        if constexpr (C::KV_SIDE) {  // own = keys j, other = queries i: visible iff j <= i + off
-          any = any && ow0 <= o0 + 31 + off;
-          full = full && ow0 + 31 <= o0 + off;
-        } else {                     // own = queries i, other = keys j
-          any = any && o0 <= ow0 + 31 + off;
-          full = full && o0 + 31 <= ow0 + off;
-        }
-      }
-      if (!any) continue;
-      // S and dP
-      f32x16 s = zero16(), dp = zero16();
-      {
-        const uint32_t a1 = y1b + (32 * sub + ln) * C::RB1, a2 = y2b + (32 * sub + ln) * C::RB2;
-#pragma unroll
-        for (int t = 0; t < C::T1; ++t) s = mfma(read_k_frag(a1 + (((2 * t + half) ^ f1) << 4)), xb1[t], s);
-#pragma unroll
-        for (int t = 0; t < C::T2; ++t) dp = mfma(read_k_frag(a2 + (((2 * t + half) ^ f2) << 4)), xb2[t], dp);
-      }
-      // elementwise: register r is other-side row o0 + 8*(r/4) + 4*half + (r%4)
-      float pw[16], dw[16];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        f32x4 nl4, dl4;
-        if constexpr (C::NORM == NORM_SOFTMAX) {
-          if constexpr (C::KV_SIDE) {
-            nl4 = lds_read16(rqb + (32 * sub + 8 * q + 4 * half) * 4);
-            dl4 = lds_read16(rqb + C::TILE * 4 + (32 * sub + 8 * q + 4 * half) * 4);
-          } else {
-            nl4 = f32x4{nl_own, nl_own, nl_own, nl_own};
-            dl4 = f32x4{dl_own, dl_own, dl_own, dl_own};
-          }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * q + e;
-          float x = __builtin_fmaf(s[r], p.c2, C::NORM == NORM_SOFTMAX ? p.b2 + nl4[e] : p.b2);
-          if (!full) {  // a hidden entry gets the exponent that makes its weight exactly 0
-            const int oth = o0 + 8 * q + 4 * half + e;
-            bool vis = oth < L_oth;
-            if constexpr (C::CAUSAL) vis = vis && (C::KV_SIDE ? own <= oth + off : oth <= own + off);
-            x = vis ? x : -INFINITY;
-          }
-          float pv, dv;
-          if constexpr (C::NORM == NORM_SOFTMAX) {
-            pv = fast_exp2(x);
-            dv = pv * (dp[r] - dl4[e]);
-          } else {
-            pv = fast_rcp(1.f + fast_exp2(-x));
-            dv = dp[r] * pv * (1.f - pv);
-          }
-          pw[r] = pv;
-          dw[r] = dv;
-        }
-      }
-      // G1^T += Y1^T dS,  G2^T += Y2^T P
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8 dsb = pack8(dw, t);
-        const uint32_t rb1 = y1b + (32 * sub + 16 * t + trow) * C::RB1 + (li & 1) * 8;
-#pragma unroll
-        for (int db = 0; db < C::DB1; ++db)
-          g1[db] = mfma(read_tr_frag(rb1 + (((4 * db + tcl) ^ f1lo) << 4), rb1 + 8 * C::RB1 + (((4 * db + tcl) ^ f1hi) << 4)),
-                        dsb, g1[db]);
-        if constexpr (C::KV_SIDE) {
-          const bf16x8 pb = pack8(pw, t);
-          const uint32_t rb2 = y2b + (32 * sub + 16 * t + trow) * C::RB2 + (li & 1) * 8;
-#pragma unroll
-          for (int db = 0; db < C::DB2; ++db)
-            g2[db] = mfma(read_tr_frag(rb2 + (((4 * db + tcl) ^ f2lo) << 4), rb2 + 8 * C::RB2 + (((4 * db + tcl) ^ f2hi) << 4)),
-                          pb, g2[db]);
-        }
-      }
-    }
-    if (n + 1 < total) store_rowq(rowq_next, stage ^ 1);
+  for (int n = 0; n < total; n += 2) {
+    tile(std::integral_constant<int, 0>{}, n);
+    if (n + 1 < total) tile(std::integral_constant<int, 1>{}, n + 1);
   }
 
   // ---- results: register r of block db is column own, row d = 32 db + 8 (r/4) + 4 half + r%4 ----
   if (own < L_own) {
-    float* o1 = C::KV_SIDE ? p.dK + (((int64_t)b * p.H_kv + hk) * p.L_k + own) * C::DQK
-                           : p.dQ + (((int64_t)b * p.H_q + ho) * p.L_q + own) * C::DQK;
+    constexpr int D = C::OUT == BWD_DV ? C::DV : C::DQK;
+    float* o = (C::OUT == BWD_DQ   ? p.dQ + ((int64_t)b * p.H_q + ho) * p.L_q * D
+                : C::OUT == BWD_DK ? p.dK + ((int64_t)b * p.H_kv + hk) * p.L_k * D
+                                   : p.dV + ((int64_t)b * p.H_kv + hk) * p.L_k * D) + (int64_t)own * D;
+    const float f = C::OUT == BWD_DV ? 1.f : p.scale;
 #pragma unroll
-    for (int db = 0; db < C::DB1; ++db)
+    for (int db = 0; db < C::DB; ++db)
 #pragma unroll
       for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<f32x4*>(o1 + 32 * db + 8 * q + 4 * half) =
-            f32x4{g1[db][4 * q] * p.scale, g1[db][4 * q + 1] * p.scale, g1[db][4 * q + 2] * p.scale, g1[db][4 * q + 3] * p.scale};
-    if constexpr (C::KV_SIDE) {
-      float* o2 = p.dV + (((int64_t)b * p.H_kv + hk) * p.L_k + own) * C::DV;
-#pragma unroll
-      for (int db = 0; db < C::DB2; ++db)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          *reinterpret_cast<f32x4*>(o2 + 32 * db + 8 * q + 4 * half) =
-              f32x4{g2[db][4 * q], g2[db][4 * q + 1], g2[db][4 * q + 2], g2[db][4 * q + 3]};
-      }
+        *reinterpret_cast<f32x4*>(o + 32 * db + 8 * q + 4 * half) =
+            f32x4{g[db][4 * q] * f, g[db][4 * q + 1] * f, g[db][4 * q + 2] * f, g[db][4 * q + 3] * f};
   }
 }
 
