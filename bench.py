@@ -266,8 +266,8 @@ def main():
         return
     if a.backward:
         # Not the contract line.  Algorithmic work of the backward pass: five contractions per visible (query, key)
-        # pair (S, dP, dV, dK, dQ) = 2 * (3 D_qk + 2 D_v) flop; each of the three kernels (dK, dV, dQ) recomputes the
-        # scores it needs, so the MFMAs they issue amount to 2 * (5 D_qk + 3 D_v) flop per pair.
+        # pair (S, dP, dV, dK, dQ) = 2 * (3 D_qk + 2 D_v) flop; the key-side and the query-side kernel each recompute
+        # S and dP, so the MFMAs they issue amount to 2 * (4 D_qk + 3 D_v) flop per pair.
         from oracle import attention_backward
         from paper_2502_15349_amd.workloads import C2, C3, C5, Workload, make_grad
         rows = []
@@ -305,7 +305,7 @@ def main():
             A.ae_attn_destroy(h)
             ms = e0.elapsed_time(e1) / n
             pairs = w.visible_pairs_per_head() * w.B * w.H_q
-            alg, issued = 2 * (3 * w.D_qk + 2 * w.D_v) * pairs, 2 * (5 * w.D_qk + 3 * w.D_v) * pairs
+            alg, issued = 2 * (3 * w.D_qk + 2 * w.D_v) * pairs, 2 * (4 * w.D_qk + 3 * w.D_v) * pairs
             par = None
             if w.L_q <= 4096:   # one (batch, k/v head) group against the oracle
                 b, hk, g = w.B - 1, w.H_kv // 2, w.H_q // w.H_kv

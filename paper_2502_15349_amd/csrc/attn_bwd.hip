@@ -22,21 +22,19 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const BwdParams p, 
   if (lane == 0) p.delta[r] = acc;
 }
 
+template <int DQK, int DV, int NORM, bool CAUSAL, int OUT>
+hipError_t launch_one(const BwdParams& p, hipStream_t s) {
+  typedef BwdCfg<DQK, DV, NORM, CAUSAL, OUT> C;
+  const int heads = C::KV_SIDE ? p.H_kv : p.H_q, L = C::KV_SIDE ? p.L_k : p.L_q;
+  hipLaunchKernelGGL(attn_bwd_kernel<C>, dim3((unsigned)(p.B * heads * ((L + C::OWN - 1) / C::OWN))), dim3(C::THREADS), 0, s, p);
+  return hipGetLastError();
+}
+
 template <int DQK, int DV, int NORM, bool CAUSAL>
 hipError_t launch_pair(const BwdParams& p, hipStream_t s) {
-  typedef BwdCfg<DQK, DV, NORM, CAUSAL, BWD_DK> CK;
-  typedef BwdCfg<DQK, DV, NORM, CAUSAL, BWD_DV> CV;
-  typedef BwdCfg<DQK, DV, NORM, CAUSAL, BWD_DQ> CQ;
-  const unsigned gk = (unsigned)(p.B * p.H_kv * ((p.L_k + CK::OWN - 1) / CK::OWN));
-  const unsigned gq = (unsigned)(p.B * p.H_q * ((p.L_q + CQ::OWN - 1) / CQ::OWN));
-  hipLaunchKernelGGL(attn_bwd_kernel<CK>, dim3(gk), dim3(CK::THREADS), 0, s, p);
-  hipError_t e = hipGetLastError();
+  const hipError_t e = launch_one<DQK, DV, NORM, CAUSAL, BWD_DKV>(p, s);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_kernel<CV>, dim3(gk), dim3(CV::THREADS), 0, s, p);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_kernel<CQ>, dim3(gq), dim3(CQ::THREADS), 0, s, p);
-  return hipGetLastError();
+  return launch_one<DQK, DV, NORM, CAUSAL, BWD_DQ>(p, s);
 }
 
 template <int DQK, int DV>

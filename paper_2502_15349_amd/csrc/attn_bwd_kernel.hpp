@@ -9,17 +9,19 @@
 //   dS' = P * (dP - delta_i), delta_i = dO_i . O_i  (softmax)   |  dP * P * (1 - P)  (sigmoid)
 //   dQ  = scale * dS' K                   dK = scale * dS'^T Q
 //
-// Three kernels of one shape, one per gradient, no atomics, every output written once:
-//   * dK, dV (key side, KV_SIDE): a workgroup owns 128 keys of one k/v head and walks the
-//     query tiles of the q heads that share it;
-//   * dQ (query side): a workgroup owns 128 query rows of one q head and walks the key tiles.
-// (dK and dV in one kernel would save recomputing S once, but its two accumulators and two
-// resident operands fill the 256 registers of a two-waves-per-SIMD kernel on their own, and
-// with nothing left to read LDS ahead of the MFMAs it ran at 28 % matrix-pipe occupancy where
-// the kernels below reach twice that.)
+// Two kernels of one shape, no atomics, every output written once:
+//   * key side (KV_SIDE): a workgroup owns 128 keys of one k/v head and walks the query tiles of
+//     the q heads that share it: dK and dV;
+//   * query side: a workgroup owns 128 query rows of one q head and walks the key tiles: dQ.
+// The key-side kernel holds two accumulators and two resident operands; from D 128/128 on that
+// is more than the 256 registers of a two-waves-per-SIMD kernel, and it then runs one workgroup
+// per CU with up to 512 (a variant squeezed into 256 spilled in its inner loop and was 1.5 x
+// slower; separate dK and dV kernels at two waves per SIMD recompute the scores once more and
+// were 15-25 % slower than the fused one).  Both kernels run against the board's power limit:
+// the clock under load is 1.4-1.7 GHz.
 // In both a wavefront owns 32 rows ("own" side) whose two operand matrices it keeps in
 // registers as MFMA B fragments (K, V | Q, dO), and the tiles of the other side (Q, dO |
-// K, V; 64 or 32 rows, double buffered) arrive in LDS by global_load_lds.  Per 32-row sub-tile
+// K, V; 64 rows, double buffered) arrive in LDS by global_load_lds.  Per 32-row sub-tile
 //   S  [other x own] = Y1 X1^T      dP [other x own] = Y2 X2^T        (bf16 MFMA 32x32x16)
 // put a lane's 16 accumulator values in one own column; after the elementwise step they
 // are, packed to bf16 and with no data movement, the B operands of
@@ -61,24 +63,21 @@ __device__ __forceinline__ int bswz(int row) {
   return CPR % 16 == 0 ? ((4 * (row & 3)) | ((row >> 2) & 3)) : ((4 * ((row >> 1) & 1)) | ((row >> 2) & 3));
 }
 
-enum : int { BWD_DQ = 0, BWD_DK = 1, BWD_DV = 2 };
+enum : int { BWD_DQ = 0, BWD_DKV = 1 };  // the query-side kernel (dQ), the key-side kernel (dK and dV)
 
 template <int DQK_, int DV_, int NORM_, bool CAUSAL_, int OUT_>
 struct BwdCfg {
   static constexpr int DQK = DQK_, DV = DV_, NORM = NORM_, OUT = OUT_;
-  static constexpr bool CAUSAL = CAUSAL_, KV_SIDE = OUT_ != BWD_DQ;
-  static constexpr bool NEED_DP = OUT_ != BWD_DV;  // the dV kernel needs the weights only
+  static constexpr bool CAUSAL = CAUSAL_, KV_SIDE = OUT_ == BWD_DKV;
   static constexpr int WAVES = 4, THREADS = 256, OWN = 128;  // own rows per workgroup
-  static constexpr int T1 = DQK / 16, T2 = NEED_DP ? DV / 16 : 0;
-  static constexpr int DB = (OUT_ == BWD_DV ? DV : DQK) / 32;  // 32-row blocks of the transposed result
+  static constexpr int T1 = DQK / 16, T2 = DV / 16;
+  static constexpr int DB = DQK / 32;  // 32-row blocks of the transposed result dQ^T / dK^T
+  static constexpr bool HAS2 = KV_SIDE;               // key side: a second result, dV^T
+  static constexpr int DB2 = HAS2 ? DV / 32 : 0;
   // Two workgroups per CU (two waves per SIMD, 256 registers each) where the accumulators, the
   // resident operands and the two score tiles leave room for the rest; one (512 registers) otherwise.
-  static constexpr bool OCC2 = 16 * DB + 4 * T1 + 4 * T2 + (NEED_DP ? 32 : 16) <= 176;
-  // other-side rows per LDS tile: 64, or 32 where two 64-row stages would not leave room for two
-  // workgroups per CU (80 KB each)
-  static constexpr int TILE = !OCC2 || 2 * 64 * (DQK + DV) * 2 + 1024 <= 80 * 1024 ? 64 : 32;
-  // per-lane fragment addresses kept in registers
-  static constexpr bool PRE = !OCC2 || DQK + DV <= 256;
+  static constexpr bool OCC2 = 16 * (DB + DB2) + 4 * T1 + 4 * T2 + 32 <= 176;
+  static constexpr int TILE = 64;  // other-side rows per LDS tile (two 32-row sub-tiles)
   static constexpr int RB1 = DQK * 2, RB2 = DV * 2, CPR1 = DQK / 8, CPR2 = DV / 8;
   static constexpr int Y1_BYTES = TILE * RB1, Y2_BYTES = TILE * RB2, STAGE_BYTES = Y1_BYTES + Y2_BYTES;
   static constexpr int ROW_BYTES = 2 * TILE * 4;  // per stage: bias*log2(e) - lse*log2(e) and delta of the tile's rows
@@ -129,7 +128,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
                                 : p.Q + b * p.qs[0] + ho * p.qs[1] + (int64_t)own_c * p.qs[2];
   const __bf16* x2 = C::KV_SIDE ? p.V + b * p.vs[0] + hk * p.vs[1] + (int64_t)own_c * p.vs[2]
                                 : p.dO + (((int64_t)b * p.H_q + ho) * p.L_q + own_c) * C::DV;
-  bf16x8 xb1[C::T1], xb2[C::NEED_DP ? C::T2 : 1];
+  bf16x8 xb1[C::T1], xb2[C::T2];
 #pragma unroll
   for (int t = 0; t < C::T1; ++t) xb1[t] = *reinterpret_cast<const bf16x8*>(x1 + (2 * t + half) * 8);
 #pragma unroll
@@ -191,7 +190,9 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       dma16(y2, goff, base + C::Y1_BYTES + nb * 1024);
     }
   };
-  // key side: the tile's row quantities, wave 0 -> (bias - lse) * log2(e), wave 1 -> delta
+  // key side: the tile's row quantities, wave 0 -> (bias - lse) * log2(e), wave 1 -> delta.  The
+  // values are requested when the tile's copy starts and only touched (converted, written to LDS)
+  // after the work on the tile before it: nothing waits for memory in between.
   auto load_rowq = [&](int n) -> float {
     float v = 0.f;
     if constexpr (C::KV_SIDE && C::NORM == NORM_SOFTMAX) {
@@ -199,53 +200,56 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
         const int hq = hk * p.g + n / nt;
         const int i = (t_first + n % nt) * C::TILE + lane;
         const int64_t r = ((int64_t)b * p.H_q + hq) * p.L_q + i;
-        if (wave == 0) {
-          const float lse = i < p.L_q ? p.lse[r] : -INFINITY;
-          v = lse == -INFINITY ? -INFINITY : p.b2 - lse * 1.4426950408889634f;
-        } else {
-          v = i < p.L_q ? p.delta[r] : 0.f;
-        }
+        const float* src = wave == 0 ? p.lse : p.delta;
+        v = wave == 0 ? -INFINITY : 0.f;
+        if (i < p.L_q) v = src[r];
       }
     }
     return v;
   };
   auto store_rowq = [&](float v, int stage) {
     if constexpr (C::KV_SIDE && C::NORM == NORM_SOFTMAX) {
-      if (wave < 2 && lane < C::TILE)
+      if (wave < 2 && lane < C::TILE) {
+        if (wave == 0) v = v == -INFINITY ? -INFINITY : p.b2 - v * 1.4426950408889634f;
         *reinterpret_cast<__attribute__((address_space(3))) float*>(
             (lds_char*)(uintptr_t)(rows0 + stage * C::ROW_BYTES + wave * C::TILE * 4 + lane * 4)) = v;
+      }
     }
   };
 
-  f32x16 g[C::DB];
+  f32x16 g[C::DB], g2[C::HAS2 ? C::DB2 : 1];
 #pragma unroll
   for (int d = 0; d < C::DB; ++d) g[d] = zero16();
+#pragma unroll
+  for (int d = 0; d < C::DB2; ++d) g2[d] = zero16();
 
   // Per-lane LDS addresses of the fragments in stage 0, sub-tile 0, step 0; stage, sub-tile and
   // 16-row step add compile-time constants (the swizzle only depends on the row modulo 16).
   //   ar1[t], ar2[t]: row fragment of contraction step t, row lane % 32 (A operand of S / dP);
   //   atl[k], ath[k]: the two transposing reads of 32-column block k, rows 4*half + i/4 (+8).
-  // Where the registers allow (PRE) all of them are kept; otherwise the XOR is redone per read.
-  constexpr int RBT = C::OUT == BWD_DV ? C::RB2 : C::RB1;  // rows of the tile that is read transposed
-  constexpr bool PRE = C::PRE;
+  constexpr int RBT = C::RB1;  // row bytes of the Y1 tile, read transposed for dQ^T / dK^T
   const int f1 = bswz<C::CPR1>(ln), f2 = bswz<C::CPR2>(ln);
   const int li = lane & 15, blk = (lane >> 4) & 1;
   const int trow = 4 * half + (li >> 2), tcl = 2 * blk + ((li & 3) >> 1);
   const int flo = bswz<RBT / 16>(trow), fhi = bswz<RBT / 16>(trow + 8);
   const uint32_t rb1 = lds0 + ln * C::RB1, rb2 = lds0 + C::Y1_BYTES + ln * C::RB2;
-  const uint32_t tbl = lds0 + (C::OUT == BWD_DV ? C::Y1_BYTES : 0) + (li & 1) * 8 + trow * RBT, tbh = tbl + 8 * RBT;
-  // (!PRE: the swizzle value passes through an empty asm at every use, or the compiler would hoist
-  // the addresses out of the loop all the same and spill them)
-  auto fresh = [](int f) {
-    if constexpr (!PRE) asm volatile("" : "+v"(f));
-    return f;
-  };
-  auto a_r1 = [&](int t) { return rb1 + (((2 * t + half) ^ fresh(f1)) << 4); };
-  auto a_r2 = [&](int t) { return rb2 + (((2 * t + half) ^ fresh(f2)) << 4); };
-  auto a_tl = [&](int k) { return tbl + (((4 * k + tcl) ^ fresh(flo)) << 4); };
-  auto a_th = [&](int k) { return tbh + (((4 * k + tcl) ^ fresh(fhi)) << 4); };
-  uint32_t ar1[PRE ? C::T1 : 1], ar2[PRE && C::NEED_DP ? C::T2 : 1], atl[PRE ? C::DB : 1], ath[PRE ? C::DB : 1];
-  if constexpr (PRE) {
+  const uint32_t tbl = lds0 + (li & 1) * 8 + trow * RBT, tbh = tbl + 8 * RBT;
+  auto a_r1 = [&](int t) { return rb1 + (((2 * t + half) ^ f1) << 4); };
+  auto a_r2 = [&](int t) { return rb2 + (((2 * t + half) ^ f2) << 4); };
+  auto a_tl = [&](int k) { return tbl + (((4 * k + tcl) ^ flo) << 4); };
+  auto a_th = [&](int k) { return tbh + (((4 * k + tcl) ^ fhi) << 4); };
+  uint32_t ar1[C::T1], ar2[C::T2], atl[C::DB], ath[C::DB];
+  uint32_t atl2[C::HAS2 ? C::DB2 : 1], ath2[C::HAS2 ? C::DB2 : 1];  // fused kernel: the same for the Y2 tile
+  if constexpr (C::HAS2) {
+    const int glo = bswz<C::CPR2>(trow), ghi = bswz<C::CPR2>(trow + 8);
+    const uint32_t t2 = lds0 + C::Y1_BYTES + (li & 1) * 8 + trow * C::RB2;
+#pragma unroll
+    for (int k = 0; k < C::DB2; ++k) {
+      atl2[k] = t2 + (((4 * k + tcl) ^ glo) << 4);
+      ath2[k] = t2 + 8 * C::RB2 + (((4 * k + tcl) ^ ghi) << 4);
+    }
+  }
+  {
 #pragma unroll
     for (int t = 0; t < C::T1; ++t) ar1[t] = a_r1(t);
 #pragma unroll
@@ -273,22 +277,26 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
     }
     if (!any) return;
     constexpr uint32_t kRow1 = STAGE * C::STAGE_BYTES + SUB * 32 * C::RB1, kRow2 = STAGE * C::STAGE_BYTES + SUB * 32 * C::RB2;
-    f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-    for (int t = 0; t < C::T1; ++t) s = mfma(read_k_frag((PRE ? ar1[PRE ? t : 0] : a_r1(t)) + kRow1), xb1[t], s);
-#pragma unroll
-    for (int t = 0; t < C::T2; ++t) dp = mfma(read_k_frag((PRE ? ar2[PRE ? t : 0] : a_r2(t)) + kRow2), xb2[t], dp);
-    // elementwise: register r is other-side row o0 + 8*(r/4) + 4*half + (r%4)
+    // key side: the row quantities of the 16 rows this lane sees, requested ahead of the MFMAs that
+    // hide their latency (register r is other-side row o0 + 8*(r/4) + 4*half + (r%4))
     constexpr uint32_t kRq = 2 * C::STAGE_BYTES + STAGE * C::ROW_BYTES + SUB * 32 * 4;
-    float x[16];
+    constexpr bool ROWQ = C::NORM == NORM_SOFTMAX && C::KV_SIDE;
+    f32x4 nl4[4], dl4[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      f32x4 nl4 = f32x4{nl_own, nl_own, nl_own, nl_own};
-      if constexpr (C::NORM == NORM_SOFTMAX && C::KV_SIDE) nl4 = lds_read16(lds0 + kRq + (8 * q + 4 * half) * 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        x[4 * q + e] = __builtin_fmaf(s[4 * q + e], p.c2, C::NORM == NORM_SOFTMAX ? nl4[e] : p.b2);
+      nl4[q] = f32x4{nl_own, nl_own, nl_own, nl_own};
+      dl4[q] = f32x4{dl_own, dl_own, dl_own, dl_own};
+      if constexpr (ROWQ) nl4[q] = lds_read16(lds0 + kRq + (8 * q + 4 * half) * 4);
     }
+    if constexpr (ROWQ) sched_fence();
+    f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+    for (int t = 0; t < C::T1; ++t) s = mfma(read_k_frag(ar1[t] + kRow1), xb1[t], s);
+#pragma unroll
+    for (int t = 0; t < C::T2; ++t) dp = mfma(read_k_frag(ar2[t] + kRow2), xb2[t], dp);
+    float x[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) x[r] = __builtin_fmaf(s[r], p.c2, C::NORM == NORM_SOFTMAX ? nl4[r / 4][r % 4] : p.b2);
     if (!full) {  // a hidden entry gets the exponent that makes its weight exactly 0
       sched_fence();  // (keeps this a branch: most sub-tiles skip it)
 #pragma unroll
@@ -300,25 +308,22 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       }
       sched_fence();
     }
-    float w[16];  // the weight (dV) or the score gradient (dQ, dK)
+    float w[16], w2[C::HAS2 ? 16 : 1];  // the weight (dV) or the score gradient (dQ, dK); fused: both
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      f32x4 dl4 = f32x4{dl_own, dl_own, dl_own, dl_own};
-      if constexpr (C::NORM == NORM_SOFTMAX && C::KV_SIDE && C::NEED_DP)
-        dl4 = lds_read16(lds0 + kRq + C::TILE * 4 + (8 * q + 4 * half) * 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int r = 4 * q + e;
-        float pv;
-        if constexpr (C::NORM == NORM_SOFTMAX) {
-          pv = fast_exp2(x[r]);
-          if constexpr (C::NEED_DP) pv = pv * (dp[r] - dl4[e]);
-        } else {
-          pv = fast_rcp(1.f + fast_exp2(-x[r]));
-          if constexpr (C::NEED_DP) pv = dp[r] * pv * (1.f - pv);
-        }
-        w[r] = pv;
+    for (int r = 0; r < 16; ++r) {
+      if constexpr (ROWQ)
+        if (r % 4 == 0) dl4[r / 4] = lds_read16(lds0 + kRq + C::TILE * 4 + (8 * (r / 4) + 4 * half) * 4);
+      float pv;
+      if constexpr (C::NORM == NORM_SOFTMAX) {
+        pv = fast_exp2(x[r]);
+        if constexpr (C::HAS2) w2[r] = pv;
+        pv = pv * (dp[r] - dl4[r / 4][r % 4]);
+      } else {
+        pv = fast_rcp(1.f + fast_exp2(-x[r]));
+        if constexpr (C::HAS2) w2[r] = pv;
+        pv = dp[r] * pv * (1.f - pv);
       }
+      w[r] = pv;
     }
     // G^T += Y^T W: per 16-row step t, the DB blocks of Y1^T (dQ, dK) or Y2^T (dV)
 #pragma unroll
@@ -327,7 +332,14 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       constexpr uint32_t kT = STAGE * C::STAGE_BYTES + SUB * 32 * RBT;
 #pragma unroll
       for (int k = 0; k < C::DB; ++k)
-        g[k] = mfma(read_tr_frag((PRE ? atl[PRE ? k : 0] : a_tl(k)) + kT + t * 16 * RBT, (PRE ? ath[PRE ? k : 0] : a_th(k)) + kT + t * 16 * RBT), wb, g[k]);
+        g[k] = mfma(read_tr_frag(atl[k] + kT + t * 16 * RBT, ath[k] + kT + t * 16 * RBT), wb, g[k]);
+      if constexpr (C::HAS2) {
+        const bf16x8 pb = pack8(w2, t);
+        constexpr uint32_t kT2 = STAGE * C::STAGE_BYTES + SUB * 32 * C::RB2;
+#pragma unroll
+        for (int k = 0; k < C::DB2; ++k)
+          g2[k] = mfma(read_tr_frag(atl2[k] + kT2 + t * 16 * C::RB2, ath2[k] + kT2 + t * 16 * C::RB2), pb, g2[k]);
+      }
     }
   };
   // Tile n: wait for it, start the copy of tile n + 1 into the other stage, work on it.
@@ -342,7 +354,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
     }
     const int r0 = (t_first + (C::KV_SIDE ? n % nt : n)) * C::TILE;
     subtile(stagec, std::integral_constant<int, 0>{}, r0);
-    if constexpr (C::TILE == 64) subtile(stagec, std::integral_constant<int, 1>{}, r0 + 32);
+    subtile(stagec, std::integral_constant<int, 1>{}, r0 + 32);
     if (n + 1 < total) store_rowq(rowq_next, STAGE ^ 1);
   };
 
@@ -357,17 +369,25 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
 
   // ---- results: register r of block db is column own, row d = 32 db + 8 (r/4) + 4 half + r%4 ----
   if (own < L_own) {
-    constexpr int D = C::OUT == BWD_DV ? C::DV : C::DQK;
-    float* o = (C::OUT == BWD_DQ   ? p.dQ + ((int64_t)b * p.H_q + ho) * p.L_q * D
-                : C::OUT == BWD_DK ? p.dK + ((int64_t)b * p.H_kv + hk) * p.L_k * D
-                                   : p.dV + ((int64_t)b * p.H_kv + hk) * p.L_k * D) + (int64_t)own * D;
-    const float f = C::OUT == BWD_DV ? 1.f : p.scale;
+    constexpr int D = C::DQK;
+    float* o = (C::KV_SIDE ? p.dK + ((int64_t)b * p.H_kv + hk) * p.L_k * D : p.dQ + ((int64_t)b * p.H_q + ho) * p.L_q * D) +
+               (int64_t)own * D;
+    const float f = p.scale;
 #pragma unroll
     for (int db = 0; db < C::DB; ++db)
 #pragma unroll
       for (int q = 0; q < 4; ++q)
         *reinterpret_cast<f32x4*>(o + 32 * db + 8 * q + 4 * half) =
             f32x4{g[db][4 * q] * f, g[db][4 * q + 1] * f, g[db][4 * q + 2] * f, g[db][4 * q + 3] * f};
+    if constexpr (C::HAS2) {
+      float* o2 = p.dV + (((int64_t)b * p.H_kv + hk) * p.L_k + own) * C::DV;
+#pragma unroll
+      for (int db = 0; db < C::DB2; ++db)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          *reinterpret_cast<f32x4*>(o2 + 32 * db + 8 * q + 4 * half) =
+              f32x4{g2[db][4 * q], g2[db][4 * q + 1], g2[db][4 * q + 2], g2[db][4 * q + 3]};
+    }
   }
 }
 
