@@ -77,6 +77,8 @@ struct BwdCfg {
   // Two workgroups per CU (two waves per SIMD, 256 registers each) where the accumulators, the
   // resident operands and the two score tiles leave room for the rest; one (512 registers) otherwise.
   static constexpr bool OCC2 = 16 * (DB + DB2) + 4 * T1 + 4 * T2 + 32 <= 176;
+  // one workgroup per CU: the LDS fragments of a step are read as a batch ahead of its MFMAs
+  static constexpr bool BATCH = !OCC2 && DQK + DV <= 320;  // (beyond that the batches do not fit 512 registers)
   static constexpr int TILE = 64;  // other-side rows per LDS tile (two 32-row sub-tiles)
   static constexpr int RB1 = DQK * 2, RB2 = DV * 2, CPR1 = DQK / 8, CPR2 = DV / 8;
   static constexpr int Y1_BYTES = TILE * RB1, Y2_BYTES = TILE * RB2, STAGE_BYTES = Y1_BYTES + Y2_BYTES;
@@ -290,10 +292,39 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
     }
     if constexpr (ROWQ) sched_fence();
     f32x16 s = zero16(), dp = zero16();
+    // the fragments of the accumulation step: tr[t][k], k < DB from Y1, the rest (key side) from Y2
+    constexpr uint32_t kT = STAGE * C::STAGE_BYTES + SUB * 32 * RBT, kT2 = STAGE * C::STAGE_BYTES + SUB * 32 * C::RB2;
+    auto read_acc = [&](int t, int k) {
+      if constexpr (C::HAS2) {
+        if (k >= C::DB) return read_tr_frag(atl2[k - C::DB] + kT2 + t * 16 * C::RB2, ath2[k - C::DB] + kT2 + t * 16 * C::RB2);
+      }
+      return read_tr_frag(atl[k < C::DB ? k : 0] + kT + t * 16 * RBT, ath[k < C::DB ? k : 0] + kT + t * 16 * RBT);
+    };
+    bf16x8 tr[2][C::BATCH ? C::DB + C::DB2 : 1];
+    if constexpr (C::BATCH) {
+      // One wave per SIMD: nothing else hides the LDS latency, so all fragments of a step are
+      // requested before its first MFMA, and those of the accumulation step before the elementwise
+      // step (the fences keep the compiler from sinking the reads back to their uses).
+      bf16x8 a1[C::T1], a2[C::T2];
 #pragma unroll
-    for (int t = 0; t < C::T1; ++t) s = mfma(read_k_frag(ar1[t] + kRow1), xb1[t], s);
+      for (int t = 0; t < C::T1; ++t) a1[t] = read_k_frag(ar1[t] + kRow1);
 #pragma unroll
-    for (int t = 0; t < C::T2; ++t) dp = mfma(read_k_frag(ar2[t] + kRow2), xb2[t], dp);
+      for (int t = 0; t < C::T2; ++t) a2[t] = read_k_frag(ar2[t] + kRow2);
+      sched_fence();
+#pragma unroll
+      for (int t = 0; t < C::T1; ++t) s = mfma(a1[t], xb1[t], s);
+#pragma unroll
+      for (int t = 0; t < C::T2; ++t) dp = mfma(a2[t], xb2[t], dp);
+      sched_fence();
+#pragma unroll
+      for (int k = 0; k < C::DB + C::DB2; ++k) tr[0][k] = read_acc(0, k);
+      sched_fence();
+    } else {
+#pragma unroll
+      for (int t = 0; t < C::T1; ++t) s = mfma(read_k_frag(ar1[t] + kRow1), xb1[t], s);
+#pragma unroll
+      for (int t = 0; t < C::T2; ++t) dp = mfma(read_k_frag(ar2[t] + kRow2), xb2[t], dp);
+    }
     float x[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) x[r] = __builtin_fmaf(s[r], p.c2, C::NORM == NORM_SOFTMAX ? nl4[r / 4][r % 4] : p.b2);
@@ -325,20 +356,23 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       }
       w[r] = pv;
     }
-    // G^T += Y^T W: per 16-row step t, the DB blocks of Y1^T (dQ, dK) or Y2^T (dV)
+    // G^T += Y^T W: per 16-row step t, the DB blocks of Y1^T (dQ^T, dK^T), then (key side) the DB2 blocks of Y2^T
+    if constexpr (C::BATCH) {
+      sched_fence();
+#pragma unroll
+      for (int k = 0; k < C::DB + C::DB2; ++k) tr[1][k] = read_acc(1, k);
+      sched_fence();
+    }
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const bf16x8 wb = pack8(w, t);
-      constexpr uint32_t kT = STAGE * C::STAGE_BYTES + SUB * 32 * RBT;
 #pragma unroll
-      for (int k = 0; k < C::DB; ++k)
-        g[k] = mfma(read_tr_frag(atl[k] + kT + t * 16 * RBT, ath[k] + kT + t * 16 * RBT), wb, g[k]);
+      for (int k = 0; k < C::DB; ++k) g[k] = mfma(C::BATCH ? tr[t][C::BATCH ? k : 0] : read_acc(t, k), wb, g[k]);
       if constexpr (C::HAS2) {
         const bf16x8 pb = pack8(w2, t);
-        constexpr uint32_t kT2 = STAGE * C::STAGE_BYTES + SUB * 32 * C::RB2;
 #pragma unroll
         for (int k = 0; k < C::DB2; ++k)
-          g2[k] = mfma(read_tr_frag(atl2[k] + kT2 + t * 16 * C::RB2, ath2[k] + kT2 + t * 16 * C::RB2), pb, g2[k]);
+          g2[k] = mfma(C::BATCH ? tr[t][C::BATCH ? C::DB + k : 0] : read_acc(t, C::DB + k), pb, g2[k]);
       }
     }
   };
@@ -362,6 +396,15 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
     issue_tile(0, 0);
     store_rowq(load_rowq(0), 0);
   }
+  // Everything loaded so far is consumed here once.  Otherwise the compiler, which must assume at
+  // the loop's entry that those loads may still be in flight, waits for vmcnt to drain in front of
+  // the MFMAs inside the loop -- and vmcnt also counts the tile copies, so every tile would wait for
+  // the copy of the next one instead of running beside it.
+#pragma unroll
+  for (int t = 0; t < C::T1; ++t) asm volatile("" ::"v"(xb1[t]));
+#pragma unroll
+  for (int t = 0; t < C::T2; ++t) asm volatile("" ::"v"(xb2[t]));
+  asm volatile("" ::"v"(nl_own), "v"(dl_own));
   for (int n = 0; n < total; n += 2) {
     tile(std::integral_constant<int, 0>{}, n);
     if (n + 1 < total) tile(std::integral_constant<int, 1>{}, n + 1);
