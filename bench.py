@@ -269,10 +269,12 @@ def main():
         # pair (S, dP, dV, dK, dQ) = 2 * (3 D_qk + 2 D_v) flop; the key-side and the query-side kernel each recompute
         # S and dP, so the MFMAs they issue amount to 2 * (4 D_qk + 3 D_v) flop per pair.
         from oracle import attention_backward
-        from paper_2502_15349_amd.workloads import C2, C3, C5, Workload, make_grad
+        from paper_2502_15349_amd.workloads import C2, C3, C5, Workload, make_grad, table2_workloads
         rows = []
-        shapes = [C2, C3, C5, Workload("t2_softmax_b8_h32_s8192_noncausal", 150, 8, 32, 32, 8192, 8192, 128, 128),
-                  Workload("t2_softmax_b8_h32_s8192_causal", 151, 8, 32, 32, 8192, 8192, 128, 128, mask="causal")]
+        # the benchmark configurations with a backward pass, one unmasked shape, and the paper's Table 2 shapes at
+        # batch 8 x 8k (softmax at three head-dim pairs, sigmoid, ReLU)
+        shapes = [C2, C3, C5, Workload("t2_softmax_b8_h32_s8192_noncausal", 150, 8, 32, 32, 8192, 8192, 128, 128)]
+        shapes += [w for w in table2_workloads() if w.B == 8 and w.L_q == 8192 and w.L_q == w.L_k]
         for w in shapes:
             if a.only not in w.name:
                 continue

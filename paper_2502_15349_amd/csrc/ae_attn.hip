@@ -356,11 +356,13 @@ ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, c
                              void* stream) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: null handle");
   const ae_attn_desc_t& d = h->desc;
-  const int norm = h->kernel->norm;
-  if (!ae::backward_supported(d.D_qk, d.D_v, norm) || (d.score_mod != AE_MOD_NONE && d.score_mod != AE_MOD_BIAS) ||
-      (d.mask != AE_MASK_NONE && d.mask != AE_MASK_CAUSAL))
+  // no normalization + ReLU is one kernel variant of its own
+  const int norm = d.norm == AE_NORM_NONE && d.score_mod == AE_MOD_RELU ? ae::BWD_NORM_NONE_RELU : h->kernel->norm;
+  const bool mod_ok = d.score_mod == AE_MOD_NONE || d.score_mod == AE_MOD_BIAS || norm == ae::BWD_NORM_NONE_RELU;
+  if (!ae::backward_supported(d.D_qk, d.D_v, norm) || !mod_ok || (d.mask != AE_MASK_NONE && d.mask != AE_MASK_CAUSAL))
     return fail(AE_ERR_UNSUPPORTED,
-                "ae_attn_backward: built for softmax and sigmoid with score_mod NONE or BIAS and masks NONE or CAUSAL");
+                "ae_attn_backward: built for softmax, sigmoid and no normalization with score_mod NONE, BIAS or (no "
+                "normalization) RELU, and masks NONE or CAUSAL");
   const bool softmax = norm == ae::NORM_SOFTMAX;
   if (!Q || !K || !V || !dO || !dQ || !dK || !dV || (softmax && (!O || !stats || !workspace)))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: null device pointer");
@@ -405,8 +407,10 @@ ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, c
     p.os[a] = h->params.os[a];
   }
   const float log2e = 1.4426950408889634f;
-  p.c2 = d.scale * log2e;
-  p.b2 = (d.score_mod == AE_MOD_BIAS ? d.bias : 0.f) * log2e;
+  // softmax and sigmoid work in powers of two; without a normalization the modified score itself is the weight
+  const float unit = norm == ae::NORM_SOFTMAX || norm == ae::NORM_SIGMOID ? log2e : 1.f;
+  p.c2 = d.scale * unit;
+  p.b2 = (d.score_mod == AE_MOD_BIAS ? d.bias : 0.f) * unit;
   p.scale = d.scale;
   hipError_t e = ae::launch_backward(p, d.D_qk, d.D_v, norm, d.mask == AE_MASK_CAUSAL, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_backward: launch failed: %s", hipGetErrorString(e));

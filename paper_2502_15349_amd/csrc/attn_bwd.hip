@@ -40,14 +40,16 @@ hipError_t launch_pair(const BwdParams& p, hipStream_t s) {
 template <int DQK, int DV>
 hipError_t launch_dims(const BwdParams& p, int norm, int causal, hipStream_t s) {
   if (norm == NORM_SOFTMAX) return causal ? launch_pair<DQK, DV, NORM_SOFTMAX, true>(p, s) : launch_pair<DQK, DV, NORM_SOFTMAX, false>(p, s);
-  return causal ? launch_pair<DQK, DV, NORM_SIGMOID, true>(p, s) : launch_pair<DQK, DV, NORM_SIGMOID, false>(p, s);
+  if (norm == NORM_SIGMOID) return causal ? launch_pair<DQK, DV, NORM_SIGMOID, true>(p, s) : launch_pair<DQK, DV, NORM_SIGMOID, false>(p, s);
+  if (norm == NORM_NONE) return causal ? launch_pair<DQK, DV, NORM_NONE, true>(p, s) : launch_pair<DQK, DV, NORM_NONE, false>(p, s);
+  return causal ? launch_pair<DQK, DV, BWD_NORM_NONE_RELU, true>(p, s) : launch_pair<DQK, DV, BWD_NORM_NONE_RELU, false>(p, s);
 }
 
 }  // namespace
 
 bool backward_supported(int dqk, int dv, int norm) {
   const bool dims = (dqk == 64 && dv == 64) || (dqk == 128 && dv == 128) || (dqk == 192 && dv == 128) || (dqk == 128 && dv == 256);
-  return dims && (norm == NORM_SOFTMAX || norm == NORM_SIGMOID);
+  return dims && (norm == NORM_SOFTMAX || norm == NORM_SIGMOID || norm == NORM_NONE || norm == BWD_NORM_NONE_RELU);
 }
 
 hipError_t launch_backward(const BwdParams& p, int dqk, int dv, int norm, int causal, hipStream_t stream) {

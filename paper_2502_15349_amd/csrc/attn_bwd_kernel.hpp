@@ -7,6 +7,7 @@
 //   P   = exp(S' - lse_i)  (softmax)   |  sigmoid(S')            S' = scale * Q K^T + bias
 //   dV  = P^T dO                          dP = dO V^T
 //   dS' = P * (dP - delta_i), delta_i = dO_i . O_i  (softmax)   |  dP * P * (1 - P)  (sigmoid)
+//   no normalization: P = S' or max(S', 0) on visible entries, dS' = dP or dP * [S' > 0]
 //   dQ  = scale * dS' K                   dK = scale * dS'^T Q
 //
 // Two kernels of one shape, no atomics, every output written once:
@@ -63,6 +64,9 @@ __device__ __forceinline__ int bswz(int row) {
   return CPR % 16 == 0 ? ((4 * (row & 3)) | ((row >> 2) & 3)) : ((4 * ((row >> 1) & 1)) | ((row >> 2) & 3));
 }
 
+// no normalization with the ReLU modification (the forward kernels carry the modification as a
+// parameter of its own; here the pair is one more value of the NORM parameter)
+constexpr int BWD_NORM_NONE_RELU = 5;
 enum : int { BWD_DQ = 0, BWD_DKV = 1 };  // the query-side kernel (dQ), the key-side kernel (dK and dV)
 
 template <int DQK_, int DV_, int NORM_, bool CAUSAL_, int OUT_>
@@ -84,7 +88,8 @@ struct BwdCfg {
   static constexpr int Y1_BYTES = TILE * RB1, Y2_BYTES = TILE * RB2, STAGE_BYTES = Y1_BYTES + Y2_BYTES;
   static constexpr int ROW_BYTES = 2 * TILE * 4;  // per stage: bias*log2(e) - lse*log2(e) and delta of the tile's rows
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * ROW_BYTES;
-  static_assert(NORM == NORM_SOFTMAX || NORM == NORM_SIGMOID, "backward: softmax and sigmoid only");
+  static_assert(NORM == NORM_SOFTMAX || NORM == NORM_SIGMOID || NORM == NORM_NONE || NORM == BWD_NORM_NONE_RELU,
+                "backward: softmax, sigmoid, and no normalization with or without ReLU");
   static_assert(LDS_BYTES <= (OCC2 ? 80 : 160) * 1024, "the workgroups of a CU must fit LDS");
   static_assert((TILE * CPR1 / 64) % WAVES == 0 && (TILE * CPR2 / 64) % WAVES == 0, "every wave copies the same number of blocks");
 };
@@ -349,10 +354,17 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
         pv = fast_exp2(x[r]);
         if constexpr (C::HAS2) w2[r] = pv;
         pv = pv * (dp[r] - dl4[r / 4][r % 4]);
-      } else {
+      } else if constexpr (C::NORM == NORM_SIGMOID) {
         pv = fast_rcp(1.f + fast_exp2(-x[r]));
         if constexpr (C::HAS2) w2[r] = pv;
         pv = dp[r] * pv * (1.f - pv);
+      } else if constexpr (C::NORM == BWD_NORM_NONE_RELU) {  // P = max(x, 0); a hidden entry has x = -inf
+        if constexpr (C::HAS2) w2[r] = fmaxf(x[r], 0.f);
+        pv = x[r] > 0.f ? dp[r] : 0.f;
+      } else {                                               // P = x on visible entries
+        const bool vis = x[r] != -INFINITY;
+        if constexpr (C::HAS2) w2[r] = vis ? x[r] : 0.f;
+        pv = vis ? dp[r] : 0.f;
       }
       w[r] = pv;
     }

@@ -194,9 +194,10 @@ def test_backward_rejects_bad_arguments_without_launching():
             assert ei.value.status == A.AE_ERR_INVALID_ARG, A.ae_attn_last_error()
     finally:
         A.ae_attn_destroy(h)
-    # sigmoid needs no workspace; normalizations and masks outside the built set are refused
+    # only softmax needs a workspace; normalizations and masks outside the built set are refused
     for patch, want in ((dict(norm="sigmoid"), None), (dict(norm="abssum"), A.AE_ERR_UNSUPPORTED),
-                        (dict(norm="none", score_mod="relu"), A.AE_ERR_UNSUPPORTED),
+                        (dict(norm="none", score_mod="relu"), None),
+                        (dict(norm="abssum", score_mod="head_decay", mask="causal", gamma=[.9] * 4), A.AE_ERR_UNSUPPORTED),
                         (dict(mask="sliding_window", window=8), A.AE_ERR_UNSUPPORTED)):
         dd = _ok_desc()
         dd.update(patch)

@@ -64,6 +64,10 @@ VARIANTS = {
     "softmax_negative_scale": dict(scale=-0.11, mask="causal"),
     "sigmoid_causal": dict(score_mod="bias", norm="sigmoid", mask="causal", bias=-math.log(300.0)),
     "sigmoid": dict(norm="sigmoid", score_mod="bias", bias=-3.0),
+    # no normalization: ReLU attention, and the bare (biased) scores as weights
+    "relu": dict(score_mod="relu", norm="none", scale=0.01),
+    "relu_causal": dict(score_mod="relu", norm="none", mask="causal", scale=0.01),
+    "none_bias_causal": dict(score_mod="bias", bias=0.02, norm="none", mask="causal", scale=0.005),
 }
 
 
@@ -82,6 +86,7 @@ def test_backward_lengths(A, Lq, Lk, mask):
     # must get zero gradient), single rows, exact tile multiples
     run_case(A, Workload(f"len{Lq}x{Lk}{mask}", 41, 1, 3, 1, Lq, Lk, 64, 64, mask=mask))
     run_case(A, Workload(f"len{Lq}x{Lk}{mask}sig", 42, 1, 2, 2, Lq, Lk, 128, 128, mask=mask, norm="sigmoid", score_mod="bias", bias=-2.0))
+    run_case(A, Workload(f"len{Lq}x{Lk}{mask}relu", 45, 1, 2, 1, Lq, Lk, 64, 64, mask=mask, norm="none", score_mod="relu", scale=0.02))
 
 
 def test_backward_bf16_forward_output(A):
