@@ -124,3 +124,65 @@ def test_backward_full_size_c2_one_group(A):
     check(got[0][b:b + 1, hs], ref[0], "C2 dQ")
     check(got[1][b:b + 1, hk:hk + 1], ref[1], "C2 dK")
     check(got[2][b:b + 1, hk:hk + 1], ref[2], "C2 dV")
+
+
+def test_backward_seeded_random_shapes(A):
+    """32 seeded draws over shapes (ragged, L_q != L_k in both directions), head grouping, head dims,
+    normalization / modification / mask, each against the backward oracle."""
+    rng = np.random.default_rng(20250305)
+    combos = [("softmax", "none"), ("softmax", "bias"), ("sigmoid", "bias"), ("none", "relu"), ("none", "none")]
+    for case in range(32):
+        dims = DIMS[int(rng.integers(len(DIMS)))]
+        norm, mod = combos[int(rng.integers(len(combos)))]
+        g = int(rng.choice([1, 2, 4]))
+        H_kv = int(rng.integers(1, 3))
+        Lq, Lk = int(rng.integers(1, 500)), int(rng.integers(1, 600))
+        mask = str(rng.choice(["none", "causal"]))
+        w = Workload(f"rand{case}", 500 + case, int(rng.integers(1, 3)), g * H_kv, H_kv, Lq, Lk, dims[0], dims[1],
+                     score_mod=mod, norm=norm, mask=mask, bias=float(rng.uniform(-2, 1)) if norm != "none" else 0.01,
+                     scale=(0.01 if norm == "none" else None))
+        run_case(A, w)
+
+
+def test_backward_hip_graph_replays(A):
+    """ae_attn_backward allocates nothing: its three launches are captured into a HIP graph and replayed four
+    times with new dO values and eager work in between; every replay must equal the eager call bit for bit."""
+    dev = torch.device("cuda:0")
+    w = Workload("graph_bwd", 46, 1, 4, 2, 300, 420, 128, 128, mask="causal")
+    Q, K, V = (x.to(dev) for x in make_inputs(w))
+    dO0 = make_grad(w).to(dev)
+    stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev)
+    O = A.run_workload(w, Q, K, V, stats=stats)
+    h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
+                         scale=w.scale_value, mask=w.mask)
+    ws = torch.empty(A.ae_attn_backward_workspace_bytes(h), dtype=torch.uint8, device=dev)
+    ws_e = torch.empty_like(ws)
+    dO = dO0.clone()
+    outs_g = [torch.zeros(x.shape, dtype=torch.float32, device=dev) for x in (Q, K, V)]
+    outs_e = [torch.zeros(x.shape, dtype=torch.float32, device=dev) for x in (Q, K, V)]
+
+    def launch(outs, wsp, stream):
+        A.ae_attn_backward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), stats.data_ptr(),
+                           outs[0].data_ptr(), outs[1].data_ptr(), outs[2].data_ptr(), wsp.data_ptr(), wsp.numel(),
+                           stream.cuda_stream)
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        launch(outs_g, ws, side)
+    torch.cuda.synchronize()
+    for replay in range(4):
+        if replay:
+            dO.copy_((dO0.float() * (1.0 + 0.3 * replay)).to(torch.bfloat16).roll(replay, dims=2))
+        for x in outs_g:
+            x.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        launch(outs_e, ws_e, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        for name, a, b in zip(("dQ", "dK", "dV"), outs_g, outs_e):
+            assert torch.equal(a, b), f"replay {replay}: {name} differs from the eager call"
+    del graph
+    A.ae_attn_destroy(h)
