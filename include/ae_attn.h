@@ -180,8 +180,8 @@ ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t *h, size_t *bytes);
  * with the weights P recomputed from Q, K and the forward pass's row statistic;
  * dK and dV of a k/v head are summed over the query heads that share it.
  * Supported: AE_NORM_SOFTMAX, AE_NORM_SIGMOID and AE_NORM_NONE with AE_MOD_NONE or
- * AE_MOD_BIAS, AE_NORM_NONE also with AE_MOD_RELU (ReLU attention); AE_MASK_NONE or
- * AE_MASK_CAUSAL, every supported pair of head dims
+ * AE_MOD_BIAS, AE_NORM_NONE also with AE_MOD_RELU (ReLU attention); every mask
+ * that ae_attn_create accepts for the pair, every supported pair of head dims
  * (AE_ERR_UNSUPPORTED otherwise; kv_splits plays no part).
  *   Q, K, V   device, bf16, laid out as the descriptor says (the forward inputs);
  *   O         device, the forward output, dtype and strides as the descriptor

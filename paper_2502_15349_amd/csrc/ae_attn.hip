@@ -359,10 +359,10 @@ ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, c
   // no normalization + ReLU is one kernel variant of its own
   const int norm = d.norm == AE_NORM_NONE && d.score_mod == AE_MOD_RELU ? ae::BWD_NORM_NONE_RELU : h->kernel->norm;
   const bool mod_ok = d.score_mod == AE_MOD_NONE || d.score_mod == AE_MOD_BIAS || norm == ae::BWD_NORM_NONE_RELU;
-  if (!ae::backward_supported(d.D_qk, d.D_v, norm) || !mod_ok || (d.mask != AE_MASK_NONE && d.mask != AE_MASK_CAUSAL))
+  if (!ae::backward_supported(d.D_qk, d.D_v, norm) || !mod_ok)
     return fail(AE_ERR_UNSUPPORTED,
                 "ae_attn_backward: built for softmax, sigmoid and no normalization with score_mod NONE, BIAS or (no "
-                "normalization) RELU, and masks NONE or CAUSAL");
+                "normalization) RELU");
   const bool softmax = norm == ae::NORM_SOFTMAX;
   if (!Q || !K || !V || !dO || !dQ || !dK || !dV || (softmax && (!O || !stats || !workspace)))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: null device pointer");
@@ -412,7 +412,8 @@ ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, c
   p.c2 = d.scale * unit;
   p.b2 = (d.score_mod == AE_MOD_BIAS ? d.bias : 0.f) * unit;
   p.scale = d.scale;
-  hipError_t e = ae::launch_backward(p, d.D_qk, d.D_v, norm, d.mask == AE_MASK_CAUSAL, static_cast<hipStream_t>(stream));
+  p.window = d.mask == AE_MASK_SLIDING_WINDOW ? std::min(d.window, d.L_q + d.L_k) : d.L_q + d.L_k;
+  hipError_t e = ae::launch_backward(p, d.D_qk, d.D_v, norm, d.mask != AE_MASK_NONE, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_backward: launch failed: %s", hipGetErrorString(e));
   return AE_OK;
 }

@@ -51,6 +51,9 @@ struct BwdParams {
   float c2;     // scale * log2(e)
   float b2;     // bias * log2(e)
   float scale;
+  // causal kernels: key j is also hidden from query i if j <= i + (L_k - L_q) - window (sliding
+  // window); L_q + L_k for the plain causal mask, which hides nothing more
+  int window;
 };
 
 // Chunk swizzle of the backward tiles.  A tile row is read both ways -- 128-bit row
@@ -160,10 +163,17 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       const int i_first = own0 - off;  // first query that sees key own0
       t_first = i_first > 0 ? i_first / C::TILE : 0;
       if (t_first > t_end) t_first = t_end;
+      const int i_last = own0 + C::OWN - 1 - off + p.window - 1;  // last query whose window holds a key here
+      const int e = i_last < 0 ? 0 : i_last / C::TILE + 1;
+      if (e < t_end) t_end = e;
+      if (t_end < t_first) t_end = t_first;
     } else {
       const int j_last = own0 + C::OWN - 1 + off;  // last key any row here may see
       const int e = j_last < 0 ? 0 : j_last / C::TILE + 1;
       if (e < t_end) t_end = e;
+      const int j_first = own0 + off - p.window + 1;  // first key inside the window of row own0
+      t_first = j_first > 0 ? j_first / C::TILE : 0;
+      if (t_first > t_end) t_first = t_end;
     }
   }
   const int nt = t_end - t_first;
@@ -274,12 +284,13 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
     // anything visible to this wave's rows?  everything?
     bool any = o0 < L_oth, full = o0 + 31 < L_oth;
     if constexpr (C::CAUSAL) {
-      if constexpr (C::KV_SIDE) {  // own = keys j, other = queries i: visible iff j <= i + off
-        any = any && ow0 <= o0 + 31 + off;
-        full = full && ow0 + 31 <= o0 + off;
+      const int wd = p.window;
+      if constexpr (C::KV_SIDE) {  // own = keys j, other = queries i: visible iff i + off - window < j <= i + off
+        any = any && ow0 <= o0 + 31 + off && o0 + off - wd < ow0 + 31;
+        full = full && ow0 + 31 <= o0 + off && o0 + 31 + off - wd < ow0;
       } else {                     // own = queries i, other = keys j
-        any = any && o0 <= ow0 + 31 + off;
-        full = full && o0 + 31 <= ow0 + off;
+        any = any && o0 <= ow0 + 31 + off && ow0 + off - wd < o0 + 31;
+        full = full && o0 + 31 <= ow0 + off && ow0 + 31 + off - wd < o0;
       }
     }
     if (!any) return;
@@ -339,7 +350,8 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       for (int r = 0; r < 16; ++r) {
         const int oth = o0 + key_offset(r) + 4 * half;
         bool vis = oth < L_oth;
-        if constexpr (C::CAUSAL) vis = vis && (C::KV_SIDE ? own <= oth + off : oth <= own + off);
+        if constexpr (C::CAUSAL)
+          vis = vis && (C::KV_SIDE ? own <= oth + off && oth + off - p.window < own : oth <= own + off && own + off - p.window < oth);
         x[r] = vis ? x[r] : -INFINITY;
       }
       sched_fence();

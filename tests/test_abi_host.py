@@ -198,12 +198,14 @@ def test_backward_rejects_bad_arguments_without_launching():
     for patch, want in ((dict(norm="sigmoid"), None), (dict(norm="abssum"), A.AE_ERR_UNSUPPORTED),
                         (dict(norm="none", score_mod="relu"), None),
                         (dict(norm="abssum", score_mod="head_decay", mask="causal", gamma=[.9] * 4), A.AE_ERR_UNSUPPORTED),
-                        (dict(mask="sliding_window", window=8), A.AE_ERR_UNSUPPORTED)):
+                        (dict(mask="sliding_window", window=8), "ws")):
         dd = _ok_desc()
         dd.update(patch)
         h = A.ae_attn_create(**dd)
         try:
-            if want is None:
+            if want == "ws":       # supported, softmax: the workspace holds delta
+                assert A.ae_attn_backward_workspace_bytes(h) == 4 * dd["B"] * dd["H_q"] * dd["L_q"]
+            elif want is None:
                 assert A.ae_attn_backward_workspace_bytes(h) == 0
             else:
                 with pytest.raises(A.AeAttnError) as ei:

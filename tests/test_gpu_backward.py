@@ -29,7 +29,7 @@ def hip_backward(A, w, Q, K, V, dO, out_dtype=None):
     stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev) if w.norm == "softmax" else None
     O = A.run_workload(w, Qd, Kd, Vd, stats=stats, out_dtype=out_dtype)
     dQ, dK, dV = A.attention_backward(Qd, Kd, Vd, O, dOd, stats, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
-                                      norm=w.norm, mask=w.mask)
+                                      norm=w.norm, mask=w.mask, window=w.window)
     torch.cuda.synchronize()
     return [x.cpu().double().numpy() for x in (dQ, dK, dV)]
 
@@ -89,6 +89,16 @@ def test_backward_lengths(A, Lq, Lk, mask):
     run_case(A, Workload(f"len{Lq}x{Lk}{mask}relu", 45, 1, 2, 1, Lq, Lk, 64, 64, mask=mask, norm="none", score_mod="relu", scale=0.02))
 
 
+@pytest.mark.parametrize("window", [1, 7, 64, 100, 333, 5000])
+@pytest.mark.parametrize("Lq,Lk", [(300, 333), (333, 300), (700, 700)])
+def test_backward_sliding_window(A, window, Lq, Lk):
+    # windows shorter than a sub-tile, spanning a few tiles, and wider than the keys (= the causal mask); the walk
+    # of either kernel starts and ends at the tiles the window allows
+    run_case(A, Workload(f"win{window}_{Lq}x{Lk}", 47, 1, 4, 2, Lq, Lk, 128, 128, mask="sliding_window", window=window))
+    run_case(A, Workload(f"win{window}_{Lq}x{Lk}sig", 48, 2, 2, 2, Lq, Lk, 64, 64, mask="sliding_window", window=window,
+                         norm="sigmoid", score_mod="bias", bias=-1.0))
+
+
 def test_backward_bf16_forward_output(A):
     # delta is formed from the forward output as stored: also when that is bf16
     run_case(A, Workload("bf16_O", 43, 1, 4, 2, 260, 260, 128, 128, mask="causal"), out_dtype=torch.bfloat16)
@@ -137,9 +147,11 @@ def test_backward_seeded_random_shapes(A):
         g = int(rng.choice([1, 2, 4]))
         H_kv = int(rng.integers(1, 3))
         Lq, Lk = int(rng.integers(1, 500)), int(rng.integers(1, 600))
-        mask = str(rng.choice(["none", "causal"]))
+        mask = str(rng.choice(["none", "causal", "sliding_window"]))
+        if mask == "sliding_window" and mod == "relu":
+            mask = "causal"
         w = Workload(f"rand{case}", 500 + case, int(rng.integers(1, 3)), g * H_kv, H_kv, Lq, Lk, dims[0], dims[1],
-                     score_mod=mod, norm=norm, mask=mask, bias=float(rng.uniform(-2, 1)) if norm != "none" else 0.01,
+                     score_mod=mod, norm=norm, mask=mask, window=int(rng.integers(1, 400)) if mask == "sliding_window" else 0, bias=float(rng.uniform(-2, 1)) if norm != "none" else 0.01,
                      scale=(0.01 if norm == "none" else None))
         run_case(A, w)
 
