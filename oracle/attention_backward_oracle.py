@@ -16,6 +16,9 @@ sum(O * dO)), by the chain rule on the fully materialised L_q x L_k matrices:
     dS' = P * (dP - rowsum(P * dP))    softmax
         = dP * P * (1 - P)             sigmoid
         = dP on visible entries        no normalization
+        = dP / n - g * rowsum(dP * S') / n^2     abs-sum family: P = S' / n, n = max(r, 1),
+          r = rowsum |S'| with g = sign(S'), or r = |rowsum S'| with g = sign(rowsum S');
+          the second term only where r > 1 (below the clamp n is the constant 1)
     dS  = dS' * d modification / dS    (1 for scale/bias, the decay factor,
                                         the step function for ReLU), times scale
     dQ  = dS K                         dK = dS^T Q
@@ -23,8 +26,9 @@ sum(O * dO)), by the chain rule on the fully materialised L_q x L_k matrices:
 Masked entries take no part (their P is a constant 0), a row with no visible
 key has zero gradient, and with grouped-query heads dK and dV of a k/v head are
 the sums over the query heads that share it.  No tiling, no recomputation from
-row statistics, no reordering.  The abs-sum normalizers (piecewise, with a
-clamp) are not covered.
+row statistics, no reordering.  The abs-sum normalizers are differentiated
+piecewise (quotient rule above the clamp, identity below it; at the kinks r = 1
+and S' = 0, a set of measure zero, the one-sided value of the branch taken).
 
 Pinned by tests/test_oracle_backward_pins.py: central finite differences of
 the (separately pinned) forward oracle, a library autograd for the softmax
@@ -73,8 +77,14 @@ def attention_backward_head(q, k, v, do, *, scale, score_mod="none", bias=0.0, g
         p = np.where(vis, 1.0 / (1.0 + np.exp(-s)), 0.0)
     elif norm == "none":
         p = np.where(vis, s, 0.0)
+    elif norm in ("abssum", "abs_of_sum"):
+        sv = np.where(vis, s, 0.0)
+        tot = sv.sum(axis=1, keepdims=True)
+        r = np.abs(sv).sum(axis=1, keepdims=True) if norm == "abssum" else np.abs(tot)
+        den = np.maximum(r, 1.0)
+        p = sv / den
     else:
-        raise ValueError(f"the backward oracle does not cover normalization {norm!r}")
+        raise ValueError(f"unknown norm {norm!r}")
 
     # aggregation O = P V
     dv = p.T @ do
@@ -84,6 +94,10 @@ def attention_backward_head(q, k, v, do, *, scale, score_mod="none", bias=0.0, g
         ds = p * (dp - (p * dp).sum(axis=1, keepdims=True))
     elif norm == "sigmoid":
         ds = dp * p * (1.0 - p)
+    elif norm in ("abssum", "abs_of_sum"):
+        # quotient rule for S' / n; d n / d S'_ij = g_ij where r > 1, 0 below the clamp
+        grad_r = np.sign(sv) if norm == "abssum" else np.sign(tot) * np.ones_like(sv)
+        ds = dp / den - np.where(r > 1.0, grad_r * (dp * sv).sum(axis=1, keepdims=True) / den ** 2, 0.0)
     else:
         ds = np.where(vis, dp, 0.0)
     # modification and scale

@@ -33,7 +33,8 @@ def finite_difference(fn, x, dO, eps=1e-6):
 
 
 CASES = [("softmax", "none"), ("softmax", "bias"), ("sigmoid", "bias"), ("softmax", "head_decay"),
-         ("none", "relu"), ("none", "none"), ("none", "head_decay"), ("sigmoid", "none")]
+         ("none", "relu"), ("none", "none"), ("none", "head_decay"), ("sigmoid", "none"),
+         ("abssum", "head_decay"), ("abs_of_sum", "head_decay"), ("abssum", "none"), ("abs_of_sum", "bias")]
 
 
 @pytest.mark.parametrize("norm,score_mod", CASES)
@@ -141,6 +142,35 @@ def test_sigmoid_and_relu_closed_forms():
         live = 1.0 if sign * (q @ k.T).item() > 0 else 0.0
         np.testing.assert_allclose(dq, live * 0.7 * 2.0 * scale * k, atol=1e-15)
         np.testing.assert_allclose(dv, [[live * 0.7 * scale * sign * (q @ k.T).item()]], atol=1e-15)
+
+
+@pytest.mark.parametrize("norm", ["abssum", "abs_of_sum"])
+def test_abs_sum_normalizers_on_both_sides_of_the_clamp(norm):
+    # rows below the clamp (r < 1) behave as no normalization; rows above it follow the quotient rule -- checked
+    # against finite differences with scores scaled to land on either side, and in closed form for one key:
+    # P = s / max(|s|, 1), so above the clamp O = sign(s) v is flat in s (zero gradient to q and k)
+    L, D = 6, 3
+    q, k, v, do = rnd(L, D), rnd(L, D), rnd(L, 2), rnd(L, 2)
+    Q, K, V, dO = q[None, None], k[None, None], v[None, None], do[None, None]
+    for scale in (0.02, 0.5, 3.0):
+        kw = dict(scale=scale, norm=norm, mask="causal", score_mod="head_decay", gamma=[0.9])
+        from oracle import row_stats_head
+        r = np.abs(row_stats_head(q, k, scale=scale, norm=norm, mask="causal", score_mod="head_decay", gamma_h=0.9))
+        assert np.abs(r - 1.0).min() > 1e-3          # no row sits on the kink
+        dQ, dK, dV = attention_backward(Q, K, V, dO, **kw)
+        fwd = lambda: attention(Q, K, V, **kw)  # noqa: E731
+        np.testing.assert_allclose(dQ, finite_difference(fwd, Q, dO), atol=5e-7)
+        np.testing.assert_allclose(dK, finite_difference(fwd, K, dO), atol=5e-7)
+        np.testing.assert_allclose(dV, finite_difference(fwd, V, dO), atol=5e-7)
+    assert (r > 1).any()                             # the largest scale is above the clamp somewhere
+    q1, k1, v1, d1 = np.array([[2.0, 0.0]]), np.array([[1.5, 0.0]]), np.array([[3.0]]), np.array([[1.0]])
+    dq, dk, dv = attention_backward_head(q1, k1, v1, d1, scale=1.0, norm=norm)   # s = 3 > 1: P = 1
+    np.testing.assert_allclose(dq, 0.0, atol=1e-15)
+    np.testing.assert_allclose(dk, 0.0, atol=1e-15)
+    np.testing.assert_allclose(dv, [[1.0]], atol=1e-15)
+    dq, dk, dv = attention_backward_head(q1, k1, v1, d1, scale=0.1, norm=norm)   # s = 0.3 < 1: P = s
+    np.testing.assert_allclose(dq, 0.1 * 3.0 * k1, atol=1e-15)
+    np.testing.assert_allclose(dv, [[0.3]], atol=1e-15)
 
 
 def test_gqa_sums_over_the_query_heads_of_a_group():
