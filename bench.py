@@ -269,11 +269,11 @@ def main():
         # pair (S, dP, dV, dK, dQ) = 2 * (3 D_qk + 2 D_v) flop; the key-side and the query-side kernel each recompute
         # S and dP, so the MFMAs they issue amount to 2 * (4 D_qk + 3 D_v) flop per pair.
         from oracle import attention_backward
-        from paper_2502_15349_amd.workloads import C2, C3, C5, Workload, make_grad, table2_workloads
+        from paper_2502_15349_amd.workloads import C2, C3, C4, C5, Workload, make_grad, table2_workloads
         rows = []
         # the benchmark configurations with a backward pass, one unmasked shape, and the paper's Table 2 shapes at
         # batch 8 x 8k (softmax at three head-dim pairs, sigmoid, ReLU)
-        shapes = [C2, C3, C5, Workload("t2_softmax_b8_h32_s8192_noncausal", 150, 8, 32, 32, 8192, 8192, 128, 128)]
+        shapes = [C2, C3, C4, C5, Workload("t2_softmax_b8_h32_s8192_noncausal", 150, 8, 32, 32, 8192, 8192, 128, 128)]
         shapes += [w for w in table2_workloads() if w.B == 8 and w.L_q == 8192 and w.L_q == w.L_k]
         for w in shapes:
             if a.only not in w.name:
@@ -281,10 +281,12 @@ def main():
             Qc, Kc, Vc = make_inputs(w)
             dOc = make_grad(w)
             Q, K, V, dO = Qc.to(dev), Kc.to(dev), Vc.to(dev), dOc.to(dev)
-            stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev) if w.norm == "softmax" else None
+            has_stat = w.norm in ("softmax", "abssum", "abs_of_sum")
+            stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev) if has_stat else None
             O = A.run_workload(w, Q, K, V, stats=stats)
             h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
-                                 scale=w.scale_value, score_mod=w.score_mod, bias=w.bias, norm=w.norm, mask=w.mask)
+                                 scale=w.scale_value, score_mod=w.score_mod, bias=w.bias, gamma=w.gamma(), norm=w.norm,
+                                 mask=w.mask)
             dQ = torch.empty(Q.shape, dtype=torch.float32, device=dev)
             dK = torch.empty(K.shape, dtype=torch.float32, device=dev)
             dV = torch.empty(V.shape, dtype=torch.float32, device=dev)
@@ -313,7 +315,8 @@ def main():
                 b, hk, g = w.B - 1, w.H_kv // 2, w.H_q // w.H_kv
                 hs = slice(hk * g, hk * g + g)
                 ref = attention_backward(Qc[b:b + 1, hs], Kc[b:b + 1, hk:hk + 1], Vc[b:b + 1, hk:hk + 1], dOc[b:b + 1, hs],
-                                         scale=w.scale_value, score_mod=w.score_mod, bias=w.bias, norm=w.norm, mask=w.mask)
+                                         scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
+                                         gamma=None if w.gamma() is None else w.gamma()[hs], norm=w.norm, mask=w.mask)
                 got = (dQ[b:b + 1, hs], dK[b:b + 1, hk:hk + 1], dV[b:b + 1, hk:hk + 1])
                 par = {}
                 for name, x, r in zip(("dQ", "dK", "dV"), got, ref):

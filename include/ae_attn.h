@@ -165,8 +165,8 @@ ae_status_t ae_attn_forward_split(const ae_attn_t *h, const void *Q,
                                   size_t workspace_bytes, void *stream);
 
 /* Bytes of device workspace that ae_attn_backward needs for this handle: one
- * fp32 value per query row (B * H_q * L_q elements) for AE_NORM_SOFTMAX, 0 for
- * the others.                                                                  */
+ * fp32 value per query row (B * H_q * L_q elements) for the normalizations that
+ * keep a row statistic (SOFTMAX, ABSSUM, ABS_OF_SUM), 0 for the others.                                                                  */
 ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t *h, size_t *bytes);
 
 /* Backward pass of the operator (the backward graph of Section 4.1's online
@@ -175,20 +175,24 @@ ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t *h, size_t *bytes);
  * respect to Q, K and V,
  *   dV = P^T dO,  dS' = P * (dO V^T - delta)  (softmax; delta_i = dO_i . O_i)
  *                     = dO V^T * P * (1 - P)  (sigmoid)
- *                     = dO V^T [* step(S')]   (no normalization [with ReLU]),
+ *                     = dO V^T [* step(S')]   (no normalization [with ReLU])
+ *                     = (dO V^T - g * [r > 1] * delta) / max(r, 1)
+ *                       (abs-sum family; r the row statistic, g = sign(S') or
+ *                       the sign of the row sum),
  *   dQ = scale * dS' K,  dK = scale * dS'^T Q,
  * with the weights P recomputed from Q, K and the forward pass's row statistic;
  * dK and dV of a k/v head are summed over the query heads that share it.
- * Supported: AE_NORM_SOFTMAX, AE_NORM_SIGMOID and AE_NORM_NONE with AE_MOD_NONE or
- * AE_MOD_BIAS, AE_NORM_NONE also with AE_MOD_RELU (ReLU attention); every mask
+ * Supported: every normalization with AE_MOD_NONE or AE_MOD_BIAS, AE_NORM_NONE
+ * also with AE_MOD_RELU (ReLU attention), AE_NORM_ABSSUM and AE_NORM_ABS_OF_SUM
+ * also with AE_MOD_HEAD_DECAY (retention); every mask
  * that ae_attn_create accepts for the pair, every supported pair of head dims
  * (AE_ERR_UNSUPPORTED otherwise; kv_splits plays no part).
  *   Q, K, V   device, bf16, laid out as the descriptor says (the forward inputs);
  *   O         device, the forward output, dtype and strides as the descriptor
- *             says (read for softmax only; may be NULL otherwise);
+ *             says (read where a row statistic exists; may be NULL otherwise);
  *   dO        device, bf16, contiguous [B, H_q, L_q, D_v];
  *   stats     device, fp32 [B, H_q, L_q] as written by ae_attn_forward_stats
- *             (softmax only; may be NULL otherwise);
+ *             (where one exists; may be NULL otherwise);
  *   dQ, dK, dV  device, fp32, contiguous, shaped like Q, K, V; every element is
  *             written (rows that see no key get zeros);
  *   workspace device, owned by the caller, 16-byte aligned, at least

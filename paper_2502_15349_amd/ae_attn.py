@@ -223,11 +223,11 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
     return out
 
 
-def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0.0, norm="softmax", mask="none",
-                       window=0, stream=None, workspace=None):
+def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
+                       mask="none", window=0, stream=None, workspace=None):
     """Runs the HIP backward pass on device tensors: Q, K, V bf16 [B, H, L, D] (last dim contiguous), O the
     forward output (fp32 or bf16), dO bf16 contiguous, stats the fp32 row statistic of the forward pass (O and
-    stats may be None unless norm is softmax); window: keys per query for mask="sliding_window".  Returns (dQ, dK, dV)
+    stats may be None for sigmoid and no normalization); window: keys per query for mask="sliding_window".  Returns (dQ, dK, dV)
     as contiguous fp32 tensors."""
     import torch
 
@@ -241,7 +241,7 @@ def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0
         raise ValueError("stats must be a contiguous fp32 tensor [B, H_q, L_q]")
     o_dtype, o_stride = ("f32", (0, 0, 0)) if O is None else ("bf16" if O.dtype == torch.bfloat16 else "f32", O.stride()[:3])
     h = ae_attn_create(B=B, H_q=H_q, H_kv=H_kv, L_q=L_q, L_k=L_k, D_qk=D_qk, D_v=D_v, scale=scale,
-                       score_mod=score_mod, bias=bias, norm=norm, mask=mask, q_stride=Q.stride()[:3],
+                       score_mod=score_mod, bias=bias, gamma=gamma, norm=norm, mask=mask, q_stride=Q.stride()[:3],
                        k_stride=K.stride()[:3], v_stride=V.stride()[:3], o_stride=o_stride, out_dtype=o_dtype,
                        window=window)
     try:

@@ -347,7 +347,8 @@ ae_status_t ae_attn_forward_split(const ae_attn_t* h, const void* Q, const void*
 
 ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t* h, size_t* bytes) {
   if (!h || !bytes) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward_workspace_bytes: null argument");
-  *bytes = h->desc.norm == AE_NORM_SOFTMAX ? (size_t)h->desc.B * h->desc.H_q * h->desc.L_q * sizeof(float) : 0;
+  const bool rows = h->desc.norm == AE_NORM_SOFTMAX || h->desc.norm == AE_NORM_ABSSUM || h->desc.norm == AE_NORM_ABS_OF_SUM;
+  *bytes = rows ? (size_t)h->desc.B * h->desc.H_q * h->desc.L_q * sizeof(float) : 0;
   return AE_OK;
 }
 
@@ -358,12 +359,14 @@ ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, c
   const ae_attn_desc_t& d = h->desc;
   // no normalization + ReLU is one kernel variant of its own
   const int norm = d.norm == AE_NORM_NONE && d.score_mod == AE_MOD_RELU ? ae::BWD_NORM_NONE_RELU : h->kernel->norm;
-  const bool mod_ok = d.score_mod == AE_MOD_NONE || d.score_mod == AE_MOD_BIAS || norm == ae::BWD_NORM_NONE_RELU;
+  const bool abs_family = norm == ae::NORM_ABSSUM || norm == ae::NORM_ABS_OF_SUM;
+  const bool mod_ok = d.score_mod == AE_MOD_NONE || d.score_mod == AE_MOD_BIAS || norm == ae::BWD_NORM_NONE_RELU ||
+                      (abs_family && d.score_mod == AE_MOD_HEAD_DECAY);
   if (!ae::backward_supported(d.D_qk, d.D_v, norm) || !mod_ok)
     return fail(AE_ERR_UNSUPPORTED,
-                "ae_attn_backward: built for softmax, sigmoid and no normalization with score_mod NONE, BIAS or (no "
-                "normalization) RELU");
-  const bool softmax = norm == ae::NORM_SOFTMAX;
+                "ae_attn_backward: built for every normalization with score_mod NONE or BIAS, no normalization also with "
+                "RELU, the abs-sum normalizations also with HEAD_DECAY");
+  const bool softmax = norm == ae::NORM_SOFTMAX || abs_family;  // the variants that read O, the row statistic and a workspace
   if (!Q || !K || !V || !dO || !dQ || !dK || !dV || (softmax && (!O || !stats || !workspace)))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: null device pointer");
   if ((((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)dO | (uintptr_t)dQ | (uintptr_t)dK | (uintptr_t)dV) & 15) ||
@@ -413,7 +416,7 @@ ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, c
   p.b2 = (d.score_mod == AE_MOD_BIAS ? d.bias : 0.f) * unit;
   p.scale = d.scale;
   p.window = d.mask == AE_MASK_SLIDING_WINDOW ? std::min(d.window, d.L_q + d.L_k) : d.L_q + d.L_k;
-  hipError_t e = ae::launch_backward(p, d.D_qk, d.D_v, norm, d.mask != AE_MASK_NONE, static_cast<hipStream_t>(stream));
+  hipError_t e = ae::launch_backward(p, h->decay, d.D_qk, d.D_v, norm, d.mask != AE_MASK_NONE, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_backward: launch failed: %s", hipGetErrorString(e));
   return AE_OK;
 }

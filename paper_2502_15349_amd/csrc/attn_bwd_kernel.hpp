@@ -8,6 +8,9 @@
 //   dV  = P^T dO                          dP = dO V^T
 //   dS' = P * (dP - delta_i), delta_i = dO_i . O_i  (softmax)   |  dP * P * (1 - P)  (sigmoid)
 //   no normalization: P = S' or max(S', 0) on visible entries, dS' = dP or dP * [S' > 0]
+//   abs-sum family (retention): S' = scale * Q K^T * decay, P = S' / n_i, n_i = max(r_i, 1), r_i = sum_j |S'| or
+//     |sum_j S'| (the forward row statistic); dS' = (dP - g * [r_i > 1] * delta_i) / n_i with g = sign(S') or
+//     sign(sum_j S'); the gradient of the raw score is dS' * decay
 //   dQ  = scale * dS' K                   dK = scale * dS'^T Q
 //
 // Two kernels of one shape, no atomics, every output written once:
@@ -40,8 +43,8 @@ struct BwdParams {
   const __bf16* V;
   const __bf16* dO;    // [B, H_q, L_q, D_v] contiguous
   const void* O;       // as the forward pass wrote it (softmax only): fp32, or bf16 if o_bf16
-  const float* lse;    // [B, H_q, L_q] row statistic of the forward pass (softmax only)
-  float* delta;        // [B, H_q, L_q] workspace (softmax only)
+  const float* lse;    // [B, H_q, L_q] row statistic of the forward pass (softmax; abs-sum family: r or the signed sum)
+  float* delta;        // [B, H_q, L_q] workspace (softmax; abs-sum family: delta where r > 1, signed for |sum|, else 0)
   float* dQ;           // [B, H_q, L_q, D_qk] contiguous fp32
   float* dK;           // [B, H_kv, L_k, D_qk]
   float* dV;           // [B, H_kv, L_k, D_v]
@@ -91,8 +94,11 @@ struct BwdCfg {
   static constexpr int Y1_BYTES = TILE * RB1, Y2_BYTES = TILE * RB2, STAGE_BYTES = Y1_BYTES + Y2_BYTES;
   static constexpr int ROW_BYTES = 2 * TILE * 4;  // per stage: bias*log2(e) - lse*log2(e) and delta of the tile's rows
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * ROW_BYTES;
-  static_assert(NORM == NORM_SOFTMAX || NORM == NORM_SIGMOID || NORM == NORM_NONE || NORM == BWD_NORM_NONE_RELU,
-                "backward: softmax, sigmoid, and no normalization with or without ReLU");
+  static_assert(NORM == NORM_SOFTMAX || NORM == NORM_SIGMOID || NORM == NORM_NONE || NORM == BWD_NORM_NONE_RELU ||
+                    NORM == NORM_ABSSUM || NORM == NORM_ABS_OF_SUM,
+                "backward: softmax, sigmoid, the abs-sum family, and no normalization with or without ReLU");
+  static constexpr bool ABS = NORM == NORM_ABSSUM || NORM == NORM_ABS_OF_SUM;
+  static constexpr bool ROWS = NORM == NORM_SOFTMAX || ABS;  // per-row quantities from the forward statistic and delta
   static_assert(LDS_BYTES <= (OCC2 ? 80 : 160) * 1024, "the workgroups of a CU must fit LDS");
   static_assert((TILE * CPR1 / 64) % WAVES == 0 && (TILE * CPR2 / 64) % WAVES == 0, "every wave copies the same number of blocks");
 };
@@ -112,7 +118,7 @@ __device__ __forceinline__ bf16x8 pack8(const float (&x)[16], int t) {
 }
 
 template <class C>
-__global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(const BwdParams p) {
+__global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(const BwdParams p, const DecayTable dt) {
   __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const uint32_t rows0 = lds0 + 2 * C::STAGE_BYTES;
@@ -144,15 +150,19 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
 #pragma unroll
   for (int t = 0; t < C::T2; ++t) xb2[t] = *reinterpret_cast<const bf16x8*>(x2 + (2 * t + half) * 8);
   // query side: the row quantities belong to the lane's own row
-  float nl_own = -INFINITY, dl_own = 0.f;
-  if constexpr (!C::KV_SIDE && C::NORM == NORM_SOFTMAX) {
+  // (first: (bias - lse) * log2(e) for softmax, 1 / max(|statistic|, 1) for the abs-sum family; second: delta)
+  float nl_own = C::ABS ? 1.f : -INFINITY, dl_own = 0.f;
+  if constexpr (!C::KV_SIDE && C::ROWS) {
     if (own < p.L_q) {
       const int64_t r = ((int64_t)b * p.H_q + ho) * p.L_q + own;
-      const float lse = p.lse[r];
-      nl_own = lse == -INFINITY ? -INFINITY : p.b2 - lse * 1.4426950408889634f;
+      const float st = p.lse[r];
+      if constexpr (C::ABS) nl_own = fast_rcp(fmaxf(fabsf(st), 1.f));
+      else nl_own = st == -INFINITY ? -INFINITY : p.b2 - st * 1.4426950408889634f;
       dl_own = p.delta[r];
     }
   }
+  float lg = 0.f;  // log2 of the decay rate of the q head at hand (0: no decay); key side: set per tile
+  if constexpr (!C::KV_SIDE && C::ABS) lg = dt.log2_gamma[ho];
 
   // ---- the walk over the other side --------------------------------------------------
   // key side: the query tiles from the first one that sees key own0, for each q head of
@@ -212,22 +222,22 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
   // after the work on the tile before it: nothing waits for memory in between.
   auto load_rowq = [&](int n) -> float {
     float v = 0.f;
-    if constexpr (C::KV_SIDE && C::NORM == NORM_SOFTMAX) {
+    if constexpr (C::KV_SIDE && C::ROWS) {
       if (wave < 2 && lane < C::TILE) {
         const int hq = hk * p.g + n / nt;
         const int i = (t_first + n % nt) * C::TILE + lane;
         const int64_t r = ((int64_t)b * p.H_q + hq) * p.L_q + i;
         const float* src = wave == 0 ? p.lse : p.delta;
-        v = wave == 0 ? -INFINITY : 0.f;
+        v = wave == 0 ? (C::ABS ? 0.f : -INFINITY) : 0.f;
         if (i < p.L_q) v = src[r];
       }
     }
     return v;
   };
   auto store_rowq = [&](float v, int stage) {
-    if constexpr (C::KV_SIDE && C::NORM == NORM_SOFTMAX) {
+    if constexpr (C::KV_SIDE && C::ROWS) {
       if (wave < 2 && lane < C::TILE) {
-        if (wave == 0) v = v == -INFINITY ? -INFINITY : p.b2 - v * 1.4426950408889634f;
+        if (wave == 0) v = C::ABS ? fast_rcp(fmaxf(fabsf(v), 1.f)) : v == -INFINITY ? -INFINITY : p.b2 - v * 1.4426950408889634f;
         *reinterpret_cast<__attribute__((address_space(3))) float*>(
             (lds_char*)(uintptr_t)(rows0 + stage * C::ROW_BYTES + wave * C::TILE * 4 + lane * 4)) = v;
       }
@@ -298,7 +308,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
     // key side: the row quantities of the 16 rows this lane sees, requested ahead of the MFMAs that
     // hide their latency (register r is other-side row o0 + 8*(r/4) + 4*half + (r%4))
     constexpr uint32_t kRq = 2 * C::STAGE_BYTES + STAGE * C::ROW_BYTES + SUB * 32 * 4;
-    constexpr bool ROWQ = C::NORM == NORM_SOFTMAX && C::KV_SIDE;
+    constexpr bool ROWQ = C::ROWS && C::KV_SIDE;
     f32x4 nl4[4], dl4[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -344,6 +354,8 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
     float x[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) x[r] = __builtin_fmaf(s[r], p.c2, C::NORM == NORM_SOFTMAX ? nl4[r / 4][r % 4] : p.b2);
+    // abs-sum family: distance to the diagonal of register 0's entry, for the decay factor
+    const float dist0 = (float)(C::KV_SIDE ? o0 + off - own + 4 * half : own + off - o0 - 4 * half);
     if (!full) {  // a hidden entry gets the exponent that makes its weight exactly 0
       sched_fence();  // (keeps this a branch: most sub-tiles skip it)
 #pragma unroll
@@ -370,6 +382,18 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
         pv = fast_rcp(1.f + fast_exp2(-x[r]));
         if constexpr (C::HAS2) w2[r] = pv;
         pv = dp[r] * pv * (1.f - pv);
+      } else if constexpr (C::ABS) {  // a hidden entry has x = -inf: weight and gradient 0
+        const bool vis = x[r] != -INFINITY;
+        const float dist = dist0 + (C::KV_SIDE ? 1.f : -1.f) * (float)key_offset(r);
+        const float dec = fast_exp2(lg * fmaxf(dist, 0.f));  // (visible entries have dist >= 0; <= 1 keeps 0 * dec finite)
+        const float sp = (vis ? x[r] : 0.f) * dec;          // S'
+        const float inv = nl4[r / 4][r % 4], dl = dl4[r / 4][r % 4];
+        if constexpr (C::HAS2) w2[r] = sp * inv;
+        // g * delta: delta with its sign flipped where S' < 0 (abs-sum), or delta already signed by the row sum
+        const float corr = C::NORM == NORM_ABSSUM
+                               ? __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, dl) ^ (__builtin_bit_cast(uint32_t, sp) & 0x80000000u))
+                               : dl;
+        pv = vis ? (dp[r] - corr) * inv * dec : 0.f;
       } else if constexpr (C::NORM == BWD_NORM_NONE_RELU) {  // P = max(x, 0); a hidden entry has x = -inf
         if constexpr (C::HAS2) w2[r] = fmaxf(x[r], 0.f);
         pv = x[r] > 0.f ? dp[r] : 0.f;
@@ -411,6 +435,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       rowq_next = load_rowq(n + 1);
     }
     const int r0 = (t_first + (C::KV_SIDE ? n % nt : n)) * C::TILE;
+    if constexpr (C::KV_SIDE && C::ABS) lg = dt.log2_gamma[hk * p.g + n / nt];
     subtile(stagec, std::integral_constant<int, 0>{}, r0);
     subtile(stagec, std::integral_constant<int, 1>{}, r0 + 32);
     if (n + 1 < total) store_rowq(rowq_next, STAGE ^ 1);

@@ -5,8 +5,9 @@
 #include "attn_bwd_kernel.hpp"
 
 namespace ae {
-// True if kernels exist for this combination (norm: NORM_SOFTMAX, NORM_SIGMOID, NORM_NONE or BWD_NORM_NONE_RELU).
+// True if kernels exist for this combination (norm: a NORM_* value or BWD_NORM_NONE_RELU).
 bool backward_supported(int dqk, int dv, int norm);
 // Launches delta (softmax), the key-side kernel (dK, dV) and the query-side kernel (dQ) on the stream.
-hipError_t launch_backward(const BwdParams& p, int dqk, int dv, int norm, int causal, hipStream_t stream);
+// dt: log2 of the per-q-head decay rates (abs-sum family with head decay; zeros otherwise).
+hipError_t launch_backward(const BwdParams& p, const DecayTable& dt, int dqk, int dv, int norm, int causal, hipStream_t stream);
 }  // namespace ae

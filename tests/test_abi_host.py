@@ -195,9 +195,10 @@ def test_backward_rejects_bad_arguments_without_launching():
     finally:
         A.ae_attn_destroy(h)
     # only softmax needs a workspace; normalizations and masks outside the built set are refused
-    for patch, want in ((dict(norm="sigmoid"), None), (dict(norm="abssum"), A.AE_ERR_UNSUPPORTED),
+    for patch, want in ((dict(norm="sigmoid"), None), (dict(norm="abssum"), "ws"),
                         (dict(norm="none", score_mod="relu"), None),
-                        (dict(norm="abssum", score_mod="head_decay", mask="causal", gamma=[.9] * 4), A.AE_ERR_UNSUPPORTED),
+                        (dict(norm="abssum", score_mod="head_decay", mask="causal", gamma=[.9] * 4), "ws"),
+                        (dict(norm="none", score_mod="head_decay", mask="causal", gamma=[.9] * 4), A.AE_ERR_UNSUPPORTED),
                         (dict(mask="sliding_window", window=8), "ws")):
         dd = _ok_desc()
         dd.update(patch)
