@@ -182,11 +182,9 @@ ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t *h, size_t *bytes);
  *   dQ = scale * dS' K,  dK = scale * dS'^T Q,
  * with the weights P recomputed from Q, K and the forward pass's row statistic;
  * dK and dV of a k/v head are summed over the query heads that share it.
- * Supported: every normalization with AE_MOD_NONE or AE_MOD_BIAS, AE_NORM_NONE
- * also with AE_MOD_RELU (ReLU attention), AE_NORM_ABSSUM and AE_NORM_ABS_OF_SUM
- * also with AE_MOD_HEAD_DECAY (retention); every mask
- * that ae_attn_create accepts for the pair, every supported pair of head dims
- * (AE_ERR_UNSUPPORTED otherwise; kv_splits plays no part).
+ * Supported: every (score_mod, norm) pair, mask and pair of head dims that
+ * ae_attn_create accepts (per-head decay multiplies dS' as it multiplies S';
+ * kv_splits plays no part).
  *   Q, K, V   device, bf16, laid out as the descriptor says (the forward inputs);
  *   O         device, the forward output, dtype and strides as the descriptor
  *             says (read where a row statistic exists; may be NULL otherwise);

@@ -361,11 +361,10 @@ ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, c
   const int norm = d.norm == AE_NORM_NONE && d.score_mod == AE_MOD_RELU ? ae::BWD_NORM_NONE_RELU : h->kernel->norm;
   const bool abs_family = norm == ae::NORM_ABSSUM || norm == ae::NORM_ABS_OF_SUM;
   const bool mod_ok = d.score_mod == AE_MOD_NONE || d.score_mod == AE_MOD_BIAS || norm == ae::BWD_NORM_NONE_RELU ||
-                      (abs_family && d.score_mod == AE_MOD_HEAD_DECAY);
+                      ((abs_family || norm == ae::NORM_NONE) && d.score_mod == AE_MOD_HEAD_DECAY);
   if (!ae::backward_supported(d.D_qk, d.D_v, norm) || !mod_ok)
     return fail(AE_ERR_UNSUPPORTED,
-                "ae_attn_backward: built for every normalization with score_mod NONE or BIAS, no normalization also with "
-                "RELU, the abs-sum normalizations also with HEAD_DECAY");
+                "ae_attn_backward: unsupported (score_mod, norm) pair or head dims");
   const bool softmax = norm == ae::NORM_SOFTMAX || abs_family;  // the variants that read O, the row statistic and a workspace
   if (!Q || !K || !V || !dO || !dQ || !dK || !dV || (softmax && (!O || !stats || !workspace)))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: null device pointer");

@@ -99,6 +99,9 @@ struct BwdCfg {
                 "backward: softmax, sigmoid, the abs-sum family, and no normalization with or without ReLU");
   static constexpr bool ABS = NORM == NORM_ABSSUM || NORM == NORM_ABS_OF_SUM;
   static constexpr bool ROWS = NORM == NORM_SOFTMAX || ABS;  // per-row quantities from the forward statistic and delta
+  // no normalization (without ReLU) is the abs-sum form with the row factors fixed at 1 and 0: P = S', dS' = dP,
+  // per-head decay included
+  static constexpr bool LIN = ABS || NORM == NORM_NONE;
   static_assert(LDS_BYTES <= (OCC2 ? 80 : 160) * 1024, "the workgroups of a CU must fit LDS");
   static_assert((TILE * CPR1 / 64) % WAVES == 0 && (TILE * CPR2 / 64) % WAVES == 0, "every wave copies the same number of blocks");
 };
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
   for (int t = 0; t < C::T2; ++t) xb2[t] = *reinterpret_cast<const bf16x8*>(x2 + (2 * t + half) * 8);
   // query side: the row quantities belong to the lane's own row
   // (first: (bias - lse) * log2(e) for softmax, 1 / max(|statistic|, 1) for the abs-sum family; second: delta)
-  float nl_own = C::ABS ? 1.f : -INFINITY, dl_own = 0.f;
+  float nl_own = C::LIN ? 1.f : -INFINITY, dl_own = 0.f;
   if constexpr (!C::KV_SIDE && C::ROWS) {
     if (own < p.L_q) {
       const int64_t r = ((int64_t)b * p.H_q + ho) * p.L_q + own;
@@ -162,7 +165,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
     }
   }
   float lg = 0.f;  // log2 of the decay rate of the q head at hand (0: no decay); key side: set per tile
-  if constexpr (!C::KV_SIDE && C::ABS) lg = dt.log2_gamma[ho];
+  if constexpr (!C::KV_SIDE && C::LIN) lg = dt.log2_gamma[ho];
 
   // ---- the walk over the other side --------------------------------------------------
   // key side: the query tiles from the first one that sees key own0, for each q head of
@@ -382,7 +385,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
         pv = fast_rcp(1.f + fast_exp2(-x[r]));
         if constexpr (C::HAS2) w2[r] = pv;
         pv = dp[r] * pv * (1.f - pv);
-      } else if constexpr (C::ABS) {  // a hidden entry has x = -inf: weight and gradient 0
+      } else if constexpr (C::LIN) {  // a hidden entry has x = -inf: weight and gradient 0
         const bool vis = x[r] != -INFINITY;
         const float dist = dist0 + (C::KV_SIDE ? 1.f : -1.f) * (float)key_offset(r);
         const float dec = fast_exp2(lg * fmaxf(dist, 0.f));  // (visible entries have dist >= 0; <= 1 keeps 0 * dec finite)
@@ -397,10 +400,6 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       } else if constexpr (C::NORM == BWD_NORM_NONE_RELU) {  // P = max(x, 0); a hidden entry has x = -inf
         if constexpr (C::HAS2) w2[r] = fmaxf(x[r], 0.f);
         pv = x[r] > 0.f ? dp[r] : 0.f;
-      } else {                                               // P = x on visible entries
-        const bool vis = x[r] != -INFINITY;
-        if constexpr (C::HAS2) w2[r] = vis ? x[r] : 0.f;
-        pv = vis ? dp[r] : 0.f;
       }
       w[r] = pv;
     }
@@ -435,7 +434,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       rowq_next = load_rowq(n + 1);
     }
     const int r0 = (t_first + (C::KV_SIDE ? n % nt : n)) * C::TILE;
-    if constexpr (C::KV_SIDE && C::ABS) lg = dt.log2_gamma[hk * p.g + n / nt];
+    if constexpr (C::KV_SIDE && C::LIN) lg = dt.log2_gamma[hk * p.g + n / nt];
     subtile(stagec, std::integral_constant<int, 0>{}, r0);
     subtile(stagec, std::integral_constant<int, 1>{}, r0 + 32);
     if (n + 1 < total) store_rowq(rowq_next, STAGE ^ 1);

@@ -74,6 +74,7 @@ VARIANTS = {
     "retnet_abssum": dict(score_mod="head_decay", norm="abssum", mask="causal", decay=True),
     "retnet_abs_of_sum": dict(score_mod="head_decay", norm="abs_of_sum", mask="causal", decay=True),
     "retnet_abssum_below_clamp": dict(score_mod="head_decay", norm="abssum", mask="causal", decay=True, scale=0.0005),
+    "decay_nonorm": dict(score_mod="head_decay", norm="none", mask="causal", decay=True, scale=0.01),
     "abssum_plain": dict(norm="abssum"),
     # (|sum| as normalizer: a bias that keeps the row sums away from cancellation, where the statistic itself --
     # and with it every gradient of the row -- is ill-conditioned)
@@ -151,21 +152,23 @@ def test_backward_full_size_c2_one_group(A):
 
 
 def test_backward_seeded_random_shapes(A):
-    """32 seeded draws over shapes (ragged, L_q != L_k in both directions), head grouping, head dims,
+    """40 seeded draws over shapes (ragged, L_q != L_k in both directions), head grouping, head dims,
     normalization / modification / mask, each against the backward oracle."""
     rng = np.random.default_rng(20250305)
-    combos = [("softmax", "none"), ("softmax", "bias"), ("sigmoid", "bias"), ("none", "relu"), ("none", "none")]
-    for case in range(32):
+    combos = [("softmax", "none"), ("softmax", "bias"), ("sigmoid", "bias"), ("none", "relu"), ("none", "none"),
+              ("abssum", "none"), ("abssum", "head_decay"), ("none", "head_decay")]
+    for case in range(40):
         dims = DIMS[int(rng.integers(len(DIMS)))]
         norm, mod = combos[int(rng.integers(len(combos)))]
         g = int(rng.choice([1, 2, 4]))
         H_kv = int(rng.integers(1, 3))
         Lq, Lk = int(rng.integers(1, 500)), int(rng.integers(1, 600))
-        mask = str(rng.choice(["none", "causal", "sliding_window"]))
-        if mask == "sliding_window" and mod == "relu":
+        mask = "causal" if mod == "head_decay" else str(rng.choice(["none", "causal", "sliding_window"]))
+        if mask == "sliding_window" and (mod == "relu" or norm == "abssum"):
             mask = "causal"
         w = Workload(f"rand{case}", 500 + case, int(rng.integers(1, 3)), g * H_kv, H_kv, Lq, Lk, dims[0], dims[1],
-                     score_mod=mod, norm=norm, mask=mask, window=int(rng.integers(1, 400)) if mask == "sliding_window" else 0, bias=float(rng.uniform(-2, 1)) if norm != "none" else 0.01,
+                     score_mod=mod, norm=norm, mask=mask, window=int(rng.integers(1, 400)) if mask == "sliding_window" else 0,
+                     decay=(mod == "head_decay"), bias=float(rng.uniform(-2, 1)) if norm != "none" else 0.01,
                      scale=(0.01 if norm == "none" else None))
         run_case(A, w)
 
