@@ -48,7 +48,7 @@ import math
 
 import numpy as np
 
-SCORE_MODS = ("none", "bias", "head_decay", "relu")
+SCORE_MODS = ("none", "bias", "head_decay", "relu", "bias_tensor")
 NORMS = ("softmax", "sigmoid", "abssum", "abs_of_sum", "none")
 MASKS = ("none", "causal", "sliding_window")  # the last one is passed as ("sliding_window", W)
 
@@ -78,7 +78,7 @@ def _visible(rows, L_q, L_k, mask):
     raise ValueError(f"unknown mask {mask!r}")
 
 
-def _modified_scores(q, k, *, scale, score_mod, bias, gamma_h, mask, rows):
+def _modified_scores(q, k, *, scale, score_mod, bias, gamma_h, mask, rows, bias_t=None):
     """(S'[rows, :], visibility[rows, :]) for one head: relevance scoring and
     the elementwise modification, before any row-wise normalization."""
     q = _as_f64(q)
@@ -103,20 +103,26 @@ def _modified_scores(q, k, *, scale, score_mod, bias, gamma_h, mask, rows):
         s = s * decay
     elif score_mod == "relu":
         s = np.maximum(s, 0.0)
+    elif score_mod == "bias_tensor":
+        # an additive bias per (query, key) pair (Section 4.1: a modification is any
+        # elementwise function of the scores; relative-position and ALiBi biases are this)
+        if bias_t is None:
+            raise ValueError("bias_tensor needs bias_t [L_q, L_k]")
+        s = s + _as_f64(bias_t)[rows]
     else:
         raise ValueError(f"unknown score_mod {score_mod!r}")
     return s, vis
 
 
 def weights_head(q, k, *, scale, score_mod="none", bias=0.0, gamma_h=None,
-                 norm="softmax", mask="none", rows=None):
+                 norm="softmax", mask="none", rows=None, bias_t=None):
     """P[rows, :] for one head: q [L_q, D_qk], k [L_k, D_qk] -> [len(rows), L_k].
 
     `rows` selects query rows (default all); each row is independent, so a
     subset is the same definition evaluated on fewer rows.
     """
     s, vis = _modified_scores(q, k, scale=scale, score_mod=score_mod, bias=bias,
-                              gamma_h=gamma_h, mask=mask, rows=rows)
+                              gamma_h=gamma_h, mask=mask, rows=rows, bias_t=bias_t)
     # row-wise normalization; masked entries take no part
     if norm == "softmax":
         sm = np.where(vis, s, -np.inf)
@@ -143,7 +149,7 @@ def weights_head(q, k, *, scale, score_mod="none", bias=0.0, gamma_h=None,
 
 
 def row_stats_head(q, k, *, scale, score_mod="none", bias=0.0, gamma_h=None,
-                   norm="softmax", mask="none", rows=None):
+                   norm="softmax", mask="none", rows=None, bias_t=None):
     """The final result of the row reduction that the normalization keeps per
     query row (Section 4.1, online row-norm interface: the final row scales),
     over the visible keys of each row:
@@ -153,7 +159,7 @@ def row_stats_head(q, k, *, scale, score_mod="none", bias=0.0, gamma_h=None,
     The running maximum and running sum of the online form are not unique
     (they depend on the block order); their combination above is."""
     s, vis = _modified_scores(q, k, scale=scale, score_mod=score_mod, bias=bias,
-                              gamma_h=gamma_h, mask=mask, rows=rows)
+                              gamma_h=gamma_h, mask=mask, rows=rows, bias_t=bias_t)
     if norm == "softmax":
         sm = np.where(vis, s, -np.inf)
         m = sm.max(axis=1)
@@ -169,18 +175,19 @@ def row_stats_head(q, k, *, scale, score_mod="none", bias=0.0, gamma_h=None,
 
 
 def attention_head(q, k, v, *, scale, score_mod="none", bias=0.0, gamma_h=None,
-                   norm="softmax", mask="none", rows=None):
+                   norm="softmax", mask="none", rows=None, bias_t=None):
     """O[rows, :] for one head: aggregation P @ V (Section 4.1)."""
     p = weights_head(q, k, scale=scale, score_mod=score_mod, bias=bias,
-                     gamma_h=gamma_h, norm=norm, mask=mask, rows=rows)
+                     gamma_h=gamma_h, norm=norm, mask=mask, rows=rows, bias_t=bias_t)
     return p @ _as_f64(v)
 
 
 def attention(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
-              norm="softmax", mask="none"):
+              norm="softmax", mask="none", bias_tensor=None):
     """Full operator.  Q [B,H_q,L_q,D_qk], K [B,H_kv,L_k,D_qk],
     V [B,H_kv,L_k,D_v] -> O [B,H_q,L_q,D_v] in fp64.  `gamma` is a length-H_q
-    sequence of per-query-head decay rates (head_decay only)."""
+    sequence of per-query-head decay rates (head_decay only); `bias_tensor`
+    [B or 1, H_q or 1, L_q, L_k] the additive bias of score_mod "bias_tensor"."""
     Q, K, V = _as_f64(Q), _as_f64(K), _as_f64(V)
     B, H_q, L_q, _ = Q.shape
     H_kv = K.shape[1]
@@ -188,18 +195,20 @@ def attention(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
         raise ValueError("H_q must be a multiple of H_kv")
     g = H_q // H_kv
     O = np.zeros((B, H_q, L_q, V.shape[3]), dtype=np.float64)
+    bt = None if bias_tensor is None else _as_f64(bias_tensor)
     for b in range(B):
         for h in range(H_q):
             O[b, h] = attention_head(
                 Q[b, h], K[b, h // g], V[b, h // g], scale=scale,
                 score_mod=score_mod, bias=bias,
                 gamma_h=None if gamma is None else float(gamma[h]),
-                norm=norm, mask=mask)
+                norm=norm, mask=mask,
+                bias_t=None if bt is None else bt[b if bt.shape[0] > 1 else 0, h if bt.shape[1] > 1 else 0])
     return O
 
 
 def brute(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
-          norm="softmax", mask="none"):
+          norm="softmax", mask="none", bias_tensor=None):
     """The same definition as scalar Python loops (tiny shapes only).  Used to
     check the vectorised functions above; written separately, element by
     element, so an indexing or broadcasting slip in one does not repeat in the
@@ -232,6 +241,9 @@ def brute(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
                         s *= float(gamma[h]) ** (i + off - j)
                     elif score_mod == "relu":
                         s = max(s, 0.0)
+                    elif score_mod == "bias_tensor":
+                        bt = bias_tensor
+                        s += float(bt[b if bt.shape[0] > 1 else 0][h if bt.shape[1] > 1 else 0][i][j])
                     w.append(s)
                 live = [x for x in w if x is not None]
                 if not live:

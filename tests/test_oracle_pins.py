@@ -443,3 +443,43 @@ def test_sliding_window_equals_brute(norm, score_mod):
     Q, K, V = rnd(1, 2, 7, 3), rnd(1, 1, 10, 3), rnd(1, 1, 10, 4)
     kw = dict(scale=0.7, score_mod=score_mod, bias=-0.3, gamma=[0.9, 0.8], norm=norm, mask=("sliding_window", 3))
     np.testing.assert_allclose(attention(Q, K, V, **kw), brute(Q, K, V, **kw), rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- additive bias tensor
+def test_bias_tensor_reduces_to_known_cases():
+    B, Hq, Hkv, Lq, Lk, D = 2, 4, 2, 6, 7, 3
+    Q, K, V = rnd(B, Hq, Lq, D), rnd(B, Hkv, Lk, D), rnd(B, Hkv, Lk, 4)
+    # a constant tensor is the constant bias, for every normalization that takes one
+    for norm in ("softmax", "sigmoid", "abssum", "none"):
+        a = attention(Q, K, V, scale=0.5, score_mod="bias", bias=0.7, norm=norm, mask="causal")
+        b = attention(Q, K, V, scale=0.5, score_mod="bias_tensor", bias_tensor=np.full((1, 1, Lq, Lk), 0.7), norm=norm,
+                      mask="causal")
+        np.testing.assert_allclose(a, b, atol=1e-14)
+    # softmax: a bias of -1e30 above the (bottom-right aligned) diagonal is the causal mask
+    tri = np.where(np.arange(Lk)[None, :] <= np.arange(Lq)[:, None] + (Lk - Lq), 0.0, -1e30)[None, None]
+    np.testing.assert_allclose(attention(Q, K, V, scale=0.5, score_mod="bias_tensor", bias_tensor=tri),
+                               attention(Q, K, V, scale=0.5, mask="causal"), atol=1e-14)
+    # softmax ignores a per-row shift of the bias; the log-sum-exp statistic moves by exactly that shift
+    bt = rnd(B, Hq, Lq, Lk)
+    shift = rnd(B, Hq, Lq, 1)
+    np.testing.assert_allclose(attention(Q, K, V, scale=0.5, score_mod="bias_tensor", bias_tensor=bt),
+                               attention(Q, K, V, scale=0.5, score_mod="bias_tensor", bias_tensor=bt + shift), atol=1e-13)
+    s0 = row_stats_head(Q[1, 2], K[1, 1], scale=0.5, score_mod="bias_tensor", bias_t=bt[1, 2])
+    s1 = row_stats_head(Q[1, 2], K[1, 1], scale=0.5, score_mod="bias_tensor", bias_t=(bt + shift)[1, 2])
+    np.testing.assert_allclose(s1 - s0, shift[1, 2, :, 0], atol=1e-13)
+    # Q = 0: the weights are softmax(bias row) whatever K is -- library softmax
+    O = attention(np.zeros_like(Q), K, V, scale=0.5, score_mod="bias_tensor", bias_tensor=bt)
+    P = torch.softmax(torch.from_numpy(bt), dim=-1).numpy()
+    ref = np.einsum("bhij,bhjd->bhid", P, np.repeat(V, 2, axis=1))
+    np.testing.assert_allclose(O, ref, atol=1e-13)
+
+
+@pytest.mark.parametrize("norm", ["softmax", "sigmoid", "none", "abs_of_sum"])
+@pytest.mark.parametrize("mask", ["none", "causal"])
+def test_bias_tensor_equals_brute(norm, mask):
+    B, Hq, Hkv, Lq, Lk, D = 2, 2, 1, 5, 6, 3
+    Q, K, V = rnd(B, Hq, Lq, D), rnd(B, Hkv, Lk, D), rnd(B, Hkv, Lk, 2)
+    for shape in ((B, Hq, Lq, Lk), (1, Hq, Lq, Lk), (1, 1, Lq, Lk)):   # per batch and head, shared over batch, over both
+        bt = rnd(*shape)
+        kw = dict(scale=0.6, score_mod="bias_tensor", bias_tensor=bt, norm=norm, mask=mask)
+        np.testing.assert_allclose(attention(Q, K, V, **kw), brute(Q, K, V, **kw), atol=1e-13)
