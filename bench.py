@@ -153,6 +153,9 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (ae_attn_backward: dQ, dK, dV) on the softmax / sigmoid benchmark "
                          "shapes and print TFLOP/s against the bf16 MFMA peak")
+    ap.add_argument("--bias-tensor", action="store_true",
+                    help="time the forward pass with an additive bias tensor (score_mod bias_tensor) beside the same shape "
+                         "without one")
     ap.add_argument("--only", default="", help="with --backward: only the shapes whose name contains this")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device-to-device copy of this many MiB "
@@ -331,6 +334,62 @@ def main():
                   f"MFMAs issued: {issued / (ms * 1e-3) / 1e12:7.1f} TFLOP/s)  parity {par}", file=sys.stderr, flush=True)
             del Q, K, V, dO, O, dQ, dK, dV
         print(json.dumps({"backward": rows, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS, "dtype": "bf16", "data": "synthetic"}))
+        return
+    if a.bias_tensor:
+        # Not the contract line.  The bias tensor [1, H_q, L_q, L_k] (bf16, shared over the batch) is read once per
+        # batch element: B * H_q * visible pairs * 2 bytes on top of Q, K, V, O.
+        from oracle import attention_head
+        from paper_2502_15349_amd.workloads import C2, Workload, make_bias_tensor
+        rows = []
+        for base in (C2, Workload("softmax_b8_h32_s4096_causal", 160, 8, 32, 32, 4096, 4096, 128, 128, mask="causal"),
+                     Workload("softmax_b8_h32_s4096", 161, 8, 32, 32, 4096, 4096, 128, 128)):
+            w = base.scaled(score_mod="bias_tensor")
+            Qc, Kc, Vc = make_inputs(w)
+            Q, K, V = Qc.to(dev), Kc.to(dev), Vc.to(dev)
+            bt = make_bias_tensor(w, per_batch=False)
+            btd = bt.to(dev)
+            O = torch.empty((w.B, w.H_q, w.L_q, w.D_v), dtype=torch.float32, device=dev)
+            res = {}
+            for name, ww in (("plain", base), ("bias_tensor", w)):
+                h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
+                                     scale=w.scale_value, score_mod=ww.score_mod, mask=w.mask,
+                                     bias_stride=(0, btd.stride(1), btd.stride(2)))
+                st = torch.cuda.current_stream()
+
+                def call():
+                    if name == "plain":
+                        A.ae_attn_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), st.cuda_stream)
+                    else:
+                        A.ae_attn_forward_bias(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), btd.data_ptr(), O.data_ptr(), 0,
+                                               st.cuda_stream)
+                t_end = time.perf_counter() + 0.3
+                while time.perf_counter() < t_end:
+                    call()
+                    torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(st)
+                for _ in range(20):
+                    call()
+                e1.record(st)
+                torch.cuda.synchronize()
+                A.ae_attn_destroy(h)
+                res[name] = e0.elapsed_time(e1) / 20
+            # parity of the bias run on sampled rows of one head
+            b, hq = w.B - 1, w.H_q // 2
+            rows_s = np.linspace(0, w.L_q - 1, 24).astype(np.int64)
+            ref = attention_head(Qc[b, hq], Kc[b, hq // (w.H_q // w.H_kv)], Vc[b, hq // (w.H_q // w.H_kv)], scale=w.scale_value,
+                                 score_mod="bias_tensor", mask=w.mask, rows=rows_s, bias_t=bt[0, hq])
+            err = float(np.abs(O[b, hq].cpu().double().numpy()[rows_s] - ref).max())
+            flop = w.mfma_flop()
+            bias_bytes = 2 * w.visible_pairs_per_head() * w.B * w.H_q
+            rows.append({"workload": w.name, "plain_ms": round(res["plain"], 4), "bias_tensor_ms": round(res["bias_tensor"], 4),
+                         "plain_tflops": round(flop / res["plain"] / 1e9, 1), "bias_tensor_tflops": round(flop / res["bias_tensor"] / 1e9, 1),
+                         "bias_GBps": round(bias_bytes / res["bias_tensor"] / 1e6, 1), "parity_max_abs": err})
+            print(f"# {w.name:32s} plain {res['plain']:8.4f} ms {flop / res['plain'] / 1e9:7.1f} TFLOP/s | bias tensor "
+                  f"{res['bias_tensor']:8.4f} ms {flop / res['bias_tensor'] / 1e9:7.1f} TFLOP/s ({100 * flop / res['bias_tensor'] / 1e9 / PEAK_BF16_TFLOPS:4.1f} % "
+                  f"of peak), bias read at {bias_bytes / res['bias_tensor'] / 1e6:7.1f} GB/s  max_abs {err:.2e}", file=sys.stderr, flush=True)
+            del Q, K, V, O, btd
+        print(json.dumps({"bias_tensor": rows, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS, "dtype": "bf16", "data": "synthetic"}))
         return
     if a.table2:
         # Not the contract line: the paper's own microbenchmark grid, one row per shape.

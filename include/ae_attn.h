@@ -43,7 +43,10 @@ typedef enum {
   AE_MOD_BIAS = 1,       /* s' + bias            (constant additive bias)      */
   AE_MOD_HEAD_DECAY = 2, /* s' * gamma[h_q]^(i + L_k - L_q - j): the retention
                             mask of RetNet parallel attention; needs CAUSAL    */
-  AE_MOD_RELU = 3        /* max(s', 0)           (ReLU attention)              */
+  AE_MOD_RELU = 3,       /* max(s', 0)           (ReLU attention)              */
+  AE_MOD_BIAS_TENSOR = 4 /* s' + bias[b, h_q, i, j]: an additive bias per
+                            (query, key) pair (relative position, ALiBi ...),
+                            a device tensor passed to ae_attn_forward_bias     */
 } ae_score_mod_t;
 
 /* Row-wise normalization of the modified scores over the visible keys.      */
@@ -108,6 +111,12 @@ typedef struct {
                           the device idle); ask ae_attn_workspace_bytes whether
                           it did.                                               */
   int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3];
+  int64_t bias_stride[3]; /* AE_MOD_BIAS_TENSOR: element strides {batch, head,
+                          row} of the bf16 bias tensor [B, H_q, L_q, L_k] (last
+                          dimension contiguous).  All zero: contiguous.  A batch
+                          or head stride of 0 beside a non-zero row stride shares
+                          the tensor over that dimension.  The row stride must be
+                          >= L_k and a multiple of 4.                           */
 } ae_attn_desc_t;
 
 /* Validates the descriptor, picks the kernel and its tile shape for
@@ -116,6 +125,8 @@ typedef struct {
  * Supported (score_mod, norm) pairs: NONE or BIAS with every norm;
  * HEAD_DECAY with ABSSUM, ABS_OF_SUM or NONE (CAUSAL mask only); RELU with NONE.
  * AE_MASK_SLIDING_WINDOW: score_mod NONE or BIAS with SOFTMAX, SIGMOID or NONE.
+ * AE_MOD_BIAS_TENSOR: with SOFTMAX, SIGMOID or NONE, masks NONE or CAUSAL, head
+ * dims 64/64, 128/128 or 192/128, no split keys.
  * Errors: AE_ERR_INVALID_ARG, AE_ERR_UNSUPPORTED, AE_ERR_NOMEM; *out is set
  * to NULL on error.                                                           */
 ae_status_t ae_attn_create(const ae_attn_desc_t *desc, ae_attn_t **out);
@@ -143,6 +154,15 @@ ae_status_t ae_attn_forward(const ae_attn_t *h, const void *Q, const void *K,
 ae_status_t ae_attn_forward_stats(const ae_attn_t *h, const void *Q,
                                   const void *K, const void *V, void *O,
                                   void *stats, void *stream);
+
+/* Forward for a handle created with AE_MOD_BIAS_TENSOR: ae_attn_forward with the
+ * additive bias tensor (device, bf16, 8-byte aligned, laid out as
+ * desc.bias_stride says, read only) and optionally the row statistic (stats may be
+ * NULL; see ae_attn_forward_stats).  One kernel, nothing allocated.  Errors as
+ * ae_attn_forward; AE_ERR_INVALID_ARG for a handle of another score_mod.        */
+ae_status_t ae_attn_forward_bias(const ae_attn_t *h, const void *Q, const void *K,
+                                 const void *V, const void *bias, void *O,
+                                 void *stats, void *stream);
 
 /* Bytes of device workspace that ae_attn_forward_split needs for this handle:
  * the partial output rows and their log-sum-exp, fp32,
@@ -183,8 +203,8 @@ ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t *h, size_t *bytes);
  * with the weights P recomputed from Q, K and the forward pass's row statistic;
  * dK and dV of a k/v head are summed over the query heads that share it.
  * Supported: every (score_mod, norm) pair, mask and pair of head dims that
- * ae_attn_create accepts (per-head decay multiplies dS' as it multiplies S';
- * kv_splits plays no part).
+ * ae_attn_create accepts, except AE_MOD_BIAS_TENSOR (AE_ERR_UNSUPPORTED);
+ * per-head decay multiplies dS' as it multiplies S'; kv_splits plays no part.
  *   Q, K, V   device, bf16, laid out as the descriptor says (the forward inputs);
  *   O         device, the forward output, dtype and strides as the descriptor
  *             says (read where a row statistic exists; may be NULL otherwise);

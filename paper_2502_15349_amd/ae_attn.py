@@ -20,7 +20,7 @@ if not os.path.exists(_LIB_PATH):
 _lib = C.CDLL(_LIB_PATH)
 
 AE_OK, AE_ERR_INVALID_ARG, AE_ERR_UNSUPPORTED, AE_ERR_HIP, AE_ERR_NOMEM = range(5)
-SCORE_MODS = {"none": 0, "bias": 1, "head_decay": 2, "relu": 3}
+SCORE_MODS = {"none": 0, "bias": 1, "head_decay": 2, "relu": 3, "bias_tensor": 4}
 NORMS = {"softmax": 0, "sigmoid": 1, "abssum": 2, "abs_of_sum": 3, "none": 4}
 MASKS = {"none": 0, "causal": 1, "sliding_window": 2}
 OUT_DTYPES = {"f32": 0, "bf16": 1}
@@ -35,6 +35,7 @@ class ae_attn_desc_t(C.Structure):
         ("window", C.c_int32), ("kv_splits", C.c_int32),
         ("q_stride", C.c_int64 * 3), ("k_stride", C.c_int64 * 3),
         ("v_stride", C.c_int64 * 3), ("o_stride", C.c_int64 * 3),
+        ("bias_stride", C.c_int64 * 3),
     ]
 
 
@@ -44,6 +45,8 @@ _lib.ae_attn_forward.argtypes = [C.c_void_p] * 6
 _lib.ae_attn_forward.restype = C.c_int
 _lib.ae_attn_forward_stats.argtypes = [C.c_void_p] * 7
 _lib.ae_attn_forward_stats.restype = C.c_int
+_lib.ae_attn_forward_bias.argtypes = [C.c_void_p] * 8
+_lib.ae_attn_forward_bias.restype = C.c_int
 _lib.ae_attn_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
 _lib.ae_attn_workspace_bytes.restype = C.c_int
 _lib.ae_attn_forward_split.argtypes = [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
@@ -89,7 +92,7 @@ def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int
                    scale: float, score_mod="none", bias: float = 0.0,
                    gamma: Optional[Sequence[float]] = None, norm="softmax", mask="none",
                    q_stride=(0, 0, 0), k_stride=(0, 0, 0), v_stride=(0, 0, 0), o_stride=(0, 0, 0),
-                   out_dtype="f32", window: int = 0, kv_splits: int = 0) -> int:
+                   out_dtype="f32", window: int = 0, kv_splits: int = 0, bias_stride=(0, 0, 0)) -> int:
     """Returns an opaque handle (int).  Enum arguments accept names or raw ints."""
     d = ae_attn_desc_t()
     d.B, d.H_q, d.H_kv, d.L_q, d.L_k, d.D_qk, d.D_v = B, H_q, H_kv, L_q, L_k, D_qk, D_v
@@ -104,7 +107,8 @@ def ae_attn_create(*, B: int, H_q: int, H_kv: int, L_q: int, L_k: int, D_qk: int
     if gamma is not None:
         keep = (C.c_float * len(gamma))(*[float(x) for x in gamma])
         d.gamma = C.cast(keep, C.POINTER(C.c_float))
-    for name, val in (("q_stride", q_stride), ("k_stride", k_stride), ("v_stride", v_stride), ("o_stride", o_stride)):
+    for name, val in (("q_stride", q_stride), ("k_stride", k_stride), ("v_stride", v_stride), ("o_stride", o_stride),
+                      ("bias_stride", bias_stride)):
         setattr(d, name, (C.c_int64 * 3)(*[int(x) for x in val]))
     h = C.c_void_p()
     _check(_lib.ae_attn_create(C.byref(d), C.byref(h)))
@@ -135,6 +139,12 @@ def ae_attn_backward(handle: int, Q: int, K: int, V: int, O: int, dO: int, stats
     """Device addresses throughout: dQ, dK, dV (fp32, contiguous) receive the gradients for the upstream
     gradient dO (bf16, contiguous); O and stats are what ae_attn_forward_stats wrote."""
     _check(_lib.ae_attn_backward(handle, Q, K, V, O, dO, stats, dQ, dK, dV, workspace, workspace_bytes, stream))
+
+
+def ae_attn_forward_bias(handle: int, Q: int, K: int, V: int, bias: int, O: int, stats: int = 0, stream: int = 0) -> None:
+    """Forward of a handle created with score_mod "bias_tensor"; bias is the device address of the bf16 bias tensor,
+    stats may be 0 (not written)."""
+    _check(_lib.ae_attn_forward_bias(handle, Q, K, V, bias, O, stats, stream))
 
 
 def ae_attn_forward_stats(handle: int, Q: int, K: int, V: int, O: int, stats: int, stream: int = 0) -> None:
@@ -170,14 +180,15 @@ def ae_attn_query(handle: int) -> dict:
 # ---- convenience for torch callers (still marshalling only) -------------------
 def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
                       mask="none", out=None, stream=None, out_dtype=None, stats=None, window=0, kv_splits=0,
-                      workspace=None):
+                      workspace=None, bias_tensor=None):
     """Runs the HIP operator on CUDA/HIP bf16 tensors laid out [B, H, L, D]
     (last dim contiguous) and returns O [B, H_q, L_q, D_v]: fp32, or bf16 if `out` is a
     bf16 tensor or out_dtype is torch.bfloat16.  stats: optional contiguous fp32 device
     tensor [B, H_q, L_q] that receives the row statistic of the normalization.  window: keys
     per query for mask="sliding_window".  kv_splits > 1: the keys are cut into that many ranges
     (few query rows, many keys); `workspace` is then a device byte tensor of at least
-    ae_attn_workspace_bytes() bytes (allocated here if not given)."""
+    ae_attn_workspace_bytes() bytes (allocated here if not given).  bias_tensor: for score_mod
+    "bias_tensor", a bf16 device tensor [B or 1, H_q or 1, L_q, L_k] (last dimension contiguous)."""
     import torch
 
     if not (Q.is_cuda and K.is_cuda and V.is_cuda):
@@ -197,7 +208,7 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
                        score_mod=score_mod, bias=bias, gamma=gamma, norm=norm, mask=mask,
                        q_stride=Q.stride()[:3], k_stride=K.stride()[:3], v_stride=V.stride()[:3],
                        o_stride=out.stride()[:3], out_dtype="bf16" if out.dtype == torch.bfloat16 else "f32",
-                       window=window, kv_splits=kv_splits)
+                       window=window, kv_splits=kv_splits, bias_stride=_bias_strides(bias_tensor, B, H_q, L_q, L_k))
     try:
         s = torch.cuda.current_stream(Q.device) if stream is None else stream
         with torch.cuda.device(Q.device):
@@ -205,7 +216,10 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
                                       or not stats.is_contiguous()):
                 raise ValueError("stats must be a contiguous fp32 tensor [B, H_q, L_q]")
             need = ae_attn_workspace_bytes(h)
-            if need:
+            if bias_tensor is not None:
+                ae_attn_forward_bias(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), bias_tensor.data_ptr(), out.data_ptr(),
+                                     0 if stats is None else stats.data_ptr(), s.cuda_stream)
+            elif need:
                 if workspace is None:
                     workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
                 ae_attn_forward_split(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
@@ -221,6 +235,19 @@ def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None,
     finally:
         ae_attn_destroy(h)
     return out
+
+
+def _bias_strides(bias_tensor, B, H_q, L_q, L_k):
+    """Element strides {batch, head, row} of a bias tensor [B or 1, H_q or 1, L_q, L_k]; a dimension of size 1 is
+    shared (stride 0)."""
+    if bias_tensor is None:
+        return (0, 0, 0)
+    import torch
+    t = bias_tensor
+    if (t.dtype != torch.bfloat16 or t.dim() != 4 or t.shape[0] not in (1, B) or t.shape[1] not in (1, H_q)
+            or tuple(t.shape[2:]) != (L_q, L_k) or t.stride(3) != 1 or not t.is_cuda):
+        raise ValueError("bias_tensor must be a bf16 device tensor [B or 1, H_q or 1, L_q, L_k] with a contiguous last dimension")
+    return (0 if t.shape[0] == 1 else t.stride(0), 0 if t.shape[1] == 1 else t.stride(1), t.stride(2))
 
 
 def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
@@ -261,8 +288,8 @@ def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0
     return dQ, dK, dV
 
 
-def run_workload(w, Q, K, V, out=None, out_dtype=None, stats=None, kv_splits=0):
+def run_workload(w, Q, K, V, out=None, out_dtype=None, stats=None, kv_splits=0, bias_tensor=None):
     """attention_forward with the parameters of a workloads.Workload."""
     return attention_forward(Q, K, V, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
                              gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out, out_dtype=out_dtype, stats=stats,
-                             window=w.window, kv_splits=kv_splits)
+                             window=w.window, kv_splits=kv_splits, bias_tensor=bias_tensor)

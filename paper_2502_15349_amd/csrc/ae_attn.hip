@@ -114,7 +114,7 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     return fail(AE_ERR_INVALID_ARG, "ae_attn_create: H_q (%d) is not a multiple of H_kv (%d)", d->H_q, d->H_kv);
   if (!std::isfinite(d->scale) || d->scale == 0.f)
     return fail(AE_ERR_INVALID_ARG, "ae_attn_create: scale must be finite and non-zero");
-  if ((int)d->score_mod < 0 || (int)d->score_mod > AE_MOD_RELU)
+  if ((int)d->score_mod < 0 || (int)d->score_mod > AE_MOD_BIAS_TENSOR)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown score_mod %d", (int)d->score_mod);
   if ((int)d->norm < 0 || (int)d->norm > AE_NORM_NONE)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: unknown norm %d", (int)d->norm);
@@ -140,6 +140,11 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   int mod = ae::MOD_PLAIN;
   if (d->score_mod == AE_MOD_HEAD_DECAY) mod = ae::MOD_DECAY;
   if (d->score_mod == AE_MOD_RELU) mod = ae::MOD_RELU;
+  if (d->score_mod == AE_MOD_BIAS_TENSOR) {
+    mod = ae::MOD_BIAS_T;
+    if (d->mask == AE_MASK_SLIDING_WINDOW || d->kv_splits > 1)
+      return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: BIAS_TENSOR comes with the masks NONE and CAUSAL and without split keys");
+  }
   if (d->score_mod == AE_MOD_HEAD_DECAY) {
     if (d->mask != AE_MASK_CAUSAL)
       return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: HEAD_DECAY needs the causal mask");
@@ -171,6 +176,11 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   fill_strides(p.ks, d->k_stride, d->H_kv, d->L_k, d->D_qk);
   fill_strides(p.vs, d->v_stride, d->H_kv, d->L_k, d->D_v);
   fill_strides(p.os, d->o_stride, d->H_q, d->L_q, d->D_v);
+  fill_strides(p.bs, d->bias_stride, d->H_q, d->L_q, d->L_k);
+  if (mod == ae::MOD_BIAS_T && (p.bs[0] < 0 || p.bs[1] < 0 || p.bs[2] < d->L_k || p.bs[2] % 4 != 0 || p.bs[0] % 4 != 0 || p.bs[1] % 4 != 0)) {
+    delete h;
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: bias strides must be non-negative multiples of 4 elements, the row stride >= L_k");
+  }
   const int64_t* in_strides[3] = {p.qs, p.ks, p.vs};
   const int in_d[3] = {d->D_qk, d->D_qk, d->D_v};
   for (int t = 0; t < 3; ++t) {
@@ -204,10 +214,11 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     p.c = a;
     p.b2 = bias;
   }
+  if (mod == ae::MOD_BIAS_T) p.b2 = (d->norm == AE_NORM_SOFTMAX || d->norm == AE_NORM_SIGMOID) ? log2e : 1.f;  // the unit of the bias values
   p.neg_q = d->scale < 0.f ? 1 : 0;
   p.out_bf16 = d->out_dtype == AE_OUT_BF16 ? 1 : 0;
   p.window = d->mask == AE_MASK_SLIDING_WINDOW ? d->window : 0;
-  p.fold = (d->norm == AE_NORM_SIGMOID && std::fabs(p.b2) <= 64.f) ? 1 : 0;
+  p.fold = (d->norm == AE_NORM_SIGMOID && mod != ae::MOD_BIAS_T && std::fabs(p.b2) <= 64.f) ? 1 : 0;
   p.kfac = p.fold ? std::exp2(-p.b2) : 1.f;
   if (mod == ae::MOD_DECAY)
     for (int hh = 0; hh < d->H_q; ++hh) h->decay.log2_gamma[hh] = std::log2(d->gamma[hh]);
@@ -269,13 +280,19 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
 }
 
 static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, float* stats,
-                                void* stream, void* workspace = nullptr, size_t workspace_bytes = 0) {
+                                void* stream, void* workspace = nullptr, size_t workspace_bytes = 0,
+                                const void* bias = nullptr) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null handle");
   if (!Q || !K || !V || !O) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null device pointer");
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
     return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: device pointers must be 16-byte aligned");
   if (O == Q || O == K || O == V) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: O aliases an input");
+  if ((h->kernel->mod == ae::MOD_BIAS_T) != (bias != nullptr))
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: a handle with AE_MOD_BIAS_TENSOR, and only such a handle, runs through "
+                                    "ae_attn_forward_bias with its bias tensor");
+  if (bias && (((uintptr_t)bias & 7) || bias == O)) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_bias: the bias tensor must be 8-byte aligned and must not alias O");
   ae::Params p = h->params;
+  p.bias = static_cast<const __bf16*>(bias);
   p.Q = static_cast<const __bf16*>(Q);
   p.K = static_cast<const __bf16*>(K);
   p.V = static_cast<const __bf16*>(V);
@@ -327,6 +344,19 @@ ae_status_t ae_attn_forward_stats(const ae_attn_t* h, const void* Q, const void*
   if (norm != ae::NORM_SOFTMAX && norm != ae::NORM_ABSSUM && norm != ae::NORM_ABS_OF_SUM)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_forward_stats: this normalization keeps no row statistic");
   return forward_impl(h, Q, K, V, O, static_cast<float*>(stats), stream);
+}
+
+ae_status_t ae_attn_forward_bias(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* bias, void* O,
+                                 void* stats, void* stream) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_bias: null handle");
+  if (!bias) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_bias: null bias tensor");
+  if (stats) {
+    if (((uintptr_t)stats & 3) || stats == O || stats == Q || stats == K || stats == V || stats == bias)
+      return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_bias: stats must be 4-byte aligned and must not alias another buffer");
+    if (h->kernel->norm != ae::NORM_SOFTMAX)
+      return fail(AE_ERR_UNSUPPORTED, "ae_attn_forward_bias: this normalization keeps no row statistic");
+  }
+  return forward_impl(h, Q, K, V, O, static_cast<float*>(stats), stream, nullptr, 0, bias);
 }
 
 ae_status_t ae_attn_workspace_bytes(const ae_attn_t* h, size_t* bytes) {

@@ -53,9 +53,10 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 enum : int { NORM_SOFTMAX = 0, NORM_SIGMOID = 1, NORM_ABSSUM = 2, NORM_ABS_OF_SUM = 3, NORM_NONE = 4 };
-enum : int { MOD_PLAIN = 0, MOD_DECAY = 1, MOD_RELU = 2 };  // PLAIN carries a runtime bias (0 for "none")
+enum : int { MOD_PLAIN = 0, MOD_DECAY = 1, MOD_RELU = 2, MOD_BIAS_T = 3 };  // PLAIN carries a runtime bias (0 for "none"); BIAS_T: an additive bias tensor
 
 constexpr int kMaxDecayHeads = 256;
 
@@ -65,6 +66,8 @@ struct Params {
   const __bf16* V;
   void* O;  // fp32, or bf16 if out_bf16
   float* stats;  // optional [B, H_q, L_q]: final row statistic of the normalization (null: not written)
+  const __bf16* bias;  // MOD_BIAS_T: additive bias per (query, key), element strides bs[] = {batch, head, row}
+  int64_t bs[3];
   int B, H_q, H_kv, L_q, L_k;
   int g;           // H_q / H_kv
   int n_qtiles;    // ceil(L_q / BLOCK_M)
@@ -356,12 +359,18 @@ __device__ __forceinline__ void mask_modified(f32x16& s, int jlim) {
 //   sigmoid  2^-(scale*s + bias) in log2 units
 //   others   the fully modified score x
 template <class C, bool FOLD = false>
-__device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, float dbase, float g2, float& mx) {
+__device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, float dbase, float g2, float& mx,
+                                          uint32_t bias_pair = 0) {
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int r = 2 * q + u;
     float x = s[r];
-    if constexpr (C::NORM == NORM_SOFTMAX) {
+    if constexpr (C::MOD == MOD_BIAS_T) {
+      // the pair's two bf16 bias values, widened; p.b2 holds their unit (log2(e) for softmax and sigmoid, else 1)
+      const float bv = __builtin_bit_cast(float, u == 0 ? bias_pair << 16 : bias_pair & 0xffff0000u) * p.b2;
+      if constexpr (C::NORM == NORM_SIGMOID) x = fast_exp2(-__builtin_fmaf(x, p.c, bv));
+      else x = __builtin_fmaf(x, p.c, bv);  // softmax: the modified score itself (the row max is taken over it)
+    } else if constexpr (C::NORM == NORM_SOFTMAX) {
     } else if constexpr (C::NORM == NORM_SIGMOID) {
       x = FOLD ? fast_exp2(x) : fast_exp2(__builtin_fmaf(x, -p.c, -p.b2));
     } else if constexpr (C::MOD == MOD_DECAY) {
@@ -382,7 +391,7 @@ template <class C>
 __device__ __forceinline__ void post_done(const Params& p, const RowState<C>& st, float mx, bool& moved, float& xm) {
   if constexpr (C::NORM == NORM_SOFTMAX) {
     mx = max_halves(mx);
-    xm = __builtin_fmaf(mx, p.c, p.b2);  // c > 0
+    xm = C::MOD == MOD_BIAS_T ? mx : __builtin_fmaf(mx, p.c, p.b2);  // c > 0
     moved = xm > st.m + kLazyLog2;
   }
 }
@@ -409,7 +418,11 @@ __device__ __forceinline__ void lazy_rescale(RowState<C>& st, bool moved, float 
 template <class C, bool FOLD = false>
 __device__ __forceinline__ uint32_t finish_pair(const Params& p, int q, const f32x16& s, float k0, float& acc) {
   float x0 = s[2 * q], x1 = s[2 * q + 1];
-  if constexpr (C::NORM == NORM_SOFTMAX) {
+  if constexpr (C::NORM == NORM_SOFTMAX && C::MOD == MOD_BIAS_T) {
+    x0 = fast_exp2(x0 + k0);
+    x1 = fast_exp2(x1 + k0);
+    acc += x0 + x1;
+  } else if constexpr (C::NORM == NORM_SOFTMAX) {
     x0 = fast_exp2(__builtin_fmaf(x0, p.c, k0));
     x1 = fast_exp2(__builtin_fmaf(x1, p.c, k0));
     // Row sum in fp32 with plain adds: v_dot2c_f32_bf16 on the packed weights would
@@ -432,7 +445,7 @@ __device__ __forceinline__ uint32_t finish_pair(const Params& p, int q, const f3
 // Softmax exponent offset for the current reference maximum.
 template <class C>
 __device__ __forceinline__ float finish_k0(const Params& p, const RowState<C>& st) {
-  if constexpr (C::NORM == NORM_SOFTMAX) return p.b2 - ((st.m == -INFINITY) ? 0.f : st.m);
+  if constexpr (C::NORM == NORM_SOFTMAX) return (C::MOD == MOD_BIAS_T ? 0.f : p.b2) - ((st.m == -INFINITY) ? 0.f : st.m);
   return 0.f;
 }
 template <class C>
@@ -574,6 +587,27 @@ struct KeyLoop {
   // register r, with the wave-uniform constants a8 = gamma^-8, b[k] = gamma^-k.
   bool fact;
   float a8, b1, b2, b3;
+  // Bias tensor: this lane's row of it, and the values of the sub-tile that starts at key bias_j0, requested one
+  // vector phase ahead (4 groups of 4 consecutive keys: registers 4a .. 4a+3 are keys j0 + 4*half + 8a ..)
+  const __bf16* brow = nullptr;
+  u32x2 bnext[4] = {};
+  int bias_j0 = -1;
+
+  __device__ __forceinline__ void load_bias(int j0, u32x2 (&dst)[4]) const {
+    const int half = (threadIdx.x & 63) >> 5;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int col = j0 + 4 * half + 8 * a;
+      if (col + 3 < p.L_k) {
+        dst[a] = *reinterpret_cast<const u32x2*>(brow + col);
+      } else {  // the ragged end of the row, element by element
+        uint32_t v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = col + e < p.L_k ? (uint32_t) * reinterpret_cast<const uint16_t*>(brow + col + e) : 0u;
+        dst[a] = u32x2{v[0] | (v[1] << 16), v[2] | (v[3] << 16)};
+      }
+    }
+  }
 
   // Issues the LDS read that feeds MFMA n.  Reads are issued in MFMA order, so
   // the fragment addresses are advanced to the next buffer exactly where the
@@ -612,6 +646,19 @@ struct KeyLoop {
     float mx = -INFINITY, xm = 0.f, acc = 0.f;
     bool moved = false;
     const bool fold = C::NORM == NORM_SIGMOID && p.fold;  // wave-uniform
+    u32x2 bcur[4] = {};
+    if constexpr (C::MOD == MOD_BIAS_T) {
+      if (bias_j0 == j0) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a) bcur[a] = bnext[a];
+      } else {
+        load_bias(j0, bcur);
+      }
+      if (j0 + C::SUB_N < p.L_k) {  // the sub-tile after this one, for the next vector phase
+        load_bias(j0 + C::SUB_N, bnext);
+        bias_j0 = j0 + C::SUB_N;
+      }
+    }
     if (masked) mask_raw<C>(s, jlim, fold ? INFINITY : -INFINITY);
     if (masked_lo) mask_raw_below<C>(s, jlo, fold ? INFINITY : -INFINITY);
     if (C::MOD == MOD_DECAY && fact) {
@@ -630,7 +677,7 @@ struct KeyLoop {
       for (int q = 0; q < 8; ++q) post_pair<C, true>(p, q, s, dbase, g2, mx);
     } else {
 #pragma unroll
-      for (int q = 0; q < 8; ++q) post_pair<C, false>(p, q, s, dbase, g2, mx);
+      for (int q = 0; q < 8; ++q) post_pair<C, false>(p, q, s, dbase, g2, mx, bcur[q / 2][q % 2]);
     }
     if (masked) mask_modified<C>(s, jlim);
     if (masked_lo) mask_modified_below<C>(s, jlo);
@@ -924,6 +971,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   if (n_walk > 0) {
     bf16x8 ring[C::PF];
     KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2, false, 1.f, 1.f, 1.f, 1.f};
+    if constexpr (C::MOD == MOD_BIAS_T) kl.brow = p.bias + b * p.bs[0] + hq * p.bs[1] + (int64_t)(i < p.L_q ? i : p.L_q - 1) * p.bs[2];
     if constexpr (C::MOD == MOD_DECAY) {
       kl.fact = g2 <= 0.f && g2 >= -4.f;  // per head, hence uniform over the workgroup
       kl.a8 = fast_exp2(-8.f * g2);

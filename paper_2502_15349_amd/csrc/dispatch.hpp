@@ -54,6 +54,16 @@ constexpr KernelEntry make_entry(const char* name) {
   AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_PLAIN, 2, SHAPE_C),         \
   AE_ENTRY(DQK, DV, NORM_NONE, MOD_PLAIN, 2, SHAPE_C)
 
+// The additive bias tensor (softmax, sigmoid, no normalization; unmasked and causal), for the head
+// dims whose kernels have registers to spare for the prefetched bias values.
+#define AE_ENTRIES_BIAS_TENSOR(DQK, DV, SHAPE_NC, SHAPE_C)        \
+  AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_BIAS_T, false, SHAPE_NC),   \
+  AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_BIAS_T, false, SHAPE_NC),   \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_BIAS_T, false, SHAPE_NC),      \
+  AE_ENTRY(DQK, DV, NORM_SOFTMAX, MOD_BIAS_T, true, SHAPE_C),     \
+  AE_ENTRY(DQK, DV, NORM_SIGMOID, MOD_BIAS_T, true, SHAPE_C),     \
+  AE_ENTRY(DQK, DV, NORM_NONE, MOD_BIAS_T, true, SHAPE_C)
+
 const KernelEntry* table_64_64(int* n);
 const KernelEntry* table_128_128(int* n);
 const KernelEntry* table_128_256(int* n);

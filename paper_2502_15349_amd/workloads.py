@@ -138,3 +138,13 @@ def make_grad(w: Workload, seed_base: Optional[int] = None):
     g = torch.Generator(device="cpu")
     g.manual_seed(base + 7)
     return torch.randn((w.B, w.H_q, w.L_q, w.D_v), generator=g, dtype=torch.float32).to(torch.bfloat16).contiguous()
+
+
+def make_bias_tensor(w: Workload, per_batch: bool = True, per_head: bool = True, seed_base: Optional[int] = None):
+    """Additive bias for score_mod "bias_tensor": a contiguous CPU bf16 tensor [B or 1, H_q or 1, L_q, L_k], standard
+    normal, from a seed of its own."""
+    base = 1000 * w.config_id if seed_base is None else seed_base
+    g = torch.Generator(device="cpu")
+    g.manual_seed(base + 11)
+    shape = (w.B if per_batch else 1, w.H_q if per_head else 1, w.L_q, w.L_k)
+    return torch.randn(shape, generator=g, dtype=torch.float32).to(torch.bfloat16).contiguous()

@@ -478,3 +478,54 @@ def test_decay_rates_outside_the_factorised_range(A):
         ref = oracle_attention(Q, K, V, scale=scale, score_mod="head_decay", gamma=gam, norm=norm, mask="causal")
         rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
         check(O.cpu().double().numpy() / rs, ref / rs, f"decay gammas {gam} norm {norm}")
+
+
+@pytest.mark.parametrize("dims", [(64, 64), (128, 128), (192, 128)], ids=lambda d: f"d{d[0]}_{d[1]}")
+@pytest.mark.parametrize("norm", ["softmax", "sigmoid", "none"])
+@pytest.mark.parametrize("mask", ["none", "causal"])
+def test_bias_tensor(A, dims, norm, mask):
+    """score_mod "bias_tensor": an additive bf16 bias per (query, key) pair, per batch and head, shared over the
+    batch, or over batch and heads; ragged sizes (L_k = 333 is no multiple of 4: the row ends are read element by
+    element), grouped heads; softmax also returns the row statistic."""
+    from oracle import row_stats_head
+    from paper_2502_15349_amd.workloads import make_bias_tensor
+    dev = torch.device("cuda:0")
+    w = Workload(f"bias_t_{norm}_{mask}", 60, 2, 4, 2, 300, 333, dims[0], dims[1], score_mod="bias_tensor", norm=norm, mask=mask,
+                 scale=(0.01 if norm == "none" else None))
+    Q, K, V = make_inputs(w)
+    for per_batch, per_head in ((True, True), (False, True), (False, False)):
+        bt = make_bias_tensor(w, per_batch, per_head)
+        if norm == "none":
+            bt = (bt.float() * 0.01).to(torch.bfloat16)
+        print(f"case {w.name} dims {dims} bias shape {tuple(bt.shape)}", flush=True)
+        stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev) if norm == "softmax" else None
+        # rows of the device copy start at multiples of 4 elements (the row stride the library asks for)
+        btd = torch.zeros(bt.shape[:3] + (336,), dtype=torch.bfloat16, device=dev)
+        btd[..., :w.L_k] = bt.to(dev)
+        O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), stats=stats, bias_tensor=btd[..., :w.L_k])
+        torch.cuda.synchronize()
+        ref = attention(Q, K, V, scale=w.scale_value, score_mod="bias_tensor", norm=norm, mask=mask, bias_tensor=bt)
+        # (sigmoid and no normalization: outputs are not O(1); judged relative to the row scale as elsewhere)
+        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+        check(O.cpu().double().numpy() / rs, ref / rs, f"bias tensor {norm} {mask} {tuple(bt.shape)}")
+        if stats is not None:
+            b, h = 1, 3
+            want = row_stats_head(Q[b, h], K[b, h // 2], scale=w.scale_value, score_mod="bias_tensor", mask=mask,
+                                  bias_t=bt[b if per_batch else 0, h if per_head else 0])
+            np.testing.assert_allclose(stats[b, h].cpu().double().numpy(), want, atol=2e-3)
+
+
+def test_bias_tensor_alibi_and_padded_rows(A):
+    """A structured bias (ALiBi: -slope_h * distance) on a longer causal problem, stored with padded rows."""
+    dev = torch.device("cuda:0")
+    w = Workload("alibi", 61, 1, 4, 4, 1000, 1000, 128, 128, score_mod="bias_tensor", mask="causal")
+    Q, K, V = make_inputs(w)
+    dist = (torch.arange(w.L_q)[:, None] - torch.arange(w.L_k)[None, :]).clamp(min=0).float()
+    slopes = torch.tensor([2.0 ** (-2 * (h + 1)) for h in range(w.H_q)])
+    bt = (-slopes[None, :, None, None] * dist[None, None]).to(torch.bfloat16)
+    padded = torch.zeros((1, w.H_q, w.L_q, 1024), dtype=torch.bfloat16, device=dev)
+    padded[..., :w.L_k] = bt.to(dev)
+    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), bias_tensor=padded[..., :w.L_k])
+    torch.cuda.synchronize()
+    ref = attention(Q, K, V, scale=w.scale_value, score_mod="bias_tensor", mask="causal", bias_tensor=bt)
+    check(O.cpu().double().numpy(), ref, "alibi")
