@@ -116,7 +116,7 @@ typedef struct {
                           dimension contiguous).  All zero: contiguous.  A batch
                           or head stride of 0 beside a non-zero row stride shares
                           the tensor over that dimension.  The row stride must be
-                          >= L_k and a multiple of 4.                           */
+                          >= L_k, every stride a multiple of 8.                 */
 } ae_attn_desc_t;
 
 /* Validates the descriptor, picks the kernel and its tile shape for
@@ -156,7 +156,7 @@ ae_status_t ae_attn_forward_stats(const ae_attn_t *h, const void *Q,
                                   void *stats, void *stream);
 
 /* Forward for a handle created with AE_MOD_BIAS_TENSOR: ae_attn_forward with the
- * additive bias tensor (device, bf16, 8-byte aligned, laid out as
+ * additive bias tensor (device, bf16, 16-byte aligned, laid out as
  * desc.bias_stride says, read only) and optionally the row statistic (stats may be
  * NULL; see ae_attn_forward_stats).  One kernel, nothing allocated.  Errors as
  * ae_attn_forward; AE_ERR_INVALID_ARG for a handle of another score_mod.        */

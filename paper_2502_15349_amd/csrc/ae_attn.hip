@@ -177,9 +177,9 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   fill_strides(p.vs, d->v_stride, d->H_kv, d->L_k, d->D_v);
   fill_strides(p.os, d->o_stride, d->H_q, d->L_q, d->D_v);
   fill_strides(p.bs, d->bias_stride, d->H_q, d->L_q, d->L_k);
-  if (mod == ae::MOD_BIAS_T && (p.bs[0] < 0 || p.bs[1] < 0 || p.bs[2] < d->L_k || p.bs[2] % 4 != 0 || p.bs[0] % 4 != 0 || p.bs[1] % 4 != 0)) {
+  if (mod == ae::MOD_BIAS_T && (p.bs[0] < 0 || p.bs[1] < 0 || p.bs[2] < d->L_k || p.bs[2] % 8 != 0 || p.bs[0] % 8 != 0 || p.bs[1] % 8 != 0)) {
     delete h;
-    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: bias strides must be non-negative multiples of 4 elements, the row stride >= L_k");
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_create: bias strides must be non-negative multiples of 8 elements, the row stride >= L_k");
   }
   const int64_t* in_strides[3] = {p.qs, p.ks, p.vs};
   const int in_d[3] = {d->D_qk, d->D_qk, d->D_v};
@@ -290,7 +290,7 @@ static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K
   if ((h->kernel->mod == ae::MOD_BIAS_T) != (bias != nullptr))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: a handle with AE_MOD_BIAS_TENSOR, and only such a handle, runs through "
                                     "ae_attn_forward_bias with its bias tensor");
-  if (bias && (((uintptr_t)bias & 7) || bias == O)) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_bias: the bias tensor must be 8-byte aligned and must not alias O");
+  if (bias && (((uintptr_t)bias & 15) || bias == O)) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_bias: the bias tensor must be 16-byte aligned and must not alias O");
   ae::Params p = h->params;
   p.bias = static_cast<const __bf16*>(bias);
   p.Q = static_cast<const __bf16*>(Q);

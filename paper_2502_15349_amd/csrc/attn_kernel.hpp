@@ -122,7 +122,9 @@ struct Cfg {
   static constexpr int STAGE_BYTES = K_BYTES + V_BYTES, Q_BYTES = WAVES * 32 * RB_K;
   static constexpr int TILE_BYTES = STAGES * STAGE_BYTES, OUT_BYTES = WAVES * 32 * OC * 4;
   static constexpr int cmax(int a, int b) { return a > b ? a : b; }
-  static constexpr int LDS_BYTES = cmax(TILE_BYTES, cmax(OUT_BYTES, STAGE_BYTES + Q_BYTES));
+  // (bias tensor: 2 KB per wave behind the stages, see KeyLoop::turn_bias)
+  static constexpr int BIAS_BYTES = MOD_ == MOD_BIAS_T ? WAVES * 2048 : 0;
+  static constexpr int LDS_BYTES = cmax(TILE_BYTES + BIAS_BYTES, cmax(OUT_BYTES, STAGE_BYTES + Q_BYTES));
   static constexpr int NB_K = K_BYTES / 1024, NB_V = V_BYTES / 1024;  // 1 KB blocks per tile
   static constexpr int KI = (NB_K + WAVES - 1) / WAVES, VI = (NB_V + WAVES - 1) / WAVES;
   static constexpr int T = DQK / 16;  // contraction steps of the scoring MFMA
@@ -587,26 +589,47 @@ struct KeyLoop {
   // register r, with the wave-uniform constants a8 = gamma^-8, b[k] = gamma^-k.
   bool fact;
   float a8, b1, b2, b3;
-  // Bias tensor: this lane's row of it, and the values of the sub-tile that starts at key bias_j0, requested one
-  // vector phase ahead (4 groups of 4 consecutive keys: registers 4a .. 4a+3 are keys j0 + 4*half + 8a ..)
-  const __bf16* brow = nullptr;
-  u32x2 bnext[4] = {};
+  // Bias tensor.  A lane needs 16 values of its own query row per sub-tile, but loads shaped like that
+  // touch 32 rows per instruction and the CU's memory pipe takes ~60 clk for each.  Instead the wave
+  // fetches its 32 rows x 32 keys as two coalesced loads (lane l: row 16t + l/4, keys 8*(l%4) ..+7,
+  // 16 bytes; 16 rows per instruction), one vector phase ahead, and turns them around through 2 KB
+  // of LDS of its own: write 16 bytes per lane, read back 4 x 8 bytes of the own row.  LDS slot of
+  // the 16-byte chunk c of row r: c ^ ((r >> 2) & 3) (16 lanes write 4 whole rows; 16 lanes read 16
+  // different slots).  The row ends (L_k no multiple of 8) are fetched element by element.
+  const __bf16* bwave = nullptr;  // bias of this (batch, q head)
+  int64_t brow16[2] = {0, 0};     // element offset of row iw0 + 16t + lane/4 (clamped), t = 0, 1
+  uint32_t bscr = 0;              // LDS address of the wave's 2 KB
+  u32x4 bnext[2] = {};
   int bias_j0 = -1;
 
-  __device__ __forceinline__ void load_bias(int j0, u32x2 (&dst)[4]) const {
-    const int half = (threadIdx.x & 63) >> 5;
+  __device__ __forceinline__ void load_bias(int j0, u32x4 (&dst)[2]) const {
+    const int col = j0 + 8 * (int)(threadIdx.x & 3);
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      const int col = j0 + 4 * half + 8 * a;
-      if (col + 3 < p.L_k) {
-        dst[a] = *reinterpret_cast<const u32x2*>(brow + col);
+    for (int t = 0; t < 2; ++t) {
+      const __bf16* src = bwave + brow16[t] + col;
+      if (col + 7 < p.L_k) {
+        dst[t] = *reinterpret_cast<const u32x4*>(src);
       } else {  // the ragged end of the row, element by element
-        uint32_t v[4];
+        uint32_t v[8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = col + e < p.L_k ? (uint32_t) * reinterpret_cast<const uint16_t*>(brow + col + e) : 0u;
-        dst[a] = u32x2{v[0] | (v[1] << 16), v[2] | (v[3] << 16)};
+        for (int e = 0; e < 8; ++e) v[e] = col + e < p.L_k ? (uint32_t) * reinterpret_cast<const uint16_t*>(src + e) : 0u;
+        dst[t] = u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
       }
     }
+  }
+  // The wave's 32 x 32 bias values from registers (load_bias layout) to the lanes that own the rows:
+  // dst[a] = keys 4*half + 8a .. +3 of row lane % 32.
+  __device__ __forceinline__ void turn_bias(const u32x4 (&src)[2], u32x2 (&dst)[4]) const {
+    const int lane = threadIdx.x & 63, half = lane >> 5, ql = lane & 31;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int r = 16 * t + (lane >> 2);
+      *reinterpret_cast<__attribute__((address_space(3))) u32x4*>((lds_char*)(uintptr_t)(bscr + r * 64 + (((lane & 3) ^ ((r >> 2) & 3)) << 4))) = src[t];
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+      dst[a] = *reinterpret_cast<__attribute__((address_space(3))) const u32x2*>(
+          (lds_char*)(uintptr_t)(bscr + ql * 64 + ((a ^ ((ql >> 2) & 3)) << 4) + 8 * half));
   }
 
   // Issues the LDS read that feeds MFMA n.  Reads are issued in MFMA order, so
@@ -648,12 +671,8 @@ struct KeyLoop {
     const bool fold = C::NORM == NORM_SIGMOID && p.fold;  // wave-uniform
     u32x2 bcur[4] = {};
     if constexpr (C::MOD == MOD_BIAS_T) {
-      if (bias_j0 == j0) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a) bcur[a] = bnext[a];
-      } else {
-        load_bias(j0, bcur);
-      }
+      if (bias_j0 != j0) load_bias(j0, bnext);  // (only the first sub-tile of a walk comes without a request ahead)
+      turn_bias(bnext, bcur);
       if (j0 + C::SUB_N < p.L_k) {  // the sub-tile after this one, for the next vector phase
         load_bias(j0 + C::SUB_N, bnext);
         bias_j0 = j0 + C::SUB_N;
@@ -971,7 +990,15 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   if (n_walk > 0) {
     bf16x8 ring[C::PF];
     KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2, false, 1.f, 1.f, 1.f, 1.f};
-    if constexpr (C::MOD == MOD_BIAS_T) kl.brow = p.bias + b * p.bs[0] + hq * p.bs[1] + (int64_t)(i < p.L_q ? i : p.L_q - 1) * p.bs[2];
+    if constexpr (C::MOD == MOD_BIAS_T) {
+      kl.bwave = p.bias + b * p.bs[0] + hq * p.bs[1];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int r = iw0 + 16 * t + (lane >> 2);
+        kl.brow16[t] = (int64_t)(r < p.L_q ? r : p.L_q - 1) * p.bs[2];
+      }
+      kl.bscr = lds0 + C::TILE_BYTES + wave * 2048;  // behind the K/V stages
+    }
     if constexpr (C::MOD == MOD_DECAY) {
       kl.fact = g2 <= 0.f && g2 >= -4.f;  // per head, hence uniform over the workgroup
       kl.a8 = fast_exp2(-8.f * g2);

@@ -199,7 +199,7 @@ def test_backward_rejects_bad_arguments_without_launching():
                         (dict(norm="none", score_mod="relu"), None),
                         (dict(norm="abssum", score_mod="head_decay", mask="causal", gamma=[.9] * 4), "ws"),
                         (dict(norm="none", score_mod="head_decay", mask="causal", gamma=[.9] * 4), None),
-                        (dict(score_mod="bias_tensor"), A.AE_ERR_UNSUPPORTED),
+                        (dict(score_mod="bias_tensor", bias_stride=(0, 0, 104)), A.AE_ERR_UNSUPPORTED),
                         (dict(mask="sliding_window", window=8), "ws")):
         dd = _ok_desc()
         dd.update(patch)
@@ -220,13 +220,13 @@ def test_backward_rejects_bad_arguments_without_launching():
 def test_bias_tensor_descriptor_and_entry_point_checks():
     from paper_2502_15349_amd import ae_attn as A
     d = _ok_desc()
-    d.update(score_mod="bias_tensor")
+    d.update(score_mod="bias_tensor", bias_stride=(0, 0, 104))    # L_k = 100: rows padded to a multiple of 8
     h = A.ae_attn_create(**d)
     try:
         with pytest.raises(A.AeAttnError) as ei:      # needs its own entry point
             A.ae_attn_forward(h, 256, 512, 768, 1024)
         assert ei.value.status == A.AE_ERR_INVALID_ARG
-        for args in ((256, 512, 768, 0, 1024), (256, 512, 768, 2052, 1024), (256, 512, 768, 1024, 1024)):   # null, misaligned, aliasing O
+        for args in ((256, 512, 768, 0, 1024), (256, 512, 768, 2056, 1024), (256, 512, 768, 1024, 1024)):   # null, misaligned, aliasing O
             with pytest.raises(A.AeAttnError) as ei:
                 A.ae_attn_forward_bias(h, *args)
             assert ei.value.status == A.AE_ERR_INVALID_ARG
@@ -242,9 +242,9 @@ def test_bias_tensor_descriptor_and_entry_point_checks():
     for patch, status in ((dict(norm="abssum"), A.AE_ERR_UNSUPPORTED), (dict(mask="sliding_window", window=4), A.AE_ERR_UNSUPPORTED),
                           (dict(kv_splits=4), A.AE_ERR_UNSUPPORTED), (dict(D_v=256), A.AE_ERR_UNSUPPORTED),
                           (dict(bias_stride=(0, 0, 96)), A.AE_ERR_INVALID_ARG),      # row stride < L_k
-                          (dict(bias_stride=(0, 0, 102)), A.AE_ERR_INVALID_ARG)):    # not a multiple of 4
+                          (dict(bias_stride=(0, 0, 100)), A.AE_ERR_INVALID_ARG)):    # not a multiple of 8
         dd = _ok_desc()
-        dd.update(score_mod="bias_tensor")
+        dd.update(score_mod="bias_tensor", bias_stride=(0, 0, 104))
         dd.update(patch)
         with pytest.raises(A.AeAttnError) as ei:
             A.ae_attn_create(**dd)

@@ -499,7 +499,7 @@ def test_bias_tensor(A, dims, norm, mask):
             bt = (bt.float() * 0.01).to(torch.bfloat16)
         print(f"case {w.name} dims {dims} bias shape {tuple(bt.shape)}", flush=True)
         stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev) if norm == "softmax" else None
-        # rows of the device copy start at multiples of 4 elements (the row stride the library asks for)
+        # rows of the device copy start at multiples of 8 elements (the row stride the library asks for)
         btd = torch.zeros(bt.shape[:3] + (336,), dtype=torch.bfloat16, device=dev)
         btd[..., :w.L_k] = bt.to(dev)
         O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), stats=stats, bias_tensor=btd[..., :w.L_k])
