@@ -601,6 +601,22 @@ struct KeyLoop {
   uint32_t bscr = 0;              // LDS address of the wave's 2 KB
   u32x4 bnext[2] = {};
   int bias_j0 = -1;
+  u32x2 bcur[4] = {};  // the sub-tile at hand, per lane (see turn_bias)
+
+  // The sub-tile's bias values to the lanes (fetching them now if they were not requested ahead: only the
+  // first sub-tile of a walk).  Called before the tile copies of the phase are issued: the wait for the
+  // requested values is a wait for everything in flight, and the copies are meant to stay in flight.
+  __device__ __forceinline__ void take_bias(int j0) {
+    if (bias_j0 != j0) load_bias(j0, bnext);
+    turn_bias(bnext, bcur);
+  }
+  // Requests the sub-tile after j0 for the next vector phase.
+  __device__ __forceinline__ void request_bias(int j0) {
+    if (j0 + C::SUB_N < p.L_k) {
+      load_bias(j0 + C::SUB_N, bnext);
+      bias_j0 = j0 + C::SUB_N;
+    }
+  }
 
   __device__ __forceinline__ void load_bias(int j0, u32x4 (&dst)[2]) const {
     const int col = j0 + 8 * (int)(threadIdx.x & 3);
@@ -669,15 +685,6 @@ struct KeyLoop {
     float mx = -INFINITY, xm = 0.f, acc = 0.f;
     bool moved = false;
     const bool fold = C::NORM == NORM_SIGMOID && p.fold;  // wave-uniform
-    u32x2 bcur[4] = {};
-    if constexpr (C::MOD == MOD_BIAS_T) {
-      if (bias_j0 != j0) load_bias(j0, bnext);  // (only the first sub-tile of a walk comes without a request ahead)
-      turn_bias(bnext, bcur);
-      if (j0 + C::SUB_N < p.L_k) {  // the sub-tile after this one, for the next vector phase
-        load_bias(j0 + C::SUB_N, bnext);
-        bias_j0 = j0 + C::SUB_N;
-      }
-    }
     if (masked) mask_raw<C>(s, jlim, fold ? INFINITY : -INFINITY);
     if (masked_lo) mask_raw_below<C>(s, jlo, fold ? INFINITY : -INFINITY);
     if (C::MOD == MOD_DECAY && fact) {
@@ -1045,16 +1052,26 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       };
       // Where the copy of tile jt+2 is issued (see Cfg::kCopyInVector).
+      // Vector phase of sub-tile j0 with the copy slice that goes in front of it.  With a bias tensor the
+      // sub-tile's bias values are taken first, and the next ones requested behind the copies.
+      auto vector_with_copy = [&](bool vis, bool real, int j0, auto&& copy_fn) {
+        if constexpr (C::MOD == MOD_BIAS_T) {
+          if (vis && real) kl.take_bias(j0);
+          copy_fn();
+          if (vis && real) kl.request_bias(j0);
+        } else {
+          copy_fn();
+        }
+        if (vis) vector_or_zero(fastc, real, j0);
+      };
       if constexpr (C::kCopyInVector) {
         using Part = std::integral_constant<int, -1>;  // 0: the K tile, 1: the V tile
-        copy(Part{}, Zero{});
-        if (vis0) vector_or_zero(fastc, real0, u * C::SUB_N);
+        vector_with_copy(vis0, real0, u * C::SUB_N, [&] { copy(Part{}, Zero{}); });
         phase_barrier();
         if (vis0) kl.template matrix_phase<0>(s_a, sc0, [] {});
         await_next_tile(std::integral_constant<int, C::KI>{});
         phase_barrier();
-        copy(Part{}, One{});
-        if (vis1) vector_or_zero(fastc, real1, (u + 1) * C::SUB_N);
+        vector_with_copy(vis1, real1, (u + 1) * C::SUB_N, [&] { copy(Part{}, One{}); });
         phase_barrier();
         if (vis1) kl.template matrix_phase<1>(s_a, sc1, [] {});
         phase_barrier();
@@ -1062,7 +1079,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
         using Two = std::integral_constant<int, 2>;
         using Three = std::integral_constant<int, 3>;
         constexpr int kSlice0 = (kCopies + 2) / 3;  // instructions in slice 0
-        if (vis0) vector_or_zero(fastc, real0, u * C::SUB_N);
+        vector_with_copy(vis0, real0, u * C::SUB_N, [] {});
         phase_barrier();
         if (vis0)
           kl.template matrix_phase<0>(s_a, sc0, [&] { copy(Three{}, Zero{}); });
@@ -1070,8 +1087,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
           copy(Three{}, Zero{});
         await_next_tile(std::integral_constant<int, kSlice0>{});
         phase_barrier();
-        copy(Three{}, One{});
-        if (vis1) vector_or_zero(fastc, real1, (u + 1) * C::SUB_N);
+        vector_with_copy(vis1, real1, (u + 1) * C::SUB_N, [&] { copy(Three{}, One{}); });
         phase_barrier();
         if (vis1)
           kl.template matrix_phase<1>(s_a, sc1, [&] { copy(Three{}, Two{}); });
