@@ -116,7 +116,9 @@ typedef struct {
                           dimension contiguous).  All zero: contiguous.  A batch
                           or head stride of 0 beside a non-zero row stride shares
                           the tensor over that dimension.  The row stride must be
-                          >= L_k, every stride a multiple of 8.                 */
+                          >= L_k, every stride a multiple of 8; rows are read in
+                          pieces of 8 elements, so the last row must be backed by
+                          memory up to the next multiple of 8 as well.          */
 } ae_attn_desc_t;
 
 /* Validates the descriptor, picks the kernel and its tile shape for

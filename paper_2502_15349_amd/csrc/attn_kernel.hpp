@@ -122,8 +122,8 @@ struct Cfg {
   static constexpr int STAGE_BYTES = K_BYTES + V_BYTES, Q_BYTES = WAVES * 32 * RB_K;
   static constexpr int TILE_BYTES = STAGES * STAGE_BYTES, OUT_BYTES = WAVES * 32 * OC * 4;
   static constexpr int cmax(int a, int b) { return a > b ? a : b; }
-  // (bias tensor: 2 KB per wave behind the stages, see KeyLoop::turn_bias)
-  static constexpr int BIAS_BYTES = MOD_ == MOD_BIAS_T ? WAVES * 2048 : 0;
+  // (bias tensor: two buffers of 2 KB per wave behind the stages, see KeyLoop::copy_bias)
+  static constexpr int BIAS_BYTES = MOD_ == MOD_BIAS_T ? WAVES * 4096 : 0;
   static constexpr int LDS_BYTES = cmax(TILE_BYTES + BIAS_BYTES, cmax(OUT_BYTES, STAGE_BYTES + Q_BYTES));
   static constexpr int NB_K = K_BYTES / 1024, NB_V = V_BYTES / 1024;  // 1 KB blocks per tile
   static constexpr int KI = (NB_K + WAVES - 1) / WAVES, VI = (NB_V + WAVES - 1) / WAVES;
@@ -591,61 +591,67 @@ struct KeyLoop {
   float a8, b1, b2, b3;
   // Bias tensor.  A lane needs 16 values of its own query row per sub-tile, but loads shaped like that
   // touch 32 rows per instruction and the CU's memory pipe takes ~60 clk for each.  Instead the wave
-  // fetches its 32 rows x 32 keys as two coalesced loads (lane l: row 16t + l/4, keys 8*(l%4) ..+7,
-  // 16 bytes; 16 rows per instruction), one vector phase ahead, and turns them around through 2 KB
-  // of LDS of its own: write 16 bytes per lane, read back 4 x 8 bytes of the own row.  LDS slot of
-  // the 16-byte chunk c of row r: c ^ ((r >> 2) & 3) (16 lanes write 4 whole rows; 16 lanes read 16
-  // different slots).  The row ends (L_k no multiple of 8) are fetched element by element.
+  // copies its 32 rows x 32 keys into 2 KB of LDS of its own with two LDS-DMA instructions (16 rows x
+  // 64 bytes each, like a K/V copy: no registers, no compiler-tracked load), one vector phase ahead
+  // and into one of two buffers, and each lane reads back 4 x 8 bytes of its own row.  LDS slot of
+  // the 16-byte chunk c of row r: c ^ ((r >> 2) & 3), applied to the global address when copying
+  // (16 lanes read 16 different slots).  Chunks that start beyond the last key are redirected to the
+  // row's last chunk (their values belong to hidden keys); rows are padded to 8 elements by contract.
+  // The copy is awaited with an exact count: `bias_newer` = the tile-copy instructions issued behind
+  // it, which may stay in flight.
   const __bf16* bwave = nullptr;  // bias of this (batch, q head)
-  int64_t brow16[2] = {0, 0};     // element offset of row iw0 + 16t + lane/4 (clamped), t = 0, 1
-  uint32_t bscr = 0;              // LDS address of the wave's 2 KB
-  u32x4 bnext[2] = {};
-  int bias_j0 = -1;
-  u32x2 bcur[4] = {};  // the sub-tile at hand, per lane (see turn_bias)
+  uint32_t bgoff[2] = {0, 0};     // byte offset of row iw0 + 16t + lane/4 (clamped), t = 0, 1
+  uint32_t bscr = 0;              // LDS address of the wave's 2 x 2 KB
+  int bias_j0 = -1;               // sub-tile whose copy was requested last
+  int bias_newer = 0;
+  u32x2 bcur[4] = {};             // the sub-tile at hand, per lane
 
-  // The sub-tile's bias values to the lanes (fetching them now if they were not requested ahead: only the
-  // first sub-tile of a walk).  Called before the tile copies of the phase are issued: the wait for the
-  // requested values is a wait for everything in flight, and the copies are meant to stay in flight.
-  __device__ __forceinline__ void take_bias(int j0) {
-    if (bias_j0 != j0) load_bias(j0, bnext);
-    turn_bias(bnext, bcur);
-  }
-  // Requests the sub-tile after j0 for the next vector phase.
-  __device__ __forceinline__ void request_bias(int j0) {
-    if (j0 + C::SUB_N < p.L_k) {
-      load_bias(j0 + C::SUB_N, bnext);
-      bias_j0 = j0 + C::SUB_N;
-    }
-  }
-
-  __device__ __forceinline__ void load_bias(int j0, u32x4 (&dst)[2]) const {
-    const int col = j0 + 8 * (int)(threadIdx.x & 3);
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const __bf16* src = bwave + brow16[t] + col;
-      if (col + 7 < p.L_k) {
-        dst[t] = *reinterpret_cast<const u32x4*>(src);
-      } else {  // the ragged end of the row, element by element
-        uint32_t v[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = col + e < p.L_k ? (uint32_t) * reinterpret_cast<const uint16_t*>(src + e) : 0u;
-        dst[t] = u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
-      }
-    }
-  }
-  // The wave's 32 x 32 bias values from registers (load_bias layout) to the lanes that own the rows:
-  // dst[a] = keys 4*half + 8a .. +3 of row lane % 32.
-  __device__ __forceinline__ void turn_bias(const u32x4 (&src)[2], u32x2 (&dst)[4]) const {
-    const int lane = threadIdx.x & 63, half = lane >> 5, ql = lane & 31;
+  __device__ __forceinline__ void copy_bias(int j0) const {
+    const int lane = threadIdx.x & 63;
+    const uint32_t dst = bscr + ((j0 / C::SUB_N) & 1) * 2048;
+    const int last = ((p.L_k - 1) >> 3) << 3;  // first key of the row's last chunk
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int r = 16 * t + (lane >> 2);
-      *reinterpret_cast<__attribute__((address_space(3))) u32x4*>((lds_char*)(uintptr_t)(bscr + r * 64 + (((lane & 3) ^ ((r >> 2) & 3)) << 4))) = src[t];
+      int col = j0 + 8 * ((lane & 3) ^ ((r >> 2) & 3));
+      col = col < p.L_k ? col : last;
+      dma16(bwave, bgoff[t] + 2u * (uint32_t)col, dst + t * 1024);
     }
+  }
+  static __device__ __forceinline__ void wait_vm(int newer) {
+    switch (newer) {
+      case 1: asm volatile("s_waitcnt vmcnt(1)" ::: "memory"); break;
+      case 2: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
+      case 3: asm volatile("s_waitcnt vmcnt(3)" ::: "memory"); break;
+      case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+      case 5: asm volatile("s_waitcnt vmcnt(5)" ::: "memory"); break;
+      case 6: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
+      default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;  // 0, or more than listed: wait for all
+    }
+  }
+  // The sub-tile's bias values to the lanes.  If its copy was not requested ahead (the first sub-tile of
+  // a walk, or a wave that sat out the phase before) it is made and fully awaited here.
+  __device__ __forceinline__ void take_bias(int j0) {
+    if (bias_j0 == j0) {
+      wait_vm(bias_newer);
+    } else {
+      copy_bias(j0);
+      wait_vm(0);
+    }
+    const int lane = threadIdx.x & 63, half = lane >> 5, ql = lane & 31;
+    const uint32_t src = bscr + ((j0 / C::SUB_N) & 1) * 2048 + ql * 64 + 8 * half;
 #pragma unroll
     for (int a = 0; a < 4; ++a)
-      dst[a] = *reinterpret_cast<__attribute__((address_space(3))) const u32x2*>(
-          (lds_char*)(uintptr_t)(bscr + ql * 64 + ((a ^ ((ql >> 2) & 3)) << 4) + 8 * half));
+      bcur[a] = *reinterpret_cast<__attribute__((address_space(3))) const u32x2*>((lds_char*)(uintptr_t)(src + ((a ^ ((ql >> 2) & 3)) << 4)));
+  }
+  // Requests the sub-tile after j0 for the next vector phase; `newer`: the tile-copy instructions that
+  // this wave issues between here and that phase.
+  __device__ __forceinline__ void request_bias(int j0, int newer) {
+    if (j0 + C::SUB_N < p.L_k) {
+      copy_bias(j0 + C::SUB_N);
+      bias_j0 = j0 + C::SUB_N;
+      bias_newer = newer;
+    }
   }
 
   // Issues the LDS read that feeds MFMA n.  Reads are issued in MFMA order, so
@@ -1002,9 +1008,9 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int r = iw0 + 16 * t + (lane >> 2);
-        kl.brow16[t] = (int64_t)(r < p.L_q ? r : p.L_q - 1) * p.bs[2];
+        kl.bgoff[t] = (uint32_t)((int64_t)(r < p.L_q ? r : p.L_q - 1) * p.bs[2] * 2);
       }
-      kl.bscr = lds0 + C::TILE_BYTES + wave * 2048;  // behind the K/V stages
+      kl.bscr = lds0 + C::TILE_BYTES + wave * 4096;  // behind the K/V stages
     }
     if constexpr (C::MOD == MOD_DECAY) {
       kl.fact = g2 <= 0.f && g2 >= -4.f;  // per head, hence uniform over the workgroup
@@ -1053,12 +1059,15 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       };
       // Where the copy of tile jt+2 is issued (see Cfg::kCopyInVector).
       // Vector phase of sub-tile j0 with the copy slice that goes in front of it.  With a bias tensor the
-      // sub-tile's bias values are taken first, and the next ones requested behind the copies.
-      auto vector_with_copy = [&](bool vis, bool real, int j0, auto&& copy_fn) {
+      // sub-tile's bias values are taken first and the next ones requested, ahead of the slice: `newer` copy
+      // instructions follow the request before the next vector phase and may stay in flight then.
+      auto vector_with_copy = [&](bool vis, bool real, int j0, int newer, auto&& copy_fn) {
         if constexpr (C::MOD == MOD_BIAS_T) {
-          if (vis && real) kl.take_bias(j0);
+          if (vis && real) {
+            kl.take_bias(j0);
+            kl.request_bias(j0, more ? newer : 0);
+          }
           copy_fn();
-          if (vis && real) kl.request_bias(j0);
         } else {
           copy_fn();
         }
@@ -1066,12 +1075,12 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       };
       if constexpr (C::kCopyInVector) {
         using Part = std::integral_constant<int, -1>;  // 0: the K tile, 1: the V tile
-        vector_with_copy(vis0, real0, u * C::SUB_N, [&] { copy(Part{}, Zero{}); });
+        vector_with_copy(vis0, real0, u * C::SUB_N, C::KI, [&] { copy(Part{}, Zero{}); });
         phase_barrier();
         if (vis0) kl.template matrix_phase<0>(s_a, sc0, [] {});
         await_next_tile(std::integral_constant<int, C::KI>{});
         phase_barrier();
-        vector_with_copy(vis1, real1, (u + 1) * C::SUB_N, [&] { copy(Part{}, One{}); });
+        vector_with_copy(vis1, real1, (u + 1) * C::SUB_N, C::VI, [&] { copy(Part{}, One{}); });
         phase_barrier();
         if (vis1) kl.template matrix_phase<1>(s_a, sc1, [] {});
         phase_barrier();
@@ -1079,7 +1088,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
         using Two = std::integral_constant<int, 2>;
         using Three = std::integral_constant<int, 3>;
         constexpr int kSlice0 = (kCopies + 2) / 3;  // instructions in slice 0
-        vector_with_copy(vis0, real0, u * C::SUB_N, [] {});
+        vector_with_copy(vis0, real0, u * C::SUB_N, kSlice0, [] {});  // (slice 0 follows in the matrix phase)
         phase_barrier();
         if (vis0)
           kl.template matrix_phase<0>(s_a, sc0, [&] { copy(Three{}, Zero{}); });
@@ -1087,7 +1096,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
           copy(Three{}, Zero{});
         await_next_tile(std::integral_constant<int, kSlice0>{});
         phase_barrier();
-        vector_with_copy(vis1, real1, (u + 1) * C::SUB_N, [&] { copy(Three{}, One{}); });
+        vector_with_copy(vis1, real1, (u + 1) * C::SUB_N, kCopies - kSlice0, [&] { copy(Three{}, One{}); });
         phase_barrier();
         if (vis1)
           kl.template matrix_phase<1>(s_a, sc1, [&] { copy(Three{}, Two{}); });
