@@ -529,3 +529,18 @@ def test_bias_tensor_alibi_and_padded_rows(A):
     torch.cuda.synchronize()
     ref = attention(Q, K, V, scale=w.scale_value, score_mod="bias_tensor", mask="causal", bias_tensor=bt)
     check(O.cpu().double().numpy(), ref, "alibi")
+
+
+@pytest.mark.parametrize("Lq,Lk", [(1, 8), (5, 16), (40, 24), (64, 64), (100, 72), (257, 136), (33, 520)])
+@pytest.mark.parametrize("mask", ["none", "causal"])
+def test_bias_tensor_small_and_uneven_lengths(A, Lq, Lk, mask):
+    """Bias tensor on problems of one sub-tile, one tile, a few tiles; L_q != L_k in both directions."""
+    from paper_2502_15349_amd.workloads import make_bias_tensor
+    dev = torch.device("cuda:0")
+    w = Workload(f"bias_small_{Lq}x{Lk}_{mask}", 62, 2, 2, 1, Lq, Lk, 128, 128, score_mod="bias_tensor", mask=mask)
+    Q, K, V = make_inputs(w)
+    bt = make_bias_tensor(w)
+    O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), bias_tensor=bt.to(dev))
+    torch.cuda.synchronize()
+    ref = attention(Q, K, V, scale=w.scale_value, score_mod="bias_tensor", mask=mask, bias_tensor=bt)
+    check(O.cpu().double().numpy(), ref, f"bias tensor {Lq}x{Lk} {mask}")
