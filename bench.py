@@ -380,15 +380,52 @@ def main():
             ref = attention_head(Qc[b, hq], Kc[b, hq // (w.H_q // w.H_kv)], Vc[b, hq // (w.H_q // w.H_kv)], scale=w.scale_value,
                                  score_mod="bias_tensor", mask=w.mask, rows=rows_s, bias_t=bt[0, hq])
             err = float(np.abs(O[b, hq].cpu().double().numpy()[rows_s] - ref).max())
+            # the backward pass of the same two problems (dQ, dK, dV; the bias gets no gradient)
+            from paper_2502_15349_amd.workloads import make_grad
+            dO = make_grad(w).to(dev)
+            stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev)
+            grads = [torch.empty(x.shape, dtype=torch.float32, device=dev) for x in (Q, K, V)]
+            bres = {}
+            for name, ww in (("plain", base), ("bias_tensor", w)):
+                A.run_workload(ww, Q, K, V, out=O, stats=stats, bias_tensor=btd if name == "bias_tensor" else None)
+                h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
+                                     scale=w.scale_value, score_mod=ww.score_mod, mask=w.mask,
+                                     bias_stride=(0, btd.stride(1), btd.stride(2)))
+                ws = torch.empty(A.ae_attn_backward_workspace_bytes(h), dtype=torch.uint8, device=dev)
+                st = torch.cuda.current_stream()
+                tail = (O.data_ptr(), dO.data_ptr(), stats.data_ptr(), grads[0].data_ptr(), grads[1].data_ptr(), grads[2].data_ptr(),
+                        ws.data_ptr(), ws.numel(), st.cuda_stream)
+
+                def bcall():
+                    if name == "plain":
+                        A.ae_attn_backward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), *tail)
+                    else:
+                        A.ae_attn_backward_bias(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), btd.data_ptr(), *tail)
+                for _ in range(3):
+                    bcall()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(st)
+                for _ in range(10):
+                    bcall()
+                e1.record(st)
+                torch.cuda.synchronize()
+                A.ae_attn_destroy(h)
+                bres[name] = e0.elapsed_time(e1) / 10
+            bflop = 2 * (3 * w.D_qk + 2 * w.D_v) * w.visible_pairs_per_head() * w.B * w.H_q
             flop = w.mfma_flop()
             bias_bytes = 2 * w.visible_pairs_per_head() * w.B * w.H_q
             rows.append({"workload": w.name, "plain_ms": round(res["plain"], 4), "bias_tensor_ms": round(res["bias_tensor"], 4),
                          "plain_tflops": round(flop / res["plain"] / 1e9, 1), "bias_tensor_tflops": round(flop / res["bias_tensor"] / 1e9, 1),
-                         "bias_GBps": round(bias_bytes / res["bias_tensor"] / 1e6, 1), "parity_max_abs": err})
+                         "bias_GBps": round(bias_bytes / res["bias_tensor"] / 1e6, 1), "parity_max_abs": err,
+                         "backward_plain_ms": round(bres["plain"], 4), "backward_bias_tensor_ms": round(bres["bias_tensor"], 4),
+                         "backward_bias_tensor_tflops": round(bflop / bres["bias_tensor"] / 1e9, 1)})
             print(f"# {w.name:32s} plain {res['plain']:8.4f} ms {flop / res['plain'] / 1e9:7.1f} TFLOP/s | bias tensor "
                   f"{res['bias_tensor']:8.4f} ms {flop / res['bias_tensor'] / 1e9:7.1f} TFLOP/s ({100 * flop / res['bias_tensor'] / 1e9 / PEAK_BF16_TFLOPS:4.1f} % "
-                  f"of peak), bias read at {bias_bytes / res['bias_tensor'] / 1e6:7.1f} GB/s  max_abs {err:.2e}", file=sys.stderr, flush=True)
-            del Q, K, V, O, btd
+                  f"of peak), bias read at {bias_bytes / res['bias_tensor'] / 1e6:7.1f} GB/s  max_abs {err:.2e} | backward plain "
+                  f"{bres['plain']:8.4f} ms, bias tensor {bres['bias_tensor']:8.4f} ms {bflop / bres['bias_tensor'] / 1e9:7.1f} TFLOP/s",
+                  file=sys.stderr, flush=True)
+            del Q, K, V, O, btd, dO, grads
         print(json.dumps({"bias_tensor": rows, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS, "dtype": "bf16", "data": "synthetic"}))
         return
     if a.table2:

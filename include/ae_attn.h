@@ -205,7 +205,7 @@ ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t *h, size_t *bytes);
  * with the weights P recomputed from Q, K and the forward pass's row statistic;
  * dK and dV of a k/v head are summed over the query heads that share it.
  * Supported: every (score_mod, norm) pair, mask and pair of head dims that
- * ae_attn_create accepts, except AE_MOD_BIAS_TENSOR (AE_ERR_UNSUPPORTED);
+ * ae_attn_create accepts (AE_MOD_BIAS_TENSOR through ae_attn_backward_bias);
  * per-head decay multiplies dS' as it multiplies S'; kv_splits plays no part.
  *   Q, K, V   device, bf16, laid out as the descriptor says (the forward inputs);
  *   O         device, the forward output, dtype and strides as the descriptor
@@ -227,6 +227,15 @@ ae_status_t ae_attn_backward(const ae_attn_t *h, const void *Q, const void *K,
                              const void *stats, void *dQ, void *dK, void *dV,
                              void *workspace, size_t workspace_bytes,
                              void *stream);
+
+/* ae_attn_backward for a handle created with AE_MOD_BIAS_TENSOR: the same, with
+ * the bias tensor of the forward pass (device, bf16, 16-byte aligned, read only).
+ * The gradient with respect to the bias itself (it equals dS') is not formed.   */
+ae_status_t ae_attn_backward_bias(const ae_attn_t *h, const void *Q, const void *K,
+                                  const void *V, const void *bias, const void *O,
+                                  const void *dO, const void *stats, void *dQ,
+                                  void *dK, void *dV, void *workspace,
+                                  size_t workspace_bytes, void *stream);
 
 /* Frees the handle.  NULL is a no-op.                                         */
 ae_status_t ae_attn_destroy(ae_attn_t *h);

@@ -43,7 +43,7 @@ from .attention_oracle import _as_f64, _visible
 
 
 def attention_backward_head(q, k, v, do, *, scale, score_mod="none", bias=0.0, gamma_h=None,
-                            norm="softmax", mask="none"):
+                            norm="softmax", mask="none", bias_t=None):
     """(dq, dk, dv) for one head: q [L_q, D_qk], k [L_k, D_qk], v [L_k, D_v],
     do [L_q, D_v]."""
     q, k, v, do = _as_f64(q), _as_f64(k), _as_f64(v), _as_f64(do)
@@ -63,6 +63,8 @@ def attention_backward_head(q, k, v, do, *, scale, score_mod="none", bias=0.0, g
         s = s0 * dmod
     elif score_mod == "relu":
         s, dmod = np.maximum(s0, 0.0), (s0 > 0).astype(np.float64)
+    elif score_mod == "bias_tensor":   # an additive constant per (query, key) pair: slope 1
+        s, dmod = s0 + _as_f64(bias_t), np.ones_like(s0)
     else:
         raise ValueError(f"unknown score_mod {score_mod!r}")
 
@@ -107,7 +109,7 @@ def attention_backward_head(q, k, v, do, *, scale, score_mod="none", bias=0.0, g
 
 
 def attention_backward(Q, K, V, dO, *, scale, score_mod="none", bias=0.0, gamma=None,
-                       norm="softmax", mask="none"):
+                       norm="softmax", mask="none", bias_tensor=None):
     """Full operator: Q [B,H_q,L_q,D_qk], K [B,H_kv,L_k,D_qk], V [B,H_kv,L_k,D_v],
     dO [B,H_q,L_q,D_v] -> (dQ, dK, dV) in fp64, shaped like Q, K, V."""
     Q, K, V, dO = _as_f64(Q), _as_f64(K), _as_f64(V), _as_f64(dO)
@@ -117,11 +119,13 @@ def attention_backward(Q, K, V, dO, *, scale, score_mod="none", bias=0.0, gamma=
         raise ValueError("H_q must be a multiple of H_kv")
     g = H_q // H_kv
     dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    bt = None if bias_tensor is None else _as_f64(bias_tensor)   # [B or 1, H_q or 1, L_q, L_k]
     for b in range(B):
         for h in range(H_q):
             dq, dk, dv = attention_backward_head(
                 Q[b, h], K[b, h // g], V[b, h // g], dO[b, h], scale=scale, score_mod=score_mod, bias=bias,
-                gamma_h=None if gamma is None else float(gamma[h]), norm=norm, mask=mask)
+                gamma_h=None if gamma is None else float(gamma[h]), norm=norm, mask=mask,
+                bias_t=None if bt is None else bt[b if bt.shape[0] > 1 else 0, h if bt.shape[1] > 1 else 0])
             dQ[b, h] = dq
             dK[b, h // g] += dk
             dV[b, h // g] += dv

@@ -55,6 +55,8 @@ _lib.ae_attn_backward_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size
 _lib.ae_attn_backward_workspace_bytes.restype = C.c_int
 _lib.ae_attn_backward.argtypes = [C.c_void_p] * 11 + [C.c_size_t, C.c_void_p]
 _lib.ae_attn_backward.restype = C.c_int
+_lib.ae_attn_backward_bias.argtypes = [C.c_void_p] * 12 + [C.c_size_t, C.c_void_p]
+_lib.ae_attn_backward_bias.restype = C.c_int
 _lib.ae_attn_destroy.argtypes = [C.c_void_p]
 _lib.ae_attn_destroy.restype = C.c_int
 _lib.ae_attn_query.argtypes = [C.c_void_p] + [C.POINTER(C.c_int32)] * 5
@@ -139,6 +141,12 @@ def ae_attn_backward(handle: int, Q: int, K: int, V: int, O: int, dO: int, stats
     """Device addresses throughout: dQ, dK, dV (fp32, contiguous) receive the gradients for the upstream
     gradient dO (bf16, contiguous); O and stats are what ae_attn_forward_stats wrote."""
     _check(_lib.ae_attn_backward(handle, Q, K, V, O, dO, stats, dQ, dK, dV, workspace, workspace_bytes, stream))
+
+
+def ae_attn_backward_bias(handle: int, Q: int, K: int, V: int, bias: int, O: int, dO: int, stats: int, dQ: int, dK: int,
+                          dV: int, workspace: int, workspace_bytes: int, stream: int = 0) -> None:
+    """ae_attn_backward for a handle created with score_mod "bias_tensor" (bias: device address of the tensor)."""
+    _check(_lib.ae_attn_backward_bias(handle, Q, K, V, bias, O, dO, stats, dQ, dK, dV, workspace, workspace_bytes, stream))
 
 
 def ae_attn_forward_bias(handle: int, Q: int, K: int, V: int, bias: int, O: int, stats: int = 0, stream: int = 0) -> None:
@@ -251,7 +259,7 @@ def _bias_strides(bias_tensor, B, H_q, L_q, L_k):
 
 
 def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
-                       mask="none", window=0, stream=None, workspace=None):
+                       mask="none", window=0, stream=None, workspace=None, bias_tensor=None):
     """Runs the HIP backward pass on device tensors: Q, K, V bf16 [B, H, L, D] (last dim contiguous), O the
     forward output (fp32 or bf16), dO bf16 contiguous, stats the fp32 row statistic of the forward pass (O and
     stats may be None for sigmoid and no normalization); window: keys per query for mask="sliding_window".  Returns (dQ, dK, dV)
@@ -270,7 +278,7 @@ def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0
     h = ae_attn_create(B=B, H_q=H_q, H_kv=H_kv, L_q=L_q, L_k=L_k, D_qk=D_qk, D_v=D_v, scale=scale,
                        score_mod=score_mod, bias=bias, gamma=gamma, norm=norm, mask=mask, q_stride=Q.stride()[:3],
                        k_stride=K.stride()[:3], v_stride=V.stride()[:3], o_stride=o_stride, out_dtype=o_dtype,
-                       window=window)
+                       window=window, bias_stride=_bias_strides(bias_tensor, B, H_q, L_q, L_k))
     try:
         s = torch.cuda.current_stream(Q.device) if stream is None else stream
         with torch.cuda.device(Q.device):
@@ -280,9 +288,13 @@ def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0
             need = ae_attn_backward_workspace_bytes(h)
             if workspace is None:
                 workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
-            ae_attn_backward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), 0 if O is None else O.data_ptr(), dO.data_ptr(),
-                             0 if stats is None else stats.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-                             workspace.data_ptr(), workspace.numel() * workspace.element_size(), s.cuda_stream)
+            tail = (0 if O is None else O.data_ptr(), dO.data_ptr(), 0 if stats is None else stats.data_ptr(), dQ.data_ptr(),
+                    dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                    s.cuda_stream)
+            if bias_tensor is not None:
+                ae_attn_backward_bias(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), bias_tensor.data_ptr(), *tail)
+            else:
+                ae_attn_backward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), *tail)
     finally:
         ae_attn_destroy(h)
     return dQ, dK, dV

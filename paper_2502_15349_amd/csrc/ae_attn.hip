@@ -382,15 +382,23 @@ ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t* h, size_t* bytes) 
   return AE_OK;
 }
 
-ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* O, const void* dO,
-                             const void* stats, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
-                             void* stream) {
+}  // extern "C"
+
+static ae_status_t backward_impl(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* bias, const void* O,
+                                 const void* dO, const void* stats, void* dQ, void* dK, void* dV, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: null handle");
+  if ((h->desc.score_mod == AE_MOD_BIAS_TENSOR) != (bias != nullptr))
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: a handle with AE_MOD_BIAS_TENSOR, and only such a handle, runs through "
+                                    "ae_attn_backward_bias with its bias tensor");
+  if (bias && (((uintptr_t)bias & 15) || bias == dQ || bias == dK || bias == dV || bias == workspace))
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_backward_bias: the bias tensor must be 16-byte aligned and must not alias an output");
   const ae_attn_desc_t& d = h->desc;
   // no normalization + ReLU is one kernel variant of its own
   const int norm = d.norm == AE_NORM_NONE && d.score_mod == AE_MOD_RELU ? ae::BWD_NORM_NONE_RELU : h->kernel->norm;
   const bool abs_family = norm == ae::NORM_ABSSUM || norm == ae::NORM_ABS_OF_SUM;
-  const bool mod_ok = d.score_mod == AE_MOD_NONE || d.score_mod == AE_MOD_BIAS || norm == ae::BWD_NORM_NONE_RELU ||
+  const bool mod_ok = d.score_mod == AE_MOD_NONE || d.score_mod == AE_MOD_BIAS || d.score_mod == AE_MOD_BIAS_TENSOR ||
+                      norm == ae::BWD_NORM_NONE_RELU ||
                       ((abs_family || norm == ae::NORM_NONE) && d.score_mod == AE_MOD_HEAD_DECAY);
   if (!ae::backward_supported(d.D_qk, d.D_v, norm) || !mod_ok)
     return fail(AE_ERR_UNSUPPORTED,
@@ -422,6 +430,8 @@ ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, c
   p.O = O;
   p.lse = static_cast<const float*>(stats);
   p.delta = static_cast<float*>(workspace);
+  p.bias = static_cast<const __bf16*>(bias);
+  for (int a = 0; a < 3; ++a) p.bs[a] = h->params.bs[a];
   p.dQ = static_cast<float*>(dQ);
   p.dK = static_cast<float*>(dK);
   p.dV = static_cast<float*>(dV);
@@ -443,11 +453,27 @@ ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, c
   const float unit = norm == ae::NORM_SOFTMAX || norm == ae::NORM_SIGMOID ? log2e : 1.f;
   p.c2 = d.scale * unit;
   p.b2 = (d.score_mod == AE_MOD_BIAS ? d.bias : 0.f) * unit;
+  p.bunit = unit;
   p.scale = d.scale;
   p.window = d.mask == AE_MASK_SLIDING_WINDOW ? std::min(d.window, d.L_q + d.L_k) : d.L_q + d.L_k;
   hipError_t e = ae::launch_backward(p, h->decay, d.D_qk, d.D_v, norm, d.mask != AE_MASK_NONE, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_backward: launch failed: %s", hipGetErrorString(e));
   return AE_OK;
+}
+
+extern "C" {
+
+ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                             const void* stats, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  return backward_impl(h, Q, K, V, nullptr, O, dO, stats, dQ, dK, dV, workspace, workspace_bytes, stream);
+}
+
+ae_status_t ae_attn_backward_bias(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* bias,
+                                  const void* O, const void* dO, const void* stats, void* dQ, void* dK, void* dV,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (!bias) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward_bias: null bias tensor");
+  return backward_impl(h, Q, K, V, bias, O, dO, stats, dQ, dK, dV, workspace, workspace_bytes, stream);
 }
 
 ae_status_t ae_attn_destroy(ae_attn_t* h) {

@@ -28,9 +28,9 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const BwdParams p, 
   if (lane == 0) p.delta[r] = acc;
 }
 
-template <int DQK, int DV, int NORM, bool CAUSAL, int OUT>
+template <int DQK, int DV, int NORM, bool CAUSAL, int OUT, bool BIAS>
 hipError_t launch_one(const BwdParams& p, const DecayTable& dt, hipStream_t s) {
-  typedef BwdCfg<DQK, DV, NORM, CAUSAL, OUT> C;
+  typedef BwdCfg<DQK, DV, NORM, CAUSAL, OUT, BIAS> C;
   const int heads = C::KV_SIDE ? p.H_kv : p.H_q, L = C::KV_SIDE ? p.L_k : p.L_q;
   hipLaunchKernelGGL(attn_bwd_kernel<C>, dim3((unsigned)(p.B * heads * ((L + C::OWN - 1) / C::OWN))), dim3(C::THREADS), 0, s, p, dt);
   return hipGetLastError();
@@ -38,9 +38,20 @@ hipError_t launch_one(const BwdParams& p, const DecayTable& dt, hipStream_t s) {
 
 template <int DQK, int DV, int NORM, bool CAUSAL>
 hipError_t launch_pair(const BwdParams& p, const DecayTable& dt, hipStream_t s) {
-  const hipError_t e = launch_one<DQK, DV, NORM, CAUSAL, BWD_DKV>(p, dt, s);
+  // the bias tensor comes with softmax, sigmoid and no normalization, and not with head dims 128/256
+  constexpr bool kBiasBuilt = (NORM == NORM_SOFTMAX || NORM == NORM_SIGMOID || NORM == NORM_NONE) && !(DQK == 128 && DV == 256);
+  if (p.bias != nullptr) {
+    if constexpr (kBiasBuilt) {
+      const hipError_t e = launch_one<DQK, DV, NORM, CAUSAL, BWD_DKV, true>(p, dt, s);
+      if (e != hipSuccess) return e;
+      return launch_one<DQK, DV, NORM, CAUSAL, BWD_DQ, true>(p, dt, s);
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
+  const hipError_t e = launch_one<DQK, DV, NORM, CAUSAL, BWD_DKV, false>(p, dt, s);
   if (e != hipSuccess) return e;
-  return launch_one<DQK, DV, NORM, CAUSAL, BWD_DQ>(p, dt, s);
+  return launch_one<DQK, DV, NORM, CAUSAL, BWD_DQ, false>(p, dt, s);
 }
 
 template <int DQK, int DV, int NORM>

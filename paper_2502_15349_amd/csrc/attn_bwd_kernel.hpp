@@ -54,6 +54,11 @@ struct BwdParams {
   float c2;     // scale * log2(e)
   float b2;     // bias * log2(e)
   float scale;
+  // bias-tensor kernels: additive bias per (query, key), bf16, element strides bs[] = {batch, head, row};
+  // bunit: log2(e) where the scores are kept in powers of two (softmax, sigmoid), else 1
+  const __bf16* bias;
+  int64_t bs[3];
+  float bunit;
   // causal kernels: key j is also hidden from query i if j <= i + (L_k - L_q) - window (sliding
   // window); L_q + L_k for the plain causal mask, which hides nothing more
   int window;
@@ -75,8 +80,9 @@ __device__ __forceinline__ int bswz(int row) {
 constexpr int BWD_NORM_NONE_RELU = 5;
 enum : int { BWD_DQ = 0, BWD_DKV = 1 };  // the query-side kernel (dQ), the key-side kernel (dK and dV)
 
-template <int DQK_, int DV_, int NORM_, bool CAUSAL_, int OUT_>
+template <int DQK_, int DV_, int NORM_, bool CAUSAL_, int OUT_, bool BIAS_ = false>
 struct BwdCfg {
+  static constexpr bool BIAS = BIAS_;  // S' = scale * S + bias[b, h_q, i, j]
   static constexpr int DQK = DQK_, DV = DV_, NORM = NORM_, OUT = OUT_;
   static constexpr bool CAUSAL = CAUSAL_, KV_SIDE = OUT_ == BWD_DKV;
   static constexpr int WAVES = 4, THREADS = 256, OWN = 128;  // own rows per workgroup
@@ -86,14 +92,18 @@ struct BwdCfg {
   static constexpr int DB2 = HAS2 ? DV / 32 : 0;
   // Two workgroups per CU (two waves per SIMD, 256 registers each) where the accumulators, the
   // resident operands and the two score tiles leave room for the rest; one (512 registers) otherwise.
-  static constexpr bool OCC2 = 16 * (DB + DB2) + 4 * T1 + 4 * T2 + 32 <= 176;
+  // bias tensor: per stage the block of it that the tile meets, 16 KB: [128 own queries][64 keys] on the query
+  // side, [64 queries][128 own keys] on the key side
+  static constexpr int BIAS_BYTES = BIAS_ ? 16384 : 0;
+  static constexpr bool OCC2 = 16 * (DB + DB2) + 4 * T1 + 4 * T2 + 32 + (BIAS_ ? 8 : 0) <= 176 &&
+                               2 * 64 * (DQK + DV) * 2 + 1024 + 2 * BIAS_BYTES <= 80 * 1024;
   // one workgroup per CU: the LDS fragments of a step are read as a batch ahead of its MFMAs
   static constexpr bool BATCH = !OCC2 && DQK + DV <= 320;  // (beyond that the batches do not fit 512 registers)
   static constexpr int TILE = 64;  // other-side rows per LDS tile (two 32-row sub-tiles)
   static constexpr int RB1 = DQK * 2, RB2 = DV * 2, CPR1 = DQK / 8, CPR2 = DV / 8;
   static constexpr int Y1_BYTES = TILE * RB1, Y2_BYTES = TILE * RB2, STAGE_BYTES = Y1_BYTES + Y2_BYTES;
   static constexpr int ROW_BYTES = 2 * TILE * 4;  // per stage: bias*log2(e) - lse*log2(e) and delta of the tile's rows
-  static constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * ROW_BYTES;
+  static constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * ROW_BYTES + 2 * BIAS_BYTES;
   static_assert(NORM == NORM_SOFTMAX || NORM == NORM_SIGMOID || NORM == NORM_NONE || NORM == BWD_NORM_NONE_RELU ||
                     NORM == NORM_ABSSUM || NORM == NORM_ABS_OF_SUM,
                 "backward: softmax, sigmoid, the abs-sum family, and no normalization with or without ReLU");
@@ -125,6 +135,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
   __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const uint32_t rows0 = lds0 + 2 * C::STAGE_BYTES;
+  const uint32_t bias0 = rows0 + 2 * C::ROW_BYTES;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ln = lane & 31, half = lane >> 5;
   const int off = p.L_k - p.L_q;
@@ -218,6 +229,26 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       row = row < L_oth ? row : L_oth - 1;
       const uint32_t goff = (uint32_t)(((int64_t)row * s2 + ((pc ^ bswz<C::CPR2>(r)) * 8)) * 2);
       dma16(y2, goff, base + C::Y1_BYTES + nb * 1024);
+    }
+    if constexpr (C::BIAS) {
+      // The block of the bias tensor that this tile meets, rows = queries.  Query side: 128 rows x 128 bytes
+      // (8 chunks), chunk slot c ^ ((row >> 1) & 7); key side: 64 rows x 256 bytes (16 chunks), slot
+      // c ^ ((row & 3) << 2) (read back transposed, 4 rows x 64 bytes at a time).  Chunks that start beyond the
+      // last key are redirected to the row's last chunk (rows are padded to 8 elements by contract).
+      const __bf16* bb = p.bias + b * p.bs[0] + hq * p.bs[1];
+      constexpr int CPRB = C::KV_SIDE ? 16 : 8;
+      const int q0 = C::KV_SIDE ? r0 : own0, k0 = C::KV_SIDE ? own0 : r0;
+      const int last = ((p.L_k - 1) >> 3) << 3;
+#pragma unroll
+      for (int i = 0; i < 16 / C::WAVES; ++i) {
+        const int nb = wave + i * C::WAVES, pos = nb * 64 + lane;
+        const int r = pos / CPRB, pc = pos % CPRB;
+        const int c = C::KV_SIDE ? pc ^ ((r & 3) << 2) : pc ^ ((r >> 1) & 7);
+        int row = q0 + r, col = k0 + 8 * c;
+        row = row < p.L_q ? row : p.L_q - 1;
+        col = col < p.L_k ? col : last;
+        dma16(bb, (uint32_t)(((int64_t)row * p.bs[2] + col) * 2), bias0 + stage * C::BIAS_BYTES + nb * 1024);
+      }
     }
   };
   // key side: the tile's row quantities, wave 0 -> (bias - lse) * log2(e), wave 1 -> delta.  The
@@ -357,6 +388,34 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
     float x[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) x[r] = __builtin_fmaf(s[r], p.c2, C::NORM == NORM_SOFTMAX ? nl4[r / 4][r % 4] : p.b2);
+    if constexpr (C::BIAS) {
+      // register r = 4 q4 + e is (query, key) = (own row, key 8 q4 + 4 half + e of the sub-tile) on the query side,
+      // (query 8 q4 + 4 half + e of the sub-tile, own key) on the key side
+      const uint32_t bt = bias0 + STAGE * C::BIAS_BYTES;
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        uint32_t lo, hi;
+        if constexpr (C::KV_SIDE) {
+          const int row = 32 * SUB + 8 * q4 + 4 * half + ((lane & 15) >> 2);   // the row this lane addresses
+          const int cl = 4 * wave + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);  // chunk of its 4 columns
+          const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)(
+              bt + row * 256 + ((cl ^ ((row & 3) << 2)) << 4) + (lane & 1) * 8));
+          const u32x2 w2 = __builtin_bit_cast(u32x2, v);
+          lo = w2[0];
+          hi = w2[1];
+        } else {
+          const int row = 32 * wave + ln;
+          const u32x2 w2 = *reinterpret_cast<__attribute__((address_space(3))) const u32x2*>(
+              (lds_char*)(uintptr_t)(bt + row * 128 + (((4 * SUB + q4) ^ ((row >> 1) & 7)) << 4) + 8 * half));
+          lo = w2[0];
+          hi = w2[1];
+        }
+        x[4 * q4 + 0] += __builtin_bit_cast(float, lo << 16) * p.bunit;
+        x[4 * q4 + 1] += __builtin_bit_cast(float, lo & 0xffff0000u) * p.bunit;
+        x[4 * q4 + 2] += __builtin_bit_cast(float, hi << 16) * p.bunit;
+        x[4 * q4 + 3] += __builtin_bit_cast(float, hi & 0xffff0000u) * p.bunit;
+      }
+    }
     // abs-sum family: distance to the diagonal of register 0's entry, for the decay factor
     const float dist0 = (float)(C::KV_SIDE ? o0 + off - own + 4 * half : own + off - o0 - 4 * half);
     if (!full) {  // a hidden entry gets the exponent that makes its weight exactly 0

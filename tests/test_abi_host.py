@@ -199,7 +199,8 @@ def test_backward_rejects_bad_arguments_without_launching():
                         (dict(norm="none", score_mod="relu"), None),
                         (dict(norm="abssum", score_mod="head_decay", mask="causal", gamma=[.9] * 4), "ws"),
                         (dict(norm="none", score_mod="head_decay", mask="causal", gamma=[.9] * 4), None),
-                        (dict(score_mod="bias_tensor", bias_stride=(0, 0, 104)), A.AE_ERR_UNSUPPORTED),
+                        # a bias-tensor handle runs through ae_attn_backward_bias
+                        (dict(score_mod="bias_tensor", bias_stride=(0, 0, 104)), A.AE_ERR_INVALID_ARG),
                         (dict(mask="sliding_window", window=8), "ws")):
         dd = _ok_desc()
         dd.update(patch)

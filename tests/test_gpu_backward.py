@@ -215,3 +215,34 @@ def test_backward_hip_graph_replays(A):
             assert torch.equal(a, b), f"replay {replay}: {name} differs from the eager call"
     del graph
     A.ae_attn_destroy(h)
+
+
+@pytest.mark.parametrize("dims", [(64, 64), (128, 128), (192, 128)], ids=lambda d: f"d{d[0]}_{d[1]}")
+@pytest.mark.parametrize("norm", ["softmax", "sigmoid", "none"])
+@pytest.mark.parametrize("mask", ["none", "causal"])
+def test_backward_bias_tensor(A, dims, norm, mask):
+    """dQ, dK, dV with an additive bias tensor (per batch and head / shared over the batch / over both) on a ragged,
+    grouped shape; the bias rows are padded to a multiple of 8 on the device."""
+    from paper_2502_15349_amd.workloads import make_bias_tensor
+    dev = torch.device("cuda:0")
+    w = Workload(f"bwd_bias_{norm}_{mask}", 63, 2, 4, 2, 300, 333, dims[0], dims[1], score_mod="bias_tensor", norm=norm,
+                 mask=mask, scale=(0.01 if norm == "none" else None))
+    Q, K, V = make_inputs(w)
+    dO = make_grad(w)
+    Qd, Kd, Vd, dOd = Q.to(dev), K.to(dev), V.to(dev), dO.to(dev)
+    for per_batch, per_head in ((True, True), (False, True), (False, False)):
+        bt = make_bias_tensor(w, per_batch, per_head)
+        if norm == "none":
+            bt = (bt.float() * 0.01).to(torch.bfloat16)
+        print(f"case {w.name} dims {dims} bias shape {tuple(bt.shape)}", flush=True)
+        btd = torch.zeros(bt.shape[:3] + (336,), dtype=torch.bfloat16, device=dev)
+        btd[..., :w.L_k] = bt.to(dev)
+        btv = btd[..., :w.L_k]
+        stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev) if norm == "softmax" else None
+        O = A.run_workload(w, Qd, Kd, Vd, stats=stats, bias_tensor=btv)
+        got = A.attention_backward(Qd, Kd, Vd, O, dOd, stats, scale=w.scale_value, score_mod="bias_tensor", norm=norm,
+                                   mask=mask, bias_tensor=btv)
+        torch.cuda.synchronize()
+        ref = attention_backward(Q, K, V, dO, scale=w.scale_value, score_mod="bias_tensor", norm=norm, mask=mask, bias_tensor=bt)
+        for name, g, r in zip(("dQ", "dK", "dV"), got, ref):
+            check(g.cpu().double().numpy(), r, f"{w.name} {tuple(bt.shape)} {name}")

@@ -173,6 +173,27 @@ def test_abs_sum_normalizers_on_both_sides_of_the_clamp(norm):
     np.testing.assert_allclose(dv, [[0.3]], atol=1e-15)
 
 
+@pytest.mark.parametrize("norm", ["softmax", "sigmoid", "none"])
+@pytest.mark.parametrize("mask", ["none", "causal"])
+def test_bias_tensor_gradients(norm, mask):
+    # finite differences of the forward oracle with the same bias tensor (per batch and head, shared over batch,
+    # shared over both), and: a constant tensor gives the gradients of the constant bias
+    B, Hq, Hkv, Lq, Lk, D = 2, 2, 1, 5, 6, 3
+    Q, K, V, dO = rnd(B, Hq, Lq, D), rnd(B, Hkv, Lk, D), rnd(B, Hkv, Lk, 2), rnd(B, Hq, Lq, 2)
+    for shape in ((B, Hq, Lq, Lk), (1, Hq, Lq, Lk), (1, 1, Lq, Lk)):
+        kw = dict(scale=0.6, score_mod="bias_tensor", bias_tensor=rnd(*shape), norm=norm, mask=mask)
+        dQ, dK, dV = attention_backward(Q, K, V, dO, **kw)
+        fwd = lambda: attention(Q, K, V, **kw)  # noqa: E731
+        np.testing.assert_allclose(dQ, finite_difference(fwd, Q, dO), atol=2e-7)
+        np.testing.assert_allclose(dK, finite_difference(fwd, K, dO), atol=2e-7)
+        np.testing.assert_allclose(dV, finite_difference(fwd, V, dO), atol=2e-7)
+    a = attention_backward(Q, K, V, dO, scale=0.6, score_mod="bias", bias=0.4, norm=norm, mask=mask)
+    b = attention_backward(Q, K, V, dO, scale=0.6, score_mod="bias_tensor", bias_tensor=np.full((1, 1, Lq, Lk), 0.4), norm=norm,
+                           mask=mask)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x, y, atol=1e-14)
+
+
 def test_gqa_sums_over_the_query_heads_of_a_group():
     B, Hq, Hkv, L, D = 1, 4, 2, 7, 4
     Q, K, V, dO = rnd(B, Hq, L, D), rnd(B, Hkv, L, D), rnd(B, Hkv, L, D), rnd(B, Hq, L, D)
