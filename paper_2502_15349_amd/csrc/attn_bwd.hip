@@ -1,4 +1,5 @@
-// Kernel instantiations and launch of the backward pass (see attn_bwd_kernel.hpp).
+// Launch of the backward pass (see attn_bwd_kernel.hpp): the delta kernel and the dispatch to the per-head-dim
+// instantiation files.
 #include "bwd.hpp"
 
 namespace ae {
@@ -28,51 +29,12 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const BwdParams p, 
   if (lane == 0) p.delta[r] = acc;
 }
 
-template <int DQK, int DV, int NORM, bool CAUSAL, int OUT, bool BIAS>
-hipError_t launch_one(const BwdParams& p, const DecayTable& dt, hipStream_t s) {
-  typedef BwdCfg<DQK, DV, NORM, CAUSAL, OUT, BIAS> C;
-  const int heads = C::KV_SIDE ? p.H_kv : p.H_q, L = C::KV_SIDE ? p.L_k : p.L_q;
-  hipLaunchKernelGGL(attn_bwd_kernel<C>, dim3((unsigned)(p.B * heads * ((L + C::OWN - 1) / C::OWN))), dim3(C::THREADS), 0, s, p, dt);
-  return hipGetLastError();
-}
-
-template <int DQK, int DV, int NORM, bool CAUSAL>
-hipError_t launch_pair(const BwdParams& p, const DecayTable& dt, hipStream_t s) {
-  // the bias tensor comes with softmax, sigmoid and no normalization, and not with head dims 128/256
-  constexpr bool kBiasBuilt = (NORM == NORM_SOFTMAX || NORM == NORM_SIGMOID || NORM == NORM_NONE) && !(DQK == 128 && DV == 256);
-  if (p.bias != nullptr) {
-    if constexpr (kBiasBuilt) {
-      const hipError_t e = launch_one<DQK, DV, NORM, CAUSAL, BWD_DKV, true>(p, dt, s);
-      if (e != hipSuccess) return e;
-      return launch_one<DQK, DV, NORM, CAUSAL, BWD_DQ, true>(p, dt, s);
-    } else {
-      return hipErrorInvalidValue;
-    }
-  }
-  const hipError_t e = launch_one<DQK, DV, NORM, CAUSAL, BWD_DKV, false>(p, dt, s);
-  if (e != hipSuccess) return e;
-  return launch_one<DQK, DV, NORM, CAUSAL, BWD_DQ, false>(p, dt, s);
-}
-
-template <int DQK, int DV, int NORM>
-hipError_t launch_norm(const BwdParams& p, const DecayTable& dt, int causal, hipStream_t s) {
-  return causal ? launch_pair<DQK, DV, NORM, true>(p, dt, s) : launch_pair<DQK, DV, NORM, false>(p, dt, s);
-}
-
-template <int DQK, int DV>
-hipError_t launch_dims(const BwdParams& p, const DecayTable& dt, int norm, int causal, hipStream_t s) {
-  switch (norm) {
-    case NORM_SOFTMAX: return launch_norm<DQK, DV, NORM_SOFTMAX>(p, dt, causal, s);
-    case NORM_SIGMOID: return launch_norm<DQK, DV, NORM_SIGMOID>(p, dt, causal, s);
-    case NORM_ABSSUM: return launch_norm<DQK, DV, NORM_ABSSUM>(p, dt, causal, s);
-    case NORM_ABS_OF_SUM: return launch_norm<DQK, DV, NORM_ABS_OF_SUM>(p, dt, causal, s);
-    case NORM_NONE: return launch_norm<DQK, DV, NORM_NONE>(p, dt, causal, s);
-    case BWD_NORM_NONE_RELU: return launch_norm<DQK, DV, BWD_NORM_NONE_RELU>(p, dt, causal, s);
-  }
-  return hipErrorInvalidValue;
-}
-
 }  // namespace
+
+hipError_t launch_backward_64_64(const BwdParams&, const DecayTable&, int, int, hipStream_t);
+hipError_t launch_backward_128_128(const BwdParams&, const DecayTable&, int, int, hipStream_t);
+hipError_t launch_backward_192_128(const BwdParams&, const DecayTable&, int, int, hipStream_t);
+hipError_t launch_backward_128_256(const BwdParams&, const DecayTable&, int, int, hipStream_t);
 
 bool backward_supported(int dqk, int dv, int norm) {
   const bool dims = (dqk == 64 && dv == 64) || (dqk == 128 && dv == 128) || (dqk == 192 && dv == 128) || (dqk == 128 && dv == 256);
@@ -87,10 +49,10 @@ hipError_t launch_backward(const BwdParams& p, const DecayTable& dt, int dqk, in
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  if (dqk == 64 && dv == 64) return launch_dims<64, 64>(p, dt, norm, causal, stream);
-  if (dqk == 128 && dv == 128) return launch_dims<128, 128>(p, dt, norm, causal, stream);
-  if (dqk == 192 && dv == 128) return launch_dims<192, 128>(p, dt, norm, causal, stream);
-  if (dqk == 128 && dv == 256) return launch_dims<128, 256>(p, dt, norm, causal, stream);
+  if (dqk == 64 && dv == 64) return launch_backward_64_64(p, dt, norm, causal, stream);
+  if (dqk == 128 && dv == 128) return launch_backward_128_128(p, dt, norm, causal, stream);
+  if (dqk == 192 && dv == 128) return launch_backward_192_128(p, dt, norm, causal, stream);
+  if (dqk == 128 && dv == 256) return launch_backward_128_256(p, dt, norm, causal, stream);
   return hipErrorInvalidValue;
 }
 

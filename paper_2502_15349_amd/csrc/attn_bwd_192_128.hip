@@ -1,0 +1,8 @@
+// Backward kernel instantiations for D_qk = 192, D_v = 128.
+#include "bwd_launch.hpp"
+
+namespace ae {
+hipError_t launch_backward_192_128(const BwdParams& p, const DecayTable& dt, int norm, int causal, hipStream_t stream) {
+  return launch_dims<192, 128>(p, dt, norm, causal, stream);
+}
+}  // namespace ae
