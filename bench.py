@@ -501,6 +501,34 @@ def main():
         tf = flop / (kms * 1e-3) / 1e12
         variants[w.name + "_bf16_out"] = {"tflops": round(tf, 2), "frac_of_peak": round(tf / PEAK_BF16_TFLOPS, 4),
                                           "kernel_ms": round(kms, 5), "parity_max_abs": pv["max_abs"]}
+        # the backward pass of the same workload (ae_attn_backward: delta, key-side and query-side kernel), timed the same
+        # way; algorithmic flop = 2 (3 D_qk + 2 D_v) per visible pair.  `bench.py --backward` has the other shapes.
+        from paper_2502_15349_amd.workloads import make_grad
+        stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev)
+        Of = A.run_workload(w, Q, K, V, stats=stats)
+        dO = make_grad(w).to(dev)
+        hb = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v, scale=w.scale_value,
+                              score_mod=w.score_mod, bias=w.bias, gamma=w.gamma(), norm=w.norm, mask=w.mask)
+        grads = [torch.empty(x.shape, dtype=torch.float32, device=dev) for x in (Q, K, V)]
+        wsb = torch.empty(max(A.ae_attn_backward_workspace_bytes(hb), 16), dtype=torch.uint8, device=dev)
+        st = torch.cuda.current_stream()
+        bargs = (hb, Q.data_ptr(), K.data_ptr(), V.data_ptr(), Of.data_ptr(), dO.data_ptr(), stats.data_ptr(), grads[0].data_ptr(),
+                 grads[1].data_ptr(), grads[2].data_ptr(), wsb.data_ptr(), wsb.numel(), st.cuda_stream)
+        t_end = time.perf_counter() + 0.3
+        while time.perf_counter() < t_end:
+            A.ae_attn_backward(*bargs)
+            torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(20):
+            A.ae_attn_backward(*bargs)
+        e1.record(st)
+        torch.cuda.synchronize()
+        A.ae_attn_destroy(hb)
+        bms = e0.elapsed_time(e1) / 20
+        btf = 2 * (3 * w.D_qk + 2 * w.D_v) * w.visible_pairs_per_head() * w.B * w.H_q / (bms * 1e-3) / 1e12
+        variants[w.name + "_backward"] = {"tflops": round(btf, 2), "frac_of_peak": round(btf / PEAK_BF16_TFLOPS, 4),
+                                         "ms": round(bms, 5)}
         out["variants"] = variants
 
     # What the matrix pipes sustain on this board with nothing else in the way: the library's
