@@ -129,6 +129,8 @@ typedef struct {
  * AE_MASK_SLIDING_WINDOW: score_mod NONE or BIAS with SOFTMAX, SIGMOID or NONE.
  * AE_MOD_BIAS_TENSOR: with SOFTMAX, SIGMOID or NONE, masks NONE or CAUSAL, head
  * dims 64/64, 128/128 or 192/128, no split keys.
+ * One (batch, head) slab of Q, K, V (and of the bias tensor) must span less than
+ * 4 GiB: rows x row stride x 2 bytes (AE_ERR_UNSUPPORTED otherwise).
  * Errors: AE_ERR_INVALID_ARG, AE_ERR_UNSUPPORTED, AE_ERR_NOMEM; *out is set
  * to NULL on error.                                                           */
 ae_status_t ae_attn_create(const ae_attn_desc_t *desc, ae_attn_t **out);

@@ -194,6 +194,15 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
       return fail(AE_ERR_INVALID_ARG, "ae_attn_create: a Q/K/V row stride is smaller than the head dim");
     }
   }
+  // the kernels address the rows of one (batch, head) slab with 32-bit byte offsets
+  {
+    const int64_t lim = (int64_t)1 << 32;
+    if ((int64_t)d->L_q * p.qs[2] * 2 >= lim || (int64_t)d->L_k * p.ks[2] * 2 >= lim || (int64_t)d->L_k * p.vs[2] * 2 >= lim ||
+        (mod == ae::MOD_BIAS_T && (int64_t)d->L_q * p.bs[2] * 2 >= lim)) {
+      delete h;
+      return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: one (batch, head) slab of Q, K, V or the bias spans 4 GiB or more");
+    }
+  }
   for (int a = 0; a < 3; ++a)
     if (p.os[a] < 0 || p.os[a] % 4 != 0) {
       delete h;

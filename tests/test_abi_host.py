@@ -255,6 +255,21 @@ def test_bias_tensor_descriptor_and_entry_point_checks():
     A.ae_attn_destroy(A.ae_attn_create(**dd))
 
 
+def test_slabs_beyond_32_bit_offsets_are_refused():
+    from paper_2502_15349_amd import ae_attn as A
+    d = _ok_desc()
+    d.update(L_q=1 << 20, L_k=1 << 20, q_stride=(0, 0, 4096))      # 2^20 rows x 8 KB = 8 GiB per (batch, head)
+    d["q_stride"] = ((1 << 20) * 4096 * 4, (1 << 20) * 4096, 4096)
+    with pytest.raises(A.AeAttnError) as ei:
+        A.ae_attn_create(**d)
+    assert ei.value.status == A.AE_ERR_UNSUPPORTED
+    d = _ok_desc()
+    d.update(L_q=1 << 16, L_k=1 << 16, score_mod="bias_tensor")    # bias rows of 128 KB x 65536 rows = 8 GiB
+    with pytest.raises(A.AeAttnError) as ei:
+        A.ae_attn_create(**d)
+    assert ei.value.status == A.AE_ERR_UNSUPPORTED
+
+
 def test_padded_strides_accepted():
     from paper_2502_15349_amd import ae_attn as A
     h = A.ae_attn_create(**_ok_desc(), q_stride=(100 * 4 * 136, 100 * 136, 136))
