@@ -223,7 +223,10 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     p.c = a;
     p.b2 = bias;
   }
-  if (mod == ae::MOD_BIAS_T) p.b2 = (d->norm == AE_NORM_SOFTMAX || d->norm == AE_NORM_SIGMOID) ? log2e : 1.f;  // the unit of the bias values
+  if (mod == ae::MOD_BIAS_T) {
+    p.b2 = (d->norm == AE_NORM_SOFTMAX || d->norm == AE_NORM_SIGMOID) ? log2e : 1.f;  // the unit of the bias values
+    if (d->norm == AE_NORM_SOFTMAX) p.c = a;  // biased scores in natural units until the exponent (see post_pair)
+  }
   p.neg_q = d->scale < 0.f ? 1 : 0;
   p.out_bf16 = d->out_dtype == AE_OUT_BF16 ? 1 : 0;
   p.window = d->mask == AE_MASK_SLIDING_WINDOW ? d->window : 0;

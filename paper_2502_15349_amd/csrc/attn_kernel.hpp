@@ -368,10 +368,13 @@ __device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, flo
     const int r = 2 * q + u;
     float x = s[r];
     if constexpr (C::MOD == MOD_BIAS_T) {
-      // the pair's two bf16 bias values, widened; p.b2 holds their unit (log2(e) for softmax and sigmoid, else 1)
-      const float bv = __builtin_bit_cast(float, u == 0 ? bias_pair << 16 : bias_pair & 0xffff0000u) * p.b2;
-      if constexpr (C::NORM == NORM_SIGMOID) x = fast_exp2(-__builtin_fmaf(x, p.c, bv));
-      else x = __builtin_fmaf(x, p.c, bv);  // softmax: the modified score itself (the row max is taken over it)
+      // the pair's two bf16 bias values, widened
+      const float bv = __builtin_bit_cast(float, u == 0 ? bias_pair << 16 : bias_pair & 0xffff0000u);
+      // sigmoid: p.c = scale * log2(e), p.b2 = log2(e).  Softmax keeps the modified score in natural units here
+      // (p.c = scale; the row max is taken over it) and moves to powers of two in the exponent's FMA (p.b2 =
+      // log2(e)), which saves the multiplication of every bias value.  Others: p.c = scale.
+      if constexpr (C::NORM == NORM_SIGMOID) x = fast_exp2(-__builtin_fmaf(x, p.c, bv * p.b2));
+      else x = __builtin_fmaf(x, p.c, bv);
     } else if constexpr (C::NORM == NORM_SOFTMAX) {
     } else if constexpr (C::NORM == NORM_SIGMOID) {
       x = FOLD ? fast_exp2(x) : fast_exp2(__builtin_fmaf(x, -p.c, -p.b2));
@@ -393,7 +396,7 @@ template <class C>
 __device__ __forceinline__ void post_done(const Params& p, const RowState<C>& st, float mx, bool& moved, float& xm) {
   if constexpr (C::NORM == NORM_SOFTMAX) {
     mx = max_halves(mx);
-    xm = C::MOD == MOD_BIAS_T ? mx : __builtin_fmaf(mx, p.c, p.b2);  // c > 0
+    xm = C::MOD == MOD_BIAS_T ? mx * p.b2 : __builtin_fmaf(mx, p.c, p.b2);  // c > 0
     moved = xm > st.m + kLazyLog2;
   }
 }
@@ -421,8 +424,8 @@ template <class C, bool FOLD = false>
 __device__ __forceinline__ uint32_t finish_pair(const Params& p, int q, const f32x16& s, float k0, float& acc) {
   float x0 = s[2 * q], x1 = s[2 * q + 1];
   if constexpr (C::NORM == NORM_SOFTMAX && C::MOD == MOD_BIAS_T) {
-    x0 = fast_exp2(x0 + k0);
-    x1 = fast_exp2(x1 + k0);
+    x0 = fast_exp2(__builtin_fmaf(x0, p.b2, k0));
+    x1 = fast_exp2(__builtin_fmaf(x1, p.b2, k0));
     acc += x0 + x1;
   } else if constexpr (C::NORM == NORM_SOFTMAX) {
     x0 = fast_exp2(__builtin_fmaf(x0, p.c, k0));
