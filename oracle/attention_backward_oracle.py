@@ -43,9 +43,10 @@ from .attention_oracle import _as_f64, _visible
 
 
 def attention_backward_head(q, k, v, do, *, scale, score_mod="none", bias=0.0, gamma_h=None,
-                            norm="softmax", mask="none", bias_t=None):
+                            norm="softmax", mask="none", bias_t=None, with_dbias=False):
     """(dq, dk, dv) for one head: q [L_q, D_qk], k [L_k, D_qk], v [L_k, D_v],
-    do [L_q, D_v]."""
+    do [L_q, D_v].  with_dbias: also the gradient with respect to the additive
+    bias tensor, [L_q, L_k] (it is dS': the bias enters S' with slope 1)."""
     q, k, v, do = _as_f64(q), _as_f64(k), _as_f64(v), _as_f64(do)
     L_q, L_k = q.shape[0], k.shape[0]
     rows = np.arange(L_q)
@@ -103,13 +104,16 @@ def attention_backward_head(q, k, v, do, *, scale, score_mod="none", bias=0.0, g
     else:
         ds = np.where(vis, dp, 0.0)
     # modification and scale
-    ds = np.where(vis, ds * dmod, 0.0) * float(scale)
+    dsp = np.where(vis, ds, 0.0)          # gradient of the modified scores S'
+    ds = dsp * dmod * float(scale)
     # relevance scoring S = Q K^T
+    if with_dbias:
+        return ds @ k, ds.T @ q, dv, dsp
     return ds @ k, ds.T @ q, dv
 
 
 def attention_backward(Q, K, V, dO, *, scale, score_mod="none", bias=0.0, gamma=None,
-                       norm="softmax", mask="none", bias_tensor=None):
+                       norm="softmax", mask="none", bias_tensor=None, with_dbias=False):
     """Full operator: Q [B,H_q,L_q,D_qk], K [B,H_kv,L_k,D_qk], V [B,H_kv,L_k,D_v],
     dO [B,H_q,L_q,D_v] -> (dQ, dK, dV) in fp64, shaped like Q, K, V."""
     Q, K, V, dO = _as_f64(Q), _as_f64(K), _as_f64(V), _as_f64(dO)
@@ -119,14 +123,21 @@ def attention_backward(Q, K, V, dO, *, scale, score_mod="none", bias=0.0, gamma=
         raise ValueError("H_q must be a multiple of H_kv")
     g = H_q // H_kv
     dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    dB = np.zeros((B, H_q, Q.shape[2], K.shape[2])) if with_dbias else None   # per batch and head, not summed
     bt = None if bias_tensor is None else _as_f64(bias_tensor)   # [B or 1, H_q or 1, L_q, L_k]
     for b in range(B):
         for h in range(H_q):
-            dq, dk, dv = attention_backward_head(
+            res = attention_backward_head(
                 Q[b, h], K[b, h // g], V[b, h // g], dO[b, h], scale=scale, score_mod=score_mod, bias=bias,
                 gamma_h=None if gamma is None else float(gamma[h]), norm=norm, mask=mask,
-                bias_t=None if bt is None else bt[b if bt.shape[0] > 1 else 0, h if bt.shape[1] > 1 else 0])
+                bias_t=None if bt is None else bt[b if bt.shape[0] > 1 else 0, h if bt.shape[1] > 1 else 0],
+                with_dbias=with_dbias)
+            dq, dk, dv = res[:3]
+            if with_dbias:
+                dB[b, h] = res[3]
             dQ[b, h] = dq
             dK[b, h // g] += dk
             dV[b, h // g] += dv
+    if with_dbias:
+        return dQ, dK, dV, dB
     return dQ, dK, dV

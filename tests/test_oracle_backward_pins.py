@@ -187,6 +187,16 @@ def test_bias_tensor_gradients(norm, mask):
         np.testing.assert_allclose(dQ, finite_difference(fwd, Q, dO), atol=2e-7)
         np.testing.assert_allclose(dK, finite_difference(fwd, K, dO), atol=2e-7)
         np.testing.assert_allclose(dV, finite_difference(fwd, V, dO), atol=2e-7)
+    # the gradient with respect to the bias tensor itself, per batch and head: finite differences in the tensor;
+    # for a tensor shared over the batch (or heads) the finite difference is the sum over the sharers
+    for shape in ((B, Hq, Lq, Lk), (1, Hq, Lq, Lk), (1, 1, Lq, Lk)):
+        bt = rnd(*shape)
+        kw = dict(scale=0.6, score_mod="bias_tensor", norm=norm, mask=mask)
+        dB = attention_backward(Q, K, V, dO, bias_tensor=bt, with_dbias=True, **kw)[3]
+        fd = finite_difference(lambda: attention(Q, K, V, bias_tensor=bt, **kw), bt, dO)
+        want = dB.sum(axis=0, keepdims=True) if shape[0] == 1 else dB
+        want = want.sum(axis=1, keepdims=True) if shape[1] == 1 else want
+        np.testing.assert_allclose(want, fd, atol=3e-7)
     a = attention_backward(Q, K, V, dO, scale=0.6, score_mod="bias", bias=0.4, norm=norm, mask=mask)
     b = attention_backward(Q, K, V, dO, scale=0.6, score_mod="bias_tensor", bias_tensor=np.full((1, 1, Lq, Lk), 0.4), norm=norm,
                            mask=mask)
