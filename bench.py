@@ -400,7 +400,7 @@ def main():
                     if name == "plain":
                         A.ae_attn_backward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), *tail)
                     else:
-                        A.ae_attn_backward_bias(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), btd.data_ptr(), *tail)
+                        A.ae_attn_backward_bias(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), btd.data_ptr(), *tail[:6], 0, 0, *tail[6:])
                 for _ in range(3):
                     bcall()
                 torch.cuda.synchronize()

@@ -232,11 +232,17 @@ ae_status_t ae_attn_backward(const ae_attn_t *h, const void *Q, const void *K,
 
 /* ae_attn_backward for a handle created with AE_MOD_BIAS_TENSOR: the same, with
  * the bias tensor of the forward pass (device, bf16, 16-byte aligned, read only).
- * The gradient with respect to the bias itself (it equals dS') is not formed.   */
+ * dBias (may be NULL): device, bf16, [B, H_q, L_q, dbias_row_stride], 8-byte
+ * aligned, row stride a multiple of 4 elements and >= L_k: receives the gradient
+ * with respect to the bias, which is dS', per batch element and query head -- for
+ * a bias shared over batch or heads the caller sums over the sharers.  Entries
+ * hidden by the mask are NOT written (their gradient is 0): clear the buffer
+ * before the call where a mask is in use.                                       */
 ae_status_t ae_attn_backward_bias(const ae_attn_t *h, const void *Q, const void *K,
                                   const void *V, const void *bias, const void *O,
                                   const void *dO, const void *stats, void *dQ,
-                                  void *dK, void *dV, void *workspace,
+                                  void *dK, void *dV, void *dBias,
+                                  int64_t dbias_row_stride, void *workspace,
                                   size_t workspace_bytes, void *stream);
 
 /* Frees the handle.  NULL is a no-op.                                         */

@@ -55,7 +55,7 @@ _lib.ae_attn_backward_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size
 _lib.ae_attn_backward_workspace_bytes.restype = C.c_int
 _lib.ae_attn_backward.argtypes = [C.c_void_p] * 11 + [C.c_size_t, C.c_void_p]
 _lib.ae_attn_backward.restype = C.c_int
-_lib.ae_attn_backward_bias.argtypes = [C.c_void_p] * 12 + [C.c_size_t, C.c_void_p]
+_lib.ae_attn_backward_bias.argtypes = [C.c_void_p] * 12 + [C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.ae_attn_backward_bias.restype = C.c_int
 _lib.ae_attn_destroy.argtypes = [C.c_void_p]
 _lib.ae_attn_destroy.restype = C.c_int
@@ -144,9 +144,12 @@ def ae_attn_backward(handle: int, Q: int, K: int, V: int, O: int, dO: int, stats
 
 
 def ae_attn_backward_bias(handle: int, Q: int, K: int, V: int, bias: int, O: int, dO: int, stats: int, dQ: int, dK: int,
-                          dV: int, workspace: int, workspace_bytes: int, stream: int = 0) -> None:
-    """ae_attn_backward for a handle created with score_mod "bias_tensor" (bias: device address of the tensor)."""
-    _check(_lib.ae_attn_backward_bias(handle, Q, K, V, bias, O, dO, stats, dQ, dK, dV, workspace, workspace_bytes, stream))
+                          dV: int, dBias: int, dbias_row_stride: int, workspace: int, workspace_bytes: int,
+                          stream: int = 0) -> None:
+    """ae_attn_backward for a handle created with score_mod "bias_tensor" (bias: device address of the tensor; dBias:
+    0, or the address of a zero-filled bf16 buffer [B, H_q, L_q, dbias_row_stride] for the bias gradient)."""
+    _check(_lib.ae_attn_backward_bias(handle, Q, K, V, bias, O, dO, stats, dQ, dK, dV, dBias, dbias_row_stride, workspace,
+                                      workspace_bytes, stream))
 
 
 def ae_attn_forward_bias(handle: int, Q: int, K: int, V: int, bias: int, O: int, stats: int = 0, stream: int = 0) -> None:
@@ -259,11 +262,11 @@ def _bias_strides(bias_tensor, B, H_q, L_q, L_k):
 
 
 def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
-                       mask="none", window=0, stream=None, workspace=None, bias_tensor=None):
+                       mask="none", window=0, stream=None, workspace=None, bias_tensor=None, want_dbias=False):
     """Runs the HIP backward pass on device tensors: Q, K, V bf16 [B, H, L, D] (last dim contiguous), O the
     forward output (fp32 or bf16), dO bf16 contiguous, stats the fp32 row statistic of the forward pass (O and
     stats may be None for sigmoid and no normalization); window: keys per query for mask="sliding_window".  Returns (dQ, dK, dV)
-    as contiguous fp32 tensors."""
+    as contiguous fp32 tensors; with want_dbias also the bias gradient, bf16 [B, H_q, L_q, L_k] (per batch and head)."""
     import torch
 
     if not (Q.is_cuda and K.is_cuda and V.is_cuda and dO.is_cuda):
@@ -291,12 +294,19 @@ def attention_backward(Q, K, V, O, dO, stats, *, scale, score_mod="none", bias=0
             tail = (0 if O is None else O.data_ptr(), dO.data_ptr(), 0 if stats is None else stats.data_ptr(), dQ.data_ptr(),
                     dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                     s.cuda_stream)
+            dB = None
             if bias_tensor is not None:
-                ae_attn_backward_bias(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), bias_tensor.data_ptr(), *tail)
+                ld = (L_k + 3) // 4 * 4
+                if want_dbias:
+                    dB = torch.zeros((B, H_q, L_q, ld), dtype=torch.bfloat16, device=Q.device)
+                ae_attn_backward_bias(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), bias_tensor.data_ptr(), *tail[:6],
+                                      0 if dB is None else dB.data_ptr(), ld, *tail[6:])
             else:
                 ae_attn_backward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), *tail)
     finally:
         ae_attn_destroy(h)
+    if want_dbias:
+        return dQ, dK, dV, dB[..., :L_k]
     return dQ, dK, dV
 
 

@@ -398,7 +398,7 @@ ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t* h, size_t* bytes) 
 
 static ae_status_t backward_impl(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* bias, const void* O,
                                  const void* dO, const void* stats, void* dQ, void* dK, void* dV, void* workspace,
-                                 size_t workspace_bytes, void* stream) {
+                                 size_t workspace_bytes, void* stream, void* dBias = nullptr, int64_t dbias_ld = 0) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: null handle");
   if ((h->desc.score_mod == AE_MOD_BIAS_TENSOR) != (bias != nullptr))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: a handle with AE_MOD_BIAS_TENSOR, and only such a handle, runs through "
@@ -443,6 +443,8 @@ static ae_status_t backward_impl(const ae_attn_t* h, const void* Q, const void* 
   p.lse = static_cast<const float*>(stats);
   p.delta = static_cast<float*>(workspace);
   p.bias = static_cast<const __bf16*>(bias);
+  p.dbias = static_cast<__bf16*>(dBias);
+  p.dbias_ld = dbias_ld;
   for (int a = 0; a < 3; ++a) p.bs[a] = h->params.bs[a];
   p.dQ = static_cast<float*>(dQ);
   p.dK = static_cast<float*>(dK);
@@ -483,9 +485,19 @@ ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, c
 
 ae_status_t ae_attn_backward_bias(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* bias,
                                   const void* O, const void* dO, const void* stats, void* dQ, void* dK, void* dV,
-                                  void* workspace, size_t workspace_bytes, void* stream) {
+                                  void* dBias, int64_t dbias_row_stride, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
   if (!bias) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward_bias: null bias tensor");
-  return backward_impl(h, Q, K, V, bias, O, dO, stats, dQ, dK, dV, workspace, workspace_bytes, stream);
+  if (dBias) {
+    if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward_bias: null handle");
+    if (((uintptr_t)dBias & 7) || dbias_row_stride < h->desc.L_k || dbias_row_stride % 4 != 0)
+      return fail(AE_ERR_INVALID_ARG,
+                  "ae_attn_backward_bias: dBias must be 8-byte aligned, its row stride a multiple of 4 elements and >= L_k");
+    if (dBias == bias || dBias == dQ || dBias == dK || dBias == dV || dBias == workspace || dBias == Q || dBias == K ||
+        dBias == V || dBias == O || dBias == dO)
+      return fail(AE_ERR_INVALID_ARG, "ae_attn_backward_bias: dBias aliases another buffer");
+  }
+  return backward_impl(h, Q, K, V, bias, O, dO, stats, dQ, dK, dV, workspace, workspace_bytes, stream, dBias, dbias_row_stride);
 }
 
 ae_status_t ae_attn_destroy(ae_attn_t* h) {

@@ -59,6 +59,10 @@ struct BwdParams {
   const __bf16* bias;
   int64_t bs[3];
   float bunit;
+  // optional gradient of the bias tensor, bf16 [B, H_q, L_q, dbias_ld] (per batch and head, not summed over
+  // sharers); written by the query-side kernel for the sub-tiles it visits
+  __bf16* dbias;
+  int64_t dbias_ld;
   // causal kernels: key j is also hidden from query i if j <= i + (L_k - L_q) - window (sliding
   // window); L_q + L_k for the plain causal mask, which hides nothing more
   int window;
@@ -461,6 +465,20 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
         pv = x[r] > 0.f ? dp[r] : 0.f;
       }
       w[r] = pv;
+    }
+    if constexpr (C::BIAS && !C::KV_SIDE) {
+      // the bias enters S' with slope 1: its gradient is dS' itself, 4 x 4 consecutive keys of the lane's own row
+      if (p.dbias != nullptr && own < p.L_q) {
+        __bf16* drow = p.dbias + (((int64_t)b * p.H_q + ho) * p.L_q + own) * p.dbias_ld + o0 + 4 * half;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          if (o0 + 8 * q4 + 4 * half < p.L_k) {  // (a group across the last key writes into the row's padding)
+            bf16x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (__bf16)w[4 * q4 + e];
+            *reinterpret_cast<bf16x4*>(drow + 8 * q4) = v;
+          }
+      }
     }
     // G^T += Y^T W: per 16-row step t, the DB blocks of Y1^T (dQ^T, dK^T), then (key side) the DB2 blocks of Y2^T
     if constexpr (C::BATCH) {

@@ -231,6 +231,20 @@ def test_bias_tensor_descriptor_and_entry_point_checks():
             with pytest.raises(A.AeAttnError) as ei:
                 A.ae_attn_forward_bias(h, *args)
             assert ei.value.status == A.AE_ERR_INVALID_ARG
+        # backward with the bias gradient: Q K V bias O dO stats dQ dK dV | dBias, row stride | workspace, bytes
+        ok = [256 * (i + 1) for i in range(10)]
+        ws = A.ae_attn_backward_workspace_bytes(h)
+        for db, ld in ((8192 + 4, 104),        # misaligned
+                       (8192, 96),             # row stride < L_k
+                       (8192, 102),            # row stride not a multiple of 4
+                       (ok[3], 104),           # aliases the bias tensor
+                       (ok[7], 104)):          # aliases dQ
+            with pytest.raises(A.AeAttnError) as ei:
+                A.ae_attn_backward_bias(h, *ok, db, ld, 1 << 16, ws)
+            assert ei.value.status == A.AE_ERR_INVALID_ARG, (db, ld, A.ae_attn_last_error())
+        with pytest.raises(A.AeAttnError) as ei:      # null bias tensor
+            A.ae_attn_backward_bias(h, *ok[:3], 0, *ok[4:], 0, 0, 1 << 16, ws)
+        assert ei.value.status == A.AE_ERR_INVALID_ARG
     finally:
         A.ae_attn_destroy(h)
     h = A.ae_attn_create(**_ok_desc())
