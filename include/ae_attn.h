@@ -274,6 +274,46 @@ const char *ae_attn_last_error(void);
 /* Library version as major * 100 + minor.                                     */
 int32_t ae_attn_version(void);
 
+/* ---- Recurrent pattern: chunk-parallel retention ------------------------------
+ *
+ * The paper's second pattern (Section 4.1, "Attention Patterns and Templates":
+ * K@V first, then Q@h, iterated over a compressed state h; Table 2, "Retention
+ * Recurrent"), with a constant decay per head as the state modification
+ * (Section 4.1, h_mod: h x decay):
+ *     h_t = gamma[head] * h_{t-1} + k_t^T v_t   (h_0 = 0, h: [D_qk x D_v])
+ *     o_t = scale * q_t h_t
+ * evaluated chunk by chunk so that the matrix units do the work (Section 4.2,
+ * kernel templates for recurrent patterns): inside a chunk the parallel-pattern
+ * kernel, across chunks one [D_qk x D_v] state per chunk, a scan over the chunks
+ * and a read-out.  The work grows linearly with L.
+ *
+ * Layouts: Q, K [B, H, L, D_qk] and V [B, H, L, D_v] bf16, O [B, H, L, D_v]
+ * fp32, all contiguous, device memory, 16-byte aligned; the caller owns them.
+ * gamma: host array [H], each in (0, 1] (read by create only).  chunk: 64, 128
+ * or 256 tokens (256 fills the parallel kernel's 256-row tile).  Head dims
+ * 64/64 and 128/128; H <= AE_MAX_DECAY_HEADS.
+ * The workspace (device memory, 256-byte aligned, owned by the caller, size
+ * from ae_recurrent_workspace_bytes; 0 when L <= chunk) holds the per-chunk
+ * states: 6 bytes x B x H x (chunks - 1) x D_qk x D_v.  Calls that share a
+ * workspace must not overlap.  Nothing allocates device memory; all kernels are
+ * enqueued on `stream` (a hipStream_t, NULL = default stream) and the call
+ * returns without waiting.
+ * Errors: AE_ERR_INVALID_ARG (nothing is launched), AE_ERR_UNSUPPORTED,
+ * AE_ERR_NOMEM (create), AE_ERR_HIP.                                            */
+typedef struct ae_recurrent ae_recurrent_t;
+typedef struct {
+  int32_t B, H, L, D_qk, D_v;
+  int32_t chunk;
+  float scale;        /* finite and non-zero */
+  const float *gamma; /* host array [H] */
+} ae_recurrent_desc_t;
+
+ae_status_t ae_recurrent_create(const ae_recurrent_desc_t *desc, ae_recurrent_t **out);
+ae_status_t ae_recurrent_workspace_bytes(const ae_recurrent_t *h, size_t *bytes);
+ae_status_t ae_recurrent_forward(const ae_recurrent_t *h, const void *Q, const void *K, const void *V, void *O,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+ae_status_t ae_recurrent_destroy(ae_recurrent_t *h); /* NULL is allowed */
+
 #ifdef __cplusplus
 }
 #endif

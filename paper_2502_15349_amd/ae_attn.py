@@ -57,6 +57,21 @@ _lib.ae_attn_backward.argtypes = [C.c_void_p] * 11 + [C.c_size_t, C.c_void_p]
 _lib.ae_attn_backward.restype = C.c_int
 _lib.ae_attn_backward_bias.argtypes = [C.c_void_p] * 12 + [C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.ae_attn_backward_bias.restype = C.c_int
+
+
+class ae_recurrent_desc_t(C.Structure):
+    _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("L", C.c_int32), ("D_qk", C.c_int32), ("D_v", C.c_int32),
+                ("chunk", C.c_int32), ("scale", C.c_float), ("gamma", C.POINTER(C.c_float))]
+
+
+_lib.ae_recurrent_create.argtypes = [C.POINTER(ae_recurrent_desc_t), C.POINTER(C.c_void_p)]
+_lib.ae_recurrent_create.restype = C.c_int
+_lib.ae_recurrent_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+_lib.ae_recurrent_workspace_bytes.restype = C.c_int
+_lib.ae_recurrent_forward.argtypes = [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
+_lib.ae_recurrent_forward.restype = C.c_int
+_lib.ae_recurrent_destroy.argtypes = [C.c_void_p]
+_lib.ae_recurrent_destroy.restype = C.c_int
 _lib.ae_attn_destroy.argtypes = [C.c_void_p]
 _lib.ae_attn_destroy.restype = C.c_int
 _lib.ae_attn_query.argtypes = [C.c_void_p] + [C.POINTER(C.c_int32)] * 5
@@ -189,6 +204,65 @@ def ae_attn_query(handle: int) -> dict:
 
 
 # ---- convenience for torch callers (still marshalling only) -------------------
+def ae_recurrent_create(*, B: int, H: int, L: int, D_qk: int, D_v: int, chunk: int, scale: float,
+                        gamma: Optional[Sequence[float]]) -> int:
+    """Handle for chunk-parallel recurrent retention (h_t = gamma h_{t-1} + k_t^T v_t, o_t = scale q_t h_t)."""
+    d = ae_recurrent_desc_t(B=B, H=H, L=L, D_qk=D_qk, D_v=D_v, chunk=chunk, scale=scale)
+    keep = None
+    if gamma is not None:
+        keep = (C.c_float * len(gamma))(*[float(g) for g in gamma])
+        d.gamma = C.cast(keep, C.POINTER(C.c_float))
+    out = C.c_void_p()
+    _check(_lib.ae_recurrent_create(C.byref(d), C.byref(out)))
+    return out.value
+
+
+def ae_recurrent_workspace_bytes(handle: int) -> int:
+    n = C.c_size_t()
+    _check(_lib.ae_recurrent_workspace_bytes(handle, C.byref(n)))
+    return n.value
+
+
+def ae_recurrent_forward(handle: int, Q: int, K: int, V: int, O: int, workspace: int, workspace_bytes: int,
+                         stream: int = 0) -> None:
+    _check(_lib.ae_recurrent_forward(handle, Q, K, V, O, workspace, workspace_bytes, stream))
+
+
+def ae_recurrent_destroy(handle: Optional[int]) -> None:
+    _check(_lib.ae_recurrent_destroy(handle))
+
+
+def retention_recurrent(Q, K, V, *, scale, gamma, chunk=256, out=None, workspace=None, stream=None):
+    """Recurrent retention on contiguous bf16 device tensors Q, K [B, H, L, D_qk], V [B, H, L, D_v];
+    returns O [B, H, L, D_v] fp32.  workspace: device byte tensor of ae_recurrent_workspace_bytes() bytes
+    (allocated here if not given)."""
+    import torch
+
+    for t in (Q, K, V):
+        if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 4 or not t.is_contiguous():
+            raise ValueError("Q, K, V must be contiguous 4-D bf16 device tensors; there is no CPU path")
+    B, H, L, D_qk = Q.shape
+    D_v = V.shape[3]
+    if K.shape != Q.shape or V.shape[:3] != Q.shape[:3]:
+        raise ValueError("K / V shape does not match Q")
+    if out is None:
+        out = torch.empty((B, H, L, D_v), dtype=torch.float32, device=Q.device)
+    if out.dtype != torch.float32 or tuple(out.shape) != (B, H, L, D_v) or not out.is_contiguous():
+        raise ValueError("O must be a contiguous fp32 tensor [B, H, L, D_v]")
+    h = ae_recurrent_create(B=B, H=H, L=L, D_qk=D_qk, D_v=D_v, chunk=chunk, scale=scale, gamma=gamma)
+    try:
+        s = torch.cuda.current_stream(Q.device) if stream is None else stream
+        with torch.cuda.device(Q.device):
+            need = ae_recurrent_workspace_bytes(h)
+            if need and workspace is None:
+                workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+            ae_recurrent_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
+                                 workspace.data_ptr() if need else 0, workspace.numel() if need else 0, s.cuda_stream)
+    finally:
+        ae_recurrent_destroy(h)
+    return out
+
+
 def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",
                       mask="none", out=None, stream=None, out_dtype=None, stats=None, window=0, kv_splits=0,
                       workspace=None, bias_tensor=None):

@@ -12,6 +12,7 @@
 
 #include "bwd.hpp"
 #include "dispatch.hpp"
+#include "recurrent.hpp"
 
 namespace {
 
@@ -521,5 +522,154 @@ const char* ae_attn_kernel_name(const ae_attn_t* h) { return h ? h->kernel->name
 const char* ae_attn_last_error(void) { return g_err; }
 
 int32_t ae_attn_version(void) { return 1; }
+
+}  // extern "C"
+
+// ---- recurrent pattern: chunk-parallel retention -----------------------------------------------------------
+// The intra-chunk part is the parallel-pattern kernel (per-head decay, causal, no normalization) run on the
+// chunks as if they were batch entries: batch' = chunk index (stride chunk * D), heads' = `fold` batch entries x H
+// heads (stride L * D, which is uniform over (batch, head) in a contiguous [B, H, L, D] tensor).  The decay table
+// of that kernel holds 256 heads, so larger B * H take one launch per batch entry.
+struct ae_recurrent {
+  ae_recurrent_desc_t desc;
+  ae_attn_t* full;  // all chunks of full length; null if L < chunk
+  ae_attn_t* tail;  // the short last chunk; null if L is a multiple of chunk
+  ae::DecayTable decay;
+  int fold, n_full, n_chunks, tail_len;
+  size_t ws_bytes;
+};
+
+extern "C" {
+
+ae_status_t ae_recurrent_create(const ae_recurrent_desc_t* d, ae_recurrent_t** out) {
+  if (out) *out = nullptr;
+  if (!d || !out) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_create: null argument");
+  if (d->B < 1 || d->H < 1 || d->L < 1) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_create: B, H, L must be >= 1");
+  if (!std::isfinite(d->scale) || d->scale == 0.f) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_create: scale must be finite and non-zero");
+  if (!d->gamma) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_create: gamma missing");
+  if (d->H > AE_MAX_DECAY_HEADS) return fail(AE_ERR_UNSUPPORTED, "ae_recurrent_create: at most %d heads", AE_MAX_DECAY_HEADS);
+  for (int i = 0; i < d->H; ++i)
+    if (!std::isfinite(d->gamma[i]) || d->gamma[i] <= 0.f || d->gamma[i] > 1.f)
+      return fail(AE_ERR_INVALID_ARG, "ae_recurrent_create: gamma[%d] must be in (0, 1]", i);
+  if (d->chunk != 64 && d->chunk != 128 && d->chunk != 256)
+    return fail(AE_ERR_UNSUPPORTED, "ae_recurrent_create: chunk must be 64, 128 or 256");
+  if (!ae::recurrent_supported(d->D_qk, d->D_v))
+    return fail(AE_ERR_UNSUPPORTED, "ae_recurrent_create: head dims %d/%d not built (64/64, 128/128)", d->D_qk, d->D_v);
+  if ((int64_t)d->L * std::max(d->D_qk, d->D_v) * 2 >= (int64_t)1 << 32)
+    return fail(AE_ERR_UNSUPPORTED, "ae_recurrent_create: one (batch, head) slab must span less than 4 GiB");
+  ae_recurrent* h = new (std::nothrow) ae_recurrent();
+  if (!h) return fail(AE_ERR_NOMEM, "ae_recurrent_create: out of host memory");
+  h->desc = *d;
+  h->desc.gamma = nullptr;
+  h->full = h->tail = nullptr;
+  h->fold = (int64_t)d->B * d->H <= AE_MAX_DECAY_HEADS ? d->B : 1;
+  h->n_full = d->L / d->chunk;
+  h->tail_len = d->L % d->chunk;
+  h->n_chunks = h->n_full + (h->tail_len ? 1 : 0);
+  std::memset(&h->decay, 0, sizeof(h->decay));
+  for (int i = 0; i < d->H; ++i) h->decay.log2_gamma[i] = std::log2(d->gamma[i]);
+  float gam[AE_MAX_DECAY_HEADS];
+  for (int i = 0; i < h->fold * d->H; ++i) gam[i] = d->gamma[i % d->H];
+  ae_attn_desc_t a;
+  std::memset(&a, 0, sizeof(a));
+  a.H_q = a.H_kv = h->fold * d->H;
+  a.D_qk = d->D_qk;
+  a.D_v = d->D_v;
+  a.score_mod = AE_MOD_HEAD_DECAY;
+  a.gamma = gam;
+  a.norm = AE_NORM_NONE;
+  a.mask = AE_MASK_CAUSAL;
+  a.scale = d->scale;
+  a.out_dtype = AE_OUT_F32;
+  const int64_t L = d->L;
+  auto strides = [&](int64_t* st, int D) { st[0] = (int64_t)d->chunk * D; st[1] = L * D; st[2] = D; };
+  strides(a.q_stride, d->D_qk);
+  strides(a.k_stride, d->D_qk);
+  strides(a.v_stride, d->D_v);
+  strides(a.o_stride, d->D_v);
+  ae_status_t st = AE_OK;
+  if (h->n_full) {
+    a.B = h->n_full;
+    a.L_q = a.L_k = d->chunk;
+    st = ae_attn_create(&a, &h->full);
+  }
+  if (st == AE_OK && h->tail_len) {
+    a.B = 1;
+    a.L_q = a.L_k = h->tail_len;
+    st = ae_attn_create(&a, &h->tail);
+  }
+  if (st != AE_OK) {
+    ae_attn_destroy(h->full);
+    ae_attn_destroy(h->tail);
+    delete h;
+    return st;  // the message of the inner call stands
+  }
+  h->ws_bytes = h->n_chunks > 1 ? (size_t)d->B * d->H * (h->n_chunks - 1) * d->D_qk * d->D_v * 6 : 0;
+  *out = h;
+  return AE_OK;
+}
+
+ae_status_t ae_recurrent_workspace_bytes(const ae_recurrent_t* h, size_t* bytes) {
+  if (!h || !bytes) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_workspace_bytes: null argument");
+  *bytes = h->ws_bytes;
+  return AE_OK;
+}
+
+ae_status_t ae_recurrent_forward(const ae_recurrent_t* h, const void* Q, const void* K, const void* V, void* O,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: null handle");
+  if (!Q || !K || !V || !O) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: null pointer");
+  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
+    return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: Q, K, V, O must be 16-byte aligned");
+  if (O == Q || O == K || O == V) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: O aliases an input");
+  if (h->ws_bytes) {
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < h->ws_bytes)
+      return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: workspace missing, not 256-byte aligned, or smaller than %zu bytes", h->ws_bytes);
+    if (workspace == O || workspace == Q || workspace == K || workspace == V)
+      return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: workspace aliases another buffer");
+  }
+  const ae_recurrent_desc_t& d = h->desc;
+  const int64_t L = d.L;
+  // intra-chunk part: O = decay-masked causal attention inside every chunk
+  for (int b = 0; b < d.B; b += h->fold) {
+    const int64_t e0 = (int64_t)b * d.H * L;  // first row of this launch's (batch, head) slabs
+    for (int part = 0; part < 2; ++part) {
+      const ae_attn_t* a = part ? h->tail : h->full;
+      if (!a) continue;
+      const int64_t r0 = e0 + (part ? (int64_t)h->n_full * d.chunk : 0);
+      const ae_status_t st = ae_attn_forward(a, static_cast<const __bf16*>(Q) + r0 * d.D_qk, static_cast<const __bf16*>(K) + r0 * d.D_qk,
+                                             static_cast<const __bf16*>(V) + r0 * d.D_v, static_cast<float*>(O) + r0 * d.D_v, stream);
+      if (st != AE_OK) return st;
+    }
+  }
+  if (h->n_chunks < 2) return AE_OK;
+  // carried state: per-chunk sums, scan over chunks, read-out added to O
+  ae::RecParams p;
+  p.Q = static_cast<const __bf16*>(Q);
+  p.K = static_cast<const __bf16*>(K);
+  p.V = static_cast<const __bf16*>(V);
+  p.O = static_cast<float*>(O);
+  const size_t n_state = (size_t)d.B * d.H * (h->n_chunks - 1) * d.D_qk * d.D_v;
+  p.S = static_cast<float*>(workspace);
+  p.HT = reinterpret_cast<__bf16*>(static_cast<char*>(workspace) + n_state * 4);
+  p.B = d.B;
+  p.H = d.H;
+  p.L = d.L;
+  p.chunk = d.chunk;
+  p.n_chunks = h->n_chunks;
+  p.scale = d.scale;
+  const hipError_t e = ae::launch_recurrent_inter(p, h->decay, d.D_qk, d.D_v, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_recurrent_forward: %s", hipGetErrorString(e));
+  return AE_OK;
+}
+
+ae_status_t ae_recurrent_destroy(ae_recurrent_t* h) {
+  if (h) {
+    ae_attn_destroy(h->full);
+    ae_attn_destroy(h->tail);
+    delete h;
+  }
+  return AE_OK;
+}
 
 }  // extern "C"

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libae_attn.so n
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "ae_attn.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(ae_(?:attn|calib)_[a-z0-9_]+)\s*\(", hdr))
+    names = set(re.findall(r"\b(ae_(?:attn|calib|recurrent)_[a-z0-9_]+)\s*\(", hdr))
     assert {"ae_attn_create", "ae_attn_forward", "ae_attn_destroy", "ae_attn_query", "ae_calib_mfma_bf16"} <= names
     lib = ctypes.CDLL(LIB)
     for n in names:
@@ -296,3 +296,37 @@ def test_calibration_kernel_rejects_bad_arguments_without_launching():
         with pytest.raises(A.AeAttnError) as ei:
             A.ae_calib_mfma_bf16(*args)
         assert ei.value.status == A.AE_ERR_INVALID_ARG
+
+
+def test_recurrent_descriptor_and_entry_point_checks():
+    from paper_2502_15349_amd import ae_attn as A
+    ok = dict(B=2, H=4, L=300, D_qk=128, D_v=128, chunk=64, scale=0.1, gamma=[0.9, 0.95, 0.99, 1.0])
+    h = A.ae_recurrent_create(**ok)
+    try:
+        need = A.ae_recurrent_workspace_bytes(h)
+        assert need == 2 * 4 * 4 * 128 * 128 * 6          # 5 chunks: a state in front of all but the first
+        good = (1 << 20, 2 << 20, 3 << 20, 4 << 20, 5 << 20)
+        for args, nbytes in (((0,) + good[1:], need), (good[:3] + (0,) + good[4:], need), ((good[0] + 8,) + good[1:], need),
+                             (good[:3] + (good[0],) + good[4:], need),             # O aliases Q
+                             (good[:4] + (0,), need), (good[:4] + (good[4] + 64,), need), (good, need - 1),
+                             (good[:4] + (good[3],), need)):                       # workspace aliases O
+            with pytest.raises(A.AeAttnError) as ei:
+                A.ae_recurrent_forward(h, *args, nbytes)
+            assert ei.value.status == A.AE_ERR_INVALID_ARG, (args, A.ae_attn_last_error())
+        with pytest.raises(A.AeAttnError):
+            A.ae_recurrent_forward(None, *good, need)
+    finally:
+        A.ae_recurrent_destroy(h)
+    A.ae_recurrent_destroy(None)
+    one = dict(ok, L=64)                                   # a single chunk carries no state
+    h = A.ae_recurrent_create(**one)
+    assert A.ae_recurrent_workspace_bytes(h) == 0
+    A.ae_recurrent_destroy(h)
+    for patch, status in ((dict(chunk=100), A.AE_ERR_UNSUPPORTED), (dict(D_qk=192), A.AE_ERR_UNSUPPORTED),
+                          (dict(D_qk=256, D_v=512), A.AE_ERR_UNSUPPORTED), (dict(H=300, gamma=[0.9] * 300), A.AE_ERR_UNSUPPORTED),
+                          (dict(gamma=[0.9, 0.9, 0.9, 1.5]), A.AE_ERR_INVALID_ARG), (dict(gamma=[0.9, 0.0, 0.9, 0.9]), A.AE_ERR_INVALID_ARG),
+                          (dict(gamma=None), A.AE_ERR_INVALID_ARG), (dict(L=0), A.AE_ERR_INVALID_ARG),
+                          (dict(scale=float("nan")), A.AE_ERR_INVALID_ARG), (dict(B=0), A.AE_ERR_INVALID_ARG)):
+        with pytest.raises(A.AeAttnError) as ei:
+            A.ae_recurrent_create(**dict(ok, **patch))
+        assert ei.value.status == status, (patch, A.ae_attn_last_error())

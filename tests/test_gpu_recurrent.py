@@ -1,0 +1,105 @@
+"""GPU parity of the recurrent pattern: ae_recurrent_forward (chunk-parallel retention, through the C ABI) against
+the token-by-token fp64 oracle on the same seeded bf16 inputs.  Bar as for the parallel pattern (bf16 operands,
+bf16 chunk states into the read-out MFMAs, fp32 accumulation and fp32 running state): max-abs <= 1e-2 and
+mean-abs <= 1e-3, relative to max(1, the largest |reference| of the row)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle.retention_recurrent_oracle import retention_recurrent as oracle_recurrent
+from oracle.retention_recurrent_oracle import retention_recurrent_head
+from paper_2502_15349_amd.workloads import Workload, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 1e-2, 1e-3
+
+
+@pytest.fixture(scope="module")
+def A():
+    from paper_2502_15349_amd import ae_attn
+    return ae_attn
+
+
+def _check(got, ref, what):
+    rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+    err = np.abs(got - ref) / rs
+    print(f"{what}: max_abs {err.max():.3e} mean_abs {err.mean():.3e} |ref|max {np.abs(ref).max():.3e}", flush=True)
+    assert np.isfinite(got).all()
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS, what
+
+
+def _workload(name, cid, B, H, L, D):
+    return Workload(name, cid, B, H, H, L, L, D, D, score_mod="head_decay", norm="none", mask="causal")
+
+
+def _gammas(H):
+    # RetNet's per-head rates 1 - 2^(-5-h), cycled, plus the undamped and a fast-forgetting head
+    base = [1.0 - 2.0 ** (-5 - i) for i in range(6)] + [1.0, 0.5]
+    return [base[i % len(base)] for i in range(H)]
+
+
+# (L, chunk): several chunks with a short last one; exact multiples; a single chunk; shorter than a chunk; one row
+CASES = [(300, 64), (700, 256), (512, 256), (384, 128), (64, 64), (50, 128), (1, 64), (257, 256), (129, 64)]
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("L,chunk", CASES)
+def test_recurrent_matches_oracle(A, D, L, chunk):
+    w = _workload(f"rec_d{D}_L{L}_c{chunk}", 700 + D + L % 97, 2, 3, L, D)
+    Q, K, V = make_inputs(w)
+    gam = _gammas(w.H_q)
+    scale = 1.0 / math.sqrt(D)
+    print(f"case {w.name}", flush=True)
+    dev = torch.device("cuda:0")
+    O = A.retention_recurrent(Q.to(dev), K.to(dev), V.to(dev), scale=scale, gamma=gam, chunk=chunk)
+    torch.cuda.synchronize()
+    ref = oracle_recurrent(Q.float().numpy(), K.float().numpy(), V.float().numpy(), scale=scale, gamma=gam)
+    _check(O.cpu().double().numpy(), ref, w.name)
+
+
+def test_many_heads_take_one_launch_per_batch_entry(A):
+    # B * H beyond the decay table of the intra-chunk kernel: the batch entries are launched one by one
+    w = _workload("rec_many_heads", 791, 5, 64, 200, 64)
+    Q, K, V = make_inputs(w)
+    gam = _gammas(64)
+    dev = torch.device("cuda:0")
+    print(f"case {w.name}", flush=True)
+    O = A.retention_recurrent(Q.to(dev), K.to(dev), V.to(dev), scale=0.125, gamma=gam, chunk=64).cpu().double().numpy()
+    for b, h in ((0, 0), (2, 7), (4, 63), (3, 38)):
+        ref = retention_recurrent_head(Q[b, h].float().numpy(), K[b, h].float().numpy(), V[b, h].float().numpy(), scale=0.125, gamma_h=gam[h])
+        _check(O[b, h], ref, f"{w.name} b{b} h{h}")
+
+
+def test_chunk_sizes_agree_and_workspace_is_reusable(A):
+    # the same inputs through every chunk size (different cuts of the same sum), the workspace handed in and reused
+    w = _workload("rec_chunks", 792, 1, 4, 1000, 128)
+    Q, K, V = make_inputs(w)
+    dev = torch.device("cuda:0")
+    Qd, Kd, Vd = Q.to(dev), K.to(dev), V.to(dev)
+    gam = _gammas(4)
+    ref = oracle_recurrent(Q.float().numpy(), K.float().numpy(), V.float().numpy(), scale=0.09, gamma=gam)
+    ws = torch.empty(1 << 24, dtype=torch.uint8, device=dev)
+    for chunk in (64, 128, 256, 64):
+        print(f"case {w.name} chunk {chunk}", flush=True)
+        O = A.retention_recurrent(Qd, Kd, Vd, scale=0.09, gamma=gam, chunk=chunk, workspace=ws)
+        torch.cuda.synchronize()
+        _check(O.cpu().double().numpy(), ref, f"{w.name} chunk {chunk}")
+
+
+def test_sampled_rows_at_benchmark_size(A):
+    # the benchmark's launch configuration; the oracle walks three heads to the end
+    B, H, L, D, chunk = 8, 32, 8192, 128, 256
+    w = _workload("rec_b8_h32_s8192_d128", 793, B, H, L, D)
+    Q, K, V = make_inputs(w)
+    gam = [1.0 - 2.0 ** (-5 - (i % 8)) for i in range(H)]
+    dev = torch.device("cuda:0")
+    print(f"case {w.name}", flush=True)
+    O = A.retention_recurrent(Q.to(dev), K.to(dev), V.to(dev), scale=1.0 / math.sqrt(D), gamma=gam, chunk=chunk)
+    torch.cuda.synchronize()
+    for b, h in ((0, 0), (5, 17), (7, 31)):
+        ref = retention_recurrent_head(Q[b, h].float().numpy(), K[b, h].float().numpy(), V[b, h].float().numpy(),
+                                       scale=1.0 / math.sqrt(D), gamma_h=gam[h])
+        _check(O[b, h].cpu().double().numpy(), ref, f"{w.name} b{b} h{h}")
