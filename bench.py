@@ -156,6 +156,9 @@ def main():
     ap.add_argument("--bias-tensor", action="store_true",
                     help="time the forward pass with an additive bias tensor (score_mod bias_tensor) beside the same shape "
                          "without one")
+    ap.add_argument("--recurrent", action="store_true",
+                    help="time the recurrent pattern (chunk-parallel retention, ae_recurrent_forward) per chunk size, beside "
+                         "the parallel form of the same sum; prints one JSON object with a row per shape")
     ap.add_argument("--only", default="", help="with --backward: only the shapes whose name contains this")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device-to-device copy of this many MiB "
@@ -427,6 +430,72 @@ def main():
                   file=sys.stderr, flush=True)
             del Q, K, V, O, btd, dO, grads
         print(json.dumps({"bias_tensor": rows, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS, "dtype": "bf16", "data": "synthetic"}))
+        return
+    if a.recurrent:
+        # Not the contract line.  Retention with a per-head decay as a recurrence: 4 D_qk D_v flop per token (state
+        # update and read-out, as the token-by-token definition does them) over 2 (2 D_qk + D_v) + 4 D_v compulsory
+        # bytes: about 50 flop per byte at 128/128, far under the chip's 300, so the recurrence is priced against HBM.
+        import math
+        from oracle.retention_recurrent_oracle import retention_recurrent_head
+        from paper_2502_15349_amd.workloads import Workload
+        rows = []
+        shapes = [("retention_b8_h32_s2048_d128", 8, 32, 2048, 128), ("retention_b8_h32_s8192_d128", 8, 32, 8192, 128),
+                  ("retention_b1_h32_s32768_d128", 1, 32, 32768, 128), ("retention_b8_h16_s8192_d64", 8, 16, 8192, 64)]
+        for name, B, H, L, D in shapes:
+            if a.only and a.only not in name:
+                continue
+            w = Workload(name, 300 + len(rows), B, H, H, L, L, D, D, score_mod="head_decay", norm="none", mask="causal")
+            Qc, Kc, Vc = make_inputs(w)
+            Q, K, V = Qc.to(dev), Kc.to(dev), Vc.to(dev)
+            gam = [1.0 - 2.0 ** (-5 - (i % 8)) for i in range(H)]   # RetNet's per-head rates, cycled
+            scale = 1.0 / math.sqrt(D)
+            O = torch.empty((B, H, L, D), dtype=torch.float32, device=dev)
+            st = torch.cuda.current_stream()
+
+            def timed(fn, n):
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(st)
+                for _ in range(n):
+                    fn()
+                e1.record(st)
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / n
+            t_par = timed(lambda: A.attention_forward(Q, K, V, scale=scale, score_mod="head_decay", gamma=gam, norm="none",
+                                                      mask="causal", out=O), max(2, a.steps // 4))
+            row = {"workload": name, "B": B, "H": H, "L": L, "D_qk": D, "D_v": D, "parallel_form_ms": round(t_par, 4)}
+            byts = B * H * L * (2 * (2 * D + D) + 4 * D)
+            flop = 4.0 * D * D * B * H * L
+            best = None
+            for chunk in (64, 128, 256):
+                h = A.ae_recurrent_create(B=B, H=H, L=L, D_qk=D, D_v=D, chunk=chunk, scale=scale, gamma=gam)
+                ws = torch.empty(max(A.ae_recurrent_workspace_bytes(h), 256), dtype=torch.uint8, device=dev)
+                t = timed(lambda: A.ae_recurrent_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), ws.data_ptr(),
+                                                         ws.numel(), st.cuda_stream), a.steps)
+                if chunk == 256:   # parity of what the last timed call left in O: one head against the oracle
+                    b_s, h_s = B - 1, H // 2
+                    ref = retention_recurrent_head(Qc[b_s, h_s].float().numpy(), Kc[b_s, h_s].float().numpy(), Vc[b_s, h_s].float().numpy(),
+                                                   scale=scale, gamma_h=gam[h_s])
+                    got = O[b_s, h_s].cpu().double().numpy()
+                    err = float((np.abs(got - ref) / np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)).max())
+                A.ae_recurrent_destroy(h)
+                row[f"chunk{chunk}_ms"] = round(t, 4)
+                if best is None or t < best[1]:
+                    best = (chunk, t)
+                del ws
+            row.update({"best_chunk": best[0], "ms": round(best[1], 4), "tokens_per_s": round(B * L / best[1] * 1e3, 1),
+                        "GBps": round(byts / best[1] / 1e6, 1), "frac_of_hbm_peak": round(byts / best[1] / 1e6 / 8000.0, 4),
+                        "recurrence_tflops": round(flop / best[1] / 1e9, 1), "speedup_vs_parallel_form": round(t_par / best[1], 2),
+                        "parity_max_abs": err})
+            rows.append(row)
+            print(f"# {name:32s} parallel form {t_par:8.4f} ms | chunks 64/128/256: {row['chunk64_ms']:8.4f} {row['chunk128_ms']:8.4f} "
+                  f"{row['chunk256_ms']:8.4f} ms | best {best[1]:8.4f} ms = {byts / best[1] / 1e6:7.1f} GB/s "
+                  f"({100 * byts / best[1] / 1e6 / 8000.0:4.1f} % of HBM peak), {t_par / best[1]:5.2f}x the parallel form, max_abs {err:.2e}",
+                  file=sys.stderr, flush=True)
+            del Q, K, V, O
+        print(json.dumps({"recurrent": rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16", "data": "synthetic"}))
         return
     if a.table2:
         # Not the contract line: the paper's own microbenchmark grid, one row per shape.

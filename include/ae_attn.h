@@ -283,9 +283,10 @@ int32_t ae_attn_version(void);
  *     h_t = gamma[head] * h_{t-1} + k_t^T v_t   (h_0 = 0, h: [D_qk x D_v])
  *     o_t = scale * q_t h_t
  * evaluated chunk by chunk so that the matrix units do the work (Section 4.2,
- * kernel templates for recurrent patterns): inside a chunk the parallel-pattern
- * kernel, across chunks one [D_qk x D_v] state per chunk, a scan over the chunks
- * and a read-out.  The work grows linearly with L.
+ * kernel templates for recurrent patterns): one kernel walks the chunks and
+ * leaves the state in front of each (bf16, [D_qk x D_v]); the parallel-pattern
+ * kernel then starts every chunk's rows from the read-out of that state and
+ * walks the chunk's own keys on top of it.  The work grows linearly with L.
  *
  * Layouts: Q, K [B, H, L, D_qk] and V [B, H, L, D_v] bf16, O [B, H, L, D_v]
  * fp32, all contiguous, device memory, 16-byte aligned; the caller owns them.
@@ -294,7 +295,7 @@ int32_t ae_attn_version(void);
  * 64/64 and 128/128; H <= AE_MAX_DECAY_HEADS.
  * The workspace (device memory, 256-byte aligned, owned by the caller, size
  * from ae_recurrent_workspace_bytes; 0 when L <= chunk) holds the per-chunk
- * states: 6 bytes x B x H x (chunks - 1) x D_qk x D_v.  Calls that share a
+ * states: 2 bytes x B x H x (chunks - 1) x D_qk x D_v.  Calls that share a
  * workspace must not overlap.  Nothing allocates device memory; all kernels are
  * enqueued on `stream` (a hipStream_t, NULL = default stream) and the call
  * returns without waiting.

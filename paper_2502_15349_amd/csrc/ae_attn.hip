@@ -292,9 +292,16 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   return AE_OK;
 }
 
+// Recurrent pattern: where the chunk-as-batch launch finds the state in front of each chunk (see ae::Params::state).
+struct CarriedState {
+  const __bf16* state;
+  int64_t batch_stride, head_stride;
+  int first_batch;
+};
+
 static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, float* stats,
                                 void* stream, void* workspace = nullptr, size_t workspace_bytes = 0,
-                                const void* bias = nullptr) {
+                                const void* bias = nullptr, const CarriedState* carried = nullptr) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null handle");
   if (!Q || !K || !V || !O) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null device pointer");
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
@@ -306,6 +313,13 @@ static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K
   if (bias && (((uintptr_t)bias & 15) || bias == O)) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_bias: the bias tensor must be 16-byte aligned and must not alias O");
   ae::Params p = h->params;
   p.bias = static_cast<const __bf16*>(bias);
+  p.state = nullptr;
+  if (carried) {
+    p.state = carried->state;
+    p.state_bs = carried->batch_stride;
+    p.state_hs = carried->head_stride;
+    p.state_b0 = carried->first_batch;
+  }
   p.Q = static_cast<const __bf16*>(Q);
   p.K = static_cast<const __bf16*>(K);
   p.V = static_cast<const __bf16*>(V);
@@ -604,7 +618,7 @@ ae_status_t ae_recurrent_create(const ae_recurrent_desc_t* d, ae_recurrent_t** o
     delete h;
     return st;  // the message of the inner call stands
   }
-  h->ws_bytes = h->n_chunks > 1 ? (size_t)d->B * d->H * (h->n_chunks - 1) * d->D_qk * d->D_v * 6 : 0;
+  h->ws_bytes = h->n_chunks > 1 ? (size_t)d->B * d->H * (h->n_chunks - 1) * d->D_qk * d->D_v * 2 : 0;
   *out = h;
   return AE_OK;
 }
@@ -629,37 +643,43 @@ ae_status_t ae_recurrent_forward(const ae_recurrent_t* h, const void* Q, const v
       return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: workspace aliases another buffer");
   }
   const ae_recurrent_desc_t& d = h->desc;
-  const int64_t L = d.L;
-  // intra-chunk part: O = decay-masked causal attention inside every chunk
+  const int64_t L = d.L, state_elems = (int64_t)d.D_qk * d.D_v;
+  const int nc1 = h->n_chunks - 1;
+  ae::RecParams p;
+  p.K = static_cast<const __bf16*>(K);
+  p.V = static_cast<const __bf16*>(V);
+  p.HT = static_cast<__bf16*>(workspace);
+  p.B = d.B;
+  p.H = d.H;
+  p.L = d.L;
+  p.chunk = d.chunk;
+  p.n_chunks = h->n_chunks;
+  if (nc1 > 0) {
+    // carried state in front of every chunk but the first: one workgroup per (batch, head, slice of D_v) walks the chunks
+    const hipError_t e = ae::launch_recurrent_states(p, h->decay, d.D_qk, d.D_v, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_recurrent_forward: %s", hipGetErrorString(e));
+  }
+  // O = read-out of the carried state + decay-masked causal attention inside the chunk, in one pass of the
+  // parallel-pattern kernel over the chunks
   for (int b = 0; b < d.B; b += h->fold) {
     const int64_t e0 = (int64_t)b * d.H * L;  // first row of this launch's (batch, head) slabs
     for (int part = 0; part < 2; ++part) {
       const ae_attn_t* a = part ? h->tail : h->full;
       if (!a) continue;
       const int64_t r0 = e0 + (part ? (int64_t)h->n_full * d.chunk : 0);
-      const ae_status_t st = ae_attn_forward(a, static_cast<const __bf16*>(Q) + r0 * d.D_qk, static_cast<const __bf16*>(K) + r0 * d.D_qk,
-                                             static_cast<const __bf16*>(V) + r0 * d.D_v, static_cast<float*>(O) + r0 * d.D_v, stream);
+      // chunk c > 0 of (batch, head) bh reads state (bh * nc1 + c - 1); the short last chunk is chunk n_full
+      CarriedState cs;
+      cs.state = p.HT + ((int64_t)b * d.H * nc1 + (part ? h->n_full - 1 : 0)) * state_elems;
+      cs.batch_stride = state_elems;
+      cs.head_stride = (int64_t)nc1 * state_elems;
+      cs.first_batch = part ? 0 : 1;
+      const bool has_state = nc1 > 0 && (part == 0 || h->n_full > 0);
+      const ae_status_t st = forward_impl(a, static_cast<const __bf16*>(Q) + r0 * d.D_qk, static_cast<const __bf16*>(K) + r0 * d.D_qk,
+                                          static_cast<const __bf16*>(V) + r0 * d.D_v, static_cast<float*>(O) + r0 * d.D_v, nullptr,
+                                          stream, nullptr, 0, nullptr, has_state ? &cs : nullptr);
       if (st != AE_OK) return st;
     }
   }
-  if (h->n_chunks < 2) return AE_OK;
-  // carried state: per-chunk sums, scan over chunks, read-out added to O
-  ae::RecParams p;
-  p.Q = static_cast<const __bf16*>(Q);
-  p.K = static_cast<const __bf16*>(K);
-  p.V = static_cast<const __bf16*>(V);
-  p.O = static_cast<float*>(O);
-  const size_t n_state = (size_t)d.B * d.H * (h->n_chunks - 1) * d.D_qk * d.D_v;
-  p.S = static_cast<float*>(workspace);
-  p.HT = reinterpret_cast<__bf16*>(static_cast<char*>(workspace) + n_state * 4);
-  p.B = d.B;
-  p.H = d.H;
-  p.L = d.L;
-  p.chunk = d.chunk;
-  p.n_chunks = h->n_chunks;
-  p.scale = d.scale;
-  const hipError_t e = ae::launch_recurrent_inter(p, h->decay, d.D_qk, d.D_v, static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_recurrent_forward: %s", hipGetErrorString(e));
   return AE_OK;
 }
 

@@ -91,6 +91,12 @@ struct Params {
   // MFMA delivers the exponent itself and 1 + 2^(-b2) * 2^x is a single FMA
   int fold;
   float kfac;      // 2^(-b2) when fold
+  // Recurrent pattern, chunks as batch entries (MOD_DECAY with NORM_NONE only; null: off): batch entry
+  // b >= state_b0 of head h starts from the carried state in front of its chunk, a bf16 matrix [D_v][D_qk] at
+  // state + (b - state_b0) * state_bs + h * state_hs:  O[i] = c * gamma^(i+1) * q_i H  +  the walk over the keys.
+  const __bf16* state;
+  int64_t state_bs, state_hs;
+  int state_b0;
 };
 
 struct DecayTable {
@@ -980,6 +986,29 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     copy_slice(One{}, Zero{}, n_walk > 1 ? tile_at(1) : tile_at(0), 1);
     if (C::WINDOW || n_vis > 2 * jt0) score_block<C>(kaddr, 0, qf, s_a);
+    if constexpr (C::MOD == MOD_DECAY && C::NORM == NORM_NONE && !C::WINDOW && C::DQK == C::DV && C::DV <= 128) {
+      // Read-out of the carried state: O^T starts at H^T Q^T instead of zero.  The state is stored transposed,
+      // so a lane's A fragment (output column lane % 32 of block db, 8 consecutive d) is 16 bytes of one row;
+      // the Q fragments serve as B operand as they stand.  The loads are plain ones: the wait the compiler puts
+      // in front of their use also covers the copies issued above, none of which is counted on before the loop.
+      if (p.state != nullptr && b >= p.state_b0) {
+        const __bf16* hrow = p.state + (int64_t)(b - p.state_b0) * p.state_bs + (int64_t)hq * p.state_hs +
+                             (int64_t)ql * C::DQK + 8 * half;
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db) {
+          bf16x8 hf[C::T];
+#pragma unroll
+          for (int tt = 0; tt < C::T; ++tt) hf[tt] = *reinterpret_cast<const bf16x8*>(hrow + db * 32 * C::DQK + tt * 16);
+#pragma unroll
+          for (int tt = 0; tt < C::T; ++tt) st.o[db] = mfma(hf[tt], qf[tt], st.o[db]);
+        }
+        const float f = p.c * fast_exp2(g2 * (float)(i + 1));
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) st.o[db][r] *= f;
+      }
+    }
   }
 
   // ---- key loop ------------------------------------------------------------------------

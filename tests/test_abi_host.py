@@ -304,7 +304,7 @@ def test_recurrent_descriptor_and_entry_point_checks():
     h = A.ae_recurrent_create(**ok)
     try:
         need = A.ae_recurrent_workspace_bytes(h)
-        assert need == 2 * 4 * 4 * 128 * 128 * 6          # 5 chunks: a state in front of all but the first
+        assert need == 2 * 4 * 4 * 128 * 128 * 2          # 5 chunks: a state in front of all but the first
         good = (1 << 20, 2 << 20, 3 << 20, 4 << 20, 5 << 20)
         for args, nbytes in (((0,) + good[1:], need), (good[:3] + (0,) + good[4:], need), ((good[0] + 8,) + good[1:], need),
                              (good[:3] + (good[0],) + good[4:], need),             # O aliases Q
