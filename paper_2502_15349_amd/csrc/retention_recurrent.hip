@@ -17,18 +17,33 @@
 namespace ae {
 namespace {
 
-constexpr int kPad = 72;  // LDS row: 64 tokens + 8 (rows stay 16-byte aligned, the 144-byte stride spreads the banks)
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-// H^T[dv][dk] += sum_j V[j][dv] * gamma^(C-1-j) K[j][dk]: both operands are needed with the token index
-// contiguous, so the 64-token blocks go through LDS transposed (the decay is applied on the way).
+// MFMA operand with the contraction index along the ROWS of a row-major LDS tile: the transposing read hands
+// each lane of a 16-lane block column (lane % 16) of the 4 rows whose addresses the block's lanes supply
+// (lane i: row i / 4, columns 4 (i % 4) .. +3).  lo / hi: this lane's address for tokens 0..3 / 4..7 of its eight.
+__device__ __forceinline__ bf16x8 read_tr(uint32_t lo, uint32_t hi) {
+  const s16x4 x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)lo);
+  const s16x4 y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)hi);
+  return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(x, y, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// H^T[dv][dk] += sum_j V[j][dv] * gamma^(C-1-j) K[j][dk]: the contraction runs over the tokens, the slow index of
+// both operands.  The 64-token blocks are stored to LDS as they come (16 bytes per lane, the decay applied to K
+// on the way) and read with the transposing LDS read.  Row strides of 16 or 48 (mod 64) words keep the four
+// rows x two column groups that half a wave reads at once on different banks.
 // DK/32 waves; wave w owns the 32 x 32 tile of dk block w.
 template <int DK, int DV>
 __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, const DecayTable dt) {
   constexpr int THREADS = 2 * DK, NS = DV / 32;  // NS slices of D_v per (batch, head)
   constexpr int KP = 64 * (DK / 8) / THREADS;    // 16-byte pieces of a K block per thread (= 4)
   constexpr int VP = (64 * 4 + THREADS - 1) / THREADS;  // and of the V slice (1 or 2)
-  __shared__ __attribute__((aligned(16))) __bf16 VT[32][kPad];
-  __shared__ __attribute__((aligned(16))) __bf16 KT[DK][kPad];
+  constexpr int KS = DK * 2 + (DK == 128 ? 64 : 64);    // bytes per K row in LDS: 80 / 48 words
+  constexpr int VS = 64;                                 // 32 columns: 16 words
+  static_assert((KS / 4) % 64 == 16 || (KS / 4) % 64 == 48, "K row stride");
+  __shared__ __attribute__((aligned(16))) char Ks[64 * KS];
+  __shared__ __attribute__((aligned(16))) char Vs[64 * VS];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   // The slices of one (batch, head) read the same K: they go to one XCD (workgroups are dealt to the 8 XCDs
   // round-robin by id), next to each other in time, so that its L2 serves the repeats.
@@ -48,6 +63,14 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
   const __bf16* Kb = p.K + (int64_t)bh * p.L * DK;
   const __bf16* Vb = p.V + (int64_t)bh * p.L * DV + slice * 32;
   __bf16* HTb = p.HT + (int64_t)bh * nc1 * (DV * DK) + (int64_t)slice * 32 * DK;
+
+  // fragment addresses of contraction step 0: tokens 8 (lane / 32) + (lane % 16) / 4, column 16 ((lane / 16) % 2) + 4 (lane % 4)
+  const int i16 = lane & 15, q = lane >> 4;
+  const int frow = 8 * (q >> 1) + (i16 >> 2), fcol = 16 * (q & 1) + 4 * (i16 & 3);
+  const uint32_t ks0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)Ks);
+  const uint32_t vs0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)Vs);
+  const uint32_t ka = ks0 + frow * KS + (w * 32 + fcol) * 2;
+  const uint32_t va = vs0 + frow * VS + fcol * 2;
 
   f32x16 acc;
 #pragma unroll
@@ -76,24 +99,22 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
     for (int it = 0; it < KP; ++it) {
       const int piece = tid + it * THREADS, row = piece / (DK / 8), c8 = piece % (DK / 8);
       const float decay = exp2f(lg * (float)(p.chunk - 1 - (j0 + row)));
+      bf16x8 x;
 #pragma unroll
-      for (int t = 0; t < 8; ++t) KT[c8 * 8 + t][row] = (__bf16)((float)kreg[it][t] * decay);
+      for (int t = 0; t < 8; ++t) x[t] = (__bf16)((float)kreg[it][t] * decay);
+      *reinterpret_cast<bf16x8*>(Ks + row * KS + c8 * 16) = x;
     }
 #pragma unroll
     for (int it = 0; it < VP; ++it) {
       const int piece = tid + it * THREADS, row = piece / 4, c8 = piece % 4;
-      if (piece < 256) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) VT[c8 * 8 + t][row] = vreg[it][t];
-      }
+      if (piece < 256) *reinterpret_cast<bf16x8*>(Vs + row * VS + c8 * 16) = vreg[it];
     }
     __syncthreads();
     if (blk + 1 < n_blocks) fetch(blk + 1);  // in flight during the MFMAs
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      const int k0 = ks * 16 + 8 * (lane >> 5);
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(&VT[lane & 31][k0]);
-      const bf16x8 b = *reinterpret_cast<const bf16x8*>(&KT[w * 32 + (lane & 31)][k0]);
+      const bf16x8 a = read_tr(va + ks * 16 * VS, va + (ks * 16 + 4) * VS);
+      const bf16x8 b = read_tr(ka + ks * 16 * KS, ka + (ks * 16 + 4) * KS);
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
     }
     if (j0 + 64 == p.chunk) {  // end of a chunk: store the state, then age it by a whole chunk
