@@ -103,3 +103,48 @@ def test_sampled_rows_at_benchmark_size(A):
         ref = retention_recurrent_head(Q[b, h].float().numpy(), K[b, h].float().numpy(), V[b, h].float().numpy(),
                                        scale=1.0 / math.sqrt(D), gamma_h=gam[h])
         _check(O[b, h].cpu().double().numpy(), ref, f"{w.name} b{b} h{h}")
+
+
+def test_hip_graph_replays(A):
+    """ae_recurrent_forward allocates nothing and clears nothing (the states are overwritten whole), so its
+    launches can be captured into a HIP graph: replayed four times with new K values and eager work between
+    the replays, every replay must equal the eager call on the same inputs bit for bit; the first one is also
+    held against the oracle."""
+    dev = torch.device("cuda:0")
+    w = _workload("rec_graph", 794, 2, 4, 600, 128)
+    Qc, Kc, Vc = make_inputs(w)
+    Q, K, V = Qc.to(dev), Kc.to(dev), Vc.to(dev)
+    gam = _gammas(4)
+    scale = 1.0 / math.sqrt(128)
+    h = A.ae_recurrent_create(B=w.B, H=w.H_q, L=w.L_q, D_qk=128, D_v=128, chunk=256, scale=scale, gamma=gam)
+    try:
+        need = A.ae_recurrent_workspace_bytes(h)
+        wsg, wse = (torch.zeros(need, dtype=torch.uint8, device=dev) for _ in range(2))
+        Kg = K.clone()
+        Og, Oe = (torch.zeros((w.B, w.H_q, w.L_q, 128), dtype=torch.float32, device=dev) for _ in range(2))
+
+        def launch(O, ws, stream):
+            A.ae_recurrent_forward(h, Q.data_ptr(), Kg.data_ptr(), V.data_ptr(), O.data_ptr(), ws.data_ptr(), need, stream.cuda_stream)
+
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            launch(Og, wsg, side)
+        torch.cuda.synchronize()
+        for replay in range(4):
+            print(f"graph replay {replay}", flush=True)
+            if replay:
+                Kg.copy_((K.float() * (1.0 - 0.2 * replay)).to(torch.bfloat16).roll(replay, dims=2))
+            Og.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            launch(Oe, wse, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            assert torch.equal(Og, Oe), f"replay {replay} differs from the eager call"
+            if replay == 0:
+                ref = oracle_recurrent(Qc.float().numpy(), Kc.float().numpy(), Vc.float().numpy(), scale=scale, gamma=gam)
+                _check(Og.cpu().double().numpy(), ref, "rec_graph replay 0")
+    finally:
+        A.ae_recurrent_destroy(h)
