@@ -954,6 +954,10 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // and read back as fragments.  They land behind stage 0, next to tile 0, which is
   // copied at the same time; tile 1 follows once every wave has its fragments.
   bf16x8 qf[C::T];
+  // recurrent pattern, chunks as batch entries: this chunk starts from a carried state (see Params::state)
+  constexpr bool kState = C::MOD == MOD_DECAY && C::NORM == NORM_NONE && !C::WINDOW && C::DQK == C::DV && C::DV <= 128;
+  bf16x8 hf[kState ? C::DB : 1][kState ? C::T : 1];
+  const bool has_state = kState && p.state != nullptr && b >= p.state_b0;  // uniform over the workgroup
   if (n_walk > 0) {
     using QMap = DmaMap<1, 32, C::CPR_K, false>;
     const uint32_t qlds = lds0 + C::STAGE_BYTES + wave * (32 * C::RB_K);
@@ -968,6 +972,19 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       dma16_at<m * 1024>(qtile, goff, qlds);
     });
     copy_slice(One{}, Zero{}, tile_at(0), 0);
+    if constexpr (kState) {
+      // The state is stored transposed ([D_v][D_qk]), so a lane's A fragment (output column lane % 32 of block
+      // db, 8 consecutive d) is 16 bytes of one row.  Plain loads, issued here so that they share the memory
+      // latency of the queries and the first tile (the wait below covers all three).
+      if (has_state) {
+        const __bf16* hrow = p.state + (int64_t)(b - p.state_b0) * p.state_bs + (int64_t)hq * p.state_hs +
+                             (int64_t)ql * C::DQK + 8 * half;
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+          for (int tt = 0; tt < C::T; ++tt) hf[db][tt] = *reinterpret_cast<const bf16x8*>(hrow + db * 32 * C::DQK + tt * 16);
+      }
+    }
     wait_dma_and_sync();  // one memory latency for the queries and the first tile
     uint32_t qaddr[C::T];
     k_frag_offsets<C>(qlds, qaddr);
@@ -982,26 +999,15 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       }
       qf[tt] = qv;
     }
-    // every wave has read its rows before tile 1 overwrites them
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    copy_slice(One{}, Zero{}, n_walk > 1 ? tile_at(1) : tile_at(0), 1);
-    if (C::WINDOW || n_vis > 2 * jt0) score_block<C>(kaddr, 0, qf, s_a);
-    if constexpr (C::MOD == MOD_DECAY && C::NORM == NORM_NONE && !C::WINDOW && C::DQK == C::DV && C::DV <= 128) {
-      // Read-out of the carried state: O^T starts at H^T Q^T instead of zero.  The state is stored transposed,
-      // so a lane's A fragment (output column lane % 32 of block db, 8 consecutive d) is 16 bytes of one row;
-      // the Q fragments serve as B operand as they stand.  The loads are plain ones: the wait the compiler puts
-      // in front of their use also covers the copies issued above, none of which is counted on before the loop.
-      if (p.state != nullptr && b >= p.state_b0) {
-        const __bf16* hrow = p.state + (int64_t)(b - p.state_b0) * p.state_bs + (int64_t)hq * p.state_hs +
-                             (int64_t)ql * C::DQK + 8 * half;
+    if constexpr (kState) {
+      // Read-out of the carried state: O^T starts at H^T Q^T instead of zero; the Q fragments serve as B operand
+      // as they stand.  Done before the copy of tile 1 is issued: the wait the compiler puts in front of the
+      // fragments' first use then finds nothing else in flight.
+      if (has_state) {
 #pragma unroll
-        for (int db = 0; db < C::DB; ++db) {
-          bf16x8 hf[C::T];
+        for (int db = 0; db < C::DB; ++db)
 #pragma unroll
-          for (int tt = 0; tt < C::T; ++tt) hf[tt] = *reinterpret_cast<const bf16x8*>(hrow + db * 32 * C::DQK + tt * 16);
-#pragma unroll
-          for (int tt = 0; tt < C::T; ++tt) st.o[db] = mfma(hf[tt], qf[tt], st.o[db]);
-        }
+          for (int tt = 0; tt < C::T; ++tt) st.o[db] = mfma(hf[db][tt], qf[tt], st.o[db]);
         const float f = p.c * fast_exp2(g2 * (float)(i + 1));
 #pragma unroll
         for (int db = 0; db < C::DB; ++db)
@@ -1009,6 +1015,10 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
           for (int r = 0; r < 16; ++r) st.o[db][r] *= f;
       }
     }
+    // every wave has read its rows before tile 1 overwrites them
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    copy_slice(One{}, Zero{}, n_walk > 1 ? tile_at(1) : tile_at(0), 1);
+    if (C::WINDOW || n_vis > 2 * jt0) score_block<C>(kaddr, 0, qf, s_a);
   }
 
   // ---- key loop ------------------------------------------------------------------------

@@ -14,6 +14,8 @@
 // Every decay factor is a power of gamma with a non-negative exponent: nothing can overflow.
 #include "recurrent.hpp"
 
+#include <type_traits>
+
 namespace ae {
 namespace {
 
@@ -29,8 +31,8 @@ __device__ __forceinline__ bf16x8 read_tr(uint32_t lo, uint32_t hi) {
   return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(x, y, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// H^T[dv][dk] += sum_j V[j][dv] * gamma^(C-1-j) K[j][dk]: the contraction runs over the tokens, the slow index of
-// both operands.  The 64-token blocks are stored to LDS as they come (16 bytes per lane, the decay applied to K
+// H^T[dv][dk] += sum_j gamma^(C-1-j) V[j][dv] K[j][dk]: the contraction runs over the tokens, the slow index of
+// both operands.  The 64-token blocks are stored to LDS as they come (16 bytes per lane, the decay applied to V
 // on the way) and read with the transposing LDS read.  Row strides of 16 or 48 (mod 64) words keep the four
 // rows x two column groups that half a wave reads at once on different banks.
 // DK/32 waves; wave w owns the 32 x 32 tile of dk block w.
@@ -77,40 +79,48 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 
   const int n_blocks = nc1 * (p.chunk / 64);  // every chunk but the last is a full one
-  bf16x8 kreg[KP], vreg[VP];
-  auto fetch = [&](int blk) {
+  // Block loads run two blocks ahead of the MFMAs, in two register sets used in turn: a workgroup's own MFMAs
+  // are far too short to cover a memory latency, and only four workgroups share a CU.
+  bf16x8 kreg[2][KP], vreg[2][VP];
+  auto fetch = [&](auto setc, int blk) {
+    constexpr int S = decltype(setc)::value;
+    if (blk >= n_blocks) return;
     const int64_t t0 = (int64_t)blk * 64;
 #pragma unroll
     for (int it = 0; it < KP; ++it) {
       const int piece = tid + it * THREADS, row = piece / (DK / 8), c8 = piece % (DK / 8);
-      kreg[it] = *reinterpret_cast<const bf16x8*>(Kb + (t0 + row) * DK + c8 * 8);
+      kreg[S][it] = *reinterpret_cast<const bf16x8*>(Kb + (t0 + row) * DK + c8 * 8);
     }
 #pragma unroll
     for (int it = 0; it < VP; ++it) {
       const int piece = tid + it * THREADS, row = piece / 4, c8 = piece % 4;
-      if (piece < 256) vreg[it] = *reinterpret_cast<const bf16x8*>(Vb + (t0 + row) * DV + c8 * 8);
+      if (piece < 256) vreg[S][it] = *reinterpret_cast<const bf16x8*>(Vb + (t0 + row) * DV + c8 * 8);
     }
   };
-  fetch(0);
-  for (int blk = 0; blk < n_blocks; ++blk) {
+  auto process = [&](auto setc, int blk) {
+    constexpr int S = decltype(setc)::value;
+    if (blk >= n_blocks) return;          // (uniform over the workgroup)
     const int j0 = (blk * 64) % p.chunk;  // position of the block inside its chunk
     __syncthreads();                      // the fragments of the previous block have been read
 #pragma unroll
     for (int it = 0; it < KP; ++it) {
       const int piece = tid + it * THREADS, row = piece / (DK / 8), c8 = piece % (DK / 8);
-      const float decay = exp2f(lg * (float)(p.chunk - 1 - (j0 + row)));
-      bf16x8 x;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) x[t] = (__bf16)((float)kreg[it][t] * decay);
-      *reinterpret_cast<bf16x8*>(Ks + row * KS + c8 * 16) = x;
+      *reinterpret_cast<bf16x8*>(Ks + row * KS + c8 * 16) = kreg[S][it];
     }
+    // the token's decay goes onto its V row: the slice has a quarter of the K block's elements (at 128/128)
 #pragma unroll
     for (int it = 0; it < VP; ++it) {
       const int piece = tid + it * THREADS, row = piece / 4, c8 = piece % 4;
-      if (piece < 256) *reinterpret_cast<bf16x8*>(Vs + row * VS + c8 * 16) = vreg[it];
+      if (piece < 256) {
+        const float decay = exp2f(lg * (float)(p.chunk - 1 - (j0 + row)));
+        bf16x8 x;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) x[t] = (__bf16)((float)vreg[S][it][t] * decay);
+        *reinterpret_cast<bf16x8*>(Vs + row * VS + c8 * 16) = x;
+      }
     }
     __syncthreads();
-    if (blk + 1 < n_blocks) fetch(blk + 1);  // in flight during the MFMAs
+    fetch(setc, blk + 2);  // this set is free again
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const bf16x8 a = read_tr(va + ks * 16 * VS, va + (ks * 16 + 4) * VS);
@@ -127,6 +137,14 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
         acc[r] *= g_chunk;
       }
     }
+  };
+  using Set0 = std::integral_constant<int, 0>;
+  using Set1 = std::integral_constant<int, 1>;
+  fetch(Set0{}, 0);
+  fetch(Set1{}, 1);
+  for (int blk = 0; blk < n_blocks; blk += 2) {
+    process(Set0{}, blk);
+    process(Set1{}, blk + 1);
   }
 }
 
