@@ -294,8 +294,14 @@ int32_t ae_attn_version(void);
  * or 256 tokens (256 fills the parallel kernel's 256-row tile).  Head dims
  * 64/64 and 128/128; H <= AE_MAX_DECAY_HEADS.
  * The workspace (device memory, 256-byte aligned, owned by the caller, size
- * from ae_recurrent_workspace_bytes; 0 when L <= chunk) holds the per-chunk
- * states: 2 bytes x B x H x (chunks - 1) x D_qk x D_v.  Calls that share a
+ * from ae_recurrent_workspace_bytes) holds the state in front of every chunk:
+ * 2 bytes x B x H x chunks x D_qk x D_v.
+ * ae_recurrent_forward_state also takes the state in front of the first token
+ * (h_in, fp32 [B, H, D_qk, D_v], device memory, 16-byte aligned; NULL: zero)
+ * and hands back the one after the last token (h_out, same layout; NULL: not
+ * computed), so that a sequence can be processed in pieces (prefill, then more
+ * tokens): the pieces' outputs equal those of one call up to rounding.  h_out
+ * may be the buffer h_in points to.  Calls that share a
  * workspace must not overlap.  Nothing allocates device memory; all kernels are
  * enqueued on `stream` (a hipStream_t, NULL = default stream) and the call
  * returns without waiting.
@@ -313,6 +319,9 @@ ae_status_t ae_recurrent_create(const ae_recurrent_desc_t *desc, ae_recurrent_t 
 ae_status_t ae_recurrent_workspace_bytes(const ae_recurrent_t *h, size_t *bytes);
 ae_status_t ae_recurrent_forward(const ae_recurrent_t *h, const void *Q, const void *K, const void *V, void *O,
                                  void *workspace, size_t workspace_bytes, void *stream);
+ae_status_t ae_recurrent_forward_state(const ae_recurrent_t *h, const void *Q, const void *K, const void *V,
+                                       const void *h_in, void *O, void *h_out, void *workspace,
+                                       size_t workspace_bytes, void *stream);
 ae_status_t ae_recurrent_destroy(ae_recurrent_t *h); /* NULL is allowed */
 
 #ifdef __cplusplus

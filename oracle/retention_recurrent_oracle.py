@@ -33,15 +33,15 @@ this module.  It shares no code with the HIP path.
 import numpy as np
 
 
-def retention_recurrent_head(q, k, v, *, scale, gamma_h, return_state=False):
+def retention_recurrent_head(q, k, v, *, scale, gamma_h, return_state=False, h0=None):
     """q [L, d_qk], k [L, d_qk], v [L, d_v] (any float dtype) -> o [L, d_v] fp64
-    (and the final state [d_qk, d_v] when asked)."""
+    (and the final state [d_qk, d_v] when asked).  h0: the state in front of the first token (default: zero)."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
     L, d_qk = q.shape
     d_v = v.shape[1]
-    h = np.zeros((d_qk, d_v), dtype=np.float64)
+    h = np.zeros((d_qk, d_v), dtype=np.float64) if h0 is None else np.array(h0, dtype=np.float64)
     o = np.zeros((L, d_v), dtype=np.float64)
     for t in range(L):
         h = float(gamma_h) * h + np.outer(k[t], v[t])

@@ -70,6 +70,8 @@ _lib.ae_recurrent_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
 _lib.ae_recurrent_workspace_bytes.restype = C.c_int
 _lib.ae_recurrent_forward.argtypes = [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
 _lib.ae_recurrent_forward.restype = C.c_int
+_lib.ae_recurrent_forward_state.argtypes = [C.c_void_p] * 8 + [C.c_size_t, C.c_void_p]
+_lib.ae_recurrent_forward_state.restype = C.c_int
 _lib.ae_recurrent_destroy.argtypes = [C.c_void_p]
 _lib.ae_recurrent_destroy.restype = C.c_int
 _lib.ae_attn_destroy.argtypes = [C.c_void_p]
@@ -228,14 +230,23 @@ def ae_recurrent_forward(handle: int, Q: int, K: int, V: int, O: int, workspace:
     _check(_lib.ae_recurrent_forward(handle, Q, K, V, O, workspace, workspace_bytes, stream))
 
 
+def ae_recurrent_forward_state(handle: int, Q: int, K: int, V: int, h_in: int, O: int, h_out: int, workspace: int,
+                               workspace_bytes: int, stream: int = 0) -> None:
+    """ae_recurrent_forward with the state in front of the first token (h_in, 0: zero) and the state after the last
+    one (h_out, 0: not computed), both fp32 [B, H, D_qk, D_v] device addresses."""
+    _check(_lib.ae_recurrent_forward_state(handle, Q, K, V, h_in, O, h_out, workspace, workspace_bytes, stream))
+
+
 def ae_recurrent_destroy(handle: Optional[int]) -> None:
     _check(_lib.ae_recurrent_destroy(handle))
 
 
-def retention_recurrent(Q, K, V, *, scale, gamma, chunk=256, out=None, workspace=None, stream=None):
+def retention_recurrent(Q, K, V, *, scale, gamma, chunk=256, out=None, workspace=None, stream=None, h_in=None,
+                        return_state=False):
     """Recurrent retention on contiguous bf16 device tensors Q, K [B, H, L, D_qk], V [B, H, L, D_v];
     returns O [B, H, L, D_v] fp32.  workspace: device byte tensor of ae_recurrent_workspace_bytes() bytes
-    (allocated here if not given)."""
+    (allocated here if not given).  h_in: optional contiguous fp32 device tensor [B, H, D_qk, D_v], the state in
+    front of the first token; return_state: also return the state after the last token (same layout)."""
     import torch
 
     for t in (Q, K, V):
@@ -254,13 +265,18 @@ def retention_recurrent(Q, K, V, *, scale, gamma, chunk=256, out=None, workspace
         s = torch.cuda.current_stream(Q.device) if stream is None else stream
         with torch.cuda.device(Q.device):
             need = ae_recurrent_workspace_bytes(h)
-            if need and workspace is None:
+            if workspace is None:
                 workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
-            ae_recurrent_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
-                                 workspace.data_ptr() if need else 0, workspace.numel() if need else 0, s.cuda_stream)
+            if h_in is not None and (h_in.dtype != torch.float32 or tuple(h_in.shape) != (B, H, D_qk, D_v)
+                                     or not h_in.is_contiguous() or not h_in.is_cuda):
+                raise ValueError("h_in must be a contiguous fp32 device tensor [B, H, D_qk, D_v]")
+            h_out = torch.empty((B, H, D_qk, D_v), dtype=torch.float32, device=Q.device) if return_state else None
+            ae_recurrent_forward_state(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), 0 if h_in is None else h_in.data_ptr(),
+                                       out.data_ptr(), 0 if h_out is None else h_out.data_ptr(), workspace.data_ptr(),
+                                       workspace.numel(), s.cuda_stream)
     finally:
         ae_recurrent_destroy(h)
-    return out
+    return (out, h_out) if return_state else out
 
 
 def attention_forward(Q, K, V, *, scale, score_mod="none", bias=0.0, gamma=None, norm="softmax",

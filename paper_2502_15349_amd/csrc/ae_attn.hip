@@ -618,7 +618,7 @@ ae_status_t ae_recurrent_create(const ae_recurrent_desc_t* d, ae_recurrent_t** o
     delete h;
     return st;  // the message of the inner call stands
   }
-  h->ws_bytes = h->n_chunks > 1 ? (size_t)d->B * d->H * (h->n_chunks - 1) * d->D_qk * d->D_v * 2 : 0;
+  h->ws_bytes = (size_t)d->B * d->H * h->n_chunks * d->D_qk * d->D_v * 2;  // one bf16 state per chunk
   *out = h;
   return AE_OK;
 }
@@ -629,33 +629,37 @@ ae_status_t ae_recurrent_workspace_bytes(const ae_recurrent_t* h, size_t* bytes)
   return AE_OK;
 }
 
-ae_status_t ae_recurrent_forward(const ae_recurrent_t* h, const void* Q, const void* K, const void* V, void* O,
-                                 void* workspace, size_t workspace_bytes, void* stream) {
+ae_status_t ae_recurrent_forward_state(const ae_recurrent_t* h, const void* Q, const void* K, const void* V,
+                                       const void* h_in, void* O, void* h_out, void* workspace, size_t workspace_bytes,
+                                       void* stream) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: null handle");
   if (!Q || !K || !V || !O) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: null pointer");
-  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15)
-    return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: Q, K, V, O must be 16-byte aligned");
+  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O | (uintptr_t)h_in | (uintptr_t)h_out) & 15)
+    return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: Q, K, V, O and the states must be 16-byte aligned");
   if (O == Q || O == K || O == V) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: O aliases an input");
-  if (h->ws_bytes) {
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < h->ws_bytes)
-      return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: workspace missing, not 256-byte aligned, or smaller than %zu bytes", h->ws_bytes);
-    if (workspace == O || workspace == Q || workspace == K || workspace == V)
-      return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: workspace aliases another buffer");
-  }
+  if (h_out && (h_out == O || h_out == Q || h_out == K || h_out == V || h_out == workspace))
+    return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: the final state aliases another buffer");
+  if (h_in && (h_in == O || h_in == workspace)) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: the initial state aliases an output");
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < h->ws_bytes)
+    return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: workspace missing, not 256-byte aligned, or smaller than %zu bytes", h->ws_bytes);
+  if (workspace == O || workspace == Q || workspace == K || workspace == V)
+    return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: workspace aliases another buffer");
   const ae_recurrent_desc_t& d = h->desc;
   const int64_t L = d.L, state_elems = (int64_t)d.D_qk * d.D_v;
-  const int nc1 = h->n_chunks - 1;
   ae::RecParams p;
   p.K = static_cast<const __bf16*>(K);
   p.V = static_cast<const __bf16*>(V);
   p.HT = static_cast<__bf16*>(workspace);
+  p.h_in = static_cast<const float*>(h_in);
+  p.h_out = static_cast<float*>(h_out);
   p.B = d.B;
   p.H = d.H;
   p.L = d.L;
   p.chunk = d.chunk;
   p.n_chunks = h->n_chunks;
-  if (nc1 > 0) {
-    // carried state in front of every chunk but the first: one workgroup per (batch, head, slice of D_v) walks the chunks
+  if (h->n_chunks > 1 || h_in || h_out) {
+    // the state in front of every chunk (slot c of a (batch, head): chunk c; slot 0 only from h_in): one workgroup
+    // per (batch, head, slice of D_v) walks the chunks
     const hipError_t e = ae::launch_recurrent_states(p, h->decay, d.D_qk, d.D_v, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_recurrent_forward: %s", hipGetErrorString(e));
   }
@@ -667,13 +671,13 @@ ae_status_t ae_recurrent_forward(const ae_recurrent_t* h, const void* Q, const v
       const ae_attn_t* a = part ? h->tail : h->full;
       if (!a) continue;
       const int64_t r0 = e0 + (part ? (int64_t)h->n_full * d.chunk : 0);
-      // chunk c > 0 of (batch, head) bh reads state (bh * nc1 + c - 1); the short last chunk is chunk n_full
-      CarriedState cs;
-      cs.state = p.HT + ((int64_t)b * d.H * nc1 + (part ? h->n_full - 1 : 0)) * state_elems;
+      CarriedState cs;  // batch entry c' of the launch is chunk c' (part 0) or chunk n_full (the short last one)
+      cs.first_batch = (part == 0 && !h_in) ? 1 : 0;  // chunk 0 has a state in front of it only if the caller gave one
+      // (the kernel counts slots from the first batch entry that has one)
+      cs.state = p.HT + ((int64_t)b * d.H * h->n_chunks + (part ? h->n_full : cs.first_batch)) * state_elems;
       cs.batch_stride = state_elems;
-      cs.head_stride = (int64_t)nc1 * state_elems;
-      cs.first_batch = part ? 0 : 1;
-      const bool has_state = nc1 > 0 && (part == 0 || h->n_full > 0);
+      cs.head_stride = (int64_t)h->n_chunks * state_elems;
+      const bool has_state = part == 0 ? (h->n_full > 1 || h_in) : (h->n_full > 0 || h_in);
       const ae_status_t st = forward_impl(a, static_cast<const __bf16*>(Q) + r0 * d.D_qk, static_cast<const __bf16*>(K) + r0 * d.D_qk,
                                           static_cast<const __bf16*>(V) + r0 * d.D_v, static_cast<float*>(O) + r0 * d.D_v, nullptr,
                                           stream, nullptr, 0, nullptr, has_state ? &cs : nullptr);
@@ -681,6 +685,11 @@ ae_status_t ae_recurrent_forward(const ae_recurrent_t* h, const void* Q, const v
     }
   }
   return AE_OK;
+}
+
+ae_status_t ae_recurrent_forward(const ae_recurrent_t* h, const void* Q, const void* K, const void* V, void* O,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  return ae_recurrent_forward_state(h, Q, K, V, nullptr, O, nullptr, workspace, workspace_bytes, stream);
 }
 
 ae_status_t ae_recurrent_destroy(ae_recurrent_t* h) {

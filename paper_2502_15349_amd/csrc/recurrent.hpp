@@ -6,14 +6,16 @@
 
 namespace ae {
 // Every (batch, head) sequence is cut into chunks of `chunk` tokens (a multiple of 64); the last one may be short.
-// HT holds one bf16 matrix [D_v][D_qk] per (batch, head, chunk but the last): the state after that chunk,
-// transposed, which the chunk behind it starts from.
+// HT holds one bf16 matrix [D_v][D_qk] per (batch, head, chunk): the state in front of that chunk, transposed
+// (slot 0 is written only when the caller hands in a state).
 struct RecParams {
   const __bf16 *K, *V;  // contiguous [B, H, L, D]
-  __bf16* HT;           // [B*H, n_chunks - 1, D_v, D_qk]
+  __bf16* HT;           // [B*H, n_chunks, D_v, D_qk]
+  const float* h_in;    // optional [B, H, D_qk, D_v]: the state in front of the first token (null: zero)
+  float* h_out;         // optional [B, H, D_qk, D_v]: the state after the last token
   int B, H, L, chunk, n_chunks;
 };
 bool recurrent_supported(int dqk, int dv);
-// The states after chunks 0 .. n_chunks-2 (n_chunks >= 2).
+// The states in front of chunks 1 .. n_chunks-1 (and 0, from h_in), and the final state if asked for.
 hipError_t launch_recurrent_states(const RecParams& p, const DecayTable& dt, int dqk, int dv, hipStream_t stream);
 }  // namespace ae

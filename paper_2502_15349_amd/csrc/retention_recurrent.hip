@@ -59,12 +59,11 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
     bh = blockIdx.x / NS;
     slice = blockIdx.x % NS;
   }
-  const int nc1 = p.n_chunks - 1;
   const float lg = dt.log2_gamma[bh % p.H];
   const float g_chunk = exp2f(lg * (float)p.chunk);
   const __bf16* Kb = p.K + (int64_t)bh * p.L * DK;
   const __bf16* Vb = p.V + (int64_t)bh * p.L * DV + slice * 32;
-  __bf16* HTb = p.HT + (int64_t)bh * nc1 * (DV * DK) + (int64_t)slice * 32 * DK;
+  __bf16* HTb = p.HT + (int64_t)bh * p.n_chunks * (DV * DK) + (int64_t)slice * 32 * DK;  // slot c: the state in front of chunk c
 
   // fragment addresses of contraction step 0: tokens 8 (lane / 32) + (lane % 16) / 4, column 16 ((lane / 16) % 2) + 4 (lane % 4)
   const int i16 = lane & 15, q = lane >> 4;
@@ -77,30 +76,44 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
   f32x16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  if (p.h_in != nullptr) {  // start from the caller's state ([D_qk][D_v] fp32); chunk 0 reads it from slot 0
+    const float* hin = p.h_in + (int64_t)bh * (DK * DV) + (int64_t)(w * 32 + (lane & 31)) * DV + slice * 32;
+    __bf16* ht = HTb + w * 32 + (lane & 31);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      acc[r] = hin[row];
+      ht[row * DK] = (__bf16)acc[r];
+      acc[r] *= exp2f(lg * (float)min(p.chunk, p.L));  // aged by the first chunk's length before its tokens are added
+    }
+  }
 
-  const int n_blocks = nc1 * (p.chunk / 64);  // every chunk but the last is a full one
+  // Without a final state to hand back the last chunk is not walked; every chunk but the last is a full one.
+  const int n_blocks = p.h_out != nullptr ? (p.L + 63) / 64 : (p.n_chunks - 1) * (p.chunk / 64);
   // Block loads run two blocks ahead of the MFMAs, in two register sets used in turn: a workgroup's own MFMAs
   // are far too short to cover a memory latency, and only four workgroups share a CU.
   bf16x8 kreg[2][KP], vreg[2][VP];
   auto fetch = [&](auto setc, int blk) {
     constexpr int S = decltype(setc)::value;
     if (blk >= n_blocks) return;
-    const int64_t t0 = (int64_t)blk * 64;
+    const int t0 = blk * 64;  // tokens past the end (last block of a short last chunk) read the last one, with weight 0
 #pragma unroll
     for (int it = 0; it < KP; ++it) {
       const int piece = tid + it * THREADS, row = piece / (DK / 8), c8 = piece % (DK / 8);
-      kreg[S][it] = *reinterpret_cast<const bf16x8*>(Kb + (t0 + row) * DK + c8 * 8);
+      kreg[S][it] = *reinterpret_cast<const bf16x8*>(Kb + (int64_t)min(t0 + row, p.L - 1) * DK + c8 * 8);
     }
 #pragma unroll
     for (int it = 0; it < VP; ++it) {
       const int piece = tid + it * THREADS, row = piece / 4, c8 = piece % 4;
-      if (piece < 256) vreg[S][it] = *reinterpret_cast<const bf16x8*>(Vb + (t0 + row) * DV + c8 * 8);
+      if (piece < 256) vreg[S][it] = *reinterpret_cast<const bf16x8*>(Vb + (int64_t)min(t0 + row, p.L - 1) * DV + c8 * 8);
     }
   };
   auto process = [&](auto setc, int blk) {
     constexpr int S = decltype(setc)::value;
     if (blk >= n_blocks) return;          // (uniform over the workgroup)
     const int j0 = (blk * 64) % p.chunk;  // position of the block inside its chunk
+    const int c = (blk * 64) / p.chunk;
+    const int len = min(p.chunk, p.L - c * p.chunk);  // tokens of this chunk (the last one may be short)
     __syncthreads();                      // the fragments of the previous block have been read
 #pragma unroll
     for (int it = 0; it < KP; ++it) {
@@ -112,7 +125,7 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
     for (int it = 0; it < VP; ++it) {
       const int piece = tid + it * THREADS, row = piece / 4, c8 = piece % 4;
       if (piece < 256) {
-        const float decay = exp2f(lg * (float)(p.chunk - 1 - (j0 + row)));
+        const float decay = j0 + row < len ? exp2f(lg * (float)(len - 1 - (j0 + row))) : 0.f;
         bf16x8 x;
 #pragma unroll
         for (int t = 0; t < 8; ++t) x[t] = (__bf16)((float)vreg[S][it][t] * decay);
@@ -127,14 +140,20 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
       const bf16x8 b = read_tr(ka + ks * 16 * KS, ka + (ks * 16 + 4) * KS);
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
     }
-    if (j0 + 64 == p.chunk) {  // end of a chunk: store the state, then age it by a whole chunk
-      const int c = (blk * 64) / p.chunk;
-      __bf16* ht = HTb + (int64_t)c * (DV * DK) + w * 32 + (lane & 31);
+    if (j0 + 64 >= len) {  // end of a chunk
+      if (c + 1 < p.n_chunks) {  // store the state for the next chunk, then age it by that chunk's length
+        const float g_next = c + 2 < p.n_chunks ? g_chunk : exp2f(lg * (float)(p.L - (c + 1) * p.chunk));
+        __bf16* ht = HTb + (int64_t)(c + 1) * (DV * DK) + w * 32 + (lane & 31);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        ht[row * DK] = (__bf16)acc[r];
-        acc[r] *= g_chunk;
+        for (int r = 0; r < 16; ++r) {
+          const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          ht[row * DK] = (__bf16)acc[r];
+          acc[r] *= g_next;
+        }
+      } else {  // the state after the last token, [D_qk][D_v] fp32 (only walked when asked for)
+        float* hout = p.h_out + (int64_t)bh * (DK * DV) + (int64_t)(w * 32 + (lane & 31)) * DV + slice * 32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) hout[8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)] = acc[r];
       }
     }
   };
@@ -159,7 +178,7 @@ hipError_t launch_dims(const RecParams& p, const DecayTable& dt, hipStream_t str
 bool recurrent_supported(int dqk, int dv) { return (dqk == 64 && dv == 64) || (dqk == 128 && dv == 128); }
 
 hipError_t launch_recurrent_states(const RecParams& p, const DecayTable& dt, int dqk, int dv, hipStream_t stream) {
-  if (p.n_chunks < 2 || p.chunk % 64 != 0) return hipErrorInvalidValue;
+  if (p.chunk % 64 != 0 || (p.n_chunks < 2 && !p.h_in && !p.h_out)) return hipErrorInvalidValue;
   if (dqk == 64 && dv == 64) return launch_dims<64, 64>(p, dt, stream);
   if (dqk == 128 && dv == 128) return launch_dims<128, 128>(p, dt, stream);
   return hipErrorInvalidValue;

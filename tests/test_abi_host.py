@@ -304,7 +304,7 @@ def test_recurrent_descriptor_and_entry_point_checks():
     h = A.ae_recurrent_create(**ok)
     try:
         need = A.ae_recurrent_workspace_bytes(h)
-        assert need == 2 * 4 * 4 * 128 * 128 * 2          # 5 chunks: a state in front of all but the first
+        assert need == 2 * 4 * 5 * 128 * 128 * 2          # 5 chunks: a bf16 state in front of each
         good = (1 << 20, 2 << 20, 3 << 20, 4 << 20, 5 << 20)
         for args, nbytes in (((0,) + good[1:], need), (good[:3] + (0,) + good[4:], need), ((good[0] + 8,) + good[1:], need),
                              (good[:3] + (good[0],) + good[4:], need),             # O aliases Q
@@ -315,12 +315,21 @@ def test_recurrent_descriptor_and_entry_point_checks():
             assert ei.value.status == A.AE_ERR_INVALID_ARG, (args, A.ae_attn_last_error())
         with pytest.raises(A.AeAttnError):
             A.ae_recurrent_forward(None, *good, need)
+        # states: Q K V h_in O h_out workspace
+        q, k, v, o, ws = good
+        for args in ((q, k, v, (6 << 20) + 4, o, 0, ws),      # misaligned h_in
+                     (q, k, v, 0, o, o, ws),                   # h_out aliases O
+                     (q, k, v, o, o, 0, ws),                   # h_in aliases O
+                     (q, k, v, 0, o, ws, ws)):                 # h_out aliases the workspace
+            with pytest.raises(A.AeAttnError) as ei:
+                A.ae_recurrent_forward_state(h, *args, need)
+            assert ei.value.status == A.AE_ERR_INVALID_ARG, (args, A.ae_attn_last_error())
     finally:
         A.ae_recurrent_destroy(h)
     A.ae_recurrent_destroy(None)
-    one = dict(ok, L=64)                                   # a single chunk carries no state
+    one = dict(ok, L=64)                                   # a single chunk: one slot (used when a state is handed in)
     h = A.ae_recurrent_create(**one)
-    assert A.ae_recurrent_workspace_bytes(h) == 0
+    assert A.ae_recurrent_workspace_bytes(h) == 2 * 4 * 128 * 128 * 2
     A.ae_recurrent_destroy(h)
     for patch, status in ((dict(chunk=100), A.AE_ERR_UNSUPPORTED), (dict(D_qk=192), A.AE_ERR_UNSUPPORTED),
                           (dict(D_qk=256, D_v=512), A.AE_ERR_UNSUPPORTED), (dict(H=300, gamma=[0.9] * 300), A.AE_ERR_UNSUPPORTED),

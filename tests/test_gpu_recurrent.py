@@ -148,3 +148,39 @@ def test_hip_graph_replays(A):
                 _check(Og.cpu().double().numpy(), ref, "rec_graph replay 0")
     finally:
         A.ae_recurrent_destroy(h)
+
+
+@pytest.mark.parametrize("D,chunk,cuts", [(128, 256, (0, 700, 1000)), (64, 64, (0, 50, 51, 300, 620)), (128, 128, (0, 128, 384, 385))])
+def test_sequence_in_pieces_with_carried_state(A, D, chunk, cuts):
+    """ae_recurrent_forward_state: a sequence processed in pieces, each starting from the state the piece before
+    handed back, against the oracle's single walk; the last state against the oracle's final state."""
+    L = cuts[-1]
+    w = _workload(f"rec_pieces_d{D}_c{chunk}", 795 + D, 2, 3, L, D)
+    Q, K, V = make_inputs(w)
+    gam = [0.96875, 1.0, 0.9]
+    scale = 1.0 / math.sqrt(D)
+    dev = torch.device("cuda:0")
+    Qd, Kd, Vd = Q.to(dev), K.to(dev), V.to(dev)
+    state, outs = None, []
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        print(f"case {w.name} tokens {a}..{b}", flush=True)
+        O, state = A.retention_recurrent(Qd[:, :, a:b].contiguous(), Kd[:, :, a:b].contiguous(), Vd[:, :, a:b].contiguous(),
+                                         scale=scale, gamma=gam, chunk=chunk, h_in=state, return_state=True)
+        outs.append(O)
+    torch.cuda.synchronize()
+    got = torch.cat(outs, dim=2).cpu().double().numpy()
+    ref = np.zeros_like(got)
+    for b_ in range(w.B):
+        for h_ in range(w.H_q):
+            ref[b_, h_], hs = retention_recurrent_head(Q[b_, h_].float().numpy(), K[b_, h_].float().numpy(), V[b_, h_].float().numpy(),
+                                                       scale=scale, gamma_h=gam[h_], return_state=True)
+            _check(state[b_, h_].cpu().double().numpy(), hs, f"{w.name} final state b{b_} h{h_}")
+    _check(got, ref, w.name)
+    # the state alone (no piece before, none after) equals the one of a plain call
+    O1, s1 = A.retention_recurrent(Qd, Kd, Vd, scale=scale, gamma=gam, chunk=chunk, return_state=True)
+    torch.cuda.synchronize()
+    _check(O1.cpu().double().numpy(), ref, w.name + " one call")
+    for b_ in range(w.B):
+        hs = retention_recurrent_head(Q[b_, 1].float().numpy(), K[b_, 1].float().numpy(), V[b_, 1].float().numpy(), scale=scale,
+                                      gamma_h=gam[1], return_state=True)[1]
+        _check(s1[b_, 1].cpu().double().numpy(), hs, f"{w.name} one call final state b{b_}")

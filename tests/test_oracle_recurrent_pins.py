@@ -72,3 +72,17 @@ def test_batched_and_per_head_gamma():
     for b in range(2):
         for h in range(3):
             np.testing.assert_array_equal(O[b, h], retention_recurrent_head(Q[b, h], K[b, h], V[b, h], scale=0.5, gamma_h=gam[h]))
+
+
+def test_initial_state_continues_a_sequence():
+    # a sequence walked in two pieces, the second starting from the first one's final state, is the sequence walked
+    # in one go (which the pins above tie to the parallel form): fixes where h0 enters and what the final state is
+    q, k, v = _rand(11, 30, 5, 4)
+    full, h_full = retention_recurrent_head(q, k, v, scale=0.4, gamma_h=0.93, return_state=True)
+    o1, h1 = retention_recurrent_head(q[:13], k[:13], v[:13], scale=0.4, gamma_h=0.93, return_state=True)
+    o2, h2 = retention_recurrent_head(q[13:], k[13:], v[13:], scale=0.4, gamma_h=0.93, return_state=True, h0=h1)
+    np.testing.assert_allclose(np.concatenate([o1, o2]), full, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(h2, h_full, rtol=1e-12, atol=1e-12)
+    # the final state by its closed form: sum_j gamma^(L-1-j) k_j^T v_j
+    w = 0.93 ** (29 - np.arange(30))
+    np.testing.assert_allclose(h_full, np.einsum("t,ti,tj->ij", w, k, v), rtol=1e-12, atol=1e-12)
