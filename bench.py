@@ -495,7 +495,40 @@ def main():
                   f"({100 * byts / best[1] / 1e6 / 8000.0:4.1f} % of HBM peak), {t_par / best[1]:5.2f}x the parallel form, max_abs {err:.2e}",
                   file=sys.stderr, flush=True)
             del Q, K, V, O
-        print(json.dumps({"recurrent": rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16", "data": "synthetic"}))
+        # One decoding step on the carried state (ae_recurrent_step): the state is read and written once,
+        # 8 bytes per element, which is all the traffic there is.
+        steps_rows = []
+        for name, B, H, D in (("retention_step_b8_h32_d128", 8, 32, 128), ("retention_step_b64_h32_d128", 64, 32, 128),
+                              ("retention_step_b64_h16_d64", 64, 16, 64)):
+            if a.only and a.only not in name:
+                continue
+            g = torch.Generator(device="cpu")
+            g.manual_seed(400 + len(steps_rows))
+            q, k, v = (torch.randn((B, H, D), generator=g).to(torch.bfloat16).to(dev) for _ in range(3))
+            state = torch.zeros((B, H, D, D), dtype=torch.float32, device=dev)
+            o = torch.empty((B, H, D), dtype=torch.float32, device=dev)
+            h = A.ae_recurrent_create(B=B, H=H, L=1, D_qk=D, D_v=D, chunk=64, scale=1.0 / math.sqrt(D),
+                                      gamma=[1.0 - 2.0 ** (-5 - (i % 8)) for i in range(H)])
+            st = torch.cuda.current_stream()
+            n = 200
+            for _ in range(10):
+                A.ae_recurrent_step(h, q.data_ptr(), k.data_ptr(), v.data_ptr(), state.data_ptr(), o.data_ptr(), st.cuda_stream)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            for _ in range(n):
+                A.ae_recurrent_step(h, q.data_ptr(), k.data_ptr(), v.data_ptr(), state.data_ptr(), o.data_ptr(), st.cuda_stream)
+            e1.record(st)
+            torch.cuda.synchronize()
+            A.ae_recurrent_destroy(h)
+            ms = e0.elapsed_time(e1) / n
+            byts = 8 * B * H * D * D
+            steps_rows.append({"workload": name, "us_per_step": round(ms * 1e3, 2), "tokens_per_s": round(B / ms * 1e3, 1),
+                               "GBps": round(byts / ms / 1e6, 1), "frac_of_hbm_peak": round(byts / ms / 1e6 / 8000.0, 4)})
+            print(f"# {name:32s} {ms * 1e3:8.2f} us per step = {byts / ms / 1e6:7.1f} GB/s ({100 * byts / ms / 1e6 / 8000.0:4.1f} % of HBM peak)",
+                  file=sys.stderr, flush=True)
+        print(json.dumps({"recurrent": rows, "recurrent_step": steps_rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16",
+                          "data": "synthetic"}))
         return
     if a.table2:
         # Not the contract line: the paper's own microbenchmark grid, one row per shape.

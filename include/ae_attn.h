@@ -322,6 +322,14 @@ ae_status_t ae_recurrent_forward(const ae_recurrent_t *h, const void *Q, const v
 ae_status_t ae_recurrent_forward_state(const ae_recurrent_t *h, const void *Q, const void *K, const void *V,
                                        const void *h_in, void *O, void *h_out, void *workspace,
                                        size_t workspace_bytes, void *stream);
+/* One token of the recurrence as Section 4.1 states it (K@V into the state,
+ * then Q@h), for decoding: state <- gamma * state + k^T v, o = scale * q state.
+ * q, k bf16 [B, H, D_qk], v bf16 [B, H, D_v], state fp32 [B, H, D_qk, D_v]
+ * (updated in place; the layout of h_in / h_out above), o fp32 [B, H, D_v]; all
+ * contiguous device memory, 16-byte aligned.  Uses B, H, the head dims, gamma
+ * and scale of the handle (L and chunk play no part).  No workspace.             */
+ae_status_t ae_recurrent_step(const ae_recurrent_t *h, const void *q, const void *k, const void *v, void *state,
+                              void *o, void *stream);
 ae_status_t ae_recurrent_destroy(ae_recurrent_t *h); /* NULL is allowed */
 
 #ifdef __cplusplus

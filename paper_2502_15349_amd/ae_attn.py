@@ -72,6 +72,8 @@ _lib.ae_recurrent_forward.argtypes = [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
 _lib.ae_recurrent_forward.restype = C.c_int
 _lib.ae_recurrent_forward_state.argtypes = [C.c_void_p] * 8 + [C.c_size_t, C.c_void_p]
 _lib.ae_recurrent_forward_state.restype = C.c_int
+_lib.ae_recurrent_step.argtypes = [C.c_void_p] * 7
+_lib.ae_recurrent_step.restype = C.c_int
 _lib.ae_recurrent_destroy.argtypes = [C.c_void_p]
 _lib.ae_recurrent_destroy.restype = C.c_int
 _lib.ae_attn_destroy.argtypes = [C.c_void_p]
@@ -235,6 +237,11 @@ def ae_recurrent_forward_state(handle: int, Q: int, K: int, V: int, h_in: int, O
     """ae_recurrent_forward with the state in front of the first token (h_in, 0: zero) and the state after the last
     one (h_out, 0: not computed), both fp32 [B, H, D_qk, D_v] device addresses."""
     _check(_lib.ae_recurrent_forward_state(handle, Q, K, V, h_in, O, h_out, workspace, workspace_bytes, stream))
+
+
+def ae_recurrent_step(handle: int, q: int, k: int, v: int, state: int, o: int, stream: int = 0) -> None:
+    """One token: state <- gamma state + k^T v (fp32 [B, H, D_qk, D_v], in place), o = scale q state (fp32 [B, H, D_v])."""
+    _check(_lib.ae_recurrent_step(handle, q, k, v, state, o, stream))
 
 
 def ae_recurrent_destroy(handle: Optional[int]) -> None:

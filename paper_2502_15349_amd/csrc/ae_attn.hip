@@ -692,6 +692,28 @@ ae_status_t ae_recurrent_forward(const ae_recurrent_t* h, const void* Q, const v
   return ae_recurrent_forward_state(h, Q, K, V, nullptr, O, nullptr, workspace, workspace_bytes, stream);
 }
 
+ae_status_t ae_recurrent_step(const ae_recurrent_t* h, const void* q, const void* k, const void* v, void* state, void* o,
+                              void* stream) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_step: null handle");
+  if (!q || !k || !v || !state || !o) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_step: null pointer");
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)state | (uintptr_t)o) & 15)
+    return fail(AE_ERR_INVALID_ARG, "ae_recurrent_step: pointers must be 16-byte aligned");
+  if (o == q || o == k || o == v || o == state || state == q || state == k || state == v)
+    return fail(AE_ERR_INVALID_ARG, "ae_recurrent_step: an output aliases another buffer");
+  ae::RecStepParams p;
+  p.q = static_cast<const __bf16*>(q);
+  p.k = static_cast<const __bf16*>(k);
+  p.v = static_cast<const __bf16*>(v);
+  p.state = static_cast<float*>(state);
+  p.o = static_cast<float*>(o);
+  p.B = h->desc.B;
+  p.H = h->desc.H;
+  p.scale = h->desc.scale;
+  const hipError_t e = ae::launch_recurrent_step(p, h->decay, h->desc.D_qk, h->desc.D_v, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_recurrent_step: %s", hipGetErrorString(e));
+  return AE_OK;
+}
+
 ae_status_t ae_recurrent_destroy(ae_recurrent_t* h) {
   if (h) {
     ae_attn_destroy(h->full);

@@ -18,4 +18,14 @@ struct RecParams {
 bool recurrent_supported(int dqk, int dv);
 // The states in front of chunks 1 .. n_chunks-1 (and 0, from h_in), and the final state if asked for.
 hipError_t launch_recurrent_states(const RecParams& p, const DecayTable& dt, int dqk, int dv, hipStream_t stream);
+// One token: state = gamma * state + k^T v (fp32 [B, H, D_qk, D_v], in place), o = scale * q state (fp32 [B, H, D_v]);
+// q, k bf16 [B, H, D_qk], v bf16 [B, H, D_v].
+struct RecStepParams {
+  const __bf16 *q, *k, *v;
+  float* state;
+  float* o;
+  int B, H;
+  float scale;
+};
+hipError_t launch_recurrent_step(const RecStepParams& p, const DecayTable& dt, int dqk, int dv, hipStream_t stream);
 }  // namespace ae

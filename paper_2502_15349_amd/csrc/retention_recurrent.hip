@@ -167,6 +167,55 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
   }
 }
 
+// One step of the recurrence as the paper's recurrent pattern states it (K@V into the state, then Q@h): a pass over
+// the state, which is all the traffic there is (8 bytes per state element).  One workgroup per (batch, head);
+// a thread owns four columns of D_v in every (256 / (D_v / 4))-th row; the partial read-outs meet in LDS.
+template <int DK, int DV>
+__global__ __launch_bounds__(256) void rec_step_kernel(const RecStepParams p, const DecayTable dt) {
+  constexpr int CG = DV / 4, RG = 256 / CG;  // column groups, row groups
+  __shared__ float4 part[RG][CG];
+  const int bh = blockIdx.x, tid = threadIdx.x, cg = tid % CG, rg = tid / CG;
+  const float g = exp2f(dt.log2_gamma[bh % p.H]);
+  const __bf16* q = p.q + (int64_t)bh * DK;
+  const __bf16* k = p.k + (int64_t)bh * DK;
+  const bf16x4 vb = *reinterpret_cast<const bf16x4*>(p.v + (int64_t)bh * DV + 4 * cg);
+  const float v0 = (float)vb[0], v1 = (float)vb[1], v2 = (float)vb[2], v3 = (float)vb[3];
+  float4* st = reinterpret_cast<float4*>(p.state + (int64_t)bh * (DK * DV)) + cg;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+  for (int r = rg; r < DK; r += RG) {
+    float4 h = st[(int64_t)r * CG];
+    const float kr = (float)k[r], qr = (float)q[r];
+    h.x = g * h.x + kr * v0;
+    h.y = g * h.y + kr * v1;
+    h.z = g * h.z + kr * v2;
+    h.w = g * h.w + kr * v3;
+    st[(int64_t)r * CG] = h;
+    acc.x += qr * h.x;
+    acc.y += qr * h.y;
+    acc.z += qr * h.z;
+    acc.w += qr * h.w;
+  }
+  part[rg][cg] = acc;
+  __syncthreads();
+  if (tid < CG) {
+    float4 s = part[0][tid];
+#pragma unroll
+    for (int i = 1; i < RG; ++i) {
+      const float4 x = part[i][tid];
+      s.x += x.x;
+      s.y += x.y;
+      s.z += x.z;
+      s.w += x.w;
+    }
+    s.x *= p.scale;
+    s.y *= p.scale;
+    s.z *= p.scale;
+    s.w *= p.scale;
+    reinterpret_cast<float4*>(p.o + (int64_t)bh * DV)[tid] = s;
+  }
+}
+
 template <int DK, int DV>
 hipError_t launch_dims(const RecParams& p, const DecayTable& dt, hipStream_t stream) {
   rec_state_kernel<DK, DV><<<dim3(p.B * p.H * (DV / 32)), dim3(2 * DK), 0, stream>>>(p, dt);
@@ -176,6 +225,13 @@ hipError_t launch_dims(const RecParams& p, const DecayTable& dt, hipStream_t str
 }  // namespace
 
 bool recurrent_supported(int dqk, int dv) { return (dqk == 64 && dv == 64) || (dqk == 128 && dv == 128); }
+
+hipError_t launch_recurrent_step(const RecStepParams& p, const DecayTable& dt, int dqk, int dv, hipStream_t stream) {
+  if (dqk == 64 && dv == 64) rec_step_kernel<64, 64><<<dim3(p.B * p.H), dim3(256), 0, stream>>>(p, dt);
+  else if (dqk == 128 && dv == 128) rec_step_kernel<128, 128><<<dim3(p.B * p.H), dim3(256), 0, stream>>>(p, dt);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
 
 hipError_t launch_recurrent_states(const RecParams& p, const DecayTable& dt, int dqk, int dv, hipStream_t stream) {
   if (p.chunk % 64 != 0 || (p.n_chunks < 2 && !p.h_in && !p.h_out)) return hipErrorInvalidValue;

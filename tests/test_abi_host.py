@@ -324,6 +324,11 @@ def test_recurrent_descriptor_and_entry_point_checks():
             with pytest.raises(A.AeAttnError) as ei:
                 A.ae_recurrent_forward_state(h, *args, need)
             assert ei.value.status == A.AE_ERR_INVALID_ARG, (args, A.ae_attn_last_error())
+        # one-token step: q k v state o
+        for args in ((0, k, v, ws, o), (q, k, v, ws + 4, o), (q, k, v, ws, ws), (q, k, v, q, o)):
+            with pytest.raises(A.AeAttnError) as ei:
+                A.ae_recurrent_step(h, *args)
+            assert ei.value.status == A.AE_ERR_INVALID_ARG, (args, A.ae_attn_last_error())
     finally:
         A.ae_recurrent_destroy(h)
     A.ae_recurrent_destroy(None)

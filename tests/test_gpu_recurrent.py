@@ -184,3 +184,57 @@ def test_sequence_in_pieces_with_carried_state(A, D, chunk, cuts):
         hs = retention_recurrent_head(Q[b_, 1].float().numpy(), K[b_, 1].float().numpy(), V[b_, 1].float().numpy(), scale=scale,
                                       gamma_h=gam[1], return_state=True)[1]
         _check(s1[b_, 1].cpu().double().numpy(), hs, f"{w.name} one call final state b{b_}")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_decoding_steps_after_a_prefill(A, D):
+    """ae_recurrent_step: a prefill through ae_recurrent_forward_state, then six tokens one at a time on the
+    carried fp32 state, against the oracle's single walk over all tokens (outputs of the steps and the last state)."""
+    B, H, L0, T = 3, 5, 200, 6
+    w = _workload(f"rec_step_d{D}", 797 + D, B, H, L0 + T, D)
+    Q, K, V = make_inputs(w)
+    gam = _gammas(H)
+    scale = 1.0 / math.sqrt(D)
+    dev = torch.device("cuda:0")
+    Qd, Kd, Vd = Q.to(dev), K.to(dev), V.to(dev)
+    print(f"case {w.name} prefill", flush=True)
+    _, state = A.retention_recurrent(Qd[:, :, :L0].contiguous(), Kd[:, :, :L0].contiguous(), Vd[:, :, :L0].contiguous(),
+                                     scale=scale, gamma=gam, chunk=64, return_state=True)
+    h = A.ae_recurrent_create(B=B, H=H, L=1, D_qk=D, D_v=D, chunk=64, scale=scale, gamma=gam)
+    outs = []
+    try:
+        st = torch.cuda.current_stream()
+        for t in range(L0, L0 + T):
+            print(f"case {w.name} step {t}", flush=True)
+            q, k, v = (x[:, :, t].contiguous() for x in (Qd, Kd, Vd))
+            o = torch.empty((B, H, D), dtype=torch.float32, device=dev)
+            A.ae_recurrent_step(h, q.data_ptr(), k.data_ptr(), v.data_ptr(), state.data_ptr(), o.data_ptr(), st.cuda_stream)
+            outs.append(o)
+        torch.cuda.synchronize()
+    finally:
+        A.ae_recurrent_destroy(h)
+    got = torch.stack(outs, dim=2).cpu().double().numpy()
+    for b_ in range(B):
+        for h_ in range(H):
+            ref, hs = retention_recurrent_head(Q[b_, h_].float().numpy(), K[b_, h_].float().numpy(), V[b_, h_].float().numpy(),
+                                               scale=scale, gamma_h=gam[h_], return_state=True)
+            _check(got[b_, h_], ref[L0:], f"{w.name} steps b{b_} h{h_}")
+            _check(state[b_, h_].cpu().double().numpy(), hs, f"{w.name} state b{b_} h{h_}")
+    # from a zero state the steps alone are the recurrence in fp32: much tighter than the bf16 bar
+    h = A.ae_recurrent_create(B=B, H=H, L=1, D_qk=D, D_v=D, chunk=64, scale=scale, gamma=gam)
+    state0 = torch.zeros((B, H, D, D), dtype=torch.float32, device=dev)
+    outs = []
+    try:
+        for t in range(T):
+            q, k, v = (x[:, :, t].contiguous() for x in (Qd, Kd, Vd))
+            o = torch.empty((B, H, D), dtype=torch.float32, device=dev)
+            A.ae_recurrent_step(h, q.data_ptr(), k.data_ptr(), v.data_ptr(), state0.data_ptr(), o.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            outs.append(o)
+        torch.cuda.synchronize()
+    finally:
+        A.ae_recurrent_destroy(h)
+    got = torch.stack(outs, dim=2).cpu().double().numpy()
+    ref = oracle_recurrent(Q[:, :, :T].float().numpy(), K[:, :, :T].float().numpy(), V[:, :, :T].float().numpy(), scale=scale, gamma=gam)
+    err = np.abs(got - ref).max()
+    print(f"{w.name} steps from zero: max abs {err:.3e}", flush=True)
+    assert err <= 1e-4
