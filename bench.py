@@ -389,8 +389,9 @@ def main():
             stats = torch.empty((w.B, w.H_q, w.L_q), dtype=torch.float32, device=dev)
             grads = [torch.empty(x.shape, dtype=torch.float32, device=dev) for x in (Q, K, V)]
             bres = {}
-            for name, ww in (("plain", base), ("bias_tensor", w)):
-                A.run_workload(ww, Q, K, V, out=O, stats=stats, bias_tensor=btd if name == "bias_tensor" else None)
+            dB = torch.zeros((w.B, w.H_q, w.L_q, w.L_k), dtype=torch.bfloat16, device=dev)   # the bias gradient, zero-filled once
+            for name, ww in (("plain", base), ("bias_tensor", w), ("bias_tensor_dbias", w)):
+                A.run_workload(ww, Q, K, V, out=O, stats=stats, bias_tensor=None if name == "plain" else btd)
                 h = A.ae_attn_create(B=w.B, H_q=w.H_q, H_kv=w.H_kv, L_q=w.L_q, L_k=w.L_k, D_qk=w.D_qk, D_v=w.D_v,
                                      scale=w.scale_value, score_mod=ww.score_mod, mask=w.mask,
                                      bias_stride=(0, btd.stride(1), btd.stride(2)))
@@ -402,8 +403,11 @@ def main():
                 def bcall():
                     if name == "plain":
                         A.ae_attn_backward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), *tail)
-                    else:
+                    elif name == "bias_tensor":
                         A.ae_attn_backward_bias(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), btd.data_ptr(), *tail[:6], 0, 0, *tail[6:])
+                    else:
+                        A.ae_attn_backward_bias(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), btd.data_ptr(), *tail[:6], dB.data_ptr(), w.L_k,
+                                                *tail[6:])
                 for _ in range(3):
                     bcall()
                 torch.cuda.synchronize()
@@ -422,13 +426,15 @@ def main():
                          "plain_tflops": round(flop / res["plain"] / 1e9, 1), "bias_tensor_tflops": round(flop / res["bias_tensor"] / 1e9, 1),
                          "bias_GBps": round(bias_bytes / res["bias_tensor"] / 1e6, 1), "parity_max_abs": err,
                          "backward_plain_ms": round(bres["plain"], 4), "backward_bias_tensor_ms": round(bres["bias_tensor"], 4),
-                         "backward_bias_tensor_tflops": round(bflop / bres["bias_tensor"] / 1e9, 1)})
+                         "backward_bias_tensor_tflops": round(bflop / bres["bias_tensor"] / 1e9, 1),
+                         "backward_with_dbias_ms": round(bres["bias_tensor_dbias"], 4)})
             print(f"# {w.name:32s} plain {res['plain']:8.4f} ms {flop / res['plain'] / 1e9:7.1f} TFLOP/s | bias tensor "
                   f"{res['bias_tensor']:8.4f} ms {flop / res['bias_tensor'] / 1e9:7.1f} TFLOP/s ({100 * flop / res['bias_tensor'] / 1e9 / PEAK_BF16_TFLOPS:4.1f} % "
                   f"of peak), bias read at {bias_bytes / res['bias_tensor'] / 1e6:7.1f} GB/s  max_abs {err:.2e} | backward plain "
-                  f"{bres['plain']:8.4f} ms, bias tensor {bres['bias_tensor']:8.4f} ms {bflop / bres['bias_tensor'] / 1e9:7.1f} TFLOP/s",
+                  f"{bres['plain']:8.4f} ms, bias tensor {bres['bias_tensor']:8.4f} ms {bflop / bres['bias_tensor'] / 1e9:7.1f} TFLOP/s, "
+                  f"with dBias {bres['bias_tensor_dbias']:8.4f} ms",
                   file=sys.stderr, flush=True)
-            del Q, K, V, O, btd, dO, grads
+            del Q, K, V, O, btd, dO, grads, dB
         print(json.dumps({"bias_tensor": rows, "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS, "dtype": "bf16", "data": "synthetic"}))
         return
     if a.recurrent:
