@@ -637,6 +637,34 @@ def main():
         btf = 2 * (3 * w.D_qk + 2 * w.D_v) * w.visible_pairs_per_head() * w.B * w.H_q / (bms * 1e-3) / 1e12
         variants[w.name + "_backward"] = {"tflops": round(btf, 2), "frac_of_peak": round(btf / PEAK_BF16_TFLOPS, 4),
                                          "ms": round(bms, 5)}
+        del grads, dO, Of, wsb
+        # the recurrent pattern (ae_recurrent_forward, chunks of 256) on 8 x 32 heads x 8192 tokens, 128/128, priced
+        # against HBM: compulsory bytes (Q, K, V once, O once) / time.  `bench.py --recurrent` has the other shapes.
+        import math
+        from paper_2502_15349_amd.workloads import Workload
+        wr = Workload("retention_b8_h32_s8192_d128", 301, 8, 32, 32, 8192, 8192, 128, 128, score_mod="head_decay", norm="none", mask="causal")
+        Qr, Kr, Vr = (x.to(dev) for x in make_inputs(wr))
+        Or = torch.empty((wr.B, wr.H_q, wr.L_q, wr.D_v), dtype=torch.float32, device=dev)
+        hr = A.ae_recurrent_create(B=wr.B, H=wr.H_q, L=wr.L_q, D_qk=128, D_v=128, chunk=256, scale=1.0 / math.sqrt(128),
+                                   gamma=[1.0 - 2.0 ** (-5 - (i % 8)) for i in range(wr.H_q)])
+        wsr = torch.empty(A.ae_recurrent_workspace_bytes(hr), dtype=torch.uint8, device=dev)
+        rargs = (hr, Qr.data_ptr(), Kr.data_ptr(), Vr.data_ptr(), Or.data_ptr(), wsr.data_ptr(), wsr.numel(), st.cuda_stream)
+        for _ in range(3):
+            A.ae_recurrent_forward(*rargs)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(20):
+            A.ae_recurrent_forward(*rargs)
+        e1.record(st)
+        torch.cuda.synchronize()
+        A.ae_recurrent_destroy(hr)
+        rms = e0.elapsed_time(e1) / 20
+        rbytes = wr.B * wr.H_q * wr.L_q * (2 * (2 * 128 + 128) + 4 * 128)
+        variants[wr.name + "_recurrent"] = {"ms": round(rms, 5), "GBps": round(rbytes / rms / 1e6, 1),
+                                            "frac_of_hbm_peak": round(rbytes / rms / 1e6 / 8000.0, 4),
+                                            "tokens_per_s": round(wr.B * wr.L_q / rms * 1e3, 1)}
+        del Qr, Kr, Vr, Or, wsr
         out["variants"] = variants
 
     # What the matrix pipes sustain on this board with nothing else in the way: the library's
