@@ -238,3 +238,34 @@ def test_decoding_steps_after_a_prefill(A, D):
     err = np.abs(got - ref).max()
     print(f"{w.name} steps from zero: max abs {err:.3e}", flush=True)
     assert err <= 1e-4
+
+
+def test_state_updated_in_place(A):
+    """h_out may be the buffer h_in points to (every workgroup reads its slice of the state before it writes it):
+    the in-place call must give the bits of the call with separate buffers."""
+    dev = torch.device("cuda:0")
+    w = _workload("rec_inplace", 799, 2, 4, 333, 128)
+    Q, K, V = (x.to(dev) for x in make_inputs(w))
+    gam = _gammas(4)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(799)
+    h0 = torch.randn((2, 4, 128, 128), generator=g, dtype=torch.float32).to(dev)
+    O1, s1 = A.retention_recurrent(Q, K, V, scale=0.09, gamma=gam, chunk=128, h_in=h0, return_state=True)
+    h = A.ae_recurrent_create(B=2, H=4, L=333, D_qk=128, D_v=128, chunk=128, scale=0.09, gamma=gam)
+    try:
+        ws = torch.empty(A.ae_recurrent_workspace_bytes(h), dtype=torch.uint8, device=dev)
+        O2 = torch.empty_like(O1)
+        buf = h0.clone()
+        print("case rec_inplace", flush=True)
+        A.ae_recurrent_forward_state(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), buf.data_ptr(), O2.data_ptr(), buf.data_ptr(),
+                                     ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+    finally:
+        A.ae_recurrent_destroy(h)
+    assert torch.equal(O1, O2) and torch.equal(s1, buf)
+    # and against the oracle, which starts from the same state
+    for b_, h_ in ((0, 0), (1, 3)):
+        ref, hs = retention_recurrent_head(Q[b_, h_].float().cpu().numpy(), K[b_, h_].float().cpu().numpy(), V[b_, h_].float().cpu().numpy(),
+                                           scale=0.09, gamma_h=gam[h_], return_state=True, h0=h0[b_, h_].cpu().double().numpy())
+        _check(O2[b_, h_].cpu().double().numpy(), ref, f"rec_inplace b{b_} h{h_}")
+        _check(buf[b_, h_].cpu().double().numpy(), hs, f"rec_inplace state b{b_} h{h_}")
