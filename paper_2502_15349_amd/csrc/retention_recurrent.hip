@@ -35,22 +35,27 @@ __device__ __forceinline__ bf16x8 read_tr(uint32_t lo, uint32_t hi) {
 // both operands.  The 64-token blocks are stored to LDS as they come (16 bytes per lane, the decay applied to V
 // on the way) and read with the transposing LDS read.  Row strides of 16 or 48 (mod 64) words keep the four
 // rows x two column groups that half a wave reads at once on different banks.
-// DK/32 waves; wave w owns the 32 x 32 tile of dk block w.
-template <int DK, int DV>
-__global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, const DecayTable dt) {
-  constexpr int THREADS = 2 * DK, NS = DV / 32;  // NS slices of D_v per (batch, head)
-  constexpr int KP = 64 * (DK / 8) / THREADS;    // 16-byte pieces of a K block per thread (= 4)
-  constexpr int VP = (64 * 4 + THREADS - 1) / THREADS;  // and of the V slice (1 or 2)
-  constexpr int KS = DK * 2 + (DK == 128 ? 64 : 64);    // bytes per K row in LDS: 80 / 48 words
-  constexpr int VS = 64;                                 // 32 columns: 16 words
+// A workgroup owns NSL slices of 32 D_v columns, NSL * DK/32 waves; a wave owns one 32 x 32 tile (slice, dk block).
+// NSL = D_v / 32: one workgroup per (batch, head), K staged once for all slices (many (batch, head) pairs);
+// NSL = 1: a workgroup per slice, four times the workgroups (few pairs: the walk is sequential per workgroup).
+template <int DK, int DV, int NSL>
+__global__ __launch_bounds__(2 * DK * NSL) void rec_state_kernel(const RecParams p, const DecayTable dt) {
+  constexpr int THREADS = 2 * DK * NSL, NS = DV / (32 * NSL);  // NS workgroups per (batch, head)
+  constexpr int KP = (64 * (DK / 8) + THREADS - 1) / THREADS;  // 16-byte pieces of a K block per thread
+  constexpr int VPIECES = 64 * 4 * NSL, VP = (VPIECES + THREADS - 1) / THREADS;  // and of the V slices
+  constexpr int KS = DK * 2 + 64;                               // bytes per K row in LDS: 80 / 48 words
+  constexpr int VS = NSL == 1 ? 64 : 64 * NSL + 64;             // 16 words, or 80 / 48
   static_assert((KS / 4) % 64 == 16 || (KS / 4) % 64 == 48, "K row stride");
+  static_assert((VS / 4) % 64 == 16 || (VS / 4) % 64 == 48, "V row stride");
+  static_assert(64 * (DK / 8) % THREADS == 0 && VPIECES % THREADS == 0, "every thread copies the same number of pieces");
   __shared__ __attribute__((aligned(16))) char Ks[64 * KS];
   __shared__ __attribute__((aligned(16))) char Vs[64 * VS];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  // The slices of one (batch, head) read the same K: they go to one XCD (workgroups are dealt to the 8 XCDs
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int w = wave % (DK / 32), sl = wave / (DK / 32);  // dk block and slice of this wave
+  // The workgroups of one (batch, head) read the same K: they go to one XCD (workgroups are dealt to the 8 XCDs
   // round-robin by id), next to each other in time, so that its L2 serves the repeats.
   const int bhs = p.B * p.H;
-  int bh, slice;
+  int bh, slice;  // slice: the first one of the workgroup, then this wave's
   if (bhs % 8 == 0) {
     const int x = blockIdx.x % 8, k = blockIdx.x / 8;
     bh = (k / NS) * 8 + x;
@@ -59,10 +64,12 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
     bh = blockIdx.x / NS;
     slice = blockIdx.x % NS;
   }
+  const int slice0 = slice * NSL;
+  slice = slice0 + sl;
   const float lg = dt.log2_gamma[bh % p.H];
   const float g_chunk = exp2f(lg * (float)p.chunk);
   const __bf16* Kb = p.K + (int64_t)bh * p.L * DK;
-  const __bf16* Vb = p.V + (int64_t)bh * p.L * DV + slice * 32;
+  const __bf16* Vb = p.V + (int64_t)bh * p.L * DV + slice0 * 32;
   __bf16* HTb = p.HT + (int64_t)bh * p.n_chunks * (DV * DK) + (int64_t)slice * 32 * DK;  // slot c: the state in front of chunk c
 
   // fragment addresses of contraction step 0: tokens 8 (lane / 32) + (lane % 16) / 4, column 16 ((lane / 16) % 2) + 4 (lane % 4)
@@ -71,7 +78,7 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
   const uint32_t ks0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)Ks);
   const uint32_t vs0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)Vs);
   const uint32_t ka = ks0 + frow * KS + (w * 32 + fcol) * 2;
-  const uint32_t va = vs0 + frow * VS + fcol * 2;
+  const uint32_t va = vs0 + frow * VS + (sl * 32 + fcol) * 2;
 
   f32x16 acc;
 #pragma unroll
@@ -104,8 +111,8 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
     }
 #pragma unroll
     for (int it = 0; it < VP; ++it) {
-      const int piece = tid + it * THREADS, row = piece / 4, c8 = piece % 4;
-      if (piece < 256) vreg[S][it] = *reinterpret_cast<const bf16x8*>(Vb + (int64_t)min(t0 + row, p.L - 1) * DV + c8 * 8);
+      const int piece = tid + it * THREADS, row = piece / (4 * NSL), c8 = piece % (4 * NSL);
+      vreg[S][it] = *reinterpret_cast<const bf16x8*>(Vb + (int64_t)min(t0 + row, p.L - 1) * DV + c8 * 8);
     }
   };
   auto process = [&](auto setc, int blk) {
@@ -123,8 +130,8 @@ __global__ __launch_bounds__(2 * DK) void rec_state_kernel(const RecParams p, co
     // the token's decay goes onto its V row: the slice has a quarter of the K block's elements (at 128/128)
 #pragma unroll
     for (int it = 0; it < VP; ++it) {
-      const int piece = tid + it * THREADS, row = piece / 4, c8 = piece % 4;
-      if (piece < 256) {
+      const int piece = tid + it * THREADS, row = piece / (4 * NSL), c8 = piece % (4 * NSL);
+      {
         const float decay = j0 + row < len ? exp2f(lg * (float)(len - 1 - (j0 + row))) : 0.f;
         bf16x8 x;
 #pragma unroll
@@ -218,7 +225,9 @@ __global__ __launch_bounds__(256) void rec_step_kernel(const RecStepParams p, co
 
 template <int DK, int DV>
 hipError_t launch_dims(const RecParams& p, const DecayTable& dt, hipStream_t stream) {
-  rec_state_kernel<DK, DV><<<dim3(p.B * p.H * (DV / 32)), dim3(2 * DK), 0, stream>>>(p, dt);
+  // enough (batch, head) pairs to give every CU a workgroup: all slices in one workgroup, K staged once
+  if (p.B * p.H >= 256) rec_state_kernel<DK, DV, DV / 32><<<dim3(p.B * p.H), dim3(2 * DK * (DV / 32)), 0, stream>>>(p, dt);
+  else rec_state_kernel<DK, DV, 1><<<dim3(p.B * p.H * (DV / 32)), dim3(2 * DK), 0, stream>>>(p, dt);
   return hipGetLastError();
 }
 
