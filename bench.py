@@ -491,6 +491,14 @@ def main():
                 if best is None or t < best[1]:
                     best = (chunk, t)
                 del ws
+            # the same with bf16 output (chunk 256): 2 instead of 4 bytes per output element
+            h = A.ae_recurrent_create(B=B, H=H, L=L, D_qk=D, D_v=D, chunk=256, scale=scale, gamma=gam, out_dtype="bf16")
+            ws = torch.empty(A.ae_recurrent_workspace_bytes(h), dtype=torch.uint8, device=dev)
+            O16 = torch.empty((B, H, L, D), dtype=torch.bfloat16, device=dev)
+            row["chunk256_bf16_out_ms"] = round(timed(lambda: A.ae_recurrent_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O16.data_ptr(),
+                                                                                      ws.data_ptr(), ws.numel(), st.cuda_stream), a.steps), 4)
+            A.ae_recurrent_destroy(h)
+            del ws, O16
             row.update({"best_chunk": best[0], "ms": round(best[1], 4), "tokens_per_s": round(B * L / best[1] * 1e3, 1),
                         "GBps": round(byts / best[1] / 1e6, 1), "frac_of_hbm_peak": round(byts / best[1] / 1e6 / 8000.0, 4),
                         "recurrence_tflops": round(flop / best[1] / 1e9, 1), "speedup_vs_parallel_form": round(t_par / best[1], 2),
@@ -498,7 +506,8 @@ def main():
             rows.append(row)
             print(f"# {name:32s} parallel form {t_par:8.4f} ms | chunks 64/128/256: {row['chunk64_ms']:8.4f} {row['chunk128_ms']:8.4f} "
                   f"{row['chunk256_ms']:8.4f} ms | best {best[1]:8.4f} ms = {byts / best[1] / 1e6:7.1f} GB/s "
-                  f"({100 * byts / best[1] / 1e6 / 8000.0:4.1f} % of HBM peak), {t_par / best[1]:5.2f}x the parallel form, max_abs {err:.2e}",
+                  f"({100 * byts / best[1] / 1e6 / 8000.0:4.1f} % of HBM peak), {t_par / best[1]:5.2f}x the parallel form, max_abs {err:.2e}"
+                  f" | bf16 out {row['chunk256_bf16_out_ms']:8.4f} ms",
                   file=sys.stderr, flush=True)
             del Q, K, V, O
         # One decoding step on the carried state (ae_recurrent_step): the state is read and written once,

@@ -289,7 +289,7 @@ int32_t ae_attn_version(void);
  * walks the chunk's own keys on top of it.  The work grows linearly with L.
  *
  * Layouts: Q, K [B, H, L, D_qk] and V [B, H, L, D_v] bf16, O [B, H, L, D_v]
- * fp32, all contiguous, device memory, 16-byte aligned; the caller owns them.
+ * fp32 (or bf16, desc.out_dtype), all contiguous, device memory, 16-byte aligned; the caller owns them.
  * gamma: host array [H], each in (0, 1] (read by create only).  chunk: 64, 128
  * or 256 tokens (256 fills the parallel kernel's 256-row tile).  Head dims
  * 64/64 and 128/128; H <= AE_MAX_DECAY_HEADS.
@@ -313,6 +313,7 @@ typedef struct {
   int32_t chunk;
   float scale;        /* finite and non-zero */
   const float *gamma; /* host array [H] */
+  ae_out_dtype_t out_dtype; /* element type of O: AE_OUT_F32 (0), or AE_OUT_BF16 (fp32 rows rounded when stored) */
 } ae_recurrent_desc_t;
 
 ae_status_t ae_recurrent_create(const ae_recurrent_desc_t *desc, ae_recurrent_t **out);

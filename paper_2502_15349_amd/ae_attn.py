@@ -61,7 +61,7 @@ _lib.ae_attn_backward_bias.restype = C.c_int
 
 class ae_recurrent_desc_t(C.Structure):
     _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("L", C.c_int32), ("D_qk", C.c_int32), ("D_v", C.c_int32),
-                ("chunk", C.c_int32), ("scale", C.c_float), ("gamma", C.POINTER(C.c_float))]
+                ("chunk", C.c_int32), ("scale", C.c_float), ("gamma", C.POINTER(C.c_float)), ("out_dtype", C.c_int)]
 
 
 _lib.ae_recurrent_create.argtypes = [C.POINTER(ae_recurrent_desc_t), C.POINTER(C.c_void_p)]
@@ -209,9 +209,10 @@ def ae_attn_query(handle: int) -> dict:
 
 # ---- convenience for torch callers (still marshalling only) -------------------
 def ae_recurrent_create(*, B: int, H: int, L: int, D_qk: int, D_v: int, chunk: int, scale: float,
-                        gamma: Optional[Sequence[float]]) -> int:
+                        gamma: Optional[Sequence[float]], out_dtype="f32") -> int:
     """Handle for chunk-parallel recurrent retention (h_t = gamma h_{t-1} + k_t^T v_t, o_t = scale q_t h_t)."""
-    d = ae_recurrent_desc_t(B=B, H=H, L=L, D_qk=D_qk, D_v=D_v, chunk=chunk, scale=scale)
+    d = ae_recurrent_desc_t(B=B, H=H, L=L, D_qk=D_qk, D_v=D_v, chunk=chunk, scale=scale,
+                            out_dtype=OUT_DTYPES[out_dtype] if isinstance(out_dtype, str) else int(out_dtype))
     keep = None
     if gamma is not None:
         keep = (C.c_float * len(gamma))(*[float(g) for g in gamma])
@@ -249,9 +250,9 @@ def ae_recurrent_destroy(handle: Optional[int]) -> None:
 
 
 def retention_recurrent(Q, K, V, *, scale, gamma, chunk=256, out=None, workspace=None, stream=None, h_in=None,
-                        return_state=False):
+                        return_state=False, out_dtype=None):
     """Recurrent retention on contiguous bf16 device tensors Q, K [B, H, L, D_qk], V [B, H, L, D_v];
-    returns O [B, H, L, D_v] fp32.  workspace: device byte tensor of ae_recurrent_workspace_bytes() bytes
+    returns O [B, H, L, D_v] fp32 (bf16 with out_dtype=torch.bfloat16 or a bf16 `out`).  workspace: device byte tensor of ae_recurrent_workspace_bytes() bytes
     (allocated here if not given).  h_in: optional contiguous fp32 device tensor [B, H, D_qk, D_v], the state in
     front of the first token; return_state: also return the state after the last token (same layout)."""
     import torch
@@ -264,10 +265,11 @@ def retention_recurrent(Q, K, V, *, scale, gamma, chunk=256, out=None, workspace
     if K.shape != Q.shape or V.shape[:3] != Q.shape[:3]:
         raise ValueError("K / V shape does not match Q")
     if out is None:
-        out = torch.empty((B, H, L, D_v), dtype=torch.float32, device=Q.device)
-    if out.dtype != torch.float32 or tuple(out.shape) != (B, H, L, D_v) or not out.is_contiguous():
-        raise ValueError("O must be a contiguous fp32 tensor [B, H, L, D_v]")
-    h = ae_recurrent_create(B=B, H=H, L=L, D_qk=D_qk, D_v=D_v, chunk=chunk, scale=scale, gamma=gamma)
+        out = torch.empty((B, H, L, D_v), dtype=out_dtype or torch.float32, device=Q.device)
+    if out.dtype not in (torch.float32, torch.bfloat16) or tuple(out.shape) != (B, H, L, D_v) or not out.is_contiguous():
+        raise ValueError("O must be a contiguous fp32 or bf16 tensor [B, H, L, D_v]")
+    h = ae_recurrent_create(B=B, H=H, L=L, D_qk=D_qk, D_v=D_v, chunk=chunk, scale=scale, gamma=gamma,
+                            out_dtype="bf16" if out.dtype == torch.bfloat16 else "f32")
     try:
         s = torch.cuda.current_stream(Q.device) if stream is None else stream
         with torch.cuda.device(Q.device):

@@ -567,6 +567,8 @@ ae_status_t ae_recurrent_create(const ae_recurrent_desc_t* d, ae_recurrent_t** o
       return fail(AE_ERR_INVALID_ARG, "ae_recurrent_create: gamma[%d] must be in (0, 1]", i);
   if (d->chunk != 64 && d->chunk != 128 && d->chunk != 256)
     return fail(AE_ERR_UNSUPPORTED, "ae_recurrent_create: chunk must be 64, 128 or 256");
+  if (d->out_dtype != AE_OUT_F32 && d->out_dtype != AE_OUT_BF16)
+    return fail(AE_ERR_INVALID_ARG, "ae_recurrent_create: unknown out_dtype");
   if (!ae::recurrent_supported(d->D_qk, d->D_v))
     return fail(AE_ERR_UNSUPPORTED, "ae_recurrent_create: head dims %d/%d not built (64/64, 128/128)", d->D_qk, d->D_v);
   if ((int64_t)d->L * std::max(d->D_qk, d->D_v) * 2 >= (int64_t)1 << 32)
@@ -594,7 +596,7 @@ ae_status_t ae_recurrent_create(const ae_recurrent_desc_t* d, ae_recurrent_t** o
   a.norm = AE_NORM_NONE;
   a.mask = AE_MASK_CAUSAL;
   a.scale = d->scale;
-  a.out_dtype = AE_OUT_F32;
+  a.out_dtype = d->out_dtype;
   const int64_t L = d->L;
   auto strides = [&](int64_t* st, int D) { st[0] = (int64_t)d->chunk * D; st[1] = L * D; st[2] = D; };
   strides(a.q_stride, d->D_qk);
@@ -679,7 +681,8 @@ ae_status_t ae_recurrent_forward_state(const ae_recurrent_t* h, const void* Q, c
       cs.head_stride = (int64_t)h->n_chunks * state_elems;
       const bool has_state = part == 0 ? (h->n_full > 1 || h_in) : (h->n_full > 0 || h_in);
       const ae_status_t st = forward_impl(a, static_cast<const __bf16*>(Q) + r0 * d.D_qk, static_cast<const __bf16*>(K) + r0 * d.D_qk,
-                                          static_cast<const __bf16*>(V) + r0 * d.D_v, static_cast<float*>(O) + r0 * d.D_v, nullptr,
+                                          static_cast<const __bf16*>(V) + r0 * d.D_v,
+                                          static_cast<char*>(O) + r0 * d.D_v * (d.out_dtype == AE_OUT_BF16 ? 2 : 4), nullptr,
                                           stream, nullptr, 0, nullptr, has_state ? &cs : nullptr);
       if (st != AE_OK) return st;
     }

@@ -339,7 +339,7 @@ def test_recurrent_descriptor_and_entry_point_checks():
     for patch, status in ((dict(chunk=100), A.AE_ERR_UNSUPPORTED), (dict(D_qk=192), A.AE_ERR_UNSUPPORTED),
                           (dict(D_qk=256, D_v=512), A.AE_ERR_UNSUPPORTED), (dict(H=300, gamma=[0.9] * 300), A.AE_ERR_UNSUPPORTED),
                           (dict(gamma=[0.9, 0.9, 0.9, 1.5]), A.AE_ERR_INVALID_ARG), (dict(gamma=[0.9, 0.0, 0.9, 0.9]), A.AE_ERR_INVALID_ARG),
-                          (dict(gamma=None), A.AE_ERR_INVALID_ARG), (dict(L=0), A.AE_ERR_INVALID_ARG),
+                          (dict(gamma=None), A.AE_ERR_INVALID_ARG), (dict(L=0), A.AE_ERR_INVALID_ARG), (dict(out_dtype=7), A.AE_ERR_INVALID_ARG),
                           (dict(scale=float("nan")), A.AE_ERR_INVALID_ARG), (dict(B=0), A.AE_ERR_INVALID_ARG)):
         with pytest.raises(A.AeAttnError) as ei:
             A.ae_recurrent_create(**dict(ok, **patch))

@@ -269,3 +269,18 @@ def test_state_updated_in_place(A):
                                            scale=0.09, gamma_h=gam[h_], return_state=True, h0=h0[b_, h_].cpu().double().numpy())
         _check(O2[b_, h_].cpu().double().numpy(), ref, f"rec_inplace b{b_} h{h_}")
         _check(buf[b_, h_].cpu().double().numpy(), hs, f"rec_inplace state b{b_} h{h_}")
+
+
+def test_bf16_output(A):
+    """desc.out_dtype = bf16: the same fp32 rows, rounded to nearest even when stored (bit-equal to rounding the
+    fp32 output; the fp32 output itself is held against the oracle above)."""
+    dev = torch.device("cuda:0")
+    for D, L, chunk in ((128, 700, 256), (64, 300, 64)):
+        w = _workload(f"rec_bf16_d{D}", 800 + D, 2, 4, L, D)
+        Q, K, V = (x.to(dev) for x in make_inputs(w))
+        gam = _gammas(4)
+        print(f"case {w.name}", flush=True)
+        O32 = A.retention_recurrent(Q, K, V, scale=0.1, gamma=gam, chunk=chunk)
+        O16 = A.retention_recurrent(Q, K, V, scale=0.1, gamma=gam, chunk=chunk, out_dtype=torch.bfloat16)
+        torch.cuda.synchronize()
+        assert O16.dtype == torch.bfloat16 and torch.equal(O16, O32.to(torch.bfloat16))
