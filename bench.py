@@ -23,15 +23,17 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6  # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 
-# HBM bytes per launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# each scaled by the same counter's reading for a 1 GiB device copy; the runs and their
-# commands are in profiles/attn_fwd_<workload>.txt.  null where not measured.
-MEASURED_TRAFFIC_BYTES = {
-    "c2_gqa_causal_softmax": int((114.8 + 134.2) * 1e6),
-    "c3_sigmoid_causal": int((407.7 + 134.2) * 1e6),
-    "c4_retnet": int((344.1 + 138.3) * 1e6),
-    "c5_mla_causal_softmax": int((2275.0 + 536.9) * 1e6),
-}
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per launch (fetch + write) of the forward kernel on this workload, as `bench.py --profile
+    --workload NAME` measured them (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by the same counter's reading
+    for a 1 GiB device copy): read from the tracked summary profiles/attn_fwd_<workload>.txt.  None where no summary
+    with that measurement exists."""
+    from paper_2502_15349_amd.rocprof_harness import read_traffic
+    t = read_traffic(os.path.join(ROOT, "profiles", f"attn_fwd_{workload_name}.txt"), "attn_fwd_kernel")
+    return None if t is None else t[0] + t[1]
+
 
 
 def time_gpu(A, torch, w, Q, K, V, steps, warmup, settle_s=0.4, out_bf16=False):
@@ -142,7 +144,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2_gqa_causal_softmax")
+    ap.add_argument("--workload", default="c5_mla_causal_softmax",
+                    help="benchmark configuration of the contract line (default: the largest single-GPU one)")
+    ap.add_argument("--profile", action="store_true",
+                    help="instead of running the benchmark in this process, run it under rocprofv3 in child processes "
+                         "(kernel trace, FETCH_SIZE, WRITE_SIZE, their 1 GiB copy calibration, SQ counters) and write a "
+                         "summary with per-kernel durations, MFMA busy fraction, HBM bytes and GB/s; combines with "
+                         "--workload, --backward / --recurrent (and --only)")
+    ap.add_argument("--profile-dir", default=os.path.join(ROOT, "gpurun_out", "profiles"),
+                    help="where --profile writes <name>.txt (and the raw rocprofv3 output, under <name>_raw/)")
     ap.add_argument("--no-variants", action="store_true", help="skip the per-variant table (other configs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--table2", action="store_true",
@@ -170,6 +180,21 @@ def main():
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if a.profile:
+        # No GPU call is made in this process: every pass is a child process under rocprofv3.
+        from paper_2502_15349_amd.rocprof_harness import profile
+        if a.backward:
+            child, name = ["--backward", "--only", a.only], f"attn_bwd_{a.only or 'all'}"
+            trace_args = pmc_args = ()
+        elif a.recurrent:
+            child, name = ["--recurrent", "--only", a.only], f"recurrent_{a.only or 'all'}"
+            trace_args, pmc_args = ("--steps", "20"), ("--steps", "3")
+        else:
+            child, name = ["--workload", a.workload, "--no-variants", "--no-cpu"], f"attn_fwd_{a.workload}"
+            trace_args, pmc_args = ("--steps", str(a.steps), "--warmup", str(a.warmup)), ("--steps", "3", "--warmup", "1")
+        profile(os.path.abspath(__file__), child, a.profile_dir, name, trace_args=trace_args, pmc_args=pmc_args)
+        return
 
     import torch
     if not torch.cuda.is_available():
@@ -585,7 +610,7 @@ def main():
                    "kernel": info["kernel"], "block_m": info["block_m"], "block_n": info["block_n"],
                    "grid": info["grid_size"], "threads": info["block_threads"], "lds_bytes": info["lds_bytes"]},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(w.name),
                      "kernel_ms": round(ker_ms, 5), "flop_per_launch": flop,
                      "compulsory_bytes": w.compulsory_bytes(),
                      },

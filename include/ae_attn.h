@@ -28,6 +28,11 @@ extern "C" {
 
 typedef struct ae_attn ae_attn_t; /* opaque; host memory only */
 
+/* The HIP runtime's stream type, declared here as the runtime declares it so
+ * that this header needs no HIP include (a repeated identical typedef is legal
+ * in C11 and C++).  NULL is the default stream.                               */
+typedef struct ihipStream_t *hipStream_t;
+
 typedef enum {
   AE_OK = 0,
   AE_ERR_INVALID_ARG = 1, /* null/misaligned pointer, bad size, bad parameter  */
@@ -121,9 +126,14 @@ typedef struct {
                           memory up to the next multiple of 8 as well.          */
 } ae_attn_desc_t;
 
-/* Validates the descriptor, picks the kernel and its tile shape for
- * (D_qk, D_v, mask, norm, score_mod) and returns a handle in *out.  Touches no
- * device.  Supported head dims (D_qk/D_v): 64/64, 128/128, 128/256, 192/128.
+/* Instantiates the parallel pattern of Section 4.1 ("Attention Patterns and
+ * Templates") for one problem: the descriptor fixes the two customizable
+ * functions (modification with its mask annotation, row-wise normalization) and
+ * the shapes; the tile shape comes from a table keyed by (D_qk, D_v, mask), the
+ * static stand-in for the enumerate-and-profile tile scheduling of Section 4.3
+ * (Algorithm 1).  Validates the descriptor, picks the kernel and its tile shape
+ * for (D_qk, D_v, mask, norm, score_mod) and returns a handle in *out.  Touches
+ * no device.  Supported head dims (D_qk/D_v): 64/64, 128/128, 128/256, 192/128.
  * Supported (score_mod, norm) pairs: NONE or BIAS with every norm;
  * HEAD_DECAY with ABSSUM, ABS_OF_SUM or NONE (CAUSAL mask only); RELU with NONE.
  * AE_MASK_SLIDING_WINDOW: score_mod NONE or BIAS with SOFTMAX, SIGMOID or NONE.
@@ -135,15 +145,18 @@ typedef struct {
  * to NULL on error.                                                           */
 ae_status_t ae_attn_create(const ae_attn_desc_t *desc, ae_attn_t **out);
 
-/* Enqueues O = rownorm(mod(scale * Q K^T)) V on `stream` (a hipStream_t, may
- * be NULL for the default stream) of the current device and returns without
- * synchronising.  Q, K, V, O: device pointers, 16-byte aligned, sized as the
+/* The parallel pattern itself (Section 4.1, "Attention Patterns and
+ * Templates": Q@K, the customizable function on the scores, then S@V; the
+ * normalization in the online form of the row-norm interface, Section 4.1),
+ * as one fused kernel.
+ * Enqueues O = rownorm(mod(scale * Q K^T)) V on `stream` (may be NULL for the
+ * default stream) of the current device and returns without synchronising.  Q, K, V, O: device pointers, 16-byte aligned, sized as the
  * descriptor says; O must not alias the inputs.  The handle is not modified:
  * concurrent calls on one handle from several threads or streams are allowed.
  * Allocates no device memory.  Errors: AE_ERR_INVALID_ARG (nothing is
  * launched), AE_ERR_HIP.                                                       */
 ae_status_t ae_attn_forward(const ae_attn_t *h, const void *Q, const void *K,
-                            const void *V, void *O, void *stream);
+                            const void *V, void *O, hipStream_t stream);
 
 /* ae_attn_forward that also writes, per query row, the final result of the row
  * reduction its normalization keeps (the online row-norm interface's final row
@@ -157,7 +170,7 @@ ae_status_t ae_attn_forward(const ae_attn_t *h, const void *Q, const void *K,
  * normalizations without a row reduction (SIGMOID, NONE).                      */
 ae_status_t ae_attn_forward_stats(const ae_attn_t *h, const void *Q,
                                   const void *K, const void *V, void *O,
-                                  void *stats, void *stream);
+                                  void *stats, hipStream_t stream);
 
 /* Forward for a handle created with AE_MOD_BIAS_TENSOR: ae_attn_forward with the
  * additive bias tensor (device, bf16, 16-byte aligned, laid out as
@@ -166,7 +179,7 @@ ae_status_t ae_attn_forward_stats(const ae_attn_t *h, const void *Q,
  * ae_attn_forward; AE_ERR_INVALID_ARG for a handle of another score_mod.        */
 ae_status_t ae_attn_forward_bias(const ae_attn_t *h, const void *Q, const void *K,
                                  const void *V, const void *bias, void *O,
-                                 void *stats, void *stream);
+                                 void *stats, hipStream_t stream);
 
 /* Bytes of device workspace that ae_attn_forward_split needs for this handle:
  * the partial output rows and their log-sum-exp, fp32,
@@ -186,7 +199,27 @@ ae_status_t ae_attn_workspace_bytes(const ae_attn_t *h, size_t *bytes);
 ae_status_t ae_attn_forward_split(const ae_attn_t *h, const void *Q,
                                   const void *K, const void *V, void *O,
                                   void *stats, void *workspace,
-                                  size_t workspace_bytes, void *stream);
+                                  size_t workspace_bytes, hipStream_t stream);
+
+/* ae_attn_forward_split for callers that cannot allocate device memory or pass
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  The same two kernels; the partial rows and their
+ * log-sum-exp live in a static device array of the library
+ * (AE_ATTN_STATIC_SCRATCH_BYTES per device that runs the library, held until
+ * the process ends) instead of a workspace.  The call allocates nothing and
+ * frees nothing.  A handle whose ae_attn_workspace_bytes() exceeds
+ * AE_ATTN_STATIC_SCRATCH_BYTES is refused with AE_ERR_UNSUPPORTED (nothing is
+ * launched); a handle without split keys runs as ae_attn_forward[_stats].
+ * Every call on one device shares that device's array, which keeps the last
+ * call's contents (nothing in it needs clearing: each call overwrites what it
+ * reads): calls that overlap in time on one device -- different streams or
+ * threads -- race; serialise them.  Q, K, V, O, stats, stream and errors as
+ * ae_attn_forward_split; AE_ERR_HIP also if the array's address cannot be
+ * looked up on the current device.                                            */
+#define AE_ATTN_STATIC_SCRATCH_BYTES (4u << 20)
+ae_status_t ae_attn_forward_split_static(const ae_attn_t *h, const void *Q,
+                                         const void *K, const void *V, void *O,
+                                         void *stats, hipStream_t stream);
 
 /* Bytes of device workspace that ae_attn_backward needs for this handle: one
  * fp32 value per query row (B * H_q * L_q elements) for the normalizations that
@@ -228,7 +261,7 @@ ae_status_t ae_attn_backward(const ae_attn_t *h, const void *Q, const void *K,
                              const void *V, const void *O, const void *dO,
                              const void *stats, void *dQ, void *dK, void *dV,
                              void *workspace, size_t workspace_bytes,
-                             void *stream);
+                             hipStream_t stream);
 
 /* ae_attn_backward for a handle created with AE_MOD_BIAS_TENSOR: the same, with
  * the bias tensor of the forward pass (device, bf16, 16-byte aligned, read only).
@@ -243,9 +276,11 @@ ae_status_t ae_attn_backward_bias(const ae_attn_t *h, const void *Q, const void 
                                   const void *dO, const void *stats, void *dQ,
                                   void *dK, void *dV, void *dBias,
                                   int64_t dbias_row_stride, void *workspace,
-                                  size_t workspace_bytes, void *stream);
+                                  size_t workspace_bytes, hipStream_t stream);
 
-/* Frees the handle.  NULL is a no-op.                                         */
+/* Frees the handle made by ae_attn_create (host memory only; no device work is
+ * waited for: kernels already enqueued keep running, their arguments were
+ * copied at launch).  NULL is a no-op.                                        */
 ae_status_t ae_attn_destroy(ae_attn_t *h);
 
 /* Tile shape and launch geometry chosen at create time (for harnesses).
@@ -266,7 +301,7 @@ const char *ae_attn_kernel_name(const ae_attn_t *h);
  * at least workgroups * 512 floats (written, contents meaningless).
  * Errors: AE_ERR_INVALID_ARG, AE_ERR_HIP.                                      */
 ae_status_t ae_calib_mfma_bf16(void *sink, size_t sink_bytes, int32_t workgroups,
-                               int32_t iters, double *flop, void *stream);
+                               int32_t iters, double *flop, hipStream_t stream);
 
 /* Message of the calling thread's most recent failing call ("" if none).     */
 const char *ae_attn_last_error(void);
@@ -319,10 +354,10 @@ typedef struct {
 ae_status_t ae_recurrent_create(const ae_recurrent_desc_t *desc, ae_recurrent_t **out);
 ae_status_t ae_recurrent_workspace_bytes(const ae_recurrent_t *h, size_t *bytes);
 ae_status_t ae_recurrent_forward(const ae_recurrent_t *h, const void *Q, const void *K, const void *V, void *O,
-                                 void *workspace, size_t workspace_bytes, void *stream);
+                                 void *workspace, size_t workspace_bytes, hipStream_t stream);
 ae_status_t ae_recurrent_forward_state(const ae_recurrent_t *h, const void *Q, const void *K, const void *V,
                                        const void *h_in, void *O, void *h_out, void *workspace,
-                                       size_t workspace_bytes, void *stream);
+                                       size_t workspace_bytes, hipStream_t stream);
 /* One token of the recurrence as Section 4.1 states it (K@V into the state,
  * then Q@h), for decoding: state <- gamma * state + k^T v, o = scale * q state.
  * q, k bf16 [B, H, D_qk], v bf16 [B, H, D_v], state fp32 [B, H, D_qk, D_v]
@@ -330,7 +365,7 @@ ae_status_t ae_recurrent_forward_state(const ae_recurrent_t *h, const void *Q, c
  * contiguous device memory, 16-byte aligned.  Uses B, H, the head dims, gamma
  * and scale of the handle (L and chunk play no part).  No workspace.             */
 ae_status_t ae_recurrent_step(const ae_recurrent_t *h, const void *q, const void *k, const void *v, void *state,
-                              void *o, void *stream);
+                              void *o, hipStream_t stream);
 ae_status_t ae_recurrent_destroy(ae_recurrent_t *h); /* NULL is allowed */
 
 #ifdef __cplusplus

@@ -51,6 +51,8 @@ _lib.ae_attn_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
 _lib.ae_attn_workspace_bytes.restype = C.c_int
 _lib.ae_attn_forward_split.argtypes = [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
 _lib.ae_attn_forward_split.restype = C.c_int
+_lib.ae_attn_forward_split_static.argtypes = [C.c_void_p] * 7
+_lib.ae_attn_forward_split_static.restype = C.c_int
 _lib.ae_attn_backward_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
 _lib.ae_attn_backward_workspace_bytes.restype = C.c_int
 _lib.ae_attn_backward.argtypes = [C.c_void_p] * 11 + [C.c_size_t, C.c_void_p]
@@ -146,6 +148,14 @@ def ae_attn_forward_split(handle: int, Q: int, K: int, V: int, O: int, stats: in
                           workspace_bytes: int, stream: int = 0) -> None:
     """Forward of a handle created with kv_splits > 1; stats may be 0 (not written)."""
     _check(_lib.ae_attn_forward_split(handle, Q, K, V, O, stats, workspace, workspace_bytes, stream))
+
+
+def ae_attn_forward_split_static(handle: int, Q: int, K: int, V: int, O: int, stats: int = 0, stream: int = 0) -> None:
+    """ae_attn_forward_split with the partial results in the library's static device scratch (no workspace, no allocation)."""
+    _check(_lib.ae_attn_forward_split_static(handle, Q, K, V, O, stats, stream))
+
+
+AE_ATTN_STATIC_SCRATCH_BYTES = 4 << 20
 
 
 def ae_attn_backward_workspace_bytes(handle: int) -> int:

@@ -3,6 +3,7 @@
 #include "../../include/ae_attn.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -13,6 +14,13 @@
 #include "bwd.hpp"
 #include "dispatch.hpp"
 #include "recurrent.hpp"
+
+// ---- static device scratch for the entry point that allocates nothing -----------------------
+// ae_attn_forward_split_static keeps the partial rows of the split-key forward in this array instead of a
+// caller's workspace.  The array's name is a host-side stand-in, not a device address: each device that
+// loads the library holds its own copy at its own address, which hipGetSymbolAddress returns for the
+// device that is current; host code uses that pointer only.
+static __device__ __align__(256) unsigned char scratch[AE_ATTN_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -91,6 +99,28 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MergeParams p) {
     else static_cast<float*>(p.O)[obase + d] = acc;
   }
   if (p.stats != nullptr && lane == 0) p.stats[r] = lse;
+}
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// The current device's copy of `scratch` (looked up once per device); null with g_err set on failure.
+void* static_scratch() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fail(AE_ERR_HIP, "ae_attn_forward_split_static: hipGetDevice: %s (device %d)", hipGetErrorString(e), dev);
+    return nullptr;
+  }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr) return ptr;
+  e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !ptr) {
+    fail(AE_ERR_HIP, "ae_attn_forward_split_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    return nullptr;
+  }
+  g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // two first calls racing store the same address
+  return ptr;
 }
 
 }  // namespace
@@ -230,7 +260,9 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   }
   p.neg_q = d->scale < 0.f ? 1 : 0;
   p.out_bf16 = d->out_dtype == AE_OUT_BF16 ? 1 : 0;
-  p.window = d->mask == AE_MASK_SLIDING_WINDOW ? d->window : 0;
+  // a window wider than every row's reach hides nothing more than the causal mask; clamped so that
+  // the kernel's row + offset - window arithmetic stays inside 32 bits
+  p.window = d->mask == AE_MASK_SLIDING_WINDOW ? (int)std::min<int64_t>(d->window, (int64_t)d->L_q + d->L_k) : 0;
   p.fold = (d->norm == AE_NORM_SIGMOID && mod != ae::MOD_BIAS_T && std::fabs(p.b2) <= 64.f) ? 1 : 0;
   p.kfac = p.fold ? std::exp2(-p.b2) : 1.f;
   if (mod == ae::MOD_DECAY)
@@ -243,8 +275,11 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   // over more L2 channels).
   const int64_t per_group = (int64_t)p.n_qtiles * p.g;
   const int64_t rounds = (p.n_groups + 7) / 8;  // groups per XCD
+#ifdef AE_TUNE_INTERLEAVE  // build-time knob of the mapping sweeps, like the AE_SHAPE_* entries of the tile table
+  int interleave = AE_TUNE_INTERLEAVE;
+#else
   int interleave = per_group >= 32 ? 2 : 8;
-  if (const char* e = getenv("AE_ATTN_INTERLEAVE")) interleave = atoi(e);  // tuning aid
+#endif
   if (interleave < 1) interleave = 1;
   if (interleave > rounds) interleave = (int)rounds;
   p.interleave = interleave;
@@ -267,7 +302,7 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     // ranges cost a start and an end of a workgroup apiece.  Only where the keys may be split
     // and the query tiles alone leave most of the device idle.
     kv_splits = 0;
-    if (d->norm == AE_NORM_SOFTMAX && d->mask != AE_MASK_SLIDING_WINDOW && grid < 160) {
+    if (d->norm == AE_NORM_SOFTMAX && d->mask != AE_MASK_SLIDING_WINDOW && mod != ae::MOD_BIAS_T && grid < 160) {
       const int key_tiles = (d->L_k + h->kernel->block_n - 1) / h->kernel->block_n;
       const int64_t want = (192 + grid / 2) / grid;  // round(192 / workgroups)
       kv_splits = (int)std::min<int64_t>(std::min<int64_t>(want, key_tiles / 8), 256);
@@ -300,7 +335,7 @@ struct CarriedState {
 };
 
 static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, float* stats,
-                                void* stream, void* workspace = nullptr, size_t workspace_bytes = 0,
+                                hipStream_t stream, void* workspace = nullptr, size_t workspace_bytes = 0,
                                 const void* bias = nullptr, const CarriedState* carried = nullptr) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null handle");
   if (!Q || !K || !V || !O) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward: null device pointer");
@@ -357,12 +392,12 @@ static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K
   return AE_OK;
 }
 
-ae_status_t ae_attn_forward(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, void* stream) {
+ae_status_t ae_attn_forward(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, hipStream_t stream) {
   return forward_impl(h, Q, K, V, O, nullptr, stream);
 }
 
 ae_status_t ae_attn_forward_stats(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, void* stats,
-                                  void* stream) {
+                                  hipStream_t stream) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_stats: null handle");
   if (!stats || ((uintptr_t)stats & 3)) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_stats: stats must be a 4-byte aligned device pointer");
   if (stats == O || stats == Q || stats == K || stats == V)
@@ -374,7 +409,7 @@ ae_status_t ae_attn_forward_stats(const ae_attn_t* h, const void* Q, const void*
 }
 
 ae_status_t ae_attn_forward_bias(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* bias, void* O,
-                                 void* stats, void* stream) {
+                                 void* stats, hipStream_t stream) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_bias: null handle");
   if (!bias) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_bias: null bias tensor");
   if (stats) {
@@ -393,13 +428,33 @@ ae_status_t ae_attn_workspace_bytes(const ae_attn_t* h, size_t* bytes) {
 }
 
 ae_status_t ae_attn_forward_split(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, void* stats,
-                                  void* workspace, size_t workspace_bytes, void* stream) {
+                                  void* workspace, size_t workspace_bytes, hipStream_t stream) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_split: null handle");
   if (stats && (((uintptr_t)stats & 3) || stats == O || stats == Q || stats == K || stats == V))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_split: stats must be 4-byte aligned and must not alias another buffer");
   if (h->params.n_splits > 1 && (workspace == O || workspace == Q || workspace == K || workspace == V || (stats && workspace == stats)))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_split: the workspace aliases another buffer");
   return forward_impl(h, Q, K, V, O, static_cast<float*>(stats), stream, workspace, workspace_bytes);
+}
+
+ae_status_t ae_attn_forward_split_static(const ae_attn_t* h, const void* Q, const void* K, const void* V, void* O, void* stats,
+                                         hipStream_t stream) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_split_static: null handle");
+  if (stats && (((uintptr_t)stats & 3) || stats == O || stats == Q || stats == K || stats == V))
+    return fail(AE_ERR_INVALID_ARG, "ae_attn_forward_split_static: stats must be 4-byte aligned and must not alias another buffer");
+  if (h->ws_bytes > (size_t)AE_ATTN_STATIC_SCRATCH_BYTES)
+    return fail(AE_ERR_UNSUPPORTED,
+                "ae_attn_forward_split_static: this handle's partial results take %zu bytes, the static scratch holds %zu; "
+                "use ae_attn_forward_split with a workspace",
+                h->ws_bytes, (size_t)AE_ATTN_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  if (h->params.n_splits > 1) {
+    ws = static_scratch();
+    if (!ws) return AE_ERR_HIP;
+  }
+  // every partial row and statistic that the merge kernel reads is written by the attention kernel of the
+  // same call (ranges without a visible key write zeros and -inf), so nothing has to be cleared
+  return forward_impl(h, Q, K, V, O, static_cast<float*>(stats), stream, ws, AE_ATTN_STATIC_SCRATCH_BYTES);
 }
 
 ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t* h, size_t* bytes) {
@@ -413,7 +468,7 @@ ae_status_t ae_attn_backward_workspace_bytes(const ae_attn_t* h, size_t* bytes) 
 
 static ae_status_t backward_impl(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* bias, const void* O,
                                  const void* dO, const void* stats, void* dQ, void* dK, void* dV, void* workspace,
-                                 size_t workspace_bytes, void* stream, void* dBias = nullptr, int64_t dbias_ld = 0) {
+                                 size_t workspace_bytes, hipStream_t stream, void* dBias = nullptr, int64_t dbias_ld = 0) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: null handle");
   if ((h->desc.score_mod == AE_MOD_BIAS_TENSOR) != (bias != nullptr))
     return fail(AE_ERR_INVALID_ARG, "ae_attn_backward: a handle with AE_MOD_BIAS_TENSOR, and only such a handle, runs through "
@@ -485,6 +540,7 @@ static ae_status_t backward_impl(const ae_attn_t* h, const void* Q, const void* 
   p.bunit = unit;
   p.scale = d.scale;
   p.window = d.mask == AE_MASK_SLIDING_WINDOW ? std::min(d.window, d.L_q + d.L_k) : d.L_q + d.L_k;
+  p.has_decay = d.score_mod == AE_MOD_HEAD_DECAY ? 1 : 0;
   hipError_t e = ae::launch_backward(p, h->decay, d.D_qk, d.D_v, norm, d.mask != AE_MASK_NONE, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_backward: launch failed: %s", hipGetErrorString(e));
   return AE_OK;
@@ -494,14 +550,14 @@ extern "C" {
 
 ae_status_t ae_attn_backward(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* O, const void* dO,
                              const void* stats, void* dQ, void* dK, void* dV, void* workspace, size_t workspace_bytes,
-                             void* stream) {
+                             hipStream_t stream) {
   return backward_impl(h, Q, K, V, nullptr, O, dO, stats, dQ, dK, dV, workspace, workspace_bytes, stream);
 }
 
 ae_status_t ae_attn_backward_bias(const ae_attn_t* h, const void* Q, const void* K, const void* V, const void* bias,
                                   const void* O, const void* dO, const void* stats, void* dQ, void* dK, void* dV,
                                   void* dBias, int64_t dbias_row_stride, void* workspace, size_t workspace_bytes,
-                                  void* stream) {
+                                  hipStream_t stream) {
   if (!bias) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward_bias: null bias tensor");
   if (dBias) {
     if (!h) return fail(AE_ERR_INVALID_ARG, "ae_attn_backward_bias: null handle");
@@ -633,7 +689,7 @@ ae_status_t ae_recurrent_workspace_bytes(const ae_recurrent_t* h, size_t* bytes)
 
 ae_status_t ae_recurrent_forward_state(const ae_recurrent_t* h, const void* Q, const void* K, const void* V,
                                        const void* h_in, void* O, void* h_out, void* workspace, size_t workspace_bytes,
-                                       void* stream) {
+                                       hipStream_t stream) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: null handle");
   if (!Q || !K || !V || !O) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: null pointer");
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O | (uintptr_t)h_in | (uintptr_t)h_out) & 15)
@@ -691,12 +747,12 @@ ae_status_t ae_recurrent_forward_state(const ae_recurrent_t* h, const void* Q, c
 }
 
 ae_status_t ae_recurrent_forward(const ae_recurrent_t* h, const void* Q, const void* K, const void* V, void* O,
-                                 void* workspace, size_t workspace_bytes, void* stream) {
+                                 void* workspace, size_t workspace_bytes, hipStream_t stream) {
   return ae_recurrent_forward_state(h, Q, K, V, nullptr, O, nullptr, workspace, workspace_bytes, stream);
 }
 
 ae_status_t ae_recurrent_step(const ae_recurrent_t* h, const void* q, const void* k, const void* v, void* state, void* o,
-                              void* stream) {
+                              hipStream_t stream) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_step: null handle");
   if (!q || !k || !v || !state || !o) return fail(AE_ERR_INVALID_ARG, "ae_recurrent_step: null pointer");
   if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)state | (uintptr_t)o) & 15)

@@ -66,6 +66,9 @@ struct BwdParams {
   // causal kernels: key j is also hidden from query i if j <= i + (L_k - L_q) - window (sliding
   // window); L_q + L_k for the plain causal mask, which hides nothing more
   int window;
+  // the handle has a per-head decay: only then is the decay table read (it holds AE_MAX_DECAY_HEADS entries, and
+  // handles without decay may have more heads than that)
+  int has_decay;
 };
 
 // Chunk swizzle of the backward tiles.  A tile row is read both ways -- 128-bit row
@@ -180,7 +183,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
     }
   }
   float lg = 0.f;  // log2 of the decay rate of the q head at hand (0: no decay); key side: set per tile
-  if constexpr (!C::KV_SIDE && C::LIN) lg = dt.log2_gamma[ho];
+  if constexpr (!C::KV_SIDE && C::LIN) lg = p.has_decay ? dt.log2_gamma[ho] : 0.f;
 
   // ---- the walk over the other side --------------------------------------------------
   // key side: the query tiles from the first one that sees key own0, for each q head of
@@ -511,7 +514,7 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
       rowq_next = load_rowq(n + 1);
     }
     const int r0 = (t_first + (C::KV_SIDE ? n % nt : n)) * C::TILE;
-    if constexpr (C::KV_SIDE && C::LIN) lg = dt.log2_gamma[hk * p.g + n / nt];
+    if constexpr (C::KV_SIDE && C::LIN) lg = p.has_decay ? dt.log2_gamma[hk * p.g + n / nt] : 0.f;
     subtile(stagec, std::integral_constant<int, 0>{}, r0);
     subtile(stagec, std::integral_constant<int, 1>{}, r0 + 32);
     if (n + 1 < total) store_rowq(rowq_next, STAGE ^ 1);

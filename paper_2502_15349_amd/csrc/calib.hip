@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kThreads) void calib_mfma_kernel(float* sink, int i
 }  // namespace
 
 extern "C" ae_status_t ae_calib_mfma_bf16(void* sink, size_t sink_bytes, int32_t workgroups, int32_t iters,
-                                          double* flop, void* stream) {
+                                          double* flop, hipStream_t stream) {
   if (!sink || workgroups <= 0 || iters <= 0 || sink_bytes < (size_t)workgroups * kThreads * sizeof(float))
     return AE_ERR_INVALID_ARG;
   hipLaunchKernelGGL(calib_mfma_kernel, dim3(workgroups), dim3(kThreads), 0, static_cast<hipStream_t>(stream),

@@ -118,6 +118,11 @@ def test_sliding_window_descriptor_checks():
         with pytest.raises(A.AeAttnError) as ei:
             A.ae_attn_create(**_ok_desc(), mask="sliding_window", window=window)
         assert ei.value.status == A.AE_ERR_INVALID_ARG
+    # a window far wider than the sequence is the causal mask (also with more queries than keys)
+    A.ae_attn_destroy(A.ae_attn_create(**_ok_desc(), mask="sliding_window", window=2**31 - 1))
+    d = _ok_desc()
+    d.update(L_q=300, L_k=40)
+    A.ae_attn_destroy(A.ae_attn_create(**d, mask="sliding_window", window=2**31 - 1))
     # the window comes with softmax, sigmoid and no normalization only
     d = _ok_desc()
     d.update(norm="abssum")
@@ -267,6 +272,15 @@ def test_bias_tensor_descriptor_and_entry_point_checks():
     dd = _ok_desc()
     dd.update(score_mod="bias_tensor", bias_stride=(0, 0, 104))    # shared over batch and heads, padded rows
     A.ae_attn_destroy(A.ae_attn_create(**dd))
+    # the automatic split choice leaves a handle with a bias tensor alone (its entry point takes no workspace):
+    # a decoding shape that would be split without the bias tensor
+    dec = dict(B=1, H_q=16, H_kv=16, L_q=1, L_k=8192, D_qk=128, D_v=128, scale=0.1, kv_splits=-1)
+    h = A.ae_attn_create(**dec)
+    assert A.ae_attn_workspace_bytes(h) > 0
+    A.ae_attn_destroy(h)
+    h = A.ae_attn_create(**dec, score_mod="bias_tensor")
+    assert A.ae_attn_workspace_bytes(h) == 0
+    A.ae_attn_destroy(h)
 
 
 def test_slabs_beyond_32_bit_offsets_are_refused():

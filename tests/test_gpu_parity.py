@@ -63,6 +63,13 @@ VARIANTS = {
 }
 
 
+# Variants whose outputs are not O(1) by construction: no normalisation, the |sum| normaliser (its
+# denominators cancel), sigmoid without the -ln L bias.  Only these are judged relative to the row
+# scale max(1, max |oracle row|); every other variant is held to the absolute bar as it stands.
+ROW_SCALED = {"sigmoid", "sigmoid_big_bias_causal", "retnet_abs_of_sum", "decay_nonorm", "abs_of_sum_plain_causal",
+              "relu", "relu_causal", "none_plain"}
+
+
 @pytest.mark.parametrize("dims", DIMS, ids=lambda d: f"d{d[0]}_{d[1]}")
 @pytest.mark.parametrize("variant", sorted(VARIANTS))
 def test_small_ragged_all_variants(A, dims, variant):
@@ -72,11 +79,9 @@ def test_small_ragged_all_variants(A, dims, variant):
     Q, K, V = make_inputs(w)
     print(f"case {variant} dims {dims}", flush=True)
     got, ref = gpu_run(A, w, Q, K, V), oracle_run(w, Q, K, V)
-    # Variants whose outputs are not O(1) (no normalisation, |sum| normaliser
-    # with cancelling denominators, sigmoid without the -ln L bias) are judged
-    # relative to the row scale; for normalised variants the factor is 1.
-    rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
-    got, ref = got / rs, ref / rs
+    if variant in ROW_SCALED:
+        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+        got, ref = got / rs, ref / rs
     check(got, ref, f"{variant} {dims}")
 
 
@@ -116,41 +121,49 @@ def test_c1_full_elementwise(A):
     check(gpu_run(A, C1, Q, K, V), oracle_run(C1, Q, K, V), f"C1")
 
 
-def _sampled_full_config(A, w, n_heads=3, n_rows=96, seed=0):
-    """Full-size launch (the configuration the benchmark times); the oracle
-    recomputes sampled query rows of sampled heads over the whole key range."""
+def _full_config(A, w, every_row, n_rows=40, seed=0):
+    """Full-size launch (the configuration the benchmark times) against the oracle on EVERY (batch, head):
+    every query row where the oracle finishes in seconds (every_row), otherwise tile edges plus random rows
+    of every head, recomputed over the whole key range."""
     Q, K, V = make_inputs(w)
     dev = torch.device("cuda:0")
     print(f"case full {w.name}", flush=True)
     O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev))
     torch.cuda.synchronize()
     assert torch.isfinite(O).all()
+    O = O.cpu()
     rng = np.random.default_rng(seed)
     g = w.H_q // w.H_kv
     gam = w.gamma()
-    errs = []
-    for _ in range(n_heads):
-        b, h = int(rng.integers(w.B)), int(rng.integers(w.H_q))
-        # first/last rows, tile edges and random rows
-        rows = np.unique(np.concatenate([
-            [0, 1, 31, 32, 63, 64, 255, 256, 257, w.L_q - 257, w.L_q - 2, w.L_q - 1],
-            rng.integers(0, w.L_q, n_rows)])).astype(np.int64)
-        rows = rows[(rows >= 0) & (rows < w.L_q)]
-        ref = attention_head(Q[b, h], K[b, h // g], V[b, h // g], scale=w.scale_value, score_mod=w.score_mod,
-                             bias=w.bias, gamma_h=None if gam is None else gam[h], norm=w.norm, mask=w.oracle_mask(),
-                             rows=rows)
-        got = O[b, h].cpu().double().numpy()[rows]
-        errs.append(np.abs(got - ref))
-        print(f"  head ({b},{h}) max_abs {errs[-1].max():.3e} mean_abs {errs[-1].mean():.3e} "
-              f"|ref|max {np.abs(ref).max():.3e} rel_max {(errs[-1].max() / np.abs(ref).max()):.3e}", flush=True)
-    e = np.concatenate([x.ravel() for x in errs])
-    assert e.max() <= MAX_ABS and e.mean() <= MEAN_ABS, (e.max(), e.mean())
-    return O
+    worst, total, count = 0.0, 0.0, 0
+    for b in range(w.B):
+        for h in range(w.H_q):
+            rows = None
+            if not every_row:
+                # first/last rows, edges of the 32-row wave blocks and the 256-row tiles, random rows
+                rows = np.unique(np.concatenate([
+                    [0, 1, 31, 32, 63, 64, 255, 256, 257, w.L_q - 257, w.L_q - 256, w.L_q - 2, w.L_q - 1],
+                    rng.integers(0, w.L_q, n_rows)])).astype(np.int64)
+                rows = rows[(rows >= 0) & (rows < w.L_q)]
+            ref = attention_head(Q[b, h], K[b, h // g], V[b, h // g], scale=w.scale_value, score_mod=w.score_mod,
+                                 bias=w.bias, gamma_h=None if gam is None else gam[h], norm=w.norm, mask=w.oracle_mask(),
+                                 rows=rows)
+            got = O[b, h].double().numpy()
+            err = np.abs((got if rows is None else got[rows]) - ref)
+            assert err.max() <= MAX_ABS, (w.name, b, h, err.max())
+            worst, total, count = max(worst, float(err.max())), total + float(err.sum()), count + err.size
+        print(f"  batch {b}: {w.H_q} heads, max_abs so far {worst:.3e} mean_abs so far {total / count:.3e}", flush=True)
+    assert total / count <= MEAN_ABS, (w.name, total / count)
 
 
-@pytest.mark.parametrize("w", [C2, C3, C4, C5], ids=lambda w: w.name)
-def test_full_config_sampled(A, w):
-    _sampled_full_config(A, w)
+@pytest.mark.parametrize("w", [C2, C4], ids=lambda w: w.name)
+def test_full_config_every_head_every_row(A, w):
+    _full_config(A, w, every_row=True)
+
+
+@pytest.mark.parametrize("w", [C3, C5], ids=lambda w: w.name)
+def test_full_config_every_head_sampled_rows(A, w):
+    _full_config(A, w, every_row=False)
 
 
 def test_table2_shapes_sampled(A):
@@ -301,13 +314,24 @@ def test_sliding_window(A, dims, norm, mod, Lq, Lk, W):
                  score_mod=mod, bias=-1.0, scale=0.005 if norm == "none" else None)
     Q, K, V = make_inputs(w)
     got, ref = gpu_run(A, w, Q, K, V), oracle_run(w, Q, K, V)
-    rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)   # row scale of the non-normalised variants
-    check(got / rs, ref / rs, f"window {W}")
+    if norm != "softmax":   # no normalisation, sigmoid with a bias of -1: not O(1) by construction, judged relative to the row scale
+        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+        got, ref = got / rs, ref / rs
+    check(got, ref, f"window {W}")
 
 
 def test_sliding_window_full_size_sampled(A):
     w = C2.scaled(name="c2_window_512", mask="sliding_window", window=512)
-    _sampled_full_config(A, w)
+    _full_config(A, w, every_row=False)
+
+
+def test_sliding_window_wider_than_everything(A):
+    """A window of 2^31 - 1 keys with more queries than keys is the causal mask (rows without keys stay zero)."""
+    w = Workload("window_max", 18, 1, 4, 2, 700, 300, 128, 128, mask="sliding_window", window=2**31 - 1)
+    Q, K, V = make_inputs(w)
+    got = gpu_run(A, w, Q, K, V)
+    check(got, oracle_run(w.scaled(mask="causal"), Q, K, V), "window 2^31-1")
+    assert (got[:, :, :400] == 0).all()
 
 
 @pytest.mark.parametrize("dims", DIMS, ids=lambda d: f"d{d[0]}_{d[1]}")
@@ -428,8 +452,10 @@ def test_seeded_random_shapes(A):
         O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), kv_splits=splits)
         torch.cuda.synchronize()
         got, ref = O.cpu().double().numpy(), oracle_run(w, Q, K, V)
-        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
-        check(got / rs, ref / rs, f"random case {case}")
+        if norm in ("none", "abs_of_sum", "sigmoid"):   # not O(1) by construction (the sigmoid bias here is not -ln L)
+            rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+            got, ref = got / rs, ref / rs
+        check(got, ref, f"random case {case}")
 
 
 def test_negative_scale_and_large_scores(A):
@@ -476,7 +502,7 @@ def test_decay_rates_outside_the_factorised_range(A):
                                 norm=norm, mask="causal")
         torch.cuda.synchronize()
         ref = oracle_attention(Q, K, V, scale=scale, score_mod="head_decay", gamma=gam, norm=norm, mask="causal")
-        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0) if norm == "none" else 1.0
         check(O.cpu().double().numpy() / rs, ref / rs, f"decay gammas {gam} norm {norm}")
 
 
@@ -506,7 +532,7 @@ def test_bias_tensor(A, dims, norm, mask):
         torch.cuda.synchronize()
         ref = attention(Q, K, V, scale=w.scale_value, score_mod="bias_tensor", norm=norm, mask=mask, bias_tensor=bt)
         # (sigmoid and no normalization: outputs are not O(1); judged relative to the row scale as elsewhere)
-        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0) if norm != "softmax" else 1.0
         check(O.cpu().double().numpy() / rs, ref / rs, f"bias tensor {norm} {mask} {tuple(bt.shape)}")
         if stats is not None:
             b, h = 1, 3
