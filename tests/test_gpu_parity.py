@@ -502,7 +502,10 @@ def test_decay_rates_outside_the_factorised_range(A):
                                 norm=norm, mask="causal")
         torch.cuda.synchronize()
         ref = oracle_attention(Q, K, V, scale=scale, score_mod="head_decay", gamma=gam, norm=norm, mask="causal")
-        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0) if norm == "none" else 1.0
+        # Judged relative to the row scale for both norms: with gamma = 0.01 a row's weight sits on one key, so O_i is
+        # v_i itself (|v| up to 4.1 here) and the half-ulp of that one bf16 weight, 2^-9 |v_i| = 8e-3, is most of the
+        # absolute bar on its own -- the row is not a mean over many keys as in the benchmark configurations.
+        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
         check(O.cpu().double().numpy() / rs, ref / rs, f"decay gammas {gam} norm {norm}")
 
 
