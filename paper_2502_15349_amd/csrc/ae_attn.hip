@@ -34,14 +34,14 @@ ae_status_t fail(ae_status_t code, const char* fmt, ...) {
   return code;
 }
 
-const ae::KernelEntry* find_kernel(int dqk, int dv, int norm, int mod, int mask) {
+const ae::KernelEntry* find_kernel(int dqk, int dv, int norm, int mod, int mask, int fold) {
   typedef const ae::KernelEntry* (*table_fn)(int*);
   static const table_fn tables[] = {ae::table_64_64, ae::table_128_128, ae::table_128_256, ae::table_192_128};
   for (table_fn tf : tables) {
     int n = 0;
     const ae::KernelEntry* t = tf(&n);
     for (int i = 0; i < n; ++i)
-      if (t[i].dqk == dqk && t[i].dv == dv && t[i].norm == norm && t[i].mod == mod && t[i].mask == mask)
+      if (t[i].dqk == dqk && t[i].dv == dv && t[i].norm == norm && t[i].mod == mod && t[i].mask == mask && t[i].fold == fold)
         return &t[i];
   }
   return nullptr;
@@ -186,7 +186,15 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
       if (!std::isfinite(d->gamma[h]) || !(d->gamma[h] > 0.f))
         return fail(AE_ERR_INVALID_ARG, "ae_attn_create: gamma[%d] must be finite and > 0", h);
   }
-  const ae::KernelEntry* k = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, (int)d->mask);
+  // Softmax and sigmoid without a bias tensor: the kernels that take the scale on Q (rounded to bf16 again, as the
+  // paper's own modification of q does) and the rest of the exponent from the accumulator's initial value -- where
+  // that second rounding is harmless: it moves an exponent by about 2^-9 |scale| log2(e) |q||k| / sqrt(D_qk), which
+  // for unit-variance inputs and |scale| sqrt(D_qk) <= 2 stays below the bf16 rounding of the weight itself.
+  // Larger scales keep the scale in fp32 on the scores.
+  const bool fold = (d->norm == AE_NORM_SOFTMAX || d->norm == AE_NORM_SIGMOID) && mod == ae::MOD_PLAIN &&
+                    std::fabs(d->scale) * std::sqrt((float)d->D_qk) <= 2.f;
+  const ae::KernelEntry* k = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, (int)d->mask, fold ? 1 : 0);
+  if (!k && fold) k = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, (int)d->mask, 0);
   if (!k)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: no kernel for score_mod %d with norm %d and mask %d",
                 (int)d->score_mod, (int)d->norm, (int)d->mask);
@@ -263,8 +271,6 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   // a window wider than every row's reach hides nothing more than the causal mask; clamped so that
   // the kernel's row + offset - window arithmetic stays inside 32 bits
   p.window = d->mask == AE_MASK_SLIDING_WINDOW ? (int)std::min<int64_t>(d->window, (int64_t)d->L_q + d->L_k) : 0;
-  p.fold = (d->norm == AE_NORM_SIGMOID && mod != ae::MOD_BIAS_T && std::fabs(p.b2) <= 64.f) ? 1 : 0;
-  p.kfac = p.fold ? std::exp2(-p.b2) : 1.f;
   if (mod == ae::MOD_DECAY)
     for (int hh = 0; hh < d->H_q; ++hh) h->decay.log2_gamma[hh] = std::log2(d->gamma[hh]);
 

@@ -86,11 +86,6 @@ struct Params {
   int n_splits, split_tiles, base_grid;
   float* ws_o;
   float* ws_lse;
-  // sigmoid with a bias small enough for 2^(-b2) to be a normal number: Q is
-  // multiplied by -scale*log2(e) when loaded (rounded to bf16 again), so that the
-  // MFMA delivers the exponent itself and 1 + 2^(-b2) * 2^x is a single FMA
-  int fold;
-  float kfac;      // 2^(-b2) when fold
   // Recurrent pattern, chunks as batch entries (MOD_DECAY with NORM_NONE only; null: off): batch entry
   // b >= state_b0 of head h starts from the carried state in front of its chunk, a bf16 matrix [D_v][D_qk] at
   // state + (b - state_b0) * state_bs + h * state_hs:  O[i] = c * gamma^(i+1) * q_i H  +  the walk over the keys.
@@ -104,9 +99,19 @@ struct DecayTable {
 };
 
 // MASK_: 0 none, 1 causal, 2 causal with a sliding window (Params::window keys per query)
-template <int DQK_, int DV_, int NORM_, int MOD_, int MASK_, int WAVES_>
+// FOLD_ (softmax and sigmoid without a bias tensor): the exponent comes out of the scoring MFMA ready to use.
+// Q is multiplied by |scale| * log2(e) when loaded and rounded to bf16 again (the paper's own form: its
+// modification scales q, Section 4.1), and the constant term of the exponent -- minus the running reference
+// maximum of the row (softmax), the bias (sigmoid) -- is the INITIAL VALUE of the MFMA accumulator, a register
+// set that only changes when the reference moves.  That removes the multiply-add in front of every exponential,
+// and for softmax the row maximum as well: the reference only has to move when a weight would overflow, which
+// the row sum (needed anyway) shows.  The host picks FOLD where the second rounding of q is harmless
+// (|scale| sqrt(D_qk) <= 2: scores of unit-variance inputs with a standard deviation of at most 2).
+template <int DQK_, int DV_, int NORM_, int MOD_, int MASK_, int WAVES_, int FOLD_ = 0>
 struct Cfg {
   static constexpr int DQK = DQK_, DV = DV_, NORM = NORM_, MOD = MOD_, WAVES = WAVES_;
+  static constexpr bool FOLD = FOLD_ != 0;
+  static_assert(!FOLD || ((NORM_ == NORM_SOFTMAX || NORM_ == NORM_SIGMOID) && MOD_ == MOD_PLAIN), "FOLD: softmax or sigmoid, no bias tensor");
   static constexpr int MASK = MASK_;
   static constexpr bool CAUSAL = MASK_ != 0, WINDOW = MASK_ == 2;
   static constexpr int SUB_N = 32;    // keys per compute sub-tile
@@ -263,6 +268,7 @@ __device__ __forceinline__ const void* uniform_ptr(const void* ptr) {
 }
 __device__ __forceinline__ void dma16(const void* base_uniform, uint32_t byte_off, uint32_t lds_addr_uniform) {
   base_uniform = uniform_ptr(base_uniform);
+  lds_addr_uniform = __builtin_amdgcn_readfirstlane(lds_addr_uniform);  // (the same for the LDS address)
   asm volatile(
       "s_mov_b32 m0, %0\n\t"
       "s_nop 0\n\t"
@@ -277,6 +283,7 @@ __device__ __forceinline__ void dma16(const void* base_uniform, uint32_t byte_of
 template <int LDS_IMM>
 __device__ __forceinline__ void dma16_at(const void* base_uniform, uint32_t byte_off, uint32_t lds_base_uniform) {
   base_uniform = uniform_ptr(base_uniform);
+  lds_base_uniform = __builtin_amdgcn_readfirstlane(lds_base_uniform);
   asm volatile(
       "s_add_i32 m0, %0, %3\n\t"
       "s_nop 0\n\t"
@@ -313,6 +320,7 @@ template <class C>
 struct RowState {
   float m;  // softmax: lazy running reference max (log2 domain)
   float l;  // softmax: running sum of weights; abs-sum family: running sum (this lane's keys only)
+  float thr;  // FOLD softmax: the lane's 16-key partial row sum above which the reference must move (-1: no reference yet)
   f32x16 o[C::DB];
 };
 
@@ -366,7 +374,7 @@ __device__ __forceinline__ void mask_modified(f32x16& s, int jlim) {
 //   softmax  the raw score (mx accumulates the lane's max)
 //   sigmoid  2^-(scale*s + bias) in log2 units
 //   others   the fully modified score x
-template <class C, bool FOLD = false>
+template <class C>
 __device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, float dbase, float g2, float& mx,
                                           uint32_t bias_pair = 0) {
 #pragma unroll
@@ -383,7 +391,7 @@ __device__ __forceinline__ void post_pair(const Params& p, int q, f32x16& s, flo
       else x = __builtin_fmaf(x, p.c, bv);
     } else if constexpr (C::NORM == NORM_SOFTMAX) {
     } else if constexpr (C::NORM == NORM_SIGMOID) {
-      x = FOLD ? fast_exp2(x) : fast_exp2(__builtin_fmaf(x, -p.c, -p.b2));
+      x = fast_exp2(__builtin_fmaf(x, -p.c, -p.b2));
     } else if constexpr (C::MOD == MOD_DECAY) {
       // gamma^(i + off - j) = 2^(log2(gamma) * (i + off - j))
       x = x * p.c * fast_exp2(__builtin_fmaf(-g2, (float)key_offset(r), dbase));
@@ -426,7 +434,7 @@ __device__ __forceinline__ void lazy_rescale(RowState<C>& st, bool moved, float 
 }
 
 // ---- second half of the row norm, one pair: weight -> packed bf16x2 ------------
-template <class C, bool FOLD = false>
+template <class C>
 __device__ __forceinline__ uint32_t finish_pair(const Params& p, int q, const f32x16& s, float k0, float& acc) {
   float x0 = s[2 * q], x1 = s[2 * q + 1];
   if constexpr (C::NORM == NORM_SOFTMAX && C::MOD == MOD_BIAS_T) {
@@ -440,8 +448,8 @@ __device__ __forceinline__ uint32_t finish_pair(const Params& p, int q, const f3
     // halve the instruction count but runs on the matrix pipe, in the MFMAs' way.
     acc += x0 + x1;
   } else if constexpr (C::NORM == NORM_SIGMOID) {
-    x0 = fast_rcp(FOLD ? __builtin_fmaf(p.kfac, x0, 1.f) : 1.f + x0);
-    x1 = fast_rcp(FOLD ? __builtin_fmaf(p.kfac, x1, 1.f) : 1.f + x1);
+    x0 = fast_rcp(1.f + x0);
+    x1 = fast_rcp(1.f + x1);
   } else if constexpr (C::NORM == NORM_ABSSUM) {
     acc += fabsf(x0) + fabsf(x1);
   } else if constexpr (C::NORM == NORM_ABS_OF_SUM) {
@@ -535,13 +543,13 @@ __device__ __forceinline__ f32x16 zero16() {
 // buffer kaddr points into (prologue: scores of the very first sub-tile).
 template <class C>
 __device__ __forceinline__ void score_block(const uint32_t (&kaddr)[C::T], int krow_off, const bf16x8 (&qf)[C::T],
-                                            f32x16& s) {
+                                            f32x16& s, const f32x16& init) {
   constexpr int PF = C::PF;
   bf16x8 ring[PF];
 #pragma unroll
   for (int g = 0; g < PF; ++g) ring[g] = read_k_frag(kaddr[g] + krow_off);
   sched_fence();
-  s = zero16();
+  s = init;
 #pragma unroll
   for (int g = 0; g < C::T; ++g) {
     s = mfma(ring[g % PF], qf[g], s);
@@ -586,6 +594,7 @@ struct KeyLoop {
   const bf16x8 (&qf)[C::T];
   RowState<C>& st;
   u32x4 (&pk)[2];
+  f32x16& cinit;  // FOLD: initial value of the scoring accumulator (see Cfg)
   bf16x8 (&ring)[S::PF];
   uint32_t (&kaddr)[C::T];
   uint32_t (&vaddr)[C::VA];
@@ -683,6 +692,92 @@ struct KeyLoop {
       ring[n % S::PF] = load_v_frag<C>(vaddr, sub, r / C::DB, r % C::DB);
   }
 
+  // FOLD kernels: the scores arrive as exponents (log2 units, constant term included; hidden ones as -inf).
+  //
+  // Softmax: y = c s - m with m the row's reference.  Weights 2^y, row sum, and that is all -- as long as no
+  // weight can overflow, which the lane's partial row sum shows: while it stays below kSumLimit every weight
+  // did.  Otherwise (rare: the reference is set from the row's first visible keys, and scores above it by
+  // more than 20 powers of two are not what attention inputs look like; or the row has no reference yet) the
+  // row maximum is formed after all, the reference moves, sum and output are rescaled and the weights redone.
+  // Any reference gives the same result up to rounding: weights, sum and output scale together.
+  //
+  // Sigmoid: y = log2 of w = e^x.  1 / (1 + 1 / w) = w - w^2 + w^3 - ...: where every w of the sub-tile is
+  // at most 1/16 the weight is taken as w - w^2, one multiply-add behind the exponential instead of an
+  // addition and a reciprocal (relative error w^2 <= 2^-8, one unit of the bf16 weight's last place, and
+  // only at the largest weights); else the exact form.  Under the usual bias of -ln(keys) almost every
+  // sub-tile qualifies.
+  static constexpr float kSumLimit = 1048576.f;  // 2^20
+  static constexpr float kSmallExp = -4.f;
+  __device__ __forceinline__ void folded_weights(f32x16& s, float& acc) {
+    if constexpr (C::NORM == NORM_SOFTMAX) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float x0 = fast_exp2(s[2 * q]), x1 = fast_exp2(s[2 * q + 1]);
+        acc += x0 + x1;
+        bf16x2 pr;
+        pr[0] = (__bf16)x0;
+        pr[1] = (__bf16)x1;
+        pk[q / 4][q % 4] = __builtin_bit_cast(uint32_t, pr);
+      }
+      if (__builtin_amdgcn_ballot_w64(acc > st.thr) != 0) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) mx = max3(mx, s[2 * q], s[2 * q + 1]);
+        mx = max_halves(mx);  // of the exponents, i.e. relative to the current reference (0 where there is none)
+        const bool unset = st.m == -INFINITY;
+        const bool move = unset ? mx > -INFINITY : mx > kLazyLog2;
+        const float d = move ? mx : 0.f;
+        if (__builtin_amdgcn_ballot_w64(move && !unset) != 0) {  // rows without a reference have nothing to rescale
+          const float alpha = (move && !unset) ? fast_exp2(-d) : 1.f;
+          st.l *= alpha;
+#pragma unroll
+          for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
+        }
+        if (move) st.m = unset ? mx : st.m + mx;
+        const bool still_unset = st.m == -INFINITY;
+        st.thr = still_unset ? -1.f : kSumLimit;
+        const float nm = still_unset ? 0.f : -st.m;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) cinit[r] = nm;
+        acc = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const float x0 = fast_exp2(s[2 * q] - d), x1 = fast_exp2(s[2 * q + 1] - d);
+          acc += x0 + x1;
+          bf16x2 pr;
+          pr[0] = (__bf16)x0;
+          pr[1] = (__bf16)x1;
+          pk[q / 4][q % 4] = __builtin_bit_cast(uint32_t, pr);
+        }
+      }
+    } else {
+      // largest exponent of the lane's 16 (a tree: three levels instead of a chain of eight)
+      const float t0 = max3(s[0], s[1], s[2]), t1 = max3(s[3], s[4], s[5]), t2 = max3(s[6], s[7], s[8]);
+      const float t3 = max3(s[9], s[10], s[11]), t4 = max3(s[12], s[13], s[14]);
+      const float mx = fmaxf(max3(t0, t1, t2), max3(t3, t4, s[15]));
+      if (__builtin_amdgcn_ballot_w64(mx > kSmallExp) != 0) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          bf16x2 pr;
+          pr[0] = (__bf16)fast_rcp(1.f + fast_exp2(-s[2 * q]));
+          pr[1] = (__bf16)fast_rcp(1.f + fast_exp2(-s[2 * q + 1]));
+          pk[q / 4][q % 4] = __builtin_bit_cast(uint32_t, pr);
+        }
+      } else {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const float w0 = fast_exp2(s[2 * q]), w1 = fast_exp2(s[2 * q + 1]);
+          bf16x2 pr;
+          pr[0] = (__bf16)__builtin_fmaf(-w0, w0, w0);
+          pr[1] = (__bf16)__builtin_fmaf(-w1, w1, w1);
+          pk[q / 4][q % 4] = __builtin_bit_cast(uint32_t, pr);
+        }
+      }
+    }
+  }
+
   // Vector phase: the raw scores in s (sub-tile u, starting at key j0 = 32u) become
   // packed weights in pk; the row state follows.
   // FAST: the caller knows that no key of the sub-tile is hidden from any row of the wave.
@@ -699,9 +794,11 @@ struct KeyLoop {
     const float dbase = C::MOD == MOD_DECAY ? g2 * (float)(i + off - j0 - 4 * half) : 0.f;
     float mx = -INFINITY, xm = 0.f, acc = 0.f;
     bool moved = false;
-    const bool fold = C::NORM == NORM_SIGMOID && p.fold;  // wave-uniform
-    if (masked) mask_raw<C>(s, jlim, fold ? INFINITY : -INFINITY);
-    if (masked_lo) mask_raw_below<C>(s, jlo, fold ? INFINITY : -INFINITY);
+    if (masked) mask_raw<C>(s, jlim, -INFINITY);
+    if (masked_lo) mask_raw_below<C>(s, jlo, -INFINITY);
+    if constexpr (C::FOLD) {
+      folded_weights(s, acc);
+    } else {
     if (C::MOD == MOD_DECAY && fact) {
       // one exponential per lane and sub-tile instead of one per score
       float ra = p.c * fast_exp2(dbase);
@@ -713,24 +810,17 @@ struct KeyLoop {
         s[4 * a + 3] *= ra * b3;
         ra *= a8;
       }
-    } else if (fold) {
-#pragma unroll
-      for (int q = 0; q < 8; ++q) post_pair<C, true>(p, q, s, dbase, g2, mx);
     } else {
 #pragma unroll
-      for (int q = 0; q < 8; ++q) post_pair<C, false>(p, q, s, dbase, g2, mx, bcur[q / 2][q % 2]);
+      for (int q = 0; q < 8; ++q) post_pair<C>(p, q, s, dbase, g2, mx, bcur[q / 2][q % 2]);
     }
     if (masked) mask_modified<C>(s, jlim);
     if (masked_lo) mask_modified_below<C>(s, jlo);
     post_done<C>(p, st, mx, moved, xm);
     lazy_rescale<C>(st, moved, xm);
     const float k0 = finish_k0<C>(p, st);
-    if (fold) {
 #pragma unroll
-      for (int q = 0; q < 8; ++q) pk[q / 4][q % 4] = finish_pair<C, true>(p, q, s, k0, acc);
-    } else {
-#pragma unroll
-      for (int q = 0; q < 8; ++q) pk[q / 4][q % 4] = finish_pair<C, false>(p, q, s, k0, acc);
+    for (int q = 0; q < 8; ++q) pk[q / 4][q % 4] = finish_pair<C>(p, q, s, k0, acc);
     }
     finish_done<C>(st, acc);
     pin(pk[0]);
@@ -754,8 +844,8 @@ struct KeyLoop {
     if (score) {
       static_for<S::NPV, S::NS>([&](auto rc) {
         constexpr int r = decltype(rc)::value, n = SUB * S::NS + r, g = r - S::NPV;
-        if constexpr (g == 0) s = zero16();
-        s = mfma(ring[n % S::PF], qf[g], s);
+        if constexpr (g == 0) s = mfma(ring[n % S::PF], qf[g], C::FOLD ? cinit : zero16());
+        else s = mfma(ring[n % S::PF], qf[g], s);
         fetch<n + S::PF>();
         sched_fence();
       });
@@ -821,6 +911,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   RowState<C> st;
   st.m = -INFINITY;
   st.l = 0.f;
+  st.thr = -1.f;
 #pragma unroll
   for (int db = 0; db < C::DB; ++db) st.o[db] = zero16();
 
@@ -945,6 +1036,11 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
 
   f32x16 s_a;   // scores of the sub-tile to aggregate next
   u32x4 pk[2];  // packed weights of the sub-tile being aggregated
+  // initial value of the scoring accumulator: zero; FOLD softmax: minus the row's reference (zero until it has
+  // one); FOLD sigmoid: the bias in log2 units
+  f32x16 cinit;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) cinit[r] = (C::FOLD && C::NORM == NORM_SIGMOID) ? p.b2 : 0.f;
 
   // ---- prologue: Q fragments; tiles 0 and 1 -> LDS; raw scores of sub-tile 0 -------
   // The Q fragments (B operand of S^T = K Q^T, resident for the whole kernel) hold,
@@ -993,9 +1089,9 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
       u32x4 v = __builtin_bit_cast(u32x4, read_k_frag(qaddr[tt]));
       if (p.neg_q) v ^= (u32x4){0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
       bf16x8 qv = __builtin_bit_cast(bf16x8, v);
-      if (C::NORM == NORM_SIGMOID && p.fold) {
+      if constexpr (C::FOLD) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) qv[e] = (__bf16)((float)qv[e] * -p.c);
+        for (int e = 0; e < 8; ++e) qv[e] = (__bf16)((float)qv[e] * p.c);
       }
       qf[tt] = qv;
     }
@@ -1018,7 +1114,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     // every wave has read its rows before tile 1 overwrites them
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     copy_slice(One{}, Zero{}, n_walk > 1 ? tile_at(1) : tile_at(0), 1);
-    if (C::WINDOW || n_vis > 2 * jt0) score_block<C>(kaddr, 0, qf, s_a);
+    if (C::WINDOW || n_vis > 2 * jt0) score_block<C>(kaddr, 0, qf, s_a, cinit);
   }
 
   // ---- key loop ------------------------------------------------------------------------
@@ -1044,7 +1140,7 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
   // last two iterations have no tile left to copy and wait for all copies instead.
   if (n_walk > 0) {
     bf16x8 ring[C::PF];
-    KeyLoop<C> kl{p, qf, st, pk, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2, false, 1.f, 1.f, 1.f, 1.f};
+    KeyLoop<C> kl{p, qf, st, pk, cinit, ring, kaddr, vaddr, 0u, 0u, i, off, iw0, g2, false, 1.f, 1.f, 1.f, 1.f};
     if constexpr (C::MOD == MOD_BIAS_T) {
       kl.bwave = p.bias + b * p.bs[0] + hq * p.bs[1];
 #pragma unroll
@@ -1180,8 +1276,9 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     float stat = l;  // abs-sum family: the sum itself
     if constexpr (C::NORM == NORM_SOFTMAX) {
       inv = l > 0.f ? 1.f / l : 0.f;
-      // weights are 2^(x*log2e - m): sum_j exp(x_j) = 2^m * l
-      stat = l > 0.f ? (st.m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : -INFINITY;
+      // weights are 2^(x*log2e - m): sum_j exp(x_j) = 2^m * l  (FOLD leaves a constant bias out of m: every
+      // weight of the row carries it, so only the statistic sees it)
+      stat = l > 0.f ? (st.m + (C::FOLD ? p.b2 : 0.f) + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : -INFINITY;
     } else if constexpr (C::NORM == NORM_ABSSUM) {
       inv = 1.f / fmaxf(l, 1.f);
     } else {

@@ -11,7 +11,8 @@
 
 namespace ae {
 static const KernelEntry kTable[] = {AE_ENTRIES_FOR_DIMS(128, 128, AE_SHAPE_128_128_NC, AE_SHAPE_128_128_C),
-                                     AE_ENTRIES_BIAS_TENSOR(128, 128, AE_SHAPE_128_128_NC, AE_SHAPE_128_128_C)};
+                                     AE_ENTRIES_BIAS_TENSOR(128, 128, AE_SHAPE_128_128_NC, AE_SHAPE_128_128_C),
+                                     AE_ENTRIES_FOLD(128, 128, AE_SHAPE_128_128_NC, AE_SHAPE_128_128_C)};
 
 const KernelEntry* table_128_128(int* n) {
   *n = (int)(sizeof(kTable) / sizeof(kTable[0]));

@@ -11,7 +11,8 @@
 
 namespace ae {
 static const KernelEntry kTable[] = {AE_ENTRIES_FOR_DIMS(64, 64, AE_SHAPE_64_64_NC, AE_SHAPE_64_64_C),
-                                     AE_ENTRIES_BIAS_TENSOR(64, 64, AE_SHAPE_64_64_NC, AE_SHAPE_64_64_C)};
+                                     AE_ENTRIES_BIAS_TENSOR(64, 64, AE_SHAPE_64_64_NC, AE_SHAPE_64_64_C),
+                                     AE_ENTRIES_FOLD(64, 64, AE_SHAPE_64_64_NC, AE_SHAPE_64_64_C)};
 
 const KernelEntry* table_64_64(int* n) {
   *n = (int)(sizeof(kTable) / sizeof(kTable[0]));

@@ -14,6 +14,13 @@ from paper_2502_15349_amd.workloads import BY_ID, C1, C2, C3, C4, C5, Workload, 
 pytestmark = pytest.mark.gpu
 
 MAX_ABS, MEAN_ABS = 1e-2, 1e-3
+# Bar of the softmax row statistic ln sum_j exp(x_ij).  The kernels take the scale on q, rounded to bf16 again (the
+# paper's own form of the modification, Section 4.1: q_mod = q / sqrt(d_k)), so every exponent carries that
+# rounding: relative 2^-9 uniform per element of q, i.e. a standard deviation of |scale| 2^-9 / sqrt(3) sqrt(sum_d
+# q_d^2 k_d^2) = about 1.1e-3 per score for unit-variance inputs at scale 1/sqrt(D); the statistic is a weighted mean
+# of such errors, held to 3.5 standard deviations.  (With the scale kept in fp32 on the scores -- the kernels used for
+# |scale| sqrt(D) > 2 -- the error is that of fp32 sums of fp32 exponentials, below 1e-3.)
+LSE_ABS = 4e-3
 DIMS = [(64, 64), (128, 128), (128, 256), (192, 128)]
 
 
@@ -261,8 +268,8 @@ def test_bf16_output(A, dims, norm, mod):
 @pytest.mark.parametrize("norm,mod,mask", [("softmax", "none", "causal"), ("softmax", "bias", "none"),
                                            ("abssum", "head_decay", "causal"), ("abs_of_sum", "none", "causal")])
 def test_row_statistics(A, dims, norm, mod, mask):
-    """ae_attn_forward_stats: the row statistic against the oracle's (fp32 sums of fp32 terms: 1e-3
-    absolute on ln-sum-exp, 1e-4 relative on the abs sums), and O unchanged by asking for it."""
+    """ae_attn_forward_stats: the row statistic against the oracle's (LSE_ABS absolute on ln-sum-exp, see above;
+    1e-4 relative on the abs sums: fp32 sums of fp32 terms), and O unchanged by asking for it."""
     from oracle import row_stats_head
     w = Workload("stats", 16, 2, 4, 2, 300, 333 if mask == "causal" else 280, dims[0], dims[1], mask=mask, norm=norm,
                  score_mod=mod, bias=0.75, decay=(mod == "head_decay"))
@@ -281,7 +288,7 @@ def test_row_statistics(A, dims, norm, mod, mask):
             ref = row_stats_head(Q[b, h], K[b, h // g], scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
                                  gamma_h=None if gam is None else gam[h], norm=w.norm, mask=w.oracle_mask())
             if norm == "softmax":
-                assert np.abs(got[b, h] - ref).max() <= 1e-3, (b, h, np.abs(got[b, h] - ref).max())
+                assert np.abs(got[b, h] - ref).max() <= LSE_ABS, (b, h, np.abs(got[b, h] - ref).max())
             else:
                 assert np.allclose(got[b, h], ref, rtol=1e-4, atol=1e-4), (b, h)
 
@@ -299,7 +306,7 @@ def test_row_statistics_rows_without_keys(A):
         ref = row_stats_head(Q[0, h], K[0, h], scale=w.scale_value, norm="softmax", mask="causal")
         assert (np.isneginf(got[0, h]) == np.isneginf(ref)).all()
         fin = np.isfinite(ref)
-        assert np.abs(got[0, h][fin] - ref[fin]).max() <= 1e-3
+        assert np.abs(got[0, h][fin] - ref[fin]).max() <= LSE_ABS
     assert (O[:, :, :63] == 0).all()
 
 
@@ -352,7 +359,7 @@ def test_split_keys(A, dims, Lq, Lk, mask, splits):
     for b in range(w.B):
         for h in range(w.H_q):
             ref = row_stats_head(Q[b, h], K[b, h // 4], scale=w.scale_value, norm="softmax", mask=w.oracle_mask())
-            assert np.abs(got[b, h] - ref).max() <= 1e-3
+            assert np.abs(got[b, h] - ref).max() <= LSE_ABS
     # bf16 output through the merge kernel: the fp32 merge result rounded
     Ob = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), kv_splits=splits, out_dtype=torch.bfloat16)
     assert torch.equal(Ob, O.to(torch.bfloat16))

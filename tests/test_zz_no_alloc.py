@@ -50,7 +50,7 @@ def _both(A, w, splits):
     want = row_stats_head(Q[0, 1], K[0, 1 // g], scale=w.scale_value, mask=w.oracle_mask())
     got = s2[0, 1].cpu().double().numpy()
     fin = np.isfinite(want)
-    assert (np.isneginf(got) == np.isneginf(want)).all() and np.abs(got[fin] - want[fin]).max() <= 1e-3
+    assert (np.isneginf(got) == np.isneginf(want)).all() and np.abs(got[fin] - want[fin]).max() <= 4e-3   # (the bar of the row statistic, see test_gpu_parity.LSE_ABS)
 
 
 def test_static_scratch_equals_workspace_two_calls_second_smaller(A):
