@@ -368,6 +368,51 @@ ae_status_t ae_recurrent_step(const ae_recurrent_t *h, const void *q, const void
                               void *o, hipStream_t stream);
 ae_status_t ae_recurrent_destroy(ae_recurrent_t *h); /* NULL is allowed */
 
+/* ---- Recurrent pattern with per-token gates: gated retention, Mamba2 SSM -----------
+ *
+ * The recurrent pattern (Section 4.1, "Attention Patterns and Templates") with
+ * the key and state modifications of Section 4.1's Mamba2 example (k_mod = k x
+ * gate, h_mod = h x decay x gate; Table 2 rows "Mamba2 SSM", "Gated Retention"):
+ *     h_t = a_t * h_{t-1} + (g_t * k_t)^T v_t        a_t = exp(log_decay_t)
+ *     o_t = scale * q_t h_t
+ * per batch entry and value head, h: [D_qk x D_v], h before the first token =
+ * h_in (zero if NULL).  The paper's "decay x gate" on the state is ONE factor
+ * a_t in (0, 1] per token here, passed as its natural logarithm (<= 0):
+ *   gated retention   log_decay = ln of the token's gate, key_gate = NULL;
+ *   Mamba2 SSM        q = C, k = B, v = x, log_decay = dt * A, key_gate = dt,
+ *                     H_qk = the number of B/C groups;
+ *   retention         log_decay = ln gamma[head] for every token.
+ * One kernel walks each (batch, head) in chunks of 64 tokens (Section 4.2: chunk
+ * parallelism) with the state on chip: Q, K, V are read once, O is written
+ * once, no workspace exists and nothing is allocated.
+ *
+ *   Q, K       device, bf16, contiguous [B, H_qk, L, D_qk]; value head h reads
+ *              q/k head h / (H / H_qk) (H_qk divides H; H_qk = H: one each);
+ *   V          device, bf16, contiguous [B, H, L, D_v];
+ *   log_decay  device, fp32, contiguous [B, H, L], every value <= 0 (not checked:
+ *              a positive value makes a_t > 1 and the chunk arithmetic may
+ *              overflow);
+ *   key_gate   device, fp32 [B, H, L], or NULL for all ones;
+ *   h_in       device, fp32 [B, H, D_qk, D_v], or NULL; h_out the same layout or
+ *              NULL (not written); h_out may be the buffer h_in points to;
+ *   O          device, [B, H, L, D_v], fp32 or (desc.out_dtype) bf16.
+ * Q, K, V, O and the states 16-byte aligned, the gates 4-byte; O and h_out must
+ * not alias the inputs.  D_qk and D_v each 64 or 128.  The launch is enqueued on
+ * `stream`; the call returns without waiting.  Errors: AE_ERR_INVALID_ARG
+ * (nothing is launched), AE_ERR_UNSUPPORTED, AE_ERR_NOMEM (create), AE_ERR_HIP. */
+typedef struct ae_gated ae_gated_t;
+typedef struct {
+  int32_t B, H, H_qk, L, D_qk, D_v;
+  float scale;              /* finite and non-zero */
+  ae_out_dtype_t out_dtype; /* element type of O */
+} ae_gated_desc_t;
+
+ae_status_t ae_gated_create(const ae_gated_desc_t *desc, ae_gated_t **out);
+ae_status_t ae_gated_forward(const ae_gated_t *h, const void *Q, const void *K, const void *V,
+                             const void *log_decay, const void *key_gate, const void *h_in,
+                             void *O, void *h_out, hipStream_t stream);
+ae_status_t ae_gated_destroy(ae_gated_t *h); /* NULL is allowed */
+
 #ifdef __cplusplus
 }
 #endif

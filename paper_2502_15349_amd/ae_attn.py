@@ -424,3 +424,64 @@ def run_workload(w, Q, K, V, out=None, out_dtype=None, stats=None, kv_splits=0, 
     return attention_forward(Q, K, V, scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
                              gamma=w.gamma(), norm=w.norm, mask=w.mask, out=out, out_dtype=out_dtype, stats=stats,
                              window=w.window, kv_splits=kv_splits, bias_tensor=bias_tensor)
+
+
+# ---- recurrent pattern with per-token gates (gated retention, Mamba2 SSM) ------------------------------------
+class ae_gated_desc_t(C.Structure):
+    _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("H_qk", C.c_int32), ("L", C.c_int32), ("D_qk", C.c_int32),
+                ("D_v", C.c_int32), ("scale", C.c_float), ("out_dtype", C.c_int)]
+
+
+_lib.ae_gated_create.argtypes = [C.POINTER(ae_gated_desc_t), C.POINTER(C.c_void_p)]
+_lib.ae_gated_create.restype = C.c_int
+_lib.ae_gated_forward.argtypes = [C.c_void_p] * 10
+_lib.ae_gated_forward.restype = C.c_int
+_lib.ae_gated_destroy.argtypes = [C.c_void_p]
+_lib.ae_gated_destroy.restype = C.c_int
+
+
+def ae_gated_create(*, B: int, H: int, L: int, D_qk: int, D_v: int, scale: float, H_qk: Optional[int] = None,
+                    out_dtype="f32") -> int:
+    d = ae_gated_desc_t()
+    d.B, d.H, d.H_qk, d.L, d.D_qk, d.D_v = B, H, H if H_qk is None else H_qk, L, D_qk, D_v
+    d.scale = float(scale)
+    d.out_dtype = OUT_DTYPES[out_dtype] if isinstance(out_dtype, str) else int(out_dtype)
+    h = C.c_void_p()
+    _check(_lib.ae_gated_create(C.byref(d), C.byref(h)))
+    return h.value
+
+
+def ae_gated_forward(handle: int, Q: int, K: int, V: int, log_decay: int, key_gate: int, h_in: int, O: int, h_out: int,
+                     stream: int = 0) -> None:
+    """Device pointers as ints; key_gate, h_in, h_out may be 0."""
+    _check(_lib.ae_gated_forward(handle, Q, K, V, log_decay, key_gate, h_in, O, h_out, stream))
+
+
+def ae_gated_destroy(handle: Optional[int]) -> None:
+    _check(_lib.ae_gated_destroy(handle))
+
+
+def gated_recurrent(Q, K, V, log_decay, key_gate=None, *, scale, h_in=None, want_state=False, out_dtype=None, stream=None):
+    """Runs the gated recurrent pattern on device tensors: Q, K bf16 [B, H_qk, L, D_qk], V bf16 [B, H, L, D_v],
+    log_decay / key_gate fp32 [B, H, L] (all contiguous), h_in fp32 [B, H, D_qk, D_v] or None.  Returns O
+    [B, H, L, D_v] (fp32, or bf16 with out_dtype=torch.bfloat16), and the final state when want_state."""
+    import torch
+
+    for t in (Q, K, V, log_decay) + (() if key_gate is None else (key_gate,)) + (() if h_in is None else (h_in,)):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("gated_recurrent needs contiguous device tensors; there is no CPU path")
+    B, H_qk, L, D_qk = Q.shape
+    _, H, _, D_v = V.shape
+    out = torch.empty((B, H, L, D_v), dtype=out_dtype or torch.float32, device=Q.device)
+    h_out = torch.empty((B, H, D_qk, D_v), dtype=torch.float32, device=Q.device) if want_state else None
+    h = ae_gated_create(B=B, H=H, H_qk=H_qk, L=L, D_qk=D_qk, D_v=D_v, scale=scale,
+                        out_dtype="bf16" if out.dtype == torch.bfloat16 else "f32")
+    try:
+        s = torch.cuda.current_stream(Q.device) if stream is None else stream
+        with torch.cuda.device(Q.device):
+            ae_gated_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), log_decay.data_ptr(),
+                             0 if key_gate is None else key_gate.data_ptr(), 0 if h_in is None else h_in.data_ptr(),
+                             out.data_ptr(), 0 if h_out is None else h_out.data_ptr(), s.cuda_stream)
+    finally:
+        ae_gated_destroy(h)
+    return (out, h_out) if want_state else out

@@ -13,6 +13,7 @@
 
 #include "bwd.hpp"
 #include "dispatch.hpp"
+#include "gated.hpp"
 #include "recurrent.hpp"
 
 // ---- static device scratch for the entry point that allocates nothing -----------------------
@@ -785,6 +786,72 @@ ae_status_t ae_recurrent_destroy(ae_recurrent_t* h) {
     ae_attn_destroy(h->tail);
     delete h;
   }
+  return AE_OK;
+}
+
+}  // extern "C"
+
+// ---- recurrent pattern with per-token gates: one kernel, state on chip ------------------------------------
+struct ae_gated {
+  ae_gated_desc_t desc;
+};
+
+extern "C" {
+
+ae_status_t ae_gated_create(const ae_gated_desc_t* d, ae_gated_t** out) {
+  if (out) *out = nullptr;
+  if (!d || !out) return fail(AE_ERR_INVALID_ARG, "ae_gated_create: null argument");
+  if (d->B < 1 || d->H < 1 || d->H_qk < 1 || d->L < 1) return fail(AE_ERR_INVALID_ARG, "ae_gated_create: B, H, H_qk, L must be >= 1");
+  if (d->H % d->H_qk != 0) return fail(AE_ERR_INVALID_ARG, "ae_gated_create: H (%d) is not a multiple of H_qk (%d)", d->H, d->H_qk);
+  if (!std::isfinite(d->scale) || d->scale == 0.f) return fail(AE_ERR_INVALID_ARG, "ae_gated_create: scale must be finite and non-zero");
+  if (d->out_dtype != AE_OUT_F32 && d->out_dtype != AE_OUT_BF16) return fail(AE_ERR_INVALID_ARG, "ae_gated_create: unknown out_dtype");
+  if (!ae::gated_supported(d->D_qk, d->D_v))
+    return fail(AE_ERR_UNSUPPORTED, "ae_gated_create: head dims %d/%d not built (D_qk and D_v each 64 or 128)", d->D_qk, d->D_v);
+  if ((int64_t)d->L * std::max(d->D_qk, d->D_v) * 2 >= (int64_t)1 << 32)
+    return fail(AE_ERR_UNSUPPORTED, "ae_gated_create: one (batch, head) slab must span less than 4 GiB");
+  if ((int64_t)d->B * d->H > 0x7fffffffLL) return fail(AE_ERR_UNSUPPORTED, "ae_gated_create: too many (batch, head) pairs");
+  ae_gated* h = new (std::nothrow) ae_gated;
+  if (!h) return fail(AE_ERR_NOMEM, "ae_gated_create: out of host memory");
+  h->desc = *d;
+  *out = h;
+  return AE_OK;
+}
+
+ae_status_t ae_gated_forward(const ae_gated_t* h, const void* Q, const void* K, const void* V, const void* log_decay,
+                             const void* key_gate, const void* h_in, void* O, void* h_out, hipStream_t stream) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_gated_forward: null handle");
+  if (!Q || !K || !V || !log_decay || !O) return fail(AE_ERR_INVALID_ARG, "ae_gated_forward: null pointer");
+  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O | (uintptr_t)h_in | (uintptr_t)h_out) & 15)
+    return fail(AE_ERR_INVALID_ARG, "ae_gated_forward: Q, K, V, O and the states must be 16-byte aligned");
+  if (((uintptr_t)log_decay | (uintptr_t)key_gate) & 3) return fail(AE_ERR_INVALID_ARG, "ae_gated_forward: the gates must be 4-byte aligned");
+  const void* ins[] = {Q, K, V, log_decay, key_gate, h_in};
+  for (const void* in : ins)
+    if (in && (in == O || (h_out && in == h_out && in != h_in)))
+      return fail(AE_ERR_INVALID_ARG, "ae_gated_forward: an output aliases an input");
+  if (h_out && h_out == O) return fail(AE_ERR_INVALID_ARG, "ae_gated_forward: the final state aliases O");
+  const ae_gated_desc_t& d = h->desc;
+  ae::GatedParams p;
+  p.Q = static_cast<const __bf16*>(Q);
+  p.K = static_cast<const __bf16*>(K);
+  p.V = static_cast<const __bf16*>(V);
+  p.log_decay = static_cast<const float*>(log_decay);
+  p.key_gate = static_cast<const float*>(key_gate);
+  p.h_in = static_cast<const float*>(h_in);
+  p.h_out = static_cast<float*>(h_out);
+  p.O = O;
+  p.B = d.B;
+  p.H = d.H;
+  p.H_qk = d.H_qk;
+  p.L = d.L;
+  p.scale = d.scale;
+  p.out_bf16 = d.out_dtype == AE_OUT_BF16;
+  const hipError_t e = ae::launch_gated_recurrent(p, d.D_qk, d.D_v, stream);
+  if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_gated_forward: %s", hipGetErrorString(e));
+  return AE_OK;
+}
+
+ae_status_t ae_gated_destroy(ae_gated_t* h) {
+  delete h;
   return AE_OK;
 }
 

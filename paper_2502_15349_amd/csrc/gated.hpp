@@ -1,0 +1,22 @@
+// Recurrent pattern with per-token gates: what ae_attn.hip needs to know of gated_recurrent.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ae {
+struct GatedParams {
+  const __bf16* Q;          // [B, H_qk, L, D_qk]
+  const __bf16* K;          // [B, H_qk, L, D_qk]
+  const __bf16* V;          // [B, H, L, D_v]
+  const float* log_decay;   // [B, H, L]: ln a_t <= 0
+  const float* key_gate;    // [B, H, L] or null (ones)
+  const float* h_in;        // [B, H, D_qk, D_v] fp32 or null (zero)
+  float* h_out;             // the same layout, or null
+  void* O;                  // [B, H, L, D_v] fp32, or bf16 if out_bf16
+  int B, H, H_qk, L;
+  float scale;
+  int out_bf16;
+};
+bool gated_supported(int dqk, int dv);
+hipError_t launch_gated_recurrent(const GatedParams& p, int dqk, int dv, hipStream_t stream);
+}  // namespace ae

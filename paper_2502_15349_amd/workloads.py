@@ -148,3 +148,21 @@ def make_bias_tensor(w: Workload, per_batch: bool = True, per_head: bool = True,
     g.manual_seed(base + 11)
     shape = (w.B if per_batch else 1, w.H_q if per_head else 1, w.L_q, w.L_k)
     return torch.randn(shape, generator=g, dtype=torch.float32).to(torch.bfloat16).contiguous()
+
+
+def make_gates(B: int, H: int, L: int, seed: int, kind: str = "gated_retention"):
+    """Per-token gates of the recurrent pattern, CPU fp32 [B, H, L], from a seed of their own.  Returns (log_decay,
+    key_gate or None); the recipes follow how the models of Table 2 produce them from a token projection x ~ N(0, 1):
+      gated_retention  decay = sigmoid(x) ** (1 / 16) (a sigmoid gate raised to a small power), no key gate;
+      mamba2           dt = softplus(x - 4) (time steps around 0.02 .. 0.2), per-head A = -(1 + h % 16):
+                       log_decay = dt * A, key_gate = dt."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    x = torch.randn((B, H, L), generator=g, dtype=torch.float32)
+    if kind == "gated_retention":
+        return (torch.nn.functional.logsigmoid(x) / 16.0).contiguous(), None
+    if kind == "mamba2":
+        dt = torch.nn.functional.softplus(x - 4.0)
+        A = -(1.0 + (torch.arange(H, dtype=torch.float32) % 16)).view(1, H, 1)
+        return (dt * A).contiguous(), dt.contiguous()
+    raise ValueError(kind)

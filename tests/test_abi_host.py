@@ -15,7 +15,7 @@ pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libae_attn.so n
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "ae_attn.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(ae_(?:attn|calib|recurrent)_[a-z0-9_]+)\s*\(", hdr))
+    names = set(re.findall(r"\b(ae_(?:attn|calib|recurrent|gated)_[a-z0-9_]+)\s*\(", hdr))
     assert {"ae_attn_create", "ae_attn_forward", "ae_attn_destroy", "ae_attn_query", "ae_calib_mfma_bf16"} <= names
     lib = ctypes.CDLL(LIB)
     for n in names:
