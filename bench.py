@@ -169,6 +169,9 @@ def main():
     ap.add_argument("--recurrent", action="store_true",
                     help="time the recurrent pattern (chunk-parallel retention, ae_recurrent_forward) per chunk size, beside "
                          "the parallel form of the same sum; prints one JSON object with a row per shape")
+    ap.add_argument("--gated", action="store_true",
+                    help="time the recurrent pattern with per-token gates (ae_gated_forward: gated retention, Mamba2 SSM, "
+                         "retention with a constant decay) on Table 2's recurrent shapes; GB/s against the HBM peak")
     ap.add_argument("--only", default="", help="with --backward: only the shapes whose name contains this")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device-to-device copy of this many MiB "
@@ -187,6 +190,9 @@ def main():
         if a.backward:
             child, name = ["--backward", "--only", a.only], f"attn_bwd_{a.only or 'all'}"
             trace_args = pmc_args = ()
+        elif a.gated:
+            child, name = ["--gated", "--only", a.only], f"gated_recurrent_{a.only or 'all'}"
+            trace_args, pmc_args = ("--steps", "20"), ("--steps", "3")
         elif a.recurrent:
             child, name = ["--recurrent", "--only", a.only], f"recurrent_{a.only or 'all'}"
             trace_args, pmc_args = ("--steps", "20"), ("--steps", "3")
@@ -569,6 +575,68 @@ def main():
                   file=sys.stderr, flush=True)
         print(json.dumps({"recurrent": rows, "recurrent_step": steps_rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16",
                           "data": "synthetic"}))
+        return
+    if a.gated:
+        # Not the contract line.  One pass over Q, K, V, the gates and O: compulsory bytes 2 (2 D_qk / g + D_v) + 4 D_v + 8
+        # per token and value head (g value heads share a q/k head) against 8 TB/s.
+        import math
+        from oracle.gated_recurrent_oracle import gated_recurrent_head
+        from paper_2502_15349_amd.workloads import Workload, make_gates
+        shapes = [  # name, B, H, H_qk, L, D_qk, D_v, gates
+            ("gated_retention_b8_h32_s8192_d128", 8, 32, 32, 8192, 128, 128, "gated_retention"),
+            ("retention_const_b8_h32_s8192_d128", 8, 32, 32, 8192, 128, 128, "const"),
+            ("gated_retention_rfa_b8_h16_s8192_d64", 8, 16, 16, 8192, 64, 64, "gated_retention"),
+            ("mamba2_ssm_b8_h80_s8192_128_64", 8, 80, 1, 8192, 128, 64, "mamba2"),
+            ("mamba2_ssm_b1_h80_s8192_128_64", 1, 80, 1, 8192, 128, 64, "mamba2"),
+            ("gated_retention_b1_h32_s32768_d128", 1, 32, 32, 32768, 128, 128, "gated_retention"),
+        ]
+        rows = []
+        for name, B, H, Hqk, L, Dq, Dv, kind in shapes:
+            if a.only and a.only not in name:
+                continue
+            cid = 500 + len(rows)
+            Qc, Kc, _ = make_inputs(Workload("q", cid, B, Hqk, Hqk, L, L, Dq, Dq))
+            _, _, Vc = make_inputs(Workload("v", cid, B, H, H, L, L, Dv, Dv))
+            if kind == "const":
+                gam = torch.tensor([1.0 - 2.0 ** (-5 - (i % 8)) for i in range(H)], dtype=torch.float32)
+                lac, kgc = torch.log(gam).view(1, H, 1).expand(B, H, L).contiguous(), None
+            else:
+                lac, kgc = make_gates(B, H, L, 1000 * cid + 5, kind)
+            Q, K, V, la = Qc.to(dev), Kc.to(dev), Vc.to(dev), lac.to(dev)
+            kg = None if kgc is None else kgc.to(dev)
+            scale = 1.0 / math.sqrt(Dq)
+            O = torch.empty((B, H, L, Dv), dtype=torch.float32, device=dev)
+            h = A.ae_gated_create(B=B, H=H, H_qk=Hqk, L=L, D_qk=Dq, D_v=Dv, scale=scale)
+            st = torch.cuda.current_stream()
+            args = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), la.data_ptr(), 0 if kg is None else kg.data_ptr(), 0, O.data_ptr(), 0,
+                    st.cuda_stream)
+            for _ in range(3):
+                A.ae_gated_forward(*args)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            for _ in range(a.steps):
+                A.ae_gated_forward(*args)
+            e1.record(st)
+            torch.cuda.synchronize()
+            A.ae_gated_destroy(h)
+            ms = e0.elapsed_time(e1) / a.steps
+            b_s, h_s = B - 1, H // 2
+            g_s = h_s // (H // Hqk)
+            ref = gated_recurrent_head(Qc[b_s, g_s].float().numpy(), Kc[b_s, g_s].float().numpy(), Vc[b_s, h_s].float().numpy(),
+                                       lac[b_s, h_s].numpy(), None if kgc is None else kgc[b_s, h_s].numpy(), scale=scale)
+            got = O[b_s, h_s].cpu().double().numpy()
+            err = float((np.abs(got - ref) / np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)).max())
+            byts = B * L * (2 * 2 * Dq * Hqk + H * (2 * Dv + 4 * Dv + (8 if kg is not None else 4)))
+            flop = 4.0 * Dq * Dv * B * H * L
+            rows.append({"workload": name, "B": B, "H": H, "H_qk": Hqk, "L": L, "D_qk": Dq, "D_v": Dv, "ms": round(ms, 4),
+                         "tokens_per_s": round(B * L / ms * 1e3, 1), "GBps": round(byts / ms / 1e6, 1),
+                         "frac_of_hbm_peak": round(byts / ms / 1e6 / 8000.0, 4), "recurrence_tflops": round(flop / ms / 1e9, 1),
+                         "compulsory_bytes": byts, "parity_max_abs": err})
+            print(f"# {name:40s} {ms:8.4f} ms = {byts / ms / 1e6:7.1f} GB/s ({100 * byts / ms / 1e6 / 8000.0:4.1f} % of HBM peak), "
+                  f"{flop / ms / 1e9:6.1f} TFLOP/s of recurrence, max_abs {err:.2e}", file=sys.stderr, flush=True)
+            del Q, K, V, O, la, kg
+        print(json.dumps({"gated_recurrent": rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16", "data": "synthetic"}))
         return
     if a.table2:
         # Not the contract line: the paper's own microbenchmark grid, one row per shape.

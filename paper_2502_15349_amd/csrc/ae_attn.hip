@@ -37,7 +37,7 @@ ae_status_t fail(ae_status_t code, const char* fmt, ...) {
 
 const ae::KernelEntry* find_kernel(int dqk, int dv, int norm, int mod, int mask, int fold) {
   typedef const ae::KernelEntry* (*table_fn)(int*);
-  static const table_fn tables[] = {ae::table_64_64, ae::table_128_128, ae::table_128_256, ae::table_192_128};
+  static const table_fn tables[] = {ae::table_64_64, ae::table_128_128, ae::table_128_256, ae::table_192_128, ae::table_256_128};
   for (table_fn tf : tables) {
     int n = 0;
     const ae::KernelEntry* t = tf(&n);
@@ -50,7 +50,7 @@ const ae::KernelEntry* find_kernel(int dqk, int dv, int norm, int mod, int mask,
 
 bool dims_supported(int dqk, int dv) {
   return (dqk == 64 && dv == 64) || (dqk == 128 && dv == 128) || (dqk == 128 && dv == 256) ||
-         (dqk == 192 && dv == 128);
+         (dqk == 192 && dv == 128) || (dqk == 256 && (dv == 128 || dv == 512));
 }
 
 void fill_strides(int64_t dst[3], const int64_t src[3], int H, int L, int D) {
@@ -133,6 +133,10 @@ struct ae_attn {
   ae::DecayTable decay;
   int grid;
   size_t ws_bytes;  // workspace the split-key forward needs (0: keys are not split)
+  // D_v = 512 (Table 2, "Retention Parallel" 256 / 512): the output accumulators of 512 columns do not fit the
+  // register file beside the 256-wide query fragments, so the forward pass is v_slices launches of the 256 / 128
+  // kernel, each over 128 columns of V and O (the scores and the row normalizer are the same in every launch)
+  int v_slices;
 };
 
 extern "C" {
@@ -166,7 +170,7 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: problem too large for 32-bit tile indices");
 
   if (!dims_supported(d->D_qk, d->D_v))
-    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: head dims %d/%d not in the tile table (64/64, 128/128, 128/256, 192/128)",
+    return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: head dims %d/%d not in the tile table (64/64, 128/128, 128/256, 192/128; 256/128 and 256/512 for retention)",
                 d->D_qk, d->D_v);
 
   int mod = ae::MOD_PLAIN;
@@ -194,8 +198,10 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   // Larger scales keep the scale in fp32 on the scores.
   const bool fold = (d->norm == AE_NORM_SOFTMAX || d->norm == AE_NORM_SIGMOID) && mod == ae::MOD_PLAIN &&
                     std::fabs(d->scale) * std::sqrt((float)d->D_qk) <= 2.f;
-  const ae::KernelEntry* k = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, (int)d->mask, fold ? 1 : 0);
-  if (!k && fold) k = find_kernel(d->D_qk, d->D_v, (int)d->norm, mod, (int)d->mask, 0);
+  const int v_slices = d->D_v == 512 ? 4 : 1;
+  if (v_slices > 1 && d->kv_splits > 1) return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: D_v = 512 comes without split keys");
+  const ae::KernelEntry* k = find_kernel(d->D_qk, d->D_v / v_slices, (int)d->norm, mod, (int)d->mask, fold ? 1 : 0);
+  if (!k && fold) k = find_kernel(d->D_qk, d->D_v / v_slices, (int)d->norm, mod, (int)d->mask, 0);
   if (!k)
     return fail(AE_ERR_UNSUPPORTED, "ae_attn_create: no kernel for score_mod %d with norm %d and mask %d",
                 (int)d->score_mod, (int)d->norm, (int)d->mask);
@@ -206,6 +212,7 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   h->desc = *d;
   h->desc.gamma = nullptr;  // the caller's array is not kept
   h->kernel = k;
+  h->v_slices = v_slices;
 
   ae::Params& p = h->params;
   p.B = d->B; p.H_q = d->H_q; p.H_kv = d->H_kv; p.L_q = d->L_q; p.L_k = d->L_k;
@@ -309,7 +316,7 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
     // ranges cost a start and an end of a workgroup apiece.  Only where the keys may be split
     // and the query tiles alone leave most of the device idle.
     kv_splits = 0;
-    if (d->norm == AE_NORM_SOFTMAX && d->mask != AE_MASK_SLIDING_WINDOW && mod != ae::MOD_BIAS_T && grid < 160) {
+    if (d->norm == AE_NORM_SOFTMAX && d->mask != AE_MASK_SLIDING_WINDOW && mod != ae::MOD_BIAS_T && v_slices == 1 && grid < 160) {
       const int key_tiles = (d->L_k + h->kernel->block_n - 1) / h->kernel->block_n;
       const int64_t want = (192 + grid / 2) / grid;  // round(192 / workgroups)
       kv_splits = (int)std::min<int64_t>(std::min<int64_t>(want, key_tiles / 8), 256);
@@ -376,7 +383,14 @@ static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K
     p.ws_o = static_cast<float*>(workspace);
     p.ws_lse = p.ws_o + (size_t)p.n_splits * rows * h->desc.D_v;
   }
-  hipError_t e = h->kernel->launch(p, h->decay, h->grid, static_cast<hipStream_t>(stream));
+  hipError_t e = hipSuccess;
+  for (int sl = 0; sl < h->v_slices && e == hipSuccess; ++sl) {
+    if (sl > 0) {  // the next 128 columns of V and O
+      p.V += h->kernel->dv;
+      p.O = static_cast<char*>(p.O) + (size_t)h->kernel->dv * (p.out_bf16 ? 2 : 4);
+    }
+    e = h->kernel->launch(p, h->decay, h->grid, static_cast<hipStream_t>(stream));
+  }
   if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_attn_forward: launch failed: %s", hipGetErrorString(e));
   if (p.n_splits > 1) {
     MergeParams m;

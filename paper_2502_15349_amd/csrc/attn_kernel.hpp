@@ -135,7 +135,10 @@ struct Cfg {
   static constexpr int cmax(int a, int b) { return a > b ? a : b; }
   // (bias tensor: two buffers of 2 KB per wave behind the stages, see KeyLoop::copy_bias)
   static constexpr int BIAS_BYTES = MOD_ == MOD_BIAS_T ? WAVES * 4096 : 0;
-  static constexpr int LDS_BYTES = cmax(TILE_BYTES + BIAS_BYTES, cmax(OUT_BYTES, STAGE_BYTES + Q_BYTES));
+  // D_qk = 256: the query rows of a workgroup (128 KB) do not fit behind stage 0; the fragments are loaded
+  // straight from memory there (a slower start of the workgroup, once per 256 rows)
+  static constexpr bool kQDirect = STAGE_BYTES + Q_BYTES > 160 * 1024;
+  static constexpr int LDS_BYTES = cmax(TILE_BYTES + BIAS_BYTES, cmax(OUT_BYTES, kQDirect ? 0 : STAGE_BYTES + Q_BYTES));
   static constexpr int NB_K = K_BYTES / 1024, NB_V = V_BYTES / 1024;  // 1 KB blocks per tile
   static constexpr int KI = (NB_K + WAVES - 1) / WAVES, VI = (NB_V + WAVES - 1) / WAVES;
   static constexpr int T = DQK / 16;  // contraction steps of the scoring MFMA
@@ -152,7 +155,7 @@ struct Cfg {
   static_assert(WAVES % 2 == 0, "waves pair up per SIMD");
   static_assert(DQK % 16 == 0 && DV % 32 == 0, "head dims must fit the MFMA tile");
   static_assert(K_BYTES % 1024 == 0 && V_BYTES % 1024 == 0, "tiles must be whole 1 KB blocks");
-  static_assert(CPR_K == 8 || CPR_K == 16 || CPR_K == 24, "K swizzle is defined for these row sizes");
+  static_assert(CPR_K == 8 || CPR_K == 16 || CPR_K == 24 || CPR_K == 32, "K swizzle is defined for these row sizes");
   static_assert(CPR_V == 8 || CPR_V == 16 || CPR_V == 32, "V swizzle is defined for these row sizes");
   static_assert(LDS_BYTES <= 160 * 1024, "tiles do not fit LDS");
 };
@@ -1060,13 +1063,15 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     // rows past the end of the queries repeat the last one (their output is not stored)
     const int qrow0 = min(iw0, max(p.L_q - 32, 0));
     const __bf16* qtile = qbase + (int64_t)qrow0 * p.qs[2];
-    static_for<0, QMap::N>([&](auto mc) {
-      constexpr int m = decltype(mc)::value;
-      const int pos = m * 64 + lane, r = pos / C::CPR_K, pc = pos % C::CPR_K;
-      const int row = min(iw0 + r, p.L_q - 1) - qrow0;
-      const uint32_t goff = (uint32_t)(row * (int)p.qs[2] + (pc ^ kswz<C::CPR_K>(r)) * 8) * 2u;
-      dma16_at<m * 1024>(qtile, goff, qlds);
-    });
+    if constexpr (!C::kQDirect) {
+      static_for<0, QMap::N>([&](auto mc) {
+        constexpr int m = decltype(mc)::value;
+        const int pos = m * 64 + lane, r = pos / C::CPR_K, pc = pos % C::CPR_K;
+        const int row = min(iw0 + r, p.L_q - 1) - qrow0;
+        const uint32_t goff = (uint32_t)(row * (int)p.qs[2] + (pc ^ kswz<C::CPR_K>(r)) * 8) * 2u;
+        dma16_at<m * 1024>(qtile, goff, qlds);
+      });
+    }
     copy_slice(One{}, Zero{}, tile_at(0), 0);
     if constexpr (kState) {
       // The state is stored transposed ([D_v][D_qk]), so a lane's A fragment (output column lane % 32 of block
@@ -1084,9 +1089,12 @@ __global__ __launch_bounds__(C::THREADS) void attn_fwd_kernel(const Params p, co
     wait_dma_and_sync();  // one memory latency for the queries and the first tile
     uint32_t qaddr[C::T];
     k_frag_offsets<C>(qlds, qaddr);
+    const __bf16* qrow = qbase + (int64_t)min(i, p.L_q - 1) * p.qs[2] + 8 * half;  // kQDirect: this lane's row
 #pragma unroll
     for (int tt = 0; tt < C::T; ++tt) {
-      u32x4 v = __builtin_bit_cast(u32x4, read_k_frag(qaddr[tt]));
+      u32x4 v;
+      if constexpr (C::kQDirect) v = *reinterpret_cast<const u32x4*>(qrow + 16 * tt);
+      else v = __builtin_bit_cast(u32x4, read_k_frag(qaddr[tt]));
       if (p.neg_q) v ^= (u32x4){0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
       bf16x8 qv = __builtin_bit_cast(bf16x8, v);
       if constexpr (C::FOLD) {

@@ -82,5 +82,6 @@ const KernelEntry* table_64_64(int* n);
 const KernelEntry* table_128_128(int* n);
 const KernelEntry* table_128_256(int* n);
 const KernelEntry* table_192_128(int* n);
+const KernelEntry* table_256_128(int* n);
 
 }  // namespace ae

@@ -37,15 +37,17 @@
 namespace ae {
 namespace {
 
-template <int DQK_, int DV_>
+// HPW_: value heads per workgroup.  Heads of one q/k group (Mamba2: every head of a group reads the same B and C)
+// can share the Q and K tiles of a workgroup: HPW_ consecutive heads, each with its own V tile, gates and state.
+template <int DQK_, int DV_, int HPW_ = 1>
 struct GCfg {
-  static constexpr int DQK = DQK_, DV = DV_, WAVES = DV_ / 32, THREADS = 64 * WAVES, CH = 64;
+  static constexpr int DQK = DQK_, DV = DV_, HPW = HPW_, WPH = DV_ / 32, WAVES = HPW_ * WPH, THREADS = 64 * WAVES, CH = 64;
   static constexpr int RBQ = DQK * 2, RBV = DV * 2, CPRQ = DQK / 8, CPRV = DV / 8;
-  static constexpr int Q_BYTES = CH * RBQ, V_BYTES = CH * RBV, STAGE_BYTES = 2 * Q_BYTES + V_BYTES;
+  static constexpr int Q_BYTES = CH * RBQ, V_BYTES = CH * RBV, STAGE_BYTES = 2 * Q_BYTES + HPW * V_BYTES;
   static constexpr int GATE_BYTES = 3 * CH * 4;  // per wavefront: b, g, w of the chunk's tokens
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES + WAVES * GATE_BYTES;
   static constexpr int T = DQK / 16, DBQ = DQK / 32;
-  static_assert(CPRQ % WAVES == 0 && CPRV % WAVES == 0, "every wave copies the same number of 1 KB blocks");
+  static_assert(CPRQ % WAVES == 0 && CPRV % WPH == 0, "every wave copies the same number of 1 KB blocks");
   static_assert(LDS_BYTES <= 160 * 1024, "tiles do not fit LDS");
 };
 
@@ -56,13 +58,21 @@ __device__ __forceinline__ void lds_write4(uint32_t addr, float v) {
   *reinterpret_cast<__attribute__((address_space(3))) float*>((lds_char*)(uintptr_t)addr) = v;
 }
 
+// x of the lane that the control word selects, 0 where it selects none or the masks switch the lane off
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ __forceinline__ float dpp_f(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROW_MASK, BANK_MASK, false));
+}
+
 template <class C>
 __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const GatedParams p) {
   __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ln = lane & 31, half = lane >> 5;
-  const int bh = blockIdx.x, b = bh / p.H, h = bh % p.H;
+  // workgroup -> batch entry and HPW consecutive value heads of one q/k group; wave -> (head, 32 value columns)
+  const int hw = wave / C::WPH, vblk = wave % C::WPH;
+  const int bh0 = blockIdx.x * C::HPW, b = bh0 / p.H, h = bh0 % p.H + hw, bh = bh0 + hw;
   const int hqk = h / (p.H / p.H_qk);
   const int64_t L = p.L;
   const __bf16* Qh = p.Q + ((int64_t)b * p.H_qk + hqk) * L * C::DQK;
@@ -77,7 +87,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
 #pragma unroll
   for (int db = 0; db < C::DBQ; ++db) {
     if (p.h_in) {
-      const float* src = p.h_in + (int64_t)bh * C::DQK * C::DV + 32 * wave + ln;
+      const float* src = p.h_in + (int64_t)bh * C::DQK * C::DV + 32 * vblk + ln;
 #pragma unroll
       for (int r = 0; r < 16; ++r) H[db][r] = src[(int64_t)(32 * db + key_offset(r) + 4 * half) * C::DV];
     } else {
@@ -89,19 +99,19 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   auto issue_chunk = [&](int c) {
     const int t0 = c * C::CH;
     const uint32_t base = lds0 + (c & 1) * C::STAGE_BYTES;
-    auto tile = [&](const __bf16* src, auto cprc, uint32_t dst) {
-      constexpr int CPR = decltype(cprc)::value;
+    auto tile = [&](const __bf16* src, auto cprc, uint32_t dst, auto nwc, int w) {
+      constexpr int CPR = decltype(cprc)::value, NW = decltype(nwc)::value;  // copied by NW waves, this one being number w
 #pragma unroll
-      for (int i = 0; i < CPR / C::WAVES; ++i) {
-        const int nb = wave + i * C::WAVES, pos = nb * 64 + lane;
+      for (int i = 0; i < CPR / NW; ++i) {
+        const int nb = w + i * NW, pos = nb * 64 + lane;
         const int r = pos / CPR, pc = pos % CPR;
         const int row = min(t0 + r, (int)L - 1);
         dma16(src, (uint32_t)((row * (CPR * 8) + ((pc ^ bswz<CPR>(r)) * 8)) * 2), dst + nb * 1024);
       }
     };
-    tile(Qh, std::integral_constant<int, C::CPRQ>{}, base);
-    tile(Kh, std::integral_constant<int, C::CPRQ>{}, base + C::Q_BYTES);
-    tile(Vh, std::integral_constant<int, C::CPRV>{}, base + 2 * C::Q_BYTES);
+    tile(Qh, std::integral_constant<int, C::CPRQ>{}, base, std::integral_constant<int, C::WAVES>{}, wave);
+    tile(Kh, std::integral_constant<int, C::CPRQ>{}, base + C::Q_BYTES, std::integral_constant<int, C::WAVES>{}, wave);
+    tile(Vh, std::integral_constant<int, C::CPRV>{}, base + 2 * C::Q_BYTES + hw * C::V_BYTES, std::integral_constant<int, C::WPH>{}, vblk);
   };
   // gates of chunk c for token lane: log-decay (0 past the end: the state is carried unchanged) and key gate (0 past the end)
   auto load_gates = [&](int c, float& la, float& g) {
@@ -141,7 +151,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   for (int c = 0; c < n_chunks; ++c) {
     const int t0 = c * C::CH;
     const uint32_t sb = lds0 + (c & 1) * C::STAGE_BYTES;
-    const uint32_t qb = sb, kb_ = sb + C::Q_BYTES, vb_ = sb + 2 * C::Q_BYTES;
+    const uint32_t qb = sb, kb_ = sb + C::Q_BYTES, vb_ = sb + 2 * C::Q_BYTES + hw * C::V_BYTES;
     const float la = la_next, g = g_next;
     // chunk c has landed (this wave's copies; the barrier: everybody's), and every wave is done with chunk c - 1
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
@@ -151,17 +161,20 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     }
 
     // ---- gates: b = inclusive prefix sum of the log-decays over the chunk's 64 tokens (lane = token) ----
+    // (data-parallel-primitive steps: within rows of 16 lanes by shifts of 1, 2, 4, 8, then the row totals onward)
     float bcum = la;
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) {
-      const float x = __shfl_up(bcum, s, 64);
-      if (lane >= s) bcum += x;
-    }
-    const float b_last = __shfl(bcum, 63, 64);
+    bcum += dpp_f<0x111, 0xf, 0xf>(bcum);
+    bcum += dpp_f<0x112, 0xf, 0xf>(bcum);
+    bcum += dpp_f<0x114, 0xf, 0xe>(bcum);
+    bcum += dpp_f<0x118, 0xf, 0xc>(bcum);
+    bcum += dpp_f<0x142, 0xa, 0xf>(bcum);
+    bcum += dpp_f<0x143, 0xc, 0xf>(bcum);
+    const float b_last = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bcum), 63));
     lds_write4(gate0 + lane * 4, bcum);
     lds_write4(gate0 + 256 + lane * 4, g);
     lds_write4(gate0 + 512 + lane * 4, __expf(b_last - bcum) * g);
-    const float bi0 = __shfl(bcum, ln, 64), bi1 = __shfl(bcum, 32 + ln, 64);  // of this lane's two queries
+    float bi0, bi1;  // of this lane's two queries: tokens ln and 32 + ln
+    swap_halves(bcum, bi0, bi1);
 
     // ---- Q fragments of both query blocks (B operands of S^T and of the read-out) ----
     bf16x8 qf[2][C::T];
@@ -230,7 +243,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     // ---- aggregation inside the chunk: O^T += V^T P^T (this wave's 32 value columns) ----
     bf16x8 vf[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) vf[s] = tr_frag(vb_, std::integral_constant<int, C::CPRV>{}, wave, s);
+    for (int s = 0; s < 4; ++s) vf[s] = tr_frag(vb_, std::integral_constant<int, C::CPRV>{}, vblk, s);
     o[0] = mfma(vf[0], __builtin_bit_cast(bf16x8, p00[0]), o[0]);
     o[0] = mfma(vf[1], __builtin_bit_cast(bf16x8, p00[1]), o[0]);
     o[1] = mfma(vf[0], __builtin_bit_cast(bf16x8, p01[0]), o[1]);
@@ -243,7 +256,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     for (int ib = 0; ib < 2; ++ib) {
       const int64_t i = t0 + 32 * ib + ln;
       if (i < L) {
-        const int64_t e0 = ((int64_t)bh * L + i) * C::DV + 32 * wave + 4 * half;
+        const int64_t e0 = ((int64_t)bh * L + i) * C::DV + 32 * vblk + 4 * half;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
           const f32x4 v = {o[ib][4 * a], o[ib][4 * a + 1], o[ib][4 * a + 2], o[ib][4 * a + 3]};
@@ -284,7 +297,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   }
 
   if (p.h_out) {
-    float* dst = p.h_out + (int64_t)bh * C::DQK * C::DV + 32 * wave + ln;
+    float* dst = p.h_out + (int64_t)bh * C::DQK * C::DV + 32 * vblk + ln;
 #pragma unroll
     for (int db = 0; db < C::DBQ; ++db)
 #pragma unroll
@@ -292,10 +305,10 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   }
 }
 
-template <int DQK, int DV>
+template <int DQK, int DV, int HPW = 1>
 hipError_t launch(const GatedParams& p, hipStream_t s) {
-  typedef GCfg<DQK, DV> C;
-  hipLaunchKernelGGL(gated_recurrent_kernel<C>, dim3((unsigned)(p.B * p.H)), dim3(C::THREADS), 0, s, p);
+  typedef GCfg<DQK, DV, HPW> C;
+  hipLaunchKernelGGL(gated_recurrent_kernel<C>, dim3((unsigned)(p.B * p.H / HPW)), dim3(C::THREADS), 0, s, p);
   return hipGetLastError();
 }
 
@@ -305,7 +318,13 @@ bool gated_supported(int dqk, int dv) { return (dqk == 64 || dqk == 128) && (dv 
 
 hipError_t launch_gated_recurrent(const GatedParams& p, int dqk, int dv, hipStream_t s) {
   if (dqk == 64 && dv == 64) return launch<64, 64>(p, s);
-  if (dqk == 128 && dv == 64) return launch<128, 64>(p, s);
+  if (dqk == 128 && dv == 64) {
+    // value heads that share their q/k head (Mamba2's groups) share the Q and K tiles of a workgroup, up to four
+    const int grp = p.H / p.H_qk;
+    if (grp % 4 == 0) return launch<128, 64, 4>(p, s);
+    if (grp % 2 == 0) return launch<128, 64, 2>(p, s);
+    return launch<128, 64>(p, s);
+  }
   if (dqk == 64 && dv == 128) return launch<64, 128>(p, s);
   if (dqk == 128 && dv == 128) return launch<128, 128>(p, s);
   return hipErrorInvalidValue;

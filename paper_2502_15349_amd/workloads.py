@@ -94,14 +94,15 @@ def table2_workloads():
     tile table covers, over its grid of batch 1 / 8 and sequence 2k / 4k / 8k (Section 6.1).
     The paper does not say which rows are causal: the language-model rows are taken as
     causal, the vision row (ReLU attention, ViT) as unmasked; the sigmoid row gets the
-    bias -ln(L) of sigmoid attention.  Retention parallel at 256/512 is outside the table
-    of head dims."""
+    bias -ln(L) of sigmoid attention; the retention row (256 / 512) gets RetNet's per-head decay
+    rates and the abs-sum normalizer of the retention configuration."""
     rows = (
         ("softmax_llama31_8b", 32, 128, 128, dict(mask="causal")),
         ("softmax_dsv2_lite", 16, 192, 128, dict(mask="causal")),
         ("softmax_difftr_3b", 12, 128, 256, dict(mask="causal")),
         ("sigmoid_llama3_8b", 32, 128, 128, dict(mask="causal", norm="sigmoid", score_mod="bias")),
         ("relu_vit_s16", 6, 64, 64, dict(norm="none", score_mod="relu")),
+        ("retention_parallel_retnet_6b7", 32, 256, 512, dict(mask="causal", score_mod="head_decay", norm="abssum", decay=True)),
     )
     out = []
     cid = 100

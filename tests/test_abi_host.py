@@ -39,6 +39,19 @@ def test_create_query_destroy_roundtrip():
     A.ae_attn_destroy(h)
     A.ae_attn_destroy(None)
     assert A.ae_attn_version() >= 1
+    # Table 2's retention head dims: 256 / 512 and 256 / 128, for the retention variants only
+    ret = dict(B=1, H_q=4, H_kv=4, L_q=100, L_k=100, D_qk=256, scale=0.1, score_mod="head_decay", gamma=[.9] * 4, mask="causal")
+    for dv in (128, 512):
+        h = A.ae_attn_create(**ret, D_v=dv, norm="abssum")
+        assert "256,128" in A.ae_attn_query(h)["kernel"]
+        A.ae_attn_destroy(h)
+    for bad in (dict(D_v=512, norm="abssum", kv_splits=4), dict(D_v=256, norm="abssum")):
+        with pytest.raises(A.AeAttnError) as ei:
+            A.ae_attn_create(**ret, **bad)
+        assert ei.value.status == A.AE_ERR_UNSUPPORTED
+    with pytest.raises(A.AeAttnError) as ei:     # softmax is not built at these head dims
+        A.ae_attn_create(B=1, H_q=4, H_kv=4, L_q=100, L_k=100, D_qk=256, D_v=512, scale=0.1)
+    assert ei.value.status == A.AE_ERR_UNSUPPORTED
 
 
 @pytest.mark.parametrize("patch,status", [

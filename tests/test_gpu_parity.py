@@ -92,6 +92,23 @@ def test_small_ragged_all_variants(A, dims, variant):
     check(got, ref, f"{variant} {dims}")
 
 
+@pytest.mark.parametrize("dv", [128, 512])
+@pytest.mark.parametrize("variant", ["retnet_abssum", "retnet_abs_of_sum", "decay_nonorm"])
+@pytest.mark.parametrize("Lq,Lk", [(300, 333), (1, 1), (513, 513), (700, 40)])
+def test_retention_head_dims_256(A, dv, variant, Lq, Lk):
+    """Table 2's "Retention Parallel" head dims, D_qk = 256 with D_v = 512 (four launches over 128 value columns
+    each) and D_v = 128 (one): ragged shapes, more queries than keys, grouped heads."""
+    kw = dict(VARIANTS[variant])
+    w = Workload(variant, 21, 2, 4, 2, Lq, Lk, 256, dv, **kw)
+    Q, K, V = make_inputs(w)
+    print(f"case {variant} 256/{dv} Lq {Lq} Lk {Lk}", flush=True)
+    got, ref = gpu_run(A, w, Q, K, V), oracle_run(w, Q, K, V)
+    if variant in ROW_SCALED:
+        rs = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)
+        got, ref = got / rs, ref / rs
+    check(got, ref, f"{variant} 256/{dv}")
+
+
 @pytest.mark.parametrize("Lq,Lk", [(1, 1), (1, 77), (77, 1), (64, 64), (257, 255), (40, 700), (700, 40), (513, 513)])
 @pytest.mark.parametrize("mask", ["none", "causal"])
 def test_shapes_softmax(A, Lq, Lk, mask):
@@ -189,7 +206,7 @@ def test_table2_shapes_sampled(A):
         h = int(rng.integers(w.H_q))
         rows = np.unique(np.concatenate([[0, 255, 256, w.L_q - 1], rng.integers(0, w.L_q, 40)])).astype(np.int64)
         ref = attention_head(Q[0, h], K[0, h], V[0, h], scale=w.scale_value, score_mod=w.score_mod, bias=w.bias,
-                             gamma_h=None, norm=w.norm, mask=w.oracle_mask(), rows=rows)
+                             gamma_h=None if w.gamma() is None else w.gamma()[h], norm=w.norm, mask=w.oracle_mask(), rows=rows)
         got = O[0, h].cpu().double().numpy()[rows]
         e = np.abs(got - ref) / np.maximum(1.0, np.abs(ref).max(axis=1, keepdims=True))
         assert e.max() <= MAX_ABS and e.mean() <= MEAN_ABS, (w.name, e.max(), e.mean())
