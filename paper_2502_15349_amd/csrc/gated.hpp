@@ -3,12 +3,14 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "attn_kernel.hpp"  // DecayTable
+
 namespace ae {
 struct GatedParams {
   const __bf16* Q;          // [B, H_qk, L, D_qk]
   const __bf16* K;          // [B, H_qk, L, D_qk]
   const __bf16* V;          // [B, H, L, D_v]
-  const float* log_decay;   // [B, H, L]: ln a_t <= 0
+  const float* log_decay;   // [B, H, L]: ln a_t <= 0; null: one constant decay per head, from the table passed beside
   const float* key_gate;    // [B, H, L] or null (ones)
   const float* h_in;        // [B, H, D_qk, D_v] fp32 or null (zero)
   float* h_out;             // the same layout, or null
@@ -18,5 +20,6 @@ struct GatedParams {
   int out_bf16;
 };
 bool gated_supported(int dqk, int dv);
-hipError_t launch_gated_recurrent(const GatedParams& p, int dqk, int dv, hipStream_t stream);
+// dt: log2 of the per-head decay, read only where p.log_decay is null
+hipError_t launch_gated_recurrent(const GatedParams& p, const DecayTable& dt, int dqk, int dv, hipStream_t stream);
 }  // namespace ae

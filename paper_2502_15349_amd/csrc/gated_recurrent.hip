@@ -65,7 +65,7 @@ __device__ __forceinline__ float dpp_f(float x) {
 }
 
 template <class C>
-__global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const GatedParams p) {
+__global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const GatedParams p, const DecayTable dt) {
   __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -78,7 +78,8 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   const __bf16* Qh = p.Q + ((int64_t)b * p.H_qk + hqk) * L * C::DQK;
   const __bf16* Kh = p.K + ((int64_t)b * p.H_qk + hqk) * L * C::DQK;
   const __bf16* Vh = p.V + (int64_t)bh * L * C::DV;
-  const float* lah = p.log_decay + (int64_t)bh * L;
+  const float* lah = p.log_decay ? p.log_decay + (int64_t)bh * L : nullptr;
+  const float la_const = lah ? 0.f : dt.log2_gamma[h] * 0.6931471805599453f;  // constant decay per head: ln gamma
   const float* gh = p.key_gate ? p.key_gate + (int64_t)bh * L : nullptr;
   const uint32_t gate0 = lds0 + 2 * C::STAGE_BYTES + wave * C::GATE_BYTES;  // this wave's b[64], g[64], w[64]
 
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     la = 0.f;
     g = 0.f;
     if (t < L) {
-      la = lah[t];
+      la = lah ? lah[t] : la_const;
       g = gh ? gh[t] : 1.f;
     }
   };
@@ -306,9 +307,9 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
 }
 
 template <int DQK, int DV, int HPW = 1>
-hipError_t launch(const GatedParams& p, hipStream_t s) {
+hipError_t launch(const GatedParams& p, const DecayTable& dt, hipStream_t s) {
   typedef GCfg<DQK, DV, HPW> C;
-  hipLaunchKernelGGL(gated_recurrent_kernel<C>, dim3((unsigned)(p.B * p.H / HPW)), dim3(C::THREADS), 0, s, p);
+  hipLaunchKernelGGL(gated_recurrent_kernel<C>, dim3((unsigned)(p.B * p.H / HPW)), dim3(C::THREADS), 0, s, p, dt);
   return hipGetLastError();
 }
 
@@ -316,17 +317,17 @@ hipError_t launch(const GatedParams& p, hipStream_t s) {
 
 bool gated_supported(int dqk, int dv) { return (dqk == 64 || dqk == 128) && (dv == 64 || dv == 128); }
 
-hipError_t launch_gated_recurrent(const GatedParams& p, int dqk, int dv, hipStream_t s) {
-  if (dqk == 64 && dv == 64) return launch<64, 64>(p, s);
+hipError_t launch_gated_recurrent(const GatedParams& p, const DecayTable& dt, int dqk, int dv, hipStream_t s) {
+  if (dqk == 64 && dv == 64) return launch<64, 64>(p, dt, s);
   if (dqk == 128 && dv == 64) {
     // value heads that share their q/k head (Mamba2's groups) share the Q and K tiles of a workgroup, up to four
     const int grp = p.H / p.H_qk;
-    if (grp % 4 == 0) return launch<128, 64, 4>(p, s);
-    if (grp % 2 == 0) return launch<128, 64, 2>(p, s);
-    return launch<128, 64>(p, s);
+    if (grp % 4 == 0) return launch<128, 64, 4>(p, dt, s);
+    if (grp % 2 == 0) return launch<128, 64, 2>(p, dt, s);
+    return launch<128, 64>(p, dt, s);
   }
-  if (dqk == 64 && dv == 128) return launch<64, 128>(p, s);
-  if (dqk == 128 && dv == 128) return launch<128, 128>(p, s);
+  if (dqk == 64 && dv == 128) return launch<64, 128>(p, dt, s);
+  if (dqk == 128 && dv == 128) return launch<128, 128>(p, dt, s);
   return hipErrorInvalidValue;
 }
 
