@@ -12,8 +12,12 @@
 //     H_new = e^{b_last} H + sum_j (e^{b_last - b_j} g_j) k_j^T v_j
 // Every exponent is <= 0: nothing overflows, nothing is divided by a decay.
 //
-// A wavefront owns 32 of the D_v output columns (D_v / 32 wavefronts per workgroup) and, for them, the state slab
-// [D_qk x 32] as D_qk / 32 accumulator tiles.  All products are transposed so that a lane owns one column -- a
+// A wavefront owns 32 of the D_v output columns and one of the chunk's two blocks of 32 queries (2 D_v / 32
+// wavefronts per head), and keeps, for its columns, the state slab [D_qk x 32] as D_qk / 32 accumulator tiles.  The
+// two wavefronts of a column block both hold the slab and both apply every update to it (the same instructions on
+// the same operands: the copies stay bit-identical): the path is bound by memory and by the latency chain of a
+// chunk, not by MFMAs, and two wavefronts per SIMD, each with half of the read-out, scores and aggregation, hide
+// each other's waits.  All products are transposed so that a lane owns one column -- a
 // query in S^T and O^T, a value column in H -- and the registers run over the contracted index:
 //     S^T [keys x queries]   = K Q^T          A: K rows, B: Q rows (16-byte row pieces in the d order below)
 //     R^T [v x queries]      = H^T Q^T        A: the state accumulators themselves, packed to bf16 (lane = value
@@ -25,8 +29,8 @@
 //                                                the per-token weights w_j = e^{b_last - b_j} g_j
 // The contraction order over d is free, so Q and K rows are read in the order the accumulator layout of H
 // dictates (register r of a tile is row 8 (r / 4) + 4 (lane / 32) + r % 4): two 8-byte pieces per fragment.
-// The three 32 x 32 blocks of S^T that the causal order inside a chunk leaves are computed by every wavefront
-// itself (cheaper than an exchange through LDS and a barrier: the path is bound by memory, not by the MFMAs).
+// Of the three 32 x 32 blocks of S^T that the causal order inside a chunk leaves, a wavefront computes those of
+// its query block itself (cheaper than an exchange through LDS and a barrier).
 // Q, K, V tiles arrive by LDS-DMA, double buffered, one barrier per chunk; the gates of the next chunk are
 // fetched a chunk ahead.  The output of a chunk is stored before the state update, whose MFMAs cover the stores.
 #include <hip/hip_runtime.h>
@@ -39,13 +43,20 @@ namespace {
 
 // HPW_: value heads per workgroup.  Heads of one q/k group (Mamba2: every head of a group reads the same B and C)
 // can share the Q and K tiles of a workgroup: HPW_ consecutive heads, each with its own V tile, gates and state.
-template <int DQK_, int DV_, int HPW_ = 1>
+// QS_: wavefronts per block of 32 value columns: 2 (one per query block of the chunk, see above) or 1 (both query
+// blocks in one wavefront: half the wavefronts, each with the whole register file where 2 would spill).
+template <int DQK_, int DV_, int HPW_ = 1, int QS_ = 2>
 struct GCfg {
-  static constexpr int DQK = DQK_, DV = DV_, HPW = HPW_, WPH = DV_ / 32, WAVES = HPW_ * WPH, THREADS = 64 * WAVES, CH = 64;
+  static constexpr int DQK = DQK_, DV = DV_, HPW = HPW_, QS = QS_, WPH = QS_ * (DV_ / 32), WAVES = HPW_ * WPH, THREADS = 64 * WAVES, CH = 64;
   static constexpr int RBQ = DQK * 2, RBV = DV * 2, CPRQ = DQK / 8, CPRV = DV / 8;
   static constexpr int Q_BYTES = CH * RBQ, V_BYTES = CH * RBV, STAGE_BYTES = 2 * Q_BYTES + HPW * V_BYTES;
-  static constexpr int GATE_BYTES = 3 * CH * 4;  // per wavefront: b, g, w of the chunk's tokens
-  static constexpr int LDS_BYTES = 2 * STAGE_BYTES + WAVES * GATE_BYTES;
+  static constexpr int STAGES = 3;                // chunk c is worked on while c + 1 and c + 2 are arriving
+  static constexpr int GATE_BYTES = 3 * CH * 4;   // per wavefront: b, g, w of the chunk's tokens
+  static constexpr int RAW_BYTES = 2 * CH * 4;    // per head and stage: the chunk's log-decays and key gates as they arrive
+  static constexpr int LDS_BYTES = STAGES * (STAGE_BYTES + HPW * RAW_BYTES) + WAVES * GATE_BYTES + 256;  // (+ a row nobody reads)
+  // copy instructions per wavefront and chunk: its shares of the Q, K and V tiles and one of the two gate rows
+  static constexpr int NDMA = 2 * (CPRQ / WAVES) + CPRV / WPH + 1;
+  static constexpr int NST = 4 * (3 - QS);        // store instructions per wavefront and (whole) chunk
   static constexpr int T = DQK / 16, DBQ = DQK / 32;
   static_assert(CPRQ % WAVES == 0 && CPRV % WPH == 0, "every wave copies the same number of 1 KB blocks");
   static_assert(LDS_BYTES <= 160 * 1024, "tiles do not fit LDS");
@@ -56,6 +67,19 @@ __device__ __forceinline__ u32x2 lds_read8(uint32_t addr) {
 }
 __device__ __forceinline__ void lds_write4(uint32_t addr, float v) {
   *reinterpret_cast<__attribute__((address_space(3))) float*>((lds_char*)(uintptr_t)addr) = v;
+}
+
+// 64 lanes x 4 bytes from base + byte_off (per lane) to LDS bytes [lds_addr, lds_addr + 256)
+__device__ __forceinline__ void dma4(const void* base_uniform, uint32_t byte_off, uint32_t lds_addr_uniform) {
+  base_uniform = uniform_ptr(base_uniform);
+  lds_addr_uniform = __builtin_amdgcn_readfirstlane(lds_addr_uniform);
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dword %1, %2"
+      :
+      : "s"(lds_addr_uniform), "v"(byte_off), "s"(base_uniform)
+      : "memory", "m0");
 }
 
 // x of the lane that the control word selects, 0 where it selects none or the masks switch the lane off
@@ -70,8 +94,9 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   const uint32_t lds0 = (uint32_t)(uintptr_t)((lds_char*)smem);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ln = lane & 31, half = lane >> 5;
-  // workgroup -> batch entry and HPW consecutive value heads of one q/k group; wave -> (head, 32 value columns)
-  const int hw = wave / C::WPH, vblk = wave % C::WPH;
+  // workgroup -> batch entry and HPW consecutive value heads of one q/k group; wave -> (head, 32 value columns,
+  // query block of the chunk)
+  const int hw = wave / C::WPH, wh = wave % C::WPH, vblk = wh / C::QS, ib = wh % C::QS;
   const int bh0 = blockIdx.x * C::HPW, b = bh0 / p.H, h = bh0 % p.H + hw, bh = bh0 + hw;
   const int hqk = h / (p.H / p.H_qk);
   const int64_t L = p.L;
@@ -81,7 +106,9 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   const float* lah = p.log_decay ? p.log_decay + (int64_t)bh * L : nullptr;
   const float la_const = lah ? 0.f : dt.log2_gamma[h] * 0.6931471805599453f;  // constant decay per head: ln gamma
   const float* gh = p.key_gate ? p.key_gate + (int64_t)bh * L : nullptr;
-  const uint32_t gate0 = lds0 + 2 * C::STAGE_BYTES + wave * C::GATE_BYTES;  // this wave's b[64], g[64], w[64]
+  const uint32_t raw0 = lds0 + C::STAGES * C::STAGE_BYTES + hw * C::RAW_BYTES;  // the head's raw gates, stage 0
+  const uint32_t gate0 = lds0 + C::STAGES * (C::STAGE_BYTES + C::HPW * C::RAW_BYTES) + wave * C::GATE_BYTES;  // this wave's b[64], g[64], w[64]
+  const uint32_t scrap0 = lds0 + C::LDS_BYTES - 256;
 
   // ---- the state slab of this wavefront: rows d, columns 32 * wave .. + 31 ----
   f32x16 H[C::DBQ];
@@ -94,35 +121,50 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     } else {
       H[db] = zero16();
     }
+    pin(H[db]);  // (the loads of the initial state are awaited here, not by a wait inside the loop)
   }
 
-  // ---- copies: chunk c -> stage c % 2 (rows past the end repeat the last row; their gates are zero) ----
+  // ---- copies: chunk c -> stage c % 3 ----
+  // Per copy instruction of this wave the lane's byte offset inside a chunk is fixed (row r of the tile, chunk slot
+  // with the tile's swizzle); the chunk's first row moves the wave-uniform base pointer.  The last chunk, if short,
+  // takes the offsets with its rows clamped to the last token (their gates are zero).
+  constexpr int NQ = C::CPRQ / C::WAVES, NV = C::CPRV / C::WPH;
+  uint32_t qoff[NQ], voff[NV];  // whole chunks: the lane's byte offsets from the chunk's first row (Q and K tiles alike)
+  auto lane_off = [&](auto cprc, int nb, int t0, bool whole) {
+    constexpr int CPR = decltype(cprc)::value;
+    const int pos = nb * 64 + lane, r = pos / CPR, pc = pos % CPR;
+    const int row = whole ? r : min(r, (int)L - 1 - t0);
+    return (uint32_t)((row * (CPR * 8) + ((pc ^ bswz<CPR>(r)) * 8)) * 2);
+  };
+#pragma unroll
+  for (int i = 0; i < NQ; ++i) qoff[i] = lane_off(std::integral_constant<int, C::CPRQ>{}, wave + i * C::WAVES, 0, true);
+#pragma unroll
+  for (int i = 0; i < NV; ++i) voff[i] = lane_off(std::integral_constant<int, C::CPRV>{}, wh + i * C::WPH, 0, true);
   auto issue_chunk = [&](int c) {
     const int t0 = c * C::CH;
-    const uint32_t base = lds0 + (c & 1) * C::STAGE_BYTES;
-    auto tile = [&](const __bf16* src, auto cprc, uint32_t dst, auto nwc, int w) {
-      constexpr int CPR = decltype(cprc)::value, NW = decltype(nwc)::value;  // copied by NW waves, this one being number w
+    const bool whole = t0 + C::CH <= L;
+    const uint32_t base = lds0 + (c % C::STAGES) * C::STAGE_BYTES;
+    const __bf16 *qc = Qh + (int64_t)t0 * C::DQK, *kc = Kh + (int64_t)t0 * C::DQK, *vc = Vh + (int64_t)t0 * C::DV;
 #pragma unroll
-      for (int i = 0; i < CPR / NW; ++i) {
-        const int nb = w + i * NW, pos = nb * 64 + lane;
-        const int r = pos / CPR, pc = pos % CPR;
-        const int row = min(t0 + r, (int)L - 1);
-        dma16(src, (uint32_t)((row * (CPR * 8) + ((pc ^ bswz<CPR>(r)) * 8)) * 2), dst + nb * 1024);
-      }
-    };
-    tile(Qh, std::integral_constant<int, C::CPRQ>{}, base, std::integral_constant<int, C::WAVES>{}, wave);
-    tile(Kh, std::integral_constant<int, C::CPRQ>{}, base + C::Q_BYTES, std::integral_constant<int, C::WAVES>{}, wave);
-    tile(Vh, std::integral_constant<int, C::CPRV>{}, base + 2 * C::Q_BYTES + hw * C::V_BYTES, std::integral_constant<int, C::WPH>{}, vblk);
-  };
-  // gates of chunk c for token lane: log-decay (0 past the end: the state is carried unchanged) and key gate (0 past the end)
-  auto load_gates = [&](int c, float& la, float& g) {
-    const int t = c * C::CH + lane;
-    la = 0.f;
-    g = 0.f;
-    if (t < L) {
-      la = lah ? lah[t] : la_const;
-      g = gh ? gh[t] : 1.f;
+    for (int i = 0; i < NQ; ++i) {
+      const int nb = wave + i * C::WAVES;
+      const uint32_t off = whole ? qoff[i] : lane_off(std::integral_constant<int, C::CPRQ>{}, nb, t0, false);
+      dma16(qc, off, base + nb * 1024);
+      dma16(kc, off, base + C::Q_BYTES + nb * 1024);
     }
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int nb = wh + i * C::WPH;
+      const uint32_t off = whole ? voff[i] : lane_off(std::integral_constant<int, C::CPRV>{}, nb, t0, false);
+      dma16(vc, off, base + 2 * C::Q_BYTES + hw * C::V_BYTES + nb * 1024);
+    }
+    // the head's gates, one token per lane: its first wave fetches the log-decays, its second the key gates; the
+    // others (and a row that does not exist: constant decay, no key gate) fetch a word they never look at, so that
+    // every wave issues the same number of copies
+    const float* grow = wh == 0 && lah ? lah : wh == 1 && gh ? gh : nullptr;
+    const uint32_t gdst = raw0 + (c % C::STAGES) * (C::HPW * C::RAW_BYTES) + (wh == 1 ? 256 : 0);
+    const uint32_t goff = grow ? (uint32_t)min(t0 + lane, (int)L - 1) * 4u : 0u;
+    dma4(grow ? (const void*)grow : (const void*)Qh, goff, grow ? gdst : scrap0);
   };
 
   // per-lane pieces of the fragment addresses (stage 0; see attn_bwd_kernel.hpp for the two read patterns of a tile)
@@ -145,20 +187,34 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   };
 
   const int n_chunks = (int)((L + C::CH - 1) / C::CH);
-  float la_next, g_next;
   issue_chunk(0);
-  load_gates(0, la_next, g_next);
+  if (n_chunks > 1) issue_chunk(1);
 
   for (int c = 0; c < n_chunks; ++c) {
     const int t0 = c * C::CH;
-    const uint32_t sb = lds0 + (c & 1) * C::STAGE_BYTES;
+    const uint32_t sb = lds0 + (c % C::STAGES) * C::STAGE_BYTES;
     const uint32_t qb = sb, kb_ = sb + C::Q_BYTES, vb_ = sb + 2 * C::Q_BYTES + hw * C::V_BYTES;
-    const float la = la_next, g = g_next;
-    // chunk c has landed (this wave's copies; the barrier: everybody's), and every wave is done with chunk c - 1
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    if (c + 1 < n_chunks) {
-      issue_chunk(c + 1);
-      load_gates(c + 1, la_next, g_next);
+    // Chunk c has landed: of this wave's memory operations only those issued after its copies may still be in
+    // flight -- the copies of chunk c + 1 (if there is one) and the stores of chunk c - 1 (if there was one; it was
+    // a whole chunk: four stores).  The counter runs in issue order.  Then the barrier: everybody's copies have
+    // landed and every wave is done with chunk c - 1, whose stage chunk c + 2 may now overwrite.
+    {
+      const bool nxt = c + 1 < n_chunks, prv = c > 0;
+      if (nxt && prv) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NDMA + C::NST) : "memory");
+      else if (nxt) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NDMA) : "memory");
+      else if (prv) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NST) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      asm volatile("s_barrier" ::: "memory");
+    }
+    if (c + 2 < n_chunks) issue_chunk(c + 2);
+    // gates of this lane's token: log-decay (0 past the end: the state is carried unchanged; at least -20: a token
+    // that lets less than e^-20 through lets nothing through at the precision of the path, and the bound keeps the
+    // factorised weights below in range) and key gate (0 past the end)
+    float la = 0.f, g = 0.f;
+    if (t0 + lane < L) {
+      const uint32_t raw = raw0 + (c % C::STAGES) * (C::HPW * C::RAW_BYTES) + lane * 4;
+      la = lah ? fmaxf(*reinterpret_cast<__attribute__((address_space(3))) const float*>((lds_char*)(uintptr_t)raw), -20.f) : la_const;
+      g = gh ? *reinterpret_cast<__attribute__((address_space(3))) const float*>((lds_char*)(uintptr_t)(raw + 256)) : 1.f;
     }
 
     // ---- gates: b = inclusive prefix sum of the log-decays over the chunk's 64 tokens (lane = token) ----
@@ -171,21 +227,30 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     bcum += dpp_f<0x142, 0xa, 0xf>(bcum);
     bcum += dpp_f<0x143, 0xc, 0xf>(bcum);
     const float b_last = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bcum), 63));
-    lds_write4(gate0 + lane * 4, bcum);
-    lds_write4(gate0 + 256 + lane * 4, g);
-    lds_write4(gate0 + 512 + lane * 4, __expf(b_last - bcum) * g);
-    float bi0, bi1;  // of this lane's two queries: tokens ln and 32 + ln
+    // Weights inside the chunk, factorised per group of four tokens: with ref_j the sum in front of token j's group
+    // (ref_j >= b_i for every i in or behind the group),  e^{b_i - b_j} g_j = e^{b_i - ref_j} * u_j,
+    // u_j = g_j e^{ref_j - b_j}: one exponential per token here and four per lane and block of keys below instead of
+    // one per score.  ref_j - b_j is at most four log-decays: with the bound of 20 above u_j stays finite.
+    {
+      const float ref = dpp_f<0x00, 0xf, 0xf>(bcum - la);  // the sum in front of lane (lane & ~3): quad broadcast of the exclusive sum
+      lds_write4(gate0 + lane * 4, ref);
+      lds_write4(gate0 + 256 + lane * 4, g * __expf(ref - bcum));
+      lds_write4(gate0 + 512 + lane * 4, g * __expf(b_last - bcum));
+    }
+    float bi0, bi1;  // b of tokens ln and 32 + ln
     swap_halves(bcum, bi0, bi1);
-
-    // ---- Q fragments of both query blocks (B operands of S^T and of the read-out) ----
-    bf16x8 qf[2][C::T];
+    bf16x8 vf[4];  // the V fragments of the chunk's four 16-token steps (this wave's 32 value columns)
+    // The wave's query block as a compile-time constant (register arrays indexed by it stay in registers).
+    auto query_block = [&](auto ibc) {
+    constexpr int IB = decltype(ibc)::value;
+    const float bi = IB ? bi1 : bi0;  // of this lane's query: token 32 IB + ln of the chunk
+    // ---- Q fragments of the wave's query block (B operands of S^T and of the read-out) ----
+    bf16x8 qf[C::T];
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib)
-#pragma unroll
-      for (int t = 0; t < C::T; ++t) qf[ib][t] = row_frag(qb, 32 * ib, t);
+    for (int t = 0; t < C::T; ++t) qf[t] = row_frag(qb, 32 * IB, t);
 
     // ---- read-out of the state in front of the chunk: O^T = H^T Q^T, times scale e^{b_i} ----
-    f32x16 o[2] = {zero16(), zero16()};
+    f32x16 o = zero16();
 #pragma unroll
     for (int db = 0; db < C::DBQ; ++db)
 #pragma unroll
@@ -193,40 +258,33 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
         bf16x8 hfrag;
 #pragma unroll
         for (int e = 0; e < 8; ++e) hfrag[e] = (__bf16)H[db][8 * tt + e];
-        o[0] = mfma(hfrag, qf[0][2 * db + tt], o[0]);
-        o[1] = mfma(hfrag, qf[1][2 * db + tt], o[1]);
+        o = mfma(hfrag, qf[2 * db + tt], o);
       }
     {
-      const float f0 = p.scale * __expf(bi0), f1 = p.scale * __expf(bi1);
+      const float f = p.scale * __expf(bi);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        o[0][r] *= f0;
-        o[1][r] *= f1;
-      }
+      for (int r = 0; r < 16; ++r) o[r] *= f;
     }
 
-    // ---- scores inside the chunk: S^T blocks (keys 0-31 | queries 0-31), (0-31 | 32-63), (32-63 | 32-63) ----
-    f32x16 s00 = zero16(), s01 = zero16(), s11 = zero16();
+    // weights of one S^T block: scale e^{b_i - b_j} g_j s for key j <= query i (positions inside the chunk), else 0
+    auto weigh = [&](const f32x16& s, int kblk, bool diag, u32x4 (&pk)[2]) {
+      float ref[4];
+      f32x4 uj[4];
 #pragma unroll
-    for (int t = 0; t < C::T; ++t) {
-      const bf16x8 k0 = row_frag(kb_, 0, t), k1 = row_frag(kb_, 32, t);
-      s00 = mfma(k0, qf[0][t], s00);
-      s01 = mfma(k0, qf[1][t], s01);
-      s11 = mfma(k1, qf[1][t], s11);
-    }
-    // weights: scale e^{b_i - b_j} g_j s for key j <= query i (positions inside the chunk), else 0
-    u32x4 p00[2], p01[2], p11[2];
-    auto weigh = [&](const f32x16& s, int kblk, float bi, int iq, bool diag, u32x4 (&pk)[2]) {
+      for (int a = 0; a < 4; ++a) {  // (all eight reads first: one LDS latency for the block, not four)
+        const uint32_t off = (32 * kblk + 8 * a + 4 * half) * 4;
+        ref[a] = *reinterpret_cast<__attribute__((address_space(3))) const float*>((lds_char*)(uintptr_t)(gate0 + off));
+        uj[a] = lds_read16(gate0 + 256 + off);
+      }
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
-        const uint32_t off = (32 * kblk + 8 * a + 4 * half) * 4;
-        const f32x4 bj = lds_read16(gate0 + off), gj = lds_read16(gate0 + 256 + off);
+        // (groups past the lane's query have bi > ref: whatever the factor becomes there, the mask below discards it)
+        const float qfac = p.scale * __expf(bi - ref[a]);
         float x[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int j = 32 * kblk + 8 * a + 4 * half + e;
-          x[e] = s[4 * a + e] * (p.scale * gj[e]) * __expf(bi - bj[e]);
-          if (diag && j > iq) x[e] = 0.f;
+          x[e] = s[4 * a + e] * (qfac * uj[a][e]);
+          if (diag && 8 * a + 4 * half + e > ln) x[e] = 0.f;
         }
         bf16x2 lo, hi;
         lo[0] = (__bf16)x[0];
@@ -237,41 +295,57 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
         pk[a / 2][2 * (a % 2) + 1] = __builtin_bit_cast(uint32_t, hi);
       }
     };
-    weigh(s00, 0, bi0, ln, true, p00);
-    weigh(s01, 0, bi1, 32 + ln, false, p01);
-    weigh(s11, 1, bi1, 32 + ln, true, p11);
-
-    // ---- aggregation inside the chunk: O^T += V^T P^T (this wave's 32 value columns) ----
-    bf16x8 vf[4];
+    // ---- scores and aggregation inside the chunk: the diagonal block of the wave's queries, and for the second
+    //      query block also the block below the diagonal (keys 0-31) ----
+    {
+      f32x16 sd = zero16();
 #pragma unroll
-    for (int s = 0; s < 4; ++s) vf[s] = tr_frag(vb_, std::integral_constant<int, C::CPRV>{}, vblk, s);
-    o[0] = mfma(vf[0], __builtin_bit_cast(bf16x8, p00[0]), o[0]);
-    o[0] = mfma(vf[1], __builtin_bit_cast(bf16x8, p00[1]), o[0]);
-    o[1] = mfma(vf[0], __builtin_bit_cast(bf16x8, p01[0]), o[1]);
-    o[1] = mfma(vf[1], __builtin_bit_cast(bf16x8, p01[1]), o[1]);
-    o[1] = mfma(vf[2], __builtin_bit_cast(bf16x8, p11[0]), o[1]);
-    o[1] = mfma(vf[3], __builtin_bit_cast(bf16x8, p11[1]), o[1]);
+      for (int t = 0; t < C::T; ++t) sd = mfma(row_frag(kb_, 32 * IB, t), qf[t], sd);
+      u32x4 pd[2];
+      weigh(sd, IB, true, pd);
+      // the V fragments of the chunk's four 16-token steps (this wave's 32 value columns): A operands of the
+      // aggregation and, weighted, B operands of the state update
+      if constexpr (IB == 0 || C::QS == 2) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) vf[s] = tr_frag(vb_, std::integral_constant<int, C::CPRV>{}, vblk, s);
+      }
+      o = mfma(vf[2 * IB], __builtin_bit_cast(bf16x8, pd[0]), o);
+      o = mfma(vf[2 * IB + 1], __builtin_bit_cast(bf16x8, pd[1]), o);
+    }
+    if constexpr (IB == 1) {
+      f32x16 sl = zero16();
+#pragma unroll
+      for (int t = 0; t < C::T; ++t) sl = mfma(row_frag(kb_, 0, t), qf[t], sl);
+      u32x4 pl[2];
+      weigh(sl, 0, false, pl);
+      o = mfma(vf[0], __builtin_bit_cast(bf16x8, pl[0]), o);
+      o = mfma(vf[1], __builtin_bit_cast(bf16x8, pl[1]), o);
+    }
 
     // ---- store: lane = query row, four 16-byte pieces of the wave's 32 columns ----
-#pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
-      const int64_t i = t0 + 32 * ib + ln;
+    {
+      const int64_t i = t0 + 32 * IB + ln;
       if (i < L) {
         const int64_t e0 = ((int64_t)bh * L + i) * C::DV + 32 * vblk + 4 * half;
+        if (p.out_bf16) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          const f32x4 v = {o[ib][4 * a], o[ib][4 * a + 1], o[ib][4 * a + 2], o[ib][4 * a + 3]};
-          if (p.out_bf16) {
+          for (int a = 0; a < 4; ++a) {
             bf16x4 hv;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) hv[e] = (__bf16)v[e];
+            for (int e = 0; e < 4; ++e) hv[e] = (__bf16)o[4 * a + e];
             *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.O) + e0 + 8 * a) = hv;
-          } else {
-            *reinterpret_cast<f32x4*>(static_cast<float*>(p.O) + e0 + 8 * a) = v;
           }
+        } else {
+#pragma unroll
+          for (int a = 0; a < 4; ++a)
+            *reinterpret_cast<f32x4*>(static_cast<float*>(p.O) + e0 + 8 * a) = (f32x4){o[4 * a], o[4 * a + 1], o[4 * a + 2], o[4 * a + 3]};
         }
       }
     }
+
+    };
+    if (C::QS == 1 || ib == 0) query_block(std::integral_constant<int, 0>{});
+    if (C::QS == 1 || ib == 1) query_block(std::integral_constant<int, 1>{});
 
     // ---- state update: H = e^{b_last} H + K^T (w . V) ----
     {
@@ -281,15 +355,20 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
 #pragma unroll
         for (int r = 0; r < 16; ++r) H[db][r] *= dec;
     }
+    f32x4 wv[8];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      wv[2 * s] = lds_read16(gate0 + 512 + (16 * s + 4 * half) * 4);
+      wv[2 * s + 1] = lds_read16(gate0 + 512 + (16 * s + 8 + 4 * half) * 4);
+    }
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       // the V fragment of token step s times the tokens' weights (element e of the fragment: token 16 s + 8 (e / 4) + 4 half + e % 4)
-      const f32x4 w0 = lds_read16(gate0 + 512 + (16 * s + 4 * half) * 4), w1 = lds_read16(gate0 + 512 + (16 * s + 8 + 4 * half) * 4);
       bf16x8 vw;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        vw[e] = (__bf16)((float)vf[s][e] * w0[e]);
-        vw[4 + e] = (__bf16)((float)vf[s][4 + e] * w1[e]);
+        vw[e] = (__bf16)((float)vf[s][e] * wv[2 * s][e]);
+        vw[4 + e] = (__bf16)((float)vf[s][4 + e] * wv[2 * s + 1][e]);
       }
 #pragma unroll
       for (int db = 0; db < C::DBQ; ++db)
@@ -297,7 +376,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     }
   }
 
-  if (p.h_out) {
+  if (p.h_out && ib == 0) {  // (the slab's other copy is identical)
     float* dst = p.h_out + (int64_t)bh * C::DQK * C::DV + 32 * vblk + ln;
 #pragma unroll
     for (int db = 0; db < C::DBQ; ++db)
@@ -306,9 +385,9 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   }
 }
 
-template <int DQK, int DV, int HPW = 1>
+template <int DQK, int DV, int HPW = 1, int QS = 2>
 hipError_t launch(const GatedParams& p, const DecayTable& dt, hipStream_t s) {
-  typedef GCfg<DQK, DV, HPW> C;
+  typedef GCfg<DQK, DV, HPW, QS> C;
   hipLaunchKernelGGL(gated_recurrent_kernel<C>, dim3((unsigned)(p.B * p.H / HPW)), dim3(C::THREADS), 0, s, p, dt);
   return hipGetLastError();
 }
@@ -320,14 +399,13 @@ bool gated_supported(int dqk, int dv) { return (dqk == 64 || dqk == 128) && (dv 
 hipError_t launch_gated_recurrent(const GatedParams& p, const DecayTable& dt, int dqk, int dv, hipStream_t s) {
   if (dqk == 64 && dv == 64) return launch<64, 64>(p, dt, s);
   if (dqk == 128 && dv == 64) {
-    // value heads that share their q/k head (Mamba2's groups) share the Q and K tiles of a workgroup, up to four
+    // value heads that share their q/k head (Mamba2's groups) share the Q and K tiles of a workgroup, two at a time
     const int grp = p.H / p.H_qk;
-    if (grp % 4 == 0) return launch<128, 64, 4>(p, dt, s);
-    if (grp % 2 == 0) return launch<128, 64, 2>(p, dt, s);
+    if (grp % 2 == 0) return launch<128, 64, 2, 1>(p, dt, s);
     return launch<128, 64>(p, dt, s);
   }
   if (dqk == 64 && dv == 128) return launch<64, 128>(p, dt, s);
-  if (dqk == 128 && dv == 128) return launch<128, 128>(p, dt, s);
+  if (dqk == 128 && dv == 128) return launch<128, 128, 1, 1>(p, dt, s);
   return hipErrorInvalidValue;
 }
 
