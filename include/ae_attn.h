@@ -133,7 +133,10 @@ typedef struct {
  * static stand-in for the enumerate-and-profile tile scheduling of Section 4.3
  * (Algorithm 1).  Validates the descriptor, picks the kernel and its tile shape
  * for (D_qk, D_v, mask, norm, score_mod) and returns a handle in *out.  Touches
- * no device.  Supported head dims (D_qk/D_v): 64/64, 128/128, 128/256, 192/128.
+ * no device.  Supported head dims (D_qk/D_v): 64/64, 128/128, 128/256, 192/128;
+ * and, for the retention variants only (HEAD_DECAY with ABSSUM, ABS_OF_SUM or
+ * NONE, CAUSAL; Table 2, "Retention Parallel"): 256/128 and 256/512, the latter
+ * evaluated as four launches over 128 value columns each (no split keys).
  * Supported (score_mod, norm) pairs: NONE or BIAS with every norm;
  * HEAD_DECAY with ABSSUM, ABS_OF_SUM or NONE (CAUSAL mask only); RELU with NONE.
  * AE_MASK_SLIDING_WINDOW: score_mod NONE or BIAS with SOFTMAX, SIGMOID or NONE.
@@ -322,6 +325,11 @@ int32_t ae_attn_version(void);
  * leaves the state in front of each (bf16, [D_qk x D_v]); the parallel-pattern
  * kernel then starts every chunk's rows from the read-out of that state and
  * walks the chunk's own keys on top of it.  The work grows linearly with L.
+ * Where B x H is at least 192 the call runs instead as ONE kernel that walks the
+ * chunks of a (batch, head) in order with the state on chip (the kernel behind
+ * ae_gated_forward, with the head's constant decay): same result up to rounding
+ * order, Q, K, V read once; the workspace is then not touched (but must still
+ * be passed: the choice is the library's).
  *
  * Layouts: Q, K [B, H, L, D_qk] and V [B, H, L, D_v] bf16, O [B, H, L, D_v]
  * fp32 (or bf16, desc.out_dtype), all contiguous, device memory, 16-byte aligned; the caller owns them.

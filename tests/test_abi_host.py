@@ -371,3 +371,36 @@ def test_recurrent_descriptor_and_entry_point_checks():
         with pytest.raises(A.AeAttnError) as ei:
             A.ae_recurrent_create(**dict(ok, **patch))
         assert ei.value.status == status, (patch, A.ae_attn_last_error())
+
+
+def test_gated_descriptor_and_entry_point_checks():
+    """ae_gated_*: every descriptor and pointer check answers with a status before anything is launched."""
+    from paper_2502_15349_amd import ae_attn as A
+    ok = dict(B=2, H=8, H_qk=2, L=300, D_qk=128, D_v=64, scale=0.1)
+    h = A.ae_gated_create(**ok)
+    try:
+        # Q K V log_decay key_gate h_in O h_out
+        q, k, v, la, kg, hin, o, hout = (i << 20 for i in range(1, 9))
+        for args in ((0, k, v, la, kg, hin, o, hout), (q, k, v, 0, kg, hin, o, hout), (q, k, v, la, kg, hin, 0, hout),
+                     (q + 8, k, v, la, 0, 0, o, 0),            # misaligned Q
+                     (q, k, v, la + 2, 0, 0, o, 0),            # misaligned gate
+                     (q, k, v, la, 0, hin + 4, o, 0),          # misaligned state
+                     (q, k, v, la, 0, 0, q, 0),                # O aliases Q
+                     (q, k, v, la, kg, 0, o, kg),              # h_out aliases an input
+                     (q, k, v, la, 0, 0, o, o)):               # h_out aliases O
+            with pytest.raises(A.AeAttnError) as ei:
+                A.ae_gated_forward(h, *args)
+            assert ei.value.status == A.AE_ERR_INVALID_ARG, (args, A.ae_attn_last_error())
+        with pytest.raises(A.AeAttnError):
+            A.ae_gated_forward(None, q, k, v, la, 0, 0, o, 0)
+    finally:
+        A.ae_gated_destroy(h)
+    A.ae_gated_destroy(None)
+    for patch, status in ((dict(D_qk=192), A.AE_ERR_UNSUPPORTED), (dict(D_v=256), A.AE_ERR_UNSUPPORTED),
+                          (dict(H_qk=3), A.AE_ERR_INVALID_ARG), (dict(H_qk=0), A.AE_ERR_INVALID_ARG), (dict(L=0), A.AE_ERR_INVALID_ARG),
+                          (dict(B=0), A.AE_ERR_INVALID_ARG), (dict(scale=0.0), A.AE_ERR_INVALID_ARG),
+                          (dict(scale=float("inf")), A.AE_ERR_INVALID_ARG), (dict(out_dtype=9), A.AE_ERR_INVALID_ARG),
+                          (dict(L=1 << 30), A.AE_ERR_UNSUPPORTED)):
+        with pytest.raises(A.AeAttnError) as ei:
+            A.ae_gated_create(**dict(ok, **patch))
+        assert ei.value.status == status, (patch, A.ae_attn_last_error())

@@ -96,14 +96,18 @@ def test_sequence_in_pieces_with_carried_state(A):
 
 def test_strong_decay_and_no_decay(A):
     # a_t down to e^-8 per token (the chunk's cumulative exponents reach -500: weights underflow to zero, nothing
-    # overflows) and a_t = 1 throughout (a plain prefix sum: outputs grow with the position)
-    w = Workload("dec", 813, 1, 2, 2, 260, 260, 64, 64)
+    # overflows), a_t = 1 throughout (a plain prefix sum: outputs grow with the position), and a slow decay broken by
+    # single tokens of e^-30 (beyond the -20 at which the kernel clamps a token's log-decay inside a chunk: what came
+    # before such a token is gone to fp32 resolution either way)
+    w = Workload("dec", 813, 1, 3, 3, 260, 260, 64, 64)
     Q, K, V = make_inputs(w)
-    la = torch.full((1, 2, 260), -8.0)
+    la = torch.full((1, 3, 260), -8.0)
     la[:, 1] = 0.0
+    la[:, 2] = -0.01
+    la[:, 2, 5::37] = -30.0
     got = run(A, Q, K, V, la, None, 0.125)
     ref = oracle_gated(Q.float().numpy(), K.float().numpy(), V.float().numpy(), la.numpy(), None, scale=0.125)
-    check(got.cpu().double().numpy(), ref, "decay e^-8 / none")
+    check(got.cpu().double().numpy(), ref, "decay e^-8 / none / resets")
 
 
 def test_sampled_heads_at_benchmark_size(A):
