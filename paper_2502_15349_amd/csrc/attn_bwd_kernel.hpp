@@ -69,6 +69,9 @@ struct BwdParams {
   // the handle has a per-head decay: only then is the decay table read (it holds AE_MAX_DECAY_HEADS entries, and
   // handles without decay may have more heads than that)
   int has_decay;
+  // (batch, k/v head) groups that one XCD walks together, per kernel ([0]: query side, [1]: key side); see the
+  // mapping at the top of attn_bwd_kernel
+  int together[2];
 };
 
 // Chunk swizzle of the backward tiles.  A tile row is read both ways -- 128-bit row
@@ -151,11 +154,21 @@ __global__ __launch_bounds__(C::THREADS, C::OCC2 ? 2 : 1) void attn_bwd_kernel(c
   // ---- which rows this workgroup owns ----------------------------------------------
   const int n_heads = C::KV_SIDE ? p.H_kv : p.H_q;
   const int n_own_tiles = (L_own + C::OWN - 1) / C::OWN;
-  const int bh = blockIdx.x % (p.B * n_heads);
-  int ot = blockIdx.x / (p.B * n_heads);        // causal: the workgroups with most work first
-  if (!C::KV_SIDE) ot = n_own_tiles - 1 - ot;
-  const int b = bh / n_heads, ho = bh % n_heads;  // ho: k/v head (key side) or q head (query side)
-  const int hk = C::KV_SIDE ? ho : ho / p.g;
+  // Workgroups are dealt to the 8 XCDs round-robin, and each XCD has its own L2.  All workgroups of one (batch,
+  // k/v head) group -- its own tiles, times the q heads of the group on the query side -- go to one XCD and run
+  // there at the same time, `together` groups side by side: they stream the same rows of the other side a few
+  // tiles apart, so a tile that one of them pulled into L2 serves the others.  Within a set of groups the
+  // workgroups with most work come first (causal).  The grid is padded to whole sets; the surplus exits here.
+  const int n_groups = p.B * p.H_kv;
+  const int per_group = C::KV_SIDE ? n_own_tiles : n_own_tiles * p.g;
+  const int tg = p.together[C::KV_SIDE ? 1 : 0];
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int set = slot / (tg * per_group), within = slot % (tg * per_group);
+  const int item = within / tg, group = (set * tg + within % tg) * 8 + xcd;
+  if (group >= n_groups) return;
+  const int b = group / p.H_kv, hk = group % p.H_kv;
+  int ot = C::KV_SIDE ? item : n_own_tiles - 1 - item / p.g;
+  const int ho = C::KV_SIDE ? hk : hk * p.g + item % p.g;  // ho: k/v head (key side) or q head (query side)
   const int own0 = ot * C::OWN, ow0 = own0 + wave * 32;  // first own row of the workgroup / of this wave
   const int own = ow0 + ln;                              // this lane's own row (column of S, dP, G^T)
   const int own_c = own < L_own ? own : L_own - 1;

@@ -9,8 +9,13 @@ namespace {
 template <int DQK, int DV, int NORM, bool CAUSAL, int OUT, bool BIAS>
 hipError_t launch_one(const BwdParams& p, const DecayTable& dt, hipStream_t s) {
   typedef BwdCfg<DQK, DV, NORM, CAUSAL, OUT, BIAS> C;
-  const int heads = C::KV_SIDE ? p.H_kv : p.H_q, L = C::KV_SIDE ? p.L_k : p.L_q;
-  hipLaunchKernelGGL(attn_bwd_kernel<C>, dim3((unsigned)(p.B * heads * ((L + C::OWN - 1) / C::OWN))), dim3(C::THREADS), 0, s, p, dt);
+  // whole sets of `together` groups per XCD (the kernel's mapping): sets x together x 8 XCDs x workgroups per group
+  const int L = C::KV_SIDE ? p.L_k : p.L_q;
+  const int64_t per_group = (int64_t)((L + C::OWN - 1) / C::OWN) * (C::KV_SIDE ? 1 : p.g);
+  const int64_t rounds = ((int64_t)p.B * p.H_kv + 7) / 8, tg = p.together[C::KV_SIDE ? 1 : 0];
+  const int64_t grid = ((rounds + tg - 1) / tg) * tg * 8 * per_group;
+  if (tg < 1 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(attn_bwd_kernel<C>, dim3((unsigned)grid), dim3(C::THREADS), 0, s, p, dt);
   return hipGetLastError();
 }
 
