@@ -619,8 +619,33 @@ def main():
                 A.ae_gated_forward(*args)
             e1.record(st)
             torch.cuda.synchronize()
-            A.ae_gated_destroy(h)
             ms = e0.elapsed_time(e1) / a.steps
+            # the backward pass (ae_gated_backward: dQ, dK, dV, dlog_decay, dkey_gate), same handle; compulsory bytes:
+            # Q, K, V, dO and the gates read once, the gradients (fp32) written once
+            from paper_2502_15349_amd.workloads import make_grad
+            dO = make_grad(Workload("v", cid, B, H, H, L, L, Dv, Dv)).to(dev)
+            f32 = dict(dtype=torch.float32, device=dev)
+            dQ, dK, dV = torch.empty(Q.shape, **f32), torch.empty(K.shape, **f32), torch.empty(V.shape, **f32)
+            dla = torch.empty((B, H, L), **f32)
+            dkg = None if kg is None else torch.empty((B, H, L), **f32)
+            nws = A.ae_gated_backward_workspace_bytes(h)
+            ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+            bargs = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), la.data_ptr(), 0 if kg is None else kg.data_ptr(), dO.data_ptr(),
+                     dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), dla.data_ptr(), 0 if dkg is None else dkg.data_ptr(), ws.data_ptr(),
+                     nws, st.cuda_stream)
+            for _ in range(2):
+                A.ae_gated_backward(*bargs)
+            torch.cuda.synchronize()
+            e0.record(st)
+            for _ in range(a.steps):
+                A.ae_gated_backward(*bargs)
+            e1.record(st)
+            torch.cuda.synchronize()
+            bwd_ms = e0.elapsed_time(e1) / a.steps
+            ngate = 2 if kg is not None else 1
+            bwd_byts = B * L * (Hqk * Dq * (2 * 2 + 2 * 4) + H * Dv * (2 + 2 + 4) + H * 8 * ngate)
+            del dO, dQ, dK, dV, dla, dkg, ws
+            A.ae_gated_destroy(h)
             b_s, h_s = B - 1, H // 2
             g_s = h_s // (H // Hqk)
             ref = gated_recurrent_head(Qc[b_s, g_s].float().numpy(), Kc[b_s, g_s].float().numpy(), Vc[b_s, h_s].float().numpy(),
@@ -632,9 +657,12 @@ def main():
             rows.append({"workload": name, "B": B, "H": H, "H_qk": Hqk, "L": L, "D_qk": Dq, "D_v": Dv, "ms": round(ms, 4),
                          "tokens_per_s": round(B * L / ms * 1e3, 1), "GBps": round(byts / ms / 1e6, 1),
                          "frac_of_hbm_peak": round(byts / ms / 1e6 / 8000.0, 4), "recurrence_tflops": round(flop / ms / 1e9, 1),
-                         "compulsory_bytes": byts, "parity_max_abs": err})
+                         "compulsory_bytes": byts, "parity_max_abs": err, "backward_ms": round(bwd_ms, 4),
+                         "backward_GBps": round(bwd_byts / bwd_ms / 1e6, 1), "backward_frac_of_hbm_peak": round(bwd_byts / bwd_ms / 1e6 / 8000.0, 4),
+                         "backward_compulsory_bytes": bwd_byts})
             print(f"# {name:40s} {ms:8.4f} ms = {byts / ms / 1e6:7.1f} GB/s ({100 * byts / ms / 1e6 / 8000.0:4.1f} % of HBM peak), "
-                  f"{flop / ms / 1e9:6.1f} TFLOP/s of recurrence, max_abs {err:.2e}", file=sys.stderr, flush=True)
+                  f"{flop / ms / 1e9:6.1f} TFLOP/s of recurrence, max_abs {err:.2e} | backward {bwd_ms:8.4f} ms = "
+                  f"{bwd_byts / bwd_ms / 1e6:7.1f} GB/s ({100 * bwd_byts / bwd_ms / 1e6 / 8000.0:4.1f} %)", file=sys.stderr, flush=True)
             del Q, K, V, O, la, kg
         print(json.dumps({"gated_recurrent": rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16", "data": "synthetic"}))
         return

@@ -419,6 +419,44 @@ ae_status_t ae_gated_create(const ae_gated_desc_t *desc, ae_gated_t **out);
 ae_status_t ae_gated_forward(const ae_gated_t *h, const void *Q, const void *K, const void *V,
                              const void *log_decay, const void *key_gate, const void *h_in,
                              void *O, void *h_out, hipStream_t stream);
+
+/* Backward pass of the recurrence above: the paper evaluates the recurrent
+ * pattern forward and backward (Section 6.1; Table 2) and takes the backward
+ * graph from automatic differentiation of the forward one (Section 5.1); here
+ * the chain rule is written out.  With A_ij the product of the decays a_t of
+ * the tokens j < t <= i, and for an upstream gradient dO of the outputs (the
+ * state in front of the first token is zero, no gradient enters the final
+ * state):
+ *     dq_i = scale sum_{j <= i} A_ij g_j (dO_i . v_j) k_j
+ *     dk_j = g_j x_j,  x_j = scale sum_{i >= j} A_ij (dO_i . v_j) q_i,   dkey_gate_j = k_j . x_j
+ *     dv_j = g_j scale sum_{i >= j} A_ij (q_i . k_j) dO_i
+ *     dlog_decay_t = sum_{i >= t} (q_i . dq_i - k_i . dk_i)
+ * (the last line because the cumulative log-decay B_i enters weight (i, j) as
+ * exp(B_i - B_j) and the sums are linear in q_i and in k_j).  Each of the first
+ * three sums is the forward recurrence on other operands -- queries dO, keys V,
+ * values K; and, walking the tokens backwards, queries V, keys dO, values Q;
+ * queries K, keys Q, values dO -- so the forward kernel computes them, chunk by
+ * chunk with the state on chip; two small kernels form the dot products, the
+ * sums over the value heads of a q/k head, and the suffix sums.
+ *
+ *   Q, K, V, log_decay, key_gate   as in ae_gated_forward;
+ *   dO         device, bf16, contiguous [B, H, L, D_v];
+ *   dQ, dK     device, fp32, contiguous [B, H_qk, L, D_qk] (summed over the value
+ *              heads of each q/k head);  dV  device, fp32, contiguous [B, H, L, D_v];
+ *   dlog_decay device, fp32 [B, H, L];  dkey_gate the same, required exactly when
+ *              key_gate is given, else NULL;
+ *   workspace  device, 256-byte aligned, ae_gated_backward_workspace_bytes: 4 B per
+ *              (batch, head, token), plus 8 D_qk B per (batch, head, token) when
+ *              H_qk < H.  Owned by the caller; calls sharing it must not overlap.
+ * Tensors 16-byte aligned, gates and their gradients 4-byte; outputs must alias
+ * neither inputs nor each other.  Uses B, H, H_qk, L, the head dims and scale of
+ * the handle (out_dtype plays no part: gradients are fp32).  Five launches on
+ * `stream`, no allocation, no wait.  Errors as ae_gated_forward.                */
+ae_status_t ae_gated_backward_workspace_bytes(const ae_gated_t *h, size_t *bytes);
+ae_status_t ae_gated_backward(const ae_gated_t *h, const void *Q, const void *K, const void *V,
+                              const void *log_decay, const void *key_gate, const void *dO,
+                              void *dQ, void *dK, void *dV, void *dlog_decay, void *dkey_gate,
+                              void *workspace, size_t workspace_bytes, hipStream_t stream);
 ae_status_t ae_gated_destroy(ae_gated_t *h); /* NULL is allowed */
 
 #ifdef __cplusplus

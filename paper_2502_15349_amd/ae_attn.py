@@ -438,6 +438,10 @@ _lib.ae_gated_forward.argtypes = [C.c_void_p] * 10
 _lib.ae_gated_forward.restype = C.c_int
 _lib.ae_gated_destroy.argtypes = [C.c_void_p]
 _lib.ae_gated_destroy.restype = C.c_int
+_lib.ae_gated_backward_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+_lib.ae_gated_backward_workspace_bytes.restype = C.c_int
+_lib.ae_gated_backward.argtypes = [C.c_void_p] * 13 + [C.c_size_t, C.c_void_p]
+_lib.ae_gated_backward.restype = C.c_int
 
 
 def ae_gated_create(*, B: int, H: int, L: int, D_qk: int, D_v: int, scale: float, H_qk: Optional[int] = None,
@@ -459,6 +463,19 @@ def ae_gated_forward(handle: int, Q: int, K: int, V: int, log_decay: int, key_ga
 
 def ae_gated_destroy(handle: Optional[int]) -> None:
     _check(_lib.ae_gated_destroy(handle))
+
+
+def ae_gated_backward_workspace_bytes(handle: int) -> int:
+    n = C.c_size_t()
+    _check(_lib.ae_gated_backward_workspace_bytes(handle, C.byref(n)))
+    return n.value
+
+
+def ae_gated_backward(handle: int, Q: int, K: int, V: int, log_decay: int, key_gate: int, dO: int, dQ: int, dK: int, dV: int,
+                      dlog_decay: int, dkey_gate: int, workspace: int, workspace_bytes: int, stream: int = 0) -> None:
+    """Device pointers as ints; key_gate and dkey_gate are 0 together."""
+    _check(_lib.ae_gated_backward(handle, Q, K, V, log_decay, key_gate, dO, dQ, dK, dV, dlog_decay, dkey_gate, workspace,
+                                  workspace_bytes, stream))
 
 
 def gated_recurrent(Q, K, V, log_decay, key_gate=None, *, scale, h_in=None, want_state=False, out_dtype=None, stream=None):
@@ -485,3 +502,32 @@ def gated_recurrent(Q, K, V, log_decay, key_gate=None, *, scale, h_in=None, want
     finally:
         ae_gated_destroy(h)
     return (out, h_out) if want_state else out
+
+
+def gated_recurrent_backward(Q, K, V, log_decay, key_gate, dO, *, scale, stream=None):
+    """Backward pass of gated_recurrent on device tensors (layouts as there, dO bf16 [B, H, L, D_v], contiguous).
+    Returns (dQ, dK, dV, dlog_decay, dkey_gate or None), all fp32; dQ and dK have the shape of Q."""
+    import torch
+
+    for t in (Q, K, V, log_decay, dO) + (() if key_gate is None else (key_gate,)):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("gated_recurrent_backward needs contiguous device tensors; there is no CPU path")
+    B, H_qk, L, D_qk = Q.shape
+    _, H, _, D_v = V.shape
+    f32 = dict(dtype=torch.float32, device=Q.device)
+    dQ, dK, dV = torch.empty(Q.shape, **f32), torch.empty(K.shape, **f32), torch.empty(V.shape, **f32)
+    dla = torch.empty((B, H, L), **f32)
+    dkg = None if key_gate is None else torch.empty((B, H, L), **f32)
+    h = ae_gated_create(B=B, H=H, H_qk=H_qk, L=L, D_qk=D_qk, D_v=D_v, scale=scale)
+    try:
+        nbytes = ae_gated_backward_workspace_bytes(h)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=Q.device)
+        s = torch.cuda.current_stream(Q.device) if stream is None else stream
+        with torch.cuda.device(Q.device):
+            ae_gated_backward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), log_decay.data_ptr(),
+                              0 if key_gate is None else key_gate.data_ptr(), dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
+                              dV.data_ptr(), dla.data_ptr(), 0 if dkg is None else dkg.data_ptr(), ws.data_ptr(), nbytes,
+                              s.cuda_stream)
+    finally:
+        ae_gated_destroy(h)
+    return dQ, dK, dV, dla, dkg

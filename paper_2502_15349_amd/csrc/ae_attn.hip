@@ -908,6 +908,116 @@ ae_status_t ae_gated_forward(const ae_gated_t* h, const void* Q, const void* K, 
   return AE_OK;
 }
 
+// Workspace of the backward pass: the per-token terms of the decay gradient, fp32 [B, H, L]; and, where value heads
+// share q/k heads, the gradients of q and of the gated key per value head, fp32 [B, H, L, D_qk] each.
+static size_t gated_backward_ws(const ae_gated_desc_t& d, size_t* per_head_off) {
+  const size_t rows = ((size_t)d.B * d.H * d.L * 4 + 255) & ~(size_t)255;
+  if (per_head_off) *per_head_off = rows;
+  return rows + (d.H != d.H_qk ? 2 * (size_t)d.B * d.H * d.L * d.D_qk * 4 : 0);
+}
+
+ae_status_t ae_gated_backward_workspace_bytes(const ae_gated_t* h, size_t* bytes) {
+  if (!h || !bytes) return fail(AE_ERR_INVALID_ARG, "ae_gated_backward_workspace_bytes: null argument");
+  *bytes = gated_backward_ws(h->desc, nullptr);
+  return AE_OK;
+}
+
+ae_status_t ae_gated_backward(const ae_gated_t* h, const void* Q, const void* K, const void* V, const void* log_decay,
+                              const void* key_gate, const void* dO, void* dQ, void* dK, void* dV, void* dlog_decay,
+                              void* dkey_gate, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+  if (!h) return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: null handle");
+  if (!Q || !K || !V || !log_decay || !dO || !dQ || !dK || !dV || !dlog_decay)
+    return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: null pointer");
+  if (key_gate && !dkey_gate) return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: a key gate needs a buffer for its gradient");
+  if (!key_gate && dkey_gate) return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: dkey_gate without a key gate");
+  if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)dO | (uintptr_t)dQ | (uintptr_t)dK | (uintptr_t)dV) & 15)
+    return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: Q, K, V, dO, dQ, dK, dV must be 16-byte aligned");
+  if (((uintptr_t)log_decay | (uintptr_t)key_gate | (uintptr_t)dlog_decay | (uintptr_t)dkey_gate) & 3)
+    return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: the gates and their gradients must be 4-byte aligned");
+  const ae_gated_desc_t& d = h->desc;
+  size_t per_head_off = 0;
+  const size_t need = gated_backward_ws(d, &per_head_off);
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)
+    return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: workspace missing, not 256-byte aligned, or smaller than %zu bytes", need);
+  const void* ins[] = {Q, K, V, log_decay, key_gate, dO};
+  void* outs[] = {dQ, dK, dV, dlog_decay, dkey_gate, workspace};
+  for (int a = 0; a < 6; ++a) {
+    if (!outs[a]) continue;
+    for (const void* in : ins)
+      if (in == outs[a]) return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: an output aliases an input");
+    for (int c = a + 1; c < 6; ++c)
+      if (outs[c] == outs[a]) return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: two outputs alias");
+  }
+  const bool grouped = d.H != d.H_qk;
+  float* dB = static_cast<float*>(workspace);
+  float* dQu = grouped ? reinterpret_cast<float*>(static_cast<char*>(workspace) + per_head_off) : static_cast<float*>(dQ);
+  float* X = grouped ? dQu + (size_t)d.B * d.H * d.L * d.D_qk : static_cast<float*>(dK);
+  static const ae::DecayTable no_table = {};
+  // The three sums of the backward pass are the forward recurrence itself on other operands (see include/ae_attn.h):
+  ae::GatedParams p;
+  p.h_in = nullptr;
+  p.h_out = nullptr;
+  p.B = d.B;
+  p.H = d.H;
+  p.L = d.L;
+  p.scale = d.scale;
+  p.out_bf16 = 0;
+  p.log_decay = static_cast<const float*>(log_decay);
+  // (1) dq_i = scale sum_{j <= i} A_ij g_j (dO_i . v_j) k_j: queries dO, keys V (both per value head), values K
+  p.Q = static_cast<const __bf16*>(dO);
+  p.K = static_cast<const __bf16*>(V);
+  p.V = static_cast<const __bf16*>(K);
+  p.H_qk = d.H;
+  p.H_v = d.H_qk;
+  p.key_gate = static_cast<const float*>(key_gate);
+  p.gate_on_output = 0;
+  p.reverse = 0;
+  p.O = dQu;
+  hipError_t e = ae::launch_gated_recurrent(p, no_table, d.D_v, d.D_qk, stream);
+  // (2) x_j = scale sum_{i >= j} A_ij (v_j . dO_i) q_i, walking backwards: queries V, keys dO, values Q, no gate
+  if (e == hipSuccess) {
+    p.Q = static_cast<const __bf16*>(V);
+    p.K = static_cast<const __bf16*>(dO);
+    p.V = static_cast<const __bf16*>(Q);
+    p.key_gate = nullptr;
+    p.reverse = 1;
+    p.O = X;
+    e = ae::launch_gated_recurrent(p, no_table, d.D_v, d.D_qk, stream);
+  }
+  // (3) dv_j = g_j scale sum_{i >= j} A_ij (k_j . q_i) dO_i, walking backwards: queries K, keys Q, values dO
+  if (e == hipSuccess) {
+    p.Q = static_cast<const __bf16*>(K);
+    p.K = static_cast<const __bf16*>(Q);
+    p.V = static_cast<const __bf16*>(dO);
+    p.H_qk = d.H_qk;
+    p.H_v = d.H;
+    p.key_gate = static_cast<const float*>(key_gate);
+    p.gate_on_output = key_gate ? 1 : 0;
+    p.O = dV;
+    e = ae::launch_gated_recurrent(p, no_table, d.D_qk, d.D_v, stream);
+  }
+  if (e == hipSuccess) {
+    ae::GatedBwdEpilogueParams q;
+    q.Q = static_cast<const __bf16*>(Q);
+    q.K = static_cast<const __bf16*>(K);
+    q.dQu = dQu;
+    q.X = X;
+    q.key_gate = static_cast<const float*>(key_gate);
+    q.dQ = static_cast<float*>(dQ);
+    q.dK = static_cast<float*>(dK);
+    q.dkey_gate = static_cast<float*>(dkey_gate);
+    q.dB = dB;
+    q.dlog_decay = static_cast<float*>(dlog_decay);
+    q.B = d.B;
+    q.H = d.H;
+    q.H_qk = d.H_qk;
+    q.L = d.L;
+    e = ae::launch_gated_backward_epilogue(q, d.D_qk, stream);
+  }
+  if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_gated_backward: %s", hipGetErrorString(e));
+  return AE_OK;
+}
+
 ae_status_t ae_gated_destroy(ae_gated_t* h) {
   delete h;
   return AE_OK;

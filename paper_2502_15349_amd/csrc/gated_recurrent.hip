@@ -102,7 +102,8 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   const int64_t L = p.L;
   const __bf16* Qh = p.Q + ((int64_t)b * p.H_qk + hqk) * L * C::DQK;
   const __bf16* Kh = p.K + ((int64_t)b * p.H_qk + hqk) * L * C::DQK;
-  const __bf16* Vh = p.V + (int64_t)bh * L * C::DV;
+  const __bf16* Vh = p.V + ((int64_t)b * p.H_v + h / (p.H / p.H_v)) * L * C::DV;
+  const bool rev = p.reverse != 0;
   const float* lah = p.log_decay ? p.log_decay + (int64_t)bh * L : nullptr;
   const float la_const = lah ? 0.f : dt.log2_gamma[h] * 0.6931471805599453f;  // constant decay per head: ln gamma
   const float* gh = p.key_gate ? p.key_gate + (int64_t)bh * L : nullptr;
@@ -133,7 +134,10 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   auto lane_off = [&](auto cprc, int nb, int t0, bool whole) {
     constexpr int CPR = decltype(cprc)::value;
     const int pos = nb * 64 + lane, r = pos / CPR, pc = pos % CPR;
-    const int row = whole ? r : min(r, (int)L - 1 - t0);
+    int row = whole ? r : min(r, (int)L - 1 - t0);
+    // walking backwards, tile row r is the token r in front of the chunk's first one, and the base pointer stands at
+    // the chunk's lowest address: its last row (row 63 of a whole chunk, token 0 of a short one)
+    if (rev) row = (whole ? C::CH - 1 : (int)L - 1 - t0) - row;
     return (uint32_t)((row * (CPR * 8) + ((pc ^ bswz<CPR>(r)) * 8)) * 2);
   };
 #pragma unroll
@@ -144,7 +148,8 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     const int t0 = c * C::CH;
     const bool whole = t0 + C::CH <= L;
     const uint32_t base = lds0 + (c % C::STAGES) * C::STAGE_BYTES;
-    const __bf16 *qc = Qh + (int64_t)t0 * C::DQK, *kc = Kh + (int64_t)t0 * C::DQK, *vc = Vh + (int64_t)t0 * C::DV;
+    const int64_t r0 = rev ? max((int)L - C::CH - t0, 0) : t0;  // the chunk's row with the lowest address
+    const __bf16 *qc = Qh + r0 * C::DQK, *kc = Kh + r0 * C::DQK, *vc = Vh + r0 * C::DV;
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
       const int nb = wave + i * C::WAVES;
@@ -163,7 +168,11 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     // every wave issues the same number of copies
     const float* grow = wh == 0 && lah ? lah : wh == 1 && gh ? gh : nullptr;
     const uint32_t gdst = raw0 + (c % C::STAGES) * (C::HPW * C::RAW_BYTES) + (wh == 1 ? 256 : 0);
-    const uint32_t goff = grow ? (uint32_t)min(t0 + lane, (int)L - 1) * 4u : 0u;
+    // walking backwards: the decay of the token one later in the sequence (the walk's first token has none: its
+    // word is replaced by 0 where it is read), the gate of the token itself
+    int gi = min(t0 + lane, (int)L - 1);
+    if (rev) gi = wh == 0 ? min((int)L - 1 - gi + 1, (int)L - 1) : (int)L - 1 - gi;
+    const uint32_t goff = grow ? (uint32_t)gi * 4u : 0u;
     dma4(grow ? (const void*)grow : (const void*)Qh, goff, grow ? gdst : scrap0);
   };
 
@@ -215,6 +224,13 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
       const uint32_t raw = raw0 + (c % C::STAGES) * (C::HPW * C::RAW_BYTES) + lane * 4;
       la = lah ? fmaxf(*reinterpret_cast<__attribute__((address_space(3))) const float*>((lds_char*)(uintptr_t)raw), -20.f) : la_const;
       g = gh ? *reinterpret_cast<__attribute__((address_space(3))) const float*>((lds_char*)(uintptr_t)(raw + 256)) : 1.f;
+      if (rev && t0 + lane == 0) la = lah ? 0.f : la;  // (a constant decay is the same for every token: nothing to shift)
+    }
+    // the gate as a factor on the output rows instead of the keys: the two query tokens of this lane
+    float og0 = 1.f, og1 = 1.f;
+    if (p.gate_on_output) {
+      swap_halves(g, og0, og1);
+      g = t0 + lane < L ? 1.f : 0.f;
     }
 
     // ---- gates: b = inclusive prefix sum of the log-decays over the chunk's 64 tokens (lane = token) ----
@@ -244,6 +260,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     auto query_block = [&](auto ibc) {
     constexpr int IB = decltype(ibc)::value;
     const float bi = IB ? bi1 : bi0;  // of this lane's query: token 32 IB + ln of the chunk
+    const float og = IB ? og1 : og0;
     // ---- Q fragments of the wave's query block (B operands of S^T and of the read-out) ----
     bf16x8 qf[C::T];
 #pragma unroll
@@ -326,7 +343,11 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     {
       const int64_t i = t0 + 32 * IB + ln;
       if (i < L) {
-        const int64_t e0 = ((int64_t)bh * L + i) * C::DV + 32 * vblk + 4 * half;
+        if (p.gate_on_output) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[r] *= og;
+        }
+        const int64_t e0 = ((int64_t)bh * L + (rev ? L - 1 - i : i)) * C::DV + 32 * vblk + 4 * half;
         if (p.out_bf16) {
 #pragma unroll
           for (int a = 0; a < 4; ++a) {
@@ -392,16 +413,109 @@ hipError_t launch(const GatedParams& p, const DecayTable& dt, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---- epilogue of the backward pass ----
+// A group of DQK / 4 lanes owns a token (16 bytes of an fp32 row, 8 of a bf16 row, per lane); a wavefront takes
+// 64 / (DQK / 4) tokens of one (batch, q/k head) at a time and loops over the value heads of the group.
+template <int DQK>
+__global__ __launch_bounds__(256) void gated_bwd_rows_kernel(const GatedBwdEpilogueParams p) {
+  constexpr int LPR = DQK / 4, TPW = 64 / LPR;
+  const int lane = threadIdx.x & 63, sub = lane % LPR;
+  const int grp = p.H / p.H_qk;
+  const int64_t blocks_per_head = ((int64_t)p.L + 4 * TPW - 1) / (4 * TPW);
+  const int64_t bhq = blockIdx.x / blocks_per_head;  // (batch, q/k head)
+  const int64_t t = (blockIdx.x % blocks_per_head) * (4 * TPW) + (threadIdx.x >> 6) * TPW + lane / LPR;
+  const bool live = t < p.L;
+  const int64_t tc = live ? t : p.L - 1;
+  const int b = (int)(bhq / p.H_qk), hq = (int)(bhq % p.H_qk);
+  const int64_t qrow = (bhq * p.L + tc) * DQK + 4 * sub;
+  const bf16x4 q4 = *reinterpret_cast<const bf16x4*>(p.Q + qrow), k4 = *reinterpret_cast<const bf16x4*>(p.K + qrow);
+  f32x4 dq = {0.f, 0.f, 0.f, 0.f}, dk = {0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < grp; ++j) {
+    const int64_t bh = (int64_t)b * p.H + (int64_t)hq * grp + j;
+    const int64_t row = (bh * p.L + tc) * DQK + 4 * sub;
+    const f32x4 u = *reinterpret_cast<const f32x4*>(p.dQu + row), x = *reinterpret_cast<const f32x4*>(p.X + row);
+    const float g = p.key_gate ? p.key_gate[bh * p.L + tc] : 1.f;
+    float qd = 0.f, kx = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      qd += (float)q4[e] * u[e];
+      kx += (float)k4[e] * x[e];
+      dq[e] += u[e];
+      dk[e] += g * x[e];
+    }
+#pragma unroll
+    for (int s = LPR / 2; s >= 1; s >>= 1) {
+      qd += __shfl_xor(qd, s);
+      kx += __shfl_xor(kx, s);
+    }
+    if (live && sub == 0) {
+      p.dB[bh * p.L + t] = qd - g * kx;
+      if (p.dkey_gate) p.dkey_gate[bh * p.L + t] = kx;
+    }
+  }
+  if (live) {
+    // (where dQu is dQ itself the values are already in place; dK is rewritten only if something changed it)
+    if (p.dQu != p.dQ) *reinterpret_cast<f32x4*>(p.dQ + qrow) = dq;
+    if (p.X != p.dK || p.key_gate) *reinterpret_cast<f32x4*>(p.dK + qrow) = dk;
+  }
+}
+
+// dlog_decay[t] = sum_{i >= t} dB[i]: one wavefront per (batch, head) walks from the end in blocks of 256 tokens,
+// four per lane; the running total is kept in double (the terms change sign and the sum is long).
+__global__ __launch_bounds__(64) void gated_bwd_suffix_sum_kernel(const GatedBwdEpilogueParams p) {
+  const int lane = threadIdx.x;
+  const float* src = p.dB + (int64_t)blockIdx.x * p.L;
+  float* dst = p.dlog_decay + (int64_t)blockIdx.x * p.L;
+  double carry = 0.0;
+  const int nblk = (p.L + 255) / 256;
+  for (int blk = nblk - 1; blk >= 0; --blk) {
+    const int t0 = blk * 256 + 4 * lane;
+    float x[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[e] = t0 + e < p.L ? src[t0 + e] : 0.f;
+    // suffix sums inside the lane, then over the lanes behind this one
+    x[2] += x[3];
+    x[1] += x[2];
+    x[0] += x[1];
+    float tot = x[0];  // inclusive suffix sum over lanes: lane l gets the sum of the totals of lanes >= l
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+      const float o = __shfl_down(tot, s);
+      if (lane + s < 64) tot += o;
+    }
+    const float behind = tot - x[0];  // the lanes strictly behind
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (t0 + e < p.L) dst[t0 + e] = (float)(carry + (double)(x[e] + behind));
+    carry += (double)__shfl(tot, 0);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_gated_backward_epilogue(const GatedBwdEpilogueParams& p, int dqk, hipStream_t s) {
+  const int tpb = 4 * (64 / (dqk / 4));
+  const int64_t grid = (int64_t)p.B * p.H_qk * (((int64_t)p.L + tpb - 1) / tpb);
+  if (grid > 0x7fffffffLL || (dqk != 64 && dqk != 128)) return hipErrorInvalidValue;
+  if (dqk == 64) hipLaunchKernelGGL(gated_bwd_rows_kernel<64>, dim3((unsigned)grid), dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(gated_bwd_rows_kernel<128>, dim3((unsigned)grid), dim3(256), 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(gated_bwd_suffix_sum_kernel, dim3((unsigned)(p.B * p.H)), dim3(64), 0, s, p);
+  return hipGetLastError();
+}
 
 bool gated_supported(int dqk, int dv) { return (dqk == 64 || dqk == 128) && (dv == 64 || dv == 128); }
 
-hipError_t launch_gated_recurrent(const GatedParams& p, const DecayTable& dt, int dqk, int dv, hipStream_t s) {
+hipError_t launch_gated_recurrent(const GatedParams& p_in, const DecayTable& dt, int dqk, int dv, hipStream_t s) {
+  GatedParams p = p_in;
+  if (p.H_v == 0) p.H_v = p.H;
+  if (p.H_qk < 1 || p.H % p.H_qk != 0 || p.H % p.H_v != 0) return hipErrorInvalidValue;
   if (dqk == 64 && dv == 64) return launch<64, 64>(p, dt, s);
   if (dqk == 128 && dv == 64) {
     // value heads that share their q/k head (Mamba2's groups) share the Q and K tiles of a workgroup, two at a time
     const int grp = p.H / p.H_qk;
-    if (grp % 2 == 0) return launch<128, 64, 2, 1>(p, dt, s);
+    if (grp % 2 == 0 && p.H_v == p.H) return launch<128, 64, 2, 1>(p, dt, s);
     return launch<128, 64>(p, dt, s);
   }
   if (dqk == 64 && dv == 128) return launch<64, 128>(p, dt, s);

@@ -404,3 +404,38 @@ def test_gated_descriptor_and_entry_point_checks():
         with pytest.raises(A.AeAttnError) as ei:
             A.ae_gated_create(**dict(ok, **patch))
         assert ei.value.status == status, (patch, A.ae_attn_last_error())
+
+
+def test_gated_backward_entry_point_checks():
+    from paper_2502_15349_amd import ae_attn as A
+    h = A.ae_gated_create(B=2, H=8, H_qk=2, L=300, D_qk=128, D_v=64, scale=0.1)
+    hu = A.ae_gated_create(B=2, H=8, H_qk=8, L=300, D_qk=128, D_v=64, scale=0.1)
+    try:
+        rows = 2 * 8 * 300 * 4
+        assert A.ae_gated_backward_workspace_bytes(hu) == (rows + 255) // 256 * 256            # per-token terms only
+        need = A.ae_gated_backward_workspace_bytes(h)
+        assert need == (rows + 255) // 256 * 256 + 2 * 2 * 8 * 300 * 128 * 4                    # + two per-head gradients
+        # Q K V log_decay key_gate dO dQ dK dV dlog_decay dkey_gate workspace
+        q, k, v, la, kg, do, dq, dk, dv, dla, dkg, ws = (i << 24 for i in range(1, 13))
+        good = (q, k, v, la, kg, do, dq, dk, dv, dla, dkg, ws)
+        for pos, val in ((0, 0), (5, 0), (6, 0), (9, 0),             # null Q, dO, dQ, dlog_decay
+                         (10, 0),                                     # key gate without a buffer for its gradient
+                         (2, v + 8), (8, dv + 4), (9, dla + 2),       # misaligned
+                         (6, q), (7, dq), (10, la), (11, dv),         # aliases
+                         (11, ws + 128), (11, 0)):                    # workspace misaligned / missing
+            args = list(good)
+            args[pos] = val
+            with pytest.raises(A.AeAttnError) as ei:
+                A.ae_gated_backward(h, *args, need)
+            assert ei.value.status == A.AE_ERR_INVALID_ARG, (pos, val, A.ae_attn_last_error())
+        with pytest.raises(A.AeAttnError) as ei:
+            A.ae_gated_backward(h, *good, need - 1)
+        assert ei.value.status == A.AE_ERR_INVALID_ARG
+        with pytest.raises(A.AeAttnError) as ei:                     # dkey_gate without a key gate
+            A.ae_gated_backward(h, q, k, v, la, 0, do, dq, dk, dv, dla, dkg, ws, need)
+        assert ei.value.status == A.AE_ERR_INVALID_ARG
+        with pytest.raises(A.AeAttnError):
+            A.ae_gated_backward(None, *good, need)
+    finally:
+        A.ae_gated_destroy(h)
+        A.ae_gated_destroy(hu)
