@@ -140,10 +140,19 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     if (rev) row = (whole ? C::CH - 1 : (int)L - 1 - t0) - row;
     return (uint32_t)((row * (CPR * 8) + ((pc ^ bswz<CPR>(r)) * 8)) * 2);
   };
+  uint32_t qoff_t[NQ], voff_t[NV];  // the same for the last chunk, if it is short
+  const int n_chunks = (int)((L + C::CH - 1) / C::CH);
+  const int t0_last = (n_chunks - 1) * C::CH;
 #pragma unroll
-  for (int i = 0; i < NQ; ++i) qoff[i] = lane_off(std::integral_constant<int, C::CPRQ>{}, wave + i * C::WAVES, 0, true);
+  for (int i = 0; i < NQ; ++i) {
+    qoff[i] = lane_off(std::integral_constant<int, C::CPRQ>{}, wave + i * C::WAVES, 0, true);
+    qoff_t[i] = lane_off(std::integral_constant<int, C::CPRQ>{}, wave + i * C::WAVES, t0_last, false);
+  }
 #pragma unroll
-  for (int i = 0; i < NV; ++i) voff[i] = lane_off(std::integral_constant<int, C::CPRV>{}, wh + i * C::WPH, 0, true);
+  for (int i = 0; i < NV; ++i) {
+    voff[i] = lane_off(std::integral_constant<int, C::CPRV>{}, wh + i * C::WPH, 0, true);
+    voff_t[i] = lane_off(std::integral_constant<int, C::CPRV>{}, wh + i * C::WPH, t0_last, false);
+  }
   auto issue_chunk = [&](int c) {
     const int t0 = c * C::CH;
     const bool whole = t0 + C::CH <= L;
@@ -153,14 +162,14 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
       const int nb = wave + i * C::WAVES;
-      const uint32_t off = whole ? qoff[i] : lane_off(std::integral_constant<int, C::CPRQ>{}, nb, t0, false);
+      const uint32_t off = whole ? qoff[i] : qoff_t[i];  // (only the last chunk can be short)
       dma16(qc, off, base + nb * 1024);
       dma16(kc, off, base + C::Q_BYTES + nb * 1024);
     }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int nb = wh + i * C::WPH;
-      const uint32_t off = whole ? voff[i] : lane_off(std::integral_constant<int, C::CPRV>{}, nb, t0, false);
+      const uint32_t off = whole ? voff[i] : voff_t[i];
       dma16(vc, off, base + 2 * C::Q_BYTES + hw * C::V_BYTES + nb * 1024);
     }
     // the head's gates, one token per lane: its first wave fetches the log-decays, its second the key gates; the
@@ -176,33 +185,69 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     dma4(grow ? (const void*)grow : (const void*)Qh, goff, grow ? gdst : scrap0);
   };
 
-  // per-lane pieces of the fragment addresses (stage 0; see attn_bwd_kernel.hpp for the two read patterns of a tile)
-  const int fq = bswz<C::CPRQ>(ln);
+  // Per-lane parts of the fragment addresses, relative to a stage (see attn_bwd_kernel.hpp for the two read patterns
+  // of a tile).  Whatever depends on the lane sits in these registers; the stage adds one uniform offset per chunk
+  // (below), and tile, row block and token step are compile-time offsets that the LDS instructions carry themselves.
   const int li = lane & 15, blk = (lane >> 4) & 1;
   const int trow = 4 * half + (li >> 2), tcl = 2 * blk + ((li & 3) >> 1);
-  // row fragment of Q or K for d-step t, rows `row0 + ln` of the tile at `tb`: d = 16 t + 4 half + {0..3} and + 8
-  auto row_frag = [&](uint32_t tb, int row0, int t) {
-    const uint32_t a = tb + (row0 + ln) * C::RBQ + 8 * half;
-    const u32x2 lo = lds_read8(a + (((2 * t) ^ fq) << 4)), hi = lds_read8(a + (((2 * t + 1) ^ fq) << 4));
-    return __builtin_bit_cast(bf16x8, (u32x4){lo[0], lo[1], hi[0], hi[1]});
-  };
-  // transposed fragment: 32 columns of block k, 16 rows of step s (lane = column, registers = rows in accumulator order)
-  auto tr_frag = [&](uint32_t tb, auto cprc, int k, int s) {
+  // row fragment of Q or K for d-step t (d = 16 t + 4 half + {0..3} and + 8), row ln of a 32-row block: two 8-byte pieces
+  uint32_t rq0[C::T][2];
+#pragma unroll
+  for (int t = 0; t < C::T; ++t)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) rq0[t][j] = ln * C::RBQ + 8 * half + (((2 * t + j) ^ bswz<C::CPRQ>(ln)) << 4);
+  // transposed fragment: 32 columns of block k, rows trow and trow + 8 of a 16-token step (lane = column, registers =
+  // rows in accumulator order)
+  auto tr_lane = [&](auto cprc, int k, int j) {
     constexpr int CPR = decltype(cprc)::value, RB = CPR * 16;
-    const int rlo = 16 * s + trow, rhi = rlo + 8;
-    const uint32_t alo = tb + (li & 1) * 8 + rlo * RB + (((4 * k + tcl) ^ bswz<CPR>(rlo)) << 4);
-    const uint32_t ahi = tb + (li & 1) * 8 + rhi * RB + (((4 * k + tcl) ^ bswz<CPR>(rhi)) << 4);
-    return read_tr_frag(alo, ahi);
+    const int r = trow + 8 * j;
+    return (uint32_t)((li & 1) * 8 + r * RB + (((4 * k + tcl) ^ bswz<CPR>(r)) << 4));
   };
+  uint32_t kt0[C::DBQ][2], vt0[2];
+#pragma unroll
+  for (int k = 0; k < C::DBQ; ++k)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) kt0[k][j] = C::Q_BYTES + tr_lane(std::integral_constant<int, C::CPRQ>{}, k, j);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) vt0[j] = 2 * C::Q_BYTES + hw * C::V_BYTES + tr_lane(std::integral_constant<int, C::CPRV>{}, vblk, j);
 
-  const int n_chunks = (int)((L + C::CH - 1) / C::CH);
   issue_chunk(0);
   if (n_chunks > 1) issue_chunk(1);
 
   for (int c = 0; c < n_chunks; ++c) {
     const int t0 = c * C::CH;
-    const uint32_t sb = lds0 + (c % C::STAGES) * C::STAGE_BYTES;
-    const uint32_t qb = sb, kb_ = sb + C::Q_BYTES, vb_ = sb + 2 * C::Q_BYTES + hw * C::V_BYTES;
+    // this chunk's fragment addresses: the lane parts plus the stage
+    uint32_t rq[C::T][2], kt[C::DBQ][2], vt[2];
+    {
+      const uint32_t sb = lds0 + (c % C::STAGES) * C::STAGE_BYTES;
+#pragma unroll
+      for (int t = 0; t < C::T; ++t)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          rq[t][j] = rq0[t][j] + sb;
+          pin(rq[t][j]);
+        }
+#pragma unroll
+      for (int k = 0; k < C::DBQ; ++k)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          kt[k][j] = kt0[k][j] + sb;
+          pin(kt[k][j]);
+        }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        vt[j] = vt0[j] + sb;
+        pin(vt[j]);
+      }
+    }
+    // rows row0 + ln of the Q tile (tile 0) or the K tile (tile 1), d-step t
+    auto row_frag = [&](int tile, int row0, int t) {
+      const uint32_t o = tile * C::Q_BYTES + row0 * C::RBQ;
+      const u32x2 lo = lds_read8(rq[t][0] + o), hi = lds_read8(rq[t][1] + o);
+      return __builtin_bit_cast(bf16x8, (u32x4){lo[0], lo[1], hi[0], hi[1]});
+    };
+    auto k_tr_frag = [&](int k, int s) { return read_tr_frag(kt[k][0] + 16 * s * C::RBQ, kt[k][1] + 16 * s * C::RBQ); };
+    auto v_tr_frag = [&](int s) { return read_tr_frag(vt[0] + 16 * s * C::RBV, vt[1] + 16 * s * C::RBV); };
     // Chunk c has landed: of this wave's memory operations only those issued after its copies may still be in
     // flight -- the copies of chunk c + 1 (if there is one) and the stores of chunk c - 1 (if there was one; it was
     // a whole chunk: four stores).  The counter runs in issue order.  Then the barrier: everybody's copies have
@@ -255,6 +300,21 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     }
     float bi0, bi1;  // b of tokens ln and 32 + ln
     swap_halves(bcum, bi0, bi1);
+    // The state in front of the chunk, rounded to bf16: the A operands of the read-out (an accumulator tile is an A
+    // operand whose contraction runs over its rows).  In the same pass over the accumulators the state takes the
+    // chunk's whole decay, as the update at the end of the iteration needs it.
+    bf16x8 hp[C::DBQ][2];
+    {
+      const float dec = __expf(b_last);
+#pragma unroll
+      for (int db = 0; db < C::DBQ; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float x = H[db][r];
+          hp[db][r / 8][r % 8] = (__bf16)x;
+          H[db][r] = x * dec;
+        }
+    }
     bf16x8 vf[4];  // the V fragments of the chunk's four 16-token steps (this wave's 32 value columns)
     // The wave's query block as a compile-time constant (register arrays indexed by it stay in registers).
     auto query_block = [&](auto ibc) {
@@ -264,19 +324,14 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     // ---- Q fragments of the wave's query block (B operands of S^T and of the read-out) ----
     bf16x8 qf[C::T];
 #pragma unroll
-    for (int t = 0; t < C::T; ++t) qf[t] = row_frag(qb, 32 * IB, t);
+    for (int t = 0; t < C::T; ++t) qf[t] = row_frag(0, 32 * IB, t);
 
     // ---- read-out of the state in front of the chunk: O^T = H^T Q^T, times scale e^{b_i} ----
     f32x16 o = zero16();
 #pragma unroll
     for (int db = 0; db < C::DBQ; ++db)
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        bf16x8 hfrag;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) hfrag[e] = (__bf16)H[db][8 * tt + e];
-        o = mfma(hfrag, qf[2 * db + tt], o);
-      }
+      for (int tt = 0; tt < 2; ++tt) o = mfma(hp[db][tt], qf[2 * db + tt], o);
     {
       const float f = p.scale * __expf(bi);
 #pragma unroll
@@ -317,14 +372,14 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     {
       f32x16 sd = zero16();
 #pragma unroll
-      for (int t = 0; t < C::T; ++t) sd = mfma(row_frag(kb_, 32 * IB, t), qf[t], sd);
+      for (int t = 0; t < C::T; ++t) sd = mfma(row_frag(1, 32 * IB, t), qf[t], sd);
       u32x4 pd[2];
       weigh(sd, IB, true, pd);
       // the V fragments of the chunk's four 16-token steps (this wave's 32 value columns): A operands of the
       // aggregation and, weighted, B operands of the state update
       if constexpr (IB == 0 || C::QS == 2) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) vf[s] = tr_frag(vb_, std::integral_constant<int, C::CPRV>{}, vblk, s);
+        for (int s = 0; s < 4; ++s) vf[s] = v_tr_frag(s);
       }
       o = mfma(vf[2 * IB], __builtin_bit_cast(bf16x8, pd[0]), o);
       o = mfma(vf[2 * IB + 1], __builtin_bit_cast(bf16x8, pd[1]), o);
@@ -332,7 +387,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     if constexpr (IB == 1) {
       f32x16 sl = zero16();
 #pragma unroll
-      for (int t = 0; t < C::T; ++t) sl = mfma(row_frag(kb_, 0, t), qf[t], sl);
+      for (int t = 0; t < C::T; ++t) sl = mfma(row_frag(1, 0, t), qf[t], sl);
       u32x4 pl[2];
       weigh(sl, 0, false, pl);
       o = mfma(vf[0], __builtin_bit_cast(bf16x8, pl[0]), o);
@@ -368,14 +423,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     if (C::QS == 1 || ib == 0) query_block(std::integral_constant<int, 0>{});
     if (C::QS == 1 || ib == 1) query_block(std::integral_constant<int, 1>{});
 
-    // ---- state update: H = e^{b_last} H + K^T (w . V) ----
-    {
-      const float dec = __expf(b_last);
-#pragma unroll
-      for (int db = 0; db < C::DBQ; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) H[db][r] *= dec;
-    }
+    // ---- state update: H (already e^{b_last} times the old state) += K^T (w . V) ----
     f32x4 wv[8];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -393,7 +441,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
       }
 #pragma unroll
       for (int db = 0; db < C::DBQ; ++db)
-        H[db] = mfma(tr_frag(kb_, std::integral_constant<int, C::CPRQ>{}, db, s), vw, H[db]);
+        H[db] = mfma(k_tr_frag(db, s), vw, H[db]);
     }
   }
 
