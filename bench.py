@@ -620,6 +620,24 @@ def main():
             e1.record(st)
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / a.steps
+            # few heads, long sequence: the same call with the walks cut into segments (ae_gated_forward_segmented)
+            seg_ms = None
+            nfw = A.ae_gated_workspace_bytes(h)
+            if nfw:
+                fws = torch.empty(nfw, dtype=torch.uint8, device=dev)
+                O2 = torch.empty_like(O)
+                sargs = args[:7] + (O2.data_ptr(), 0, fws.data_ptr(), nfw, st.cuda_stream)
+                for _ in range(3):
+                    A.ae_gated_forward_segmented(*sargs)
+                torch.cuda.synchronize()
+                e0.record(st)
+                for _ in range(a.steps):
+                    A.ae_gated_forward_segmented(*sargs)
+                e1.record(st)
+                torch.cuda.synchronize()
+                seg_ms = e0.elapsed_time(e1) / a.steps
+                seg_diff = float((O2 - O).abs().max())
+                del fws, O2
             # the backward pass (ae_gated_backward: dQ, dK, dV, dlog_decay, dkey_gate), same handle; compulsory bytes:
             # Q, K, V, dO and the gates read once, the gradients (fp32) written once
             from paper_2502_15349_amd.workloads import make_grad
@@ -663,6 +681,12 @@ def main():
             print(f"# {name:40s} {ms:8.4f} ms = {byts / ms / 1e6:7.1f} GB/s ({100 * byts / ms / 1e6 / 8000.0:4.1f} % of HBM peak), "
                   f"{flop / ms / 1e9:6.1f} TFLOP/s of recurrence, max_abs {err:.2e} | backward {bwd_ms:8.4f} ms = "
                   f"{bwd_byts / bwd_ms / 1e6:7.1f} GB/s ({100 * bwd_byts / bwd_ms / 1e6 / 8000.0:4.1f} %)", file=sys.stderr, flush=True)
+            if seg_ms is not None:
+                rows[-1].update({"segmented_ms": round(seg_ms, 4), "segmented_GBps": round(byts / seg_ms / 1e6, 1),
+                                 "segmented_max_diff_to_single_walk": seg_diff})
+                print(f"#   {'cut into segments':38s} {seg_ms:8.4f} ms = {byts / seg_ms / 1e6:7.1f} GB/s "
+                      f"({100 * byts / seg_ms / 1e6 / 8000.0:4.1f} % of HBM peak), max difference to the single walk {seg_diff:.2e}",
+                      file=sys.stderr, flush=True)
             del Q, K, V, O, la, kg
         print(json.dumps({"gated_recurrent": rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16", "data": "synthetic"}))
         return

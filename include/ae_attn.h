@@ -420,6 +420,26 @@ ae_status_t ae_gated_forward(const ae_gated_t *h, const void *Q, const void *K, 
                              const void *log_decay, const void *key_gate, const void *h_in,
                              void *O, void *h_out, hipStream_t stream);
 
+/* The same call for few (batch, head) pairs and long sequences.  One workgroup
+ * walks a (batch, head) from the first token to the last, so B x H of them keep
+ * B x H compute units busy, however long L is.  Where that leaves most of the
+ * chip idle (create decides: fewer than 128 workgroups and L >= 1024) this entry
+ * point cuts every walk into segments (Section 4.2: parallelism over chunks of
+ * the sequence): all segments are walked side by side for their final states from
+ * a zero start, a small kernel chains those into the state in front of every
+ * segment (h_s+1 = exp(sum of the segment's log-decays) h_s + the segment's own
+ * state), and the segments are walked again, side by side, for the outputs.
+ * Same result as ae_gated_forward up to rounding order.
+ *   workspace  device, 256-byte aligned, ae_gated_workspace_bytes (0 where create
+ *              chose not to cut: then it may be NULL and the call is
+ *              ae_gated_forward); owned by the caller; calls sharing it must not
+ *              overlap.  Everything else as ae_gated_forward.  Three launches.   */
+ae_status_t ae_gated_workspace_bytes(const ae_gated_t *h, size_t *bytes);
+ae_status_t ae_gated_forward_segmented(const ae_gated_t *h, const void *Q, const void *K, const void *V,
+                                       const void *log_decay, const void *key_gate, const void *h_in,
+                                       void *O, void *h_out, void *workspace, size_t workspace_bytes,
+                                       hipStream_t stream);
+
 /* Backward pass of the recurrence above: the paper evaluates the recurrent
  * pattern forward and backward (Section 6.1; Table 2) and takes the backward
  * graph from automatic differentiation of the forward one (Section 5.1); here

@@ -438,6 +438,10 @@ _lib.ae_gated_forward.argtypes = [C.c_void_p] * 10
 _lib.ae_gated_forward.restype = C.c_int
 _lib.ae_gated_destroy.argtypes = [C.c_void_p]
 _lib.ae_gated_destroy.restype = C.c_int
+_lib.ae_gated_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+_lib.ae_gated_workspace_bytes.restype = C.c_int
+_lib.ae_gated_forward_segmented.argtypes = [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]
+_lib.ae_gated_forward_segmented.restype = C.c_int
 _lib.ae_gated_backward_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
 _lib.ae_gated_backward_workspace_bytes.restype = C.c_int
 _lib.ae_gated_backward.argtypes = [C.c_void_p] * 13 + [C.c_size_t, C.c_void_p]
@@ -465,6 +469,17 @@ def ae_gated_destroy(handle: Optional[int]) -> None:
     _check(_lib.ae_gated_destroy(handle))
 
 
+def ae_gated_workspace_bytes(handle: int) -> int:
+    n = C.c_size_t()
+    _check(_lib.ae_gated_workspace_bytes(handle, C.byref(n)))
+    return n.value
+
+
+def ae_gated_forward_segmented(handle: int, Q: int, K: int, V: int, log_decay: int, key_gate: int, h_in: int, O: int, h_out: int,
+                               workspace: int, workspace_bytes: int, stream: int = 0) -> None:
+    _check(_lib.ae_gated_forward_segmented(handle, Q, K, V, log_decay, key_gate, h_in, O, h_out, workspace, workspace_bytes, stream))
+
+
 def ae_gated_backward_workspace_bytes(handle: int) -> int:
     n = C.c_size_t()
     _check(_lib.ae_gated_backward_workspace_bytes(handle, C.byref(n)))
@@ -478,10 +493,12 @@ def ae_gated_backward(handle: int, Q: int, K: int, V: int, log_decay: int, key_g
                                   workspace_bytes, stream))
 
 
-def gated_recurrent(Q, K, V, log_decay, key_gate=None, *, scale, h_in=None, want_state=False, out_dtype=None, stream=None):
+def gated_recurrent(Q, K, V, log_decay, key_gate=None, *, scale, h_in=None, want_state=False, out_dtype=None, stream=None,
+                    segmented=False):
     """Runs the gated recurrent pattern on device tensors: Q, K bf16 [B, H_qk, L, D_qk], V bf16 [B, H, L, D_v],
     log_decay / key_gate fp32 [B, H, L] (all contiguous), h_in fp32 [B, H, D_qk, D_v] or None.  Returns O
-    [B, H, L, D_v] (fp32, or bf16 with out_dtype=torch.bfloat16), and the final state when want_state."""
+    [B, H, L, D_v] (fp32, or bf16 with out_dtype=torch.bfloat16), and the final state when want_state.  segmented: through
+    ae_gated_forward_segmented (the walks cut into segments where few heads meet a long sequence)."""
     import torch
 
     for t in (Q, K, V, log_decay) + (() if key_gate is None else (key_gate,)) + (() if h_in is None else (h_in,)):
@@ -495,10 +512,16 @@ def gated_recurrent(Q, K, V, log_decay, key_gate=None, *, scale, h_in=None, want
                         out_dtype="bf16" if out.dtype == torch.bfloat16 else "f32")
     try:
         s = torch.cuda.current_stream(Q.device) if stream is None else stream
+        nbytes = ae_gated_workspace_bytes(h) if segmented else 0
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=Q.device) if nbytes else None
         with torch.cuda.device(Q.device):
-            ae_gated_forward(h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), log_decay.data_ptr(),
-                             0 if key_gate is None else key_gate.data_ptr(), 0 if h_in is None else h_in.data_ptr(),
-                             out.data_ptr(), 0 if h_out is None else h_out.data_ptr(), s.cuda_stream)
+            args = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), log_decay.data_ptr(),
+                    0 if key_gate is None else key_gate.data_ptr(), 0 if h_in is None else h_in.data_ptr(),
+                    out.data_ptr(), 0 if h_out is None else h_out.data_ptr())
+            if segmented:
+                ae_gated_forward_segmented(*args, 0 if ws is None else ws.data_ptr(), nbytes, s.cuda_stream)
+            else:
+                ae_gated_forward(*args, s.cuda_stream)
     finally:
         ae_gated_destroy(h)
     return (out, h_out) if want_state else out

@@ -638,6 +638,54 @@ int32_t ae_attn_version(void) { return 1; }
 // chunks as if they were batch entries: batch' = chunk index (stride chunk * D), heads' = `fold` batch entries x H
 // heads (stride L * D, which is uniform over (batch, head) in a contiguous [B, H, L, D] tensor).  The decay table
 // of that kernel holds 256 heads, so larger B * H take one launch per batch entry.
+// Segments for a walk of L tokens by `workgroups` workgroups of the single-pass recurrent kernel: enough of them to
+// give every compute unit one, none shorter than 512 tokens (each segment is walked twice, the first time for its
+// state only).  nseg = 1: not cut.
+static void gated_segments(int64_t workgroups, int L, int* nseg, int* seg_len) {
+  *nseg = 1;
+  *seg_len = 0;
+  if (workgroups >= 128 || L < 1024) return;
+  int64_t n = std::min<int64_t>((256 + workgroups - 1) / workgroups, L / 512);
+  if (n < 2) return;
+  const int len = (int)(((L + n - 1) / n + 63) / 64 * 64);
+  *seg_len = len;
+  *nseg = (L + len - 1) / len;
+}
+
+static size_t gated_segments_ws(int B, int H, int nseg, int dqk, int dv) {
+  if (nseg == 1) return 0;
+  const size_t slots = (size_t)B * H * nseg;
+  return slots * dqk * dv * 4 + ((slots * 4 + 255) & ~(size_t)255);
+}
+
+// The walk described by p (whole sequence, caller's h_in / h_out), cut into segments: every segment's final state
+// from a zero start and the sum of its log-decays; those chained into the state in front of every segment; the
+// segments walked again, side by side, for their outputs.
+static hipError_t launch_gated_segmented(const ae::GatedParams& p, const ae::DecayTable& dt, int dqk, int dv, int nseg, int seg_len,
+                                         void* workspace, hipStream_t stream) {
+  const size_t slots = (size_t)p.B * p.H * nseg;
+  float* dec = static_cast<float*>(workspace);
+  float* buf = reinterpret_cast<float*>(static_cast<char*>(workspace) + ((slots * 4 + 255) & ~(size_t)255));
+  ae::GatedParams s1 = p;
+  s1.nseg = nseg;
+  s1.seg_len = seg_len;
+  s1.state_only = 1;
+  s1.h_in = nullptr;
+  s1.h_out = buf;
+  s1.seg_decay = dec;
+  s1.O = nullptr;
+  hipError_t e = ae::launch_gated_recurrent(s1, dt, dqk, dv, stream);
+  if (e != hipSuccess) return e;
+  e = ae::launch_gated_combine_segments(buf, dec, p.h_in, p.B * p.H, nseg, dqk * dv, stream);
+  if (e != hipSuccess) return e;
+  ae::GatedParams s2 = p;
+  s2.nseg = nseg;
+  s2.seg_len = seg_len;
+  s2.h_in = buf;
+  s2.h_out_last_only = 1;
+  return ae::launch_gated_recurrent(s2, dt, dqk, dv, stream);
+}
+
 struct ae_recurrent {
   ae_recurrent_desc_t desc;
   ae_attn_t* full;  // all chunks of full length; null if L < chunk
@@ -646,6 +694,7 @@ struct ae_recurrent {
   int fold, n_full, n_chunks, tail_len;
   size_t ws_bytes;
   bool single_pass;  // forward runs as one kernel with the state on chip (see ae_recurrent_forward_state)
+  int nseg, seg_len;  // ... or, with few (batch, head) pairs and a long sequence, as that kernel on segments (nseg > 1)
 };
 
 extern "C" {
@@ -720,6 +769,12 @@ ae_status_t ae_recurrent_create(const ae_recurrent_desc_t* d, ae_recurrent_t** o
   // the state on chip beats the two-kernel form once there is about a workgroup per compute unit; with few pairs
   // (batch 1) the sequential walk leaves the device idle and the chunk-parallel form wins.
   h->single_pass = ae::gated_supported(d->D_qk, d->D_v) && (int64_t)d->B * d->H >= 192;
+  h->nseg = 1;
+  h->seg_len = 0;
+  if (!h->single_pass && ae::gated_supported(d->D_qk, d->D_v)) {
+    gated_segments((int64_t)d->B * d->H, d->L, &h->nseg, &h->seg_len);
+    h->ws_bytes = std::max(h->ws_bytes, gated_segments_ws(d->B, d->H, h->nseg, d->D_qk, d->D_v));
+  }
   *out = h;
   return AE_OK;
 }
@@ -747,9 +802,10 @@ ae_status_t ae_recurrent_forward_state(const ae_recurrent_t* h, const void* Q, c
     return fail(AE_ERR_INVALID_ARG, "ae_recurrent_forward: workspace aliases another buffer");
   const ae_recurrent_desc_t& d = h->desc;
   const int64_t L = d.L, state_elems = (int64_t)d.D_qk * d.D_v;
-  if (h->single_pass) {
+  if (h->single_pass || h->nseg > 1) {
     // enough (batch, head) pairs to fill the device with one workgroup each: the kernel of the gated pattern with a
-    // constant decay per head -- state on chip, Q, K, V read once, the workspace untouched
+    // constant decay per head -- state on chip, Q, K, V read once, the workspace untouched; or few pairs and a long
+    // sequence: the same kernel on segments of the sequence, whose states pass through the workspace
     ae::GatedParams g;
     g.Q = static_cast<const __bf16*>(Q);
     g.K = static_cast<const __bf16*>(K);
@@ -764,7 +820,8 @@ ae_status_t ae_recurrent_forward_state(const ae_recurrent_t* h, const void* Q, c
     g.L = d.L;
     g.scale = d.scale;
     g.out_bf16 = d.out_dtype == AE_OUT_BF16;
-    const hipError_t e = ae::launch_gated_recurrent(g, h->decay, d.D_qk, d.D_v, stream);
+    const hipError_t e = h->nseg > 1 ? launch_gated_segmented(g, h->decay, d.D_qk, d.D_v, h->nseg, h->seg_len, workspace, stream)
+                                     : ae::launch_gated_recurrent(g, h->decay, d.D_qk, d.D_v, stream);
     if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_recurrent_forward: %s", hipGetErrorString(e));
     return AE_OK;
   }
@@ -851,6 +908,9 @@ ae_status_t ae_recurrent_destroy(ae_recurrent_t* h) {
 // ---- recurrent pattern with per-token gates: one kernel, state on chip ------------------------------------
 struct ae_gated {
   ae_gated_desc_t desc;
+  // ae_gated_forward_segmented: the walk of a (batch, head) cut into nseg segments of seg_len tokens where the
+  // (batch, head) pairs alone would leave most compute units idle; 1: not cut
+  int nseg, seg_len;
 };
 
 extern "C" {
@@ -870,12 +930,24 @@ ae_status_t ae_gated_create(const ae_gated_desc_t* d, ae_gated_t** out) {
   ae_gated* h = new (std::nothrow) ae_gated;
   if (!h) return fail(AE_ERR_NOMEM, "ae_gated_create: out of host memory");
   h->desc = *d;
+  {
+    // (two heads of a group share a workgroup at 128/64, see launch_gated_recurrent)
+    const bool pairs = d->D_qk == 128 && d->D_v == 64 && (d->H / d->H_qk) % 2 == 0;
+    gated_segments((int64_t)d->B * d->H / (pairs ? 2 : 1), d->L, &h->nseg, &h->seg_len);
+  }
   *out = h;
   return AE_OK;
 }
 
-ae_status_t ae_gated_forward(const ae_gated_t* h, const void* Q, const void* K, const void* V, const void* log_decay,
-                             const void* key_gate, const void* h_in, void* O, void* h_out, hipStream_t stream) {
+}  // extern "C"
+
+static size_t gated_forward_ws(const ae_gated* h) {
+  return gated_segments_ws(h->desc.B, h->desc.H, h->nseg, h->desc.D_qk, h->desc.D_v);
+}
+
+static ae_status_t gated_forward_impl(const ae_gated_t* h, const void* Q, const void* K, const void* V, const void* log_decay,
+                                      const void* key_gate, const void* h_in, void* O, void* h_out, void* workspace,
+                                      size_t workspace_bytes, bool segmented, hipStream_t stream) {
   if (!h) return fail(AE_ERR_INVALID_ARG, "ae_gated_forward: null handle");
   if (!Q || !K || !V || !log_decay || !O) return fail(AE_ERR_INVALID_ARG, "ae_gated_forward: null pointer");
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O | (uintptr_t)h_in | (uintptr_t)h_out) & 15)
@@ -903,9 +975,39 @@ ae_status_t ae_gated_forward(const ae_gated_t* h, const void* Q, const void* K, 
   p.scale = d.scale;
   p.out_bf16 = d.out_dtype == AE_OUT_BF16;
   static const ae::DecayTable no_table = {};
-  const hipError_t e = ae::launch_gated_recurrent(p, no_table, d.D_qk, d.D_v, stream);
+  hipError_t e;
+  if (segmented && h->nseg > 1) {
+    const size_t need = gated_forward_ws(h);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)
+      return fail(AE_ERR_INVALID_ARG, "ae_gated_forward_segmented: workspace missing, not 256-byte aligned, or smaller than %zu bytes", need);
+    for (const void* in : ins)
+      if (in == workspace) return fail(AE_ERR_INVALID_ARG, "ae_gated_forward_segmented: the workspace aliases an input");
+    if (workspace == O || workspace == h_out) return fail(AE_ERR_INVALID_ARG, "ae_gated_forward_segmented: the workspace aliases an output");
+    e = launch_gated_segmented(p, no_table, d.D_qk, d.D_v, h->nseg, h->seg_len, workspace, stream);
+  } else {
+    e = ae::launch_gated_recurrent(p, no_table, d.D_qk, d.D_v, stream);
+  }
   if (e != hipSuccess) return fail(AE_ERR_HIP, "ae_gated_forward: %s", hipGetErrorString(e));
   return AE_OK;
+}
+
+extern "C" {
+
+ae_status_t ae_gated_forward(const ae_gated_t* h, const void* Q, const void* K, const void* V, const void* log_decay,
+                             const void* key_gate, const void* h_in, void* O, void* h_out, hipStream_t stream) {
+  return gated_forward_impl(h, Q, K, V, log_decay, key_gate, h_in, O, h_out, nullptr, 0, false, stream);
+}
+
+ae_status_t ae_gated_workspace_bytes(const ae_gated_t* h, size_t* bytes) {
+  if (!h || !bytes) return fail(AE_ERR_INVALID_ARG, "ae_gated_workspace_bytes: null argument");
+  *bytes = gated_forward_ws(h);
+  return AE_OK;
+}
+
+ae_status_t ae_gated_forward_segmented(const ae_gated_t* h, const void* Q, const void* K, const void* V, const void* log_decay,
+                                       const void* key_gate, const void* h_in, void* O, void* h_out, void* workspace,
+                                       size_t workspace_bytes, hipStream_t stream) {
+  return gated_forward_impl(h, Q, K, V, log_decay, key_gate, h_in, O, h_out, workspace, workspace_bytes, true, stream);
 }
 
 // Workspace of the backward pass: the per-token terms of the decay gradient, fp32 [B, H, L]; and, where value heads

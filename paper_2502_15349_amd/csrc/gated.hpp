@@ -25,7 +25,23 @@ struct GatedParams {
   // log_decay[t + 1] (0 for the last token of the sequence, which is the first of the walk).  Only the memory
   // addresses change.  This is the form the sums over later tokens of the backward pass take.
   int reverse = 0;
+  // Segments: the walk of a (batch, head) cut into nseg pieces of seg_len tokens (a multiple of 64; the last may be
+  // shorter), one workgroup each.  h_in / h_out are then [B, H, nseg, D_qk, D_v]: every segment starts from its
+  // own slot and leaves its final state in its own slot -- unless h_out_last_only, where h_out is [B, H, D_qk, D_v]
+  // and only the last segment writes.  nseg = 1: the whole sequence, the layouts above.
+  int nseg = 1;
+  int seg_len = 0;
+  int h_out_last_only = 0;
+  // state_only: no outputs -- only the state update is walked (O is not touched); seg_decay, if set, receives the
+  // sum of the segment's log-decays, fp32 [B, H, nseg]
+  int state_only = 0;
+  float* seg_decay = nullptr;
 };
+// In place on buf [B, H, nseg, D_qk x D_v] (the segments' final states from a zero start, as a state_only walk
+// leaves them): slot s becomes the state in front of segment s, given the state in front of the sequence (h_in,
+// [B, H, D_qk x D_v], or null for zero) and the segments' decays.
+hipError_t launch_gated_combine_segments(float* buf, const float* seg_decay, const float* h_in, int BH, int nseg, int state_elems,
+                                         hipStream_t stream);
 // Epilogue of the backward pass (see ae_gated_backward): per q/k head and token, over the value heads of its group,
 //   dB[h, t] = q_t . dQu[h, t] - g[h, t] (k_t . X[h, t]),   dkey_gate[h, t] = k_t . X[h, t],
 //   dQ[t] = sum_h dQu[h, t],   dK[t] = sum_h g[h, t] X[h, t]

@@ -97,16 +97,22 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
   // workgroup -> batch entry and HPW consecutive value heads of one q/k group; wave -> (head, 32 value columns,
   // query block of the chunk)
   const int hw = wave / C::WPH, wh = wave % C::WPH, vblk = wh / C::QS, ib = wh % C::QS;
-  const int bh0 = blockIdx.x * C::HPW, b = bh0 / p.H, h = bh0 % p.H + hw, bh = bh0 + hw;
+  const int seg = blockIdx.x % p.nseg;
+  const int bh0 = (blockIdx.x / p.nseg) * C::HPW, b = bh0 / p.H, h = bh0 % p.H + hw, bh = bh0 + hw;
   const int hqk = h / (p.H / p.H_qk);
-  const int64_t L = p.L;
-  const __bf16* Qh = p.Q + ((int64_t)b * p.H_qk + hqk) * L * C::DQK;
-  const __bf16* Kh = p.K + ((int64_t)b * p.H_qk + hqk) * L * C::DQK;
-  const __bf16* Vh = p.V + ((int64_t)b * p.H_v + h / (p.H / p.H_v)) * L * C::DV;
   const bool rev = p.reverse != 0;
-  const float* lah = p.log_decay ? p.log_decay + (int64_t)bh * L : nullptr;
+  // the tokens this workgroup walks: L of them from position `first` of the walk (the whole sequence unless it is
+  // cut into segments); row_lo: the one with the lowest address, where all base pointers below stand
+  const int64_t Lt = p.L, first = (int64_t)seg * p.seg_len;
+  const int64_t L = p.nseg > 1 ? min(Lt - first, (int64_t)p.seg_len) : Lt;
+  const int64_t row_lo = rev ? Lt - first - L : first;
+  const __bf16* Qh = p.Q + (((int64_t)b * p.H_qk + hqk) * Lt + row_lo) * C::DQK;
+  const __bf16* Kh = p.K + (((int64_t)b * p.H_qk + hqk) * Lt + row_lo) * C::DQK;
+  const __bf16* Vh = p.V + (((int64_t)b * p.H_v + h / (p.H / p.H_v)) * Lt + row_lo) * C::DV;
+  const float* lah = p.log_decay ? p.log_decay + (int64_t)bh * Lt + row_lo : nullptr;
   const float la_const = lah ? 0.f : dt.log2_gamma[h] * 0.6931471805599453f;  // constant decay per head: ln gamma
-  const float* gh = p.key_gate ? p.key_gate + (int64_t)bh * L : nullptr;
+  const float* gh = p.key_gate ? p.key_gate + (int64_t)bh * Lt + row_lo : nullptr;
+  const int64_t slot = (int64_t)bh * p.nseg + seg;  // of this segment's states
   const uint32_t raw0 = lds0 + C::STAGES * C::STAGE_BYTES + hw * C::RAW_BYTES;  // the head's raw gates, stage 0
   const uint32_t gate0 = lds0 + C::STAGES * (C::STAGE_BYTES + C::HPW * C::RAW_BYTES) + wave * C::GATE_BYTES;  // this wave's b[64], g[64], w[64]
   const uint32_t scrap0 = lds0 + C::LDS_BYTES - 256;
@@ -116,7 +122,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
 #pragma unroll
   for (int db = 0; db < C::DBQ; ++db) {
     if (p.h_in) {
-      const float* src = p.h_in + (int64_t)bh * C::DQK * C::DV + 32 * vblk + ln;
+      const float* src = p.h_in + slot * C::DQK * C::DV + 32 * vblk + ln;
 #pragma unroll
       for (int r = 0; r < 16; ++r) H[db][r] = src[(int64_t)(32 * db + key_offset(r) + 4 * half) * C::DV];
     } else {
@@ -179,8 +185,9 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     const uint32_t gdst = raw0 + (c % C::STAGES) * (C::HPW * C::RAW_BYTES) + (wh == 1 ? 256 : 0);
     // walking backwards: the decay of the token one later in the sequence (the walk's first token has none: its
     // word is replaced by 0 where it is read), the gate of the token itself
+    // (cut into segments, the first token of a later segment does have a successor: the word behind the segment)
     int gi = min(t0 + lane, (int)L - 1);
-    if (rev) gi = wh == 0 ? min((int)L - 1 - gi + 1, (int)L - 1) : (int)L - 1 - gi;
+    if (rev) gi = wh == 0 ? min((int)L - gi, first > 0 ? (int)L : (int)L - 1) : (int)L - 1 - gi;
     const uint32_t goff = grow ? (uint32_t)gi * 4u : 0u;
     dma4(grow ? (const void*)grow : (const void*)Qh, goff, grow ? gdst : scrap0);
   };
@@ -211,6 +218,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
 #pragma unroll
   for (int j = 0; j < 2; ++j) vt0[j] = 2 * C::Q_BYTES + hw * C::V_BYTES + tr_lane(std::integral_constant<int, C::CPRV>{}, vblk, j);
 
+  float seg_b = 0.f;  // sum of the log-decays walked so far
   issue_chunk(0);
   if (n_chunks > 1) issue_chunk(1);
 
@@ -254,9 +262,10 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     // landed and every wave is done with chunk c - 1, whose stage chunk c + 2 may now overwrite.
     {
       const bool nxt = c + 1 < n_chunks, prv = c > 0;
-      if (nxt && prv) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NDMA + C::NST) : "memory");
+      const bool st = prv && !p.state_only;  // (a walk that only updates the state stores nothing)
+      if (nxt && st) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NDMA + C::NST) : "memory");
       else if (nxt) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NDMA) : "memory");
-      else if (prv) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NST) : "memory");
+      else if (st) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::NST) : "memory");
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       asm volatile("s_barrier" ::: "memory");
     }
@@ -269,7 +278,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
       const uint32_t raw = raw0 + (c % C::STAGES) * (C::HPW * C::RAW_BYTES) + lane * 4;
       la = lah ? fmaxf(*reinterpret_cast<__attribute__((address_space(3))) const float*>((lds_char*)(uintptr_t)raw), -20.f) : la_const;
       g = gh ? *reinterpret_cast<__attribute__((address_space(3))) const float*>((lds_char*)(uintptr_t)(raw + 256)) : 1.f;
-      if (rev && t0 + lane == 0) la = lah ? 0.f : la;  // (a constant decay is the same for every token: nothing to shift)
+      if (rev && t0 + lane == 0 && first == 0) la = lah ? 0.f : la;  // (a constant decay is the same for every token: nothing to shift)
     }
     // the gate as a factor on the output rows instead of the keys: the two query tokens of this lane
     float og0 = 1.f, og1 = 1.f;
@@ -402,7 +411,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[r] *= og;
         }
-        const int64_t e0 = ((int64_t)bh * L + (rev ? L - 1 - i : i)) * C::DV + 32 * vblk + 4 * half;
+        const int64_t e0 = ((int64_t)bh * Lt + row_lo + (rev ? L - 1 - i : i)) * C::DV + 32 * vblk + 4 * half;
         if (p.out_bf16) {
 #pragma unroll
           for (int a = 0; a < 4; ++a) {
@@ -420,8 +429,15 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     }
 
     };
-    if (C::QS == 1 || ib == 0) query_block(std::integral_constant<int, 0>{});
-    if (C::QS == 1 || ib == 1) query_block(std::integral_constant<int, 1>{});
+    if (!p.state_only) {
+      if (C::QS == 1 || ib == 0) query_block(std::integral_constant<int, 0>{});
+      if (C::QS == 1 || ib == 1) query_block(std::integral_constant<int, 1>{});
+    } else {
+      // (the V fragments that a query block would have left behind for the update)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) vf[s] = v_tr_frag(s);
+    }
+    seg_b += b_last;
 
     // ---- state update: H (already e^{b_last} times the old state) += K^T (w . V) ----
     f32x4 wv[8];
@@ -445,8 +461,9 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     }
   }
 
-  if (p.h_out && ib == 0) {  // (the slab's other copy is identical)
-    float* dst = p.h_out + (int64_t)bh * C::DQK * C::DV + 32 * vblk + ln;
+  if (p.seg_decay && wh == 0 && lane == 0) p.seg_decay[slot] = seg_b;
+  if (p.h_out && ib == 0 && (!p.h_out_last_only || seg == p.nseg - 1)) {  // (the slab's other copy is identical)
+    float* dst = p.h_out + (p.h_out_last_only ? (int64_t)bh : slot) * C::DQK * C::DV + 32 * vblk + ln;
 #pragma unroll
     for (int db = 0; db < C::DBQ; ++db)
 #pragma unroll
@@ -457,8 +474,23 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
 template <int DQK, int DV, int HPW = 1, int QS = 2>
 hipError_t launch(const GatedParams& p, const DecayTable& dt, hipStream_t s) {
   typedef GCfg<DQK, DV, HPW, QS> C;
-  hipLaunchKernelGGL(gated_recurrent_kernel<C>, dim3((unsigned)(p.B * p.H / HPW)), dim3(C::THREADS), 0, s, p, dt);
+  hipLaunchKernelGGL(gated_recurrent_kernel<C>, dim3((unsigned)(p.B * p.H / HPW * p.nseg)), dim3(C::THREADS), 0, s, p, dt);
   return hipGetLastError();
+}
+
+// ---- segments: from the final states of the segments (each from a zero start) to the states in front of them ----
+__global__ __launch_bounds__(256) void gated_combine_segments_kernel(float* buf, const float* seg_decay, const float* h_in, int nseg,
+                                                                      int state_elems) {
+  const int64_t bh = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= state_elems) return;
+  float x = h_in ? h_in[bh * state_elems + e] : 0.f;
+  for (int s = 0; s < nseg; ++s) {
+    float* slot = buf + (bh * nseg + s) * state_elems + e;
+    const float local = *slot;
+    *slot = x;
+    x = __expf(seg_decay[bh * nseg + s]) * x + local;
+  }
 }
 
 // ---- epilogue of the backward pass ----
@@ -541,6 +573,14 @@ __global__ __launch_bounds__(64) void gated_bwd_suffix_sum_kernel(const GatedBwd
 
 }  // namespace
 
+hipError_t launch_gated_combine_segments(float* buf, const float* seg_decay, const float* h_in, int BH, int nseg, int state_elems,
+                                         hipStream_t s) {
+  if (BH < 1 || BH > 65535 || nseg < 1 || state_elems < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gated_combine_segments_kernel, dim3((unsigned)((state_elems + 255) / 256), (unsigned)BH), dim3(256), 0, s, buf,
+                     seg_decay, h_in, nseg, state_elems);
+  return hipGetLastError();
+}
+
 hipError_t launch_gated_backward_epilogue(const GatedBwdEpilogueParams& p, int dqk, hipStream_t s) {
   const int tpb = 4 * (64 / (dqk / 4));
   const int64_t grid = (int64_t)p.B * p.H_qk * (((int64_t)p.L + tpb - 1) / tpb);
@@ -559,6 +599,9 @@ hipError_t launch_gated_recurrent(const GatedParams& p_in, const DecayTable& dt,
   GatedParams p = p_in;
   if (p.H_v == 0) p.H_v = p.H;
   if (p.H_qk < 1 || p.H % p.H_qk != 0 || p.H % p.H_v != 0) return hipErrorInvalidValue;
+  if (p.nseg < 1 || (p.nseg > 1 && (p.seg_len < 64 || p.seg_len % 64 != 0 || (int64_t)(p.nseg - 1) * p.seg_len >= p.L)))
+    return hipErrorInvalidValue;
+  if ((int64_t)p.B * p.H * p.nseg > 0x7fffffffLL) return hipErrorInvalidValue;
   if (dqk == 64 && dv == 64) return launch<64, 64>(p, dt, s);
   if (dqk == 128 && dv == 64) {
     // value heads that share their q/k head (Mamba2's groups) share the Q and K tiles of a workgroup, two at a time

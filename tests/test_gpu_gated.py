@@ -39,10 +39,10 @@ def inputs(cid, B, H, H_qk, L, dqk, dv, kind):
     return Q, K, V, la, kg
 
 
-def run(A, Q, K, V, la, kg, scale, h_in=None, want_state=False):
+def run(A, Q, K, V, la, kg, scale, h_in=None, want_state=False, segmented=False):
     dev = torch.device("cuda:0")
     r = A.gated_recurrent(Q.to(dev), K.to(dev), V.to(dev), la.to(dev), None if kg is None else kg.to(dev), scale=scale,
-                          h_in=None if h_in is None else h_in.to(dev), want_state=want_state)
+                          h_in=None if h_in is None else h_in.to(dev), want_state=want_state, segmented=segmented)
     torch.cuda.synchronize()
     return r
 
@@ -108,6 +108,39 @@ def test_strong_decay_and_no_decay(A):
     got = run(A, Q, K, V, la, None, 0.125)
     ref = oracle_gated(Q.float().numpy(), K.float().numpy(), V.float().numpy(), la.numpy(), None, scale=0.125)
     check(got.cpu().double().numpy(), ref, "decay e^-8 / none / resets")
+
+
+@pytest.mark.parametrize("dqk,dv,H,H_qk", [(128, 128, 2, 2), (64, 64, 3, 3), (128, 64, 4, 1), (64, 128, 2, 2)])
+@pytest.mark.parametrize("kind", ["gated_retention", "mamba2"])
+@pytest.mark.parametrize("L", [1061, 2560])
+def test_segmented_walk(A, dqk, dv, H, H_qk, kind, L):
+    # few heads, a long sequence: ae_gated_forward_segmented cuts the walks into segments (2 and 5 here; a ragged
+    # last one), with a state handed in and the final state handed back; against the oracle's single walk
+    Q, K, V, la, kg = inputs(820 + L % 5, 1, H, H_qk, L, dqk, dv, kind)
+    g = torch.Generator().manual_seed(77)
+    h0 = torch.randn((1, H, dqk, dv), generator=g, dtype=torch.float32)
+    scale = 1.0 / math.sqrt(dqk)
+    dev = torch.device("cuda:0")
+    h = A.ae_gated_create(B=1, H=H, H_qk=H_qk, L=L, D_qk=dqk, D_v=dv, scale=scale)
+    assert A.ae_gated_workspace_bytes(h) > 0          # this shape is cut
+    A.ae_gated_destroy(h)
+    o, hN = run(A, Q, K, V, la, kg, scale, h_in=h0, want_state=True, segmented=True)
+    ref, ref_h = oracle_gated(Q.float().numpy(), K.float().numpy(), V.float().numpy(), la.numpy(), None if kg is None else kg.numpy(),
+                              scale=scale, h0=h0.double().numpy(), return_state=True)
+    check(o.cpu().double().numpy(), ref, f"segmented {kind} {dqk}/{dv} L={L}")
+    hs = np.maximum(np.abs(ref_h).max(axis=-1, keepdims=True), 1.0)
+    assert (np.abs(hN.cpu().double().numpy() - ref_h) / hs).max() <= MAX_ABS
+
+
+def test_segmented_entry_point_on_a_shape_that_is_not_cut(A):
+    # many heads or a short sequence: no workspace, and the bits of ae_gated_forward
+    Q, K, V, la, kg = inputs(830, 2, 3, 3, 300, 64, 64, "mamba2")
+    h = A.ae_gated_create(B=2, H=3, H_qk=3, L=300, D_qk=64, D_v=64, scale=0.125)
+    assert A.ae_gated_workspace_bytes(h) == 0
+    A.ae_gated_destroy(h)
+    a = run(A, Q, K, V, la, kg, 0.125)
+    b = run(A, Q, K, V, la, kg, 0.125, segmented=True)
+    assert torch.equal(a, b)
 
 
 def test_sampled_heads_at_benchmark_size(A):
