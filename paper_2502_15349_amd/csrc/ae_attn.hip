@@ -1012,15 +1012,20 @@ ae_status_t ae_gated_forward_segmented(const ae_gated_t* h, const void* Q, const
 
 // Workspace of the backward pass: the per-token terms of the decay gradient, fp32 [B, H, L]; and, where value heads
 // share q/k heads, the gradients of q and of the gated key per value head, fp32 [B, H, L, D_qk] each.
-static size_t gated_backward_ws(const ae_gated_desc_t& d, size_t* per_head_off) {
+// Where the forward pass would cut the walks into segments, so do the three walks of the backward pass: the segments'
+// states (one set, used by the walks in turn) follow.
+static size_t gated_backward_ws(const ae_gated* h, size_t* per_head_off, size_t* seg_off) {
+  const ae_gated_desc_t& d = h->desc;
   const size_t rows = ((size_t)d.B * d.H * d.L * 4 + 255) & ~(size_t)255;
+  const size_t per_head = d.H != d.H_qk ? 2 * (size_t)d.B * d.H * d.L * d.D_qk * 4 : 0;
   if (per_head_off) *per_head_off = rows;
-  return rows + (d.H != d.H_qk ? 2 * (size_t)d.B * d.H * d.L * d.D_qk * 4 : 0);
+  if (seg_off) *seg_off = rows + per_head;
+  return rows + per_head + gated_segments_ws(d.B, d.H, h->nseg, d.D_qk, d.D_v);
 }
 
 ae_status_t ae_gated_backward_workspace_bytes(const ae_gated_t* h, size_t* bytes) {
   if (!h || !bytes) return fail(AE_ERR_INVALID_ARG, "ae_gated_backward_workspace_bytes: null argument");
-  *bytes = gated_backward_ws(h->desc, nullptr);
+  *bytes = gated_backward_ws(h, nullptr, nullptr);
   return AE_OK;
 }
 
@@ -1037,8 +1042,14 @@ ae_status_t ae_gated_backward(const ae_gated_t* h, const void* Q, const void* K,
   if (((uintptr_t)log_decay | (uintptr_t)key_gate | (uintptr_t)dlog_decay | (uintptr_t)dkey_gate) & 3)
     return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: the gates and their gradients must be 4-byte aligned");
   const ae_gated_desc_t& d = h->desc;
-  size_t per_head_off = 0;
-  const size_t need = gated_backward_ws(d, &per_head_off);
+  size_t per_head_off = 0, seg_off = 0;
+  const size_t need = gated_backward_ws(h, &per_head_off, &seg_off);
+  void* seg_ws = static_cast<char*>(workspace) + seg_off;
+  auto walk = [&](const ae::GatedParams& g, int dqk, int dv) {
+    static const ae::DecayTable none = {};
+    return h->nseg > 1 ? launch_gated_segmented(g, none, dqk, dv, h->nseg, h->seg_len, seg_ws, stream)
+                       : ae::launch_gated_recurrent(g, none, dqk, dv, stream);
+  };
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)
     return fail(AE_ERR_INVALID_ARG, "ae_gated_backward: workspace missing, not 256-byte aligned, or smaller than %zu bytes", need);
   const void* ins[] = {Q, K, V, log_decay, key_gate, dO};
@@ -1075,7 +1086,7 @@ ae_status_t ae_gated_backward(const ae_gated_t* h, const void* Q, const void* K,
   p.gate_on_output = 0;
   p.reverse = 0;
   p.O = dQu;
-  hipError_t e = ae::launch_gated_recurrent(p, no_table, d.D_v, d.D_qk, stream);
+  hipError_t e = walk(p, d.D_v, d.D_qk);
   // (2) x_j = scale sum_{i >= j} A_ij (v_j . dO_i) q_i, walking backwards: queries V, keys dO, values Q, no gate
   if (e == hipSuccess) {
     p.Q = static_cast<const __bf16*>(V);
@@ -1084,7 +1095,7 @@ ae_status_t ae_gated_backward(const ae_gated_t* h, const void* Q, const void* K,
     p.key_gate = nullptr;
     p.reverse = 1;
     p.O = X;
-    e = ae::launch_gated_recurrent(p, no_table, d.D_v, d.D_qk, stream);
+    e = walk(p, d.D_v, d.D_qk);
   }
   // (3) dv_j = g_j scale sum_{i >= j} A_ij (k_j . q_i) dO_i, walking backwards: queries K, keys Q, values dO
   if (e == hipSuccess) {
@@ -1096,7 +1107,7 @@ ae_status_t ae_gated_backward(const ae_gated_t* h, const void* Q, const void* K,
     p.key_gate = static_cast<const float*>(key_gate);
     p.gate_on_output = key_gate ? 1 : 0;
     p.O = dV;
-    e = ae::launch_gated_recurrent(p, no_table, d.D_qk, d.D_v, stream);
+    e = walk(p, d.D_qk, d.D_v);
   }
   if (e == hipSuccess) {
     ae::GatedBwdEpilogueParams q;

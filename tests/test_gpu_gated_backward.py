@@ -11,15 +11,19 @@ column j, dkey_gate_j = k_j . dk_j / g_j, and dlog_decay_t = sum_{i >= t} (q_i .
 column sums come out of different runs of the kernel, each of which rounds its weights (and the carried state, and
 the weighted values that update it) to bf16: every term G_ij carries an independent relative error of up to 2^-9
 per rounding, about 2^-9 in standard deviation for the three together.  A sum of such terms is off by 2^-9 times the
-root of the sum of their squares, and for terms of random sign that root is about the size of the sum itself -- or,
-where a sum happens to cancel, about the size such sums have elsewhere in the head.  With [x]_i = max(|x_i|, rms of
-x over the head) standing in for that root,
-    dkey_gate_j   is held to  6 x 2^-9 x [dkey_gate]_j,
-    dlog_decay_t  is held to  6 x 2^-9 x sqrt(sum_{i >= t} ([q . dq]_i^2 + [k . dk]_i^2))   (+ 1e-3 absolute),
-six standard deviations of that model (the stand-in for the root of the sum of squares is itself only right to a
-factor of about 1.5), with the dot products taken from the oracle.  The errors of unrelated pairs (i, j >= t) do
-not cancel in the suffix sum as their exact values do, which is why the bar grows with the root of the number of
-later tokens; an implementation that forms both sums from one set of rounded weights would not need that.
+root of the sum of their squares.  The tests form G from the inputs (its entries are what the model needs, not an
+expected value) and hold
+    dkey_gate_j   to  3 x 2^-9 x sum_i |G_ij| / g_j                                         (+ 1e-4 absolute),
+    dlog_decay_t  to  8 x 2^-9 x sqrt(sum_{i >= t} (sum_j G_ij^2 + sum_j G_ji^2))           (+ 1e-3 absolute).
+The first is the worst case of the three roundings (a column of G has few terms of weight, and the rounded state and
+the rounded weighted values are shared by many of them, so their errors add up coherently rather than at random).
+The second is eight standard deviations of the model: a long sum over many tokens, near enough to Gaussian, with
+the same shared roundings fattening its tails (measured: the mean error is 0.8 standard deviations, as the model
+says; the worst of some 10^5 tokens 7.1).  At the benchmark size, where G does not fit, the root of a sum of squares is
+replaced by max(|sum|, rms of such sums over the head): for terms of random sign the two are of one size.  The errors
+of unrelated pairs (i, j >= t) do not cancel in the suffix sum as their exact values do, which is why the bar grows
+with the root of the number of later tokens; an implementation that forms both sums from one set of rounded weights
+would not need that.
 """
 import math
 
@@ -77,27 +81,36 @@ def check_tokens(got, bound, ref, what):
     assert ratio.max() <= 1.0, (what, ratio.max())
 
 
-def token_bounds(qdq, kdk, dkg):
-    """qdq, kdk: the oracle's q_i . dq_i and k_i . dk_i per value head [.., L]; dkg: its dkey_gate.  Returns the bars of
-    dlog_decay and dkey_gate described at the top."""
+def token_bounds_proxy(qdq, kdk):
+    """The bar of dlog_decay where G is too large to form: qdq, kdk are the oracle's q_i . dq_i and k_i . dk_i [L]."""
     def floored(x):
         return np.maximum(np.abs(x), np.sqrt(np.mean(x ** 2, axis=-1, keepdims=True)))
-    tail = np.sqrt(np.cumsum((floored(qdq) ** 2 + floored(kdk) ** 2)[..., ::-1], axis=-1)[..., ::-1])
-    return 6 * U * tail + 1e-3, 6 * U * floored(dkg) + 1e-6
+    return 8 * U * np.sqrt(np.cumsum((floored(qdq) ** 2 + floored(kdk) ** 2)[..., ::-1], axis=-1)[..., ::-1]) + 1e-3
 
 
-def head_dots(Q, K, V, la, kg, dO, scale):
-    """q . dq and k . dk per VALUE head from the oracle (the grouped sums dQ, dK do not give them)."""
-    B, H, L = la.shape
+def head_bounds(q, k, v, la, g, dO, scale):
+    """One value head: G_ij = P_ij dP_ij from the inputs, and from it the bars of dlog_decay and dkey_gate [L]."""
+    L = q.shape[0]
+    B = np.cumsum(la)
+    expo = B[:, None] - B[None, :]
+    A = np.where(np.tril(np.ones((L, L), dtype=bool)), np.exp(np.minimum(expo, 0.0)), 0.0)
+    gg = np.ones(L) if g is None else g
+    G = scale * A * (q @ k.T) * gg[None, :] * (dO @ v.T)
+    row2, col2 = np.sum(G * G, axis=1), np.sum(G * G, axis=0)
+    b_dla = 8 * U * np.sqrt(np.cumsum((row2 + col2)[::-1])[::-1]) + 1e-3
+    b_dkg = 3 * U * np.sum(np.abs(G), axis=0) / np.abs(gg) + 1e-4
+    return b_dla, b_dkg
+
+
+def all_bounds(Q, K, V, la, kg, dO, scale):
+    Bn, H, L = la.shape
     grp = H // Q.shape[1]
-    qdq, kdk = np.zeros((B, H, L)), np.zeros((B, H, L))
-    for b in range(B):
+    b_dla, b_dkg = np.zeros((Bn, H, L)), np.zeros((Bn, H, L))
+    for b in range(Bn):
         for h in range(H):
-            r = gated_recurrent_backward_head(Q[b, h // grp], K[b, h // grp], V[b, h], la[b, h], None if kg is None else kg[b, h],
-                                              dO[b, h], scale=scale)
-            qdq[b, h] = np.sum(Q[b, h // grp] * r["dq"], axis=-1)
-            kdk[b, h] = np.sum(K[b, h // grp] * r["dk"], axis=-1)
-    return qdq, kdk
+            b_dla[b, h], b_dkg[b, h] = head_bounds(Q[b, h // grp], K[b, h // grp], V[b, h], la[b, h], None if kg is None else kg[b, h],
+                                                   dO[b, h], scale)
+    return b_dla, b_dkg
 
 
 def compare(got, ref, what, with_gate, dots):
@@ -105,7 +118,7 @@ def compare(got, ref, what, with_gate, dots):
     check_rows(dQ, ref["dQ"], what + " dQ")
     check_rows(dK, ref["dK"], what + " dK")
     check_rows(dV, ref["dV"], what + " dV")
-    b_dla, b_dkg = token_bounds(dots[0], dots[1], ref["dkey_gate"])
+    b_dla, b_dkg = dots
     check_tokens(dla, b_dla, ref["dlog_decay"], what + " dlog_decay")
     if with_gate:
         check_tokens(dkg, b_dkg, ref["dkey_gate"], what + " dkey_gate")
@@ -116,7 +129,7 @@ def compare(got, ref, what, with_gate, dots):
 def oracle_all(Q, K, V, la, kg, dO, scale):
     n = [Q.float().numpy().astype(np.float64), K.float().numpy().astype(np.float64), V.float().numpy().astype(np.float64),
          la.numpy().astype(np.float64), None if kg is None else kg.numpy().astype(np.float64), dO.float().numpy().astype(np.float64)]
-    return oracle_backward(*n, scale=scale), head_dots(*n, scale)
+    return oracle_backward(*n, scale=scale), all_bounds(*n, scale)
 
 
 @pytest.mark.parametrize("dqk,dv", [(64, 64), (128, 64), (64, 128), (128, 128)])
@@ -139,6 +152,18 @@ def test_grouped_query_key_heads(A, dqk, dv):
     got = run(A, Q, K, V, la, kg, dO, 1.0)
     ref, dots = oracle_all(Q, K, V, la, kg, dO, 1.0)
     compare(got, ref, f"mamba2 groups {dqk}/{dv}", True, dots)
+
+
+@pytest.mark.parametrize("dqk,dv,H,H_qk", [(128, 128, 2, 2), (64, 64, 3, 3), (128, 64, 4, 1)])
+@pytest.mark.parametrize("kind", ["gated_retention", "mamba2"])
+@pytest.mark.parametrize("L", [1061, 2560])
+def test_few_heads_long_sequence(A, dqk, dv, H, H_qk, kind, L):
+    # shapes whose walks the library cuts into segments (2 and 5 here, a ragged last one), forwards and backwards
+    Q, K, V, la, kg, dO = inputs(920 + L % 5, 1, H, H_qk, L, dqk, dv, kind)
+    scale = 1.0 / math.sqrt(dqk)
+    got = run(A, Q, K, V, la, kg, dO, scale)
+    ref, dots = oracle_all(Q, K, V, la, kg, dO, scale)
+    compare(got, ref, f"segments {kind} {dqk}/{dv} L={L}", kg is not None, dots)
 
 
 def test_strong_decay_and_no_decay(A):
@@ -169,5 +194,5 @@ def test_sampled_heads_at_benchmark_size(A):
         check_rows(dK[b, h], ref["dk"], f"benchmark size ({b},{h}) dK")
         check_rows(dV[b, h], ref["dv"], f"benchmark size ({b},{h}) dV")
         qn, kn = Q[b, h].float().numpy().astype(np.float64), K[b, h].float().numpy().astype(np.float64)
-        b_dla, _ = token_bounds(np.sum(qn * ref["dq"], axis=-1), np.sum(kn * ref["dk"], axis=-1), ref["dkey_gate"])
+        b_dla = token_bounds_proxy(np.sum(qn * ref["dq"], axis=-1), np.sum(kn * ref["dk"], axis=-1))
         check_tokens(dla[b, h], b_dla, ref["dlog_decay"], f"benchmark size ({b},{h}) dlog_decay")
