@@ -170,7 +170,7 @@ def main():
                     help="time the recurrent pattern (chunk-parallel retention, ae_recurrent_forward) per chunk size, beside "
                          "the parallel form of the same sum; prints one JSON object with a row per shape")
     ap.add_argument("--gated", action="store_true",
-                    help="time the recurrent pattern with per-token gates (ae_gated_forward: gated retention, Mamba2 SSM, "
+                    help="time the recurrent pattern with per-token gates (ae_gated_forward; with --backward: ae_gated_backward; gated retention, Mamba2 SSM, "
                          "retention with a constant decay) on Table 2's recurrent shapes; GB/s against the HBM peak")
     ap.add_argument("--only", default="", help="with --backward: only the shapes whose name contains this")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MiB",
@@ -187,7 +187,10 @@ def main():
     if a.profile:
         # No GPU call is made in this process: every pass is a child process under rocprofv3.
         from paper_2502_15349_amd.rocprof_harness import profile
-        if a.backward:
+        if a.gated and a.backward:
+            child, name = ["--gated", "--backward", "--only", a.only], f"gated_recurrent_bwd_{a.only or 'all'}"
+            trace_args, pmc_args = ("--steps", "10"), ("--steps", "2")
+        elif a.backward:
             child, name = ["--backward", "--only", a.only], f"attn_bwd_{a.only or 'all'}"
             trace_args = pmc_args = ()
         elif a.gated:
@@ -301,7 +304,7 @@ def main():
                       file=sys.stderr, flush=True)
         print(json.dumps({"decode": rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16", "data": "synthetic"}))
         return
-    if a.backward:
+    if a.backward and not a.gated:
         # Not the contract line.  Algorithmic work of the backward pass: five contractions per visible (query, key)
         # pair (S, dP, dV, dK, dQ) = 2 * (3 D_qk + 2 D_v) flop; the key-side and the query-side kernel each recompute
         # S and dP, so the MFMAs they issue amount to 2 * (4 D_qk + 3 D_v) flop per pair.
@@ -610,83 +613,77 @@ def main():
             st = torch.cuda.current_stream()
             args = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), la.data_ptr(), 0 if kg is None else kg.data_ptr(), 0, O.data_ptr(), 0,
                     st.cuda_stream)
-            for _ in range(3):
-                A.ae_gated_forward(*args)
-            torch.cuda.synchronize()
+            # --gated times the forward pass, --gated --backward the backward pass: one kind of launch per run, so that a
+            # profile of the run speaks of one of them
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(st)
-            for _ in range(a.steps):
-                A.ae_gated_forward(*args)
-            e1.record(st)
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / a.steps
-            # few heads, long sequence: the same call with the walks cut into segments (ae_gated_forward_segmented)
-            seg_ms = None
-            nfw = A.ae_gated_workspace_bytes(h)
-            if nfw:
-                fws = torch.empty(nfw, dtype=torch.uint8, device=dev)
-                O2 = torch.empty_like(O)
-                sargs = args[:7] + (O2.data_ptr(), 0, fws.data_ptr(), nfw, st.cuda_stream)
-                for _ in range(3):
-                    A.ae_gated_forward_segmented(*sargs)
+
+            def timed(call, n_warm):
+                for _ in range(n_warm):
+                    call()
                 torch.cuda.synchronize()
                 e0.record(st)
                 for _ in range(a.steps):
-                    A.ae_gated_forward_segmented(*sargs)
+                    call()
                 e1.record(st)
                 torch.cuda.synchronize()
-                seg_ms = e0.elapsed_time(e1) / a.steps
-                seg_diff = float((O2 - O).abs().max())
-                del fws, O2
-            # the backward pass (ae_gated_backward: dQ, dK, dV, dlog_decay, dkey_gate), same handle; compulsory bytes:
-            # Q, K, V, dO and the gates read once, the gradients (fp32) written once
-            from paper_2502_15349_amd.workloads import make_grad
-            dO = make_grad(Workload("v", cid, B, H, H, L, L, Dv, Dv)).to(dev)
-            f32 = dict(dtype=torch.float32, device=dev)
-            dQ, dK, dV = torch.empty(Q.shape, **f32), torch.empty(K.shape, **f32), torch.empty(V.shape, **f32)
-            dla = torch.empty((B, H, L), **f32)
-            dkg = None if kg is None else torch.empty((B, H, L), **f32)
-            nws = A.ae_gated_backward_workspace_bytes(h)
-            ws = torch.empty(nws, dtype=torch.uint8, device=dev)
-            bargs = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), la.data_ptr(), 0 if kg is None else kg.data_ptr(), dO.data_ptr(),
-                     dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), dla.data_ptr(), 0 if dkg is None else dkg.data_ptr(), ws.data_ptr(),
-                     nws, st.cuda_stream)
-            for _ in range(2):
-                A.ae_gated_backward(*bargs)
-            torch.cuda.synchronize()
-            e0.record(st)
-            for _ in range(a.steps):
-                A.ae_gated_backward(*bargs)
-            e1.record(st)
-            torch.cuda.synchronize()
-            bwd_ms = e0.elapsed_time(e1) / a.steps
+                return e0.elapsed_time(e1) / a.steps
+
             ngate = 2 if kg is not None else 1
-            bwd_byts = B * L * (Hqk * Dq * (2 * 2 + 2 * 4) + H * Dv * (2 + 2 + 4) + H * 8 * ngate)
-            del dO, dQ, dK, dV, dla, dkg, ws
+            row = {"workload": name, "B": B, "H": H, "H_qk": Hqk, "L": L, "D_qk": Dq, "D_v": Dv}
+            if not a.backward:
+                ms = timed(lambda: A.ae_gated_forward(*args), 3)
+                b_s, h_s = B - 1, H // 2
+                g_s = h_s // (H // Hqk)
+                ref = gated_recurrent_head(Qc[b_s, g_s].float().numpy(), Kc[b_s, g_s].float().numpy(), Vc[b_s, h_s].float().numpy(),
+                                           lac[b_s, h_s].numpy(), None if kgc is None else kgc[b_s, h_s].numpy(), scale=scale)
+                got = O[b_s, h_s].cpu().double().numpy()
+                err = float((np.abs(got - ref) / np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)).max())
+                # compulsory bytes: Q, K, V and the gates read once, O (fp32) written once
+                byts = B * L * (2 * 2 * Dq * Hqk + H * (2 * Dv + 4 * Dv + 4 * ngate))
+                flop = 4.0 * Dq * Dv * B * H * L
+                row.update({"ms": round(ms, 4), "tokens_per_s": round(B * L / ms * 1e3, 1), "GBps": round(byts / ms / 1e6, 1),
+                            "frac_of_hbm_peak": round(byts / ms / 1e6 / 8000.0, 4), "recurrence_tflops": round(flop / ms / 1e9, 1),
+                            "compulsory_bytes": byts, "parity_max_abs": err})
+                print(f"# {name:40s} {ms:8.4f} ms = {byts / ms / 1e6:7.1f} GB/s ({100 * byts / ms / 1e6 / 8000.0:4.1f} % of HBM peak), "
+                      f"{flop / ms / 1e9:6.1f} TFLOP/s of recurrence, max_abs {err:.2e}", file=sys.stderr, flush=True)
+                # few heads, long sequence: the same call with the walks cut into segments (ae_gated_forward_segmented)
+                nfw = A.ae_gated_workspace_bytes(h)
+                if nfw:
+                    fws = torch.empty(nfw, dtype=torch.uint8, device=dev)
+                    O2 = torch.empty_like(O)
+                    sargs = args[:7] + (O2.data_ptr(), 0, fws.data_ptr(), nfw, st.cuda_stream)
+                    seg_ms = timed(lambda: A.ae_gated_forward_segmented(*sargs), 3)
+                    seg_diff = float((O2 - O).abs().max())
+                    del fws, O2
+                    row.update({"segmented_ms": round(seg_ms, 4), "segmented_GBps": round(byts / seg_ms / 1e6, 1),
+                                "segmented_max_diff_to_single_walk": seg_diff})
+                    print(f"#   {'cut into segments':38s} {seg_ms:8.4f} ms = {byts / seg_ms / 1e6:7.1f} GB/s "
+                          f"({100 * byts / seg_ms / 1e6 / 8000.0:4.1f} % of HBM peak), max difference to the single walk {seg_diff:.2e}",
+                          file=sys.stderr, flush=True)
+            else:
+                # ae_gated_backward: dQ, dK, dV, dlog_decay, dkey_gate; compulsory bytes: Q, K, V, dO and the gates read
+                # once, the gradients (fp32) written once
+                from paper_2502_15349_amd.workloads import make_grad
+                dO = make_grad(Workload("v", cid, B, H, H, L, L, Dv, Dv)).to(dev)
+                f32 = dict(dtype=torch.float32, device=dev)
+                dQ, dK, dV = torch.empty(Q.shape, **f32), torch.empty(K.shape, **f32), torch.empty(V.shape, **f32)
+                dla = torch.empty((B, H, L), **f32)
+                dkg = None if kg is None else torch.empty((B, H, L), **f32)
+                nws = A.ae_gated_backward_workspace_bytes(h)
+                ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+                bargs = (h, Q.data_ptr(), K.data_ptr(), V.data_ptr(), la.data_ptr(), 0 if kg is None else kg.data_ptr(), dO.data_ptr(),
+                         dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), dla.data_ptr(), 0 if dkg is None else dkg.data_ptr(), ws.data_ptr(),
+                         nws, st.cuda_stream)
+                bwd_ms = timed(lambda: A.ae_gated_backward(*bargs), 2)
+                bwd_byts = B * L * (Hqk * Dq * (2 * 2 + 2 * 4) + H * Dv * (2 + 2 + 4) + H * 8 * ngate)
+                row.update({"backward_ms": round(bwd_ms, 4), "backward_GBps": round(bwd_byts / bwd_ms / 1e6, 1),
+                            "backward_frac_of_hbm_peak": round(bwd_byts / bwd_ms / 1e6 / 8000.0, 4),
+                            "backward_compulsory_bytes": bwd_byts, "workspace_bytes": nws})
+                print(f"# {name:40s} backward {bwd_ms:8.4f} ms = {bwd_byts / bwd_ms / 1e6:7.1f} GB/s "
+                      f"({100 * bwd_byts / bwd_ms / 1e6 / 8000.0:4.1f} % of HBM peak)", file=sys.stderr, flush=True)
+                del dO, dQ, dK, dV, dla, dkg, ws
+            rows.append(row)
             A.ae_gated_destroy(h)
-            b_s, h_s = B - 1, H // 2
-            g_s = h_s // (H // Hqk)
-            ref = gated_recurrent_head(Qc[b_s, g_s].float().numpy(), Kc[b_s, g_s].float().numpy(), Vc[b_s, h_s].float().numpy(),
-                                       lac[b_s, h_s].numpy(), None if kgc is None else kgc[b_s, h_s].numpy(), scale=scale)
-            got = O[b_s, h_s].cpu().double().numpy()
-            err = float((np.abs(got - ref) / np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1.0)).max())
-            byts = B * L * (2 * 2 * Dq * Hqk + H * (2 * Dv + 4 * Dv + (8 if kg is not None else 4)))
-            flop = 4.0 * Dq * Dv * B * H * L
-            rows.append({"workload": name, "B": B, "H": H, "H_qk": Hqk, "L": L, "D_qk": Dq, "D_v": Dv, "ms": round(ms, 4),
-                         "tokens_per_s": round(B * L / ms * 1e3, 1), "GBps": round(byts / ms / 1e6, 1),
-                         "frac_of_hbm_peak": round(byts / ms / 1e6 / 8000.0, 4), "recurrence_tflops": round(flop / ms / 1e9, 1),
-                         "compulsory_bytes": byts, "parity_max_abs": err, "backward_ms": round(bwd_ms, 4),
-                         "backward_GBps": round(bwd_byts / bwd_ms / 1e6, 1), "backward_frac_of_hbm_peak": round(bwd_byts / bwd_ms / 1e6 / 8000.0, 4),
-                         "backward_compulsory_bytes": bwd_byts})
-            print(f"# {name:40s} {ms:8.4f} ms = {byts / ms / 1e6:7.1f} GB/s ({100 * byts / ms / 1e6 / 8000.0:4.1f} % of HBM peak), "
-                  f"{flop / ms / 1e9:6.1f} TFLOP/s of recurrence, max_abs {err:.2e} | backward {bwd_ms:8.4f} ms = "
-                  f"{bwd_byts / bwd_ms / 1e6:7.1f} GB/s ({100 * bwd_byts / bwd_ms / 1e6 / 8000.0:4.1f} %)", file=sys.stderr, flush=True)
-            if seg_ms is not None:
-                rows[-1].update({"segmented_ms": round(seg_ms, 4), "segmented_GBps": round(byts / seg_ms / 1e6, 1),
-                                 "segmented_max_diff_to_single_walk": seg_diff})
-                print(f"#   {'cut into segments':38s} {seg_ms:8.4f} ms = {byts / seg_ms / 1e6:7.1f} GB/s "
-                      f"({100 * byts / seg_ms / 1e6 / 8000.0:4.1f} % of HBM peak), max difference to the single walk {seg_diff:.2e}",
-                      file=sys.stderr, flush=True)
             del Q, K, V, O, la, kg
         print(json.dumps({"gated_recurrent": rows, "bound": "hbm", "peak_GBps": 8000.0, "dtype": "bf16", "data": "synthetic"}))
         return
@@ -819,6 +816,38 @@ def main():
                                             "frac_of_hbm_peak": round(rbytes / rms / 1e6 / 8000.0, 4),
                                             "tokens_per_s": round(wr.B * wr.L_q / rms * 1e3, 1)}
         del Qr, Kr, Vr, Or, wsr
+        # the same shape with per-token gates (gated retention: ae_gated_forward, ae_gated_backward); `bench.py --gated`
+        # and `--gated --backward` have the other shapes (Mamba2, batch 1)
+        from paper_2502_15349_amd.workloads import make_gates, make_grad
+        wg = Workload("gated_retention_b8_h32_s8192_d128", 500, 8, 32, 32, 8192, 8192, 128, 128)
+        Qg, Kg, Vg = (x.to(dev) for x in make_inputs(wg))
+        lag = make_gates(wg.B, wg.H_q, wg.L_q, 500005, "gated_retention")[0].to(dev)
+        dOg = make_grad(wg).to(dev)
+        f32 = dict(dtype=torch.float32, device=dev)
+        Og, dQg, dKg, dVg = (torch.empty(Qg.shape, **f32) for _ in range(4))
+        dlag = torch.empty(lag.shape, **f32)
+        hg = A.ae_gated_create(B=wg.B, H=wg.H_q, L=wg.L_q, D_qk=128, D_v=128, scale=1.0 / math.sqrt(128))
+        nwg = A.ae_gated_backward_workspace_bytes(hg)
+        wsg = torch.empty(nwg, dtype=torch.uint8, device=dev)
+        fargs = (hg, Qg.data_ptr(), Kg.data_ptr(), Vg.data_ptr(), lag.data_ptr(), 0, 0, Og.data_ptr(), 0, st.cuda_stream)
+        bargs = (hg, Qg.data_ptr(), Kg.data_ptr(), Vg.data_ptr(), lag.data_ptr(), 0, dOg.data_ptr(), dQg.data_ptr(), dKg.data_ptr(),
+                 dVg.data_ptr(), dlag.data_ptr(), 0, wsg.data_ptr(), nwg, st.cuda_stream)
+        for call, cargs, tag, byts in ((A.ae_gated_forward, fargs, "", wg.B * wg.H_q * wg.L_q * (2 * 3 * 128 + 4 * 128 + 4)),
+                                       (A.ae_gated_backward, bargs, "_backward", wg.B * wg.H_q * wg.L_q * (2 * 4 * 128 + 4 * 3 * 128 + 8))):
+            for _ in range(2):
+                call(*cargs)
+            torch.cuda.synchronize()
+            e0.record(st)
+            for _ in range(10):
+                call(*cargs)
+            e1.record(st)
+            torch.cuda.synchronize()
+            gms = e0.elapsed_time(e1) / 10
+            variants[wg.name + tag] = {"ms": round(gms, 5), "GBps": round(byts / gms / 1e6, 1),
+                                       "frac_of_hbm_peak": round(byts / gms / 1e6 / 8000.0, 4),
+                                       "tokens_per_s": round(wg.B * wg.L_q / gms * 1e3, 1)}
+        A.ae_gated_destroy(hg)
+        del Qg, Kg, Vg, lag, dOg, Og, dQg, dKg, dVg, dlag, wsg
         out["variants"] = variants
 
     # What the matrix pipes sustain on this board with nothing else in the way: the library's

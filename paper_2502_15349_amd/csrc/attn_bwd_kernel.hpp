@@ -90,6 +90,9 @@ __device__ __forceinline__ int bswz(int row) {
 constexpr int BWD_NORM_NONE_RELU = 5;
 enum : int { BWD_DQ = 0, BWD_DKV = 1 };  // the query-side kernel (dQ), the key-side kernel (dK and dV)
 
+#ifndef AE_BWD_OCC2_REGS
+#define AE_BWD_OCC2_REGS 176
+#endif
 template <int DQK_, int DV_, int NORM_, bool CAUSAL_, int OUT_, bool BIAS_ = false>
 struct BwdCfg {
   static constexpr bool BIAS = BIAS_;  // S' = scale * S + bias[b, h_q, i, j]
@@ -105,14 +108,17 @@ struct BwdCfg {
   // bias tensor: per stage the block of it that the tile meets, 16 KB: [128 own queries][64 keys] on the query
   // side, [64 queries][128 own keys] on the key side
   static constexpr int BIAS_BYTES = BIAS_ ? 16384 : 0;
-  static constexpr bool OCC2 = 16 * (DB + DB2) + 4 * T1 + 4 * T2 + 32 + (BIAS_ ? 8 : 0) <= 176 &&
-                               2 * 64 * (DQK + DV) * 2 + 1024 + 2 * BIAS_BYTES <= 80 * 1024;
+  // (row quantities pass through LDS on the key side only, see ROW_BYTES)
+  static constexpr bool OCC2 = 16 * (DB + DB2) + 4 * T1 + 4 * T2 + 32 + (BIAS_ ? 8 : 0) <= AE_BWD_OCC2_REGS &&
+                               2 * 64 * (DQK + DV) * 2 + (KV_SIDE ? 1024 : 0) + 2 * BIAS_BYTES <= 80 * 1024;
   // one workgroup per CU: the LDS fragments of a step are read as a batch ahead of its MFMAs
   static constexpr bool BATCH = !OCC2 && DQK + DV <= 320;  // (beyond that the batches do not fit 512 registers)
   static constexpr int TILE = 64;  // other-side rows per LDS tile (two 32-row sub-tiles)
   static constexpr int RB1 = DQK * 2, RB2 = DV * 2, CPR1 = DQK / 8, CPR2 = DV / 8;
   static constexpr int Y1_BYTES = TILE * RB1, Y2_BYTES = TILE * RB2, STAGE_BYTES = Y1_BYTES + Y2_BYTES;
-  static constexpr int ROW_BYTES = 2 * TILE * 4;  // per stage: bias*log2(e) - lse*log2(e) and delta of the tile's rows
+  // per stage: bias*log2(e) - lse*log2(e) and delta of the tile's rows (key side: they belong to the registers' rows;
+  // on the query side they belong to the lane's own row and stay in registers)
+  static constexpr int ROW_BYTES = KV_SIDE ? 2 * TILE * 4 : 0;
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES + 2 * ROW_BYTES + 2 * BIAS_BYTES;
   static_assert(NORM == NORM_SOFTMAX || NORM == NORM_SIGMOID || NORM == NORM_NONE || NORM == BWD_NORM_NONE_RELU ||
                     NORM == NORM_ABSSUM || NORM == NORM_ABS_OF_SUM,
