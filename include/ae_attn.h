@@ -423,7 +423,7 @@ ae_status_t ae_gated_forward(const ae_gated_t *h, const void *Q, const void *K, 
 /* The same call for few (batch, head) pairs and long sequences.  One workgroup
  * walks a (batch, head) from the first token to the last, so B x H of them keep
  * B x H compute units busy, however long L is.  Where that leaves most of the
- * chip idle (create decides: fewer than 128 workgroups and L >= 1024) this entry
+ * chip idle (create decides: fewer than 192 workgroups and L >= 1024) this entry
  * point cuts every walk into segments (Section 4.2: parallelism over chunks of
  * the sequence): all segments are walked side by side for their final states from
  * a zero start, a small kernel chains those into the state in front of every

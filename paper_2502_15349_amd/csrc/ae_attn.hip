@@ -644,7 +644,7 @@ int32_t ae_attn_version(void) { return 1; }
 static void gated_segments(int64_t workgroups, int L, int* nseg, int* seg_len) {
   *nseg = 1;
   *seg_len = 0;
-  if (workgroups >= 128 || L < 1024) return;
+  if (workgroups >= 192 || L < 1024) return;
   int64_t n = std::min<int64_t>((256 + workgroups - 1) / workgroups, L / 512);
   if (n < 2) return;
   const int len = (int)(((L + n - 1) / n + 63) / 64 * 64);
