@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libae_attn.so")
 
-SOURCES = ["ae_attn.hip", "attn_bwd.hip", "attn_bwd_64_64.hip", "attn_bwd_128_128.hip", "attn_bwd_192_128.hip",
+SOURCES = ["ae_attn.hip", "attn_decode.hip", "attn_bwd.hip", "attn_bwd_64_64.hip", "attn_bwd_128_128.hip", "attn_bwd_192_128.hip",
            "attn_bwd_128_256.hip", "retention_recurrent.hip", "gated_recurrent.hip", "calib.hip", "inst_64_64.hip", "inst_128_128.hip", "inst_128_256.hip", "inst_192_128.hip", "inst_256_128.hip"]
 
 HIPCC_FLAGS = [

@@ -13,6 +13,7 @@
 
 #include "bwd.hpp"
 #include "dispatch.hpp"
+#include "attn_decode.hpp"
 #include "gated.hpp"
 #include "recurrent.hpp"
 
@@ -83,18 +84,38 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MergeParams p) {
   const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // one wavefront per row
   if (r >= rows) return;
   const int lane = threadIdx.x & 63;
+  // the ranges' log-sum-exp: range c in lane c % 64, slot c / 64 (at most kMaxSplits ranges), all loads at once
+  constexpr int kSlots = 4;  // kMaxSplits / 64
+  float lc[kSlots];
   float mx = -INFINITY;
-  for (int c = 0; c < p.n_splits; ++c) mx = fmaxf(mx, p.ws_lse[c * rows + r]);
+#pragma unroll
+  for (int k = 0; k < kSlots; ++k) {
+    const int c = lane + 64 * k;
+    lc[k] = c < p.n_splits ? p.ws_lse[c * rows + r] : -INFINITY;
+    mx = fmaxf(mx, lc[k]);
+  }
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s));
   float tot = 0.f;
-  for (int c = 0; c < p.n_splits; ++c) tot += mx == -INFINITY ? 0.f : __expf(p.ws_lse[c * rows + r] - mx);
+#pragma unroll
+  for (int k = 0; k < kSlots; ++k) tot += lc[k] == -INFINITY ? 0.f : __expf(lc[k] - mx);
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) tot += __shfl_xor(tot, s);
   const float lse = mx == -INFINITY ? -INFINITY : mx + __logf(tot);
+  float wc[kSlots];  // the ranges' weights
+#pragma unroll
+  for (int k = 0; k < kSlots; ++k) wc[k] = lc[k] == -INFINITY ? 0.f : __expf(lc[k] - lse);
   const int i = (int)(r % p.L_q), hq = (int)((r / p.L_q) % p.H_q), b = (int)(r / ((int64_t)p.L_q * p.H_q));
   const int64_t obase = b * p.os[0] + hq * p.os[1] + (int64_t)i * p.os[2];
   for (int d = lane; d < p.D_v; d += 64) {
     float acc = 0.f;
-    for (int c = 0; c < p.n_splits; ++c) {
-      const float wgt = mx == -INFINITY ? 0.f : __expf(p.ws_lse[c * rows + r] - lse);
-      acc += wgt * p.ws_o[(c * rows + r) * p.D_v + d];
+#pragma unroll
+    for (int k = 0; k < kSlots; ++k) {
+      if (64 * k >= p.n_splits) break;
+      const int n = min(64, p.n_splits - 64 * k);
+#pragma unroll 8
+      for (int cc = 0; cc < n; ++cc)  // (independent loads: the unrolled ones are in flight together)
+        acc += __shfl(wc[k], cc) * p.ws_o[((64 * k + cc) * rows + r) * p.D_v + d];
     }
     if (p.out_bf16) static_cast<__bf16*>(p.O)[obase + d] = (__bf16)acc;
     else static_cast<float*>(p.O)[obase + d] = acc;
@@ -137,6 +158,9 @@ struct ae_attn {
   // register file beside the 256-wide query fragments, so the forward pass is v_slices launches of the 256 / 128
   // kernel, each over 128 columns of V and O (the scores and the row normalizer are the same in every launch)
   int v_slices;
+  // One query row per head, softmax, every key visible (a decoding step): with split keys the ranges are walked by
+  // the streaming kernel of attn_decode.hip instead of the 256-row attention kernel
+  bool decode;
 };
 
 extern "C" {
@@ -310,7 +334,17 @@ ae_status_t ae_attn_create(const ae_attn_desc_t* d, ae_attn_t** out) {
   p.base_grid = (int)grid;
   h->ws_bytes = 0;
   int kv_splits = d->kv_splits;
-  if (kv_splits == AE_KV_SPLITS_AUTO) {
+  h->decode = d->L_q == 1 && d->norm == AE_NORM_SOFTMAX && mod == ae::MOD_PLAIN && d->mask != AE_MASK_SLIDING_WINDOW &&
+              v_slices == 1 && ae::decode_supported(d->D_qk, d->D_v);
+  if (kv_splits == AE_KV_SPLITS_AUTO && h->decode) {
+    // Measured on the decoding row of Table 2 (16 heads, batch 1 and 8, 2k-8k keys): fastest with 128-256
+    // workgroups (8 ranges at batch 1, 2 at batch 8) -- every workgroup pays the latency of its first loads and of
+    // the combination at its end, and every range costs the merge kernel a row to read -- and with ranges of at
+    // least four key tiles.
+    const int key_tiles = (d->L_k + h->kernel->block_n - 1) / h->kernel->block_n;
+    const int64_t rows = (int64_t)d->B * d->H_q, want = (192 + rows / 2) / rows;
+    kv_splits = (int)std::min<int64_t>(std::min<int64_t>(want, key_tiles / 4), 256);
+  } else if (kv_splits == AE_KV_SPLITS_AUTO) {
     // Measured on decoding shapes (one query row, 16 heads, 2k-8k keys, batch 1 and 8): the
     // fastest launches hold some 128-256 workgroups with at least 8 key tiles each; more
     // ranges cost a start and an end of a workgroup apiece.  Only where the keys may be split
@@ -384,7 +418,30 @@ static ae_status_t forward_impl(const ae_attn_t* h, const void* Q, const void* K
     p.ws_lse = p.ws_o + (size_t)p.n_splits * rows * h->desc.D_v;
   }
   hipError_t e = hipSuccess;
-  for (int sl = 0; sl < h->v_slices && e == hipSuccess; ++sl) {
+  const bool decode = h->decode && p.n_splits > 1 && !carried && !bias;
+  if (decode) {
+    ae::DecodeParams q;
+    q.Q = p.Q;
+    q.K = p.K;
+    q.V = p.V;
+    q.ws_o = p.ws_o;
+    q.ws_lse = p.ws_lse;
+    for (int a = 0; a < 3; ++a) {
+      if (a < 2) q.qs[a] = p.qs[a];
+      q.ks[a] = p.ks[a];
+      q.vs[a] = p.vs[a];
+    }
+    q.rows = (int64_t)p.B * p.H_q;
+    q.H_q = p.H_q;
+    q.g = p.g;
+    q.L_k = p.L_k;
+    q.n_splits = p.n_splits;
+    q.split_keys = p.split_tiles * h->kernel->block_n;
+    q.c = h->desc.scale * 1.4426950408889634f;
+    q.b2 = (h->desc.score_mod == AE_MOD_BIAS ? h->desc.bias : 0.f) * 1.4426950408889634f;
+    e = ae::launch_decode(q, h->desc.D_qk, h->desc.D_v, static_cast<hipStream_t>(stream));
+  }
+  for (int sl = 0; sl < h->v_slices && e == hipSuccess && !decode; ++sl) {
     if (sl > 0) {  // the next 128 columns of V and O
       p.V += h->kernel->dv;
       p.O = static_cast<char*>(p.O) + (size_t)h->kernel->dv * (p.out_bf16 ? 2 : 4);

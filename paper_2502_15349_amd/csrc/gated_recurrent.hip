@@ -38,6 +38,10 @@
 #include "attn_bwd_kernel.hpp"  // bswz, read_tr_frag
 #include "gated.hpp"
 
+#ifndef AE_GATED_QS_128
+#define AE_GATED_QS_128 1  // wavefronts per block of 32 value columns at 128/128 (build-time knob of the sweeps)
+#endif
+
 namespace ae {
 namespace {
 
@@ -610,7 +614,7 @@ hipError_t launch_gated_recurrent(const GatedParams& p_in, const DecayTable& dt,
     return launch<128, 64>(p, dt, s);
   }
   if (dqk == 64 && dv == 128) return launch<64, 128>(p, dt, s);
-  if (dqk == 128 && dv == 128) return launch<128, 128, 1, 1>(p, dt, s);
+  if (dqk == 128 && dv == 128) return launch<128, 128, 1, AE_GATED_QS_128>(p, dt, s);
   return hipErrorInvalidValue;
 }
 
