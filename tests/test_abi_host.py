@@ -176,6 +176,9 @@ def test_split_keys_descriptor_and_workspace():
     h = A.ae_attn_create(B=1, H_q=16, H_kv=16, L_q=1, L_k=8192, D_qk=192, D_v=128, scale=0.1, kv_splits=-1)
     assert A.ae_attn_workspace_bytes(h) == 12 * 16 * (128 + 1) * 4      # 128 key tiles in 12 ranges of 11
     A.ae_attn_destroy(h)
+    h = A.ae_attn_create(B=8, H_q=16, H_kv=4, L_q=1, L_k=8192, D_qk=128, D_v=128, scale=0.1, kv_splits=-1)
+    assert A.ae_attn_workspace_bytes(h) == 2 * 128 * (128 + 1) * 4      # 128 rows: about 192 workgroups = 2 ranges
+    A.ae_attn_destroy(h)
     for kw in (dict(B=4, H_q=32, H_kv=8, L_q=2048, L_k=2048), dict(B=1, H_q=16, H_kv=16, L_q=1, L_k=8192, norm="sigmoid"),
                dict(B=1, H_q=16, H_kv=16, L_q=1, L_k=200)):
         h = A.ae_attn_create(D_qk=128, D_v=128, scale=0.1, kv_splits=-1, **kw)
