@@ -273,7 +273,14 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       asm volatile("s_barrier" ::: "memory");
     }
-    if (c + 2 < n_chunks) issue_chunk(c + 2);
+    // The copies of chunk c + 2 (its stage is free from the barrier on).  The compute unit's memory pipe takes 64
+    // bytes per clock, a chunk's tiles are 48 KB: if all wavefronts queued their copies here, they would wait for the
+    // pipe and for each other.  Each issues its share at a different point of the iteration instead (the counts
+    // in the waits above do not care in which order a wavefront's copies and stores were issued: both are younger
+    // than the copies it waits for).
+    const bool more = c + 2 < n_chunks;
+    const int turn = wave & 3;
+    if (more && turn == 0) issue_chunk(c + 2);
     // gates of this lane's token: log-decay (0 past the end: the state is carried unchanged; at least -20: a token
     // that lets less than e^-20 through lets nothing through at the precision of the path, and the bound keeps the
     // factorised weights below in range) and key gate (0 past the end)
@@ -311,6 +318,7 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
       lds_write4(gate0 + 256 + lane * 4, g * __expf(ref - bcum));
       lds_write4(gate0 + 512 + lane * 4, g * __expf(b_last - bcum));
     }
+    if (more && turn == 1) issue_chunk(c + 2);
     float bi0, bi1;  // b of tokens ln and 32 + ln
     swap_halves(bcum, bi0, bi1);
     // The state in front of the chunk, rounded to bf16: the A operands of the read-out (an accumulator tile is an A
@@ -435,13 +443,16 @@ __global__ __launch_bounds__(C::THREADS) void gated_recurrent_kernel(const Gated
     };
     if (!p.state_only) {
       if (C::QS == 1 || ib == 0) query_block(std::integral_constant<int, 0>{});
+      if (more && turn == 2) issue_chunk(c + 2);
       if (C::QS == 1 || ib == 1) query_block(std::integral_constant<int, 1>{});
     } else {
+      if (more && turn == 2) issue_chunk(c + 2);
       // (the V fragments that a query block would have left behind for the update)
 #pragma unroll
       for (int s = 0; s < 4; ++s) vf[s] = v_tr_frag(s);
     }
     seg_b += b_last;
+    if (more && turn == 3) issue_chunk(c + 2);
 
     // ---- state update: H (already e^{b_last} times the old state) += K^T (w . V) ----
     f32x4 wv[8];
