@@ -467,7 +467,10 @@ ae_status_t ae_gated_forward_segmented(const ae_gated_t *h, const void *Q, const
  *              key_gate is given, else NULL;
  *   workspace  device, 256-byte aligned, ae_gated_backward_workspace_bytes: 4 B per
  *              (batch, head, token), plus 8 D_qk B per (batch, head, token) when
- *              H_qk < H.  Owned by the caller; calls sharing it must not overlap.
+ *              H_qk < H (the gradients of q and of the gated key per value head,
+ *              which a small kernel sums over each group), plus the segments'
+ *              states where the walks are cut (see ae_gated_forward_segmented).
+ *              Owned by the caller; calls sharing it must not overlap.
  * Tensors 16-byte aligned, gates and their gradients 4-byte; outputs must alias
  * neither inputs nor each other.  Uses B, H, H_qk, L, the head dims and scale of
  * the handle (out_dtype plays no part: gradients are fp32).  Five launches on
