@@ -382,6 +382,31 @@ def test_split_keys(A, dims, Lq, Lk, mask, splits):
     assert torch.equal(Ob, O.to(torch.bfloat16))
 
 
+@pytest.mark.parametrize("dims", [(64, 64), (128, 128), (192, 128)], ids=lambda d: f"d{d[0]}_{d[1]}")
+@pytest.mark.parametrize("Lk,splits", [(65, 2), (130, 3), (131, 2), (1000, 7), (1027, 16), (4099, 5)])
+def test_decoding_rows(A, dims, Lk, splits):
+    """One query row per head with split keys (the streaming kernel): key counts that leave the last range, the last
+    wavefront and the last group of four keys ragged (a range of 2 or 3 keys among them); 8 q heads per k/v head; a
+    constant bias; a negative scale; the row statistic; bf16 output."""
+    from oracle import row_stats_head
+    dev = torch.device("cuda:0")
+    for kw in (dict(), dict(score_mod="bias", bias=-3.0), dict(scale=-0.05)):
+        w = Workload("decode_rows", 21, 2, 8, 1, 1, Lk, dims[0], dims[1], mask="causal", **kw)
+        Q, K, V = make_inputs(w)
+        st = torch.zeros((w.B, w.H_q, 1), dtype=torch.float32, device=dev)
+        O = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), stats=st, kv_splits=splits)
+        torch.cuda.synchronize()
+        check(O.cpu().double().numpy(), oracle_run(w, Q, K, V), f"decoding rows {dims} L_k {Lk} {kw}")
+        got = st.cpu().double().numpy()
+        for b in range(w.B):
+            for h in range(w.H_q):
+                ref = row_stats_head(Q[b, h], K[b, 0], scale=w.scale_value, score_mod=w.score_mod, bias=w.bias, norm="softmax",
+                                     mask=w.oracle_mask())
+                assert np.abs(got[b, h] - ref).max() <= 1e-3, (b, h)      # (the scale stays in fp32 on this path)
+        Ob = A.run_workload(w, Q.to(dev), K.to(dev), V.to(dev), kv_splits=splits, out_dtype=torch.bfloat16)
+        assert torch.equal(Ob, O.to(torch.bfloat16))
+
+
 def test_split_keys_decode_full_size(A):
     """The paper's decoding row (Table 2: one query row, 16 heads, 192/128) at 8k keys, batch 8."""
     w = Workload("decode", 20, 8, 16, 16, 1, 8192, 192, 128, mask="causal")
