@@ -493,9 +493,12 @@ def main():
             st = torch.cuda.current_stream()
 
             def timed(fn, n):
-                for _ in range(3):
-                    fn()
-                torch.cuda.synchronize()
+                import time
+                t_settle = time.perf_counter()   # (0.2 s of the same call first: the board's clock under this load settles)
+                while time.perf_counter() - t_settle < 0.2:
+                    for _ in range(3):
+                        fn()
+                    torch.cuda.synchronize()
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(st)
                 for _ in range(n):
@@ -618,9 +621,14 @@ def main():
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
             def timed(call, n_warm):
-                for _ in range(n_warm):
-                    call()
-                torch.cuda.synchronize()
+                # (the same call for 0.3 s first: the clock the board holds under this load has to settle, as for the
+                # contract line)
+                import time
+                t_settle = time.perf_counter()
+                while time.perf_counter() - t_settle < 0.3:
+                    for _ in range(max(n_warm, 4)):
+                        call()
+                    torch.cuda.synchronize()
                 e0.record(st)
                 for _ in range(a.steps):
                     call()
@@ -800,9 +808,11 @@ def main():
                                    gamma=[1.0 - 2.0 ** (-5 - (i % 8)) for i in range(wr.H_q)])
         wsr = torch.empty(A.ae_recurrent_workspace_bytes(hr), dtype=torch.uint8, device=dev)
         rargs = (hr, Qr.data_ptr(), Kr.data_ptr(), Vr.data_ptr(), Or.data_ptr(), wsr.data_ptr(), wsr.numel(), st.cuda_stream)
-        for _ in range(3):
-            A.ae_recurrent_forward(*rargs)
-        torch.cuda.synchronize()
+        t_settle = time.perf_counter()   # (the board's clock under this load settles, as for the contract line)
+        while time.perf_counter() - t_settle < 0.2:
+            for _ in range(3):
+                A.ae_recurrent_forward(*rargs)
+            torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(st)
         for _ in range(20):
@@ -834,9 +844,11 @@ def main():
                  dVg.data_ptr(), dlag.data_ptr(), 0, wsg.data_ptr(), nwg, st.cuda_stream)
         for call, cargs, tag, byts in ((A.ae_gated_forward, fargs, "", wg.B * wg.H_q * wg.L_q * (2 * 3 * 128 + 4 * 128 + 4)),
                                        (A.ae_gated_backward, bargs, "_backward", wg.B * wg.H_q * wg.L_q * (2 * 4 * 128 + 4 * 3 * 128 + 8))):
-            for _ in range(2):
-                call(*cargs)
-            torch.cuda.synchronize()
+            t_settle = time.perf_counter()
+            while time.perf_counter() - t_settle < 0.2:
+                for _ in range(2):
+                    call(*cargs)
+                torch.cuda.synchronize()
             e0.record(st)
             for _ in range(10):
                 call(*cargs)
