@@ -12,12 +12,13 @@
 //     H_new = e^{b_last} H + sum_j (e^{b_last - b_j} g_j) k_j^T v_j
 // Every exponent is <= 0: nothing overflows, nothing is divided by a decay.
 //
-// A wavefront owns 32 of the D_v output columns and one of the chunk's two blocks of 32 queries (2 D_v / 32
-// wavefronts per head), and keeps, for its columns, the state slab [D_qk x 32] as D_qk / 32 accumulator tiles.  The
-// two wavefronts of a column block both hold the slab and both apply every update to it (the same instructions on
-// the same operands: the copies stay bit-identical): the path is bound by memory and by the latency chain of a
-// chunk, not by MFMAs, and two wavefronts per SIMD, each with half of the read-out, scores and aggregation, hide
-// each other's waits.  All products are transposed so that a lane owns one column -- a
+// A wavefront owns 32 of the D_v output columns and keeps, for its columns, the state slab [D_qk x 32] as D_qk / 32
+// accumulator tiles.  It takes both of the chunk's two blocks of 32 queries (QS = 1: D_v / 32 wavefronts per head,
+// each alone on its SIMD with the whole register file) or one of them (QS = 2: two wavefronts per column block that
+// both hold the slab and both apply every update to it -- the same instructions on the same operands, so the copies
+// stay bit-identical -- where the registers allow two wavefronts per SIMD: 64 / 128).  The path is bound by memory
+// and by the latency chain of a chunk, not by MFMAs.
+// All products are transposed so that a lane owns one column -- a
 // query in S^T and O^T, a value column in H -- and the registers run over the contracted index:
 //     S^T [keys x queries]   = K Q^T          A: K rows, B: Q rows (16-byte row pieces in the d order below)
 //     R^T [v x queries]      = H^T Q^T        A: the state accumulators themselves, packed to bf16 (lane = value
@@ -31,8 +32,11 @@
 // dictates (register r of a tile is row 8 (r / 4) + 4 (lane / 32) + r % 4): two 8-byte pieces per fragment.
 // Of the three 32 x 32 blocks of S^T that the causal order inside a chunk leaves, a wavefront computes those of
 // its query block itself (cheaper than an exchange through LDS and a barrier).
-// Q, K, V tiles arrive by LDS-DMA, double buffered, one barrier per chunk; the gates of the next chunk are
-// fetched a chunk ahead.  The output of a chunk is stored before the state update, whose MFMAs cover the stores.
+// Q, K, V tiles and the chunk's gates arrive by LDS-DMA into a ring of three stages (chunk c is worked on while
+// c + 1 and c + 2 are in flight), one barrier per chunk, the wavefronts issuing their shares of the copies at
+// different points of the iteration.  The output of a chunk is stored before the state update, whose MFMAs cover
+// the stores.  The same kernel serves the backward pass (other operands, a walk from the last token to the first,
+// see GatedParams::reverse) and walks cut into segments (GatedParams::nseg).
 #include <hip/hip_runtime.h>
 
 #include "attn_bwd_kernel.hpp"  // bswz, read_tr_frag
