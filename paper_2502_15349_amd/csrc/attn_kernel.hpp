@@ -144,7 +144,16 @@ struct Cfg {
   static constexpr int T = DQK / 16;  // contraction steps of the scoring MFMA
   static constexpr int DB = DV / 32;  // 32-wide blocks of output columns
   static constexpr int VA = DB < 4 ? DB : 4;  // V fragment base addresses kept per lane
-  static constexpr int PF = 4;  // LDS fragment reads kept in flight ahead of their MFMA
+  // LDS fragment reads kept in flight ahead of their MFMA: a ring of PF register quads.  It must divide the MFMAs of
+  // an iteration, 4 (DB + T), and fit either block of a sub-step.  Four cover an LDS latency of 128 clocks at one
+  // MFMA per 32; under the load of eight wavefronts and the tile copies the latency is longer, and eight measured
+  // 1-3 % faster where the registers are there (128/128 and 192/128; the sliding-window kernels have none to spare).
+#ifndef AE_TUNE_PF
+#define AE_TUNE_PF 8
+#endif
+  static constexpr int PF = (4 * (DV / 32 + DQK / 16)) % AE_TUNE_PF == 0 && AE_TUNE_PF <= DQK / 16 && AE_TUNE_PF <= 2 * (DV / 32) &&
+                                    DQK + DV <= 320 && MASK_ != 2 && MOD_ != MOD_BIAS_T
+                                ? AE_TUNE_PF : 4;
   // A copy instruction that finds the CU's vector memory queue full blocks the wave
   // that issues it, and with it everything behind it in program order.  Where the
   // matrix phase is the longer one the copies are issued in the vector phases (the
