@@ -861,11 +861,12 @@ struct KeyLoop {
       static_for<S::NPV, S::NS>([&](auto rc) {
         constexpr int r = decltype(rc)::value, n = SUB * S::NS + r, g = r - S::NPV;
         if constexpr (g == 0) {
-          if constexpr (C::FOLD && C::NORM == NORM_SIGMOID && C::kSplatInit) {
-            // the constant term as 16 moves here, in the matrix phase, whose wave leaves the vector port idle, instead
-            // of 16 registers held for the whole kernel (the value is hidden from the optimiser so that it does not
-            // hoist the vector back out of the loop)
-            float b = p.b2;
+          if constexpr (C::FOLD && C::kSplatInit) {
+            // the constant term (sigmoid: the bias; softmax: minus the row's reference, zero while it has none) as 16
+            // moves here, in the matrix phase, whose wave leaves the vector port idle, instead of 16 registers held
+            // for the whole kernel (the value is hidden from the optimiser so that it does not hoist the vector back
+            // out of the loop)
+            float b = C::NORM == NORM_SIGMOID ? p.b2 : (st.m == -INFINITY ? 0.f : -st.m);
             asm volatile("" : "+v"(b));
             f32x16 init;
 #pragma unroll
